@@ -1,0 +1,137 @@
+"""Seeded synthetic inputs for the five measured workloads.
+
+This module holds no arithmetic of the method: it only draws random tensors (and rounds them to
+bfloat16 where a workload asks for bf16 inputs).  The same host arrays are handed to the GPU
+library and to the CPU oracle, so the random number generator is not part of any parity claim.
+
+The paper's own workloads (MNIST images, random 768-vectors, VGG16 inputs; Section 6.1) are not
+used; seeded tensors of the same kind of shape stand in for them ("MNIST-shaped" = 784 inputs in
+[0, 1), 10 classes).
+
+Draw order for a workload: W_1, b_1, ..., W_L, b_L, X, labels, all from one Philox stream seeded
+with ``BASE_SEED + index``.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+BASE_SEED = 190304243
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    index: int
+    call: str                      # "per_example_grads" | "jacobian_input" | "jacobian_weights"
+    dims: Tuple[int, ...]
+    act: str                       # hidden activation
+    dtype: str                     # "f32" | "bf16" (dtype of X, W, b; outputs are always f32)
+    B: int
+    x_dist: str                    # "normal" | "uniform01"
+    w_init: str                    # "glorot_uniform" | "normal_fan_in"
+    S: int = 1                     # seed rows per example (Jacobians)
+    head: str = "logits"           # jacobian_weights only
+    layers_out: Optional[Tuple[int, ...]] = None   # 1-based layers whose dW / JW is produced
+    also: Tuple[str, ...] = field(default_factory=tuple)   # further calls on the same inputs
+
+
+WORKLOADS: Dict[str, Workload] = {
+    w.name: w for w in [
+        Workload("c1_tiny", 0, "per_example_grads", (32, 64, 10), "relu", "f32", 16,
+                 "normal", "glorot_uniform", S=10, also=("jacobian_input",)),
+        Workload("c2_mnist_mlp_grads", 1, "per_example_grads", (784, 512, 512, 10), "relu", "f32",
+                 128, "uniform01", "glorot_uniform"),
+        Workload("c3_tanh_jacobian", 2, "jacobian_input", (1024, 2048, 2048, 1024), "tanh", "f32",
+                 64, "normal", "normal_fan_in", S=1024),
+        Workload("c4_gelu_bf16_grads", 3, "per_example_grads", (4096, 4096, 4096, 10), "gelu",
+                 "bf16", 256, "normal", "normal_fan_in"),
+        Workload("c5_nested_weight_jacobian", 4, "jacobian_weights", (256, 256, 16), "tanh", "f32",
+                 64, "normal", "normal_fan_in", S=16, head="softmax", layers_out=(1,)),
+    ]
+}
+
+
+def bf16_round(a: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Round float32 values to bfloat16 (nearest, ties to even).
+
+    Returns (bits uint16, the rounded values as float32).  Inputs are finite."""
+    a32 = np.ascontiguousarray(a, dtype=np.float32)
+    u = a32.view(np.uint32)
+    bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    r = ((u + bias) >> np.uint32(16)).astype(np.uint16)
+    back = (r.astype(np.uint32) << np.uint32(16)).view(np.float32).reshape(a32.shape)
+    return r.reshape(a32.shape), back
+
+
+@dataclass
+class Inputs:
+    """Host arrays of one workload.  ``Ws``/``bs``/``X`` are float32 and, for a bf16 workload,
+    already hold bf16-representable values; ``*_bits`` then hold the matching uint16 patterns."""
+    workload: Workload
+    Ws: List[np.ndarray]
+    bs: List[np.ndarray]
+    X: np.ndarray
+    labels: np.ndarray
+    Ws_bits: Optional[List[np.ndarray]] = None
+    bs_bits: Optional[List[np.ndarray]] = None
+    X_bits: Optional[np.ndarray] = None
+
+
+def draw_weights(rng: np.random.Generator, dims, w_init: str, bias_scale: float = 0.0):
+    Ws, bs = [], []
+    for l in range(1, len(dims)):
+        fan_in, fan_out = dims[l - 1], dims[l]
+        if w_init == "glorot_uniform":
+            r = np.sqrt(6.0 / (fan_in + fan_out))
+            W = rng.uniform(-r, r, size=(fan_in, fan_out))
+        elif w_init == "normal_fan_in":          # variance 1/fan_in
+            W = rng.standard_normal(size=(fan_in, fan_out)) / np.sqrt(fan_in)
+        else:
+            raise ValueError(w_init)
+        b = rng.standard_normal(size=(fan_out,)) * bias_scale
+        Ws.append(W.astype(np.float32))
+        bs.append(b.astype(np.float32))
+    return Ws, bs
+
+
+def make_inputs(w: Workload, B: Optional[int] = None, dims=None, bias_scale: float = 0.0,
+                seed: Optional[int] = None) -> Inputs:
+    """Draw one workload's tensors.  ``B``/``dims`` override the size (scaled-down parity cases);
+    ``bias_scale`` > 0 gives non-zero biases (the measured workloads use zero biases)."""
+    B = w.B if B is None else B
+    dims = tuple(w.dims if dims is None else dims)
+    rng = np.random.Generator(np.random.Philox(BASE_SEED + w.index if seed is None else seed))
+    Ws, bs = draw_weights(rng, dims, w.w_init, bias_scale)
+    if w.x_dist == "normal":
+        X = rng.standard_normal(size=(B, dims[0]))
+    elif w.x_dist == "uniform01":
+        X = rng.uniform(0.0, 1.0, size=(B, dims[0]))
+    else:
+        raise ValueError(w.x_dist)
+    X = X.astype(np.float32)
+    labels = rng.integers(0, dims[-1], size=(B,)).astype(np.int32)
+    inp = Inputs(w, Ws, bs, X, labels)
+    if w.dtype == "bf16":
+        Wr = [bf16_round(W) for W in Ws]
+        br = [bf16_round(b) for b in bs]
+        Xr = bf16_round(X)
+        inp.Ws_bits, inp.Ws = [r[0] for r in Wr], [r[1] for r in Wr]
+        inp.bs_bits, inp.bs = [r[0] for r in br], [r[1] for r in br]
+        inp.X_bits, inp.X = Xr
+    return inp
+
+
+def output_values(w: Workload, B: Optional[int] = None) -> int:
+    """Number of float32 values the workload's call writes (weight and bias gradients, or the
+    Jacobian)."""
+    B = w.B if B is None else B
+    d = w.dims
+    if w.call == "per_example_grads":
+        return B * sum(d[l - 1] * d[l] + d[l] for l in range(1, len(d)))
+    if w.call == "jacobian_input":
+        return B * w.S * d[0]
+    layers = w.layers_out or tuple(range(1, len(d)))
+    return B * w.S * sum(d[l - 1] * d[l] for l in layers)

@@ -1,0 +1,62 @@
+"""The pins must have teeth: plant one plausible mistake at a time in a COPY of the oracle's C
+source (a dropped term, a wrong sign or index, a transposed operand), build it on the CPU, and
+check that the pin suite then fails.  The mistakes are planted in the oracle only; nothing here
+touches the GPU."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "pfg_oracle.c")
+
+MUTANTS = [
+    ("forward_transposed_weight", "s += prev[i] * W[(size_t)i * dout + j];",
+     "s += prev[i] * W[(size_t)j * din + i];"),
+    ("forward_bias_dropped", "double s = bias ? bias[j] : 0.0;", "double s = 0.0;"),
+    ("backward_transposed_weight", "s += g[j] * W[(size_t)i * dout + j];",
+     "s += g[j] * W[(size_t)j * din + i];"),
+    ("backward_mask_dropped", "pfgo_act_deriv(net->act, t.z[l - 2][i]) * s : s;", "s : s;"),
+    ("backward_mask_wrong_layer", "pfgo_act_deriv(net->act, t.z[l - 2][i]) * s",
+     "pfgo_act_deriv(net->act, t.z[l - 1][i < dout ? i : 0]) * s"),
+    ("outer_product_wrong_input", "const double *ain = (l == 1) ? x : t.a[l - 2];",
+     "const double *ain = (l == 1) ? x : t.z[l - 2];"),
+    ("outer_product_transposed", "dW[l - 1][(size_t)i * dout + j] = ain[i] * g[j];",
+     "dW[l - 1][(size_t)i * dout + j] = ain[i] * g[(i + j) % dout];"),
+    ("head_sign", "p[label] -= 1.0;", "p[label] += 1.0;"),
+    ("head_onehot_dropped", "p[label] -= 1.0;", ""),
+    ("softmax_no_normalise", "for (int j = 0; j < n; ++j) p[j] /= den;", ""),
+    ("gelu_deriv_sign", "return Phi + z * pdf;", "return Phi - z * pdf;"),
+    ("gelu_deriv_term_dropped", "return Phi + z * pdf;", "return Phi;"),
+    ("tanh_deriv", "return 1.0 - t * t;", "return 1.0 - t;"),
+    ("relu_deriv_at_zero", "case PFGO_ACT_RELU: return z > 0.0 ? 1.0 : 0.0;",
+     "case PFGO_ACT_RELU: return z >= 0.0 ? 1.0 : 0.0;"),
+    ("softmax_jacobian_sign", "row[j] = p[k] * ((j == k ? 1.0 : 0.0) - p[j]);",
+     "row[j] = p[k] * ((j == k ? 1.0 : 0.0) + p[j]);"),
+    ("softmax_jacobian_transposed_scale", "row[j] = p[k] * ((j == k ? 1.0 : 0.0) - p[j]);",
+     "row[j] = p[j] * ((j == k ? 1.0 : 0.0) - p[j]);"),
+    ("jacobian_row_stacking", "body_row_input(net, x, t, row, J + ((size_t)b * S + s) * d0);",
+     "body_row_input(net, x, t, row, J + ((size_t)s * B + b) * d0);"),
+    ("seed_stride_ignored", "row = seeds + (size_t)b * seed_batch_stride + (size_t)s * dL;",
+     "row = seeds + (size_t)s * dL;"),
+    ("per_example_slice_offset",
+     "dWi[l - 1] = dW[l - 1] + (size_t)i * net->dims[l - 1] * net->dims[l];",
+     "dWi[l - 1] = dW[l - 1] + (size_t)(B - 1 - i) * net->dims[l - 1] * net->dims[l];"),
+    ("loss_not_log", "if (loss) *loss = -log(p[label]);", "if (loss) *loss = -p[label];"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_pins_catch_planted_mistake(tmp_path, oracle, name, old, new):
+    src = open(SRC).read()
+    assert src.count(old) >= 1, f"pattern for {name} not found in the oracle source"
+    mutated = tmp_path / "pfg_oracle_mutant.c"
+    mutated.write_text(src.replace(old, new))
+    lib = tmp_path / "libpfg_oracle_mutant.so"
+    oracle.compile_source(str(mutated), str(lib))
+    env = dict(os.environ, PFG_ORACLE_LIB=str(lib))
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests",
+                        "test_oracle_pins.py"), "-x", "-q", "-p", "no:cacheprovider"],
+                       env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0, f"mutant {name} passed every pin:\n{r.stdout[-2000:]}"
