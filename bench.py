@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only-primary] [--no-cpu-baseline]
+
+A step is one call of the library on one batch of seeded synthetic input that is already
+resident in HBM.  The headline line is the MNIST-shaped per-example-gradient workload
+(784 -> 512 -> 512 -> 10, ReLU, float32, batch 128); the other measured workloads are reported
+under "other_workloads" in the same JSON line.  Per-kernel durations come from HIP events the
+library records on the call's stream in a second, instrumented pass over the same steps.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--only-primary", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="do not also time a HIP-graph replay")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this library has no multi-GPU path (parallel-for "
+                 "iterations are independent; a batch would simply be split across devices). "
+                 "Run with --gpus 1.")
+
+    import numpy as np
+    import torch
+
+    import paper_1903_04243_amd as pfg
+    from paper_1903_04243_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    if not os.path.exists(pfg.LIB_PATH):
+        from paper_1903_04243_amd import build as pfg_build
+        pfg_build.build()
+    pfg.load_library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    def upload(w):
+        inp = wl.make_inputs(w)
+        net = pfg.Mlp.from_numpy(inp.Ws, inp.bs, w.act, w.dtype, inp.Ws_bits, inp.bs_bits)
+        if w.dtype == "bf16":
+            X = torch.from_numpy(inp.X_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        else:
+            X = torch.from_numpy(inp.X).to(dev)
+        labels = torch.from_numpy(inp.labels).to(dev)
+        return inp, net, X, labels
+
+    def make_step(w, net, X, labels):
+        """Allocate outputs and workspace once; return the step function."""
+        f32 = dict(dtype=torch.float32, device=dev)
+        L, d, B, S = net.L, net.dims, w.B, w.S
+        if w.call == "per_example_grads":
+            dW = [torch.empty((B, d[l], d[l + 1]), **f32) for l in range(L)]
+            db = [torch.empty((B, d[l + 1]), **f32) for l in range(L)]
+            loss = torch.empty((B,), **f32)
+            ws = torch.empty(pfg.pfg_workspace_bytes(net, w.call, B), dtype=torch.uint8, device=dev)
+            return lambda: pfg.pfg_per_example_grads(net, X, labels, out_dW=dW, out_db=db,
+                                                     out_loss=loss, workspace=ws)
+        if w.call == "jacobian_input":
+            J = torch.empty((B, S, d[0]), **f32)
+            ws = torch.empty(pfg.pfg_workspace_bytes(net, w.call, B, S), dtype=torch.uint8,
+                             device=dev)
+            return lambda: pfg.pfg_jacobian_input(net, X, out=J, workspace=ws)
+        layers = w.layers_out or tuple(range(1, L + 1))
+        JW = [torch.empty((B, S, d[l], d[l + 1]), **f32) if (l + 1) in layers else None
+              for l in range(L)]
+        Jb = [torch.empty((B, S, d[l + 1]), **f32) for l in range(L)]
+        ws = torch.empty(pfg.pfg_workspace_bytes(net, w.call, B, S), dtype=torch.uint8, device=dev)
+        return lambda: pfg.pfg_jacobian_weights(net, X, head=w.head, out_JW=JW, out_Jb=Jb,
+                                                workspace=ws)
+
+    def timed(step, steps, warmup):
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def timed_graph(step, steps, warmup):
+        """The same step captured once into a HIP graph and replayed."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        for _ in range(warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def kernel_times(step, steps):
+        """Average duration per launch of every kernel family, from the library's HIP events."""
+        pfg.pfg_timing_reset()
+        pfg.pfg_timing_enable(True)
+        try:
+            for _ in range(steps):
+                step()
+            torch.cuda.synchronize()
+        finally:
+            pfg.pfg_timing_enable(False)
+        out = {}
+        for name in pfg.pfg_timing_names():
+            n, ms = pfg.pfg_timing_query(name)
+            out[name] = {"launches_per_step": n / steps, "ms_per_step": ms / steps}
+        pfg.pfg_timing_reset()
+        return out
+
+    def algorithmic(w):
+        """Algorithmic work of the dominant kernels of one step."""
+        d, B, S = w.dims, w.B, w.S
+        if w.call == "per_example_grads":
+            return {"outer_product": {"bytes": 4 * B * sum(d[l - 1] * d[l] for l in range(1, len(d)))}}
+        if w.call == "jacobian_input":
+            rows = B * S
+            cot = sum(2 * rows * d[l] * d[l - 1] for l in range(2, len(d) - 1))
+            return {"gemm_cotangent": {"flops": cot},
+                    "gemm_jacobian": {"flops": 2 * rows * d[1] * d[0]}}
+        layers = w.layers_out or tuple(range(1, len(d)))
+        return {"outer_product": {"bytes": 4 * B * S * sum(d[l - 1] * d[l] for l in layers)}}
+
+    def roofline(w, kt):
+        alg = algorithmic(w)
+        if "outer_product" in alg:
+            k = kt["outer_product"]
+            per_launch_bytes = alg["outer_product"]["bytes"] / k["launches_per_step"]
+            per_launch_ms = k["ms_per_step"] / k["launches_per_step"]
+            gbs = per_launch_bytes / (per_launch_ms * 1e-3) / 1e9
+            return {"kernel": "outer_product", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                    "bytes_per_launch": per_launch_bytes, "ms_per_launch": per_launch_ms,
+                    "launches_per_step": k["launches_per_step"]}
+        flops = sum(v["flops"] for v in alg.values())
+        ms = sum(kt[name]["ms_per_step"] for name in alg)
+        launches = sum(kt[name]["launches_per_step"] for name in alg)
+        tf = flops / (ms * 1e-3) / 1e12
+        peak = MFMA_PEAK_TFLOPS[w.dtype]
+        return {"kernel": "+".join(alg), "bound": "mfma", "achieved": tf, "peak": peak,
+                "unit": "TFLOP/s", "frac": tf / peak, "traffic": None,
+                "flops_per_launch": flops / launches, "ms_per_launch": ms / launches,
+                "launches_per_step": launches}
+
+    def measure(name, steps, warmup):
+        w = wl.WORKLOADS[name]
+        log(f"[bench] {name}: uploading inputs")
+        inp, net, X, labels = upload(w)
+        step = make_step(w, net, X, labels)
+        step()
+        torch.cuda.synchronize()
+        log(f"[bench] {name}: timing {steps} steps")
+        sec = timed(step, steps, warmup)
+        sec_graph = None
+        if not args.no_graph:
+            try:
+                sec_graph = timed_graph(step, steps, warmup)
+            except Exception as e:  # graph capture is optional; eager timing stands
+                log(f"[bench] {name}: graph replay not measured ({e})")
+        kt = kernel_times(step, steps)
+        values = wl.output_values(w)
+        rec = {
+            "workload": name, "call": w.call, "dims": list(w.dims), "act": w.act, "dtype": w.dtype,
+            "B": w.B, "S": w.S, "steps": steps, "ms_per_step": sec * 1e3,
+            "ms_per_step_graph_replay": None if sec_graph is None else sec_graph * 1e3,
+            "output_values": values, "output_GB": values * 4 / 1e9,
+            "kernels": kt, "roofline": roofline(w, kt),
+        }
+        if w.call == "per_example_grads":
+            rec["per_example_grads_per_sec"] = w.B / sec
+        else:
+            rec["jacobian_entries_per_sec"] = values / sec
+            rec["jacobian_rows_per_sec"] = w.B * w.S / sec
+        log(f"[bench] {name}: {rec['ms_per_step']:.4f} ms/step, roofline frac "
+            f"{rec['roofline']['frac']:.3f}")
+        return rec, inp
+
+    primary = "c2_mnist_mlp_grads"
+    rec, inp = measure(primary, args.steps, args.warmup)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        w = wl.WORKLOADS[primary]
+        onet = oracle.Net(inp.Ws, inp.bs, w.act)
+        log("[bench] cpu_baseline: float64 oracle on the same batch")
+        oracle.per_example_grads(onet, inp.X[:8], inp.labels[:8])     # load / page in
+        passes, t_cpu = 0, 0.0
+        while passes < 3 or (t_cpu < 4.0 and passes < 40):
+            t0 = time.perf_counter()
+            oracle.per_example_grads(onet, inp.X, inp.labels)
+            t_cpu += time.perf_counter() - t0
+            passes += 1
+        cpu = {"value": w.B * passes / t_cpu, "unit": "grads/s", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": f"{passes} passes over the full batch of {w.B} examples of {primary} "
+                         f"(float64, OpenMP over examples), {t_cpu:.2f} s wall"}
+
+    others = {}
+    if not args.only_primary:
+        for name, steps in (("c5_nested_weight_jacobian", args.steps),
+                            ("c3_tanh_jacobian", max(3, args.steps // 20)),
+                            ("c4_gelu_bf16_grads", max(3, args.steps // 20))):
+            try:
+                others[name], _ = measure(name, steps, max(1, min(args.warmup, steps // 2)))
+            except Exception as e:
+                others[name] = {"error": str(e)}
+            torch.cuda.empty_cache()
+
+    w = wl.WORKLOADS[primary]
+    line = {
+        "metric": "per_example_grads_per_sec", "value": rec["per_example_grads_per_sec"],
+        "unit": "grads/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": rec["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": primary, "call": w.call, "dims": list(w.dims), "act": w.act,
+                   "batch": w.B, "output_GB_per_step": rec["output_GB"]},
+        "roofline": rec["roofline"], "cpu_baseline": cpu,
+        "ms_per_step_graph_replay": rec["ms_per_step_graph_replay"],
+        "kernels": rec["kernels"], "other_workloads": others,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,149 @@
+/*
+ * pfg.h -- per-example gradients and Jacobians of a dense feed-forward network on one AMD
+ * MI355X (gfx950), as a plain C ABI.
+ *
+ * What is computed is the result of the statically vectorised parallel-for of
+ * "Auto-Vectorizing TensorFlow Graphs: Jacobians, Auto-Batching and Beyond" (arXiv 1903.04243)
+ * for two of its uses: per-example gradients (Section 5.3) and Jacobians (Section 5.1).  The
+ * result of pfor(body, n) is the body's output for iterations 0..n-1 stacked on a new leading
+ * dimension (Section 4); every output below is laid out that way, iteration index first.
+ *
+ * Network.  L dense layers of widths d_0 -> d_1 -> ... -> d_L.
+ *      a_0 = x,   z_l = a_{l-1} W_l + b_l,   a_l = phi(z_l) for l < L,   y = z_L
+ *   W_l is row-major [d_{l-1}, d_l]; b_l is [d_l]; phi is one activation for all hidden layers.
+ *
+ * Memory.  Unless marked HOST, every pointer is a DEVICE pointer.  The caller owns every buffer
+ * (inputs, outputs, workspace).  The library allocates no device memory, keeps no pointer after
+ * a call returns, enqueues all work on the stream it is given and does not synchronise it.
+ * Inputs are only read; requested outputs are overwritten in full (never accumulated into).
+ * Outputs are always float32, row-major, last index fastest.  Buffers should be 16-byte aligned
+ * (unaligned buffers are accepted and take a slower scalar path).
+ *
+ * Errors.  Every function returns a pfg_status.  All argument checks run on the host before
+ * anything is enqueued, so a call that fails has not touched its outputs (PFG_ERR_DEVICE, a
+ * failed kernel launch, is the one exception).  pfg_last_error() describes the last failure on
+ * the calling thread.  No C++ exception crosses this boundary.  Label values are not checked
+ * (they live on the device); a label outside [0, d_L) gives an unspecified gradient for that
+ * example but no out-of-bounds access.
+ */
+#ifndef PFG_H_
+#define PFG_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PFG_OK = 0,
+  PFG_ERR_NULL = -1,        /* a required pointer is NULL                                  */
+  PFG_ERR_SHAPE = -2,       /* a size, stride or count is out of range or inconsistent     */
+  PFG_ERR_UNSUPPORTED = -3, /* unknown activation, dtype, head or op                       */
+  PFG_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned (256 B) or too small             */
+  PFG_ERR_OVERFLOW = -5,    /* a tensor would have more elements than the kernels index    */
+  PFG_ERR_DEVICE = -6       /* the HIP runtime reported an error                           */
+} pfg_status;
+
+/* Hidden activation phi.  ReLU'(0) is taken as 0.  GELU is the exact form z * Phi(z) with the
+ * normal CDF Phi, derivative Phi(z) + z * exp(-z^2 / 2) / sqrt(2 pi). */
+typedef enum { PFG_ACT_IDENTITY = 0, PFG_ACT_RELU = 1, PFG_ACT_TANH = 2, PFG_ACT_GELU_ERF = 3 } pfg_act;
+
+/* Element type of X, W_l and b_l.  With PFG_BF16 the matrix products run on bf16 operands
+ * (hidden activations and cotangents are rounded to bf16 when they feed a product) with float32
+ * accumulation; everything written out is the float32 accumulator value. */
+typedef enum { PFG_F32 = 0, PFG_BF16 = 1 } pfg_dtype;
+
+/* Which vector the seed rows of pfg_jacobian_weights are contracted with: the logits y, or
+ * softmax(y). */
+typedef enum { PFG_HEAD_LOGITS = 0, PFG_HEAD_SOFTMAX = 1 } pfg_head;
+
+typedef enum { PFG_OP_PER_EXAMPLE_GRADS = 0, PFG_OP_JACOBIAN_INPUT = 1, PFG_OP_JACOBIAN_WEIGHTS = 2 } pfg_op;
+
+typedef struct {
+  int32_t num_layers;     /* L >= 1                                                         */
+  const int32_t *dims;    /* HOST, L+1 entries d_0..d_L, each >= 1                          */
+  const void *const *W;   /* HOST array of L device pointers; W[l-1] is W_l [d_{l-1}, d_l]  */
+  const void *const *b;   /* HOST array of L device pointers or NULL; a NULL array or a NULL
+                             entry means a zero bias                                        */
+  int32_t hidden_act;     /* pfg_act, applied after layers 1..L-1, never after layer L      */
+  int32_t dtype;          /* pfg_dtype of X, W_l, b_l                                       */
+} pfg_mlp;
+
+/* Bytes of workspace the given op needs for batch B and S seed rows per example (S is ignored
+ * by PFG_OP_PER_EXAMPLE_GRADS).  The figure covers the case where no optional output is given;
+ * it is a multiple of 256 and never 0.  The workspace passed to an op must be 256-byte aligned. */
+int pfg_workspace_bytes(const pfg_mlp *net, int op, int64_t B, int64_t S, size_t *bytes);
+
+/* Per-example gradients (Section 5.3): iteration b of the parallel-for computes the gradient of
+ * example b's own loss  ell_b = -log softmax(y_b)[labels[b]]  (not divided by B), so
+ *      dW_out[l-1][b, i, j] = d ell_b / d W_l[i, j] = a_{l-1}[b, i] * delta_l[b, j]
+ *      db_out[l-1][b, j]    = d ell_b / d b_l[j]    = delta_l[b, j]
+ *      loss_out[b]          = ell_b
+ * with delta_L = softmax(y_b) - onehot(labels[b]) and
+ * delta_{l-1} = (delta_l W_l^T) * phi'(z_{l-1}).  Contributions of different examples are kept
+ * separate; summing dW_out[l-1] over b gives the gradient of the summed loss.
+ *   X       [B, d_0], element type net->dtype
+ *   labels  [B] int32
+ *   dW_out  HOST array of L device pointers, entry l-1 is [B, d_{l-1}, d_l]; a NULL array or
+ *           entry skips that output
+ *   db_out  HOST array of L device pointers, entry l-1 is [B, d_l]; NULL skips
+ *   loss_out [B] or NULL */
+int pfg_per_example_grads(const pfg_mlp *net, const void *X, const int32_t *labels, int64_t B,
+                          float *const *dW_out, float *const *db_out, float *loss_out,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Input Jacobian (Section 5.1: a parallel-for in which every iteration is the gradient of one
+ * scalar of the output), nested inside the parallel-for over examples (Section 3.7):
+ *      J_out[b, s, i] = d <seed row s of example b, y_b> / d x_b[i]
+ * Only the diagonal blocks (output of example b with respect to input of example b) exist; the
+ * others are identically zero and are not produced.
+ *   seeds   NULL: the identity, S must equal d_L, so J_out[b, s, i] = d y_b[s] / d x_b[i].
+ *           Otherwise float32 rows of length d_L: example b reads rows
+ *           seeds + b * seed_batch_stride + s * d_L.  seed_batch_stride == 0 shares one [S, d_L]
+ *           block between all examples (a loop-invariant operand is not stacked, Section 3.4);
+ *           otherwise it must be >= S * d_L.
+ *   J_out   [B, S, d_0] */
+int pfg_jacobian_input(const pfg_mlp *net, const void *X, int64_t B, const float *seeds,
+                       int64_t S, int64_t seed_batch_stride, float *J_out, void *workspace,
+                       size_t workspace_bytes, void *hip_stream);
+
+/* Jacobian with respect to the weights (the same nesting, differentiating with respect to the
+ * loop-invariant W_l and b_l; the per-iteration results stay separate):
+ *      JW_out[l-1][b, s, i, j] = d <seed row s, h(y_b)> / d W_l[i, j] = a_{l-1}[b, i] * G_l[b, s, j]
+ *      Jb_out[l-1][b, s, j]    = G_l[b, s, j]
+ * where h is the identity (PFG_HEAD_LOGITS) or softmax (PFG_HEAD_SOFTMAX), G_L[b, s, :] is the
+ * seed row pulled back through h, and G_{l-1} = (G_l W_l^T) * phi'(z_{l-1}).  With head =
+ * SOFTMAX and seeds = NULL, row s is the gradient of softmax(y_b)[s].
+ *   seeds, S, seed_batch_stride   as for pfg_jacobian_input
+ *   JW_out  HOST array of L device pointers, entry l-1 is [B, S, d_{l-1}, d_l]; NULL skips
+ *   Jb_out  HOST array of L device pointers, entry l-1 is [B, S, d_l]; NULL skips */
+int pfg_jacobian_weights(const pfg_mlp *net, const void *X, int64_t B, int head,
+                         const float *seeds, int64_t S, int64_t seed_batch_stride,
+                         float *const *JW_out, float *const *Jb_out, void *workspace,
+                         size_t workspace_bytes, void *hip_stream);
+
+/* Text of the last error on the calling thread ("" if none).  Valid until the next call into the
+ * library from that thread. */
+const char *pfg_last_error(void);
+
+/* Per-kernel device timing, for measurement.  While enabled, every kernel the library enqueues
+ * is bracketed by two HIP events recorded on the call's stream.  pfg_timing_query waits for the
+ * events recorded so far and reports, for the kernel family called `name`, the number of launches
+ * and their summed duration in milliseconds since the last reset; it returns PFG_ERR_SHAPE if no
+ * launch of that family was recorded.  pfg_timing_names writes the recorded family names,
+ * separated by '\n', into buf (truncated to cap bytes including the final NUL).  Do not enable
+ * timing while the stream is being captured into a graph. */
+int pfg_timing_enable(int on);
+int pfg_timing_reset(void);
+int pfg_timing_query(const char *name, int64_t *launches, double *total_ms);
+int pfg_timing_names(char *buf, size_t cap);
+
+/* Library version, major * 100 + minor. */
+int pfg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PFG_H_ */

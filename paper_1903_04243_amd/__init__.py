@@ -1,0 +1,260 @@
+"""Python binding of libpfg: per-example gradients and Jacobians of a dense network on MI355X.
+
+This module only marshals arguments: it allocates outputs and workspace as torch tensors on the
+GPU, passes raw device pointers and the current HIP stream to the C ABI declared in
+``include/pfg.h``, and returns the tensors.  Every step of the computation runs in the library's
+HIP kernels.  There is no CPU fallback: if ``libpfg.so`` is missing or a call fails, an exception
+is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpfg.so")
+
+PFG_OK = 0
+PFG_ERR_NULL, PFG_ERR_SHAPE, PFG_ERR_UNSUPPORTED = -1, -2, -3
+PFG_ERR_WORKSPACE, PFG_ERR_OVERFLOW, PFG_ERR_DEVICE = -4, -5, -6
+ACT = {"identity": 0, "relu": 1, "tanh": 2, "gelu": 3}
+DTYPE = {"f32": 0, "bf16": 1}
+HEAD = {"logits": 0, "softmax": 1}
+OP = {"per_example_grads": 0, "jacobian_input": 1, "jacobian_weights": 2}
+
+EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_jacobian_input",
+           "pfg_jacobian_weights", "pfg_last_error", "pfg_timing_enable", "pfg_timing_reset",
+           "pfg_timing_query", "pfg_timing_names", "pfg_version"]
+
+
+class PfgError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"pfg status {code}: {message}")
+        self.code = code
+
+
+class pfg_mlp(ctypes.Structure):
+    _fields_ = [
+        ("num_layers", ctypes.c_int32),
+        ("dims", ctypes.POINTER(ctypes.c_int32)),
+        ("W", ctypes.POINTER(ctypes.c_void_p)),
+        ("b", ctypes.POINTER(ctypes.c_void_p)),
+        ("hidden_act", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+    ]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libpfg.so from the package directory (build it with ``build.py`` first)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_1903_04243_amd.build` "
+                               "(there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        netp = ctypes.POINTER(pfg_mlp)
+        lib.pfg_workspace_bytes.argtypes = [netp, i32, i64, i64, ctypes.POINTER(ctypes.c_size_t)]
+        lib.pfg_per_example_grads.argtypes = [netp, vp, vp, i64, ctypes.POINTER(vp),
+                                              ctypes.POINTER(vp), vp, vp, ctypes.c_size_t, vp]
+        lib.pfg_jacobian_input.argtypes = [netp, vp, i64, vp, i64, i64, vp, vp, ctypes.c_size_t, vp]
+        lib.pfg_jacobian_weights.argtypes = [netp, vp, i64, i32, vp, i64, i64, ctypes.POINTER(vp),
+                                             ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
+        lib.pfg_last_error.restype = ctypes.c_char_p
+        lib.pfg_timing_enable.argtypes = [i32]
+        lib.pfg_timing_query.argtypes = [ctypes.c_char_p, ctypes.POINTER(i64),
+                                         ctypes.POINTER(ctypes.c_double)]
+        lib.pfg_timing_names.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != PFG_OK:
+        raise PfgError(rc, load_library().pfg_last_error().decode())
+
+
+def pfg_last_error() -> str:
+    return load_library().pfg_last_error().decode()
+
+
+def pfg_version() -> int:
+    return int(load_library().pfg_version())
+
+
+class Mlp:
+    """Device-resident network: ``Ws[l]`` is a contiguous [d_l, d_{l+1}] tensor (float32, or
+    bfloat16 for dtype "bf16"), ``bs[l]`` a [d_{l+1}] tensor or None."""
+
+    def __init__(self, Ws: Sequence, bs: Optional[Sequence], act: str, dtype: str = "f32"):
+        import torch
+        want = torch.float32 if dtype == "f32" else torch.bfloat16
+        self.Ws = list(Ws)
+        self.L = len(self.Ws)
+        self.bs = [None] * self.L if bs is None else list(bs)
+        for t in self.Ws + [b for b in self.bs if b is not None]:
+            if t.dtype != want or not t.is_contiguous() or not t.is_cuda:
+                raise ValueError("weights must be contiguous GPU tensors of the network dtype")
+        self.dims = [self.Ws[0].shape[0]] + [W.shape[1] for W in self.Ws]
+        for l, W in enumerate(self.Ws):
+            if tuple(W.shape) != (self.dims[l], self.dims[l + 1]):
+                raise ValueError(f"W[{l}] has shape {tuple(W.shape)}")
+            if self.bs[l] is not None and tuple(self.bs[l].shape) != (self.dims[l + 1],):
+                raise ValueError(f"b[{l}] has shape {tuple(self.bs[l].shape)}")
+        self.act, self.dtype = act, dtype
+        self.device = self.Ws[0].device
+        self._dims = (ctypes.c_int32 * (self.L + 1))(*self.dims)
+        self._W = (ctypes.c_void_p * self.L)(*[W.data_ptr() for W in self.Ws])
+        self._b = (ctypes.c_void_p * self.L)(*[None if b is None else b.data_ptr()
+                                               for b in self.bs])
+        self.c = pfg_mlp(self.L, self._dims, self._W, self._b, ACT[act], DTYPE[dtype])
+
+    @staticmethod
+    def from_numpy(Ws, bs, act: str, dtype: str = "f32", Ws_bits=None, bs_bits=None,
+                   device: str = "cuda:0") -> "Mlp":
+        """Upload host arrays.  For bf16 pass the uint16 bit patterns in ``Ws_bits``/``bs_bits``."""
+        import torch
+        if dtype == "f32":
+            tW = [torch.from_numpy(W).to(device) for W in Ws]
+            tb = None if bs is None else [None if b is None else torch.from_numpy(b).to(device)
+                                          for b in bs]
+        else:
+            tW = [torch.from_numpy(w.view("int16")).to(device).view(torch.bfloat16) for w in Ws_bits]
+            tb = None if bs_bits is None else [
+                None if b is None else torch.from_numpy(b.view("int16")).to(device).view(torch.bfloat16)
+                for b in bs_bits]
+        return Mlp(tW, tb, act, dtype)
+
+
+def _stream_ptr():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptrs(tensors: Sequence):
+    return (ctypes.c_void_p * len(tensors))(*[None if t is None else t.data_ptr() for t in tensors])
+
+
+def pfg_workspace_bytes(net: Mlp, op: str, B: int, S: int = 1) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().pfg_workspace_bytes(ctypes.byref(net.c), OP[op], B, S, ctypes.byref(n)))
+    return int(n.value)
+
+
+def _workspace(net: Mlp, op: str, B: int, S: int, workspace):
+    import torch
+    need = pfg_workspace_bytes(net, op, B, S)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=net.device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def _check_x(net: Mlp, X):
+    import torch
+    want = torch.float32 if net.dtype == "f32" else torch.bfloat16
+    if X.dtype != want or not X.is_contiguous() or X.dim() != 2 or X.shape[1] != net.dims[0]:
+        raise ValueError("X must be a contiguous [B, d_0] tensor of the network dtype")
+
+
+def pfg_per_example_grads(net: Mlp, X, labels, want_dW: Optional[Sequence[bool]] = None,
+                          want_db: bool = True, want_loss: bool = True, out_dW=None, out_db=None,
+                          out_loss=None, workspace=None):
+    """Returns (dW list [B, d_{l-1}, d_l] or None per layer, db list [B, d_l] or None, loss [B] or
+    None).  ``out_*`` reuse caller tensors instead of allocating."""
+    import torch
+    _check_x(net, X)
+    B = X.shape[0]
+    if labels.dtype != torch.int32 or tuple(labels.shape) != (B,) or not labels.is_contiguous():
+        raise ValueError("labels must be a contiguous int32 [B] tensor")
+    want = [True] * net.L if want_dW is None else list(want_dW)
+    f32 = dict(dtype=torch.float32, device=net.device)
+    dW = out_dW if out_dW is not None else [
+        torch.empty((B, net.dims[l], net.dims[l + 1]), **f32) if want[l] else None
+        for l in range(net.L)]
+    db = out_db if out_db is not None else (
+        [torch.empty((B, net.dims[l + 1]), **f32) for l in range(net.L)] if want_db else None)
+    loss = out_loss if out_loss is not None else (torch.empty((B,), **f32) if want_loss else None)
+    workspace, ws_bytes = _workspace(net, "per_example_grads", B, 1, workspace)
+    _check(load_library().pfg_per_example_grads(
+        ctypes.byref(net.c), X.data_ptr(), labels.data_ptr(), B, _ptrs(dW),
+        _ptrs(db) if db is not None else None, None if loss is None else loss.data_ptr(),
+        workspace.data_ptr(), ws_bytes, _stream_ptr()))
+    return dW, db, loss
+
+
+def _seed_args(net: Mlp, B: int, seeds, S: Optional[int]):
+    import torch
+    dL = net.dims[-1]
+    if seeds is None:
+        return None, (dL if S is None else S), 0
+    if seeds.dtype != torch.float32 or not seeds.is_contiguous() or seeds.shape[-1] != dL:
+        raise ValueError("seeds must be a contiguous float32 tensor with last dimension d_L")
+    if seeds.dim() == 2:
+        return seeds, seeds.shape[0], 0
+    if seeds.dim() != 3 or seeds.shape[0] != B:
+        raise ValueError("seeds must be [S, d_L] or [B, S, d_L]")
+    return seeds, seeds.shape[1], seeds.shape[1] * dL
+
+
+def pfg_jacobian_input(net: Mlp, X, seeds=None, S: Optional[int] = None, out=None, workspace=None):
+    """J[b, s, :] = gradient of <seed row s, y_b> with respect to x_b, shape [B, S, d_0]."""
+    import torch
+    _check_x(net, X)
+    B = X.shape[0]
+    seeds, S, stride = _seed_args(net, B, seeds, S)
+    J = out if out is not None else torch.empty((B, S, net.dims[0]), dtype=torch.float32,
+                                                device=net.device)
+    workspace, ws_bytes = _workspace(net, "jacobian_input", B, S, workspace)
+    _check(load_library().pfg_jacobian_input(
+        ctypes.byref(net.c), X.data_ptr(), B, None if seeds is None else seeds.data_ptr(), S,
+        stride, J.data_ptr(), workspace.data_ptr(), ws_bytes, _stream_ptr()))
+    return J
+
+
+def pfg_jacobian_weights(net: Mlp, X, head: str = "logits", seeds=None, S: Optional[int] = None,
+                         want_JW: Optional[Sequence[bool]] = None, want_Jb: bool = True,
+                         out_JW=None, out_Jb=None, workspace=None):
+    """Returns (JW list [B, S, d_{l-1}, d_l] or None per layer, Jb list [B, S, d_l] or None)."""
+    import torch
+    _check_x(net, X)
+    B = X.shape[0]
+    seeds, S, stride = _seed_args(net, B, seeds, S)
+    want = [True] * net.L if want_JW is None else list(want_JW)
+    f32 = dict(dtype=torch.float32, device=net.device)
+    JW = out_JW if out_JW is not None else [
+        torch.empty((B, S, net.dims[l], net.dims[l + 1]), **f32) if want[l] else None
+        for l in range(net.L)]
+    Jb = out_Jb if out_Jb is not None else (
+        [torch.empty((B, S, net.dims[l + 1]), **f32) for l in range(net.L)] if want_Jb else None)
+    workspace, ws_bytes = _workspace(net, "jacobian_weights", B, S, workspace)
+    _check(load_library().pfg_jacobian_weights(
+        ctypes.byref(net.c), X.data_ptr(), B, HEAD[head],
+        None if seeds is None else seeds.data_ptr(), S, stride, _ptrs(JW),
+        _ptrs(Jb) if Jb is not None else None, workspace.data_ptr(), ws_bytes, _stream_ptr()))
+    return JW, Jb
+
+
+def pfg_timing_enable(on: bool) -> None:
+    _check(load_library().pfg_timing_enable(1 if on else 0))
+
+
+def pfg_timing_reset() -> None:
+    _check(load_library().pfg_timing_reset())
+
+
+def pfg_timing_query(name: str):
+    """(launches, total milliseconds) of one kernel family since the last reset."""
+    n, ms = ctypes.c_int64(0), ctypes.c_double(0.0)
+    _check(load_library().pfg_timing_query(name.encode(), ctypes.byref(n), ctypes.byref(ms)))
+    return int(n.value), float(ms.value)
+
+
+def pfg_timing_names() -> List[str]:
+    buf = ctypes.create_string_buffer(4096)
+    _check(load_library().pfg_timing_names(buf, 4096))
+    s = buf.value.decode()
+    return s.split("\n") if s else []

@@ -1,0 +1,89 @@
+// Internal declarations shared by the HIP sources of libpfg (not part of the public C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pfg {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+enum Act : int { ACT_IDENTITY = 0, ACT_RELU = 1, ACT_TANH = 2, ACT_GELU = 3 };
+
+enum Epilogue : int {
+  EPI_NONE = 0,      // C = acc
+  EPI_BIAS = 1,      // C = acc + bias                      (last forward layer: logits)
+  EPI_FORWARD = 2,   // z = acc + bias; C = phi(z); C2 = phi'(z)   (hidden forward layer)
+  EPI_MASK = 3       // C = acc * emask[m / S, n]           (cotangent step)
+};
+
+// One matrix product  C[M, N] = Aeff[M, K] * Weff[K, N]  with fused prologue and epilogue.
+//
+// A operand.  Row m of A belongs to parallel-for iteration (b, s) = (m / S, m % S) and starts at
+//     A + b * a_batch_stride + s * lda            (elements)
+// a_batch_stride == 0 is a loop-invariant block shared by every b (never tiled in memory).
+// If a_scale is set, Aeff[m, k] = A[m, k] * a_scale[b * ld_scale + k]  (the activation-derivative
+// mask of the layer the cotangent sits at, broadcast over the seed index s).
+//
+// W operand.  w_kn == 1: W is [K, N] row-major (forward, a W).  w_kn == 0: W is [N, K] row-major
+// and the product uses its transpose (cotangent, g W^T).
+//
+// a_is_f32: A holds float32 even though the product runs in bf16 (rounded when staged).
+struct GemmArgs {
+  const void *A;
+  int64_t lda;
+  int64_t a_batch_stride;
+  int32_t S;
+  int32_t a_is_f32;
+  const float *a_scale;
+  int64_t ld_scale;
+  const void *W;
+  int64_t ldw;
+  int32_t w_kn;
+  int32_t bf16;         // operands of the product: 0 float32, 1 bfloat16
+  int32_t M, N, K;
+  const void *bias;     // [N] in the network dtype, or nullptr
+  int32_t epilogue;
+  int32_t act;
+  float *C;
+  int64_t ldc;
+  float *C2;
+  const float *emask;
+  int64_t ld_emask;
+  int32_t streaming;    // 1: C is written once and not read again by this call
+};
+
+hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream);
+
+// out[m, i, j] = a[m / S, i] * g[m, j]   for m < M, i < d_in, j < d_out   (float32 out)
+struct OuterArgs {
+  const void *a;        // [M / S, d_in], float32 or bf16
+  int64_t lda;
+  int32_t a_bf16;
+  const float *g;       // [M, d_out]
+  int64_t ldg;
+  float *out;           // [M, d_in, d_out]
+  int64_t M;
+  int32_t S;
+  int32_t d_in, d_out;
+};
+
+hipError_t launch_outer(const OuterArgs &o, hipStream_t stream);
+
+// delta[b, :] = softmax(y[b, :]) - onehot(labels[b]);  loss[b] = -log softmax(y[b])[labels[b]]
+hipError_t launch_head_softmax_ce(const float *y, const int32_t *labels, int64_t B, int32_t n,
+                                  float *delta, float *loss, hipStream_t stream);
+
+// G[b, s, :] = pull-back of seed row (b, s) through the head.  seeds == nullptr: identity rows.
+hipError_t launch_seed_rows(const float *y, const float *seeds, int64_t seed_batch_stride,
+                            int64_t B, int64_t S, int32_t n, int32_t head, float *G,
+                            hipStream_t stream);
+
+// dst[c, r] = (float) src[r, c]   for an [R, C] row-major src in float32 or bf16
+hipError_t launch_transpose(const void *src, int32_t src_bf16, int32_t R, int32_t C, float *dst,
+                            hipStream_t stream);
+
+}  // namespace pfg

@@ -1,0 +1,424 @@
+// MFMA-tiled matrix product for the stacked forward pass and the cotangent propagation.
+//
+// Section 3.4 of the paper turns matmul(X[i], Y) with a loop-invariant Y into ONE matmul over
+// the rows of all iterations folded together ([n * x, y] x [y, z]).  Here the folded row index is
+// m = b * S + s (example b, seed row s); the weights are the invariant operand and are never
+// tiled.  The activation-derivative mask, which is invariant over s, is broadcast in registers
+// (Section 3.4's broadcasting rule) either onto the A operand while it is staged or onto the
+// accumulators before they are stored.
+//
+// Tiling (gfx950, wave64): a workgroup is 4 waves in a 2 x 2 arrangement; each wave owns
+// TM x TN MFMA tiles of 32 x 32, so the workgroup tile is (64 TM) x (64 TN).  Both operands are
+// staged in LDS as [row][k] with 16 bytes of padding per row, so that one ds_read_b128 per lane
+// fetches 16 bytes of k for one row: four k-steps of v_mfma_f32_32x32x2_f32, or one
+// v_mfma_f32_32x32x16_bf16.  The k index is permuted identically for both operands, which a
+// contraction does not notice.  Global loads for stage t+1 are issued before the MFMA loop of
+// stage t and written to the other LDS buffer after it (one barrier per stage).
+#include "common.h"
+
+namespace pfg {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+enum AMode : int { A_F32 = 0, A_BF16 = 1, A_F32_TO_BF16 = 2 };
+
+__device__ __forceinline__ float act_value(int act, float z) {
+  switch (act) {
+    case ACT_RELU: return z > 0.f ? z : 0.f;
+    case ACT_TANH: return tanhf(z);
+    case ACT_GELU: return 0.5f * z * (1.f + erff(z * 0.70710678118654752440f));
+    default: return z;
+  }
+}
+
+__device__ __forceinline__ float act_deriv(int act, float z) {
+  switch (act) {
+    case ACT_RELU: return z > 0.f ? 1.f : 0.f;
+    case ACT_TANH: { float t = tanhf(z); return 1.f - t * t; }
+    case ACT_GELU: {
+      float Phi = 0.5f * (1.f + erff(z * 0.70710678118654752440f));
+      float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
+      return Phi + z * pdf;
+    }
+    default: return 1.f;
+  }
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// Up to 16 bytes of one operand row, k in [k0, k0 + n): float32 source.
+__device__ __forceinline__ f32x4 load4_f32(const float *row, int k0, int K, bool vec_ok) {
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (row == nullptr) return v;
+  if (vec_ok && k0 + 4 <= K) {
+    v = *reinterpret_cast<const f32x4 *>(row + k0);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (k0 + e < K) v[e] = row[k0 + e];
+  }
+  return v;
+}
+
+__device__ __forceinline__ u32x4 load8_bf16(const __bf16 *row, int k0, int K, bool vec_ok) {
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (row == nullptr) return v;
+  if (vec_ok && k0 + 8 <= K) {
+    v = *reinterpret_cast<const u32x4 *>(row + k0);
+  } else {
+    const uint16_t *r16 = reinterpret_cast<const uint16_t *>(row);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      uint32_t bits = (k0 + e < K) ? (uint32_t)r16[k0 + e] : 0u;
+      v[e >> 1] |= bits << ((e & 1) * 16);
+    }
+  }
+  return v;
+}
+
+// Raw registers of one 16-byte LDS chunk of the A operand, before scaling / rounding.
+template <int AMODE> struct RawA;
+template <> struct RawA<A_F32> { f32x4 v, s; };
+template <> struct RawA<A_BF16> { u32x4 v; };
+template <> struct RawA<A_F32_TO_BF16> { f32x4 v0, v1, s0, s1; };
+
+template <int AMODE>
+__device__ __forceinline__ RawA<AMODE> fetch_a(const void *row, const float *srow, int k0, int K,
+                                               bool vec_ok, bool svec_ok) {
+  RawA<AMODE> r;
+  if constexpr (AMODE == A_F32) {
+    r.v = load4_f32(static_cast<const float *>(row), k0, K, vec_ok);
+    if (srow) r.s = load4_f32(srow, k0, K, svec_ok);
+  } else if constexpr (AMODE == A_BF16) {
+    r.v = load8_bf16(static_cast<const __bf16 *>(row), k0, K, vec_ok);
+  } else {
+    r.v0 = load4_f32(static_cast<const float *>(row), k0, K, vec_ok);
+    r.v1 = load4_f32(static_cast<const float *>(row), k0 + 4, K, vec_ok);
+    if (srow) {
+      r.s0 = load4_f32(srow, k0, K, svec_ok);
+      r.s1 = load4_f32(srow, k0 + 4, K, svec_ok);
+    }
+  }
+  return r;
+}
+
+template <int AMODE>
+__device__ __forceinline__ u32x4 finish_a(const RawA<AMODE> &r, bool scaled) {
+  if constexpr (AMODE == A_F32) {
+    f32x4 v = scaled ? r.v * r.s : r.v;
+    return __builtin_bit_cast(u32x4, v);
+  } else if constexpr (AMODE == A_BF16) {
+    return r.v;
+  } else {
+    f32x4 a = scaled ? r.v0 * r.s0 : r.v0;
+    f32x4 b = scaled ? r.v1 * r.s1 : r.v1;
+    u32x4 o = {pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(b[0], b[1]),
+               pack_bf16(b[2], b[3])};
+    return o;
+  }
+}
+
+template <int AMODE, bool WKN, int TM, int TN, int BKB>
+__global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
+  constexpr bool BF16 = (AMODE != A_F32);
+  constexpr int ELEM = BF16 ? 2 : 4;
+  constexpr int EPC = 16 / ELEM;            // elements per 16-byte chunk
+  constexpr int BK = BKB / ELEM;            // k elements per stage
+  constexpr int CPR = BKB / 16;             // chunks per LDS row
+  constexpr int STRIDE = BKB + 16;          // LDS row stride in bytes
+  constexpr int BM = 64 * TM, BN = 64 * TN;
+  constexpr int A_CHUNKS = BM * CPR / kThreads;
+  constexpr int W_CHUNKS = BN * CPR / kThreads;
+  constexpr int STAGE = (BM + BN) * STRIDE;
+  static_assert(BM * CPR % kThreads == 0 && BN * CPR % kThreads == 0, "tile / thread mismatch");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int half = lane >> 5;
+  const int l32 = lane & 31;
+  const int wm = (wave >> 1) * (32 * TM);
+  const int wn = (wave & 1) * (32 * TN);
+
+  // Workgroup -> tile.  Consecutive workgroup ids walk down M first, so that the workgroups
+  // resident at one time share a narrow band of W columns.
+  const int tiles_m = (g.M + BM - 1) / BM;
+  const int tile_m = blockIdx.x % tiles_m;
+  const int tile_n = blockIdx.x / tiles_m;
+  const int m0 = tile_m * BM;
+  const int n0 = tile_n * BN;
+  const int M = g.M, N = g.N, K = g.K;
+
+  const bool a_vec_ok = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
+                        ((g.lda * (AMODE == A_BF16 ? 2 : 4)) % 16 == 0) &&
+                        ((g.a_batch_stride * (AMODE == A_BF16 ? 2 : 4)) % 16 == 0);
+  const bool s_vec_ok = g.a_scale && ((reinterpret_cast<uintptr_t>(g.a_scale) & 15) == 0) &&
+                        ((g.ld_scale * 4) % 16 == 0);
+  const bool w_vec_ok = ((reinterpret_cast<uintptr_t>(g.W) & 15) == 0) &&
+                        ((g.ldw * ELEM) % 16 == 0);
+  const bool scaled = (g.a_scale != nullptr);
+
+  // ---- per-thread staging assignments ----
+  const void *a_row[A_CHUNKS];
+  const float *a_srow[A_CHUNKS];
+  int a_lds[A_CHUNKS];
+  int a_k[A_CHUNKS];
+#pragma unroll
+  for (int c = 0; c < A_CHUNKS; ++c) {
+    const int id = tid + kThreads * c;
+    const int row = id / CPR, kc = id % CPR;
+    const int m = m0 + row;
+    a_lds[c] = row * STRIDE + kc * 16;
+    a_k[c] = kc * EPC;
+    a_row[c] = nullptr;
+    a_srow[c] = nullptr;
+    if (m < M) {
+      const int64_t b = m / g.S, s = m % g.S;
+      const int64_t off = b * g.a_batch_stride + s * g.lda;
+      if constexpr (AMODE == A_BF16)
+        a_row[c] = static_cast<const __bf16 *>(g.A) + off;
+      else
+        a_row[c] = static_cast<const float *>(g.A) + off;
+      if (scaled) a_srow[c] = g.a_scale + b * g.ld_scale;
+    }
+  }
+
+  // W chunks.  WKN == false: rows are n, 16 bytes along k (same shape as A).
+  // WKN == true: W is [K, N]; a chunk is 16 bytes along n at one k and is scattered into the
+  // [n][k] LDS layout element by element.
+  const void *w_row[W_CHUNKS];   // !WKN: row pointer of n (or nullptr)
+  int w_lds[W_CHUNKS];
+  int w_k[W_CHUNKS];             // k offset of the chunk inside a stage
+  int w_n[W_CHUNKS];             // WKN: first n of the chunk (global)
+#pragma unroll
+  for (int c = 0; c < W_CHUNKS; ++c) {
+    const int id = tid + kThreads * c;
+    if constexpr (!WKN) {
+      const int row = id / CPR, kc = id % CPR;
+      const int n = n0 + row;
+      w_lds[c] = row * STRIDE + kc * 16;
+      w_k[c] = kc * EPC;
+      w_n[c] = n;
+      w_row[c] = nullptr;
+      if (n < N) {
+        if constexpr (BF16)
+          w_row[c] = static_cast<const __bf16 *>(g.W) + (int64_t)n * g.ldw;
+        else
+          w_row[c] = static_cast<const float *>(g.W) + (int64_t)n * g.ldw;
+      }
+    } else {
+      const int kl = id % BK, ng = id / BK;
+      w_k[c] = kl;
+      w_n[c] = n0 + ng * EPC;
+      w_lds[c] = (ng * EPC) * STRIDE + kl * ELEM;
+      w_row[c] = nullptr;
+    }
+  }
+
+  RawA<AMODE> ra[A_CHUNKS];
+  u32x4 rw[W_CHUNKS];
+
+  auto fetch = [&](int kt) {
+    const int kbase = kt * BK;
+#pragma unroll
+    for (int c = 0; c < A_CHUNKS; ++c)
+      ra[c] = fetch_a<AMODE>(a_row[c], a_srow[c], kbase + a_k[c], K, a_vec_ok, s_vec_ok);
+#pragma unroll
+    for (int c = 0; c < W_CHUNKS; ++c) {
+      if constexpr (!WKN) {
+        if constexpr (BF16)
+          rw[c] = load8_bf16(static_cast<const __bf16 *>(w_row[c]), kbase + w_k[c], K, w_vec_ok);
+        else
+          rw[c] = __builtin_bit_cast(
+              u32x4, load4_f32(static_cast<const float *>(w_row[c]), kbase + w_k[c], K, w_vec_ok));
+      } else {
+        const int k = kbase + w_k[c];
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (k < K) {
+          if constexpr (BF16) {
+            const __bf16 *row = static_cast<const __bf16 *>(g.W) + (int64_t)k * g.ldw;
+            v = load8_bf16(w_n[c] < N ? row : nullptr, w_n[c], N, w_vec_ok);
+          } else {
+            const float *row = static_cast<const float *>(g.W) + (int64_t)k * g.ldw;
+            v = __builtin_bit_cast(u32x4, load4_f32(w_n[c] < N ? row : nullptr, w_n[c], N, w_vec_ok));
+          }
+        }
+        rw[c] = v;
+      }
+    }
+  };
+
+  auto stash = [&](int buf) {
+    unsigned char *sA = smem + buf * STAGE;
+    unsigned char *sW = sA + BM * STRIDE;
+#pragma unroll
+    for (int c = 0; c < A_CHUNKS; ++c)
+      *reinterpret_cast<u32x4 *>(sA + a_lds[c]) = finish_a<AMODE>(ra[c], scaled);
+#pragma unroll
+    for (int c = 0; c < W_CHUNKS; ++c) {
+      if constexpr (!WKN) {
+        *reinterpret_cast<u32x4 *>(sW + w_lds[c]) = rw[c];
+      } else if constexpr (BF16) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          *reinterpret_cast<uint16_t *>(sW + w_lds[c] + e * STRIDE) =
+              (uint16_t)(rw[c][e >> 1] >> ((e & 1) * 16));
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          *reinterpret_cast<uint32_t *>(sW + w_lds[c] + e * STRIDE) = rw[c][e];
+      }
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = (K + BK - 1) / BK;
+  fetch(0);
+  stash(0);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) fetch(kt + 1);
+
+    const unsigned char *sA = smem + buf * STAGE + (wm + l32) * STRIDE + half * 16;
+    const unsigned char *sW = smem + buf * STAGE + BM * STRIDE + (wn + l32) * STRIDE + half * 16;
+#pragma unroll
+    for (int step = 0; step < CPR / 2; ++step) {
+      u32x4 av[TM], wv[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        av[i] = *reinterpret_cast<const u32x4 *>(sA + i * 32 * STRIDE + step * 32);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        wv[j] = *reinterpret_cast<const u32x4 *>(sW + j * 32 * STRIDE + step * 32);
+      if constexpr (BF16) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, av[i]), __builtin_bit_cast(bf16x8, wv[j]), acc[i][j], 0, 0,
+                0);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                  __builtin_bit_cast(float, av[i][e]), __builtin_bit_cast(float, wv[j][e]),
+                  acc[i][j], 0, 0, 0);
+      }
+    }
+
+    if (kt + 1 < nk) stash(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: accumulator element r of lane (half, l32) is row 8 (r / 4) + 4 half + r % 4,
+  // column l32 of its 32 x 32 tile ----
+  const int epi = g.epilogue;
+  float bias[TN];
+  bool n_ok[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = n0 + wn + j * 32 + l32;
+    n_ok[j] = n < N;
+    bias[j] = 0.f;
+    if (n_ok[j] && (epi == EPI_BIAS || epi == EPI_FORWARD) && g.bias) {
+      if (g.bf16)
+        bias[j] = (float)static_cast<const __bf16 *>(g.bias)[n];
+      else
+        bias[j] = static_cast<const float *>(g.bias)[n];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (m >= M) continue;
+      const float *mrow = (epi == EPI_MASK) ? g.emask + (int64_t)(m / g.S) * g.ld_emask : nullptr;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        if (!n_ok[j]) continue;
+        const int n = n0 + wn + j * 32 + l32;
+        float v = acc[i][j][r];
+        const int64_t o = (int64_t)m * g.ldc + n;
+        if (epi == EPI_FORWARD) {
+          const float z = v + bias[j];
+          g.C2[o] = act_deriv(g.act, z);
+          if (g.C == nullptr) continue;       // only phi'(z) is wanted
+          v = act_value(g.act, z);
+        } else if (epi == EPI_BIAS) {
+          v += bias[j];
+        } else if (epi == EPI_MASK) {
+          v *= mrow[n];
+        }
+        if (g.streaming)
+          __builtin_nontemporal_store(v, g.C + o);
+        else
+          g.C[o] = v;
+      }
+    }
+  }
+}
+
+template <int AMODE, bool WKN, int TM, int TN, int BKB>
+hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
+  constexpr int BM = 64 * TM, BN = 64 * TN;
+  constexpr int smem = 2 * (BM + BN) * (BKB + 16);
+  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB>;
+  static bool attr_set = false;   // benign race: the attribute is idempotent
+  if (!attr_set && smem > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int64_t tiles = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(kThreads), smem, stream, g);
+  return hipGetLastError();
+}
+
+template <int AMODE, bool WKN>
+hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
+  // Large tiles once they still give the 256 compute units a full wave of workgroups; otherwise
+  // 64 x 64 tiles, so that small-batch products (M = B) spread over more units.
+  const int64_t big = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
+  if (big >= 256) return launch_one<AMODE, WKN, 2, 2, 128>(g, stream);
+  return launch_one<AMODE, WKN, 1, 1, 128>(g, stream);
+}
+
+}  // namespace
+
+hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipSuccess;
+  if (!g.bf16) {
+    return g.w_kn ? launch_tiles<A_F32, true>(g, stream) : launch_tiles<A_F32, false>(g, stream);
+  }
+  if (g.a_is_f32) {
+    return g.w_kn ? launch_tiles<A_F32_TO_BF16, true>(g, stream)
+                  : launch_tiles<A_F32_TO_BF16, false>(g, stream);
+  }
+  return g.w_kn ? launch_tiles<A_BF16, true>(g, stream) : launch_tiles<A_BF16, false>(g, stream);
+}
+
+}  // namespace pfg

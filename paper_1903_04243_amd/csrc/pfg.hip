@@ -1,0 +1,509 @@
+// C ABI of libpfg: argument checks, workspace layout and the order in which the kernels of the
+// three operations are enqueued.  No arithmetic of the method happens on the host.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/pfg.h"
+#include "common.h"
+
+namespace {
+
+using namespace pfg;
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+// ------------------------------------------------------------------------------------------
+// Per-kernel timing with HIP events on the call's stream.
+// ------------------------------------------------------------------------------------------
+struct TimedLaunch { const char *name; hipEvent_t start, stop; };
+std::mutex g_timing_mu;
+bool g_timing_on = false;
+std::vector<TimedLaunch> g_pending;
+std::map<std::string, std::pair<int64_t, double>> g_totals;
+
+struct TimedScope {
+  const char *name;
+  hipStream_t stream;
+  hipEvent_t start = nullptr, stop = nullptr;
+  bool on;
+  TimedScope(const char *n, hipStream_t s) : name(n), stream(s), on(g_timing_on) {
+    if (!on) return;
+    if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) { on = false; return; }
+    (void)hipEventRecord(start, stream);
+  }
+  ~TimedScope() {
+    if (!on) return;
+    (void)hipEventRecord(stop, stream);
+    std::lock_guard<std::mutex> lk(g_timing_mu);
+    g_pending.push_back({name, start, stop});
+  }
+};
+
+void drain_pending() {
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  for (auto &t : g_pending) {
+    float ms = 0.f;
+    if (hipEventSynchronize(t.stop) == hipSuccess &&
+        hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) {
+      auto &e = g_totals[t.name];
+      e.first += 1;
+      e.second += ms;
+    }
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
+  }
+  g_pending.clear();
+}
+
+// ------------------------------------------------------------------------------------------
+// Validation helpers.
+// ------------------------------------------------------------------------------------------
+constexpr int kMaxLayers = 256;
+constexpr int64_t kMaxDim = 1 << 24;
+constexpr int64_t kMaxRows = 0x7fffffffLL;          // folded iteration index m = b * S + s
+constexpr int64_t kMaxElems = (int64_t)1 << 46;     // per tensor
+
+int check_net(const pfg_mlp *net) {
+  if (!net) return fail(PFG_ERR_NULL, "net is NULL");
+  if (net->num_layers < 1 || net->num_layers > kMaxLayers)
+    return fail(PFG_ERR_SHAPE, "num_layers = %d is outside [1, %d]", net->num_layers, kMaxLayers);
+  if (!net->dims) return fail(PFG_ERR_NULL, "net->dims is NULL");
+  for (int l = 0; l <= net->num_layers; ++l)
+    if (net->dims[l] < 1 || net->dims[l] > kMaxDim)
+      return fail(PFG_ERR_SHAPE, "dims[%d] = %d is outside [1, %lld]", l, net->dims[l],
+                  (long long)kMaxDim);
+  if (net->hidden_act < PFG_ACT_IDENTITY || net->hidden_act > PFG_ACT_GELU_ERF)
+    return fail(PFG_ERR_UNSUPPORTED, "unknown activation %d", net->hidden_act);
+  if (net->dtype != PFG_F32 && net->dtype != PFG_BF16)
+    return fail(PFG_ERR_UNSUPPORTED, "unknown dtype %d", net->dtype);
+  return PFG_OK;
+}
+
+int check_weights(const pfg_mlp *net) {
+  if (!net->W) return fail(PFG_ERR_NULL, "net->W is NULL");
+  for (int l = 0; l < net->num_layers; ++l)
+    if (!net->W[l]) return fail(PFG_ERR_NULL, "net->W[%d] is NULL", l);
+  return PFG_OK;
+}
+
+int check_rows(int64_t B, int64_t S) {
+  if (B < 1) return fail(PFG_ERR_SHAPE, "B = %lld must be at least 1", (long long)B);
+  if (S < 1) return fail(PFG_ERR_SHAPE, "S = %lld must be at least 1", (long long)S);
+  if (B > kMaxRows || S > kMaxRows || B * S > kMaxRows)
+    return fail(PFG_ERR_OVERFLOW, "B * S = %lld * %lld exceeds %lld rows", (long long)B,
+                (long long)S, (long long)kMaxRows);
+  return PFG_OK;
+}
+
+int check_elems(const pfg_mlp *net, int64_t rows) {
+  for (int l = 1; l <= net->num_layers; ++l) {
+    const int64_t per = (int64_t)net->dims[l - 1] * net->dims[l];
+    if (per > kMaxElems / rows)
+      return fail(PFG_ERR_OVERFLOW, "layer %d: %lld x %d x %d values exceed the indexing limit", l,
+                  (long long)rows, net->dims[l - 1], net->dims[l]);
+  }
+  return PFG_OK;
+}
+
+int check_seeds(const pfg_mlp *net, const float *seeds, int64_t S, int64_t stride) {
+  const int dL = net->dims[net->num_layers];
+  if (!seeds) {
+    if (S != dL)
+      return fail(PFG_ERR_SHAPE, "identity seeds (seeds == NULL) need S == d_L, got S = %lld, d_L = %d",
+                  (long long)S, dL);
+    return PFG_OK;
+  }
+  if (stride != 0 && stride < S * dL)
+    return fail(PFG_ERR_SHAPE, "seed_batch_stride = %lld must be 0 or at least S * d_L = %lld",
+                (long long)stride, (long long)(S * dL));
+  return PFG_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Workspace layout.  Every block is 256-byte aligned.
+// ------------------------------------------------------------------------------------------
+struct Plan {
+  size_t total = 0;
+  std::vector<size_t> act, dphi, G;   // indexed by layer l (1-based; entry 0 unused)
+  size_t logits = 0, P = 0, ping = 0, pong = 0;
+  size_t take(size_t bytes) {
+    const size_t at = total;
+    total += (bytes + 255) / 256 * 256;
+    return at;
+  }
+};
+
+Plan make_plan(const pfg_mlp *net, int op, int64_t B, int64_t S) {
+  const int L = net->num_layers;
+  const int32_t *d = net->dims;
+  Plan p;
+  p.act.assign(L + 1, 0);
+  p.dphi.assign(L + 1, 0);
+  p.G.assign(L + 1, 0);
+  const int hidden_last = L - 1;
+  for (int l = 1; l <= hidden_last; ++l) {
+    p.act[l] = p.take(sizeof(float) * B * d[l]);
+    p.dphi[l] = p.take(sizeof(float) * B * d[l]);
+  }
+  if (op == PFG_OP_JACOBIAN_INPUT) {
+    size_t widest = 0;
+    for (int l = 1; l <= hidden_last; ++l) widest = widest > (size_t)d[l] ? widest : (size_t)d[l];
+    // loop-invariant seed block: [S, d_{L-1}] after the first step, or the [S, d_L] identity of
+    // a one-layer network
+    p.P = p.take(sizeof(float) * S * (L >= 2 ? d[L - 1] : d[L]));
+    // two folded cotangent blocks [B * S, widest hidden width] used alternately
+    p.ping = p.take(sizeof(float) * B * S * (widest ? widest : 1));
+    p.pong = p.take(sizeof(float) * B * S * (widest ? widest : 1));
+  } else {
+    const int64_t rows = (op == PFG_OP_JACOBIAN_WEIGHTS) ? B * S : B;
+    p.logits = p.take(sizeof(float) * B * d[L]);
+    for (int l = 1; l <= L; ++l) p.G[l] = p.take(sizeof(float) * rows * d[l]);
+  }
+  if (p.total == 0) p.total = 256;
+  return p;
+}
+
+int check_workspace(const Plan &p, void *ws, size_t bytes) {
+  if (!ws) return fail(PFG_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", p.total);
+  if (reinterpret_cast<uintptr_t>(ws) & 255)
+    return fail(PFG_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  if (bytes < p.total)
+    return fail(PFG_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", bytes, p.total);
+  return PFG_OK;
+}
+
+inline float *at(void *ws, size_t off) { return reinterpret_cast<float *>(static_cast<char *>(ws) + off); }
+
+#define PFG_LAUNCH(name, expr)                                                         \
+  do {                                                                                 \
+    hipError_t e_;                                                                     \
+    { TimedScope ts_(name, stream); e_ = (expr); }                                     \
+    if (e_ != hipSuccess)                                                              \
+      return fail(PFG_ERR_DEVICE, "%s: %s", name, hipGetErrorString(e_));              \
+  } while (0)
+
+const void *bias_of(const pfg_mlp *net, int l) { return net->b ? net->b[l - 1] : nullptr; }
+
+// Stacked forward pass through layers 1..upto.  Hidden layers store a_l and phi'(z_l); layer L
+// (if reached) stores the logits.
+int forward(const pfg_mlp *net, const void *X, int64_t B, int upto, void *ws, const Plan &p,
+            bool keep_last_hidden_act, hipStream_t stream) {
+  const int L = net->num_layers;
+  const int32_t *d = net->dims;
+  for (int l = 1; l <= upto; ++l) {
+    GemmArgs g{};
+    g.A = (l == 1) ? X : at(ws, p.act[l - 1]);
+    g.lda = d[l - 1];
+    g.a_batch_stride = d[l - 1];
+    g.S = 1;
+    g.a_is_f32 = (l == 1) ? (net->dtype == PFG_F32) : 1;
+    g.W = net->W[l - 1];
+    g.ldw = d[l];
+    g.w_kn = 1;
+    g.bf16 = (net->dtype == PFG_BF16);
+    g.M = (int32_t)B;
+    g.N = d[l];
+    g.K = d[l - 1];
+    g.bias = bias_of(net, l);
+    g.act = net->hidden_act;
+    g.ldc = d[l];
+    if (l < L) {
+      g.epilogue = EPI_FORWARD;
+      g.C = (l == upto && !keep_last_hidden_act) ? nullptr : at(ws, p.act[l]);
+      g.C2 = at(ws, p.dphi[l]);
+    } else {
+      g.epilogue = EPI_BIAS;
+      g.C = at(ws, p.logits);
+    }
+    PFG_LAUNCH("gemm_forward", launch_gemm(g, stream));
+  }
+  return PFG_OK;
+}
+
+// G_{l-1} = (G_l W_l^T) * phi'(z_{l-1}) on the folded rows m = b * S + s.
+int cotangent_step(const pfg_mlp *net, int l, const float *G_l, int64_t rows, int64_t S,
+                   float *G_prev, void *ws, const Plan &p, hipStream_t stream) {
+  const int32_t *d = net->dims;
+  GemmArgs g{};
+  g.A = G_l;
+  g.lda = d[l];
+  g.a_batch_stride = S * d[l];
+  g.S = (int32_t)S;
+  g.a_is_f32 = 1;
+  g.W = net->W[l - 1];
+  g.ldw = d[l];
+  g.w_kn = 0;
+  g.bf16 = (net->dtype == PFG_BF16);
+  g.M = (int32_t)rows;
+  g.N = d[l - 1];
+  g.K = d[l];
+  g.epilogue = EPI_MASK;
+  g.emask = at(ws, p.dphi[l - 1]);
+  g.ld_emask = d[l - 1];
+  g.C = G_prev;
+  g.ldc = d[l - 1];
+  PFG_LAUNCH("gemm_cotangent", launch_gemm(g, stream));
+  return PFG_OK;
+}
+
+int outer(const pfg_mlp *net, int l, const void *X, const float *G_l, int64_t rows, int64_t S,
+          float *out, void *ws, const Plan &p, hipStream_t stream) {
+  const int32_t *d = net->dims;
+  OuterArgs o{};
+  o.a = (l == 1) ? X : at(ws, p.act[l - 1]);
+  o.lda = d[l - 1];
+  o.a_bf16 = (l == 1) && (net->dtype == PFG_BF16);
+  o.g = G_l;
+  o.ldg = d[l];
+  o.out = out;
+  o.M = rows;
+  o.S = (int32_t)S;
+  o.d_in = d[l - 1];
+  o.d_out = d[l];
+  PFG_LAUNCH("outer_product", launch_outer(o, stream));
+  return PFG_OK;
+}
+
+// Backward sweep shared by the two weight-gradient operations: G_L is already in place.
+int weight_sweep(const pfg_mlp *net, const void *X, int64_t B, int64_t S, float *const *W_out,
+                 float *const *b_out, std::vector<float *> &G, void *ws, const Plan &p,
+                 hipStream_t stream) {
+  const int L = net->num_layers;
+  int lowest = L + 1;
+  for (int l = 1; l <= L; ++l)
+    if ((W_out && W_out[l - 1]) || (b_out && b_out[l - 1])) { lowest = l; break; }
+  for (int l = L; l >= lowest; --l) {
+    if (W_out && W_out[l - 1]) {
+      int rc = outer(net, l, X, G[l], B * S, S, W_out[l - 1], ws, p, stream);
+      if (rc) return rc;
+    }
+    if (l > lowest) {
+      int rc = cotangent_step(net, l, G[l], B * S, S, G[l - 1], ws, p, stream);
+      if (rc) return rc;
+    }
+  }
+  return PFG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pfg_version(void) { return 100; }
+
+const char *pfg_last_error(void) { return g_err; }
+
+int pfg_timing_enable(int on) {
+  g_timing_on = (on != 0);
+  return PFG_OK;
+}
+
+int pfg_timing_reset(void) {
+  drain_pending();
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  g_totals.clear();
+  return PFG_OK;
+}
+
+int pfg_timing_query(const char *name, int64_t *launches, double *total_ms) {
+  if (!name || !launches || !total_ms) return fail(PFG_ERR_NULL, "pfg_timing_query: NULL argument");
+  drain_pending();
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  auto it = g_totals.find(name);
+  if (it == g_totals.end()) return fail(PFG_ERR_SHAPE, "no launch of '%s' was recorded", name);
+  *launches = it->second.first;
+  *total_ms = it->second.second;
+  return PFG_OK;
+}
+
+int pfg_timing_names(char *buf, size_t cap) {
+  if (!buf || cap == 0) return fail(PFG_ERR_NULL, "pfg_timing_names: NULL buffer");
+  drain_pending();
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  std::string s;
+  for (auto &kv : g_totals) {
+    if (!s.empty()) s += "\n";
+    s += kv.first;
+  }
+  snprintf(buf, cap, "%s", s.c_str());
+  return PFG_OK;
+}
+
+int pfg_workspace_bytes(const pfg_mlp *net, int op, int64_t B, int64_t S, size_t *bytes) {
+  g_err[0] = 0;
+  int rc = check_net(net);
+  if (rc) return rc;
+  if (!bytes) return fail(PFG_ERR_NULL, "bytes is NULL");
+  if (op < PFG_OP_PER_EXAMPLE_GRADS || op > PFG_OP_JACOBIAN_WEIGHTS)
+    return fail(PFG_ERR_UNSUPPORTED, "unknown op %d", op);
+  if (op == PFG_OP_PER_EXAMPLE_GRADS) S = 1;
+  if ((rc = check_rows(B, S))) return rc;
+  if ((rc = check_elems(net, B * S))) return rc;
+  *bytes = make_plan(net, op, B, S).total;
+  return PFG_OK;
+}
+
+int pfg_per_example_grads(const pfg_mlp *net, const void *X, const int32_t *labels, int64_t B,
+                          float *const *dW_out, float *const *db_out, float *loss_out,
+                          void *workspace, size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  int rc = check_net(net);
+  if (rc) return rc;
+  if ((rc = check_weights(net))) return rc;
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
+  if ((rc = check_rows(B, 1))) return rc;
+  if ((rc = check_elems(net, B))) return rc;
+  const Plan p = make_plan(net, PFG_OP_PER_EXAMPLE_GRADS, B, 1);
+  if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int L = net->num_layers;
+  const int32_t *d = net->dims;
+
+  if ((rc = forward(net, X, B, L, workspace, p, true, stream))) return rc;
+
+  // delta_l lives in the caller's db_out[l-1] when given (db_l = delta_l), else in the workspace
+  std::vector<float *> G(L + 1, nullptr);
+  for (int l = 1; l <= L; ++l)
+    G[l] = (db_out && db_out[l - 1]) ? db_out[l - 1] : at(workspace, p.G[l]);
+
+  PFG_LAUNCH("head", launch_head_softmax_ce(at(workspace, p.logits), labels, B, d[L], G[L],
+                                            loss_out, stream));
+  return weight_sweep(net, X, B, 1, dW_out, db_out, G, workspace, p, stream);
+}
+
+int pfg_jacobian_input(const pfg_mlp *net, const void *X, int64_t B, const float *seeds, int64_t S,
+                       int64_t seed_batch_stride, float *J_out, void *workspace,
+                       size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  int rc = check_net(net);
+  if (rc) return rc;
+  if ((rc = check_weights(net))) return rc;
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!J_out) return fail(PFG_ERR_NULL, "J_out is NULL");
+  if ((rc = check_rows(B, S))) return rc;
+  if ((rc = check_seeds(net, seeds, S, seed_batch_stride))) return rc;
+  if ((rc = check_elems(net, B * S))) return rc;
+  const Plan p = make_plan(net, PFG_OP_JACOBIAN_INPUT, B, S);
+  if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int L = net->num_layers;
+  const int32_t *d = net->dims;
+  const bool bf16 = (net->dtype == PFG_BF16);
+  const int64_t rows = B * S;
+
+  // the logits themselves are not needed: the Jacobian depends on phi'(z_l), l < L, only
+  if ((rc = forward(net, X, B, L - 1, workspace, p, false, stream))) return rc;
+
+  // Current cotangent block: rows (b, s) at cur + b * cur_bstride + s * cur_ld, times an optional
+  // pending mask row b of cur_scale (the mask is invariant over s and is applied while the block
+  // is staged as the A operand of the next product).
+  const float *cur = seeds;
+  int64_t cur_ld = d[L], cur_bstride = seed_batch_stride;
+  const float *cur_scale = nullptr;
+  int64_t cur_scale_ld = 0;
+  int level = L;     // cur is the cotangent at the output of layer `level`
+  float *bufs[2] = {at(workspace, p.ping), at(workspace, p.pong)};
+  int which = 0;
+
+  const bool shared = (seeds == nullptr) || (seed_batch_stride == 0);
+  if (shared && L >= 2) {
+    // Loop-invariant seeds: G_{L-1}[b, s, :] = (seeds[s, :] W_L^T) * phi'(z_{L-1}[b, :]).  The
+    // product in brackets does not depend on b, so it is formed once ([S, d_{L-1}], not stacked)
+    // and the mask is left pending.  Identity seeds make it a transpose of W_L.
+    float *P = at(workspace, p.P);
+    if (!seeds) {
+      PFG_LAUNCH("transpose", launch_transpose(net->W[L - 1], bf16, d[L - 1], d[L], P, stream));
+    } else {
+      GemmArgs g{};
+      g.A = seeds; g.lda = d[L]; g.a_batch_stride = 0; g.S = (int32_t)S; g.a_is_f32 = 1;
+      g.W = net->W[L - 1]; g.ldw = d[L]; g.w_kn = 0; g.bf16 = bf16;
+      g.M = (int32_t)S; g.N = d[L - 1]; g.K = d[L];
+      g.epilogue = EPI_NONE; g.C = P; g.ldc = d[L - 1];
+      PFG_LAUNCH("gemm_cotangent", launch_gemm(g, stream));
+    }
+    cur = P; cur_ld = d[L - 1]; cur_bstride = 0;
+    cur_scale = at(workspace, p.dphi[L - 1]); cur_scale_ld = d[L - 1];
+    level = L - 1;
+  }
+
+  for (int l = level; l >= 1; --l) {
+    GemmArgs g{};
+    g.S = (int32_t)S;
+    g.a_is_f32 = 1;
+    g.a_scale = cur_scale; g.ld_scale = cur_scale_ld;
+    g.W = net->W[l - 1]; g.ldw = d[l]; g.w_kn = 0; g.bf16 = bf16;
+    g.M = (int32_t)rows; g.N = d[l - 1]; g.K = d[l];
+    if (cur == nullptr) {
+      // identity seeds of a one-layer network: J[b] = W_1^T for every b
+      float *P = at(workspace, p.P);
+      PFG_LAUNCH("seed_rows", launch_seed_rows(nullptr, nullptr, 0, 1, S, d[L], 0, P, stream));
+      cur = P; cur_ld = d[L]; cur_bstride = 0;
+    }
+    g.A = cur; g.lda = cur_ld; g.a_batch_stride = cur_bstride;
+    if (l > 1) {
+      g.epilogue = EPI_MASK;
+      g.emask = at(workspace, p.dphi[l - 1]); g.ld_emask = d[l - 1];
+      g.C = bufs[which]; g.ldc = d[l - 1];
+      PFG_LAUNCH("gemm_cotangent", launch_gemm(g, stream));
+      cur = bufs[which]; cur_ld = d[l - 1]; cur_bstride = S * d[l - 1];
+      cur_scale = nullptr; cur_scale_ld = 0;
+      which ^= 1;
+    } else {
+      g.epilogue = EPI_NONE;
+      g.C = J_out; g.ldc = d[0];
+      g.streaming = 1;
+      PFG_LAUNCH("gemm_jacobian", launch_gemm(g, stream));
+    }
+  }
+  return PFG_OK;
+}
+
+int pfg_jacobian_weights(const pfg_mlp *net, const void *X, int64_t B, int head, const float *seeds,
+                         int64_t S, int64_t seed_batch_stride, float *const *JW_out,
+                         float *const *Jb_out, void *workspace, size_t workspace_bytes,
+                         void *hip_stream) {
+  g_err[0] = 0;
+  int rc = check_net(net);
+  if (rc) return rc;
+  if ((rc = check_weights(net))) return rc;
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (head != PFG_HEAD_LOGITS && head != PFG_HEAD_SOFTMAX)
+    return fail(PFG_ERR_UNSUPPORTED, "unknown head %d", head);
+  if ((rc = check_rows(B, S))) return rc;
+  if ((rc = check_seeds(net, seeds, S, seed_batch_stride))) return rc;
+  if ((rc = check_elems(net, B * S))) return rc;
+  const Plan p = make_plan(net, PFG_OP_JACOBIAN_WEIGHTS, B, S);
+  if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int L = net->num_layers;
+  const int32_t *d = net->dims;
+
+  if ((rc = forward(net, X, B, L, workspace, p, true, stream))) return rc;
+
+  std::vector<float *> G(L + 1, nullptr);
+  for (int l = 1; l <= L; ++l)
+    G[l] = (Jb_out && Jb_out[l - 1]) ? Jb_out[l - 1] : at(workspace, p.G[l]);
+
+  PFG_LAUNCH("seed_rows", launch_seed_rows(at(workspace, p.logits), seeds, seed_batch_stride, B, S,
+                                           d[L], head, G[L], stream));
+  return weight_sweep(net, X, B, S, JW_out, Jb_out, G, workspace, p, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,180 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol that
+include/pfg.h declares, sizes workspaces as documented and rejects bad arguments before anything
+is enqueued (no kernel is launched by any test in this file)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_1903_04243_amd as pfg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(pfg.LIB_PATH):
+        from paper_1903_04243_amd import build
+        build.build()
+    return pfg.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "pfg.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pfg_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert set(names) == set(pfg.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert lib.pfg_version() == 100
+
+
+FAKE = 0x1000  # a non-NULL, 256-aligned value; never dereferenced because validation fails first
+
+
+def make_net(dims, act=1, dtype=0, W_null_at=None, with_W=True):
+    L = len(dims) - 1
+    d = (ctypes.c_int32 * (L + 1))(*dims)
+    W = (ctypes.c_void_p * L)(*[None if W_null_at == l else FAKE for l in range(L)])
+    net = pfg.pfg_mlp(L, d, W if with_W else None, None, act, dtype)
+    net._keep = (d, W)
+    return net
+
+
+def ws_bytes(lib, net, op, B, S):
+    n = ctypes.c_size_t(0)
+    rc = lib.pfg_workspace_bytes(ctypes.byref(net), op, B, S, ctypes.byref(n))
+    return rc, n.value
+
+
+def up(x):
+    return (x + 255) // 256 * 256
+
+
+def test_workspace_sizes(lib):
+    net = make_net([784, 512, 512, 10])
+    B = 128
+    rc, n = ws_bytes(lib, net, 0, B, 1)
+    assert rc == 0
+    expect = 4 * up(4 * B * 512) + up(4 * B * 10) + 2 * up(4 * B * 512) + up(4 * B * 10)
+    assert n == expect
+    # per-example gradients ignore S
+    assert ws_bytes(lib, net, 0, B, 77) == (0, expect)
+    net3 = make_net([1024, 2048, 2048, 1024], act=2)
+    rc, n = ws_bytes(lib, net3, 1, 64, 1024)
+    assert rc == 0
+    assert n == 4 * up(4 * 64 * 2048) + up(4 * 1024 * 2048) + 2 * up(4 * 64 * 1024 * 2048)
+    net5 = make_net([256, 256, 16], act=2)
+    rc, n = ws_bytes(lib, net5, 2, 64, 16)
+    assert rc == 0
+    assert n == 2 * up(4 * 64 * 256) + up(4 * 64 * 16) + up(4 * 1024 * 256) + up(4 * 1024 * 16)
+    assert ws_bytes(lib, make_net([3, 2]), 1, 1, 2)[1] % 256 == 0
+
+
+def test_workspace_bytes_rejects_bad_arguments(lib):
+    net = make_net([4, 3, 2])
+    n = ctypes.c_size_t(0)
+    assert lib.pfg_workspace_bytes(None, 0, 1, 1, ctypes.byref(n)) == pfg.PFG_ERR_NULL
+    assert lib.pfg_workspace_bytes(ctypes.byref(net), 0, 1, 1, None) == pfg.PFG_ERR_NULL
+    assert ws_bytes(lib, net, 3, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
+    assert ws_bytes(lib, net, 0, 0, 1)[0] == pfg.PFG_ERR_SHAPE
+    assert ws_bytes(lib, net, 1, 1, 0)[0] == pfg.PFG_ERR_SHAPE
+    assert ws_bytes(lib, net, 1, 1 << 20, 1 << 20)[0] == pfg.PFG_ERR_OVERFLOW
+    assert ws_bytes(lib, make_net([4, 0, 2]), 0, 1, 1)[0] == pfg.PFG_ERR_SHAPE
+    assert ws_bytes(lib, make_net([4, 3, 2], act=9), 0, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
+    assert ws_bytes(lib, make_net([4, 3, 2], dtype=5), 0, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
+    big = make_net([1 << 24, 1 << 24])
+    assert ws_bytes(lib, big, 0, 1 << 20, 1)[0] == pfg.PFG_ERR_OVERFLOW
+    bad = pfg.pfg_mlp(0, None, None, None, 0, 0)
+    assert ws_bytes(lib, bad, 0, 1, 1)[0] == pfg.PFG_ERR_SHAPE
+    nodims = pfg.pfg_mlp(2, None, None, None, 0, 0)
+    assert ws_bytes(lib, nodims, 0, 1, 1)[0] == pfg.PFG_ERR_NULL
+    assert "dims" in lib.pfg_last_error().decode()
+
+
+def call_grads(lib, net, X=FAKE, labels=FAKE, B=4, ws=FAKE, ws_bytes_=1 << 30):
+    L = net.num_layers
+    outs = (ctypes.c_void_p * L)(*[FAKE] * L)
+    return lib.pfg_per_example_grads(ctypes.byref(net), X, labels, B, outs, outs, None, ws,
+                                     ws_bytes_, None)
+
+
+def test_per_example_grads_rejects_before_launch(lib):
+    net = make_net([4, 3, 2])
+    assert call_grads(lib, net, X=None) == pfg.PFG_ERR_NULL
+    assert call_grads(lib, net, labels=None) == pfg.PFG_ERR_NULL
+    assert call_grads(lib, net, B=0) == pfg.PFG_ERR_SHAPE
+    assert call_grads(lib, net, ws=None) == pfg.PFG_ERR_WORKSPACE
+    assert call_grads(lib, net, ws=FAKE + 8) == pfg.PFG_ERR_WORKSPACE
+    assert call_grads(lib, net, ws_bytes_=16) == pfg.PFG_ERR_WORKSPACE
+    assert "needed" in lib.pfg_last_error().decode()
+    assert call_grads(lib, make_net([4, 3, 2], W_null_at=1)) == pfg.PFG_ERR_NULL
+    assert call_grads(lib, make_net([4, 3, 2], with_W=False)) == pfg.PFG_ERR_NULL
+    assert call_grads(lib, make_net([4, 3, 2], act=-1)) == pfg.PFG_ERR_UNSUPPORTED
+    assert lib.pfg_per_example_grads(None, FAKE, FAKE, 1, None, None, None, FAKE, 1 << 20,
+                                     None) == pfg.PFG_ERR_NULL
+
+
+def test_jacobians_reject_before_launch(lib):
+    net = make_net([4, 3, 2], act=2)
+    ji = lib.pfg_jacobian_input
+    big = 1 << 30
+    assert ji(ctypes.byref(net), None, 2, None, 2, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert ji(ctypes.byref(net), FAKE, 2, None, 2, 0, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    # identity seeds need S == d_L
+    assert ji(ctypes.byref(net), FAKE, 2, None, 3, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+    assert "identity" in lib.pfg_last_error().decode()
+    # explicit seeds: stride must be 0 or >= S * d_L
+    assert ji(ctypes.byref(net), FAKE, 2, FAKE, 3, 5, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+    assert ji(ctypes.byref(net), FAKE, 2, FAKE, 0, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+    assert ji(ctypes.byref(net), FAKE, 2, None, 2, 0, FAKE, None, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert ji(ctypes.byref(net), FAKE, 2, None, 2, 0, FAKE, FAKE, 8, None) == pfg.PFG_ERR_WORKSPACE
+    jw = lib.pfg_jacobian_weights
+    outs = (ctypes.c_void_p * 2)(FAKE, FAKE)
+    assert jw(ctypes.byref(net), FAKE, 2, 7, None, 2, 0, outs, outs, FAKE, big,
+              None) == pfg.PFG_ERR_UNSUPPORTED
+    assert jw(ctypes.byref(net), None, 2, 1, None, 2, 0, outs, outs, FAKE, big,
+              None) == pfg.PFG_ERR_NULL
+    assert jw(ctypes.byref(net), FAKE, 2, 1, None, 5, 0, outs, outs, FAKE, big,
+              None) == pfg.PFG_ERR_SHAPE
+    assert jw(ctypes.byref(net), FAKE, 2, 1, None, 2, 0, outs, outs, FAKE, 0,
+              None) == pfg.PFG_ERR_WORKSPACE
+
+
+def test_last_error_is_cleared_by_a_good_call(lib):
+    net = make_net([4, 3, 2])
+    assert ws_bytes(lib, net, 9, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
+    assert lib.pfg_last_error().decode() != ""
+    assert ws_bytes(lib, net, 0, 1, 1)[0] == 0
+    assert lib.pfg_last_error().decode() == ""
+
+
+def test_timing_query_without_launches(lib):
+    assert lib.pfg_timing_reset() == 0
+    n, ms = ctypes.c_int64(0), ctypes.c_double(0)
+    assert lib.pfg_timing_query(b"outer_product", ctypes.byref(n), ctypes.byref(ms)) == pfg.PFG_ERR_SHAPE
+    assert lib.pfg_timing_query(None, ctypes.byref(n), ctypes.byref(ms)) == pfg.PFG_ERR_NULL
+    buf = ctypes.create_string_buffer(64)
+    assert lib.pfg_timing_names(buf, 64) == 0 and buf.value == b""
+
+
+def test_bf16_rounding_of_inputs():
+    import numpy as np
+    from paper_1903_04243_amd.workloads import bf16_round
+    import torch
+    x = np.array([1.0, 1.00390625, 1.01171875, -3.14159, 1e-3, 65504.0, 0.0, -0.0,
+                  1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8], dtype=np.float32)
+    bits, back = bf16_round(x)
+    t = torch.from_numpy(x).to(torch.bfloat16)
+    np.testing.assert_array_equal(back, t.to(torch.float32).numpy())
+    np.testing.assert_array_equal(bits, t.view(torch.int16).numpy().view(np.uint16))
+    rng = np.random.default_rng(0)
+    y = rng.standard_normal(10000).astype(np.float32)
+    bits, back = bf16_round(y)
+    t = torch.from_numpy(y).to(torch.bfloat16)
+    np.testing.assert_array_equal(back, t.to(torch.float32).numpy())
