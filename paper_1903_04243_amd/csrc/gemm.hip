@@ -316,15 +316,21 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
                 __builtin_bit_cast(bf16x8, av[i]), __builtin_bit_cast(bf16x8, wv[j]), acc[i][j], 0, 0,
                 0);
       } else {
+        // whole-vector casts: a bit_cast applied to a single vector element is not reliable
+        f32x4 af[TM], wf[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[i] = __builtin_bit_cast(f32x4, av[i]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) wf[j] = __builtin_bit_cast(f32x4, wv[j]);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
           for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                  __builtin_bit_cast(float, av[i][e]), __builtin_bit_cast(float, wv[j][e]),
-                  acc[i][j], 0, 0, 0);
+            for (int j = 0; j < TN; ++j) {
+              const float a_e = af[i][e], w_e = wf[j][e];
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_e, w_e, acc[i][j], 0, 0, 0);
+            }
       }
     }
 
