@@ -17,7 +17,9 @@ enum Epilogue : int {
   EPI_NONE = 0,      // C = acc
   EPI_BIAS = 1,      // C = acc + bias                      (last forward layer: logits)
   EPI_FORWARD = 2,   // z = acc + bias; C = phi(z); C2 = phi'(z)   (hidden forward layer)
-  EPI_MASK = 3       // C = acc * emask[m / S, n]           (cotangent step)
+  EPI_MASK = 3,      // C = acc * emask[m / S, n]           (cotangent step)
+  EPI_HEAD = 4       // y = acc + bias (N <= 32, optional C = y); C2 = softmax(y) - onehot(label);
+                     // loss = -log softmax(y)[label]       (last forward layer fused with the head)
 };
 
 // One matrix product  C[M, N] = Aeff[M, K] * Weff[K, N]  with fused prologue and epilogue.
@@ -54,9 +56,13 @@ struct GemmArgs {
   const float *emask;
   int64_t ld_emask;
   int32_t streaming;    // 1: C is written once and not read again by this call
+  const int32_t *labels;  // EPI_HEAD: [M]
+  float *loss;            // EPI_HEAD: [M] or nullptr
 };
 
+// Picks the LDS-tiled kernel or the small-problem kernel.
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream);
+hipError_t launch_gemm_skinny(const GemmArgs &g, hipStream_t stream);
 
 // out[m, i, j] = a[m / S, i] * g[m, j]   for m < M, i < d_in, j < d_out   (float32 out)
 struct OuterArgs {
@@ -71,7 +77,8 @@ struct OuterArgs {
   int32_t d_in, d_out;
 };
 
-hipError_t launch_outer(const OuterArgs &o, hipStream_t stream);
+// Enqueues the n outer products in as few launches as possible (normally one).
+hipError_t launch_outer(const OuterArgs *jobs, int n, hipStream_t stream);
 
 // delta[b, :] = softmax(y[b, :]) - onehot(labels[b]);  loss[b] = -log softmax(y[b])[labels[b]]
 hipError_t launch_head_softmax_ce(const float *y, const int32_t *labels, int64_t B, int32_t n,

@@ -1,0 +1,252 @@
+// Matrix product for SMALL problems (few rows or a short contraction), where the LDS-tiled
+// kernel would leave most of the chip idle and the run time is one dependent latency chain.
+//
+// A workgroup owns one 32 x 32 tile of C and splits the contraction index over its NW waves
+// (wave w takes k-slices w, w + NW, ...).  Operands go straight from global memory (L2-resident
+// at these sizes) into MFMA registers, several slices in flight per wave; the NW partial tiles
+// are then summed in a fixed order through LDS, so the result does not depend on timing.  The
+// fused epilogues are those of the tiled kernel, plus EPI_HEAD: when the whole row of logits
+// fits one tile (d_L <= 32), softmax cross-entropy's gradient and loss are produced in the same
+// launch as the last forward layer.
+#include "common.h"
+#include "gemm_device.h"
+
+namespace pfg {
+
+namespace {
+
+using namespace dev;
+
+template <int AMODE, bool WKN, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) {
+  constexpr bool BF16 = (AMODE != A_F32);
+  constexpr int ELEM = BF16 ? 2 : 4;
+  constexpr int EPC = 16 / ELEM;       // k elements one lane feeds to the MFMA(s) of a slice
+  constexpr int KSLICE = 2 * EPC;      // k elements per slice (two lane halves)
+  constexpr int R = 4;                 // slices in flight per wave
+  constexpr int NT = 64 * NW;
+
+  __shared__ float red[NW][32][33];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int half = lane >> 5;
+  const int l32 = lane & 31;
+  const int M = g.M, N = g.N, K = g.K;
+  const int tiles_m = (M + 31) / 32;
+  const int m0 = (blockIdx.x % tiles_m) * 32;
+  const int n0 = (blockIdx.x / tiles_m) * 32;
+
+  const bool a_vec_ok = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
+                        ((g.lda * (AMODE == A_BF16 ? 2 : 4)) % 16 == 0) &&
+                        ((g.a_batch_stride * (AMODE == A_BF16 ? 2 : 4)) % 16 == 0);
+  const bool s_vec_ok = g.a_scale && ((reinterpret_cast<uintptr_t>(g.a_scale) & 15) == 0) &&
+                        ((g.ld_scale * 4) % 16 == 0);
+  const bool w_vec_ok = ((reinterpret_cast<uintptr_t>(g.W) & 15) == 0) && ((g.ldw * ELEM) % 16 == 0);
+  const bool scaled = (g.a_scale != nullptr);
+
+  // this lane's A row and W column
+  const void *a_row = nullptr;
+  const float *a_srow = nullptr;
+  {
+    const int m = m0 + l32;
+    if (m < M) {
+      const int64_t b = m / g.S, s = m % g.S;
+      const int64_t off = b * g.a_batch_stride + s * g.lda;
+      if constexpr (AMODE == A_BF16)
+        a_row = static_cast<const __bf16 *>(g.A) + off;
+      else
+        a_row = static_cast<const float *>(g.A) + off;
+      if (scaled) a_srow = g.a_scale + b * g.ld_scale;
+    }
+  }
+  const int n = n0 + l32;
+  const bool n_in = n < N;
+  const void *w_row = nullptr;           // !WKN: row n of W [N, K]
+  if constexpr (!WKN) {
+    if (n_in) {
+      if constexpr (BF16)
+        w_row = static_cast<const __bf16 *>(g.W) + (int64_t)n * g.ldw;
+      else
+        w_row = static_cast<const float *>(g.W) + (int64_t)n * g.ldw;
+    }
+  }
+
+  RawA<AMODE> ra[R];
+  u32x4 rw[R];
+
+  auto load = [&](int slice, RawA<AMODE> &a, u32x4 &w) {
+    const int k0 = slice * KSLICE + half * EPC;
+    a = fetch_a<AMODE>(a_row, a_srow, k0, K, a_vec_ok, s_vec_ok);
+    if constexpr (!WKN) {
+      if constexpr (BF16)
+        w = load8_bf16(static_cast<const __bf16 *>(w_row), k0, K, w_vec_ok);
+      else
+        w = __builtin_bit_cast(u32x4, load4_f32(static_cast<const float *>(w_row), k0, K, w_vec_ok));
+    } else {
+      // W is [K, N]: EPC strided loads down column n (coalesced across the 32 lanes of a half)
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (n_in) {
+        if constexpr (BF16) {
+          const uint16_t *col = static_cast<const uint16_t *>(g.W) + n;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const uint32_t bits = (k0 + e < K) ? (uint32_t)col[(int64_t)(k0 + e) * g.ldw] : 0u;
+            v[e >> 1] |= bits << ((e & 1) * 16);
+          }
+        } else {
+          const float *col = static_cast<const float *>(g.W) + n;
+          f32x4 f = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (k0 + e < K) f[e] = col[(int64_t)(k0 + e) * g.ldw];
+          v = __builtin_bit_cast(u32x4, f);
+        }
+      }
+      w = v;
+    }
+  };
+
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+
+  auto compute = [&](const RawA<AMODE> &a, const u32x4 &w) {
+    const u32x4 av = finish_a<AMODE>(a, scaled);
+    if constexpr (BF16) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av),
+                                                    __builtin_bit_cast(bf16x8, w), acc, 0, 0, 0);
+    } else {
+      const f32x4 af = __builtin_bit_cast(f32x4, av), wf = __builtin_bit_cast(f32x4, w);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float a_e = af[e], w_e = wf[e];
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_e, w_e, acc, 0, 0, 0);
+      }
+    }
+  };
+
+  // wave w handles slices w, w + NW, ...; R - 1 of them are in flight ahead of the MFMAs
+  const int nslices = (K + KSLICE - 1) / KSLICE;
+#pragma unroll
+  for (int u = 0; u < R - 1; ++u)
+    if (wave + u * NW < nslices) load(wave + u * NW, ra[u], rw[u]);
+  for (int base = wave; base < nslices; base += R * NW) {
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+      const int cur = base + u * NW;
+      if (cur < nslices) {
+        const int nxt = cur + (R - 1) * NW;
+        if (nxt < nslices) load(nxt, ra[(u + R - 1) % R], rw[(u + R - 1) % R]);
+        compute(ra[u], rw[u]);
+      }
+    }
+  }
+
+  // ---- fixed-order reduction of the NW partial tiles ----
+#pragma unroll
+  for (int r = 0; r < 16; ++r) red[wave][8 * (r >> 2) + 4 * half + (r & 3)][l32] = acc[r];
+  __syncthreads();
+
+  const int epi = g.epilogue;
+  for (int o = tid; o < 32 * 32; o += NT) {
+    const int row = o >> 5, col = o & 31;
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) v += red[w][row][col];
+    const int m = m0 + row, nn = n0 + col;
+    const bool inside = (m < M) && (nn < N);
+    float bias = 0.f;
+    if (inside && (epi == EPI_BIAS || epi == EPI_FORWARD || epi == EPI_HEAD) && g.bias)
+      bias = g.bf16 ? (float)static_cast<const __bf16 *>(g.bias)[nn]
+                    : static_cast<const float *>(g.bias)[nn];
+    if (epi == EPI_HEAD) {
+      // keep the biased logits in LDS for the softmax pass below (every thread reaches the
+      // barrier that follows this loop)
+      v += bias;
+      red[0][row][col] = v;          // safe: slot (row, col) is read and written by this thread only
+      if (inside && g.C) g.C[(int64_t)m * g.ldc + nn] = v;
+      continue;
+    }
+    if (!inside) continue;
+    const int64_t off = (int64_t)m * g.ldc + nn;
+    if (epi == EPI_FORWARD) {
+      const float z = v + bias;
+      g.C2[off] = act_deriv(g.act, z);
+      if (g.C == nullptr) continue;
+      v = act_value(g.act, z);
+    } else if (epi == EPI_BIAS) {
+      v += bias;
+    } else if (epi == EPI_MASK) {
+      v *= g.emask[(int64_t)(m / g.S) * g.ld_emask + nn];
+    }
+    if (g.streaming)
+      __builtin_nontemporal_store(v, g.C + off);
+    else
+      g.C[off] = v;
+  }
+
+  if (epi == EPI_HEAD) {
+    // softmax cross-entropy on rows of the tile: delta = softmax(y) - onehot(label),
+    // loss = -log softmax(y)[label].  N <= 32, one row per wave pass, lanes 32..63 idle.
+    __syncthreads();
+    for (int row = wave; row < 32; row += NW) {
+      const int m = m0 + row;
+      if (m >= M) break;
+      const bool live = (lane < N);
+      const float y = live ? red[0][row][lane] : -INFINITY;
+      float mx = y;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+      const float ex = live ? expf(y - mx) : 0.f;
+      const int label = g.labels[m];
+      float den = ex, others = (lane == label) ? 0.f : ex;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        den += __shfl_xor(den, off, 64);
+        others += __shfl_xor(others, off, 64);
+      }
+      const float inv = 1.f / den;
+      if (live) g.C2[(int64_t)m * g.ldc + lane] = (lane == label) ? -others * inv : ex * inv;
+      if (g.loss) {
+        const float yl = __shfl(y, (label >= 0 && label < N) ? label : 0, 64);
+        if (lane == 0) g.loss[m] = logf(den) - (((label >= 0 && label < N) ? yl : mx) - mx);
+      }
+    }
+  }
+}
+
+template <int AMODE, bool WKN, int NW>
+hipError_t launch_nw(const GemmArgs &g, hipStream_t stream) {
+  const int64_t tiles = (int64_t)((g.M + 31) / 32) * ((g.N + 31) / 32);
+  hipLaunchKernelGGL((gemm_skinny_kernel<AMODE, WKN, NW>), dim3((unsigned)tiles), dim3(64 * NW), 0,
+                     stream, g);
+  return hipGetLastError();
+}
+
+template <int AMODE, bool WKN>
+hipError_t launch_mode(const GemmArgs &g, hipStream_t stream) {
+  // enough waves that each handles about four k-slices, at most eight
+  const int kslice = (AMODE == A_F32) ? 8 : 16;
+  const int slices = (g.K + kslice - 1) / kslice;
+  if (slices >= 32) return launch_nw<AMODE, WKN, 8>(g, stream);
+  if (slices >= 16) return launch_nw<AMODE, WKN, 4>(g, stream);
+  if (slices >= 8) return launch_nw<AMODE, WKN, 2>(g, stream);
+  return launch_nw<AMODE, WKN, 1>(g, stream);
+}
+
+}  // namespace
+
+hipError_t launch_gemm_skinny(const GemmArgs &g, hipStream_t stream) {
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipSuccess;
+  if (g.epilogue == EPI_HEAD && g.N > 32) return hipErrorInvalidValue;
+  if (!g.bf16)
+    return g.w_kn ? launch_mode<A_F32, true>(g, stream) : launch_mode<A_F32, false>(g, stream);
+  if (g.a_is_f32)
+    return g.w_kn ? launch_mode<A_F32_TO_BF16, true>(g, stream)
+                  : launch_mode<A_F32_TO_BF16, false>(g, stream);
+  return g.w_kn ? launch_mode<A_BF16, true>(g, stream) : launch_mode<A_BF16, false>(g, stream);
+}
+
+}  // namespace pfg

@@ -1,5 +1,6 @@
 // C ABI of libpfg: argument checks, workspace layout and the order in which the kernels of the
 // three operations are enqueued.  No arithmetic of the method happens on the host.
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -199,8 +200,14 @@ const void *bias_of(const pfg_mlp *net, int l) { return net->b ? net->b[l - 1] :
 
 // Stacked forward pass through layers 1..upto.  Hidden layers store a_l and phi'(z_l); layer L
 // (if reached) stores the logits.
+struct HeadFusion {      // softmax cross-entropy folded into the last forward layer
+  const int32_t *labels;
+  float *delta;          // [B, d_L]
+  float *loss;           // [B] or nullptr
+};
+
 int forward(const pfg_mlp *net, const void *X, int64_t B, int upto, void *ws, const Plan &p,
-            bool keep_last_hidden_act, hipStream_t stream) {
+            bool keep_last_hidden_act, hipStream_t stream, const HeadFusion *head = nullptr) {
   const int L = net->num_layers;
   const int32_t *d = net->dims;
   for (int l = 1; l <= upto; ++l) {
@@ -224,6 +231,12 @@ int forward(const pfg_mlp *net, const void *X, int64_t B, int upto, void *ws, co
       g.epilogue = EPI_FORWARD;
       g.C = (l == upto && !keep_last_hidden_act) ? nullptr : at(ws, p.act[l]);
       g.C2 = at(ws, p.dphi[l]);
+    } else if (head) {
+      g.epilogue = EPI_HEAD;
+      g.C = nullptr;
+      g.C2 = head->delta;
+      g.labels = head->labels;
+      g.loss = head->loss;
     } else {
       g.epilogue = EPI_BIAS;
       g.C = at(ws, p.logits);
@@ -259,8 +272,8 @@ int cotangent_step(const pfg_mlp *net, int l, const float *G_l, int64_t rows, in
   return PFG_OK;
 }
 
-int outer(const pfg_mlp *net, int l, const void *X, const float *G_l, int64_t rows, int64_t S,
-          float *out, void *ws, const Plan &p, hipStream_t stream) {
+OuterArgs outer_job(const pfg_mlp *net, int l, const void *X, const float *G_l, int64_t rows,
+                    int64_t S, float *out, void *ws, const Plan &p) {
   const int32_t *d = net->dims;
   OuterArgs o{};
   o.a = (l == 1) ? X : at(ws, p.act[l - 1]);
@@ -273,11 +286,11 @@ int outer(const pfg_mlp *net, int l, const void *X, const float *G_l, int64_t ro
   o.S = (int32_t)S;
   o.d_in = d[l - 1];
   o.d_out = d[l];
-  PFG_LAUNCH("outer_product", launch_outer(o, stream));
-  return PFG_OK;
+  return o;
 }
 
-// Backward sweep shared by the two weight-gradient operations: G_L is already in place.
+// Backward sweep shared by the two weight-gradient operations: G_L is already in place.  The
+// cotangent chain runs first; the outer products of all requested layers then go out together.
 int weight_sweep(const pfg_mlp *net, const void *X, int64_t B, int64_t S, float *const *W_out,
                  float *const *b_out, std::vector<float *> &G, void *ws, const Plan &p,
                  hipStream_t stream) {
@@ -285,16 +298,19 @@ int weight_sweep(const pfg_mlp *net, const void *X, int64_t B, int64_t S, float 
   int lowest = L + 1;
   for (int l = 1; l <= L; ++l)
     if ((W_out && W_out[l - 1]) || (b_out && b_out[l - 1])) { lowest = l; break; }
-  for (int l = L; l >= lowest; --l) {
-    if (W_out && W_out[l - 1]) {
-      int rc = outer(net, l, X, G[l], B * S, S, W_out[l - 1], ws, p, stream);
-      if (rc) return rc;
-    }
-    if (l > lowest) {
-      int rc = cotangent_step(net, l, G[l], B * S, S, G[l - 1], ws, p, stream);
-      if (rc) return rc;
-    }
+  for (int l = L; l > lowest; --l) {
+    int rc = cotangent_step(net, l, G[l], B * S, S, G[l - 1], ws, p, stream);
+    if (rc) return rc;
   }
+  // largest layer first, so that the small ones fill the tail of the launch
+  std::vector<OuterArgs> jobs;
+  for (int l = 1; l <= L; ++l)
+    if (W_out && W_out[l - 1]) jobs.push_back(outer_job(net, l, X, G[l], B * S, S, W_out[l - 1], ws, p));
+  std::stable_sort(jobs.begin(), jobs.end(), [](const OuterArgs &x, const OuterArgs &y) {
+    return (int64_t)x.d_in * x.d_out > (int64_t)y.d_in * y.d_out;
+  });
+  if (!jobs.empty())
+    PFG_LAUNCH("outer_product", launch_outer(jobs.data(), (int)jobs.size(), stream));
   return PFG_OK;
 }
 
@@ -374,15 +390,20 @@ int pfg_per_example_grads(const pfg_mlp *net, const void *X, const int32_t *labe
   const int L = net->num_layers;
   const int32_t *d = net->dims;
 
-  if ((rc = forward(net, X, B, L, workspace, p, true, stream))) return rc;
-
   // delta_l lives in the caller's db_out[l-1] when given (db_l = delta_l), else in the workspace
   std::vector<float *> G(L + 1, nullptr);
   for (int l = 1; l <= L; ++l)
     G[l] = (db_out && db_out[l - 1]) ? db_out[l - 1] : at(workspace, p.G[l]);
 
-  PFG_LAUNCH("head", launch_head_softmax_ce(at(workspace, p.logits), labels, B, d[L], G[L],
-                                            loss_out, stream));
+  if (d[L] <= 32) {
+    // a whole row of logits fits one output tile: the loss head rides on the last forward layer
+    const HeadFusion hf{labels, G[L], loss_out};
+    if ((rc = forward(net, X, B, L, workspace, p, true, stream, &hf))) return rc;
+  } else {
+    if ((rc = forward(net, X, B, L, workspace, p, true, stream))) return rc;
+    PFG_LAUNCH("head", launch_head_softmax_ce(at(workspace, p.logits), labels, B, d[L], G[L],
+                                              loss_out, stream));
+  }
   return weight_sweep(net, X, B, 1, dW_out, db_out, G, workspace, p, stream);
 }
 
