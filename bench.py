@@ -35,6 +35,10 @@ def main():
     ap.add_argument("--only-primary", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="do not also time a HIP-graph replay")
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="run a plain elementwise copy of known size (scale for HBM counters)")
+    ap.add_argument("--workload", default=None,
+                    help="measure only this workload and print its record (for profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this library has no multi-GPU path (parallel-for "
@@ -203,6 +207,23 @@ def main():
         log(f"[bench] {name}: {rec['ms_per_step']:.4f} ms/step, roofline frac "
             f"{rec['roofline']['frac']:.3f}")
         return rec, inp
+
+    if args.copy_reference:
+        # out = src + 1 over 64 Mi float32: reads 256 MiB and writes 256 MiB per launch
+        n = 64 * 1024 * 1024
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_reference": "torch.add(src, 1.0, out=dst)", "launches": args.steps,
+                          "read_bytes_per_launch": 4 * n, "write_bytes_per_launch": 4 * n}))
+        return
+
+    if args.workload:
+        rec, _ = measure(args.workload, args.steps, args.warmup)
+        print(json.dumps(rec), flush=True)
+        return
 
     primary = "c2_mnist_mlp_grads"
     rec, inp = measure(primary, args.steps, args.warmup)

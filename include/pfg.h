@@ -128,8 +128,9 @@ int pfg_jacobian_weights(const pfg_mlp *net, const void *X, int64_t B, int head,
  * library from that thread. */
 const char *pfg_last_error(void);
 
-/* Per-kernel device timing, for measurement.  While enabled, every kernel the library enqueues
- * is bracketed by two HIP events recorded on the call's stream.  pfg_timing_query waits for the
+/* Per-kernel device timing, for measurement.  While enabled, every call records one HIP event on
+ * its stream when it begins and one after each kernel it enqueues; a kernel's duration is the
+ * time between the event before it and the event after it.  pfg_timing_query waits for the
  * events recorded so far and reports, for the kernel family called `name`, the number of launches
  * and their summed duration in milliseconds since the last reset; it returns PFG_ERR_SHAPE if no
  * launch of that family was recorded.  pfg_timing_names writes the recorded family names,

@@ -19,7 +19,8 @@ enum Epilogue : int {
   EPI_FORWARD = 2,   // z = acc + bias; C = phi(z); C2 = phi'(z)   (hidden forward layer)
   EPI_MASK = 3,      // C = acc * emask[m / S, n]           (cotangent step)
   EPI_HEAD = 4       // y = acc + bias (N <= 32, optional C = y); C2 = softmax(y) - onehot(label);
-                     // loss = -log softmax(y)[label]       (last forward layer fused with the head)
+                     // loss = -log softmax(y)[label]       (last forward layer fused with the head,
+                     // and optionally with the cotangent step through that layer)
 };
 
 // One matrix product  C[M, N] = Aeff[M, K] * Weff[K, N]  with fused prologue and epilogue.
@@ -58,6 +59,10 @@ struct GemmArgs {
   int32_t streaming;    // 1: C is written once and not read again by this call
   const int32_t *labels;  // EPI_HEAD: [M]
   float *loss;            // EPI_HEAD: [M] or nullptr
+  // EPI_HEAD, optional first cotangent step in the same launch (W is W_L [K, N]):
+  //   head_gprev[m, i] = head_mask[m, i] * sum_j C2[m, j] * W[i, j]     for i < K
+  float *head_gprev;        // [M, K] or nullptr
+  const float *head_mask;   // [M, K]
 };
 
 // Picks the LDS-tiled kernel or the small-problem kernel.

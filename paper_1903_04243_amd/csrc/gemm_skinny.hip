@@ -23,10 +23,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   constexpr int ELEM = BF16 ? 2 : 4;
   constexpr int EPC = 16 / ELEM;       // k elements one lane feeds to the MFMA(s) of a slice
   constexpr int KSLICE = 2 * EPC;      // k elements per slice (two lane halves)
-  constexpr int R = 4;                 // slices in flight per wave
+  constexpr int R = (AMODE == A_F32) ? 8 : 4;   // slices in flight per wave
   constexpr int NT = 64 * NW;
 
   __shared__ float red[NW][32][33];
+  __shared__ __align__(16) float hd[32][32];   // EPI_HEAD: delta rows of the tile, zero-padded
+  __shared__ int lab[32];                      // EPI_HEAD: labels of the tile's rows
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -45,6 +47,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
                         ((g.ld_scale * 4) % 16 == 0);
   const bool w_vec_ok = ((reinterpret_cast<uintptr_t>(g.W) & 15) == 0) && ((g.ldw * ELEM) % 16 == 0);
   const bool scaled = (g.a_scale != nullptr);
+  const int epi = g.epilogue;
+  const bool head_step = (epi == EPI_HEAD) && (g.head_gprev != nullptr);
+  const int tile_rows = min(32, g.M - m0);
+  // operands of the head that do not depend on this kernel's product are fetched early, off the
+  // critical path (the barriers of the reduction order these LDS writes before their reads)
+  if (epi == EPI_HEAD && tid < 32) lab[tid] = (tid < tile_rows) ? g.labels[m0 + tid] : -1;
 
   // this lane's A row and W column
   const void *a_row = nullptr;
@@ -144,12 +152,28 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
     }
   }
 
+  // Cotangent step fused behind the head: column i = tid of W_L (N values) and of the mask
+  // (one value per tile row) are requested now and consumed after the softmax.
+  float hw[32], hm[32];
+  auto head_fetch = [&](int i) {
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+      hw[j] = 0.f;
+      if (j < N)
+        hw[j] = g.bf16 ? (float)static_cast<const __bf16 *>(g.W)[(int64_t)i * g.ldw + j]
+                       : static_cast<const float *>(g.W)[(int64_t)i * g.ldw + j];
+    }
+#pragma unroll
+    for (int r = 0; r < 32; ++r)
+      hm[r] = (r < tile_rows) ? g.head_mask[(int64_t)(m0 + r) * K + i] : 0.f;
+  };
+  if (head_step && tid < K) head_fetch(tid);
+
   // ---- fixed-order reduction of the NW partial tiles ----
 #pragma unroll
   for (int r = 0; r < 16; ++r) red[wave][8 * (r >> 2) + 4 * half + (r & 3)][l32] = acc[r];
   __syncthreads();
 
-  const int epi = g.epilogue;
   for (int o = tid; o < 32 * 32; o += NT) {
     const int row = o >> 5, col = o & 31;
     float v = 0.f;
@@ -188,30 +212,60 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   }
 
   if (epi == EPI_HEAD) {
-    // softmax cross-entropy on rows of the tile: delta = softmax(y) - onehot(label),
-    // loss = -log softmax(y)[label].  N <= 32, one row per wave pass, lanes 32..63 idle.
+    // softmax cross-entropy on the rows of the tile: delta = softmax(y) - onehot(label),
+    // loss = -log softmax(y)[label].  N <= 32: each half of a wave takes one row per pass, and
+    // the reductions stay inside the half.
     __syncthreads();
-    for (int row = wave; row < 32; row += NW) {
+    for (int row0 = 2 * wave; row0 < 32; row0 += 2 * NW) {
+      const int row = row0 + half;
       const int m = m0 + row;
-      if (m >= M) break;
-      const bool live = (lane < N);
-      const float y = live ? red[0][row][lane] : -INFINITY;
+      const bool valid = row < tile_rows;
+      const bool live = valid && (l32 < N);
+      const float y = live ? red[0][row][l32] : -INFINITY;
       float mx = y;
 #pragma unroll
-      for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+      for (int off = 16; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
       const float ex = live ? expf(y - mx) : 0.f;
-      const int label = g.labels[m];
-      float den = ex, others = (lane == label) ? 0.f : ex;
+      const int label = lab[row];
+      float den = ex, others = (l32 == label) ? 0.f : ex;
 #pragma unroll
-      for (int off = 32; off > 0; off >>= 1) {
+      for (int off = 16; off > 0; off >>= 1) {
         den += __shfl_xor(den, off, 64);
         others += __shfl_xor(others, off, 64);
       }
-      const float inv = 1.f / den;
-      if (live) g.C2[(int64_t)m * g.ldc + lane] = (lane == label) ? -others * inv : ex * inv;
-      if (g.loss) {
-        const float yl = __shfl(y, (label >= 0 && label < N) ? label : 0, 64);
-        if (lane == 0) g.loss[m] = logf(den) - (((label >= 0 && label < N) ? yl : mx) - mx);
+      const float inv = valid ? 1.f / den : 0.f;
+      // p[label] - 1 = -(sum of the other classes) / den, free of cancellation
+      const float delta = (l32 == label) ? -others * inv : ex * inv;
+      if (live) g.C2[(int64_t)m * g.ldc + l32] = delta;
+      hd[row][l32] = live ? delta : 0.f;       // kept, zero-padded, for the cotangent step below
+      const bool label_ok = (label >= 0) && (label < N);
+      const float yl = __shfl(y, half * 32 + (label_ok ? label : 0), 64);
+      if (g.loss && valid && l32 == 0) g.loss[m] = logf(den) - ((label_ok ? yl : mx) - mx);
+    }
+    if (head_step) {
+      // cotangent through the last layer for the tile's rows, on the vector ALUs (the contraction
+      // is only N <= 32 long): g_prev[m, i] = phi'(z[m, i]) * sum_j delta[m, j] * W[i, j].
+      // A thread owns column i; consecutive threads store consecutive i of one row.
+      __syncthreads();
+      for (int i = tid; i < K; i += NT) {
+        if (i != tid) head_fetch(i);
+#pragma unroll
+        for (int r = 0; r < 32; ++r) {
+          if (r < tile_rows) {
+            float acc2 = 0.f;
+#pragma unroll
+            for (int j4 = 0; j4 < 8; ++j4) {
+              if (4 * j4 < N) {      // uniform: skips the zero padding beyond d_L
+                const f32x4 dv = *reinterpret_cast<const f32x4 *>(&hd[r][4 * j4]);
+                acc2 += dv[0] * hw[4 * j4] + dv[1] * hw[4 * j4 + 1] + dv[2] * hw[4 * j4 + 2] +
+                        dv[3] * hw[4 * j4 + 3];
+              }
+            }
+            g.head_gprev[(int64_t)(m0 + r) * K + i] = acc2 * hm[r];
+          }
+          // keep the scheduler from hoisting the LDS reads of all 32 rows at once
+          if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
   }

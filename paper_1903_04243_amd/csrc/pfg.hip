@@ -29,33 +29,47 @@ int fail(int code, const char *fmt, ...) {
 // ------------------------------------------------------------------------------------------
 // Per-kernel timing with HIP events on the call's stream.
 // ------------------------------------------------------------------------------------------
-struct TimedLaunch { const char *name; hipEvent_t start, stop; };
+// Each timed kernel is followed by one event; its duration is the time since the previous event
+// on the stream (the one after the preceding kernel, or the one recorded when the call began).
+// In a queue that is kept busy this is the interval the kernel occupies the device.
+struct TimedLaunch { const char *name; hipEvent_t start, stop; bool owns_start; };
 std::mutex g_timing_mu;
 bool g_timing_on = false;
 std::vector<TimedLaunch> g_pending;
 std::map<std::string, std::pair<int64_t, double>> g_totals;
+thread_local hipEvent_t t_last_event = nullptr;   // last event of the call in progress
+
+void timing_begin_call(hipStream_t stream) {
+  t_last_event = nullptr;
+  if (!g_timing_on) return;
+  hipEvent_t e;
+  if (hipEventCreate(&e) != hipSuccess) return;
+  (void)hipEventRecord(e, stream);
+  t_last_event = e;
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  g_pending.push_back({nullptr, e, nullptr, true});    // keeps the first event alive until drained
+}
 
 struct TimedScope {
   const char *name;
   hipStream_t stream;
-  hipEvent_t start = nullptr, stop = nullptr;
   bool on;
-  TimedScope(const char *n, hipStream_t s) : name(n), stream(s), on(g_timing_on) {
-    if (!on) return;
-    if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) { on = false; return; }
-    (void)hipEventRecord(start, stream);
-  }
+  TimedScope(const char *n, hipStream_t s) : name(n), stream(s), on(g_timing_on && t_last_event) {}
   ~TimedScope() {
     if (!on) return;
+    hipEvent_t stop;
+    if (hipEventCreate(&stop) != hipSuccess) return;
     (void)hipEventRecord(stop, stream);
     std::lock_guard<std::mutex> lk(g_timing_mu);
-    g_pending.push_back({name, start, stop});
+    g_pending.push_back({name, t_last_event, stop, false});
+    t_last_event = stop;
   }
 };
 
 void drain_pending() {
   std::lock_guard<std::mutex> lk(g_timing_mu);
   for (auto &t : g_pending) {
+    if (!t.name) continue;
     float ms = 0.f;
     if (hipEventSynchronize(t.stop) == hipSuccess &&
         hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) {
@@ -63,8 +77,11 @@ void drain_pending() {
       e.first += 1;
       e.second += ms;
     }
-    (void)hipEventDestroy(t.start);
-    (void)hipEventDestroy(t.stop);
+  }
+  // every event is the stop of one entry or the first event of a call: destroy each once
+  for (auto &t : g_pending) {
+    if (t.owns_start) (void)hipEventDestroy(t.start);
+    if (t.stop) (void)hipEventDestroy(t.stop);
   }
   g_pending.clear();
 }
@@ -112,6 +129,9 @@ int check_rows(int64_t B, int64_t S) {
 int check_elems(const pfg_mlp *net, int64_t rows) {
   for (int l = 1; l <= net->num_layers; ++l) {
     const int64_t per = (int64_t)net->dims[l - 1] * net->dims[l];
+    if (per > 0x7fffffffLL)
+      return fail(PFG_ERR_OVERFLOW, "layer %d: %d x %d weights exceed 2^31 - 1 per iteration", l,
+                  net->dims[l - 1], net->dims[l]);
     if (per > kMaxElems / rows)
       return fail(PFG_ERR_OVERFLOW, "layer %d: %lld x %d x %d values exceed the indexing limit", l,
                   (long long)rows, net->dims[l - 1], net->dims[l]);
@@ -204,6 +224,7 @@ struct HeadFusion {      // softmax cross-entropy folded into the last forward l
   const int32_t *labels;
   float *delta;          // [B, d_L]
   float *loss;           // [B] or nullptr
+  float *g_prev;         // [B, d_{L-1}]: also take the cotangent step through layer L, or nullptr
 };
 
 int forward(const pfg_mlp *net, const void *X, int64_t B, int upto, void *ws, const Plan &p,
@@ -237,6 +258,10 @@ int forward(const pfg_mlp *net, const void *X, int64_t B, int upto, void *ws, co
       g.C2 = head->delta;
       g.labels = head->labels;
       g.loss = head->loss;
+      if (head->g_prev && L >= 2) {
+        g.head_gprev = head->g_prev;
+        g.head_mask = at(ws, p.dphi[L - 1]);
+      }
     } else {
       g.epilogue = EPI_BIAS;
       g.C = at(ws, p.logits);
@@ -291,14 +316,18 @@ OuterArgs outer_job(const pfg_mlp *net, int l, const void *X, const float *G_l, 
 
 // Backward sweep shared by the two weight-gradient operations: G_L is already in place.  The
 // cotangent chain runs first; the outer products of all requested layers then go out together.
+int lowest_requested(const pfg_mlp *net, float *const *W_out, float *const *b_out) {
+  for (int l = 1; l <= net->num_layers; ++l)
+    if ((W_out && W_out[l - 1]) || (b_out && b_out[l - 1])) return l;
+  return net->num_layers + 1;
+}
+
 int weight_sweep(const pfg_mlp *net, const void *X, int64_t B, int64_t S, float *const *W_out,
                  float *const *b_out, std::vector<float *> &G, void *ws, const Plan &p,
-                 hipStream_t stream) {
+                 hipStream_t stream, bool top_step_done = false) {
   const int L = net->num_layers;
-  int lowest = L + 1;
-  for (int l = 1; l <= L; ++l)
-    if ((W_out && W_out[l - 1]) || (b_out && b_out[l - 1])) { lowest = l; break; }
-  for (int l = L; l > lowest; --l) {
+  const int lowest = lowest_requested(net, W_out, b_out);
+  for (int l = top_step_done ? L - 1 : L; l > lowest; --l) {
     int rc = cotangent_step(net, l, G[l], B * S, S, G[l - 1], ws, p, stream);
     if (rc) return rc;
   }
@@ -387,6 +416,7 @@ int pfg_per_example_grads(const pfg_mlp *net, const void *X, const int32_t *labe
   if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  timing_begin_call(stream);
   const int L = net->num_layers;
   const int32_t *d = net->dims;
 
@@ -395,16 +425,19 @@ int pfg_per_example_grads(const pfg_mlp *net, const void *X, const int32_t *labe
   for (int l = 1; l <= L; ++l)
     G[l] = (db_out && db_out[l - 1]) ? db_out[l - 1] : at(workspace, p.G[l]);
 
+  bool top_step_done = false;
   if (d[L] <= 32) {
-    // a whole row of logits fits one output tile: the loss head rides on the last forward layer
-    const HeadFusion hf{labels, G[L], loss_out};
+    // a whole row of logits fits one output tile: the loss head, and the cotangent step through
+    // the last layer if a lower layer's gradient is wanted, ride on the last forward layer
+    top_step_done = (L >= 2) && (lowest_requested(net, dW_out, db_out) < L);
+    const HeadFusion hf{labels, G[L], loss_out, top_step_done ? G[L - 1] : nullptr};
     if ((rc = forward(net, X, B, L, workspace, p, true, stream, &hf))) return rc;
   } else {
     if ((rc = forward(net, X, B, L, workspace, p, true, stream))) return rc;
     PFG_LAUNCH("head", launch_head_softmax_ce(at(workspace, p.logits), labels, B, d[L], G[L],
                                               loss_out, stream));
   }
-  return weight_sweep(net, X, B, 1, dW_out, db_out, G, workspace, p, stream);
+  return weight_sweep(net, X, B, 1, dW_out, db_out, G, workspace, p, stream, top_step_done);
 }
 
 int pfg_jacobian_input(const pfg_mlp *net, const void *X, int64_t B, const float *seeds, int64_t S,
@@ -423,6 +456,7 @@ int pfg_jacobian_input(const pfg_mlp *net, const void *X, int64_t B, const float
   if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  timing_begin_call(stream);
   const int L = net->num_layers;
   const int32_t *d = net->dims;
   const bool bf16 = (net->dtype == PFG_BF16);
@@ -513,6 +547,7 @@ int pfg_jacobian_weights(const pfg_mlp *net, const void *X, int64_t B, int head,
   if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  timing_begin_call(stream);
   const int L = net->num_layers;
   const int32_t *d = net->dims;
 

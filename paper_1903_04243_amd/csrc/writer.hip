@@ -22,40 +22,50 @@ __device__ __forceinline__ float load_a(const void *a, int a_bf16, int64_t idx) 
   return static_cast<const float *>(a)[idx];
 }
 
-// One unit of work of the launch: a stacked outer product and how it is cut into workgroups.
+// One unit of work of the launch: a stacked outer product and how one iteration m of it is cut
+// into workgroups.
 struct OuterJob {
   OuterArgs o;
   int32_t vec;              // 1: 16-byte stores (d_out % 4 == 0, out 16-byte aligned); 0: scalar
+  int32_t nt;               // 1: non-temporal stores
   int32_t V;                // vec: d_out / 4 vector columns
-  int32_t slabs;            // vec: column slabs of up to 256 vectors
+  int32_t slabs;            // vec: column slabs of up to THREADS vectors
   int32_t chunks;           // row chunks (vec) or flat element chunks (scalar) per iteration m
   int32_t per_chunk;        // rows (vec) or elements (scalar) per chunk
-  int64_t block_begin;      // first workgroup id of this job inside the launch
+  uint32_t x_begin;         // first blockIdx.x of this job
 };
 
 constexpr int kMaxJobs = 8;
 struct OuterBatch {
   OuterJob job[kMaxJobs];
   int32_t n;
+  int64_t M;                // iterations, the same for every job of a launch
 };
 
+// The index arithmetic below is kept to 32-bit, wave-uniform operations (and none at all in the
+// common one-slab case): a workgroup issues only a few stores per lane, so a long prologue would
+// cost more than the stores.
+
 // d_out % 4 == 0, out 16-byte aligned.  V = d_out / 4 vector columns.
-// Workgroup = (m, column slab of up to 256 vectors, chunk of rows).  When V < 256 a pass covers
-// 256 / V rows at once.
-__device__ __forceinline__ void outer_vec4(const OuterJob &jb, int64_t bid) {
+// Workgroup = (m, column slab of up to THREADS vectors, chunk of rows).  When V < THREADS a pass
+// covers THREADS / V rows at once.
+template <int THREADS>
+__device__ __forceinline__ void outer_vec4(const OuterJob &jb, uint32_t x, int64_t m) {
   const OuterArgs &o = jb.o;
   const int V = jb.V;
-  const int chunk = (int)(bid % jb.chunks);
-  const int slab = (int)((bid / jb.chunks) % jb.slabs);
-  const int64_t m = bid / ((int64_t)jb.chunks * jb.slabs);
+  uint32_t chunk = x, slab = 0;
+  if (jb.slabs > 1) {
+    chunk = x % (uint32_t)jb.chunks;
+    slab = x / (uint32_t)jb.chunks;
+  }
 
   int vc, r0, rstep;
-  if (V >= kThreads) {
-    vc = slab * kThreads + threadIdx.x;
+  if (V >= THREADS) {
+    vc = slab * THREADS + threadIdx.x;
     r0 = 0;
     rstep = 1;
   } else {
-    rstep = kThreads / V;
+    rstep = THREADS / V;
     r0 = threadIdx.x / V;
     vc = threadIdx.x - r0 * V;
     if (r0 >= rstep) return;           // lanes beyond the last whole row of a pass idle
@@ -70,104 +80,145 @@ __device__ __forceinline__ void outer_vec4(const OuterJob &jb, int64_t bid) {
     gv[0] = grow[0]; gv[1] = grow[1]; gv[2] = grow[2]; gv[3] = grow[3];
   }
 
-  const int64_t abase = (m / o.S) * o.lda;
+  const int64_t abase = (o.S == 1 ? m : (int64_t)((uint32_t)m / (uint32_t)o.S)) * o.lda;
   const int i_begin = chunk * jb.per_chunk;
   const int i_end = min(i_begin + jb.per_chunk, o.d_in);
   f32x4 *obase = reinterpret_cast<f32x4 *>(o.out + m * (int64_t)o.d_in * o.d_out) + vc;
 
-  for (int i = i_begin + r0; i < i_end; i += rstep) {
-    const float av = load_a(o.a, o.a_bf16, abase + i);
-    __builtin_nontemporal_store(gv * av, obase + (int64_t)i * V);
+  if (jb.nt) {
+    for (int i = i_begin + r0; i < i_end; i += rstep) {
+      const float av = load_a(o.a, o.a_bf16, abase + i);
+      __builtin_nontemporal_store(gv * av, obase + (int64_t)i * V);
+    }
+  } else {
+    for (int i = i_begin + r0; i < i_end; i += rstep) {
+      const float av = load_a(o.a, o.a_bf16, abase + i);
+      obase[(int64_t)i * V] = gv * av;
+    }
   }
 }
 
 // Any d_out, any alignment: one thread per output value of a flattened [d_in * d_out] iteration.
-__device__ __forceinline__ void outer_flat(const OuterJob &jb, int64_t bid) {
+template <int THREADS>
+__device__ __forceinline__ void outer_flat(const OuterJob &jb, uint32_t chunk, int64_t m) {
   const OuterArgs &o = jb.o;
-  const int chunk = (int)(bid % jb.chunks);
-  const int64_t m = bid / jb.chunks;
   const int64_t per_m = (int64_t)o.d_in * o.d_out;
   const int64_t e_begin = (int64_t)chunk * jb.per_chunk;
   const int64_t e_end = min(e_begin + jb.per_chunk, per_m);
-  const int64_t abase = (m / o.S) * o.lda;
+  const int64_t abase = (o.S == 1 ? m : (int64_t)((uint32_t)m / (uint32_t)o.S)) * o.lda;
   const float *grow = o.g + m * o.ldg;
   float *obase = o.out + m * per_m;
-  for (int64_t e = e_begin + threadIdx.x; e < e_end; e += kThreads) {
-    const int i = (int)(e / o.d_out);
-    const int j = (int)(e - (int64_t)i * o.d_out);
+  for (int64_t e = e_begin + threadIdx.x; e < e_end; e += THREADS) {
+    const uint32_t i = (uint32_t)e / (uint32_t)o.d_out;     // per_m < 2^31 is checked by the host
+    const uint32_t j = (uint32_t)e - i * (uint32_t)o.d_out;
     obase[e] = load_a(o.a, o.a_bf16, abase + i) * grow[j];
   }
 }
 
-// All outer products of one call (one per layer) in a single launch: the workgroup id selects
-// the job, so that the short ramp-up and tail of a streaming kernel are paid once per call and
-// small layers fill the tail of large ones.
-__global__ __launch_bounds__(kThreads) void outer_product_kernel(const OuterBatch batch) {
-  const int64_t bid = blockIdx.x;
+// All outer products of one call go out in a single launch:
+// blockIdx.x selects the job and the piece of one iteration, blockIdx.y/z the iteration m.  The
+// ramp-up and tail of a streaming kernel are then paid once and small layers fill in between
+// large ones.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void outer_product_kernel(const OuterBatch batch) {
+  const int64_t m = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
+  if (m >= batch.M) return;
+  const uint32_t x = blockIdx.x;
   int j = 0;
 #pragma unroll
   for (int t = 1; t < kMaxJobs; ++t)
-    if (t < batch.n && bid >= batch.job[t].block_begin) j = t;
+    if (t < batch.n && x >= batch.job[t].x_begin) j = t;
   const OuterJob &jb = batch.job[j];
   if (jb.vec)
-    outer_vec4(jb, bid - jb.block_begin);
+    outer_vec4<THREADS>(jb, x - jb.x_begin, m);
   else
-    outer_flat(jb, bid - jb.block_begin);
+    outer_flat<THREADS>(jb, x - jb.x_begin, m);
 }
 
-// Cuts one outer product into workgroups; returns the number of workgroups.
-int64_t plan_job(const OuterArgs &o, OuterJob &jb) {
+// Cuts one iteration of an outer product into workgroups; returns how many.
+int64_t plan_job(const OuterArgs &o, OuterJob &jb, int64_t target) {
+  constexpr int threads = kThreads;
   jb.o = o;
   jb.vec = (o.d_out % 4 == 0) && ((reinterpret_cast<uintptr_t>(o.out) & 15) == 0);
   if (jb.vec) {
     const int V = o.d_out / 4;
     jb.V = V;
-    jb.slabs = V >= kThreads ? (V + kThreads - 1) / kThreads : 1;
-    const int rows_per_pass = V >= kThreads ? 1 : kThreads / V;
-    // about 64 KiB of output per workgroup
-    const int64_t pass_bytes = (int64_t)rows_per_pass * (V >= kThreads ? kThreads : V) * 16;
-    int passes = (int)((65536 + pass_bytes - 1) / pass_bytes);
+    jb.slabs = V >= threads ? (V + threads - 1) / threads : 1;
+    const int rows_per_pass = V >= threads ? 1 : threads / V;
+    const int64_t pass_bytes = (int64_t)rows_per_pass * (V >= threads ? threads : V) * 16;
+    int passes = (int)((target + pass_bytes - 1) / pass_bytes);
     if (passes < 1) passes = 1;
     int rows_per_chunk = passes * rows_per_pass;
     if (rows_per_chunk > o.d_in)
       rows_per_chunk = ((o.d_in + rows_per_pass - 1) / rows_per_pass) * rows_per_pass;
     jb.per_chunk = rows_per_chunk;
     jb.chunks = (o.d_in + rows_per_chunk - 1) / rows_per_chunk;
-    return o.M * jb.slabs * jb.chunks;
+    return (int64_t)jb.slabs * jb.chunks;
   }
   const int64_t per_m = (int64_t)o.d_in * o.d_out;
   jb.V = 0;
   jb.slabs = 1;
-  jb.per_chunk = 16384;
+  jb.per_chunk = 4096;
   jb.chunks = (int)((per_m + jb.per_chunk - 1) / jb.per_chunk);
-  return o.M * jb.chunks;
+  return jb.chunks;
+}
+
+// One launch per group of jobs with the same iteration count (normally all of them).
+hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, int nt, int64_t target,
+                        hipStream_t stream) {
+  int at = 0;
+  while (at < n) {
+    OuterBatch batch{};
+    batch.M = M;
+    int64_t xs = 0;
+    while (at < n && batch.n < kMaxJobs) {
+      const OuterArgs &o = jobs[at++];
+      if (o.M != M || o.d_in <= 0 || o.d_out <= 0) continue;
+      OuterJob &jb = batch.job[batch.n];
+      const int64_t nx = plan_job(o, jb, target);
+      if (xs + nx > 0x7fffffffLL) {
+        if (batch.n == 0) return hipErrorInvalidConfiguration;   // one job alone is too large
+        --at;                                                    // start a new launch with it
+        break;
+      }
+      jb.nt = nt;
+      jb.x_begin = (uint32_t)xs;
+      xs += nx;
+      ++batch.n;
+    }
+    if (batch.n == 0) continue;
+    const unsigned gy = (unsigned)(M < 65535 ? M : 65535);
+    const unsigned gz = (unsigned)((M + gy - 1) / gy);
+    if (gz > 65535) return hipErrorInvalidConfiguration;
+    const dim3 grid((unsigned)xs, gy, gz);
+    hipLaunchKernelGGL(outer_product_kernel<kThreads>, grid, dim3(kThreads), 0, stream, batch);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace
 
 hipError_t launch_outer(const OuterArgs *jobs, int n, hipStream_t stream) {
-  int at = 0;
-  while (at < n) {
-    OuterBatch batch{};
-    int64_t blocks = 0;
-    while (at < n && batch.n < kMaxJobs) {
-      const OuterArgs &o = jobs[at++];
-      if (o.M <= 0 || o.d_in <= 0 || o.d_out <= 0) continue;
-      OuterJob &jb = batch.job[batch.n];
-      const int64_t nb = plan_job(o, jb);
-      if (blocks + nb > 0x7fffffffLL) {
-        if (batch.n == 0) return hipErrorInvalidConfiguration;   // one job alone is too large
-        --at;                                                    // start a new launch with it
-        break;
-      }
-      jb.block_begin = blocks;
-      blocks += nb;
-      ++batch.n;
-    }
-    if (batch.n == 0) continue;
-    hipLaunchKernelGGL(outer_product_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream,
-                       batch);
-    hipError_t e = hipGetLastError();
+  // Workgroup size and store kind, from sweeps of this kernel on MI355X (HBM absorbs plain
+  // hipMemset fills at 6.1 to 6.4 TB/s, so that is the practical ceiling).  Many small independent
+  // workgroups do best: 8 KiB each (two stores per lane) for outputs of a few hundred MB, where
+  // non-temporal stores were 0 to 10 % faster than ordinary ones; 32 KiB each and ordinary stores
+  // for outputs of many GB (6.0 TB/s against 5.8 TB/s non-temporal).  One store per lane is too
+  // little: the index prologue then dominates.
+  double total_bytes = 0.0;
+  for (int i = 0; i < n; ++i) total_bytes += 4.0 * (double)jobs[i].M * jobs[i].d_in * jobs[i].d_out;
+  const bool huge = total_bytes > 1024.0 * 1024.0 * 1024.0;
+  const int nt = huge ? 0 : 1;
+  const int64_t target = huge ? 32768 : 8192;
+  for (int i = 0; i < n; ++i) {
+    if (jobs[i].M <= 0) continue;
+    if ((int64_t)jobs[i].d_in * jobs[i].d_out > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    bool seen = false;
+    for (int k = 0; k < i; ++k) seen = seen || (jobs[k].M == jobs[i].M);
+    if (seen) continue;
+    hipError_t e = launch_class(jobs, n, jobs[i].M, nt, target, stream);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
