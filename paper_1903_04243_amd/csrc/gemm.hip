@@ -25,7 +25,7 @@ using namespace dev;
 
 constexpr int kThreads = 256;
 
-template <int AMODE, bool WKN, int TM, int TN, int BKB>
+template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
   constexpr bool BF16 = (AMODE != A_F32);
   constexpr int ELEM = BF16 ? 2 : 4;
@@ -81,8 +81,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
     a_k[c] = kc * EPC;
     a_row[c] = nullptr;
     a_srow[c] = nullptr;
-    if (m < M) {
-      const int64_t b = m / g.S, s = m % g.S;
+    if (FAST || m < M) {
+      const int mc = FAST ? min(m, M - 1) : m;     // FAST: rows past the end re-read the last row
+      const int64_t b = mc / g.S, s = mc % g.S;
       const int64_t off = b * g.a_batch_stride + s * g.lda;
       if constexpr (AMODE == A_BF16)
         a_row[c] = static_cast<const __bf16 *>(g.A) + off;
@@ -109,11 +110,12 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
       w_k[c] = kc * EPC;
       w_n[c] = n;
       w_row[c] = nullptr;
-      if (n < N) {
+      if (FAST || n < N) {
+        const int nc = FAST ? min(n, N - 1) : n;
         if constexpr (BF16)
-          w_row[c] = static_cast<const __bf16 *>(g.W) + (int64_t)n * g.ldw;
+          w_row[c] = static_cast<const __bf16 *>(g.W) + (int64_t)nc * g.ldw;
         else
-          w_row[c] = static_cast<const float *>(g.W) + (int64_t)n * g.ldw;
+          w_row[c] = static_cast<const float *>(g.W) + (int64_t)nc * g.ldw;
       }
     } else {
       const int kl = id % BK, ng = id / BK;
@@ -131,15 +133,24 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
     const int kbase = kt * BK;
 #pragma unroll
     for (int c = 0; c < A_CHUNKS; ++c)
-      ra[c] = fetch_a<AMODE>(a_row[c], a_srow[c], kbase + a_k[c], K, a_vec_ok, s_vec_ok);
+      ra[c] = fetch_a<AMODE, FAST>(a_row[c], a_srow[c], scaled, kbase + a_k[c], K, a_vec_ok, s_vec_ok);
 #pragma unroll
     for (int c = 0; c < W_CHUNKS; ++c) {
       if constexpr (!WKN) {
         if constexpr (BF16)
-          rw[c] = load8_bf16(static_cast<const __bf16 *>(w_row[c]), kbase + w_k[c], K, w_vec_ok);
+          rw[c] = ld8<FAST>(static_cast<const __bf16 *>(w_row[c]), kbase + w_k[c], K, w_vec_ok);
         else
           rw[c] = __builtin_bit_cast(
-              u32x4, load4_f32(static_cast<const float *>(w_row[c]), kbase + w_k[c], K, w_vec_ok));
+              u32x4, ld4<FAST>(static_cast<const float *>(w_row[c]), kbase + w_k[c], K, w_vec_ok));
+      } else if constexpr (FAST) {
+        // 16 bytes along n of row k; both indices clamped (zeroed in stash if out of range)
+        const int k = kbase + w_k[c];
+        const int64_t roff = (int64_t)min(k, K - 1) * g.ldw;
+        if constexpr (BF16)
+          rw[c] = load8_bf16_fast(static_cast<const __bf16 *>(g.W) + roff, w_n[c], N);
+        else
+          rw[c] = __builtin_bit_cast(
+              u32x4, load4_f32_fast(static_cast<const float *>(g.W) + roff, w_n[c], N));
       } else {
         const int k = kbase + w_k[c];
         u32x4 v = {0u, 0u, 0u, 0u};
@@ -157,14 +168,21 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
     }
   };
 
-  auto stash = [&](int buf) {
+  // kt: the stage the registers were fetched for (FAST loads are zeroed here, not when issued)
+  auto stash = [&](int buf, int kt) {
     unsigned char *sA = smem + buf * STAGE;
     unsigned char *sW = sA + BM * STRIDE;
+    const int kbase = kt * BK;
 #pragma unroll
     for (int c = 0; c < A_CHUNKS; ++c)
-      *reinterpret_cast<u32x4 *>(sA + a_lds[c]) = finish_a<AMODE>(ra[c], scaled);
+      *reinterpret_cast<u32x4 *>(sA + a_lds[c]) =
+          finish_a<AMODE>(ra[c], scaled, FAST && (kbase + a_k[c] >= K));
 #pragma unroll
     for (int c = 0; c < W_CHUNKS; ++c) {
+      if constexpr (FAST) {
+        const bool past = WKN ? (kbase + w_k[c] >= K || w_n[c] >= N) : (kbase + w_k[c] >= K);
+        if (past) rw[c] = u32x4{0u, 0u, 0u, 0u};
+      }
       if constexpr (!WKN) {
         *reinterpret_cast<u32x4 *>(sW + w_lds[c]) = rw[c];
       } else if constexpr (BF16) {
@@ -190,13 +208,10 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
 
   const int nk = (K + BK - 1) / BK;
   fetch(0);
-  stash(0);
+  stash(0, 0);
   __syncthreads();
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) fetch(kt + 1);
-
+  auto mma_stage = [&](int buf) {
     const unsigned char *sA = smem + buf * STAGE + (wm + l32) * STRIDE + half * 16;
     const unsigned char *sW = smem + buf * STAGE + BM * STRIDE + (wn + l32) * STRIDE + half * 16;
 #pragma unroll
@@ -235,9 +250,20 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
       }
     }
 
-    if (kt + 1 < nk) stash(buf ^ 1);
+  };
+
+  // The last stage is peeled off so that the loop body has no conditional loads: the compiler
+  // can then prove that nothing is outstanding at the loop head and does not wait in mid-stage.
+  for (int kt = 0; kt + 1 < nk; ++kt) {
+    const int buf = kt & 1;
+    fetch(kt + 1);
+    __builtin_amdgcn_sched_barrier(0);   // keep the global loads ahead of the MFMAs ...
+    mma_stage(buf);
+    __builtin_amdgcn_sched_barrier(0);   // ... and their first use behind them
+    stash(buf ^ 1, kt + 1);
     __syncthreads();
   }
+  mma_stage((nk - 1) & 1);
 
   // ---- epilogue: accumulator element r of lane (half, l32) is row 8 (r / 4) + 4 half + r % 4,
   // column l32 of its 32 x 32 tile ----
@@ -288,11 +314,11 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
   }
 }
 
-template <int AMODE, bool WKN, int TM, int TN, int BKB>
+template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST>
 hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
   constexpr int smem = 2 * (BM + BN) * (BKB + 16);
-  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB>;
+  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB, FAST>;
   static bool attr_set = false;   // benign race: the attribute is idempotent
   if (!attr_set && smem > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -310,8 +336,12 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
   // Large tiles once they still give the 256 compute units a full wave of workgroups; otherwise
   // 64 x 64 tiles, so that small-batch products (M = B) spread over more units.
   const int64_t big = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
-  if (big >= 256) return launch_one<AMODE, WKN, 2, 2, 128>(g, stream);
-  return launch_one<AMODE, WKN, 1, 1, 128>(g, stream);
+  const bool fast = fast_loads_ok(g);
+  if (big >= 256)
+    return fast ? launch_one<AMODE, WKN, 2, 2, 128, true>(g, stream)
+                : launch_one<AMODE, WKN, 2, 2, 128, false>(g, stream);
+  return fast ? launch_one<AMODE, WKN, 1, 1, 128, true>(g, stream)
+              : launch_one<AMODE, WKN, 1, 1, 128, false>(g, stream);
 }
 
 }  // namespace

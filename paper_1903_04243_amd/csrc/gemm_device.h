@@ -37,7 +37,29 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
-// Up to 16 bytes of one operand row, k in [k0, k0 + n): float32 source.
+// Operand loads come in two flavours, chosen per launch on the host.
+//
+// FAST: every operand is 16-byte aligned with 16-byte-multiple strides and the contraction length
+// is a multiple of the chunk, so a chunk is either wholly inside or wholly outside the row.  The
+// load is then one unconditional 16-byte load from a clamped address (chunks past the end are
+// zeroed when the registers are consumed): no branch, nothing that would make the compiler wait
+// for earlier loads, so many loads stay in flight.  Row pointers are never null (out-of-range rows are clamped to the last row; what they
+// produce is never stored).
+//
+// General: any alignment and length; element-wise loads with bounds checks where needed.
+
+// The FAST loads return whatever sits at the clamped address; the caller zeroes a chunk whose
+// k0 is past the end LATER, when it consumes the registers (a select placed here would make
+// the compiler wait for the load at once and serialise all loads of a stage).
+__device__ __forceinline__ f32x4 load4_f32_fast(const float *row, int k0, int K) {
+  return *reinterpret_cast<const f32x4 *>(row + min(k0, K - 4));
+}
+
+__device__ __forceinline__ u32x4 load8_bf16_fast(const __bf16 *row, int k0, int K) {
+  return *reinterpret_cast<const u32x4 *>(row + min(k0, K - 8));
+}
+
+// Up to 16 bytes of one operand row, k in [k0, k0 + 4): float32 source (nullptr row = zeros).
 __device__ __forceinline__ f32x4 load4_f32(const float *row, int k0, int K, bool vec_ok) {
   f32x4 v = {0.f, 0.f, 0.f, 0.f};
   if (row == nullptr) return v;
@@ -67,34 +89,65 @@ __device__ __forceinline__ u32x4 load8_bf16(const __bf16 *row, int k0, int K, bo
   return v;
 }
 
+template <bool FAST>
+__device__ __forceinline__ f32x4 ld4(const float *row, int k0, int K, bool vec_ok) {
+  if constexpr (FAST) return load4_f32_fast(row, k0, K);
+  else return load4_f32(row, k0, K, vec_ok);
+}
+
+template <bool FAST>
+__device__ __forceinline__ u32x4 ld8(const __bf16 *row, int k0, int K, bool vec_ok) {
+  if constexpr (FAST) return load8_bf16_fast(row, k0, K);
+  else return load8_bf16(row, k0, K, vec_ok);
+}
+
 // Raw registers of one 16-byte LDS chunk of the A operand, before scaling / rounding.
 template <int AMODE> struct RawA;
 template <> struct RawA<A_F32> { f32x4 v, s; };
 template <> struct RawA<A_BF16> { u32x4 v; };
 template <> struct RawA<A_F32_TO_BF16> { f32x4 v0, v1, s0, s1; };
 
-template <int AMODE>
-__device__ __forceinline__ RawA<AMODE> fetch_a(const void *row, const float *srow, int k0, int K,
-                                               bool vec_ok, bool svec_ok) {
+// scaled is uniform over the workgroup (a scale operand exists); a null srow (general loads, row
+// out of range) reads as zeros.
+template <int AMODE, bool FAST>
+__device__ __forceinline__ RawA<AMODE> fetch_a(const void *row, const float *srow, bool scaled,
+                                               int k0, int K, bool vec_ok, bool svec_ok) {
   RawA<AMODE> r;
   if constexpr (AMODE == A_F32) {
-    r.v = load4_f32(static_cast<const float *>(row), k0, K, vec_ok);
-    if (srow) r.s = load4_f32(srow, k0, K, svec_ok);
+    r.v = ld4<FAST>(static_cast<const float *>(row), k0, K, vec_ok);
+    if (scaled) r.s = ld4<FAST>(srow, k0, K, svec_ok);
   } else if constexpr (AMODE == A_BF16) {
-    r.v = load8_bf16(static_cast<const __bf16 *>(row), k0, K, vec_ok);
+    r.v = ld8<FAST>(static_cast<const __bf16 *>(row), k0, K, vec_ok);
   } else {
-    r.v0 = load4_f32(static_cast<const float *>(row), k0, K, vec_ok);
-    r.v1 = load4_f32(static_cast<const float *>(row), k0 + 4, K, vec_ok);
-    if (srow) {
-      r.s0 = load4_f32(srow, k0, K, svec_ok);
-      r.s1 = load4_f32(srow, k0 + 4, K, svec_ok);
+    r.v0 = ld4<FAST>(static_cast<const float *>(row), k0, K, vec_ok);
+    r.v1 = ld4<FAST>(static_cast<const float *>(row), k0 + 4, K, vec_ok);
+    if (scaled) {
+      r.s0 = ld4<FAST>(srow, k0, K, svec_ok);
+      r.s1 = ld4<FAST>(srow, k0 + 4, K, svec_ok);
     }
   }
   return r;
 }
 
+// Host side: may this product take the FAST loads?
+inline bool fast_loads_ok(const GemmArgs &g) {
+  const int a_elem = (g.bf16 && !g.a_is_f32) ? 2 : 4;
+  const int w_elem = g.bf16 ? 2 : 4;
+  const int kchunk = g.bf16 ? 8 : 4;          // k elements per 16-byte LDS chunk
+  auto aligned = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  if (!aligned(g.A) || (g.lda * a_elem) % 16 || (g.a_batch_stride * a_elem) % 16) return false;
+  if (g.a_scale && (!aligned(g.a_scale) || (g.ld_scale * 4) % 16)) return false;
+  if (!aligned(g.W) || (g.ldw * w_elem) % 16) return false;
+  if (g.K % kchunk || g.K < kchunk) return false;
+  if (g.w_kn && (g.N % (16 / w_elem) || g.N < 16 / w_elem)) return false;
+  return true;
+}
+
+// zero: the chunk lies past the end of the contraction (FAST loads only; the general loads
+// zero-fill by themselves).
 template <int AMODE>
-__device__ __forceinline__ u32x4 finish_a(const RawA<AMODE> &r, bool scaled) {
+__device__ __forceinline__ u32x4 finish_a(const RawA<AMODE> &r, bool scaled, bool zero = false) {
+  if (zero) return u32x4{0u, 0u, 0u, 0u};
   if constexpr (AMODE == A_F32) {
     f32x4 v = scaled ? r.v * r.s : r.v;
     return __builtin_bit_cast(u32x4, v);

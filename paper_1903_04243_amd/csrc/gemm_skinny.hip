@@ -17,7 +17,7 @@ namespace {
 
 using namespace dev;
 
-template <int AMODE, bool WKN, int NW>
+template <int AMODE, bool WKN, int NW, bool FAST>
 __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) {
   constexpr bool BF16 = (AMODE != A_F32);
   constexpr int ELEM = BF16 ? 2 : 4;
@@ -59,8 +59,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   const float *a_srow = nullptr;
   {
     const int m = m0 + l32;
-    if (m < M) {
-      const int64_t b = m / g.S, s = m % g.S;
+    if (FAST || m < M) {
+      const int mc = FAST ? min(m, M - 1) : m;     // FAST: rows past the end re-read the last row
+      const int64_t b = mc / g.S, s = mc % g.S;
       const int64_t off = b * g.a_batch_stride + s * g.lda;
       if constexpr (AMODE == A_BF16)
         a_row = static_cast<const __bf16 *>(g.A) + off;
@@ -73,11 +74,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   const bool n_in = n < N;
   const void *w_row = nullptr;           // !WKN: row n of W [N, K]
   if constexpr (!WKN) {
-    if (n_in) {
+    if (FAST || n_in) {
+      const int nc = FAST ? min(n, N - 1) : n;
       if constexpr (BF16)
-        w_row = static_cast<const __bf16 *>(g.W) + (int64_t)n * g.ldw;
+        w_row = static_cast<const __bf16 *>(g.W) + (int64_t)nc * g.ldw;
       else
-        w_row = static_cast<const float *>(g.W) + (int64_t)n * g.ldw;
+        w_row = static_cast<const float *>(g.W) + (int64_t)nc * g.ldw;
     }
   }
 
@@ -86,12 +88,32 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
 
   auto load = [&](int slice, RawA<AMODE> &a, u32x4 &w) {
     const int k0 = slice * KSLICE + half * EPC;
-    a = fetch_a<AMODE>(a_row, a_srow, k0, K, a_vec_ok, s_vec_ok);
+    a = fetch_a<AMODE, FAST>(a_row, a_srow, scaled, k0, K, a_vec_ok, s_vec_ok);
     if constexpr (!WKN) {
       if constexpr (BF16)
-        w = load8_bf16(static_cast<const __bf16 *>(w_row), k0, K, w_vec_ok);
+        w = ld8<FAST>(static_cast<const __bf16 *>(w_row), k0, K, w_vec_ok);
       else
-        w = __builtin_bit_cast(u32x4, load4_f32(static_cast<const float *>(w_row), k0, K, w_vec_ok));
+        w = __builtin_bit_cast(u32x4, ld4<FAST>(static_cast<const float *>(w_row), k0, K, w_vec_ok));
+    } else if constexpr (FAST) {
+      // W is [K, N]: EPC strided loads down column n (coalesced across the 32 lanes of a half);
+      // indices clamped, no branches (out-of-range values are zeroed in compute())
+      const int nc = min(n, N - 1);
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if constexpr (BF16) {
+        const uint16_t *col = static_cast<const uint16_t *>(g.W) + nc;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t bits = (uint32_t)col[(int64_t)min(k0 + e, K - 1) * g.ldw];
+          v[e >> 1] |= bits << ((e & 1) * 16);
+        }
+      } else {
+        const float *col = static_cast<const float *>(g.W) + nc;
+        f32x4 f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) f[e] = col[(int64_t)min(k0 + e, K - 1) * g.ldw];
+        v = __builtin_bit_cast(u32x4, f);
+      }
+      w = v;
     } else {
       // W is [K, N]: EPC strided loads down column n (coalesced across the 32 lanes of a half)
       u32x4 v = {0u, 0u, 0u, 0u};
@@ -120,8 +142,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 
-  auto compute = [&](const RawA<AMODE> &a, const u32x4 &w) {
-    const u32x4 av = finish_a<AMODE>(a, scaled);
+  // slice: the k-slice the registers were loaded for (FAST loads are zeroed here, not when issued)
+  auto compute = [&](int slice, const RawA<AMODE> &a, u32x4 w) {
+    const bool past = FAST && (slice * KSLICE + half * EPC >= K);
+    const u32x4 av = finish_a<AMODE>(a, scaled, past);
+    if (FAST && (past || (WKN && !n_in))) w = u32x4{0u, 0u, 0u, 0u};
     if constexpr (BF16) {
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av),
                                                     __builtin_bit_cast(bf16x8, w), acc, 0, 0, 0);
@@ -147,7 +172,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
       if (cur < nslices) {
         const int nxt = cur + (R - 1) * NW;
         if (nxt < nslices) load(nxt, ra[(u + R - 1) % R], rw[(u + R - 1) % R]);
-        compute(ra[u], rw[u]);
+        compute(cur, ra[u], rw[u]);
       }
     }
   }
@@ -274,8 +299,15 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
 template <int AMODE, bool WKN, int NW>
 hipError_t launch_nw(const GemmArgs &g, hipStream_t stream) {
   const int64_t tiles = (int64_t)((g.M + 31) / 32) * ((g.N + 31) / 32);
-  hipLaunchKernelGGL((gemm_skinny_kernel<AMODE, WKN, NW>), dim3((unsigned)tiles), dim3(64 * NW), 0,
-                     stream, g);
+  // the strided column loads of the [K, N] layout need no alignment of N
+  GemmArgs probe = g;
+  if (WKN) probe.N = 16;
+  if (fast_loads_ok(probe))
+    hipLaunchKernelGGL((gemm_skinny_kernel<AMODE, WKN, NW, true>), dim3((unsigned)tiles),
+                       dim3(64 * NW), 0, stream, g);
+  else
+    hipLaunchKernelGGL((gemm_skinny_kernel<AMODE, WKN, NW, false>), dim3((unsigned)tiles),
+                       dim3(64 * NW), 0, stream, g);
   return hipGetLastError();
 }
 
