@@ -129,16 +129,18 @@ __device__ __forceinline__ RawA<AMODE> fetch_a(const void *row, const float *sro
   return r;
 }
 
-// Host side: may this product take the FAST loads?
-inline bool fast_loads_ok(const GemmArgs &g) {
+// Host side: may this product take the FAST loads?  check_w = false leaves W out of it (for a
+// kernel that reads W element by element).
+inline bool fast_loads_ok(const GemmArgs &g, bool check_w = true) {
   const int a_elem = (g.bf16 && !g.a_is_f32) ? 2 : 4;
   const int w_elem = g.bf16 ? 2 : 4;
   const int kchunk = g.bf16 ? 8 : 4;          // k elements per 16-byte LDS chunk
   auto aligned = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
   if (!aligned(g.A) || (g.lda * a_elem) % 16 || (g.a_batch_stride * a_elem) % 16) return false;
   if (g.a_scale && (!aligned(g.a_scale) || (g.ld_scale * 4) % 16)) return false;
-  if (!aligned(g.W) || (g.ldw * w_elem) % 16) return false;
   if (g.K % kchunk || g.K < kchunk) return false;
+  if (!check_w) return true;
+  if (!aligned(g.W) || (g.ldw * w_elem) % 16) return false;
   if (g.w_kn && (g.N % (16 / w_elem) || g.N < 16 / w_elem)) return false;
   return true;
 }

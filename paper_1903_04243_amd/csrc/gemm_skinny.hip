@@ -299,10 +299,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
 template <int AMODE, bool WKN, int NW>
 hipError_t launch_nw(const GemmArgs &g, hipStream_t stream) {
   const int64_t tiles = (int64_t)((g.M + 31) / 32) * ((g.N + 31) / 32);
-  // the strided column loads of the [K, N] layout need no alignment of N
-  GemmArgs probe = g;
-  if (WKN) probe.N = 16;
-  if (fast_loads_ok(probe))
+  // the element-wise column loads of the [K, N] layout put no condition on W
+  if (fast_loads_ok(g, !WKN))
     hipLaunchKernelGGL((gemm_skinny_kernel<AMODE, WKN, NW, true>), dim3((unsigned)tiles),
                        dim3(64 * NW), 0, stream, g);
   else
