@@ -17,13 +17,60 @@ namespace {
 
 using namespace dev;
 
+// Cotangent step through the last layer for the 32 rows of a head tile, on the vector ALUs (the
+// contraction is only N <= 32 = 4 N4 long):
+//     g_prev[m, i] = phi'(z[m, i]) * sum_j delta[m, j] * W[i, j]
+// The columns i of one tile are shared out over the `groups` workgroups that computed the same
+// tile (group index `cg`); inside a workgroup a thread owns one column and one band of rows
+// (consecutive threads store consecutive i of a row).  It keeps W[i, :] in registers; delta rows
+// come from LDS (zero beyond N); the mask value of the next row is requested while the current
+// one is computed.
+template <int N4, int NT>
+__device__ __forceinline__ void head_cotangent(const GemmArgs &g, const float (*hd)[32], int m0,
+                                               int tile_rows, int tid, int cg, int groups) {
+  const int K = g.K, N = g.N;
+  const int cols = (K + groups - 1) / groups;            // columns of this workgroup
+  const int c_begin = cg * cols, c_end = min(c_begin + cols, K);
+  const int bands = cols >= NT ? 1 : NT / cols;          // row bands worked on side by side
+  const int band = cols >= NT ? 0 : tid / cols;
+  const int c_first = c_begin + (cols >= NT ? tid : tid - band * cols);
+  if (band >= bands) return;
+  const int rows_per_band = (tile_rows + bands - 1) / bands;
+  const int r_begin = band * rows_per_band, r_end = min(r_begin + rows_per_band, tile_rows);
+  if (r_begin >= r_end) return;
+#pragma unroll 1
+  for (int i = c_first; i < c_end; i += NT) {
+    float w[4 * N4];
+#pragma unroll
+    for (int j = 0; j < 4 * N4; ++j) {
+      const int64_t at = (int64_t)i * g.ldw + min(j, N - 1);      // clamped: delta is 0 there
+      w[j] = g.bf16 ? (float)static_cast<const __bf16 *>(g.W)[at] : static_cast<const float *>(g.W)[at];
+    }
+    const float *mcol = g.head_mask + (int64_t)m0 * K + i;
+    float *gcol = g.head_gprev + (int64_t)m0 * K + i;
+    float nxt = mcol[(int64_t)r_begin * K];
+#pragma unroll 1
+    for (int r = r_begin; r < r_end; ++r) {
+      const float cur = nxt;
+      nxt = mcol[(int64_t)min(r + 1, r_end - 1) * K];
+      float acc = 0.f;
+#pragma unroll
+      for (int j4 = 0; j4 < N4; ++j4) {
+        const f32x4 dv = *reinterpret_cast<const f32x4 *>(&hd[r][4 * j4]);
+        acc += dv[0] * w[4 * j4] + dv[1] * w[4 * j4 + 1] + dv[2] * w[4 * j4 + 2] + dv[3] * w[4 * j4 + 3];
+      }
+      gcol[(int64_t)r * K] = acc * cur;
+    }
+  }
+}
+
 template <int AMODE, bool WKN, int NW, bool FAST>
 __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) {
   constexpr bool BF16 = (AMODE != A_F32);
   constexpr int ELEM = BF16 ? 2 : 4;
   constexpr int EPC = 16 / ELEM;       // k elements one lane feeds to the MFMA(s) of a slice
   constexpr int KSLICE = 2 * EPC;      // k elements per slice (two lane halves)
-  constexpr int R = (AMODE == A_F32) ? 8 : 4;   // slices in flight per wave
+  constexpr int R = 4;                 // slices in flight per wave
   constexpr int NT = 64 * NW;
 
   __shared__ float red[NW][32][33];
@@ -38,7 +85,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   const int M = g.M, N = g.N, K = g.K;
   const int tiles_m = (M + 31) / 32;
   const int m0 = (blockIdx.x % tiles_m) * 32;
-  const int n0 = (blockIdx.x / tiles_m) * 32;
+  // EPI_HEAD has a single column tile (N <= 32); the second grid index then counts the workgroups
+  // that share out the fused cotangent step of one row tile (each recomputes the tile's logits)
+  const bool is_head = (g.epilogue == EPI_HEAD);
+  const int second = blockIdx.x / tiles_m;
+  const int n0 = is_head ? 0 : second * 32;
 
   const bool a_vec_ok = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
                         ((g.lda * (AMODE == A_BF16 ? 2 : 4)) % 16 == 0) &&
@@ -177,28 +228,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
     }
   }
 
-  // Cotangent step fused behind the head: column i = tid of W_L (N values) and of the mask
-  // (one value per tile row) are requested now and consumed after the softmax.
-  float hw[32], hm[32];
-  auto head_fetch = [&](int i) {
-#pragma unroll
-    for (int j = 0; j < 32; ++j) {
-      hw[j] = 0.f;
-      if (j < N)
-        hw[j] = g.bf16 ? (float)static_cast<const __bf16 *>(g.W)[(int64_t)i * g.ldw + j]
-                       : static_cast<const float *>(g.W)[(int64_t)i * g.ldw + j];
-    }
-#pragma unroll
-    for (int r = 0; r < 32; ++r)
-      hm[r] = (r < tile_rows) ? g.head_mask[(int64_t)(m0 + r) * K + i] : 0.f;
-  };
-  if (head_step && tid < K) head_fetch(tid);
-
   // ---- fixed-order reduction of the NW partial tiles ----
 #pragma unroll
   for (int r = 0; r < 16; ++r) red[wave][8 * (r >> 2) + 4 * half + (r & 3)][l32] = acc[r];
   __syncthreads();
 
+#pragma unroll 1
   for (int o = tid; o < 32 * 32; o += NT) {
     const int row = o >> 5, col = o & 31;
     float v = 0.f;
@@ -215,7 +250,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
       // barrier that follows this loop)
       v += bias;
       red[0][row][col] = v;          // safe: slot (row, col) is read and written by this thread only
-      if (inside && g.C) g.C[(int64_t)m * g.ldc + nn] = v;
+      if (inside && g.C && second == 0) g.C[(int64_t)m * g.ldc + nn] = v;
       continue;
     }
     if (!inside) continue;
@@ -237,10 +272,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   }
 
   if (epi == EPI_HEAD) {
-    // softmax cross-entropy on the rows of the tile: delta = softmax(y) - onehot(label),
+    // Softmax cross-entropy on the rows of the tile: delta = softmax(y) - onehot(label),
     // loss = -log softmax(y)[label].  N <= 32: each half of a wave takes one row per pass, and
-    // the reductions stay inside the half.
+    // the reductions stay inside the half.  These few waves run the code once, so what they pay
+    // for is instruction fetch: the loops below are kept rolled and short on purpose.
     __syncthreads();
+#pragma unroll 1
     for (int row0 = 2 * wave; row0 < 32; row0 += 2 * NW) {
       const int row = row0 + half;
       const int m = m0 + row;
@@ -250,7 +287,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
       float mx = y;
 #pragma unroll
       for (int off = 16; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-      const float ex = live ? expf(y - mx) : 0.f;
+      const float ex = live ? __expf(y - mx) : 0.f;
       const int label = lab[row];
       float den = ex, others = (l32 == label) ? 0.f : ex;
 #pragma unroll
@@ -261,36 +298,23 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
       const float inv = valid ? 1.f / den : 0.f;
       // p[label] - 1 = -(sum of the other classes) / den, free of cancellation
       const float delta = (l32 == label) ? -others * inv : ex * inv;
-      if (live) g.C2[(int64_t)m * g.ldc + l32] = delta;
+      if (live && second == 0) g.C2[(int64_t)m * g.ldc + l32] = delta;
       hd[row][l32] = live ? delta : 0.f;       // kept, zero-padded, for the cotangent step below
       const bool label_ok = (label >= 0) && (label < N);
       const float yl = __shfl(y, half * 32 + (label_ok ? label : 0), 64);
-      if (g.loss && valid && l32 == 0) g.loss[m] = logf(den) - ((label_ok ? yl : mx) - mx);
+      if (g.loss && valid && l32 == 0 && second == 0) g.loss[m] = __logf(den) - ((label_ok ? yl : mx) - mx);
     }
     if (head_step) {
-      // cotangent through the last layer for the tile's rows, on the vector ALUs (the contraction
-      // is only N <= 32 long): g_prev[m, i] = phi'(z[m, i]) * sum_j delta[m, j] * W[i, j].
-      // A thread owns column i; consecutive threads store consecutive i of one row.
       __syncthreads();
-      for (int i = tid; i < K; i += NT) {
-        if (i != tid) head_fetch(i);
-#pragma unroll
-        for (int r = 0; r < 32; ++r) {
-          if (r < tile_rows) {
-            float acc2 = 0.f;
-#pragma unroll
-            for (int j4 = 0; j4 < 8; ++j4) {
-              if (4 * j4 < N) {      // uniform: skips the zero padding beyond d_L
-                const f32x4 dv = *reinterpret_cast<const f32x4 *>(&hd[r][4 * j4]);
-                acc2 += dv[0] * hw[4 * j4] + dv[1] * hw[4 * j4 + 1] + dv[2] * hw[4 * j4 + 2] +
-                        dv[3] * hw[4 * j4 + 3];
-              }
-            }
-            g.head_gprev[(int64_t)(m0 + r) * K + i] = acc2 * hm[r];
-          }
-          // keep the scheduler from hoisting the LDS reads of all 32 rows at once
-          if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
-        }
+      switch ((N + 3) >> 2) {
+        case 1: head_cotangent<1, NT>(g, hd, m0, tile_rows, tid, second, (int)gridDim.x / tiles_m); break;
+        case 2: head_cotangent<2, NT>(g, hd, m0, tile_rows, tid, second, (int)gridDim.x / tiles_m); break;
+        case 3: head_cotangent<3, NT>(g, hd, m0, tile_rows, tid, second, (int)gridDim.x / tiles_m); break;
+        case 4: head_cotangent<4, NT>(g, hd, m0, tile_rows, tid, second, (int)gridDim.x / tiles_m); break;
+        case 5: head_cotangent<5, NT>(g, hd, m0, tile_rows, tid, second, (int)gridDim.x / tiles_m); break;
+        case 6: head_cotangent<6, NT>(g, hd, m0, tile_rows, tid, second, (int)gridDim.x / tiles_m); break;
+        case 7: head_cotangent<7, NT>(g, hd, m0, tile_rows, tid, second, (int)gridDim.x / tiles_m); break;
+        default: head_cotangent<8, NT>(g, hd, m0, tile_rows, tid, second, (int)gridDim.x / tiles_m); break;
       }
     }
   }
@@ -298,7 +322,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
 
 template <int AMODE, bool WKN, int NW>
 hipError_t launch_nw(const GemmArgs &g, hipStream_t stream) {
-  const int64_t tiles = (int64_t)((g.M + 31) / 32) * ((g.N + 31) / 32);
+  int64_t tiles = (int64_t)((g.M + 31) / 32) * ((g.N + 31) / 32);
+  if (g.epilogue == EPI_HEAD && g.head_gprev) {
+    // share the fused cotangent step of each row tile out over up to 8 workgroups
+    int groups = g.K / 64;
+    groups = groups < 1 ? 1 : (groups > 8 ? 8 : groups);
+    tiles *= groups;
+  }
   // the element-wise column loads of the [K, N] layout put no condition on W
   if (fast_loads_ok(g, !WKN))
     hipLaunchKernelGGL((gemm_skinny_kernel<AMODE, WKN, NW, true>), dim3((unsigned)tiles),
