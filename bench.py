@@ -154,6 +154,19 @@ def main():
         layers = w.layers_out or tuple(range(1, len(d)))
         return {"outer_product": {"bytes": 4 * B * S * sum(d[l - 1] * d[l] for l in layers)}}
 
+    def measured_traffic(name):
+        """HBM bytes per launch of the outer-product kernel from the committed counter runs, or
+        None if that kernel's source has changed since they were taken."""
+        import hashlib
+        try:
+            rec = json.load(open(os.path.join(ROOT, "profiles", "outer_product_hbm_traffic.txt")))
+            src = os.path.join(ROOT, "paper_1903_04243_amd", "csrc", "writer.hip")
+            if hashlib.sha256(open(src, "rb").read()).hexdigest() != rec["writer_hip_sha256"]:
+                return None
+            return rec["workloads"][name]["hbm_bytes_per_launch"]
+        except (OSError, KeyError, ValueError):
+            return None
+
     def roofline(w, kt):
         alg = algorithmic(w)
         if "outer_product" in alg:
@@ -162,7 +175,7 @@ def main():
             per_launch_ms = k["ms_per_step"] / k["launches_per_step"]
             gbs = per_launch_bytes / (per_launch_ms * 1e-3) / 1e9
             return {"kernel": "outer_product", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                    "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                     "bytes_per_launch": per_launch_bytes, "ms_per_launch": per_launch_ms,
                     "launches_per_step": k["launches_per_step"]}
         flops = sum(v["flops"] for v in alg.values())

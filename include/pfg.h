@@ -128,14 +128,14 @@ int pfg_jacobian_weights(const pfg_mlp *net, const void *X, int64_t B, int head,
  * library from that thread. */
 const char *pfg_last_error(void);
 
-/* Per-kernel device timing, for measurement.  While enabled, every call records one HIP event on
- * its stream when it begins and one after each kernel it enqueues; a kernel's duration is the
- * time between the event before it and the event after it.  pfg_timing_query waits for the
- * events recorded so far and reports, for the kernel family called `name`, the number of launches
- * and their summed duration in milliseconds since the last reset; it returns PFG_ERR_SHAPE if no
- * launch of that family was recorded.  pfg_timing_names writes the recorded family names,
- * separated by '\n', into buf (truncated to cap bytes including the final NUL).  Do not enable
- * timing while the stream is being captured into a graph. */
+/* Per-kernel device timing, for measurement.  While enabled, every kernel the library enqueues
+ * carries its own pair of HIP events, attached to the dispatch, whose timestamps are the kernel's
+ * begin and end on the device.  pfg_timing_query waits for the kernels enqueued so far and
+ * reports, for the kernel family called `name`, the number of launches and their summed run
+ * time in milliseconds since the last reset; it returns PFG_ERR_SHAPE if no launch of that
+ * family was recorded.  pfg_timing_names writes the recorded family names, separated by '\n',
+ * into buf (truncated to cap bytes including the final NUL).  Do not enable timing while the
+ * stream is being captured into a graph. */
 int pfg_timing_enable(int on);
 int pfg_timing_reset(void);
 int pfg_timing_query(const char *name, int64_t *launches, double *total_ms);

@@ -2,9 +2,25 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace pfg {
+
+// Per-kernel timing.  When timing is enabled this hands out a fresh pair of events that the
+// launch attaches to the kernel dispatch itself (hipExtLaunchKernelGGL), so that their timestamps
+// are the kernel's own begin and end on the device; it returns false when timing is off.
+bool timing_next_events(hipEvent_t *start, hipEvent_t *stop);
+
+#define PFG_KERNEL(kern, grid, block, smem, stream, ...)                                   \
+  do {                                                                                     \
+    hipEvent_t ev_start_, ev_stop_;                                                        \
+    if (::pfg::timing_next_events(&ev_start_, &ev_stop_))                                  \
+      hipExtLaunchKernelGGL(kern, grid, block, smem, stream, ev_start_, ev_stop_, 0,       \
+                            __VA_ARGS__);                                                  \
+    else                                                                                   \
+      hipLaunchKernelGGL(kern, grid, block, smem, stream, __VA_ARGS__);                    \
+  } while (0)
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));

@@ -125,7 +125,7 @@ hipError_t launch_head_softmax_ce(const float *y, const int32_t *labels, int64_t
                                   float *delta, float *loss, hipStream_t stream) {
   if (B <= 0) return hipSuccess;
   const int64_t blocks = (B + kWavesPerBlock - 1) / kWavesPerBlock;
-  hipLaunchKernelGGL(head_softmax_ce_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, y,
+  PFG_KERNEL(head_softmax_ce_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, y,
                      labels, B, n, delta, loss);
   return hipGetLastError();
 }
@@ -135,7 +135,7 @@ hipError_t launch_seed_rows(const float *y, const float *seeds, int64_t seed_bat
                             hipStream_t stream) {
   if (B * S <= 0) return hipSuccess;
   const int64_t blocks = (B * S + kWavesPerBlock - 1) / kWavesPerBlock;
-  hipLaunchKernelGGL(seed_rows_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, y, seeds,
+  PFG_KERNEL(seed_rows_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, y, seeds,
                      seed_batch_stride, B, S, n, head, G);
   return hipGetLastError();
 }
@@ -144,7 +144,7 @@ hipError_t launch_transpose(const void *src, int32_t src_bf16, int32_t R, int32_
                             hipStream_t stream) {
   if (R <= 0 || C <= 0) return hipSuccess;
   const int64_t blocks = (int64_t)((R + 31) / 32) * ((C + 31) / 32);
-  hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, src,
+  PFG_KERNEL(transpose_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, src,
                      src_bf16, R, C, dst);
   return hipGetLastError();
 }

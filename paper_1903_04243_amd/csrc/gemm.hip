@@ -327,7 +327,7 @@ hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
     attr_set = true;
   }
   const int64_t tiles = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(kThreads), smem, stream, g);
+  PFG_KERNEL(kern, dim3((unsigned)tiles), dim3(kThreads), smem, stream, g);
   return hipGetLastError();
 }
 

@@ -331,10 +331,10 @@ hipError_t launch_nw(const GemmArgs &g, hipStream_t stream) {
   }
   // the element-wise column loads of the [K, N] layout put no condition on W
   if (fast_loads_ok(g, !WKN))
-    hipLaunchKernelGGL((gemm_skinny_kernel<AMODE, WKN, NW, true>), dim3((unsigned)tiles),
+    PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, true>), dim3((unsigned)tiles),
                        dim3(64 * NW), 0, stream, g);
   else
-    hipLaunchKernelGGL((gemm_skinny_kernel<AMODE, WKN, NW, false>), dim3((unsigned)tiles),
+    PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, false>), dim3((unsigned)tiles),
                        dim3(64 * NW), 0, stream, g);
   return hipGetLastError();
 }

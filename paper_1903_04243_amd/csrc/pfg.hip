@@ -27,49 +27,19 @@ int fail(int code, const char *fmt, ...) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Per-kernel timing with HIP events on the call's stream.
+// Per-kernel timing: every kernel launch gets its own pair of events attached to the dispatch
+// (see PFG_KERNEL); their difference is the kernel's run time on the device.
 // ------------------------------------------------------------------------------------------
-// Each timed kernel is followed by one event; its duration is the time since the previous event
-// on the stream (the one after the preceding kernel, or the one recorded when the call began).
-// In a queue that is kept busy this is the interval the kernel occupies the device.
-struct TimedLaunch { const char *name; hipEvent_t start, stop; bool owns_start; };
+struct TimedLaunch { const char *name; hipEvent_t start, stop; };
 std::mutex g_timing_mu;
 bool g_timing_on = false;
 std::vector<TimedLaunch> g_pending;
 std::map<std::string, std::pair<int64_t, double>> g_totals;
-thread_local hipEvent_t t_last_event = nullptr;   // last event of the call in progress
-
-void timing_begin_call(hipStream_t stream) {
-  t_last_event = nullptr;
-  if (!g_timing_on) return;
-  hipEvent_t e;
-  if (hipEventCreate(&e) != hipSuccess) return;
-  (void)hipEventRecord(e, stream);
-  t_last_event = e;
-  std::lock_guard<std::mutex> lk(g_timing_mu);
-  g_pending.push_back({nullptr, e, nullptr, true});    // keeps the first event alive until drained
-}
-
-struct TimedScope {
-  const char *name;
-  hipStream_t stream;
-  bool on;
-  TimedScope(const char *n, hipStream_t s) : name(n), stream(s), on(g_timing_on && t_last_event) {}
-  ~TimedScope() {
-    if (!on) return;
-    hipEvent_t stop;
-    if (hipEventCreate(&stop) != hipSuccess) return;
-    (void)hipEventRecord(stop, stream);
-    std::lock_guard<std::mutex> lk(g_timing_mu);
-    g_pending.push_back({name, t_last_event, stop, false});
-    t_last_event = stop;
-  }
-};
+thread_local const char *t_family = "kernel";   // family name of the launches being enqueued
 
 void drain_pending() {
   std::lock_guard<std::mutex> lk(g_timing_mu);
   for (auto &t : g_pending) {
-    if (!t.name) continue;
     float ms = 0.f;
     if (hipEventSynchronize(t.stop) == hipSuccess &&
         hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) {
@@ -77,14 +47,26 @@ void drain_pending() {
       e.first += 1;
       e.second += ms;
     }
-  }
-  // every event is the stop of one entry or the first event of a call: destroy each once
-  for (auto &t : g_pending) {
-    if (t.owns_start) (void)hipEventDestroy(t.start);
-    if (t.stop) (void)hipEventDestroy(t.stop);
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
   }
   g_pending.clear();
 }
+
+}  // namespace
+
+namespace pfg {
+bool timing_next_events(hipEvent_t *start, hipEvent_t *stop) {
+  if (!g_timing_on) return false;
+  if (hipEventCreate(start) != hipSuccess) return false;
+  if (hipEventCreate(stop) != hipSuccess) { (void)hipEventDestroy(*start); return false; }
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  g_pending.push_back({t_family, *start, *stop});
+  return true;
+}
+}  // namespace pfg
+
+namespace {
 
 // ------------------------------------------------------------------------------------------
 // Validation helpers.
@@ -210,8 +192,8 @@ inline float *at(void *ws, size_t off) { return reinterpret_cast<float *>(static
 
 #define PFG_LAUNCH(name, expr)                                                         \
   do {                                                                                 \
-    hipError_t e_;                                                                     \
-    { TimedScope ts_(name, stream); e_ = (expr); }                                     \
+    t_family = name;                                                                   \
+    hipError_t e_ = (expr);                                                            \
     if (e_ != hipSuccess)                                                              \
       return fail(PFG_ERR_DEVICE, "%s: %s", name, hipGetErrorString(e_));              \
   } while (0)
@@ -416,7 +398,6 @@ int pfg_per_example_grads(const pfg_mlp *net, const void *X, const int32_t *labe
   if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  timing_begin_call(stream);
   const int L = net->num_layers;
   const int32_t *d = net->dims;
 
@@ -456,7 +437,6 @@ int pfg_jacobian_input(const pfg_mlp *net, const void *X, int64_t B, const float
   if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  timing_begin_call(stream);
   const int L = net->num_layers;
   const int32_t *d = net->dims;
   const bool bf16 = (net->dtype == PFG_BF16);
@@ -547,7 +527,6 @@ int pfg_jacobian_weights(const pfg_mlp *net, const void *X, int64_t B, int head,
   if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  timing_begin_call(stream);
   const int L = net->num_layers;
   const int32_t *d = net->dims;
 

@@ -191,7 +191,7 @@ hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, int nt, int64_t
     const unsigned gz = (unsigned)((M + gy - 1) / gy);
     if (gz > 65535) return hipErrorInvalidConfiguration;
     const dim3 grid((unsigned)xs, gy, gz);
-    hipLaunchKernelGGL(outer_product_kernel<kThreads>, grid, dim3(kThreads), 0, stream, batch);
+    PFG_KERNEL(outer_product_kernel<kThreads>, grid, dim3(kThreads), 0, stream, batch);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
