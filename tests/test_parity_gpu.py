@@ -340,6 +340,100 @@ def test_unaligned_buffers_take_the_scalar_paths(oracle):
     assert slice_rel_err(J.cpu().numpy(), oracle.jacobian_input(onet, inp.X), lead=2) <= TOL_F32
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_large_batch_takes_the_tiled_kernels(oracle, dtype):
+    # B = 8200 rows: every product has at least 128 tiles of 64 x 64 and goes through the LDS-tiled
+    # kernel (forward [K, N] layout and cotangent [N, K] layout), with a ragged last row tile;
+    # dims chosen so that one layer meets the fast-load conditions and one does not
+    dims, B, act = (96, 160, 70, 12), 8200, "gelu"
+    say(f"tiled kernels: dims {dims} B={B} {dtype}")
+    w = wl.Workload("tiled", 60, "per_example_grads", dims, act, dtype, B, "normal", "normal_fan_in")
+    inp = draw(w, bias_scale=0.2)
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16
+    check_grads(oracle, inp, act, dtype, tol, want_dW=[False, False, True], tag=f"tiled-{dtype}")
+    # input Jacobian with per-example seeds: M = B * S rows through the cotangent kernels
+    Bj, S = 700, 12
+    onet = oracle.Net(inp.Ws, inp.bs, act)
+    seeds = np.random.default_rng(5).standard_normal((Bj, S, dims[-1])).astype(np.float32)
+    ref = oracle.jacobian_input(onet, inp.X[:Bj], seeds=seeds)
+    net = gpu_net(inp, act, dtype)
+    J = pfg.pfg_jacobian_input(net, gpu_x(inp, dtype)[:Bj].contiguous(), seeds=dev(seeds))
+    torch.cuda.synchronize()
+    e = slice_rel_err(J.cpu().numpy(), ref, lead=2)
+    say(f"  tiled-{dtype} J per-example seeds rel err {e:.3e}")
+    assert e <= tol
+
+
+def test_deep_network_and_wide_seed_block(oracle):
+    # five layers; weight Jacobian with shared seeds S = 40 > d_L, all layers, softmax head
+    dims, B, act = (24, 48, 40, 56, 32, 20), 9, "tanh"
+    say(f"deep network {dims} B={B}")
+    w = wl.Workload("deep", 61, "per_example_grads", dims, act, "f32", B, "normal", "normal_fan_in")
+    inp = draw(w, bias_scale=0.3)
+    check_grads(oracle, inp, act, "f32", TOL_F32, tag="deep")
+    onet = oracle.Net(inp.Ws, inp.bs, act)
+    net = gpu_net(inp, act, "f32")
+    seeds = np.random.default_rng(6).standard_normal((40, dims[-1])).astype(np.float32)
+    rJW, rJb = oracle.jacobian_weights(onet, inp.X, head="softmax", seeds=seeds)
+    JW, Jb = pfg.pfg_jacobian_weights(net, gpu_x(inp, "f32"), head="softmax", seeds=dev(seeds))
+    J = pfg.pfg_jacobian_input(net, gpu_x(inp, "f32"), seeds=dev(seeds))
+    torch.cuda.synchronize()
+    e = max(max(slice_rel_err(JW[l].cpu().numpy(), rJW[l], lead=2),
+                slice_rel_err(Jb[l].cpu().numpy(), rJb[l], lead=2)) for l in range(net.L))
+    say(f"  deep JW/Jb rel err {e:.3e}")
+    assert e <= TOL_F32
+    e = slice_rel_err(J.cpu().numpy(), oracle.jacobian_input(onet, inp.X, seeds=seeds), lead=2)
+    say(f"  deep J rel err {e:.3e}")
+    assert e <= TOL_F32
+
+
+def test_graph_replay_matches_eager(oracle):
+    # one call captured into a HIP graph (the library records only kernel launches, no memsets)
+    # and replayed several times with eager work and synchronisations in between; every replay
+    # must reproduce the eager result bit for bit
+    w = wl.WORKLOADS["c2_mnist_mlp_grads"]
+    inp = draw(w, B=32)
+    net = gpu_net(inp, w.act, "f32")
+    X, labels = gpu_x(inp, "f32"), dev(inp.labels)
+    f32 = dict(dtype=torch.float32, device="cuda:0")
+    B = 32
+
+    def buffers():
+        return ([torch.zeros((B, net.dims[l], net.dims[l + 1]), **f32) for l in range(net.L)],
+                [torch.zeros((B, net.dims[l + 1]), **f32) for l in range(net.L)],
+                torch.zeros((B,), **f32),
+                torch.empty(pfg.pfg_workspace_bytes(net, "per_example_grads", B), dtype=torch.uint8,
+                            device="cuda:0"))
+
+    dW_e, db_e, loss_e, ws_e = buffers()
+    pfg.pfg_per_example_grads(net, X, labels, out_dW=dW_e, out_db=db_e, out_loss=loss_e,
+                              workspace=ws_e)
+    torch.cuda.synchronize()
+    dW_g, db_g, loss_g, ws_g = buffers()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pfg.pfg_per_example_grads(net, X, labels, out_dW=dW_g, out_db=db_g, out_loss=loss_g,
+                                  workspace=ws_g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pfg.pfg_per_example_grads(net, X, labels, out_dW=dW_g, out_db=db_g, out_loss=loss_g,
+                                  workspace=ws_g)
+    for replay in range(4):
+        for t in dW_g + db_g + [loss_g]:
+            t.fill_(float("nan"))                      # eager work between the replays
+        pfg.pfg_jacobian_input(net, X)                 # an eager call of the library in between
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l in range(net.L):
+            assert torch.equal(dW_g[l], dW_e[l]), f"replay {replay}: dW{l + 1} differs"
+            assert torch.equal(db_g[l], db_e[l]), f"replay {replay}: db{l + 1} differs"
+        assert torch.equal(loss_g, loss_e)
+
+
 def test_iterations_are_independent(oracle):
     # permuting the batch permutes the slices bit for bit; a duplicated example gives identical
     # slices (stateless parallel-for, Section 3.4)
