@@ -403,6 +403,11 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
   if (big >= 256)
     return fast ? launch_one<AMODE, WKN, 2, 2, 128, true>(g, stream)
                 : launch_one<AMODE, WKN, 2, 2, 128, false>(g, stream);
+  if constexpr (AMODE != A_F32) {
+    // bf16 MFMAs are 16 times faster: a 64 x 64 tile needs a deeper stage (128 k) to have
+    // enough MFMA work between two barriers
+    if (fast && g.K >= 256) return launch_one<AMODE, WKN, 1, 1, 256, true>(g, stream);
+  }
   return fast ? launch_one<AMODE, WKN, 1, 1, 128, true>(g, stream)
               : launch_one<AMODE, WKN, 1, 1, 128, false>(g, stream);
 }

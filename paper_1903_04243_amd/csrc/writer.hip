@@ -204,14 +204,14 @@ hipError_t launch_outer(const OuterArgs *jobs, int n, hipStream_t stream) {
   // Workgroup size and store kind, from sweeps of this kernel on MI355X (HBM absorbs plain
   // hipMemset fills at 6.1 to 6.4 TB/s, so that is the practical ceiling).  Many small independent
   // workgroups do best: 8 KiB each (two stores per lane) for outputs of a few hundred MB, where
-  // non-temporal stores were 0 to 10 % faster than ordinary ones; 32 KiB each and ordinary stores
-  // for outputs of many GB (6.0 TB/s against 5.8 TB/s non-temporal).  One store per lane is too
-  // little: the index prologue then dominates.
+  // non-temporal stores were 0 to 10 % faster than ordinary ones; 16 KiB each and ordinary stores
+  // for outputs of many GB (6.2 TB/s against 5.8 TB/s non-temporal; 8 KiB: 5.7, 32 KiB: 6.1).
+  // One store per lane is too little: the index prologue then dominates.
   double total_bytes = 0.0;
   for (int i = 0; i < n; ++i) total_bytes += 4.0 * (double)jobs[i].M * jobs[i].d_in * jobs[i].d_out;
   const bool huge = total_bytes > 1024.0 * 1024.0 * 1024.0;
   const int nt = huge ? 0 : 1;
-  const int64_t target = huge ? 32768 : 8192;
+  const int64_t target = huge ? 16384 : 8192;
   for (int i = 0; i < n; ++i) {
     if (jobs[i].M <= 0) continue;
     if ((int64_t)jobs[i].d_in * jobs[i].d_out > 0x7fffffffLL) return hipErrorInvalidConfiguration;
