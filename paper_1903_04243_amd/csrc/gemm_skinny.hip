@@ -73,7 +73,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   constexpr int R = 4;                 // slices in flight per wave
   constexpr int NT = 64 * NW;
 
-  __shared__ float red[NW][32][33];
+  __shared__ __align__(16) float red[NW][32][36];   // row stride 144 B: 16-byte aligned rows
   __shared__ __align__(16) float hd[32][32];   // EPI_HEAD: delta rows of the tile, zero-padded
   __shared__ int lab[32];                      // EPI_HEAD: labels of the tile's rows
 
@@ -233,42 +233,106 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   for (int r = 0; r < 16; ++r) red[wave][8 * (r >> 2) + 4 * half + (r & 3)][l32] = acc[r];
   __syncthreads();
 
-#pragma unroll 1
-  for (int o = tid; o < 32 * 32; o += NT) {
-    const int row = o >> 5, col = o & 31;
-    float v = 0.f;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) v += red[w][row][col];
+  // Each thread finishes Q consecutive columns of one row: it sums the NW partial tiles, fetches
+  // the bias / mask values it needs in one go (a vector load when alignment allows) and writes
+  // its Q results, again as one vector when possible.  One pass, no loop: with so few waves the
+  // latency of every dependent global access counts.
+  constexpr int Q = 1024 / NT;                    // 4 (NW = 4) or 2 (NW = 8)
+  static_assert(Q == 2 || Q == 4, "the epilogue expects 256 or 512 threads");
+  {
+    const int row = tid / (32 / Q), col = (tid % (32 / Q)) * Q;
     const int m = m0 + row, nn = n0 + col;
-    const bool inside = (m < M) && (nn < N);
-    float bias = 0.f;
-    if (inside && (epi == EPI_BIAS || epi == EPI_FORWARD || epi == EPI_HEAD) && g.bias)
-      bias = g.bf16 ? (float)static_cast<const __bf16 *>(g.bias)[nn]
-                    : static_cast<const float *>(g.bias)[nn];
-    if (epi == EPI_HEAD) {
-      // keep the biased logits in LDS for the softmax pass below (every thread reaches the
-      // barrier that follows this loop)
-      v += bias;
-      red[0][row][col] = v;          // safe: slot (row, col) is read and written by this thread only
-      if (inside && g.C && second == 0) g.C[(int64_t)m * g.ldc + nn] = v;
-      continue;
-    }
-    if (!inside) continue;
+    float v[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) v[q] = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w)
+#pragma unroll
+      for (int q = 0; q < Q; ++q) v[q] += red[w][row][col + q];
+    const bool row_in = m < M;
+    const bool all_in = row_in && (nn + Q <= N);
     const int64_t off = (int64_t)m * g.ldc + nn;
-    if (epi == EPI_FORWARD) {
-      const float z = v + bias;
-      g.C2[off] = act_deriv(g.act, z);
-      if (g.C == nullptr) continue;
-      v = act_value(g.act, z);
-    } else if (epi == EPI_BIAS) {
-      v += bias;
-    } else if (epi == EPI_MASK) {
-      v *= g.emask[(int64_t)(m / g.S) * g.ld_emask + nn];
+    const bool want_bias = (epi == EPI_BIAS || epi == EPI_FORWARD || epi == EPI_HEAD) && g.bias;
+    float aux[Q];                                  // bias (added) or mask (multiplied)
+#pragma unroll
+    for (int q = 0; q < Q; ++q) aux[q] = (epi == EPI_MASK) ? 1.f : 0.f;
+    if (row_in) {
+      if (want_bias) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+          if (nn + q < N)
+            aux[q] = g.bf16 ? (float)static_cast<const __bf16 *>(g.bias)[nn + q]
+                            : static_cast<const float *>(g.bias)[nn + q];
+      } else if (epi == EPI_MASK) {
+        const float *mp = g.emask + (int64_t)(m / g.S) * g.ld_emask + nn;
+        if (all_in && ((reinterpret_cast<uintptr_t>(mp) & (4 * Q - 1)) == 0)) {
+          typedef float fq __attribute__((ext_vector_type(Q)));
+          const fq mv = *reinterpret_cast<const fq *>(mp);
+#pragma unroll
+          for (int q = 0; q < Q; ++q) aux[q] = mv[q];
+        } else {
+#pragma unroll
+          for (int q = 0; q < Q; ++q)
+            if (nn + q < N) aux[q] = mp[q];
+        }
+      }
     }
-    if (g.streaming)
-      __builtin_nontemporal_store(v, g.C + off);
-    else
-      g.C[off] = v;
+    if (epi == EPI_HEAD) {
+      // keep the biased logits in LDS for the softmax pass below
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
+        v[q] += aux[q];
+        red[0][row][col + q] = v[q];   // safe: these slots are read and written by this thread only
+        if (row_in && nn + q < N && g.C && second == 0) g.C[off + q] = v[q];
+      }
+    } else if (row_in) {
+      float out2[Q];
+      if (epi == EPI_FORWARD) {
+#pragma unroll 1
+        for (int q = 0; q < Q; ++q) {              // rolled: the activation code is long
+          const float z = v[q] + aux[q];
+          out2[q] = act_deriv(g.act, z);
+          v[q] = act_value(g.act, z);
+        }
+      } else if (epi == EPI_BIAS) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) v[q] += aux[q];
+      } else if (epi == EPI_MASK) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) v[q] *= aux[q];
+      }
+      typedef float fq __attribute__((ext_vector_type(Q)));
+      const bool vec_c = all_in && g.C && ((reinterpret_cast<uintptr_t>(g.C + off) & (4 * Q - 1)) == 0);
+      const bool vec_c2 = all_in && (epi == EPI_FORWARD) &&
+                          ((reinterpret_cast<uintptr_t>(g.C2 + off) & (4 * Q - 1)) == 0);
+      if (epi == EPI_FORWARD) {
+        if (vec_c2) {
+          fq o2;
+#pragma unroll
+          for (int q = 0; q < Q; ++q) o2[q] = out2[q];
+          *reinterpret_cast<fq *>(g.C2 + off) = o2;
+        } else {
+#pragma unroll
+          for (int q = 0; q < Q; ++q)
+            if (nn + q < N) g.C2[off + q] = out2[q];
+        }
+      }
+      if (g.C) {
+        if (vec_c) {
+          fq o1;
+#pragma unroll
+          for (int q = 0; q < Q; ++q) o1[q] = v[q];
+          if (g.streaming)
+            __builtin_nontemporal_store(o1, reinterpret_cast<fq *>(g.C + off));
+          else
+            *reinterpret_cast<fq *>(g.C + off) = o1;
+        } else {
+#pragma unroll
+          for (int q = 0; q < Q; ++q)
+            if (nn + q < N) g.C[off + q] = v[q];
+        }
+      }
+    }
   }
 
   if (epi == EPI_HEAD) {
@@ -341,13 +405,12 @@ hipError_t launch_nw(const GemmArgs &g, hipStream_t stream) {
 
 template <int AMODE, bool WKN>
 hipError_t launch_mode(const GemmArgs &g, hipStream_t stream) {
-  // enough waves that each handles about four k-slices, at most eight
+  // eight waves once each gets about four k-slices, else four (the epilogue wants at least 256
+  // threads on the 1024 outputs of a tile; with a short contraction some waves only help there)
   const int kslice = (AMODE == A_F32) ? 8 : 16;
   const int slices = (g.K + kslice - 1) / kslice;
   if (slices >= 32) return launch_nw<AMODE, WKN, 8>(g, stream);
-  if (slices >= 16) return launch_nw<AMODE, WKN, 4>(g, stream);
-  if (slices >= 8) return launch_nw<AMODE, WKN, 2>(g, stream);
-  return launch_nw<AMODE, WKN, 1>(g, stream);
+  return launch_nw<AMODE, WKN, 4>(g, stream);
 }
 
 }  // namespace
