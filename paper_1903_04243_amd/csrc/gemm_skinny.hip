@@ -189,6 +189,42 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
     }
   };
 
+  // Epilogue assignment: each thread finishes Q consecutive columns of one row.  What it needs
+  // from global memory for that (bias or mask values) does not depend on the product, so it is
+  // requested here, before the contraction, and has arrived by the time it is used.
+  constexpr int Q = 1024 / NT;                    // 4 (NW = 4) or 2 (NW = 8)
+  static_assert(Q == 2 || Q == 4, "the epilogue expects 256 or 512 threads");
+  const int row = tid / (32 / Q), col = (tid % (32 / Q)) * Q;
+  const int m = m0 + row, nn = n0 + col;
+  const bool row_in = m < M;
+  const bool all_in = row_in && (nn + Q <= N);
+  const int64_t off = (int64_t)m * g.ldc + nn;
+  const bool want_bias = (epi == EPI_BIAS || epi == EPI_FORWARD || epi == EPI_HEAD) && g.bias;
+  float aux[Q];                                  // bias (added) or mask (multiplied)
+#pragma unroll
+  for (int q = 0; q < Q; ++q) aux[q] = (epi == EPI_MASK) ? 1.f : 0.f;
+  if (row_in) {
+    if (want_bias) {
+#pragma unroll
+      for (int q = 0; q < Q; ++q)
+        if (nn + q < N)
+          aux[q] = g.bf16 ? (float)static_cast<const __bf16 *>(g.bias)[nn + q]
+                          : static_cast<const float *>(g.bias)[nn + q];
+    } else if (epi == EPI_MASK) {
+      const float *mp = g.emask + (int64_t)(m / g.S) * g.ld_emask + nn;
+      if (all_in && ((reinterpret_cast<uintptr_t>(mp) & (4 * Q - 1)) == 0)) {
+        typedef float fq __attribute__((ext_vector_type(Q)));
+        const fq mv = *reinterpret_cast<const fq *>(mp);
+#pragma unroll
+        for (int q = 0; q < Q; ++q) aux[q] = mv[q];
+      } else {
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+          if (nn + q < N) aux[q] = mp[q];
+      }
+    }
+  }
+
   f32x16 acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -237,11 +273,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   // the bias / mask values it needs in one go (a vector load when alignment allows) and writes
   // its Q results, again as one vector when possible.  One pass, no loop: with so few waves the
   // latency of every dependent global access counts.
-  constexpr int Q = 1024 / NT;                    // 4 (NW = 4) or 2 (NW = 8)
-  static_assert(Q == 2 || Q == 4, "the epilogue expects 256 or 512 threads");
   {
-    const int row = tid / (32 / Q), col = (tid % (32 / Q)) * Q;
-    const int m = m0 + row, nn = n0 + col;
     float v[Q];
 #pragma unroll
     for (int q = 0; q < Q; ++q) v[q] = 0.f;
@@ -249,34 +281,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
     for (int w = 0; w < NW; ++w)
 #pragma unroll
       for (int q = 0; q < Q; ++q) v[q] += red[w][row][col + q];
-    const bool row_in = m < M;
-    const bool all_in = row_in && (nn + Q <= N);
-    const int64_t off = (int64_t)m * g.ldc + nn;
-    const bool want_bias = (epi == EPI_BIAS || epi == EPI_FORWARD || epi == EPI_HEAD) && g.bias;
-    float aux[Q];                                  // bias (added) or mask (multiplied)
-#pragma unroll
-    for (int q = 0; q < Q; ++q) aux[q] = (epi == EPI_MASK) ? 1.f : 0.f;
-    if (row_in) {
-      if (want_bias) {
-#pragma unroll
-        for (int q = 0; q < Q; ++q)
-          if (nn + q < N)
-            aux[q] = g.bf16 ? (float)static_cast<const __bf16 *>(g.bias)[nn + q]
-                            : static_cast<const float *>(g.bias)[nn + q];
-      } else if (epi == EPI_MASK) {
-        const float *mp = g.emask + (int64_t)(m / g.S) * g.ld_emask + nn;
-        if (all_in && ((reinterpret_cast<uintptr_t>(mp) & (4 * Q - 1)) == 0)) {
-          typedef float fq __attribute__((ext_vector_type(Q)));
-          const fq mv = *reinterpret_cast<const fq *>(mp);
-#pragma unroll
-          for (int q = 0; q < Q; ++q) aux[q] = mv[q];
-        } else {
-#pragma unroll
-          for (int q = 0; q < Q; ++q)
-            if (nn + q < N) aux[q] = mp[q];
-        }
-      }
-    }
     if (epi == EPI_HEAD) {
       // keep the biased logits in LDS for the softmax pass below
 #pragma unroll
