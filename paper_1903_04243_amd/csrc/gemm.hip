@@ -49,11 +49,16 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
   const int wm = (wave >> 1) * (32 * TM);
   const int wn = (wave & 1) * (32 * TN);
 
-  // Workgroup -> tile.  Consecutive workgroup ids walk down M first, so that the workgroups
-  // resident at one time share a narrow band of W columns.
+  // Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Give
+  // every XCD a contiguous run of tiles that walks the N tiles of one M tile before moving on, so
+  // that a band of A rows is fetched into one L2 once and reused there for all its N tiles.
   const int tiles_m = (g.M + BM - 1) / BM;
-  const int tile_m = blockIdx.x % tiles_m;
-  const int tile_n = blockIdx.x / tiles_m;
+  const int tiles_n = (g.N + BN - 1) / BN;
+  const int total = tiles_m * tiles_n;
+  int t = blockIdx.x;
+  if (total % 8 == 0) t = (t % 8) * (total / 8) + t / 8;
+  const int tile_m = t / tiles_n;
+  const int tile_n = t % tiles_n;
   const int m0 = tile_m * BM;
   const int n0 = tile_n * BN;
   const int M = g.M, N = g.N, K = g.K;
