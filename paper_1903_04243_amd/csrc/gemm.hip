@@ -23,17 +23,17 @@ namespace {
 
 using namespace dev;
 
-constexpr int kThreads = 256;
-
-template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST>
-__global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
+// WGM x WGN: arrangement of the workgroup's waves over the tile (2 x 2, or 4 x 2 for the largest).
+template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) {
+  constexpr int kThreads = 64 * WGM * WGN;
   constexpr bool BF16 = (AMODE != A_F32);
   constexpr int ELEM = BF16 ? 2 : 4;
   constexpr int EPC = 16 / ELEM;            // elements per 16-byte chunk
   constexpr int BK = BKB / ELEM;            // k elements per stage
   constexpr int CPR = BKB / 16;             // chunks per LDS row
   constexpr int STRIDE = BKB + 16;          // LDS row stride in bytes
-  constexpr int BM = 64 * TM, BN = 64 * TN;
+  constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
   constexpr int A_CHUNKS = BM * CPR / kThreads;
   constexpr int W_CHUNKS = BN * CPR / kThreads;
   constexpr int STAGE = (BM + BN) * STRIDE;
@@ -46,8 +46,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
   const int wave = tid >> 6;
   const int half = lane >> 5;
   const int l32 = lane & 31;
-  const int wm = (wave >> 1) * (32 * TM);
-  const int wn = (wave & 1) * (32 * TN);
+  const int wm = (wave / WGN) * (32 * TM);
+  const int wn = (wave % WGN) * (32 * TN);
 
   // Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Give
   // every XCD a contiguous run of tiles that walks the N tiles of one M tile before moving on, so
@@ -382,11 +382,12 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const GemmArgs g) {
   }
 }
 
-template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST>
+template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2>
 hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
-  constexpr int BM = 64 * TM, BN = 64 * TN;
+  constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
+  constexpr int kThreads = 64 * WGM * WGN;
   constexpr int smem = 2 * (BM + BN) * (BKB + 16);
-  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB, FAST>;
+  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB, FAST, WGM, WGN>;
   static bool attr_set = false;   // benign race: the attribute is idempotent
   if (!attr_set && smem > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -405,6 +406,8 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
   // 64 x 64 tiles, so that small-batch products (M = B) spread over more units.
   const int64_t big = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
   const bool fast = fast_loads_ok(g);
+  // (256 x 128 tiles on 8 waves were measured slower than 128 x 128 on 4: 4.82 against 4.46 ms
+  // on the 65536 x 2048 x 2048 cotangent product; the wider barrier costs more than the saved loads)
   if (big >= 256)
     return fast ? launch_one<AMODE, WKN, 2, 2, 128, true>(g, stream)
                 : launch_one<AMODE, WKN, 2, 2, 128, false>(g, stream);
