@@ -36,7 +36,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
   constexpr int A_CHUNKS = BM * CPR / kThreads;
   constexpr int W_CHUNKS = BN * CPR / kThreads;
-  constexpr int STAGE = (BM + BN) * STRIDE;
+  // bf16 weights in [K, N] layout (forward) stay in that layout in LDS, rows of BN values, and
+  // are transposed on the way to the MFMA registers by ds_read_b64_tr_b16
+  constexpr bool WTR = WKN && BF16;
+  constexpr int W_STRIDE = WTR ? BN * 2 + 16 : STRIDE;
+  constexpr int W_ROWS = WTR ? BK : BN;
+  constexpr int STAGE = BM * STRIDE + W_ROWS * W_STRIDE;
   static_assert(BM * CPR % kThreads == 0 && BN * CPR % kThreads == 0, "tile / thread mismatch");
 
   extern __shared__ __align__(16) unsigned char smem[];
@@ -122,6 +127,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
         else
           w_row[c] = static_cast<const float *>(g.W) + (int64_t)nc * g.ldw;
       }
+    } else if constexpr (WTR) {
+      constexpr int NGR = BN / 8;                  // 16-byte pieces per tile row
+      const int kl = id / NGR, ng = id % NGR;      // consecutive lanes: consecutive pieces of a row
+      w_k[c] = kl;
+      w_n[c] = n0 + ng * 8;
+      w_lds[c] = kl * W_STRIDE + ng * 16;
+      w_row[c] = nullptr;
     } else {
       const int kl = id % BK, ng = id / BK;
       w_k[c] = kl;
@@ -187,7 +199,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
       const bool past = WKN ? (kbase + w_k[c] >= K || w_n[c] >= N) : (kbase + w_k[c] >= K);
       if (past) rw[c] = u32x4{0u, 0u, 0u, 0u};
     }
-    if constexpr (!WKN) {
+    if constexpr (!WKN || WTR) {
       *reinterpret_cast<u32x4 *>(sW + w_lds[c]) = rw[c];
     } else if constexpr (BF16) {
 #pragma unroll
@@ -239,9 +251,31 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
 #pragma unroll
       for (int i = 0; i < TM; ++i)
         av[i] = *reinterpret_cast<const u32x4 *>(sA + i * 32 * STRIDE + step * 32);
+      if constexpr (WTR) {
+        // Transposing read: in each group of 16 lanes, lane i passes the address of 4 values of
+        // tile row (i / 4) at columns 4 (i % 4) .. +3, and lane j gets back column j of those four
+        // rows.  Two reads (k .. k+3, k+4 .. k+7) give a lane its 8 consecutive k of column
+        // wn + 32 j + lane % 32; lanes 32..63 take the upper 8 k of the 16-wide slab.
+        typedef short s16x4 __attribute__((ext_vector_type(4)));
+        typedef __attribute__((address_space(3))) s16x4 *lds_s16x4;
+        const int i16 = lane & 15;
+        const unsigned char *base = smem + buf * STAGE + BM * STRIDE +
+                                    (step * 16 + half * 8 + (i16 >> 2)) * W_STRIDE +
+                                    (wn + ((lane >> 4) & 1) * 16 + (i16 & 3) * 4) * 2;
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        wv[j] = *reinterpret_cast<const u32x4 *>(sW + j * 32 * STRIDE + step * 32);
+        for (int j = 0; j < TN; ++j) {
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(base + j * 64));
+          const s16x4 hi =
+              __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(base + j * 64 + 4 * W_STRIDE));
+          typedef short s16x8 __attribute__((ext_vector_type(8)));
+          const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          wv[j] = __builtin_bit_cast(u32x4, both);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          wv[j] = *reinterpret_cast<const u32x4 *>(sW + j * 32 * STRIDE + step * 32);
+      }
       if constexpr (BF16) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -386,7 +420,9 @@ template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, 
 hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
   constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
   constexpr int kThreads = 64 * WGM * WGN;
-  constexpr int smem = 2 * (BM + BN) * (BKB + 16);
+  constexpr bool WTR = WKN && (AMODE != A_F32);
+  constexpr int BK = BKB / (AMODE != A_F32 ? 2 : 4);
+  constexpr int smem = 2 * (BM * (BKB + 16) + (WTR ? BK * (BN * 2 + 16) : BN * (BKB + 16)));
   auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB, FAST, WGM, WGN>;
   static bool attr_set = false;   // benign race: the attribute is idempotent
   if (!attr_set && smem > 48 * 1024) {
