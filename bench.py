@@ -204,10 +204,38 @@ def main():
             except Exception as e:  # graph capture is optional; eager timing stands
                 log(f"[bench] {name}: graph replay not measured ({e})")
         kt = kernel_times(step, steps)
+        # one isolated call at a time (synchronised before and after), median of 15
+        singles = []
+        for _ in range(15):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            step()
+            torch.cuda.synchronize()
+            singles.append(time.perf_counter() - t0)
+        single_ms = sorted(singles)[len(singles) // 2] * 1e3
+        # the small products (M = B rows): flops and weight bytes against both peaks
+        d, B, S = w.dims, w.B, w.S
+        elem = 2 if w.dtype == "bf16" else 4
+        last = len(d) - 1
+        fwd_layers = range(1, last) if w.call == "jacobian_input" else range(1, last + 1)
+        fwd_flops = sum(2 * B * d[l - 1] * d[l] for l in fwd_layers)
+        fwd_bytes = sum(elem * d[l - 1] * d[l] for l in fwd_layers)
+        gemm_report = {}
+        for fam, flops, nbytes in (("gemm_forward", fwd_flops, fwd_bytes),):
+            if fam in kt and kt[fam]["ms_per_step"] > 0:
+                sec_f = kt[fam]["ms_per_step"] * 1e-3
+                tf, gbs = flops / sec_f / 1e12, nbytes / sec_f / 1e9
+                gemm_report[fam] = {
+                    "flops_per_step": flops, "TFLOP/s": tf,
+                    "mfma_frac": tf / MFMA_PEAK_TFLOPS[w.dtype], "weight_bytes_per_step": nbytes,
+                    "GB/s": gbs, "hbm_frac": gbs / HBM_PEAK_GBS,
+                    "bound": "launch and memory latency (M = B rows: neither roofline is near)"
+                    if max(tf / MFMA_PEAK_TFLOPS[w.dtype], gbs / HBM_PEAK_GBS) < 0.25 else "see fractions"}
         values = wl.output_values(w)
         rec = {
             "workload": name, "call": w.call, "dims": list(w.dims), "act": w.act, "dtype": w.dtype,
             "B": w.B, "S": w.S, "steps": steps, "ms_per_step": sec * 1e3,
+            "ms_single_call": single_ms, "small_products": gemm_report,
             "ms_per_step_graph_replay": None if sec_graph is None else sec_graph * 1e3,
             "output_values": values, "output_GB": values * 4 / 1e9,
             "kernels": kt, "roofline": roofline(w, kt),
@@ -249,7 +277,7 @@ def main():
         log("[bench] cpu_baseline: float64 oracle on the same batch")
         oracle.per_example_grads(onet, inp.X[:8], inp.labels[:8])     # load / page in
         passes, t_cpu = 0, 0.0
-        while passes < 3 or (t_cpu < 4.0 and passes < 40):
+        while passes < 3 or (t_cpu < 12.0 and passes < 2000):
             t0 = time.perf_counter()
             oracle.per_example_grads(onet, inp.X, inp.labels)
             t_cpu += time.perf_counter() - t0
@@ -280,6 +308,7 @@ def main():
                    "batch": w.B, "output_GB_per_step": rec["output_GB"]},
         "roofline": rec["roofline"], "cpu_baseline": cpu,
         "ms_per_step_graph_replay": rec["ms_per_step_graph_replay"],
+        "ms_single_call": rec["ms_single_call"], "small_products": rec["small_products"],
         "kernels": rec["kernels"], "other_workloads": others,
     }
     print(json.dumps(line), flush=True)
