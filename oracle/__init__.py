@@ -64,6 +64,8 @@ def _load():
         lib.pfgo_act.argtypes = [ctypes.c_int, ctypes.c_double]
         lib.pfgo_act_deriv.restype = ctypes.c_double
         lib.pfgo_act_deriv.argtypes = [ctypes.c_int, ctypes.c_double]
+        lib.pfgo_act_deriv2.restype = ctypes.c_double
+        lib.pfgo_act_deriv2.argtypes = [ctypes.c_int, ctypes.c_double]
         lib.pfgo_loss.restype = ctypes.c_double
         lib.pfgo_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -109,6 +111,10 @@ def act(name: str, z: float) -> float:
 
 def act_deriv(name: str, z: float) -> float:
     return float(_load().pfgo_act_deriv(ACT[name], float(z)))
+
+
+def act_deriv2(name: str, z: float) -> float:
+    return float(_load().pfgo_act_deriv2(ACT[name], float(z)))
 
 
 def forward(net: Net, x) -> np.ndarray:
@@ -220,6 +226,46 @@ def jacobian_weights(net: Net, X, head: str = "logits", seeds=None, S: Optional[
                                   ctypes.c_int(HEAD[head]), _dp(seeds), ctypes.c_int64(S),
                                   ctypes.c_int64(stride), _ptr_array(JW), _ptr_array(Jb))
     return JW, Jb
+
+
+def per_example_grad_norms(net: Net, X, labels):
+    """(sq_layers [B, L], norm [B]): squared gradient norm of every layer (weights plus the bias,
+    where the layer has one) and the norm over all parameters, for each example's own loss."""
+    X = _f64(X)
+    B = X.shape[0]
+    assert X.shape == (B, net.dims[0])
+    labels = np.ascontiguousarray(np.asarray(labels, dtype=np.int32))
+    assert labels.shape == (B,) and labels.min(initial=0) >= 0 and labels.max(initial=0) < net.dims[-1]
+    sq = np.empty((B, net.L))
+    norm = np.empty(B)
+    _load().pfgo_per_example_grad_norms(ctypes.byref(net.c), _dp(X),
+                                        labels.ctypes.data_as(_c_int32_p), ctypes.c_int64(B),
+                                        _dp(sq), _dp(norm))
+    return sq, norm
+
+
+def body_hessian_input_dir(net: Net, x, seed_row, j: int) -> np.ndarray:
+    """One iteration of the Hessian parfor: d J[s, :] / d x[j] for one example and one seed row."""
+    x = _f64(x)
+    seed_row = _f64(seed_row)
+    assert x.shape == (net.dims[0],) and seed_row.shape == (net.dims[-1],)
+    assert 0 <= int(j) < net.dims[0]
+    col = np.empty(net.dims[0])
+    _load().pfgo_body_hessian_input_dir(ctypes.byref(net.c), _dp(x), _dp(seed_row),
+                                        ctypes.c_int(int(j)), _dp(col))
+    return col
+
+
+def hessian_input(net: Net, X, seeds=None, S: Optional[int] = None) -> np.ndarray:
+    """H[b, s, i, j] = d^2 <seed row s, y_b> / d x_b[i] d x_b[j], as [B, S, d_0, d_0]."""
+    X = _f64(X)
+    B = X.shape[0]
+    assert X.shape == (B, net.dims[0])
+    seeds, S, stride = _seed_args(net, B, seeds, S)
+    H = np.empty((B, S, net.dims[0], net.dims[0]))
+    _load().pfgo_hessian_input(ctypes.byref(net.c), _dp(X), ctypes.c_int64(B), _dp(seeds),
+                               ctypes.c_int64(S), ctypes.c_int64(stride), _dp(H))
+    return H
 
 
 def softmax_jacobian_row(y, k: int) -> np.ndarray:

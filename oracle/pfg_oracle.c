@@ -73,6 +73,20 @@ double pfgo_act_deriv(int act, double z) {
   }
 }
 
+/* phi''(z).  ReLU and the identity are piecewise linear: 0 everywhere (the kink of ReLU at 0
+ * is given 0, consistent with phi'(0) := 0).  tanh'' = -2 tanh (1 - tanh^2).
+ * GELU: d/dz [Phi(z) + z pdf(z)] = pdf(z) + pdf(z) - z^2 pdf(z) = pdf(z) (2 - z^2). */
+double pfgo_act_deriv2(int act, double z) {
+  switch (act) {
+    case PFGO_ACT_TANH: { double t = tanh(z); return -2.0 * t * (1.0 - t * t); }
+    case PFGO_ACT_GELU: {
+      double pdf = exp(-0.5 * z * z) / sqrt(2.0 * PFGO_PI);
+      return pdf * (2.0 - z * z);
+    }
+    default: return 0.0;
+  }
+}
+
 int pfgo_num_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();
@@ -321,6 +335,150 @@ void pfgo_jacobian_weights(const pfgo_net *net, const double *X, int64_t B, int 
     }
     free(row); free(g); free(srow); free(JWi); free(Jbi);
     tape_free(net, t);
+  }
+}
+
+/* ---------------------------------------------------------------------------------------
+ * Per-example gradient norms (the use Section 5.3 motivates: a statistic of each example's own
+ * gradient).  Written as the definition: materialise example b's gradient with the Section 5.3
+ * body, then sum the squares of all of its entries.
+ *   sq_layers[l-1] = sum_ij (d ell / d W_l[i,j])^2 + sum_j (d ell / d b_l[j])^2
+ *   norm           = sqrt(sum_l sq_layers[l-1])
+ * The bias of a layer counts only if that layer has a bias (a NULL bias is not a parameter).
+ * ------------------------------------------------------------------------------------- */
+void pfgo_body_grad_norm(const pfgo_net *net, const double *x, int label, double *sq_layers,
+                         double *norm) {
+  const int L = net->L;
+  double **dW = (double **)calloc((size_t)L, sizeof(double *));
+  double **db = (double **)calloc((size_t)L, sizeof(double *));
+  for (int l = 1; l <= L; ++l) {
+    dW[l - 1] = (double *)malloc(sizeof(double) * (size_t)net->dims[l - 1] * net->dims[l]);
+    db[l - 1] = (double *)malloc(sizeof(double) * (size_t)net->dims[l]);
+  }
+  pfgo_body_per_example_grads(net, x, label, dW, db, NULL);
+  double total = 0.0;
+  for (int l = 1; l <= L; ++l) {
+    const size_t nW = (size_t)net->dims[l - 1] * net->dims[l];
+    double sq = 0.0;
+    for (size_t e = 0; e < nW; ++e) sq += dW[l - 1][e] * dW[l - 1][e];
+    if (net->b && net->b[l - 1])
+      for (int j = 0; j < net->dims[l]; ++j) sq += db[l - 1][j] * db[l - 1][j];
+    if (sq_layers) sq_layers[l - 1] = sq;
+    total += sq;
+    free(dW[l - 1]); free(db[l - 1]);
+  }
+  if (norm) *norm = sqrt(total);
+  free(dW); free(db);
+}
+
+/* pfor(body, B): sq_layers is [B, L] (or NULL), norm is [B]. */
+void pfgo_per_example_grad_norms(const pfgo_net *net, const double *X, const int32_t *labels,
+                                 int64_t B, double *sq_layers, double *norm) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < B; ++i)
+    pfgo_body_grad_norm(net, X + (size_t)i * net->dims[0], labels[i],
+                        sq_layers ? sq_layers + (size_t)i * net->L : NULL, norm ? norm + i : NULL);
+}
+
+/* ---------------------------------------------------------------------------------------
+ * Hessians as the Jacobian of a Jacobian (Section 5.1): every scalar J[s, i] of the input
+ * Jacobian is differentiated once more with respect to x,
+ *      H[s, i, j] = d J[s, i] / d x[j],      J[s, i] = d <seed row s, y> / d x[i].
+ * The body below handles ONE seed row and ONE direction j: it carries, next to every quantity
+ * of the forward pass and of the reverse sweep that computes the Jacobian row, that quantity's
+ * derivative along x[j] (written with a leading "d"), by the product and chain rules:
+ *   forward   a_0 = x              da_0 = e_j
+ *             z_l = a_{l-1} W_l    dz_l = da_{l-1} W_l
+ *             a_l = phi(z_l)       da_l = phi'(z_l) dz_l
+ *   reverse   g_L = seed           dg_L = 0
+ *             h_{l-1} = g_l W_l^T  dh_{l-1} = dg_l W_l^T
+ *             g_{l-1} = h_{l-1} phi'(z_{l-1})
+ *             dg_{l-1} = dh_{l-1} phi'(z_{l-1}) + h_{l-1} phi''(z_{l-1}) dz_{l-1}
+ *   J row = h_0, so column j of this seed row's Hessian is dh_0.
+ * ------------------------------------------------------------------------------------- */
+void pfgo_body_hessian_input_dir(const pfgo_net *net, const double *x, const double *seed_row,
+                                 int j, double *col) {
+  const int L = net->L;
+  pfgo_tape t = tape_alloc(net);
+  forward_one(net, x, t);
+  /* derivative of the forward pass along x[j] */
+  double **dz = (double **)malloc(sizeof(double *) * (size_t)L);
+  double **da = (double **)malloc(sizeof(double *) * (size_t)L);
+  for (int l = 1; l <= L; ++l) {
+    const int din = net->dims[l - 1], dout = net->dims[l];
+    const double *W = net->W[l - 1];
+    dz[l - 1] = (double *)malloc(sizeof(double) * (size_t)dout);
+    da[l - 1] = (double *)malloc(sizeof(double) * (size_t)dout);
+    for (int c = 0; c < dout; ++c) {
+      double s = 0.0;
+      for (int i = 0; i < din; ++i) {
+        const double dprev = (l == 1) ? (i == j ? 1.0 : 0.0) : da[l - 2][i];
+        s += dprev * W[(size_t)i * dout + c];
+      }
+      dz[l - 1][c] = s;
+      da[l - 1][c] = (l < L) ? pfgo_act_deriv(net->act, t.z[l - 1][c]) * s : s;
+    }
+  }
+  /* reverse sweep and its derivative */
+  int maxd = 0;
+  for (int l = 0; l <= L; ++l) if (net->dims[l] > maxd) maxd = net->dims[l];
+  double *g = (double *)malloc(sizeof(double) * (size_t)maxd);
+  double *dg = (double *)malloc(sizeof(double) * (size_t)maxd);
+  double *gp = (double *)malloc(sizeof(double) * (size_t)maxd);
+  double *dgp = (double *)malloc(sizeof(double) * (size_t)maxd);
+  for (int c = 0; c < net->dims[L]; ++c) { g[c] = seed_row[c]; dg[c] = 0.0; }
+  for (int l = L; l >= 1; --l) {
+    const int din = net->dims[l - 1], dout = net->dims[l];
+    const double *W = net->W[l - 1];
+    for (int i = 0; i < din; ++i) {
+      double h = 0.0, dh = 0.0;
+      for (int c = 0; c < dout; ++c) {
+        h += g[c] * W[(size_t)i * dout + c];
+        dh += dg[c] * W[(size_t)i * dout + c];
+      }
+      if (l > 1) {
+        const double zi = t.z[l - 2][i];
+        gp[i] = h * pfgo_act_deriv(net->act, zi);
+        dgp[i] = dh * pfgo_act_deriv(net->act, zi) + h * pfgo_act_deriv2(net->act, zi) * dz[l - 2][i];
+      } else {
+        gp[i] = h;
+        dgp[i] = dh;
+      }
+    }
+    double *tmp = g; g = gp; gp = tmp;
+    tmp = dg; dg = dgp; dgp = tmp;
+  }
+  memcpy(col, dg, sizeof(double) * (size_t)net->dims[0]);
+  for (int l = 1; l <= L; ++l) { free(dz[l - 1]); free(da[l - 1]); }
+  free(dz); free(da); free(g); free(dg); free(gp); free(dgp);
+  tape_free(net, t);
+}
+
+/* Nested pfor over examples b, seed rows s and directions j.  H is [B, S, d_0, d_0] with
+ * H[b, s, i, j] = d J[b, s, i] / d x_b[j].  Seeds as for pfgo_jacobian_input. */
+void pfgo_hessian_input(const pfgo_net *net, const double *X, int64_t B, const double *seeds,
+                        int64_t S, int64_t seed_batch_stride, double *H) {
+  const int d0 = net->dims[0], dL = net->dims[net->L];
+#pragma omp parallel for schedule(static) collapse(2)
+  for (int64_t b = 0; b < B; ++b) {
+    for (int64_t s = 0; s < S; ++s) {
+      const double *x = X + (size_t)b * d0;
+      double *e = (double *)malloc(sizeof(double) * (size_t)dL);
+      double *col = (double *)malloc(sizeof(double) * (size_t)d0);
+      const double *row;
+      if (seeds) {
+        row = seeds + (size_t)b * seed_batch_stride + (size_t)s * dL;
+      } else {
+        for (int c = 0; c < dL; ++c) e[c] = (c == s) ? 1.0 : 0.0;
+        row = e;
+      }
+      double *Hbs = H + ((size_t)b * S + s) * d0 * d0;
+      for (int j = 0; j < d0; ++j) {
+        pfgo_body_hessian_input_dir(net, x, row, j, col);
+        for (int i = 0; i < d0; ++i) Hbs[(size_t)i * d0 + j] = col[i];
+      }
+      free(e); free(col);
+    }
   }
 }
 

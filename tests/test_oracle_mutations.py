@@ -44,6 +44,27 @@ MUTANTS = [
      "dWi[l - 1] = dW[l - 1] + (size_t)i * net->dims[l - 1] * net->dims[l];",
      "dWi[l - 1] = dW[l - 1] + (size_t)(B - 1 - i) * net->dims[l - 1] * net->dims[l];"),
     ("loss_not_log", "if (loss) *loss = -log(p[label]);", "if (loss) *loss = -p[label];"),
+    ("norm_bias_always_counted", "if (net->b && net->b[l - 1])\n      for (int j = 0; j < net->dims[l]; ++j) sq +=",
+     "for (int j = 0; j < net->dims[l]; ++j) sq +="),
+    ("norm_bias_never_counted", "sq += db[l - 1][j] * db[l - 1][j];", ";"),
+    ("norm_not_rooted", "if (norm) *norm = sqrt(total);", "if (norm) *norm = total;"),
+    ("norm_abs_instead_of_square", "sq += dW[l - 1][e] * dW[l - 1][e];", "sq += fabs(dW[l - 1][e]);"),
+    ("tanh_second_deriv_sign", "return -2.0 * t * (1.0 - t * t);", "return 2.0 * t * (1.0 - t * t);"),
+    ("gelu_second_deriv_constant", "return pdf * (2.0 - z * z);", "return pdf * (1.0 - z * z);"),
+    ("hessian_curvature_term_dropped",
+     "dgp[i] = dh * pfgo_act_deriv(net->act, zi) + h * pfgo_act_deriv2(net->act, zi) * dz[l - 2][i];",
+     "dgp[i] = dh * pfgo_act_deriv(net->act, zi);"),
+    ("hessian_curvature_uses_masked_cotangent",
+     "h * pfgo_act_deriv2(net->act, zi) * dz[l - 2][i];",
+     "gp[i] * pfgo_act_deriv2(net->act, zi) * dz[l - 2][i];"),
+    ("hessian_tangent_of_activation", "da[l - 1][c] = (l < L) ? pfgo_act_deriv(net->act, t.z[l - 1][c]) * s : s;",
+     "da[l - 1][c] = s;"),
+    ("hessian_tangent_mask_dropped_in_reverse", "dgp[i] = dh * pfgo_act_deriv(net->act, zi) +",
+     "dgp[i] = dh +"),
+    ("hessian_direction_ignored", "(i == j ? 1.0 : 0.0) : da[l - 2][i];",
+     "(i == 0 ? 1.0 : 0.0) : da[l - 2][i];"),
+    ("hessian_seed_stacking", "double *Hbs = H + ((size_t)b * S + s) * d0 * d0;",
+     "double *Hbs = H + ((size_t)s * B + b) * d0 * d0;"),
 ]
 
 

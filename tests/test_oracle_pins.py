@@ -527,3 +527,190 @@ def test_skipped_outputs_do_not_change_the_rest(oracle):
     JWf, _ = oracle.jacobian_weights(net, X, head="softmax")
     assert JW[1] is None
     np.testing.assert_array_equal(JW[0], JWf[0])
+
+
+# --------------------------------------------------------------------------------------------
+# Per-example gradient norms.
+# --------------------------------------------------------------------------------------------
+def test_grad_norm_hand_fixture(oracle):
+    g = json.load(open(os.path.join(GOLD, "relu_2_2_2.json")))
+    p1 = 1.0 / (1.0 + math.exp(3.0))
+    net = oracle.Net([np.array(g["W1"], float), np.array(g["W2"], float)],
+                     [np.array(g["b1"], float), np.array(g["b2"], float)], g["act"])
+    sq, norm = oracle.per_example_grad_norms(net, np.array([g["x"]], float), [g["label"]])
+    np.testing.assert_allclose(sq[0], p1 * p1 * np.array(g["sq_layers_in_units_of_p1_squared"]),
+                               rtol=1e-13)
+    assert norm[0] == pytest.approx(p1 * math.sqrt(g["norm_squared_in_units_of_p1_squared"]),
+                                    rel=1e-13)
+
+
+@pytest.mark.parametrize("bias", [True, False])
+def test_grad_norm_single_linear_layer_closed_form(oracle, bias):
+    # ell = -log softmax(x W + b)[y]: d/dW = outer(x, p - e_y), d/db = p - e_y, so the squared
+    # norm is (|x|^2 + 1) |p - e_y|^2 with a bias and |x|^2 |p - e_y|^2 without
+    rng = np.random.default_rng(41)
+    net = rand_net(oracle, rng, (7, 5), "relu", bias=bias)
+    X = rng.standard_normal((6, 7))
+    labels = rng.integers(0, 5, size=6)
+    sq, norm = oracle.per_example_grad_norms(net, X, labels)
+    z = X @ net.Ws[0] + (net.bs[0] if bias else 0.0)
+    p = scipy.special.softmax(z, axis=1)
+    p[np.arange(6), labels] -= 1.0
+    want = ((X * X).sum(1) + (1.0 if bias else 0.0)) * (p * p).sum(1)
+    np.testing.assert_allclose(sq[:, 0], want, rtol=1e-12)
+    np.testing.assert_allclose(norm, np.sqrt(want), rtol=1e-12)
+
+
+@pytest.mark.parametrize("act", ACTS)
+def test_grad_norm_against_autograd_library(oracle, act):
+    rng = np.random.default_rng(42)
+    net = rand_net(oracle, rng, (6, 9, 7, 4), act)
+    net_nb = oracle.Net(net.Ws, [net.bs[0], None, net.bs[2]], act)   # middle layer without a bias
+    X = rng.standard_normal((5, 6))
+    labels = rng.integers(0, 4, size=5)
+    for n in (net, net_nb):
+        sq, norm = oracle.per_example_grad_norms(n, X, labels)
+        for b in range(5):
+            Ws = [torch.from_numpy(W).clone().requires_grad_(True) for W in n.Ws]
+            bs = [None if v is None else torch.from_numpy(v).clone().requires_grad_(True)
+                  for v in n.bs]
+            a = torch.from_numpy(X[b])
+            for l in range(n.L):
+                z = a @ Ws[l]
+                if bs[l] is not None:
+                    z = z + bs[l]
+                a = z if l == n.L - 1 else {"identity": lambda t: t, "relu": torch.relu,
+                                            "tanh": torch.tanh,
+                                            "gelu": torch.nn.functional.gelu}[act](z)
+            ell = -torch.log_softmax(a, dim=0)[int(labels[b])]
+            params = Ws + [v for v in bs if v is not None]
+            grads = torch.autograd.grad(ell, params)
+            per_layer = []
+            k = n.L
+            for l in range(n.L):
+                s = float((grads[l] ** 2).sum())
+                if bs[l] is not None:
+                    s += float((grads[k] ** 2).sum())
+                    k += 1
+                per_layer.append(s)
+            np.testing.assert_allclose(sq[b], per_layer, rtol=1e-11)
+            assert norm[b] == pytest.approx(math.sqrt(sum(per_layer)), rel=1e-11)
+
+
+def test_grad_norm_is_rank_one_product_and_permutes_with_the_batch(oracle):
+    # the gradient of a layer is the outer product of its input and its cotangent, whose squared
+    # Frobenius norm factorises; the cotangent is the bias gradient the (pinned) gradient call gives
+    rng = np.random.default_rng(43)
+    net = rand_net(oracle, rng, (5, 8, 6, 3), "tanh")
+    X = rng.standard_normal((7, 5))
+    labels = rng.integers(0, 3, size=7)
+    sq, norm = oracle.per_example_grad_norms(net, X, labels)
+    _, db, _ = oracle.per_example_grads(net, X, labels)
+    a, _ = np_forward(net, X, NP_ACT["tanh"])
+    for l in range(net.L):
+        want = ((a[l] * a[l]).sum(1) + 1.0) * (db[l] * db[l]).sum(1)
+        np.testing.assert_allclose(sq[:, l], want, rtol=1e-12)
+    perm = rng.permutation(7)
+    sq_p, norm_p = oracle.per_example_grad_norms(net, X[perm], labels[perm])
+    np.testing.assert_array_equal(sq_p, sq[perm])
+    np.testing.assert_array_equal(norm_p, norm[perm])
+
+
+# --------------------------------------------------------------------------------------------
+# Hessians (Jacobian of the Jacobian, Section 5.1).
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("act", ACTS)
+def test_activation_second_derivative_by_finite_differences(oracle, act):
+    for z in (-2.3, -0.7, -0.1, 0.4, 1.1, 2.9):
+        h = 1e-5
+        fd = (oracle.act_deriv(act, z + h) - oracle.act_deriv(act, z - h)) / (2 * h)
+        assert oracle.act_deriv2(act, z) == pytest.approx(fd, abs=1e-8)
+    assert oracle.act_deriv2("relu", 0.0) == 0.0
+    assert oracle.act_deriv2("tanh", 0.0) == 0.0
+    assert oracle.act_deriv2("gelu", 0.0) == pytest.approx(2.0 / math.sqrt(2.0 * math.pi), rel=1e-14)
+
+
+def test_hessian_hand_fixture(oracle):
+    g = json.load(open(os.path.join(GOLD, "hessian_tanh_2_1_2.json")))
+    t = math.tanh(0.5)
+    c = -2.0 * t * (1.0 - t * t)
+    net = oracle.Net([np.array(g["W1"], float), np.array(g["W2"], float)],
+                     [np.array(g["b1"], float), np.array(g["b2"], float)], g["act"])
+    H = oracle.hessian_input(net, np.array([g["x"]], float))
+    assert H.shape == (1, 2, 2, 2)
+    np.testing.assert_allclose(H[0], c * np.array(g["H_in_units_of_c"], float), rtol=1e-13)
+
+
+@pytest.mark.parametrize("act", ["tanh", "gelu"])
+def test_hessian_one_hidden_layer_closed_form(oracle, act):
+    # y_o = sum_k W2[k, o] phi(z_k) + b2[o], z = x W1 + b1:
+    # H_o = W1 diag(W2[:, o] phi''(z)) W1^T, with phi'' from library routines
+    rng = np.random.default_rng(51)
+    net = rand_net(oracle, rng, (4, 6, 3), act)
+    X = rng.standard_normal((3, 4))
+    H = oracle.hessian_input(net, X)
+    z = X @ net.Ws[0] + net.bs[0]
+    if act == "tanh":
+        d2 = -2.0 * np.tanh(z) / np.cosh(z) ** 2
+    else:
+        d2 = scipy.stats.norm.pdf(z) * (2.0 - z * z)
+    want = np.einsum("ik,bk,ko,jk->boij", net.Ws[0], d2, net.Ws[1], net.Ws[0])
+    np.testing.assert_allclose(H, want, rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("act", ["identity", "relu"])
+def test_hessian_of_piecewise_linear_net_is_zero(oracle, act):
+    rng = np.random.default_rng(52)
+    net = rand_net(oracle, rng, (4, 5, 5, 3), act)
+    H = oracle.hessian_input(net, rng.standard_normal((3, 4)))
+    assert np.all(H == 0.0)
+
+
+@pytest.mark.parametrize("act", ["tanh", "gelu"])
+def test_hessian_by_finite_differences_of_the_jacobian(oracle, act):
+    # the inner Jacobian is pinned on its own; difference it along every input direction
+    rng = np.random.default_rng(53)
+    net = rand_net(oracle, rng, (5, 7, 6, 4), act)
+    X = rng.standard_normal((2, 5))
+    seeds = rng.standard_normal((2, 3, 4))
+    H = oracle.hessian_input(net, X, seeds=seeds)
+    h = 1e-5
+    for j in range(5):
+        Xp, Xm = X.copy(), X.copy()
+        Xp[:, j] += h
+        Xm[:, j] -= h
+        fd = (oracle.jacobian_input(net, Xp, seeds=seeds) -
+              oracle.jacobian_input(net, Xm, seeds=seeds)) / (2 * h)
+        np.testing.assert_allclose(H[:, :, :, j], fd, rtol=1e-6, atol=1e-8)
+
+
+@pytest.mark.parametrize("act", ["tanh", "gelu"])
+def test_hessian_against_autograd_library(oracle, act):
+    rng = np.random.default_rng(54)
+    net = rand_net(oracle, rng, (4, 6, 5, 3), act)
+    X = rng.standard_normal((2, 4))
+    H = oracle.hessian_input(net, X)
+    for b in range(2):
+        for o in range(3):
+            f = lambda x: torch_net_forward(net, x, act)[o]
+            want = torch.autograd.functional.hessian(f, torch.from_numpy(X[b])).numpy()
+            np.testing.assert_allclose(H[b, o], want, rtol=1e-10, atol=1e-13)
+
+
+def test_hessian_symmetry_seed_linearity_and_seed_forms(oracle):
+    rng = np.random.default_rng(55)
+    net = rand_net(oracle, rng, (4, 5, 3), "tanh")
+    X = rng.standard_normal((3, 4))
+    H = oracle.hessian_input(net, X)                      # identity seeds: one per output
+    np.testing.assert_allclose(H, H.transpose(0, 1, 3, 2), rtol=1e-12, atol=1e-15)
+    shared = rng.standard_normal((2, 3))
+    Hs = oracle.hessian_input(net, X, seeds=shared)
+    np.testing.assert_allclose(Hs, np.einsum("so,boij->bsij", shared, H), rtol=1e-12, atol=1e-15)
+    tiled = np.broadcast_to(shared, (3, 2, 3)).copy()
+    np.testing.assert_array_equal(oracle.hessian_input(net, X, seeds=tiled), Hs)
+    per = rng.standard_normal((3, 2, 3))
+    Hp = oracle.hessian_input(net, X, seeds=per)
+    np.testing.assert_allclose(Hp, np.einsum("bso,boij->bsij", per, H), rtol=1e-12, atol=1e-15)
+    # one iteration of the parfor is one column of one example's Hessian
+    col = oracle.body_hessian_input_dir(net, X[1], per[1, 0], 2)
+    np.testing.assert_array_equal(col, Hp[1, 0, :, 2])
