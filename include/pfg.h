@@ -59,7 +59,13 @@ typedef enum { PFG_F32 = 0, PFG_BF16 = 1 } pfg_dtype;
  * softmax(y). */
 typedef enum { PFG_HEAD_LOGITS = 0, PFG_HEAD_SOFTMAX = 1 } pfg_head;
 
-typedef enum { PFG_OP_PER_EXAMPLE_GRADS = 0, PFG_OP_JACOBIAN_INPUT = 1, PFG_OP_JACOBIAN_WEIGHTS = 2 } pfg_op;
+typedef enum {
+  PFG_OP_PER_EXAMPLE_GRADS = 0,
+  PFG_OP_JACOBIAN_INPUT = 1,
+  PFG_OP_JACOBIAN_WEIGHTS = 2,
+  PFG_OP_GRAD_NORMS = 3,
+  PFG_OP_HESSIAN_INPUT = 4
+} pfg_op;
 
 typedef struct {
   int32_t num_layers;     /* L >= 1                                                         */
@@ -72,7 +78,7 @@ typedef struct {
 } pfg_mlp;
 
 /* Bytes of workspace the given op needs for batch B and S seed rows per example (S is ignored
- * by PFG_OP_PER_EXAMPLE_GRADS).  The figure covers the case where no optional output is given;
+ * by PFG_OP_PER_EXAMPLE_GRADS and PFG_OP_GRAD_NORMS).  The figure covers the case where no optional output is given;
  * it is a multiple of 256 and never 0.  The workspace passed to an op must be 256-byte aligned. */
 int pfg_workspace_bytes(const pfg_mlp *net, int op, int64_t B, int64_t S, size_t *bytes);
 
@@ -123,6 +129,36 @@ int pfg_jacobian_weights(const pfg_mlp *net, const void *X, int64_t B, int head,
                          const float *seeds, int64_t S, int64_t seed_batch_stride,
                          float *const *JW_out, float *const *Jb_out, void *workspace,
                          size_t workspace_bytes, void *hip_stream);
+
+/* Norms of the per-example gradients of Section 5.3 without writing the gradients out (the
+ * statistic that per-example clipping and importance weighting need).  The gradient of layer l
+ * for example b is the product of a column a_{l-1}[b, :] and a row delta_l[b, :] -- the matmul
+ * with both operands stacked (Section 3.4) and contraction length 1 -- so its squared Frobenius
+ * norm is |a_{l-1}[b]|^2 |delta_l[b]|^2 and never needs the [B, d_{l-1}, d_l] tensor:
+ *      sq_layers_out[b, l-1] = sum_ij dW_l[b,i,j]^2 + (layer l has a bias ? sum_j db_l[b,j]^2 : 0)
+ *      norm_out[b]           = sqrt(sum_l sq_layers_out[b, l-1])
+ * A layer "has a bias" when net->b and net->b[l-1] are non-NULL.
+ *   X, labels, loss_out   as for pfg_per_example_grads
+ *   sq_layers_out [B, L] or NULL;  norm_out [B] or NULL (at least one of the two is required) */
+int pfg_per_example_grad_norms(const pfg_mlp *net, const void *X, const int32_t *labels, int64_t B,
+                               float *sq_layers_out, float *norm_out, float *loss_out,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Input Hessian as the Jacobian of the Jacobian (Section 5.1 names Hessians of non-scalar outputs
+ * as a use of the nested parallel-for): every scalar of pfg_jacobian_input's result is
+ * differentiated once more with respect to the example's own input,
+ *      H_out[b, s, i, j] = d J[b, s, i] / d x_b[j] = d^2 <seed row s of example b, y_b> / d x_b[i] d x_b[j].
+ * With T_l[b] = d z_l[b] / d x_b (a [d_l, d_0] matrix, T_1 = W_1^T, T_{l+1} = W_{l+1}^T diag(phi'(z_l)) T_l)
+ * and h_l[b, s, :] the cotangent of the seed row at a_l, the result is
+ *      H[b, s] = sum_{l < L} T_l[b]^T diag(h_l[b, s, :] * phi''(z_l[b, :])) T_l[b],
+ * one batched matrix product per call (both operands depend on b).  It is identically zero for
+ * PFG_ACT_IDENTITY and PFG_ACT_RELU (phi'' = 0, also at the kink) and for L = 1.
+ *   net->dtype must be PFG_F32 (PFG_BF16 returns PFG_ERR_UNSUPPORTED)
+ *   seeds, S, seed_batch_stride   as for pfg_jacobian_input
+ *   H_out   [B, S, d_0, d_0] */
+int pfg_hessian_input(const pfg_mlp *net, const void *X, int64_t B, const float *seeds, int64_t S,
+                      int64_t seed_batch_stride, float *H_out, void *workspace,
+                      size_t workspace_bytes, void *hip_stream);
 
 /* Text of the last error on the calling thread ("" if none).  Valid until the next call into the
  * library from that thread. */

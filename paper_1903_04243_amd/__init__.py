@@ -21,10 +21,11 @@ PFG_ERR_WORKSPACE, PFG_ERR_OVERFLOW, PFG_ERR_DEVICE = -4, -5, -6
 ACT = {"identity": 0, "relu": 1, "tanh": 2, "gelu": 3}
 DTYPE = {"f32": 0, "bf16": 1}
 HEAD = {"logits": 0, "softmax": 1}
-OP = {"per_example_grads": 0, "jacobian_input": 1, "jacobian_weights": 2}
+OP = {"per_example_grads": 0, "jacobian_input": 1, "jacobian_weights": 2, "grad_norms": 3,
+      "hessian_input": 4}
 
 EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_jacobian_input",
-           "pfg_jacobian_weights", "pfg_last_error", "pfg_timing_enable", "pfg_timing_reset",
+           "pfg_jacobian_weights", "pfg_per_example_grad_norms", "pfg_hessian_input", "pfg_last_error", "pfg_timing_enable", "pfg_timing_reset",
            "pfg_timing_query", "pfg_timing_names", "pfg_version"]
 
 
@@ -64,6 +65,8 @@ def load_library() -> ctypes.CDLL:
         lib.pfg_jacobian_input.argtypes = [netp, vp, i64, vp, i64, i64, vp, vp, ctypes.c_size_t, vp]
         lib.pfg_jacobian_weights.argtypes = [netp, vp, i64, i32, vp, i64, i64, ctypes.POINTER(vp),
                                              ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
+        lib.pfg_per_example_grad_norms.argtypes = [netp, vp, vp, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.pfg_hessian_input.argtypes = [netp, vp, i64, vp, i64, i64, vp, vp, ctypes.c_size_t, vp]
         lib.pfg_last_error.restype = ctypes.c_char_p
         lib.pfg_timing_enable.argtypes = [i32]
         lib.pfg_timing_query.argtypes = [ctypes.c_char_p, ctypes.POINTER(i64),
@@ -236,6 +239,45 @@ def pfg_jacobian_weights(net: Mlp, X, head: str = "logits", seeds=None, S: Optio
         None if seeds is None else seeds.data_ptr(), S, stride, _ptrs(JW),
         _ptrs(Jb) if Jb is not None else None, workspace.data_ptr(), ws_bytes, _stream_ptr()))
     return JW, Jb
+
+
+def pfg_per_example_grad_norms(net: Mlp, X, labels, want_sq_layers: bool = True, want_norm: bool = True,
+                               want_loss: bool = True, out_sq_layers=None, out_norm=None,
+                               out_loss=None, workspace=None):
+    """Returns (sq_layers [B, L] or None, norm [B] or None, loss [B] or None): squared per-layer
+    norms and the overall norm of each example's own gradient, without forming the gradients."""
+    import torch
+    _check_x(net, X)
+    B = X.shape[0]
+    if labels.dtype != torch.int32 or tuple(labels.shape) != (B,) or not labels.is_contiguous():
+        raise ValueError("labels must be a contiguous int32 [B] tensor")
+    f32 = dict(dtype=torch.float32, device=net.device)
+    sq = out_sq_layers if out_sq_layers is not None else (
+        torch.empty((B, net.L), **f32) if want_sq_layers else None)
+    norm = out_norm if out_norm is not None else (torch.empty((B,), **f32) if want_norm else None)
+    loss = out_loss if out_loss is not None else (torch.empty((B,), **f32) if want_loss else None)
+    workspace, ws_bytes = _workspace(net, "grad_norms", B, 1, workspace)
+    _check(load_library().pfg_per_example_grad_norms(
+        ctypes.byref(net.c), X.data_ptr(), labels.data_ptr(), B,
+        None if sq is None else sq.data_ptr(), None if norm is None else norm.data_ptr(),
+        None if loss is None else loss.data_ptr(), workspace.data_ptr(), ws_bytes, _stream_ptr()))
+    return sq, norm, loss
+
+
+def pfg_hessian_input(net: Mlp, X, seeds=None, S: Optional[int] = None, out=None, workspace=None):
+    """H[b, s, i, j] = second derivative of <seed row s, y_b> with respect to x_b[i], x_b[j],
+    shape [B, S, d_0, d_0]."""
+    import torch
+    _check_x(net, X)
+    B = X.shape[0]
+    seeds, S, stride = _seed_args(net, B, seeds, S)
+    n = net.dims[0]
+    H = out if out is not None else torch.empty((B, S, n, n), dtype=torch.float32, device=net.device)
+    workspace, ws_bytes = _workspace(net, "hessian_input", B, S, workspace)
+    _check(load_library().pfg_hessian_input(
+        ctypes.byref(net.c), X.data_ptr(), B, None if seeds is None else seeds.data_ptr(), S,
+        stride, H.data_ptr(), workspace.data_ptr(), ws_bytes, _stream_ptr()))
+    return H
 
 
 def pfg_timing_enable(on: bool) -> None:

@@ -79,6 +79,11 @@ struct GemmArgs {
   //   head_gprev[m, i] = head_mask[m, i] * sum_j C2[m, j] * W[i, j]     for i < K
   float *head_gprev;        // [M, K] or nullptr
   const float *head_mask;   // [M, K]
+  // Batched product (both operands differ from one parallel-for iteration to the next): nbatch > 1
+  // runs nbatch independent products; product z uses A + z * batch_A, a_scale + z * batch_scale,
+  // W + z * batch_W (float32 weights only) and C + z * batch_C (strides in elements).  EPI_NONE only.
+  int32_t nbatch;
+  int64_t batch_A, batch_scale, batch_W, batch_C;
 };
 
 // Picks the LDS-tiled kernel or the small-problem kernel.
@@ -113,5 +118,38 @@ hipError_t launch_seed_rows(const float *y, const float *seeds, int64_t seed_bat
 // dst[c, r] = (float) src[r, c]   for an [R, C] row-major src in float32 or bf16
 hipError_t launch_transpose(const void *src, int32_t src_bf16, int32_t R, int32_t C, float *dst,
                             hipStream_t stream);
+
+// z [B, d] (pre-activations) -> a = phi(z), dphi = phi'(z), d2phi = phi''(z); any output may be null
+hipError_t launch_act_from_z(const float *z, int64_t B, int32_t d, int32_t act, float *a, float *dphi,
+                             float *d2phi, hipStream_t stream);
+
+// out[(b, s), j] = in[b * in_batch_stride + s * ld_in + j] * (mask ? mask[b * ld_mask + j] : 1)
+// for b < B, s < S, j < d; out row (b, s) starts at out + (b * S + s) * ld_out.  in may be float32
+// or bf16 (in_bf16).
+hipError_t launch_scale_rows(const void *in, int32_t in_bf16, int64_t in_batch_stride, int64_t ld_in,
+                             const float *mask, int64_t ld_mask, int64_t B, int64_t S, int32_t d,
+                             float *out, int64_t ld_out, hipStream_t stream);
+
+// Squared gradient norms of the dense layers of a launch (at most kNormLayers per launch):
+//   sq[b * ld_sq + layer] = (|a[b, :]|^2 + (has_bias ? 1 : 0)) * |g[b, :]|^2
+// and, if norm is given, norm[b] = sqrt(sum over the launch's layers) (the launch must then cover
+// every layer).  sq may be null when norm is given.
+constexpr int kNormLayers = 16;
+struct NormLayer {
+  const void *a;      // [B, d_in] float32 or bf16
+  const float *g;     // [B, d_out]
+  int32_t d_in, d_out;
+  int32_t a_bf16, has_bias;
+  int32_t index;      // column of sq
+};
+hipError_t launch_grad_sqnorms(const NormLayer *layers, int n, int64_t B, float *sq, int64_t ld_sq,
+                               float *norm, hipStream_t stream);
+
+// norm[b] = sqrt(sum_l sq[b * ld_sq + l]), l < L
+hipError_t launch_norm_finalize(const float *sq, int64_t ld_sq, int32_t L, int64_t B, float *norm,
+                                hipStream_t stream);
+
+// out[0 .. n) = 0
+hipError_t launch_fill_zero(float *out, int64_t n, hipStream_t stream);
 
 }  // namespace pfg

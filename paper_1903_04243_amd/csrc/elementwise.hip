@@ -1,8 +1,11 @@
-// Small row-wise kernels: the loss head, the seed rows of the Jacobians, and a transpose.
+// Small row-wise and element-wise kernels: the loss head, the seed rows of the Jacobians, a
+// transpose, activation derivatives from stored pre-activations, row scaling, and the squared
+// norms of rank-one gradients.
 // Each row is handled by one 64-lane wave; lanes stride over the d_L classes and combine with
 // wave reductions (Section 3.4: a reduction inside the loop body keeps reducing over its own
 // axis after vectorisation; it never reduces over the iteration index).
 #include "common.h"
+#include "gemm_device.h"
 
 namespace pfg {
 
@@ -119,7 +122,144 @@ __global__ __launch_bounds__(kThreads) void transpose_kernel(const void *src, in
   }
 }
 
+// a = phi(z), dphi = phi'(z), d2phi = phi''(z), element by element.
+__global__ __launch_bounds__(kThreads) void act_from_z_kernel(const float *z, int64_t n, int act,
+                                                              float *a, float *dphi, float *d2phi) {
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += step) {
+    const float v = z[i];
+    if (a) a[i] = dev::act_value(act, v);
+    if (dphi) dphi[i] = dev::act_deriv(act, v);
+    if (d2phi) d2phi[i] = dev::act_deriv2(act, v);
+  }
+}
+
+// out[(b, s), j] = in[b, s, j] * mask[b, j]: the mask of a layer does not depend on the inner
+// iteration index s and is broadcast over it (Section 3.4: loop-invariant operands are not stacked).
+__global__ __launch_bounds__(kThreads) void scale_rows_kernel(const void *in, int in_bf16,
+                                                              int64_t in_batch_stride, int64_t ld_in,
+                                                              const float *mask, int64_t ld_mask,
+                                                              int64_t rows, int64_t S, int d,
+                                                              float *out, int64_t ld_out) {
+  const int64_t total = rows * d;
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += step) {
+    const int64_t row = i / d;
+    const int j = (int)(i - row * d);
+    const int64_t b = row / S, s = row - b * S;
+    const int64_t at = b * in_batch_stride + s * ld_in + j;
+    float v = in_bf16 ? (float)static_cast<const __bf16 *>(in)[at] : static_cast<const float *>(in)[at];
+    if (mask) v *= mask[b * ld_mask + j];
+    out[row * ld_out + j] = v;
+  }
+}
+
+struct NormBatch {
+  NormLayer layer[kNormLayers];
+  int n;
+};
+
+// The gradient of a dense layer for one example is the outer product of the layer's input row and
+// its cotangent row (the both-operands-stacked matmul case of Section 3.4 with contraction
+// length 1), so its squared Frobenius norm is the product of the two rows' squared norms; the
+// bias gradient is the cotangent row itself.  One workgroup per example, sums in a fixed order.
+__global__ __launch_bounds__(kThreads) void grad_sqnorms_kernel(const NormBatch nb, float *sq,
+                                                                int64_t ld_sq, float *norm) {
+  __shared__ float part[2][kWavesPerBlock];
+  const int64_t b = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float total = 0.f;
+  for (int li = 0; li < nb.n; ++li) {
+    const NormLayer &ly = nb.layer[li];
+    float sa = 0.f, sg = 0.f;
+    if (ly.a_bf16) {
+      const __bf16 *a = static_cast<const __bf16 *>(ly.a) + b * ly.d_in;
+      for (int i = tid; i < ly.d_in; i += kThreads) { const float v = (float)a[i]; sa += v * v; }
+    } else {
+      const float *a = static_cast<const float *>(ly.a) + b * ly.d_in;
+      for (int i = tid; i < ly.d_in; i += kThreads) { const float v = a[i]; sa += v * v; }
+    }
+    const float *g = ly.g + b * ly.d_out;
+    for (int j = tid; j < ly.d_out; j += kThreads) { const float v = g[j]; sg += v * v; }
+    sa = wave_sum(sa);
+    sg = wave_sum(sg);
+    __syncthreads();                       // the previous layer's partial sums have been read
+    if (lane == 0) { part[0][wave] = sa; part[1][wave] = sg; }
+    __syncthreads();
+    float ta = 0.f, tg = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) { ta += part[0][w]; tg += part[1][w]; }
+    const float v = (ta + (ly.has_bias ? 1.f : 0.f)) * tg;
+    if (sq && tid == 0) sq[b * ld_sq + ly.index] = v;
+    total += v;
+  }
+  if (norm && tid == 0) norm[b] = sqrtf(total);
+}
+
+__global__ __launch_bounds__(kThreads) void norm_finalize_kernel(const float *sq, int64_t ld_sq, int L,
+                                                                 int64_t B, float *norm) {
+  const int64_t b = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (b >= B) return;
+  float total = 0.f;
+  for (int l = 0; l < L; ++l) total += sq[b * ld_sq + l];
+  norm[b] = sqrtf(total);
+}
+
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(float *out, int64_t n) {
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += step) out[i] = 0.f;
+}
+
+inline unsigned capped_blocks(int64_t work_items) {
+  const int64_t blocks = (work_items + kThreads - 1) / kThreads;
+  return (unsigned)(blocks < (1 << 20) ? blocks : (1 << 20));
+}
+
 }  // namespace
+
+hipError_t launch_act_from_z(const float *z, int64_t B, int32_t d, int32_t act, float *a, float *dphi,
+                             float *d2phi, hipStream_t stream) {
+  const int64_t n = B * d;
+  if (n <= 0) return hipSuccess;
+  PFG_KERNEL(act_from_z_kernel, dim3(capped_blocks(n)), dim3(kThreads), 0, stream, z, n, act, a, dphi,
+             d2phi);
+  return hipGetLastError();
+}
+
+hipError_t launch_scale_rows(const void *in, int32_t in_bf16, int64_t in_batch_stride, int64_t ld_in,
+                             const float *mask, int64_t ld_mask, int64_t B, int64_t S, int32_t d,
+                             float *out, int64_t ld_out, hipStream_t stream) {
+  const int64_t rows = B * S;
+  if (rows <= 0 || d <= 0) return hipSuccess;
+  PFG_KERNEL(scale_rows_kernel, dim3(capped_blocks(rows * d)), dim3(kThreads), 0, stream, in, in_bf16,
+             in_batch_stride, ld_in, mask, ld_mask, rows, S, d, out, ld_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_grad_sqnorms(const NormLayer *layers, int n, int64_t B, float *sq, int64_t ld_sq,
+                               float *norm, hipStream_t stream) {
+  if (B <= 0 || n <= 0) return hipSuccess;
+  if (n > kNormLayers || B > 0x7fffffffLL) return hipErrorInvalidValue;
+  NormBatch nb{};
+  for (int i = 0; i < n; ++i) nb.layer[i] = layers[i];
+  nb.n = n;
+  PFG_KERNEL(grad_sqnorms_kernel, dim3((unsigned)B), dim3(kThreads), 0, stream, nb, sq, ld_sq, norm);
+  return hipGetLastError();
+}
+
+hipError_t launch_norm_finalize(const float *sq, int64_t ld_sq, int32_t L, int64_t B, float *norm,
+                                hipStream_t stream) {
+  if (B <= 0) return hipSuccess;
+  PFG_KERNEL(norm_finalize_kernel, dim3((unsigned)((B + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+             stream, sq, ld_sq, L, B, norm);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(float *out, int64_t n, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  PFG_KERNEL(fill_zero_kernel, dim3(capped_blocks(n)), dim3(kThreads), 0, stream, out, n);
+  return hipGetLastError();
+}
 
 hipError_t launch_head_softmax_ce(const float *y, const int32_t *labels, int64_t B, int32_t n,
                                   float *delta, float *loss, hipStream_t stream) {

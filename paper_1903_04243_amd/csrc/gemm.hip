@@ -25,10 +25,19 @@ using namespace dev;
 
 // WGM x WGN: arrangement of the workgroup's waves over the tile (2 x 2, or 4 x 2 for the largest).
 template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) {
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs gk) {
   constexpr int kThreads = 64 * WGM * WGN;
   constexpr bool BF16 = (AMODE != A_F32);
   constexpr int ELEM = BF16 ? 2 : 4;
+  // batched product: the second grid index selects the product; its operands sit at fixed strides
+  GemmArgs g = gk;
+  if (gk.nbatch > 1) {
+    const int64_t z = blockIdx.y;
+    g.A = static_cast<const char *>(gk.A) + z * gk.batch_A * (AMODE == A_BF16 ? 2 : 4);
+    g.W = static_cast<const char *>(gk.W) + z * gk.batch_W * ELEM;
+    if (gk.a_scale) g.a_scale = gk.a_scale + z * gk.batch_scale;
+    g.C = gk.C + z * gk.batch_C;
+  }
   constexpr int EPC = 16 / ELEM;            // elements per 16-byte chunk
   constexpr int BK = BKB / ELEM;            // k elements per stage
   constexpr int CPR = BKB / 16;             // chunks per LDS row
@@ -432,7 +441,8 @@ hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
     attr_set = true;
   }
   const int64_t tiles = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  PFG_KERNEL(kern, dim3((unsigned)tiles), dim3(kThreads), smem, stream, g);
+  const unsigned nbatch = g.nbatch > 1 ? (unsigned)g.nbatch : 1u;
+  PFG_KERNEL(kern, dim3((unsigned)tiles, nbatch), dim3(kThreads), smem, stream, g);
   return hipGetLastError();
 }
 
@@ -440,7 +450,8 @@ template <int AMODE, bool WKN>
 hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
   // Large tiles once they still give the 256 compute units a full wave of workgroups; otherwise
   // 64 x 64 tiles, so that small-batch products (M = B) spread over more units.
-  const int64_t big = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
+  const int64_t nb = g.nbatch > 1 ? g.nbatch : 1;
+  const int64_t big = nb * ((g.M + 127) / 128) * ((g.N + 127) / 128);
   const bool fast = fast_loads_ok(g);
   // (256 x 128 tiles on 8 waves were measured slower than 128 x 128 on 4: 4.82 against 4.46 ms
   // on the 65536 x 2048 x 2048 cotangent product; the wider barrier costs more than the saved loads)
@@ -460,9 +471,11 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
 
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipSuccess;
+  if (g.nbatch > 1 && (g.epilogue != EPI_NONE || g.nbatch > 65535))
+    return hipErrorInvalidValue;
   // Fewer than 128 tiles of 64 x 64 cannot occupy the chip: such products (M = B rows, or a
   // narrow output) go to the kernel that splits the contraction over the waves of a workgroup.
-  const int64_t tiles64 = (int64_t)((g.M + 63) / 64) * ((g.N + 63) / 64);
+  const int64_t tiles64 = (int64_t)(g.nbatch > 1 ? g.nbatch : 1) * ((g.M + 63) / 64) * ((g.N + 63) / 64);
   if (g.epilogue == EPI_HEAD || tiles64 < 128) return launch_gemm_skinny(g, stream);
   if (!g.bf16) {
     return g.w_kn ? launch_tiles<A_F32, true>(g, stream) : launch_tiles<A_F32, false>(g, stream);

@@ -31,6 +31,15 @@ __device__ __forceinline__ float act_deriv(int act, float z) {
   }
 }
 
+// phi''(z); 0 for the piecewise-linear activations (also at the kink of ReLU)
+__device__ __forceinline__ float act_deriv2(int act, float z) {
+  switch (act) {
+    case ACT_TANH: { float t = tanhf(z); return -2.f * t * (1.f - t * t); }
+    case ACT_GELU: return 0.39894228040143267794f * __expf(-0.5f * z * z) * (2.f - z * z);
+    default: return 0.f;
+  }
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
   bf16x2 v = {(__bf16)lo, (__bf16)hi};
@@ -138,6 +147,9 @@ inline bool fast_loads_ok(const GemmArgs &g, bool check_w = true) {
   auto aligned = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
   if (!aligned(g.A) || (g.lda * a_elem) % 16 || (g.a_batch_stride * a_elem) % 16) return false;
   if (g.a_scale && (!aligned(g.a_scale) || (g.ld_scale * 4) % 16)) return false;
+  if (g.nbatch > 1 && ((g.batch_A * a_elem) % 16 || (g.batch_W * w_elem) % 16 ||
+                       (g.batch_scale * 4) % 16))
+    return false;
   if (g.K % kchunk || g.K < kchunk) return false;
   if (!check_w) return true;
   if (!aligned(g.W) || (g.ldw * w_elem) % 16) return false;

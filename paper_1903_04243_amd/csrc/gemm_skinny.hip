@@ -422,6 +422,21 @@ hipError_t launch_mode(const GemmArgs &g, hipStream_t stream) {
 hipError_t launch_gemm_skinny(const GemmArgs &g, hipStream_t stream) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipSuccess;
   if (g.epilogue == EPI_HEAD && g.N > 32) return hipErrorInvalidValue;
+  if (g.nbatch > 1) {
+    // small batched products: one launch per product (this kernel has no batch index)
+    const int a_elem = (g.bf16 && !g.a_is_f32) ? 2 : 4, w_elem = g.bf16 ? 2 : 4;
+    for (int z = 0; z < g.nbatch; ++z) {
+      GemmArgs one = g;
+      one.nbatch = 0;
+      one.A = static_cast<const char *>(g.A) + (int64_t)z * g.batch_A * a_elem;
+      one.W = static_cast<const char *>(g.W) + (int64_t)z * g.batch_W * w_elem;
+      if (g.a_scale) one.a_scale = g.a_scale + (int64_t)z * g.batch_scale;
+      one.C = g.C + (int64_t)z * g.batch_C;
+      hipError_t e = launch_gemm_skinny(one, stream);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
   if (!g.bf16)
     return g.w_kn ? launch_mode<A_F32, true>(g, stream) : launch_mode<A_F32, false>(g, stream);
   if (g.a_is_f32)

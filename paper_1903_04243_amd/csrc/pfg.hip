@@ -135,13 +135,30 @@ int check_seeds(const pfg_mlp *net, const float *seeds, int64_t S, int64_t strid
   return PFG_OK;
 }
 
+int check_hessian(const pfg_mlp *net, int64_t B, int64_t S) {
+  if (net->dtype != PFG_F32)
+    return fail(PFG_ERR_UNSUPPORTED, "the Hessian is computed in float32 only (dtype %d given)", net->dtype);
+  const int64_t n = net->dims[0];
+  int64_t ktot = 0;
+  for (int l = 1; l < net->num_layers; ++l) ktot += net->dims[l];
+  if (n * n > 0x7fffffffLL || S * n > kMaxRows || B * n > kMaxRows || ktot > 0x7fffffffLL)
+    return fail(PFG_ERR_OVERFLOW, "d_0 = %lld is too wide for B = %lld, S = %lld", (long long)n,
+                (long long)B, (long long)S);
+  if (n * n > kMaxElems / (B * S) || (ktot && B * (n > S ? n : S) > kMaxElems / ktot))
+    return fail(PFG_ERR_OVERFLOW, "B * S * d_0 * d_0 = %lld * %lld * %lld^2 values exceed the indexing limit",
+                (long long)B, (long long)S, (long long)n);
+  return PFG_OK;
+}
+
 // ------------------------------------------------------------------------------------------
 // Workspace layout.  Every block is 256-byte aligned.
 // ------------------------------------------------------------------------------------------
 struct Plan {
   size_t total = 0;
-  std::vector<size_t> act, dphi, G;   // indexed by layer l (1-based; entry 0 unused)
-  size_t logits = 0, P = 0, ping = 0, pong = 0;
+  std::vector<size_t> act, dphi, d2phi, G;   // indexed by layer l (1-based; entry 0 unused)
+  size_t logits = 0, P = 0, ping = 0, pong = 0, sq = 0, U = 0, Cc = 0;
+  int64_t ktot = 0;                   // Hessian: sum of the hidden widths
+  std::vector<int64_t> koff;          // Hessian: column offset of hidden layer l in U and Cc
   size_t take(size_t bytes) {
     const size_t at = total;
     total += (bytes + 255) / 256 * 256;
@@ -156,12 +173,29 @@ Plan make_plan(const pfg_mlp *net, int op, int64_t B, int64_t S) {
   p.act.assign(L + 1, 0);
   p.dphi.assign(L + 1, 0);
   p.G.assign(L + 1, 0);
+  p.d2phi.assign(L + 1, 0);
+  p.koff.assign(L + 1, 0);
   const int hidden_last = L - 1;
   for (int l = 1; l <= hidden_last; ++l) {
     p.act[l] = p.take(sizeof(float) * B * d[l]);
     p.dphi[l] = p.take(sizeof(float) * B * d[l]);
   }
-  if (op == PFG_OP_JACOBIAN_INPUT) {
+  if (op == PFG_OP_HESSIAN_INPUT) {
+    size_t widest = 1;
+    for (int l = 1; l <= hidden_last; ++l) {
+      p.d2phi[l] = p.take(sizeof(float) * B * d[l]);
+      p.koff[l] = p.ktot;
+      p.ktot += d[l];
+      widest = widest > (size_t)d[l] ? widest : (size_t)d[l];
+    }
+    if (hidden_last >= 1) {
+      p.U = p.take(sizeof(float) * B * d[0] * p.ktot);     // tangents [B * d_0, ktot]
+      p.Cc = p.take(sizeof(float) * B * S * p.ktot);       // curvature weights [B * S, ktot]
+      p.P = p.take(sizeof(float) * S * d[L - 1]);
+      p.ping = p.take(sizeof(float) * B * S * widest);
+      p.pong = p.take(sizeof(float) * B * S * widest);
+    }
+  } else if (op == PFG_OP_JACOBIAN_INPUT) {
     size_t widest = 0;
     for (int l = 1; l <= hidden_last; ++l) widest = widest > (size_t)d[l] ? widest : (size_t)d[l];
     // loop-invariant seed block: [S, d_{L-1}] after the first step, or the [S, d_L] identity of
@@ -174,6 +208,7 @@ Plan make_plan(const pfg_mlp *net, int op, int64_t B, int64_t S) {
     const int64_t rows = (op == PFG_OP_JACOBIAN_WEIGHTS) ? B * S : B;
     p.logits = p.take(sizeof(float) * B * d[L]);
     for (int l = 1; l <= L; ++l) p.G[l] = p.take(sizeof(float) * rows * d[l]);
+    if (op == PFG_OP_GRAD_NORMS) p.sq = p.take(sizeof(float) * B * L);
   }
   if (p.total == 0) p.total = 256;
   return p;
@@ -329,7 +364,7 @@ int weight_sweep(const pfg_mlp *net, const void *X, int64_t B, int64_t S, float 
 
 extern "C" {
 
-int pfg_version(void) { return 100; }
+int pfg_version(void) { return 101; }
 
 const char *pfg_last_error(void) { return g_err; }
 
@@ -374,11 +409,15 @@ int pfg_workspace_bytes(const pfg_mlp *net, int op, int64_t B, int64_t S, size_t
   int rc = check_net(net);
   if (rc) return rc;
   if (!bytes) return fail(PFG_ERR_NULL, "bytes is NULL");
-  if (op < PFG_OP_PER_EXAMPLE_GRADS || op > PFG_OP_JACOBIAN_WEIGHTS)
+  if (op < PFG_OP_PER_EXAMPLE_GRADS || op > PFG_OP_HESSIAN_INPUT)
     return fail(PFG_ERR_UNSUPPORTED, "unknown op %d", op);
-  if (op == PFG_OP_PER_EXAMPLE_GRADS) S = 1;
+  if (op == PFG_OP_PER_EXAMPLE_GRADS || op == PFG_OP_GRAD_NORMS) S = 1;
   if ((rc = check_rows(B, S))) return rc;
-  if ((rc = check_elems(net, B * S))) return rc;
+  if (op == PFG_OP_HESSIAN_INPUT) {
+    if ((rc = check_hessian(net, B, S))) return rc;
+  } else if ((rc = check_elems(net, B * S))) {
+    return rc;
+  }
   *bytes = make_plan(net, op, B, S).total;
   return PFG_OK;
 }
@@ -419,6 +458,194 @@ int pfg_per_example_grads(const pfg_mlp *net, const void *X, const int32_t *labe
                                               loss_out, stream));
   }
   return weight_sweep(net, X, B, 1, dW_out, db_out, G, workspace, p, stream, top_step_done);
+}
+
+int pfg_per_example_grad_norms(const pfg_mlp *net, const void *X, const int32_t *labels, int64_t B,
+                               float *sq_layers_out, float *norm_out, float *loss_out,
+                               void *workspace, size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  int rc = check_net(net);
+  if (rc) return rc;
+  if ((rc = check_weights(net))) return rc;
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
+  if (!sq_layers_out && !norm_out) return fail(PFG_ERR_NULL, "sq_layers_out and norm_out are both NULL");
+  if ((rc = check_rows(B, 1))) return rc;
+  if ((rc = check_elems(net, B))) return rc;
+  const Plan p = make_plan(net, PFG_OP_GRAD_NORMS, B, 1);
+  if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int L = net->num_layers;
+  const int32_t *d = net->dims;
+
+  std::vector<float *> G(L + 1, nullptr);
+  for (int l = 1; l <= L; ++l) G[l] = at(workspace, p.G[l]);
+
+  // forward pass and cotangent chain exactly as for the gradients themselves
+  bool top_step_done = false;
+  if (d[L] <= 32) {
+    top_step_done = (L >= 2);
+    const HeadFusion hf{labels, G[L], loss_out, top_step_done ? G[L - 1] : nullptr};
+    if ((rc = forward(net, X, B, L, workspace, p, true, stream, &hf))) return rc;
+  } else {
+    if ((rc = forward(net, X, B, L, workspace, p, true, stream))) return rc;
+    PFG_LAUNCH("head", launch_head_softmax_ce(at(workspace, p.logits), labels, B, d[L], G[L],
+                                              loss_out, stream));
+  }
+  for (int l = top_step_done ? L - 1 : L; l > 1; --l)
+    if ((rc = cotangent_step(net, l, G[l], B, 1, G[l - 1], workspace, p, stream))) return rc;
+
+  // the outer products are never formed: only the squared norms of their two factors
+  std::vector<NormLayer> layers(L);
+  for (int l = 1; l <= L; ++l) {
+    NormLayer &ly = layers[l - 1];
+    ly.a = (l == 1) ? X : at(workspace, p.act[l - 1]);
+    ly.a_bf16 = (l == 1) && (net->dtype == PFG_BF16);
+    ly.g = G[l];
+    ly.d_in = d[l - 1];
+    ly.d_out = d[l];
+    ly.has_bias = (bias_of(net, l) != nullptr);
+    ly.index = l - 1;
+  }
+  if (L <= kNormLayers) {
+    PFG_LAUNCH("grad_norms", launch_grad_sqnorms(layers.data(), L, B, sq_layers_out, L, norm_out, stream));
+  } else {
+    float *sq = sq_layers_out ? sq_layers_out : at(workspace, p.sq);
+    for (int l0 = 0; l0 < L; l0 += kNormLayers)
+      PFG_LAUNCH("grad_norms", launch_grad_sqnorms(layers.data() + l0, std::min(kNormLayers, L - l0), B,
+                                                   sq, L, nullptr, stream));
+    if (norm_out) PFG_LAUNCH("grad_norms", launch_norm_finalize(sq, L, L, B, norm_out, stream));
+  }
+  return PFG_OK;
+}
+
+int pfg_hessian_input(const pfg_mlp *net, const void *X, int64_t B, const float *seeds, int64_t S,
+                      int64_t seed_batch_stride, float *H_out, void *workspace,
+                      size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  int rc = check_net(net);
+  if (rc) return rc;
+  if ((rc = check_weights(net))) return rc;
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!H_out) return fail(PFG_ERR_NULL, "H_out is NULL");
+  if ((rc = check_rows(B, S))) return rc;
+  if ((rc = check_seeds(net, seeds, S, seed_batch_stride))) return rc;
+  if ((rc = check_hessian(net, B, S))) return rc;
+  const Plan p = make_plan(net, PFG_OP_HESSIAN_INPUT, B, S);
+  if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int L = net->num_layers;
+  const int32_t *d = net->dims;
+  const int64_t n = d[0], rows = B * S, ktot = p.ktot;
+
+  if (L == 1 || net->hidden_act == PFG_ACT_IDENTITY || net->hidden_act == PFG_ACT_RELU) {
+    // piecewise-linear network: every second derivative vanishes
+    PFG_LAUNCH("fill_zero", launch_fill_zero(H_out, rows * n * n, stream));
+    return PFG_OK;
+  }
+  const int H = L - 1;   // hidden layers 1..H
+
+  // ---- forward pass: z_l, then a_l, phi'(z_l) and phi''(z_l) ----
+  for (int l = 1; l <= H; ++l) {
+    GemmArgs g{};
+    g.A = (l == 1) ? X : at(workspace, p.act[l - 1]);
+    g.lda = d[l - 1]; g.a_batch_stride = d[l - 1]; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->W[l - 1]; g.ldw = d[l]; g.w_kn = 1;
+    g.M = (int32_t)B; g.N = d[l]; g.K = d[l - 1];
+    g.bias = bias_of(net, l);
+    g.epilogue = EPI_BIAS;
+    g.C = at(workspace, p.d2phi[l]);      // holds z_l until the next kernel overwrites it in place
+    g.ldc = d[l];
+    PFG_LAUNCH("gemm_forward", launch_gemm(g, stream));
+    PFG_LAUNCH("activation", launch_act_from_z(at(workspace, p.d2phi[l]), B, d[l], net->hidden_act,
+                                               l < H ? at(workspace, p.act[l]) : nullptr,
+                                               at(workspace, p.dphi[l]), at(workspace, p.d2phi[l]),
+                                               stream));
+  }
+
+  // ---- tangents: U_l[b] = (d z_l[b] / d x_b)^T, [d_0, d_l], side by side in U [B * d_0, ktot] ----
+  // U_1 = W_1 for every b; U_{l+1}[b] = (U_l[b] * phi'(z_l[b, :])) W_{l+1}: rows (b, i) folded into
+  // one product with the loop-invariant W_{l+1}, the mask broadcast over i.
+  float *U = at(workspace, p.U);
+  PFG_LAUNCH("tangent_seed", launch_scale_rows(net->W[0], 0, 0, d[1], nullptr, 0, B, n, d[1], U, ktot,
+                                               stream));
+  for (int l = 1; l < H; ++l) {
+    GemmArgs g{};
+    g.A = U + p.koff[l]; g.lda = ktot; g.a_batch_stride = n * ktot; g.S = (int32_t)n; g.a_is_f32 = 1;
+    g.a_scale = at(workspace, p.dphi[l]); g.ld_scale = d[l];
+    g.W = net->W[l]; g.ldw = d[l + 1]; g.w_kn = 1;
+    g.M = (int32_t)(B * n); g.N = d[l + 1]; g.K = d[l];
+    g.epilogue = EPI_NONE;
+    g.C = U + p.koff[l + 1]; g.ldc = ktot;
+    PFG_LAUNCH("gemm_tangent", launch_gemm(g, stream));
+  }
+
+  // ---- cotangents at a_l (before the mask), times phi''(z_l): Cc [B * S, ktot] ----
+  float *Cc = at(workspace, p.Cc);
+  float *bufs[2] = {at(workspace, p.ping), at(workspace, p.pong)};
+  int which = 0;
+  const float *cur;
+  int64_t cur_bstride;
+  const bool shared = (seeds == nullptr) || (seed_batch_stride == 0);
+  {
+    GemmArgs g{};
+    g.A = seeds; g.lda = d[L]; g.S = (int32_t)S; g.a_is_f32 = 1;
+    g.W = net->W[L - 1]; g.ldw = d[L]; g.w_kn = 0;
+    g.N = d[H]; g.K = d[L];
+    g.epilogue = EPI_NONE; g.ldc = d[H];
+    if (shared) {
+      // loop-invariant seeds: the product does not depend on b and is formed once, not stacked
+      float *P = at(workspace, p.P);
+      if (!seeds) {
+        PFG_LAUNCH("transpose", launch_transpose(net->W[L - 1], 0, d[H], d[L], P, stream));
+      } else {
+        g.a_batch_stride = 0; g.M = (int32_t)S; g.C = P;
+        PFG_LAUNCH("gemm_cotangent", launch_gemm(g, stream));
+      }
+      cur = P; cur_bstride = 0;
+    } else {
+      g.a_batch_stride = seed_batch_stride; g.M = (int32_t)rows; g.C = bufs[which];
+      PFG_LAUNCH("gemm_cotangent", launch_gemm(g, stream));
+      cur = bufs[which]; cur_bstride = S * d[H];
+      which ^= 1;
+    }
+  }
+  for (int l = H; l >= 1; --l) {
+    // cur = h_l (cotangent at a_l), rows (b, s)
+    PFG_LAUNCH("curvature_rows", launch_scale_rows(cur, 0, cur_bstride, d[l], at(workspace, p.d2phi[l]),
+                                                   d[l], B, S, d[l], Cc + p.koff[l], ktot, stream));
+    if (l == 1) break;
+    GemmArgs g{};
+    g.A = cur; g.lda = d[l]; g.a_batch_stride = cur_bstride; g.S = (int32_t)S; g.a_is_f32 = 1;
+    g.a_scale = at(workspace, p.dphi[l]); g.ld_scale = d[l];
+    g.W = net->W[l - 1]; g.ldw = d[l]; g.w_kn = 0;
+    g.M = (int32_t)rows; g.N = d[l - 1]; g.K = d[l];
+    g.epilogue = EPI_NONE;
+    g.C = bufs[which]; g.ldc = d[l - 1];
+    PFG_LAUNCH("gemm_cotangent", launch_gemm(g, stream));
+    cur = bufs[which]; cur_bstride = S * d[l - 1];
+    which ^= 1;
+  }
+
+  // ---- H[b, (s, i), j] = sum_k U[b, i, k] Cc[b, s, k] U[b, j, k]: one product per example, both
+  // operands stacked (Section 3.4's batched matmul); the weights Cc scale the A rows as they are staged ----
+  for (int64_t b0 = 0; b0 < B; b0 += 32768) {
+    const int64_t nb = std::min<int64_t>(32768, B - b0);
+    GemmArgs g{};
+    g.A = U + b0 * n * ktot; g.lda = ktot; g.a_batch_stride = 0; g.S = (int32_t)n; g.a_is_f32 = 1;
+    g.a_scale = Cc + b0 * S * ktot; g.ld_scale = ktot;
+    g.W = U + b0 * n * ktot; g.ldw = ktot; g.w_kn = 0;
+    g.M = (int32_t)(S * n); g.N = (int32_t)n; g.K = (int32_t)ktot;
+    g.epilogue = EPI_NONE;
+    g.C = H_out + b0 * S * n * n; g.ldc = n;
+    g.streaming = 1;
+    g.nbatch = (int32_t)nb;
+    g.batch_A = n * ktot; g.batch_scale = S * ktot; g.batch_W = n * ktot; g.batch_C = S * n * n;
+    PFG_LAUNCH("gemm_hessian", launch_gemm(g, stream));
+  }
+  return PFG_OK;
 }
 
 int pfg_jacobian_input(const pfg_mlp *net, const void *X, int64_t B, const float *seeds, int64_t S,

@@ -1,4 +1,4 @@
-"""Seeded synthetic inputs for the five measured workloads.
+"""Seeded synthetic inputs for the measured workloads.
 
 This module holds no arithmetic of the method: it only draws random tensors (and rounds them to
 bfloat16 where a workload asks for bf16 inputs).  The same host arrays are handed to the GPU
@@ -25,7 +25,8 @@ BASE_SEED = 190304243
 class Workload:
     name: str
     index: int
-    call: str                      # "per_example_grads" | "jacobian_input" | "jacobian_weights"
+    call: str                      # "per_example_grads" | "jacobian_input" | "jacobian_weights" |
+                                   # "hessian_input"
     dims: Tuple[int, ...]
     act: str                       # hidden activation
     dtype: str                     # "f32" | "bf16" (dtype of X, W, b; outputs are always f32)
@@ -50,6 +51,9 @@ WORKLOADS: Dict[str, Workload] = {
                  "bf16", 256, "normal", "normal_fan_in"),
         Workload("c5_nested_weight_jacobian", 4, "jacobian_weights", (256, 256, 16), "tanh", "f32",
                  64, "normal", "normal_fan_in", S=16, head="softmax", layers_out=(1,)),
+        # Jacobian of the Jacobian: 64 Hessians of 256 x 256 per example
+        Workload("c6_tanh_hessian", 5, "hessian_input", (256, 512, 512, 64), "tanh", "f32", 32,
+                 "normal", "normal_fan_in", S=64),
     ]
 }
 
@@ -133,5 +137,7 @@ def output_values(w: Workload, B: Optional[int] = None) -> int:
         return B * sum(d[l - 1] * d[l] + d[l] for l in range(1, len(d)))
     if w.call == "jacobian_input":
         return B * w.S * d[0]
+    if w.call == "hessian_input":
+        return B * w.S * d[0] * d[0]
     layers = w.layers_out or tuple(range(1, len(d)))
     return B * w.S * sum(d[l - 1] * d[l] for l in layers)

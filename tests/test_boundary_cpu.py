@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert set(names) == set(pfg.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
-    assert lib.pfg_version() == 100
+    assert lib.pfg_version() == 101
 
 
 FAKE = 0x1000  # a non-NULL, 256-aligned value; never dereferenced because validation fails first
@@ -81,7 +81,8 @@ def test_workspace_bytes_rejects_bad_arguments(lib):
     n = ctypes.c_size_t(0)
     assert lib.pfg_workspace_bytes(None, 0, 1, 1, ctypes.byref(n)) == pfg.PFG_ERR_NULL
     assert lib.pfg_workspace_bytes(ctypes.byref(net), 0, 1, 1, None) == pfg.PFG_ERR_NULL
-    assert ws_bytes(lib, net, 3, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
+    assert ws_bytes(lib, net, 5, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
+    assert ws_bytes(lib, net, -1, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
     assert ws_bytes(lib, net, 0, 0, 1)[0] == pfg.PFG_ERR_SHAPE
     assert ws_bytes(lib, net, 1, 1, 0)[0] == pfg.PFG_ERR_SHAPE
     assert ws_bytes(lib, net, 1, 1 << 20, 1 << 20)[0] == pfg.PFG_ERR_OVERFLOW
@@ -144,6 +145,58 @@ def test_jacobians_reject_before_launch(lib):
               None) == pfg.PFG_ERR_SHAPE
     assert jw(ctypes.byref(net), FAKE, 2, 1, None, 2, 0, outs, outs, FAKE, 0,
               None) == pfg.PFG_ERR_WORKSPACE
+
+
+def test_grad_norms_workspace_and_rejections(lib):
+    net = make_net([784, 512, 512, 10])
+    B = 128
+    grads = ws_bytes(lib, net, 0, B, 1)[1]
+    # the gradient call's blocks plus [B, L] squared norms; S is ignored
+    assert ws_bytes(lib, net, 3, B, 1) == (0, grads + up(4 * B * 3))
+    assert ws_bytes(lib, net, 3, B, 55) == (0, grads + up(4 * B * 3))
+    fn = lib.pfg_per_example_grad_norms
+    big = 1 << 30
+    small = make_net([4, 3, 2])
+    r = ctypes.byref(small)
+    assert fn(r, None, FAKE, 2, FAKE, FAKE, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r, FAKE, None, 2, FAKE, FAKE, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r, FAKE, FAKE, 2, None, None, FAKE, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert "both NULL" in lib.pfg_last_error().decode()
+    assert fn(r, FAKE, FAKE, 0, FAKE, FAKE, None, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+    assert fn(r, FAKE, FAKE, 2, FAKE, FAKE, None, None, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(r, FAKE, FAKE, 2, FAKE, FAKE, None, FAKE, 16, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(None, FAKE, FAKE, 2, FAKE, FAKE, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+
+
+def test_hessian_workspace_and_rejections(lib):
+    net = make_net([256, 512, 512, 64], act=2)
+    B, S, n, ktot = 32, 64, 256, 1024
+    rc, nbytes = ws_bytes(lib, net, 4, B, S)
+    assert rc == 0
+    expect = (6 * up(4 * B * 512)                    # a_l, phi'(z_l), phi''(z_l) for two hidden layers
+              + up(4 * B * n * ktot)                 # tangents
+              + up(4 * B * S * ktot)                 # curvature weights
+              + up(4 * S * 512)                      # loop-invariant seed block
+              + 2 * up(4 * B * S * 512))             # two cotangent blocks
+    assert nbytes == expect
+    # a one-layer network has no hidden layer: nothing but the minimum
+    assert ws_bytes(lib, make_net([7, 3], act=2), 4, 5, 3) == (0, 256)
+    assert ws_bytes(lib, make_net([4, 3, 2], act=2, dtype=1), 4, 1, 2)[0] == pfg.PFG_ERR_UNSUPPORTED
+    assert ws_bytes(lib, make_net([1 << 16, 3, 2], act=2), 4, 1, 2)[0] == pfg.PFG_ERR_OVERFLOW
+    fn = lib.pfg_hessian_input
+    big = 1 << 30
+    small = make_net([4, 3, 2], act=2)
+    r = ctypes.byref(small)
+    assert fn(r, None, 2, None, 2, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r, FAKE, 2, None, 2, 0, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r, FAKE, 2, None, 3, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE      # identity seeds
+    assert fn(r, FAKE, 2, FAKE, 3, 5, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE      # stride < S * d_L
+    assert fn(r, FAKE, 0, None, 2, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+    assert fn(r, FAKE, 2, None, 2, 0, FAKE, None, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(r, FAKE, 2, None, 2, 0, FAKE, FAKE, 8, None) == pfg.PFG_ERR_WORKSPACE
+    bf = make_net([4, 3, 2], act=2, dtype=1)
+    assert fn(ctypes.byref(bf), FAKE, 2, None, 2, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_UNSUPPORTED
+    assert "float32" in lib.pfg_last_error().decode()
 
 
 def test_last_error_is_cleared_by_a_good_call(lib):
