@@ -81,6 +81,18 @@ def main():
             ws = torch.empty(pfg.pfg_workspace_bytes(net, w.call, B), dtype=torch.uint8, device=dev)
             return lambda: pfg.pfg_per_example_grads(net, X, labels, out_dW=dW, out_db=db,
                                                      out_loss=loss, workspace=ws)
+        if w.call == "grad_norms":
+            sq = torch.empty((B, L), **f32)
+            norm = torch.empty((B,), **f32)
+            loss = torch.empty((B,), **f32)
+            ws = torch.empty(pfg.pfg_workspace_bytes(net, w.call, B), dtype=torch.uint8, device=dev)
+            return lambda: pfg.pfg_per_example_grad_norms(net, X, labels, out_sq_layers=sq,
+                                                          out_norm=norm, out_loss=loss, workspace=ws)
+        if w.call == "hessian_input":
+            H = torch.empty((B, S, d[0], d[0]), **f32)
+            ws = torch.empty(pfg.pfg_workspace_bytes(net, w.call, B, S), dtype=torch.uint8,
+                             device=dev)
+            return lambda: pfg.pfg_hessian_input(net, X, out=H, workspace=ws)
         if w.call == "jacobian_input":
             J = torch.empty((B, S, d[0]), **f32)
             ws = torch.empty(pfg.pfg_workspace_bytes(net, w.call, B, S), dtype=torch.uint8,
@@ -146,6 +158,16 @@ def main():
         d, B, S = w.dims, w.B, w.S
         if w.call == "per_example_grads":
             return {"outer_product": {"bytes": 4 * B * sum(d[l - 1] * d[l] for l in range(1, len(d)))}}
+        if w.call == "grad_norms":
+            # no large output: the forward products dominate; each reads its weights once, reads
+            # its input rows and writes a_l and phi'(z_l)
+            elem = 2 if w.dtype == "bf16" else 4
+            L = len(d) - 1
+            return {"gemm_forward": {"bytes": sum(
+                elem * d[l - 1] * d[l] + (elem if l == 1 else 4) * B * d[l - 1] +
+                (8 if l < L else 4) * B * d[l] for l in range(1, L + 1))}}
+        if w.call == "hessian_input":
+            return {"gemm_hessian": {"flops": 2 * B * S * d[0] * d[0] * sum(d[1:-1])}}
         if w.call == "jacobian_input":
             rows = B * S
             cot = sum(2 * rows * d[l] * d[l - 1] for l in range(2, len(d) - 1))
@@ -169,13 +191,15 @@ def main():
 
     def roofline(w, kt):
         alg = algorithmic(w)
-        if "outer_product" in alg:
-            k = kt["outer_product"]
-            per_launch_bytes = alg["outer_product"]["bytes"] / k["launches_per_step"]
+        fam = next(iter(alg))
+        if "bytes" in alg[fam]:
+            k = kt[fam]
+            per_launch_bytes = alg[fam]["bytes"] / k["launches_per_step"]
             per_launch_ms = k["ms_per_step"] / k["launches_per_step"]
             gbs = per_launch_bytes / (per_launch_ms * 1e-3) / 1e9
-            return {"kernel": "outer_product", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
+            return {"kernel": fam, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                    "traffic": measured_traffic(w.name) if fam == "outer_product" else None,
                     "bytes_per_launch": per_launch_bytes, "ms_per_launch": per_launch_ms,
                     "launches_per_step": k["launches_per_step"]}
         flops = sum(v["flops"] for v in alg.values())
@@ -217,7 +241,7 @@ def main():
         d, B, S = w.dims, w.B, w.S
         elem = 2 if w.dtype == "bf16" else 4
         last = len(d) - 1
-        fwd_layers = range(1, last) if w.call == "jacobian_input" else range(1, last + 1)
+        fwd_layers = range(1, last) if w.call in ("jacobian_input", "hessian_input") else range(1, last + 1)
         fwd_flops = sum(2 * B * d[l - 1] * d[l] for l in fwd_layers)
         fwd_bytes = sum(elem * d[l - 1] * d[l] for l in fwd_layers)
         gemm_report = {}
@@ -242,6 +266,11 @@ def main():
         }
         if w.call == "per_example_grads":
             rec["per_example_grads_per_sec"] = w.B / sec
+        elif w.call == "grad_norms":
+            rec["per_example_grad_norms_per_sec"] = w.B / sec
+        elif w.call == "hessian_input":
+            rec["hessian_entries_per_sec"] = values / sec
+            rec["hessians_per_sec"] = w.B * w.S / sec
         else:
             rec["jacobian_entries_per_sec"] = values / sec
             rec["jacobian_rows_per_sec"] = w.B * w.S / sec
@@ -291,7 +320,10 @@ def main():
     if not args.only_primary:
         for name, steps in (("c5_nested_weight_jacobian", args.steps),
                             ("c3_tanh_jacobian", max(3, args.steps // 20)),
-                            ("c4_gelu_bf16_grads", max(3, args.steps // 20))):
+                            ("c4_gelu_bf16_grads", max(3, args.steps // 20)),
+                            ("c2_mnist_mlp_grad_norms", args.steps),
+                            ("c4_gelu_bf16_grad_norms", max(3, args.steps // 4)),
+                            ("c6_tanh_hessian", max(3, args.steps // 20))):
             try:
                 others[name], _ = measure(name, steps, max(1, min(args.warmup, steps // 2)))
             except Exception as e:

@@ -154,6 +154,21 @@ __global__ __launch_bounds__(kThreads) void scale_rows_kernel(const void *in, in
   }
 }
 
+// This thread's share of the sum of squares of one float32 row (16-byte loads when the row allows).
+__device__ __forceinline__ float row_sumsq(const float *row, int d, int tid) {
+  float s = 0.f;
+  if ((reinterpret_cast<uintptr_t>(row) & 15) == 0 && d % 4 == 0) {
+    const f32x4 *r4 = reinterpret_cast<const f32x4 *>(row);
+    for (int i = tid; i < d / 4; i += kThreads) {
+      const f32x4 v = r4[i];
+      s += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+    }
+  } else {
+    for (int i = tid; i < d; i += kThreads) { const float v = row[i]; s += v * v; }
+  }
+  return s;
+}
+
 struct NormBatch {
   NormLayer layer[kNormLayers];
   int n;
@@ -176,11 +191,9 @@ __global__ __launch_bounds__(kThreads) void grad_sqnorms_kernel(const NormBatch 
       const __bf16 *a = static_cast<const __bf16 *>(ly.a) + b * ly.d_in;
       for (int i = tid; i < ly.d_in; i += kThreads) { const float v = (float)a[i]; sa += v * v; }
     } else {
-      const float *a = static_cast<const float *>(ly.a) + b * ly.d_in;
-      for (int i = tid; i < ly.d_in; i += kThreads) { const float v = a[i]; sa += v * v; }
+      sa = row_sumsq(static_cast<const float *>(ly.a) + b * ly.d_in, ly.d_in, tid);
     }
-    const float *g = ly.g + b * ly.d_out;
-    for (int j = tid; j < ly.d_out; j += kThreads) { const float v = g[j]; sg += v * v; }
+    sg = row_sumsq(ly.g + b * ly.d_out, ly.d_out, tid);
     sa = wave_sum(sa);
     sg = wave_sum(sg);
     __syncthreads();                       // the previous layer's partial sums have been read

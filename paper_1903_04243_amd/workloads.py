@@ -26,7 +26,7 @@ class Workload:
     name: str
     index: int
     call: str                      # "per_example_grads" | "jacobian_input" | "jacobian_weights" |
-                                   # "hessian_input"
+                                   # "grad_norms" | "hessian_input"
     dims: Tuple[int, ...]
     act: str                       # hidden activation
     dtype: str                     # "f32" | "bf16" (dtype of X, W, b; outputs are always f32)
@@ -51,6 +51,11 @@ WORKLOADS: Dict[str, Workload] = {
                  "bf16", 256, "normal", "normal_fan_in"),
         Workload("c5_nested_weight_jacobian", 4, "jacobian_weights", (256, 256, 16), "tanh", "f32",
                  64, "normal", "normal_fan_in", S=16, head="softmax", layers_out=(1,)),
+        # the norms of the per-example gradients of c2 and c4 (same inputs), gradients not formed
+        Workload("c2_mnist_mlp_grad_norms", 1, "grad_norms", (784, 512, 512, 10), "relu", "f32",
+                 128, "uniform01", "glorot_uniform"),
+        Workload("c4_gelu_bf16_grad_norms", 3, "grad_norms", (4096, 4096, 4096, 10), "gelu",
+                 "bf16", 256, "normal", "normal_fan_in"),
         # Jacobian of the Jacobian: 64 Hessians of 256 x 256 per example
         Workload("c6_tanh_hessian", 5, "hessian_input", (256, 512, 512, 64), "tanh", "f32", 32,
                  "normal", "normal_fan_in", S=64),
@@ -139,5 +144,7 @@ def output_values(w: Workload, B: Optional[int] = None) -> int:
         return B * w.S * d[0]
     if w.call == "hessian_input":
         return B * w.S * d[0] * d[0]
+    if w.call == "grad_norms":
+        return B * (len(d) - 1) + 2 * B
     layers = w.layers_out or tuple(range(1, len(d)))
     return B * w.S * sum(d[l - 1] * d[l] for l in layers)
