@@ -56,6 +56,9 @@ def load_library() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_1903_04243_amd.build` "
                                "(there is no fallback path)")
+        # torch first: it brings its own HIP runtime, and the library must bind to that one (a
+        # second runtime loaded ahead of torch's would see no device)
+        import torch  # noqa: F401
         lib = ctypes.CDLL(LIB_PATH)
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         netp = ctypes.POINTER(pfg_mlp)
