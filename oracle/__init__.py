@@ -3,8 +3,9 @@
 Only ``tests/``, ``__graft_entry__.smoke()`` and the CPU-baseline leg of ``bench.py`` may import
 this package.  It is independent of the HIP library: it neither imports nor is imported by it.
 
-The arithmetic lives in ``pfg_oracle.c`` (plain C, literal loops over examples and seed rows);
-this module only builds that file with gcc, loads it through ctypes and marshals numpy arrays.
+The arithmetic lives in ``pfg_oracle.c`` (dense networks; plain C, literal loops over examples and
+seed rows) and ``lstm_oracle.c`` (the unrolled LSTM, wrapped by ``oracle.lstm``); this module only
+builds them with gcc, loads the first through ctypes and marshals numpy arrays.
 Every array that crosses this boundary is float64 (labels: int32).
 """
 from __future__ import annotations
@@ -44,9 +45,11 @@ def compile_source(src: str, lib: str) -> None:
 
 
 def build(force: bool = False) -> str:
-    """Compile the C oracle with gcc (OpenMP only parallelises the outermost pfor index)."""
+    """Compile the C oracles with gcc (OpenMP only parallelises the outermost pfor index)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         compile_source(_SRC, _LIB)
+    from . import lstm
+    lstm.build(force)
     return _LIB
 
 

@@ -1,0 +1,155 @@
+"""float64 CPU oracle for the unrolled LSTM (test infrastructure, not product code).
+
+The arithmetic lives in ``lstm_oracle.c``; this module builds it with gcc, loads it through ctypes
+and marshals numpy arrays (all float64, labels int32).  Only ``tests/``,
+``__graft_entry__.smoke()`` and the CPU-baseline leg of ``bench.py`` may import it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+from . import _c_double_p, _c_int32_p, _dp, _f64, compile_source
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lstm_oracle.c")
+_LIB = os.path.join(_HERE, "liblstm_oracle.so")
+
+
+class _Net(ctypes.Structure):
+    _fields_ = [("dx", ctypes.c_int32), ("H", ctypes.c_int32), ("dy", ctypes.c_int32),
+                ("T", ctypes.c_int32), ("W", _c_double_p), ("b", _c_double_p),
+                ("Wout", _c_double_p), ("bout", _c_double_p)]
+
+
+def build(force: bool = False) -> str:
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        compile_source(_SRC, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        # PFG_LSTM_ORACLE_LIB: a deliberately broken build, used only by the mutation test
+        lib = ctypes.CDLL(os.environ.get("PFG_LSTM_ORACLE_LIB") or build())
+        lib.lstmo_loss.restype = ctypes.c_double
+        _lib = lib
+    return _lib
+
+
+class Lstm:
+    """W [dx + H, 4H] (column blocks i, g, f, o), b [4H] or None, Wout [H, dy], bout [dy] or None,
+    unrolled to T steps."""
+
+    def __init__(self, W, b, Wout, bout, T: int):
+        self.W, self.Wout = _f64(W), _f64(Wout)
+        self.b = None if b is None else _f64(b)
+        self.bout = None if bout is None else _f64(bout)
+        self.H, self.dy = self.Wout.shape
+        self.dx = self.W.shape[0] - self.H
+        self.T = int(T)
+        assert self.dx >= 1 and self.T >= 1 and self.W.shape == (self.dx + self.H, 4 * self.H)
+        assert self.b is None or self.b.shape == (4 * self.H,)
+        assert self.bout is None or self.bout.shape == (self.dy,)
+        self.c = _Net(self.dx, self.H, self.dy, self.T, _dp(self.W), _dp(self.b), _dp(self.Wout),
+                      _dp(self.bout))
+
+
+def _seq(net: Lstm, x) -> np.ndarray:
+    x = _f64(x)
+    assert x.shape == (net.T, net.dx)
+    return x
+
+
+def forward(net: Lstm, x) -> np.ndarray:
+    y = np.empty(net.dy)
+    _load().lstmo_forward(ctypes.byref(net.c), _dp(_seq(net, x)), _dp(y))
+    return y
+
+
+def states(net: Lstm, x):
+    """(h [T, H], c [T, H]) after every step."""
+    h, c = np.empty((net.T, net.H)), np.empty((net.T, net.H))
+    _load().lstmo_states(ctypes.byref(net.c), _dp(_seq(net, x)), _dp(h), _dp(c))
+    return h, c
+
+
+def loss(net: Lstm, x, label: int) -> float:
+    assert 0 <= int(label) < net.dy
+    return float(_load().lstmo_loss(ctypes.byref(net.c), _dp(_seq(net, x)), ctypes.c_int(int(label))))
+
+
+def _labels(net: Lstm, labels, B: int) -> np.ndarray:
+    labels = np.ascontiguousarray(np.asarray(labels, dtype=np.int32))
+    assert labels.shape == (B,) and labels.min(initial=0) >= 0 and labels.max(initial=0) < net.dy
+    return labels
+
+
+def per_example_grads(net: Lstm, X, labels, want_dW: bool = True):
+    """(dW [B, dx+H, 4H] or None, db [B, 4H], dWout [B, H, dy], dbout [B, dy], loss [B])."""
+    X = _f64(X)
+    B = X.shape[0]
+    assert X.shape == (B, net.T, net.dx)
+    labels = _labels(net, labels, B)
+    dW = np.empty((B, net.dx + net.H, 4 * net.H)) if want_dW else None
+    db = np.empty((B, 4 * net.H))
+    dWout = np.empty((B, net.H, net.dy))
+    dbout = np.empty((B, net.dy))
+    ls = np.empty(B)
+    _load().lstmo_per_example_grads(ctypes.byref(net.c), _dp(X), labels.ctypes.data_as(_c_int32_p),
+                                    ctypes.c_int64(B), _dp(dW), _dp(db), _dp(dWout), _dp(dbout),
+                                    _dp(ls))
+    return dW, db, dWout, dbout, ls
+
+
+def body_per_example_grads(net: Lstm, x, label: int):
+    dW = np.empty((net.dx + net.H, 4 * net.H))
+    db = np.empty(4 * net.H)
+    dWout = np.empty((net.H, net.dy))
+    dbout = np.empty(net.dy)
+    ls = ctypes.c_double(0.0)
+    _load().lstmo_body_per_example_grads(ctypes.byref(net.c), _dp(_seq(net, x)),
+                                         ctypes.c_int(int(label)), _dp(dW), _dp(db), _dp(dWout),
+                                         _dp(dbout), ctypes.byref(ls))
+    return dW, db, dWout, dbout, float(ls.value)
+
+
+def _seed_args(net: Lstm, B: int, seeds, S: Optional[int]):
+    if seeds is None:
+        S = net.dy if S is None else S
+        assert S == net.dy, "identity seeds need S == dy"
+        return None, S, 0
+    seeds = _f64(seeds)
+    if seeds.ndim == 2:
+        assert seeds.shape[1] == net.dy
+        return seeds, seeds.shape[0], 0
+    assert seeds.ndim == 3 and seeds.shape[0] == B and seeds.shape[2] == net.dy
+    return seeds, seeds.shape[1], seeds.shape[1] * net.dy
+
+
+def jacobian_input(net: Lstm, X, seeds=None, S: Optional[int] = None) -> np.ndarray:
+    """J[b, s, t, :] = gradient of <seed row s, y_b> with respect to x_b[t, :], [B, S, T, dx]."""
+    X = _f64(X)
+    B = X.shape[0]
+    assert X.shape == (B, net.T, net.dx)
+    seeds, S, stride = _seed_args(net, B, seeds, S)
+    J = np.empty((B, S, net.T, net.dx))
+    _load().lstmo_jacobian_input(ctypes.byref(net.c), _dp(X), ctypes.c_int64(B), _dp(seeds),
+                                 ctypes.c_int64(S), ctypes.c_int64(stride), _dp(J))
+    return J
+
+
+def body_jacobian_input_row(net: Lstm, x, seed_row) -> np.ndarray:
+    seed_row = _f64(seed_row)
+    assert seed_row.shape == (net.dy,)
+    row = np.empty((net.T, net.dx))
+    _load().lstmo_body_jacobian_input_row(ctypes.byref(net.c), _dp(_seq(net, x)), _dp(seed_row),
+                                          _dp(row))
+    return row

@@ -1,0 +1,231 @@
+"""Pins for the float64 LSTM oracle (oracle/lstm_oracle.c), against things other than itself: a
+hand-worked scalar fixture, the library LSTM cell of torch (float64), autograd through that cell,
+central finite differences, closed forms for one step, and invariants.
+
+CPU only.  Nothing here touches the HIP library.
+"""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import lstm
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rand_lstm(rng, dx, H, dy, T, bias=True, scale=1.0):
+    W = rng.standard_normal((dx + H, 4 * H)) * scale / math.sqrt(dx + H)
+    b = rng.standard_normal(4 * H) * 0.3 if bias else None
+    Wout = rng.standard_normal((H, dy)) / math.sqrt(H)
+    bout = rng.standard_normal(dy) * 0.3 if bias else None
+    return lstm.Lstm(W, b, Wout, bout, T)
+
+
+def torch_cell(net, requires_grad=False):
+    """torch.nn.LSTMCell (gate order i, f, g, o; weights [4H, in]) holding the oracle's weights
+    (column blocks i, g, f, o of a [dx + H, 4H] matrix), plus the readout as tensors."""
+    H, dx = net.H, net.dx
+    blocks = [0, 2, 1, 3]                                   # torch block k is our block blocks[k]
+    cols = np.concatenate([np.arange(k * H, (k + 1) * H) for k in blocks])
+    cell = torch.nn.LSTMCell(dx, H, bias=True, dtype=torch.float64)
+    with torch.no_grad():
+        cell.weight_ih.copy_(torch.from_numpy(net.W[:dx][:, cols].T.copy()))
+        cell.weight_hh.copy_(torch.from_numpy(net.W[dx:][:, cols].T.copy()))
+        cell.bias_ih.copy_(torch.from_numpy((net.b if net.b is not None else np.zeros(4 * H))[cols]))
+        cell.bias_hh.zero_()
+    Wout = torch.from_numpy(net.Wout).clone().requires_grad_(requires_grad)
+    bout = torch.from_numpy(net.bout if net.bout is not None else np.zeros(net.dy)).clone()
+    bout.requires_grad_(requires_grad)
+    return cell, Wout, bout, cols
+
+
+def torch_run(net, cell, Wout, bout, x):
+    h = torch.zeros(1, net.H, dtype=torch.float64)
+    c = torch.zeros(1, net.H, dtype=torch.float64)
+    hs, cs = [], []
+    for t in range(net.T):
+        h, c = cell(x[t:t + 1], (h, c))
+        hs.append(h[0])
+        cs.append(c[0])
+    return h[0] @ Wout + bout, hs, cs
+
+
+def test_hand_fixture_two_steps():
+    g = json.load(open(os.path.join(GOLD, "lstm_1_1_2_T2.json")))
+    sig = lambda v: 1.0 / (1.0 + math.exp(-v))
+    i1, g1, o1 = sig(0.5), math.tanh(-1.0), sig(2.0)
+    c1 = i1 * g1
+    h1 = o1 * math.tanh(c1)
+    i2, g2, f2, o2 = sig(-0.5 + h1), math.tanh(1.0 + 0.5 * h1), sig(0.75 - 0.5 * h1), sig(-2.0 - h1)
+    c2 = f2 * c1 + i2 * g2
+    h2 = o2 * math.tanh(c2)
+    net = lstm.Lstm(np.array(g["W"], float), np.array(g["b"], float), np.array(g["Wout"], float),
+                    np.array(g["bout"], float), g["T"])
+    x = np.array(g["x"], float)
+    h, c = lstm.states(net, x)
+    np.testing.assert_allclose(h[:, 0], [h1, h2], rtol=1e-14)
+    np.testing.assert_allclose(c[:, 0], [c1, c2], rtol=1e-14)
+    np.testing.assert_allclose(lstm.forward(net, x), [2 * h2 + 0.5, -3 * h2], rtol=1e-14)
+
+
+@pytest.mark.parametrize("bias", [True, False])
+def test_states_match_the_library_cell(bias):
+    rng = np.random.default_rng(61)
+    net = rand_lstm(rng, 5, 7, 3, 6, bias=bias)
+    x = rng.standard_normal((6, 5))
+    cell, Wout, bout, _ = torch_cell(net)
+    with torch.no_grad():
+        y, hs, cs = torch_run(net, cell, Wout, bout, torch.from_numpy(x))
+    h, c = lstm.states(net, x)
+    np.testing.assert_allclose(h, torch.stack(hs).numpy(), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(c, torch.stack(cs).numpy(), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(lstm.forward(net, x), y.numpy(), rtol=1e-12, atol=1e-14)
+    p = scipy.special.softmax(y.numpy())
+    assert lstm.loss(net, x, 1) == pytest.approx(-math.log(p[1]), rel=1e-12)
+
+
+def test_one_step_closed_form():
+    # T = 1 from a zero state: c = i g, h = o tanh(c); the forget gate multiplies c_0 = 0
+    rng = np.random.default_rng(62)
+    net = rand_lstm(rng, 4, 3, 2, 1)
+    x = rng.standard_normal((1, 4))
+    z = x[0] @ net.W[:4] + net.b
+    i, g, o = scipy.special.expit(z[0:3]), np.tanh(z[3:6]), scipy.special.expit(z[9:12])
+    h = o * np.tanh(i * g)
+    np.testing.assert_allclose(lstm.forward(net, x), h @ net.Wout + net.bout, rtol=1e-13)
+    # gradient with respect to the forget-gate columns and the recurrent rows is exactly zero
+    dW, db, _, _, _ = lstm.body_per_example_grads(net, x, 0)
+    assert not dW[:, 6:9].any() and not db[6:9].any() and not dW[4:].any()
+
+
+def test_per_example_grads_against_autograd_through_the_library_cell():
+    rng = np.random.default_rng(63)
+    net = rand_lstm(rng, 4, 6, 5, 7)
+    B = 3
+    X = rng.standard_normal((B, 7, 4))
+    labels = rng.integers(0, 5, size=B)
+    dW, db, dWout, dbout, loss = lstm.per_example_grads(net, X, labels)
+    for b in range(B):
+        cell, Wout, bout, cols = torch_cell(net, requires_grad=True)
+        y, _, _ = torch_run(net, cell, Wout, bout, torch.from_numpy(X[b]))
+        ell = -torch.log_softmax(y, dim=0)[int(labels[b])]
+        g_ih, g_hh, g_b, g_Wout, g_bout = torch.autograd.grad(
+            ell, [cell.weight_ih, cell.weight_hh, cell.bias_ih, Wout, bout])
+        want_W = np.empty_like(net.W)
+        want_W[:4][:, cols] = g_ih.numpy().T
+        want_W[4:][:, cols] = g_hh.numpy().T
+        want_b = np.empty(24)
+        want_b[cols] = g_b.numpy()
+        np.testing.assert_allclose(dW[b], want_W, rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(db[b], want_b, rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(dWout[b], g_Wout.numpy(), rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(dbout[b], g_bout.numpy(), rtol=1e-10, atol=1e-13)
+        assert loss[b] == pytest.approx(float(ell.detach()), rel=1e-12)
+
+
+def test_per_example_grads_by_central_finite_differences():
+    rng = np.random.default_rng(64)
+    net = rand_lstm(rng, 3, 4, 3, 5)
+    x = rng.standard_normal((5, 3))
+    label = int(np.argmin(lstm.forward(net, x)))           # least likely class: a large gradient
+    dW, db, dWout, dbout, _ = lstm.body_per_example_grads(net, x, label)
+    h = 1e-6
+
+    def fd(arr, idx):
+        keep = arr[idx]
+        arr[idx] = keep + h
+        up = lstm.loss(lstm.Lstm(net.W, net.b, net.Wout, net.bout, net.T), x, label)
+        arr[idx] = keep - h
+        dn = lstm.loss(lstm.Lstm(net.W, net.b, net.Wout, net.bout, net.T), x, label)
+        arr[idx] = keep
+        return (up - dn) / (2 * h)
+
+    for idx in [(0, 0), (2, 5), (3, 9), (6, 15), (5, 2), (1, 12)]:     # input rows and recurrent rows
+        assert dW[idx] == pytest.approx(fd(net.W, idx), rel=1e-6, abs=1e-9)
+    for k in (0, 5, 10, 15):
+        assert db[k] == pytest.approx(fd(net.b, k), rel=1e-6, abs=1e-9)
+    assert dWout[2, 1] == pytest.approx(fd(net.Wout, (2, 1)), rel=1e-6, abs=1e-9)
+    assert dbout[0] == pytest.approx(fd(net.bout, 0), rel=1e-6, abs=1e-9)
+
+
+def test_readout_gradients_closed_form_and_weight_sharing_over_steps():
+    rng = np.random.default_rng(65)
+    net = rand_lstm(rng, 3, 5, 4, 6)
+    X = rng.standard_normal((4, 6, 3))
+    labels = rng.integers(0, 4, size=4)
+    dW, db, dWout, dbout, loss = lstm.per_example_grads(net, X, labels)
+    for b in range(4):
+        h, _ = lstm.states(net, X[b])
+        p = scipy.special.softmax(lstm.forward(net, X[b]))
+        assert loss[b] == pytest.approx(-math.log(p[labels[b]]), rel=1e-12)
+        p[labels[b]] -= 1.0
+        np.testing.assert_allclose(dbout[b], p, rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(dWout[b], np.outer(h[-1], p), rtol=1e-12, atol=1e-15)
+        # the bias gradient is the sum over steps of the same rows that multiply u_t in dW: the
+        # input rows of dW are sum_t x_t dz_t; with x_t = e_0 for every t they equal db
+    ones = np.zeros((1, 6, 3))
+    ones[:, :, 0] = 1.0
+    dW1, db1, _, _, _ = lstm.per_example_grads(net, ones, [0])
+    np.testing.assert_allclose(dW1[0, 0], db1[0], rtol=1e-12, atol=1e-15)
+    assert not dW1[0, 1:3].any()
+
+
+def test_pfor_driver_equals_body_and_permutes_with_the_batch():
+    rng = np.random.default_rng(66)
+    net = rand_lstm(rng, 3, 4, 3, 4)
+    X = rng.standard_normal((5, 4, 3))
+    labels = rng.integers(0, 3, size=5)
+    outs = lstm.per_example_grads(net, X, labels)
+    for b in range(5):
+        body = lstm.body_per_example_grads(net, X[b], int(labels[b]))
+        for got, want in zip(outs, body):
+            np.testing.assert_array_equal(got[b], want)
+    perm = rng.permutation(5)
+    outs_p = lstm.per_example_grads(net, X[perm], labels[perm])
+    for got, want in zip(outs_p, outs):
+        np.testing.assert_array_equal(got, want[perm])
+
+
+def test_input_jacobian_against_autograd_and_finite_differences():
+    rng = np.random.default_rng(67)
+    net = rand_lstm(rng, 3, 5, 4, 6)
+    X = rng.standard_normal((2, 6, 3))
+    J = lstm.jacobian_input(net, X)
+    assert J.shape == (2, 4, 6, 3)
+    cell, Wout, bout, _ = torch_cell(net)
+    for b in range(2):
+        f = lambda x: torch_run(net, cell, Wout, bout, x)[0]
+        want = torch.autograd.functional.jacobian(f, torch.from_numpy(X[b])).numpy()
+        np.testing.assert_allclose(J[b], want, rtol=1e-10, atol=1e-13)
+    h = 1e-6
+    for (t, r) in [(0, 0), (3, 2), (5, 1)]:
+        xp, xm = X[0].copy(), X[0].copy()
+        xp[t, r] += h
+        xm[t, r] -= h
+        fd = (lstm.forward(net, xp) - lstm.forward(net, xm)) / (2 * h)
+        np.testing.assert_allclose(J[0, :, t, r], fd, rtol=1e-6, atol=1e-9)
+
+
+def test_jacobian_seed_forms_and_rows():
+    rng = np.random.default_rng(68)
+    net = rand_lstm(rng, 2, 4, 3, 5)
+    X = rng.standard_normal((3, 5, 2))
+    J = lstm.jacobian_input(net, X)
+    shared = rng.standard_normal((2, 3))
+    Js = lstm.jacobian_input(net, X, seeds=shared)
+    np.testing.assert_allclose(Js, np.einsum("so,botr->bstr", shared, J), rtol=1e-12, atol=1e-15)
+    tiled = np.broadcast_to(shared, (3, 2, 3)).copy()
+    np.testing.assert_array_equal(lstm.jacobian_input(net, X, seeds=tiled), Js)
+    per = rng.standard_normal((3, 2, 3))
+    Jp = lstm.jacobian_input(net, X, seeds=per)
+    np.testing.assert_allclose(Jp, np.einsum("bso,botr->bstr", per, J), rtol=1e-12, atol=1e-15)
+    np.testing.assert_array_equal(lstm.body_jacobian_input_row(net, X[2], per[2, 1]), Jp[2, 1])
+    # the last step's block of the Jacobian does not involve the recurrent weights:
+    # d y / d x_T = Wout^T diag-chain through the last cell only; check it against one-step FD
+    zero_out = lstm.Lstm(net.W, net.b, np.zeros_like(net.Wout), net.bout, net.T)
+    assert not lstm.jacobian_input(zero_out, X).any()

@@ -81,3 +81,56 @@ def test_pins_catch_planted_mistake(tmp_path, oracle, name, old, new):
                         "test_oracle_pins.py"), "-x", "-q", "-p", "no:cacheprovider"],
                        env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
     assert r.returncode != 0, f"mutant {name} passed every pin:\n{r.stdout[-2000:]}"
+
+
+LSTM_SRC = os.path.join(ROOT, "oracle", "lstm_oracle.c")
+
+LSTM_MUTANTS = [
+    ("gate_order_g_and_f", "g = tanh(z[H + k]), f = sigmoid(z[2 * H + k]),",
+     "g = tanh(z[2 * H + k]), f = sigmoid(z[H + k]),"),
+    ("forget_gate_dropped", "const double c = f * (cprev ? cprev[k] : 0.0) + i * g;",
+     "const double c = (cprev ? cprev[k] : 0.0) + i * g;"),
+    ("output_gate_on_cell", "tp.h[(size_t)t * H + k] = o * tanh(c);", "tp.h[(size_t)t * H + k] = o * c;"),
+    ("recurrent_rows_offset", "s += hprev[r] * net->W[(size_t)(dx + r) * G + col];",
+     "s += hprev[r] * net->W[(size_t)r * G + col];"),
+    ("bias_dropped", "double s = net->b ? net->b[col] : 0.0;", "double s = 0.0;"),
+    ("initial_state_not_zero", "const double *cprev = t > 0 ? tp.c + (size_t)(t - 1) * H : NULL;   /* c_0 = 0 */",
+     "const double *cprev = tp.c + (size_t)(t > 0 ? t - 1 : 0) * H;"),
+    ("bptt_cell_path_dropped", "const double dct = dc[k] + dh[k] * o * (1.0 - tc * tc);",
+     "const double dct = dh[k] * o * (1.0 - tc * tc);"),
+    ("bptt_tanh_deriv", "const double dct = dc[k] + dh[k] * o * (1.0 - tc * tc);",
+     "const double dct = dc[k] + dh[k] * o * (1.0 - tc);"),
+    ("bptt_output_gate", "dz[3 * H + k] = dh[k] * tc * o * (1.0 - o);", "dz[3 * H + k] = dh[k] * o * (1.0 - o);"),
+    ("bptt_input_gate_swapped", "dz[k] = dct * g * i * (1.0 - i);", "dz[k] = dct * i * i * (1.0 - i);"),
+    ("bptt_forget_uses_current_cell", "dz[2 * H + k] = dct * (cprev ? cprev[k] : 0.0) * f * (1.0 - f);",
+     "dz[2 * H + k] = dct * tp.c[(size_t)t * H + k] * f * (1.0 - f);"),
+    ("bptt_cell_carry", "dc[k] = dct * f;", "dc[k] = dct;"),
+    ("weights_not_summed_over_steps", "dW[(size_t)r * G + col] += xt[r] * dz[col];",
+     "dW[(size_t)r * G + col] = xt[r] * dz[col];"),
+    ("bias_not_summed_over_steps", "db[col] += dz[col];", "db[col] = dz[col];"),
+    ("recurrent_grad_uses_current_state", "dW[(size_t)(dx + r) * G + col] += hprev[r] * dz[col];",
+     "dW[(size_t)(dx + r) * G + col] += tp.h[(size_t)t * H + r] * dz[col];"),
+    ("hidden_cotangent_transposed", "s += dz[col] * net->W[(size_t)(dx + r) * G + col];",
+     "s += dz[col] * net->W[(size_t)(dx + col % H) * G + (r + (col / H) * H)];"),
+    ("input_cotangent_wrong_step", "gx[(size_t)t * dx + r] = s;", "gx[(size_t)(T - 1 - t) * dx + r] = s;"),
+    ("readout_cotangent", "s += gy[j] * net->Wout[(size_t)k * dy + j];", "s += gy[j] * net->Wout[(size_t)j * H + k];"),
+    ("head_sign", "p[label] -= 1.0;", "p[label] += 1.0;"),
+    ("jacobian_row_stacking", "J + ((size_t)b * S + s) * nx);", "J + ((size_t)s * B + b) * nx);"),
+    ("seed_stride_ignored", "row = seeds + (size_t)b * seed_batch_stride + (size_t)s * dy;",
+     "row = seeds + (size_t)s * dy;"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", LSTM_MUTANTS, ids=[m[0] for m in LSTM_MUTANTS])
+def test_lstm_pins_catch_planted_mistake(tmp_path, oracle, name, old, new):
+    src = open(LSTM_SRC).read()
+    assert src.count(old) >= 1, f"pattern for {name} not found in the oracle source"
+    mutated = tmp_path / "lstm_oracle_mutant.c"
+    mutated.write_text(src.replace(old, new))
+    lib = tmp_path / "liblstm_oracle_mutant.so"
+    oracle.compile_source(str(mutated), str(lib))
+    env = dict(os.environ, PFG_LSTM_ORACLE_LIB=str(lib))
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests",
+                        "test_oracle_lstm_pins.py"), "-x", "-q", "-p", "no:cacheprovider"],
+                       env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0, f"mutant {name} passed every pin:\n{r.stdout[-2000:]}"
