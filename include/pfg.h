@@ -160,6 +160,58 @@ int pfg_hessian_input(const pfg_mlp *net, const void *X, int64_t B, const float 
                       int64_t seed_batch_stride, float *H_out, void *workspace,
                       size_t workspace_bytes, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Statically unrolled LSTM (the model of the paper's own per-example-gradient and Jacobian
+ * benchmarks, Sections 6.1, 6.3 and 6.4: a single-layer unidirectional RNN, every example a
+ * complete sequence, unrolled to a fixed number of steps).
+ *      u_t = [x_t, h_{t-1}],   z_t = u_t W + b,   W row-major [input_size + state_size, 4 state_size]
+ *      column blocks of W and b in the order i, g, f, o:
+ *      i = sigmoid(z_i), g = tanh(z_g), f = sigmoid(z_f), o = sigmoid(z_o)
+ *      c_t = f c_{t-1} + i g,   h_t = o tanh(c_t),   h_0 = c_0 = 0
+ *      y = h_T W_out + b_out,   W_out row-major [state_size, output_size]
+ * A sequence is one parallel-for iteration: X is [B, steps, input_size], example index first.
+ * All tensors are float32 (dtype must be PFG_F32).
+ * ---------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t input_size;   /* >= 1 */
+  int32_t state_size;   /* >= 1 */
+  int32_t output_size;  /* >= 1 */
+  int32_t steps;        /* T >= 1 */
+  const void *W;        /* DEVICE [input_size + state_size, 4 * state_size] */
+  const void *b;        /* DEVICE [4 * state_size] or NULL (zero bias)      */
+  const void *W_out;    /* DEVICE [state_size, output_size]                 */
+  const void *b_out;    /* DEVICE [output_size] or NULL (zero bias)         */
+  int32_t dtype;        /* PFG_F32                                          */
+} pfg_lstm;
+
+typedef enum { PFG_LSTM_OP_PER_EXAMPLE_GRADS = 0, PFG_LSTM_OP_JACOBIAN_INPUT = 1 } pfg_lstm_op;
+
+/* Workspace bytes of an LSTM op (S is ignored by PFG_LSTM_OP_PER_EXAMPLE_GRADS); a multiple of
+ * 256, never 0. */
+int pfg_lstm_workspace_bytes(const pfg_lstm *net, int op, int64_t B, int64_t S, size_t *bytes);
+
+/* Per-example gradients (Section 5.3) of ell_b = -log softmax(y_b)[labels[b]] (not divided by B).
+ * The same W acts at every step, so an example's gradient with respect to W is the sum over the
+ * steps of that step's outer product (contributions of different examples stay separate):
+ *      dW_out[b]     = sum_t u_t[b]^T dz_t[b]          [B, input_size + state_size, 4 state_size]
+ *      db_out[b]     = sum_t dz_t[b]                   [B, 4 state_size]
+ *      dWout_out[b]  = h_T[b]^T (softmax(y_b) - onehot)  [B, state_size, output_size]
+ *      dbout_out[b]  = softmax(y_b) - onehot           [B, output_size]
+ *      loss_out[b]   = ell_b
+ * where dz_t is the cotangent of z_t from back-propagation through the unrolled steps.  Any output
+ * pointer may be NULL (skipped). */
+int pfg_lstm_per_example_grads(const pfg_lstm *net, const void *X, const int32_t *labels, int64_t B,
+                               float *dW_out, float *db_out, float *dWout_out, float *dbout_out,
+                               float *loss_out, void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
+
+/* Input Jacobian (Section 5.1 nested in the loop over examples, Section 3.7):
+ *      J_out[b, s, t, i] = d <seed row s of example b, y_b> / d x_b[t, i]     [B, S, steps, input_size]
+ * seeds, S, seed_batch_stride as for pfg_jacobian_input (rows of length output_size). */
+int pfg_lstm_jacobian_input(const pfg_lstm *net, const void *X, int64_t B, const float *seeds,
+                            int64_t S, int64_t seed_batch_stride, float *J_out, void *workspace,
+                            size_t workspace_bytes, void *hip_stream);
+
 /* Text of the last error on the calling thread ("" if none).  Valid until the next call into the
  * library from that thread. */
 const char *pfg_last_error(void);

@@ -25,7 +25,9 @@ OP = {"per_example_grads": 0, "jacobian_input": 1, "jacobian_weights": 2, "grad_
       "hessian_input": 4}
 
 EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_jacobian_input",
-           "pfg_jacobian_weights", "pfg_per_example_grad_norms", "pfg_hessian_input", "pfg_last_error", "pfg_timing_enable", "pfg_timing_reset",
+           "pfg_jacobian_weights", "pfg_per_example_grad_norms", "pfg_hessian_input",
+           "pfg_lstm_workspace_bytes", "pfg_lstm_per_example_grads", "pfg_lstm_jacobian_input",
+           "pfg_last_error", "pfg_timing_enable", "pfg_timing_reset",
            "pfg_timing_query", "pfg_timing_names", "pfg_version"]
 
 
@@ -45,6 +47,22 @@ class pfg_mlp(ctypes.Structure):
         ("dtype", ctypes.c_int32),
     ]
 
+
+class pfg_lstm(ctypes.Structure):
+    _fields_ = [
+        ("input_size", ctypes.c_int32),
+        ("state_size", ctypes.c_int32),
+        ("output_size", ctypes.c_int32),
+        ("steps", ctypes.c_int32),
+        ("W", ctypes.c_void_p),
+        ("b", ctypes.c_void_p),
+        ("W_out", ctypes.c_void_p),
+        ("b_out", ctypes.c_void_p),
+        ("dtype", ctypes.c_int32),
+    ]
+
+
+LSTM_OP = {"per_example_grads": 0, "jacobian_input": 1}
 
 _lib = None
 
@@ -70,6 +88,11 @@ def load_library() -> ctypes.CDLL:
                                              ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
         lib.pfg_per_example_grad_norms.argtypes = [netp, vp, vp, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.pfg_hessian_input.argtypes = [netp, vp, i64, vp, i64, i64, vp, vp, ctypes.c_size_t, vp]
+        lstmp = ctypes.POINTER(pfg_lstm)
+        lib.pfg_lstm_workspace_bytes.argtypes = [lstmp, i32, i64, i64, ctypes.POINTER(ctypes.c_size_t)]
+        lib.pfg_lstm_per_example_grads.argtypes = [lstmp, vp, vp, i64, vp, vp, vp, vp, vp, vp,
+                                                   ctypes.c_size_t, vp]
+        lib.pfg_lstm_jacobian_input.argtypes = [lstmp, vp, i64, vp, i64, i64, vp, vp, ctypes.c_size_t, vp]
         lib.pfg_last_error.restype = ctypes.c_char_p
         lib.pfg_timing_enable.argtypes = [i32]
         lib.pfg_timing_query.argtypes = [ctypes.c_char_p, ctypes.POINTER(i64),
@@ -281,6 +304,108 @@ def pfg_hessian_input(net: Mlp, X, seeds=None, S: Optional[int] = None, out=None
         ctypes.byref(net.c), X.data_ptr(), B, None if seeds is None else seeds.data_ptr(), S,
         stride, H.data_ptr(), workspace.data_ptr(), ws_bytes, _stream_ptr()))
     return H
+
+
+class Lstm:
+    """Device-resident unrolled LSTM: W [dx + H, 4H] (column blocks i, g, f, o), b [4H] or None,
+    W_out [H, dy], b_out [dy] or None, all contiguous float32 GPU tensors; T steps."""
+
+    def __init__(self, W, b, W_out, b_out, steps: int):
+        import torch
+        for t in (W, b, W_out, b_out):
+            if t is not None and (t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda):
+                raise ValueError("LSTM weights must be contiguous float32 GPU tensors")
+        self.H, self.dy = int(W_out.shape[0]), int(W_out.shape[1])
+        self.dx = int(W.shape[0]) - self.H
+        self.T = int(steps)
+        if self.dx < 1 or tuple(W.shape) != (self.dx + self.H, 4 * self.H):
+            raise ValueError(f"W has shape {tuple(W.shape)}")
+        if b is not None and tuple(b.shape) != (4 * self.H,):
+            raise ValueError(f"b has shape {tuple(b.shape)}")
+        if b_out is not None and tuple(b_out.shape) != (self.dy,):
+            raise ValueError(f"b_out has shape {tuple(b_out.shape)}")
+        self.W, self.b, self.W_out, self.b_out = W, b, W_out, b_out
+        self.device = W.device
+        self.c = pfg_lstm(self.dx, self.H, self.dy, self.T, W.data_ptr(),
+                          None if b is None else b.data_ptr(), W_out.data_ptr(),
+                          None if b_out is None else b_out.data_ptr(), DTYPE["f32"])
+
+    @staticmethod
+    def from_numpy(W, b, W_out, b_out, steps: int, device: str = "cuda:0") -> "Lstm":
+        import torch
+        up = lambda a: None if a is None else torch.from_numpy(a).to(device)
+        return Lstm(up(W), up(b), up(W_out), up(b_out), steps)
+
+
+def pfg_lstm_workspace_bytes(net: Lstm, op: str, B: int, S: int = 1) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().pfg_lstm_workspace_bytes(ctypes.byref(net.c), LSTM_OP[op], B, S,
+                                                   ctypes.byref(n)))
+    return int(n.value)
+
+
+def _lstm_workspace(net: Lstm, op: str, B: int, S: int, workspace):
+    import torch
+    if workspace is None:
+        workspace = torch.empty(pfg_lstm_workspace_bytes(net, op, B, S), dtype=torch.uint8,
+                                device=net.device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def _check_seq(net: Lstm, X):
+    import torch
+    if (X.dtype != torch.float32 or not X.is_contiguous() or X.dim() != 3 or
+            tuple(X.shape[1:]) != (net.T, net.dx)):
+        raise ValueError("X must be a contiguous float32 [B, steps, input_size] tensor")
+
+
+def pfg_lstm_per_example_grads(net: Lstm, X, labels, want_dW: bool = True, want_db: bool = True,
+                               want_dWout: bool = True, want_dbout: bool = True,
+                               want_loss: bool = True, out=None, workspace=None):
+    """Returns (dW [B, dx+H, 4H], db [B, 4H], dWout [B, H, dy], dbout [B, dy], loss [B]), each None
+    if not wanted.  ``out`` may hold caller tensors in that order."""
+    import torch
+    _check_seq(net, X)
+    B = X.shape[0]
+    if labels.dtype != torch.int32 or tuple(labels.shape) != (B,) or not labels.is_contiguous():
+        raise ValueError("labels must be a contiguous int32 [B] tensor")
+    f32 = dict(dtype=torch.float32, device=net.device)
+    shapes = [(B, net.dx + net.H, 4 * net.H), (B, 4 * net.H), (B, net.H, net.dy), (B, net.dy), (B,)]
+    wants = [want_dW, want_db, want_dWout, want_dbout, want_loss]
+    outs = list(out) if out is not None else [torch.empty(sh, **f32) if w else None
+                                              for sh, w in zip(shapes, wants)]
+    workspace, ws_bytes = _lstm_workspace(net, "per_example_grads", B, 1, workspace)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(load_library().pfg_lstm_per_example_grads(
+        ctypes.byref(net.c), X.data_ptr(), labels.data_ptr(), B, ptr(outs[0]), ptr(outs[1]),
+        ptr(outs[2]), ptr(outs[3]), ptr(outs[4]), workspace.data_ptr(), ws_bytes, _stream_ptr()))
+    return tuple(outs)
+
+
+def pfg_lstm_jacobian_input(net: Lstm, X, seeds=None, S: Optional[int] = None, out=None,
+                            workspace=None):
+    """J[b, s, t, :] = gradient of <seed row s, y_b> with respect to x_b[t, :], [B, S, T, dx]."""
+    import torch
+    _check_seq(net, X)
+    B = X.shape[0]
+    if seeds is None:
+        S, stride = (net.dy if S is None else S), 0
+    else:
+        if seeds.dtype != torch.float32 or not seeds.is_contiguous() or seeds.shape[-1] != net.dy:
+            raise ValueError("seeds must be a contiguous float32 tensor with last dimension output_size")
+        if seeds.dim() == 2:
+            S, stride = seeds.shape[0], 0
+        elif seeds.dim() == 3 and seeds.shape[0] == B:
+            S, stride = seeds.shape[1], seeds.shape[1] * net.dy
+        else:
+            raise ValueError("seeds must be [S, dy] or [B, S, dy]")
+    J = out if out is not None else torch.empty((B, S, net.T, net.dx), dtype=torch.float32,
+                                                device=net.device)
+    workspace, ws_bytes = _lstm_workspace(net, "jacobian_input", B, S, workspace)
+    _check(load_library().pfg_lstm_jacobian_input(
+        ctypes.byref(net.c), X.data_ptr(), B, None if seeds is None else seeds.data_ptr(), S,
+        stride, J.data_ptr(), workspace.data_ptr(), ws_bytes, _stream_ptr()))
+    return J
 
 
 def pfg_timing_enable(on: bool) -> None:

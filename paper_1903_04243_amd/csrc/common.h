@@ -152,4 +152,28 @@ hipError_t launch_norm_finalize(const float *sq, int64_t ld_sq, int32_t L, int64
 // out[0 .. n) = 0
 hipError_t launch_fill_zero(float *out, int64_t n, hipStream_t stream);
 
+// LSTM cell update of step t for every (b, k): zx [B, T, 4H] holds x_t W_x + b, zh [B, 4H] holds
+// h_{t-1} W_h (nullptr at the first step); writes step t of gates [B, T, 4H], cs and hs [B, T, H].
+hipError_t launch_lstm_cell_forward(const float *zx, const float *zh, float *gates, float *cs,
+                                    float *hs, int64_t B, int32_t H, int32_t T, int32_t t,
+                                    hipStream_t stream);
+
+// Reverse cell step t on rows m = b * S + s: reads dh (row m at dh + b * dh_batch_stride + s * H)
+// and dc [rows, H] (taken as zero if first), writes dz (row m at dz + m * dz_row_stride, 4H wide)
+// and dc_{t-1} in place of dc.
+hipError_t launch_lstm_cell_backward(const float *dh, int64_t dh_batch_stride, float *dc, int32_t first,
+                                     const float *gates, const float *cs, int64_t rows, int32_t S,
+                                     int32_t H, int32_t T, int32_t t, float *dz, int64_t dz_row_stride,
+                                     hipStream_t stream);
+
+// out[b * out_bs + i * d_out + j] = sum_{t < nt} a[b * a_bs + t * a_ts + i] * g[b * g_bs + t * g_ts + j]
+// for i < d_in, j < d_out (float32; nt <= 0 writes zeros)
+hipError_t launch_outer_sum(const float *a, int64_t a_bs, int64_t a_ts, const float *g, int64_t g_bs,
+                            int64_t g_ts, int32_t nt, int64_t B, int32_t d_in, int32_t d_out,
+                            float *out, int64_t out_bs, hipStream_t stream);
+
+// out[b, j] = sum_{t < T} g[b, t, j]
+hipError_t launch_sum_steps(const float *g, int64_t B, int32_t T, int32_t d, float *out,
+                            hipStream_t stream);
+
 }  // namespace pfg

@@ -1,0 +1,204 @@
+// Kernels of the unrolled LSTM that are not matrix products: the cell update, its reverse step on
+// stacked cotangent rows, and the per-example weight gradient, which sums one outer product per
+// time step because the same weights are used at every step.
+//
+// Cell (column blocks i, g, f, o of the [dx + H, 4H] weight matrix):
+//   i = sigmoid(z_i), g = tanh(z_g), f = sigmoid(z_f), o = sigmoid(z_o)
+//   c_t = f c_{t-1} + i g,   h_t = o tanh(c_t)
+#include "common.h"
+
+namespace pfg {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ float sigmoidf_(float v) { return 1.f / (1.f + __expf(-v)); }
+
+// One thread per (b, k).  zx already holds x_t W_x + b; zh = h_{t-1} W_h (null at the first step,
+// where the state is zero).  gates, cs and hs are [B, T, .] and receive step t.
+__global__ __launch_bounds__(kThreads) void lstm_cell_forward_kernel(
+    const float *zx, const float *zh, float *gates, float *cs, float *hs, int64_t B, int H, int T,
+    int t) {
+  const int64_t id = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (id >= B * H) return;
+  const int64_t b = id / H;
+  const int k = (int)(id - b * H);
+  const float *zrow = zx + (b * T + t) * 4 * (int64_t)H;
+  float zi = zrow[k], zg = zrow[H + k], zf = zrow[2 * H + k], zo = zrow[3 * H + k];
+  if (zh) {
+    const float *hrow = zh + b * 4 * (int64_t)H;
+    zi += hrow[k]; zg += hrow[H + k]; zf += hrow[2 * H + k]; zo += hrow[3 * H + k];
+  }
+  const float i = sigmoidf_(zi), g = tanhf(zg), f = sigmoidf_(zf), o = sigmoidf_(zo);
+  const float cprev = t > 0 ? cs[(b * T + t - 1) * (int64_t)H + k] : 0.f;
+  const float c = f * cprev + i * g;
+  float *grow = gates + (b * T + t) * 4 * (int64_t)H;
+  grow[k] = i; grow[H + k] = g; grow[2 * H + k] = f; grow[3 * H + k] = o;
+  cs[(b * T + t) * (int64_t)H + k] = c;
+  hs[(b * T + t) * (int64_t)H + k] = o * tanhf(c);
+}
+
+// Reverse step t on stacked cotangent rows m = b * S + s.  The gate values and cell states belong
+// to example b and are shared by its S rows (loop-invariant over s: not stacked, Section 3.4).
+//   dc   += dh * o * (1 - tanh(c_t)^2)
+//   dz_o  = dh * tanh(c_t) * o (1 - o)
+//   dz_i  = dc * g * i (1 - i),  dz_g = dc * i * (1 - g^2),  dz_f = dc * c_{t-1} * f (1 - f)
+//   dc_{t-1} = dc * f
+// dh row m starts at dh + (m / S) * dh_batch_stride + (m % S) * H (batch stride 0: one block shared
+// by all b).  dc is [rows, H], read unless first, and overwritten with dc_{t-1}.  dz row m starts
+// at dz + m * dz_row_stride.
+__global__ __launch_bounds__(kThreads) void lstm_cell_backward_kernel(
+    const float *dh, int64_t dh_batch_stride, float *dc, int first, const float *gates,
+    const float *cs, int64_t rows, int S, int H, int T, int t, float *dz, int64_t dz_row_stride) {
+  const int64_t id = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (id >= rows * H) return;
+  const int64_t m = id / H;
+  const int k = (int)(id - m * H);
+  const int64_t b = m / S, s = m - b * S;
+  const float *grow = gates + (b * T + t) * 4 * (int64_t)H;
+  const float i = grow[k], g = grow[H + k], f = grow[2 * H + k], o = grow[3 * H + k];
+  const float tc = tanhf(cs[(b * T + t) * (int64_t)H + k]);
+  const float cprev = t > 0 ? cs[(b * T + t - 1) * (int64_t)H + k] : 0.f;
+  const float dhv = dh[b * dh_batch_stride + s * H + k];
+  const float dct = (first ? 0.f : dc[m * H + k]) + dhv * o * (1.f - tc * tc);
+  float *out = dz + m * dz_row_stride;
+  out[k] = dct * g * i * (1.f - i);
+  out[H + k] = dct * i * (1.f - g * g);
+  out[2 * H + k] = dct * cprev * f * (1.f - f);
+  out[3 * H + k] = dhv * tc * o * (1.f - o);
+  dc[m * H + k] = dct * f;
+}
+
+// out[b, i, j] = sum_{t < nt} a[b * a_bs + t * a_ts + i] * g[b * g_bs + t * g_ts + j]
+// (Section 3.4's both-operands-stacked matmul with a contraction over the time steps).  A lane keeps
+// its four columns of all nt cotangent rows in registers and walks the rows i of its chunk, whose
+// a values are uniform over the workgroup.  kMaxSteps steps per pass; later passes add to the result.
+constexpr int kMaxSteps = 16;
+constexpr int kRowsPerBlock = 16;
+
+struct OuterSumArgs {
+  const float *a; int64_t a_bs, a_ts;
+  const float *g; int64_t g_bs, g_ts;
+  float *out;            // example b at out + b * out_bs, [d_in, d_out]
+  int64_t out_bs;
+  int d_in, d_out, nt;
+  int accumulate;        // add to out instead of overwriting it
+  int vec;               // d_out % 4 == 0 and g, out 16-byte aligned with aligned strides
+};
+
+__global__ __launch_bounds__(kThreads) void outer_sum_kernel(const OuterSumArgs p) {
+  const int64_t b = blockIdx.y;
+  const int col_chunks = (p.d_out + 4 * kThreads - 1) / (4 * kThreads);
+  const int cchunk = blockIdx.x % col_chunks, rchunk = blockIdx.x / col_chunks;
+  const int i0 = rchunk * kRowsPerBlock;
+  const int i1 = min(p.d_in, i0 + kRowsPerBlock);
+  const float *a = p.a + b * p.a_bs;
+  const float *g = p.g + b * p.g_bs;
+  float *out = p.out + b * p.out_bs;
+  const int j = (cchunk * kThreads + threadIdx.x) * 4;
+  if (j >= p.d_out) return;
+  f32x4 gv[kMaxSteps];
+#pragma unroll
+  for (int t = 0; t < kMaxSteps; ++t) {
+    gv[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (t < p.nt) {
+      if (p.vec) {
+        gv[t] = *reinterpret_cast<const f32x4 *>(g + t * p.g_ts + j);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (j + e < p.d_out) gv[t][e] = g[t * p.g_ts + j + e];
+      }
+    }
+  }
+  for (int i = i0; i < i1; ++i) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < kMaxSteps; ++t)
+      if (t < p.nt) acc += a[t * p.a_ts + i] * gv[t];
+    float *o = out + (int64_t)i * p.d_out + j;
+    if (p.vec) {
+      if (p.accumulate)
+        *reinterpret_cast<f32x4 *>(o) = *reinterpret_cast<const f32x4 *>(o) + acc;
+      else
+        __builtin_nontemporal_store(acc, reinterpret_cast<f32x4 *>(o));
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (j + e < p.d_out) o[e] = p.accumulate ? o[e] + acc[e] : acc[e];
+    }
+  }
+}
+
+// out[b, j] = sum_t g[b, t, j]
+__global__ __launch_bounds__(kThreads) void sum_steps_kernel(const float *g, int64_t B, int T, int d,
+                                                             float *out) {
+  const int64_t id = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (id >= B * d) return;
+  const int64_t b = id / d;
+  const int j = (int)(id - b * d);
+  float s = 0.f;
+  for (int t = 0; t < T; ++t) s += g[(b * T + t) * (int64_t)d + j];
+  out[id] = s;
+}
+
+inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads); }
+
+}  // namespace
+
+hipError_t launch_lstm_cell_forward(const float *zx, const float *zh, float *gates, float *cs,
+                                    float *hs, int64_t B, int32_t H, int32_t T, int32_t t,
+                                    hipStream_t stream) {
+  if (B <= 0) return hipSuccess;
+  PFG_KERNEL(lstm_cell_forward_kernel, dim3(blocks_for(B * H)), dim3(kThreads), 0, stream, zx, zh,
+             gates, cs, hs, B, H, T, t);
+  return hipGetLastError();
+}
+
+hipError_t launch_lstm_cell_backward(const float *dh, int64_t dh_batch_stride, float *dc, int32_t first,
+                                     const float *gates, const float *cs, int64_t rows, int32_t S,
+                                     int32_t H, int32_t T, int32_t t, float *dz, int64_t dz_row_stride,
+                                     hipStream_t stream) {
+  if (rows <= 0) return hipSuccess;
+  PFG_KERNEL(lstm_cell_backward_kernel, dim3(blocks_for(rows * H)), dim3(kThreads), 0, stream, dh,
+             dh_batch_stride, dc, first, gates, cs, rows, S, H, T, t, dz, dz_row_stride);
+  return hipGetLastError();
+}
+
+hipError_t launch_outer_sum(const float *a, int64_t a_bs, int64_t a_ts, const float *g, int64_t g_bs,
+                            int64_t g_ts, int32_t nt, int64_t B, int32_t d_in, int32_t d_out,
+                            float *out, int64_t out_bs, hipStream_t stream) {
+  if (B <= 0 || d_in <= 0 || d_out <= 0) return hipSuccess;
+  auto aligned = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  const int vec = d_out % 4 == 0 && aligned(g) && aligned(out) && g_bs % 4 == 0 && g_ts % 4 == 0 &&
+                  out_bs % 4 == 0;
+  const int col_chunks = (d_out + 4 * kThreads - 1) / (4 * kThreads);
+  const int row_chunks = (d_in + kRowsPerBlock - 1) / kRowsPerBlock;
+  if (nt < 0) nt = 0;        // no step contributes: the block is written as zeros
+  for (int64_t b0 = 0; b0 < B; b0 += 32768) {          // the second grid index holds 65535 at most
+    const int64_t nb = B - b0 < 32768 ? B - b0 : 32768;
+    int t0 = 0;
+    do {
+      OuterSumArgs p{a + b0 * a_bs + (int64_t)t0 * a_ts, a_bs, a_ts,
+                     g + b0 * g_bs + (int64_t)t0 * g_ts, g_bs, g_ts,
+                     out + b0 * out_bs, out_bs, d_in, d_out,
+                     nt - t0 < kMaxSteps ? nt - t0 : kMaxSteps, t0 > 0, vec};
+      PFG_KERNEL(outer_sum_kernel, dim3((unsigned)(col_chunks * row_chunks), (unsigned)nb),
+                 dim3(kThreads), 0, stream, p);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      t0 += kMaxSteps;
+    } while (t0 < nt);
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_sum_steps(const float *g, int64_t B, int32_t T, int32_t d, float *out,
+                            hipStream_t stream) {
+  if (B <= 0) return hipSuccess;
+  PFG_KERNEL(sum_steps_kernel, dim3(blocks_for(B * d)), dim3(kThreads), 0, stream, g, B, T, d, out);
+  return hipGetLastError();
+}
+
+}  // namespace pfg

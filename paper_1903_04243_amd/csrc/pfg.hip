@@ -11,13 +11,14 @@
 
 #include "../../include/pfg.h"
 #include "common.h"
+#include "host.h"
 
 namespace {
-
-using namespace pfg;
-
 thread_local char g_err[512] = "";
+thread_local const char *t_family = "kernel";   // family name of the launches being enqueued
+}  // namespace
 
+namespace pfg {
 int fail(int code, const char *fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -25,6 +26,13 @@ int fail(int code, const char *fmt, ...) {
   va_end(ap);
   return code;
 }
+void clear_error() { g_err[0] = 0; }
+void set_timing_family(const char *name) { t_family = name; }
+}  // namespace pfg
+
+namespace {
+
+using namespace pfg;
 
 // ------------------------------------------------------------------------------------------
 // Per-kernel timing: every kernel launch gets its own pair of events attached to the dispatch
@@ -35,8 +43,6 @@ std::mutex g_timing_mu;
 bool g_timing_on = false;
 std::vector<TimedLaunch> g_pending;
 std::map<std::string, std::pair<int64_t, double>> g_totals;
-thread_local const char *t_family = "kernel";   // family name of the launches being enqueued
-
 void drain_pending() {
   std::lock_guard<std::mutex> lk(g_timing_mu);
   for (auto &t : g_pending) {
@@ -73,8 +79,6 @@ namespace {
 // ------------------------------------------------------------------------------------------
 constexpr int kMaxLayers = 256;
 constexpr int64_t kMaxDim = 1 << 24;
-constexpr int64_t kMaxRows = 0x7fffffffLL;          // folded iteration index m = b * S + s
-constexpr int64_t kMaxElems = (int64_t)1 << 46;     // per tensor
 
 int check_net(const pfg_mlp *net) {
   if (!net) return fail(PFG_ERR_NULL, "net is NULL");
@@ -224,14 +228,6 @@ int check_workspace(const Plan &p, void *ws, size_t bytes) {
 }
 
 inline float *at(void *ws, size_t off) { return reinterpret_cast<float *>(static_cast<char *>(ws) + off); }
-
-#define PFG_LAUNCH(name, expr)                                                         \
-  do {                                                                                 \
-    t_family = name;                                                                   \
-    hipError_t e_ = (expr);                                                            \
-    if (e_ != hipSuccess)                                                              \
-      return fail(PFG_ERR_DEVICE, "%s: %s", name, hipGetErrorString(e_));              \
-  } while (0)
 
 const void *bias_of(const pfg_mlp *net, int l) { return net->b ? net->b[l - 1] : nullptr; }
 

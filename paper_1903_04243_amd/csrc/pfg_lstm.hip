@@ -1,0 +1,306 @@
+// C ABI of the unrolled LSTM: argument checks, workspace layout and the order in which the kernels
+// are enqueued.  No arithmetic of the method happens on the host.
+#include <algorithm>
+
+#include "../../include/pfg.h"
+#include "common.h"
+#include "host.h"
+
+namespace {
+
+using namespace pfg;
+
+int check_lstm(const pfg_lstm *net) {
+  if (!net) return fail(PFG_ERR_NULL, "net is NULL");
+  if (net->input_size < 1 || net->state_size < 1 || net->output_size < 1 || net->steps < 1)
+    return fail(PFG_ERR_SHAPE, "input_size %d, state_size %d, output_size %d and steps %d must all be >= 1",
+                net->input_size, net->state_size, net->output_size, net->steps);
+  constexpr int64_t kMaxDim = 1 << 22;
+  if (net->input_size > kMaxDim || net->state_size > kMaxDim || net->output_size > kMaxDim ||
+      net->steps > (1 << 16))
+    return fail(PFG_ERR_SHAPE, "a size of the LSTM is out of range");
+  if (net->dtype != PFG_F32)
+    return fail(PFG_ERR_UNSUPPORTED, "the LSTM path is float32 only (dtype %d given)", net->dtype);
+  if (!net->W) return fail(PFG_ERR_NULL, "net->W is NULL");
+  if (!net->W_out) return fail(PFG_ERR_NULL, "net->W_out is NULL");
+  return PFG_OK;
+}
+
+int check_lstm_rows(const pfg_lstm *net, int64_t B, int64_t S, bool grads) {
+  if (B < 1) return fail(PFG_ERR_SHAPE, "B = %lld must be at least 1", (long long)B);
+  if (S < 1) return fail(PFG_ERR_SHAPE, "S = %lld must be at least 1", (long long)S);
+  const int64_t H = net->state_size, dx = net->input_size, T = net->steps, dy = net->output_size;
+  if (B > kMaxRows || S > kMaxRows || B * S > kMaxRows || B * T > kMaxRows)
+    return fail(PFG_ERR_OVERFLOW, "B * S = %lld * %lld or B * steps exceeds %lld rows", (long long)B,
+                (long long)S, (long long)kMaxRows);
+  const int64_t rows = B * S;
+  if (4 * H > kMaxElems / (rows * (grads ? T : 1)) || T * dx > kMaxElems / rows ||
+      rows * H > ((int64_t)1 << 38) || (dx + H) * 4 * H > 0x7fffffffLL || H * dy > 0x7fffffffLL ||
+      (grads && (dx + H) * 4 * H > kMaxElems / B))
+    return fail(PFG_ERR_OVERFLOW, "the tensors of this call exceed the indexing limits");
+  return PFG_OK;
+}
+
+int check_lstm_seeds(const pfg_lstm *net, const float *seeds, int64_t S, int64_t stride) {
+  const int64_t dy = net->output_size;
+  if (!seeds) {
+    if (S != dy)
+      return fail(PFG_ERR_SHAPE, "identity seeds (seeds == NULL) need S == output_size, got S = %lld, output_size = %lld",
+                  (long long)S, (long long)dy);
+    return PFG_OK;
+  }
+  if (stride != 0 && stride < S * dy)
+    return fail(PFG_ERR_SHAPE, "seed_batch_stride = %lld must be 0 or at least S * output_size = %lld",
+                (long long)stride, (long long)(S * dy));
+  return PFG_OK;
+}
+
+struct LstmPlan {
+  size_t total = 0;
+  size_t zx = 0, zh = 0, gates = 0, cs = 0, hs = 0;   // forward
+  size_t y = 0, dy = 0, dh = 0, dc = 0, dz = 0, P = 0;
+  size_t take(size_t bytes) {
+    const size_t at = total;
+    total += (bytes + 255) / 256 * 256;
+    return at;
+  }
+};
+
+LstmPlan make_lstm_plan(const pfg_lstm *net, int op, int64_t B, int64_t S) {
+  const size_t H = net->state_size, T = net->steps, dy = net->output_size, f = sizeof(float);
+  LstmPlan p;
+  p.zx = p.take(f * B * T * 4 * H);
+  p.zh = p.take(f * B * 4 * H);
+  p.gates = p.take(f * B * T * 4 * H);
+  p.cs = p.take(f * B * T * H);
+  p.hs = p.take(f * B * T * H);
+  if (op == PFG_LSTM_OP_PER_EXAMPLE_GRADS) {
+    p.y = p.take(f * B * dy);
+    p.dy = p.take(f * B * dy);
+    p.dh = p.take(f * B * H);
+    p.dc = p.take(f * B * H);
+    p.dz = p.take(f * B * T * 4 * H);       // all steps are kept: the weight gradient sums over them
+  } else {
+    const size_t rows = (size_t)B * S;
+    p.P = p.take(f * S * H);                // loop-invariant seeds pulled through the readout
+    p.dh = p.take(f * rows * H);
+    p.dc = p.take(f * rows * H);
+    p.dz = p.take(f * rows * 4 * H);        // one step at a time
+  }
+  return p;
+}
+
+int check_ws(const LstmPlan &p, void *ws, size_t bytes) {
+  if (!ws) return fail(PFG_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", p.total);
+  if (reinterpret_cast<uintptr_t>(ws) & 255)
+    return fail(PFG_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  if (bytes < p.total)
+    return fail(PFG_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", bytes, p.total);
+  return PFG_OK;
+}
+
+// Forward pass of all examples, all steps.  The input projections x_t W_x + b of every step do not
+// depend on the recurrence and go out as ONE product over the B * T rows (Section 3.4: a matmul
+// whose weight operand is loop-invariant folds the iteration index into its rows); only
+// h_{t-1} W_h and the cell update remain on the sequential path.
+int lstm_forward(const pfg_lstm *net, const void *X, int64_t B, void *ws, const LstmPlan &p,
+                 hipStream_t stream) {
+  const int32_t dx = net->input_size, H = net->state_size, T = net->steps;
+  const float *W = static_cast<const float *>(net->W);
+  {
+    GemmArgs g{};
+    g.A = X; g.lda = dx; g.a_batch_stride = dx; g.S = 1; g.a_is_f32 = 1;
+    g.W = W; g.ldw = 4 * H; g.w_kn = 1;
+    g.M = (int32_t)(B * T); g.N = 4 * H; g.K = dx;
+    g.bias = net->b; g.epilogue = EPI_BIAS;
+    g.C = ws_at(ws, p.zx); g.ldc = 4 * H;
+    PFG_LAUNCH("lstm_gemm_input", launch_gemm(g, stream));
+  }
+  float *hs = ws_at(ws, p.hs);
+  for (int t = 0; t < T; ++t) {
+    if (t > 0) {
+      GemmArgs g{};
+      g.A = hs + (int64_t)(t - 1) * H; g.lda = (int64_t)T * H; g.a_batch_stride = (int64_t)T * H;
+      g.S = 1; g.a_is_f32 = 1;
+      g.W = W + (int64_t)dx * 4 * H; g.ldw = 4 * H; g.w_kn = 1;
+      g.M = (int32_t)B; g.N = 4 * H; g.K = H;
+      g.epilogue = EPI_NONE;
+      g.C = ws_at(ws, p.zh); g.ldc = 4 * H;
+      PFG_LAUNCH("lstm_gemm_recurrent", launch_gemm(g, stream));
+    }
+    PFG_LAUNCH("lstm_cell", launch_lstm_cell_forward(ws_at(ws, p.zx), t > 0 ? ws_at(ws, p.zh) : nullptr,
+                                                     ws_at(ws, p.gates), ws_at(ws, p.cs), hs, B, H, T,
+                                                     t, stream));
+  }
+  return PFG_OK;
+}
+
+// dh_{t-1} = dz_t W_h^T on `rows` rows of dz (row stride ld_dz).
+int recurrent_cotangent(const pfg_lstm *net, const float *dz, int64_t ld_dz, int64_t rows, float *dh,
+                        hipStream_t stream) {
+  const int32_t dx = net->input_size, H = net->state_size;
+  GemmArgs g{};
+  g.A = dz; g.lda = ld_dz; g.a_batch_stride = ld_dz; g.S = 1; g.a_is_f32 = 1;
+  g.W = static_cast<const float *>(net->W) + (int64_t)dx * 4 * H; g.ldw = 4 * H; g.w_kn = 0;
+  g.M = (int32_t)rows; g.N = H; g.K = 4 * H;
+  g.epilogue = EPI_NONE;
+  g.C = dh; g.ldc = H;
+  PFG_LAUNCH("lstm_gemm_cotangent", launch_gemm(g, stream));
+  return PFG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pfg_lstm_workspace_bytes(const pfg_lstm *net, int op, int64_t B, int64_t S, size_t *bytes) {
+  clear_error();
+  int rc = check_lstm(net);
+  if (rc) return rc;
+  if (!bytes) return fail(PFG_ERR_NULL, "bytes is NULL");
+  if (op != PFG_LSTM_OP_PER_EXAMPLE_GRADS && op != PFG_LSTM_OP_JACOBIAN_INPUT)
+    return fail(PFG_ERR_UNSUPPORTED, "unknown LSTM op %d", op);
+  const bool grads = (op == PFG_LSTM_OP_PER_EXAMPLE_GRADS);
+  if (grads) S = 1;
+  if ((rc = check_lstm_rows(net, B, S, grads))) return rc;
+  *bytes = make_lstm_plan(net, op, B, S).total;
+  return PFG_OK;
+}
+
+int pfg_lstm_per_example_grads(const pfg_lstm *net, const void *X, const int32_t *labels, int64_t B,
+                               float *dW_out, float *db_out, float *dWout_out, float *dbout_out,
+                               float *loss_out, void *workspace, size_t workspace_bytes,
+                               void *hip_stream) {
+  clear_error();
+  int rc = check_lstm(net);
+  if (rc) return rc;
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
+  if ((rc = check_lstm_rows(net, B, 1, true))) return rc;
+  const LstmPlan p = make_lstm_plan(net, PFG_LSTM_OP_PER_EXAMPLE_GRADS, B, 1);
+  if ((rc = check_ws(p, workspace, workspace_bytes))) return rc;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int32_t dx = net->input_size, H = net->state_size, T = net->steps, dy = net->output_size;
+  void *ws = workspace;
+  if ((rc = lstm_forward(net, X, B, ws, p, stream))) return rc;
+
+  // readout and loss head on the last state; d ell / d y lands in the caller's dbout when given
+  const float *hT = ws_at(ws, p.hs) + (int64_t)(T - 1) * H;
+  float *gy = dbout_out ? dbout_out : ws_at(ws, p.dy);
+  {
+    GemmArgs g{};
+    g.A = hT; g.lda = (int64_t)T * H; g.a_batch_stride = (int64_t)T * H; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->W_out; g.ldw = dy; g.w_kn = 1;
+    g.M = (int32_t)B; g.N = dy; g.K = H;
+    g.bias = net->b_out; g.ldc = dy;
+    if (dy <= 32) {
+      g.epilogue = EPI_HEAD; g.C = nullptr; g.C2 = gy; g.labels = labels; g.loss = loss_out;
+      PFG_LAUNCH("lstm_gemm_readout", launch_gemm(g, stream));
+    } else {
+      g.epilogue = EPI_BIAS; g.C = ws_at(ws, p.y);
+      PFG_LAUNCH("lstm_gemm_readout", launch_gemm(g, stream));
+      PFG_LAUNCH("head", launch_head_softmax_ce(ws_at(ws, p.y), labels, B, dy, gy, loss_out, stream));
+    }
+  }
+  if (dWout_out) {
+    OuterArgs o{};
+    o.a = hT; o.lda = (int64_t)T * H; o.a_bf16 = 0; o.g = gy; o.ldg = dy; o.out = dWout_out;
+    o.M = B; o.S = 1; o.d_in = H; o.d_out = dy;
+    PFG_LAUNCH("outer_product", launch_outer(&o, 1, stream));
+  }
+  if (!dW_out && !db_out) return PFG_OK;
+
+  // dh_T = (d ell / d y) W_out^T, then back through the steps; dz of every step is kept
+  float *dh = ws_at(ws, p.dh), *dc = ws_at(ws, p.dc), *dz = ws_at(ws, p.dz);
+  {
+    GemmArgs g{};
+    g.A = gy; g.lda = dy; g.a_batch_stride = dy; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->W_out; g.ldw = dy; g.w_kn = 0;
+    g.M = (int32_t)B; g.N = H; g.K = dy;
+    g.epilogue = EPI_NONE; g.C = dh; g.ldc = H;
+    PFG_LAUNCH("lstm_gemm_cotangent", launch_gemm(g, stream));
+  }
+  const int64_t ld_dz = (int64_t)T * 4 * H;
+  for (int t = T - 1; t >= 0; --t) {
+    PFG_LAUNCH("lstm_cell_backward",
+               launch_lstm_cell_backward(dh, H, dc, t == T - 1, ws_at(ws, p.gates), ws_at(ws, p.cs), B,
+                                         1, H, T, t, dz + (int64_t)t * 4 * H, ld_dz, stream));
+    if (t > 0 && (rc = recurrent_cotangent(net, dz + (int64_t)t * 4 * H, ld_dz, B, dh, stream))) return rc;
+  }
+  if (dW_out) {
+    // Both operands are stacked and the weights are shared by the steps: per example a product
+    // with the step index as contraction.  Rows of x: all T steps of x_t^T dz_t.  Rows of h: steps
+    // 2..T of h_{t-1}^T dz_t (h_0 = 0 contributes nothing).
+    const int64_t out_bs = (int64_t)(dx + H) * 4 * H;
+    PFG_LAUNCH("outer_sum", launch_outer_sum(static_cast<const float *>(X), (int64_t)T * dx, dx, dz, ld_dz,
+                                             4 * H, T, B, dx, 4 * H, dW_out, out_bs, stream));
+    PFG_LAUNCH("outer_sum", launch_outer_sum(ws_at(ws, p.hs), (int64_t)T * H, H, dz + 4 * H, ld_dz,
+                                             4 * H, T - 1, B, H, 4 * H, dW_out + (int64_t)dx * 4 * H,
+                                             out_bs, stream));
+  }
+  if (db_out) PFG_LAUNCH("sum_steps", launch_sum_steps(dz, B, T, 4 * H, db_out, stream));
+  return PFG_OK;
+}
+
+int pfg_lstm_jacobian_input(const pfg_lstm *net, const void *X, int64_t B, const float *seeds,
+                            int64_t S, int64_t seed_batch_stride, float *J_out, void *workspace,
+                            size_t workspace_bytes, void *hip_stream) {
+  clear_error();
+  int rc = check_lstm(net);
+  if (rc) return rc;
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!J_out) return fail(PFG_ERR_NULL, "J_out is NULL");
+  if ((rc = check_lstm_rows(net, B, S, false))) return rc;
+  if ((rc = check_lstm_seeds(net, seeds, S, seed_batch_stride))) return rc;
+  const LstmPlan p = make_lstm_plan(net, PFG_LSTM_OP_JACOBIAN_INPUT, B, S);
+  if ((rc = check_ws(p, workspace, workspace_bytes))) return rc;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int32_t dx = net->input_size, H = net->state_size, T = net->steps, dy = net->output_size;
+  const int64_t rows = B * S;
+  void *ws = workspace;
+  if ((rc = lstm_forward(net, X, B, ws, p, stream))) return rc;
+
+  // cotangent of the last state, dh_T[b, s, :] = seed row (b, s) W_out^T.  Loop-invariant seeds
+  // (identity or shared) give one [S, H] block for all examples, which is not stacked: the first
+  // reverse cell step reads it with batch stride 0.
+  float *dh = ws_at(ws, p.dh), *dc = ws_at(ws, p.dc), *dz = ws_at(ws, p.dz);
+  const float *dh_first;
+  int64_t dh_first_bs;
+  const bool shared = (seeds == nullptr) || (seed_batch_stride == 0);
+  if (shared && !seeds) {
+    PFG_LAUNCH("transpose", launch_transpose(net->W_out, 0, H, dy, ws_at(ws, p.P), stream));
+    dh_first = ws_at(ws, p.P); dh_first_bs = 0;
+  } else {
+    GemmArgs g{};
+    g.A = seeds; g.lda = dy; g.a_batch_stride = shared ? 0 : seed_batch_stride; g.S = (int32_t)S;
+    g.a_is_f32 = 1;
+    g.W = net->W_out; g.ldw = dy; g.w_kn = 0;
+    g.M = (int32_t)(shared ? S : rows); g.N = H; g.K = dy;
+    g.epilogue = EPI_NONE; g.C = shared ? ws_at(ws, p.P) : dh; g.ldc = H;
+    PFG_LAUNCH("lstm_gemm_cotangent", launch_gemm(g, stream));
+    dh_first = g.C; dh_first_bs = shared ? 0 : S * (int64_t)H;
+  }
+
+  for (int t = T - 1; t >= 0; --t) {
+    const bool first = (t == T - 1);
+    PFG_LAUNCH("lstm_cell_backward",
+               launch_lstm_cell_backward(first ? dh_first : dh, first ? dh_first_bs : S * (int64_t)H, dc,
+                                         first, ws_at(ws, p.gates), ws_at(ws, p.cs), rows, (int32_t)S,
+                                         H, T, t, dz, 4 * H, stream));
+    // J[b, s, t, :] = dz_t W_x^T, streamed straight into its slot of the output
+    GemmArgs g{};
+    g.A = dz; g.lda = 4 * H; g.a_batch_stride = 4 * H; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->W; g.ldw = 4 * H; g.w_kn = 0;
+    g.M = (int32_t)rows; g.N = dx; g.K = 4 * H;
+    g.epilogue = EPI_NONE;
+    g.C = J_out + (int64_t)t * dx; g.ldc = (int64_t)T * dx;
+    g.streaming = 1;
+    PFG_LAUNCH("lstm_gemm_jacobian", launch_gemm(g, stream));
+    if (t > 0 && (rc = recurrent_cotangent(net, dz, 4 * H, rows, dh, stream))) return rc;
+  }
+  return PFG_OK;
+}
+
+}  // extern "C"

@@ -148,3 +148,57 @@ def output_values(w: Workload, B: Optional[int] = None) -> int:
         return B * (len(d) - 1) + 2 * B
     layers = w.layers_out or tuple(range(1, len(d)))
     return B * w.S * sum(d[l - 1] * d[l] for l in layers)
+
+
+# --------------------------------------------------------------------------------------------
+# Unrolled LSTM workloads (the model of the paper's own per-example-gradient and Jacobian
+# benchmarks: sequences of 128-dimensional vectors, state size 256, 10 steps).
+# --------------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class LstmWorkload:
+    name: str
+    index: int
+    call: str                      # "lstm_per_example_grads" | "lstm_jacobian_input"
+    dx: int
+    H: int
+    dy: int
+    T: int
+    B: int
+    S: int = 1
+
+
+LSTM_WORKLOADS: Dict[str, LstmWorkload] = {
+    w.name: w for w in [
+        LstmWorkload("c7_lstm_grads", 6, "lstm_per_example_grads", 128, 256, 10, 10, 256),
+        LstmWorkload("c8_lstm_jacobian", 7, "lstm_jacobian_input", 128, 256, 128, 10, 64, S=128),
+    ]
+}
+
+
+@dataclass
+class LstmInputs:
+    workload: LstmWorkload
+    W: np.ndarray          # [dx + H, 4H], column blocks i, g, f, o
+    b: np.ndarray          # [4H]
+    Wout: np.ndarray       # [H, dy]
+    bout: np.ndarray       # [dy]
+    X: np.ndarray          # [B, T, dx]
+    labels: np.ndarray     # [B]
+
+
+def make_lstm_inputs(w: LstmWorkload, B: Optional[int] = None, dx=None, H=None, dy=None, T=None,
+                     bias_scale: float = 0.0, seed: Optional[int] = None) -> LstmInputs:
+    """Weights uniform in +-1/sqrt(H) (readout: +-1/sqrt(H)), inputs standard normal, labels
+    uniform; draw order W, b, Wout, bout, X, labels from one Philox stream."""
+    B = w.B if B is None else B
+    dx, H = w.dx if dx is None else dx, w.H if H is None else H
+    dy, T = w.dy if dy is None else dy, w.T if T is None else T
+    rng = np.random.Generator(np.random.Philox(BASE_SEED + w.index if seed is None else seed))
+    r = 1.0 / np.sqrt(H)
+    W = rng.uniform(-r, r, size=(dx + H, 4 * H)).astype(np.float32)
+    b = (rng.standard_normal(4 * H) * bias_scale).astype(np.float32)
+    Wout = rng.uniform(-r, r, size=(H, dy)).astype(np.float32)
+    bout = (rng.standard_normal(dy) * bias_scale).astype(np.float32)
+    X = rng.standard_normal(size=(B, T, dx)).astype(np.float32)
+    labels = rng.integers(0, dy, size=(B,)).astype(np.int32)
+    return LstmInputs(w, W, b, Wout, bout, X, labels)

@@ -1,0 +1,208 @@
+"""GPU parity for the unrolled LSTM: per-example gradients and the input Jacobian from the HIP
+library, called through its C ABI, against the float64 CPU oracle (oracle/lstm_oracle.c) on the
+same seeded inputs.  Error measure as in test_parity_gpu.py: per leading slice
+max|gpu - ref| / max|ref|, at most 1e-4 (everything here is float32).
+"""
+import numpy as np
+import pytest
+
+from parity_util import TOL_F32, slice_rel_err
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_1903_04243_amd as pfg  # noqa: E402
+from paper_1903_04243_amd import workloads as wl  # noqa: E402
+
+from gpu_helpers import dev, say  # noqa: E402
+from oracle import lstm as olstm  # noqa: E402
+
+
+@pytest.fixture(scope="module", autouse=True)
+def gpu_ready():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    pfg.load_library()
+    yield
+
+
+def nan_like(*shape):
+    return torch.full(shape, float("nan"), dtype=torch.float32, device="cuda:0")
+
+
+def nets(inp, bias=True):
+    w = inp
+    b, bout = (w.b, w.bout) if bias else (None, None)
+    T = w.X.shape[1]
+    return (olstm.Lstm(w.W, b, w.Wout, bout, T), pfg.Lstm.from_numpy(w.W, b, w.Wout, bout, T))
+
+
+NAMES = ("dW", "db", "dWout", "dbout", "loss")
+
+
+def check_lstm_grads(inp, tag, bias=True, examples=None):
+    onet, net = nets(inp, bias)
+    B, T, dx = inp.X.shape
+    H, dy = net.H, net.dy
+    outs = [nan_like(B, dx + H, 4 * H), nan_like(B, 4 * H), nan_like(B, H, dy), nan_like(B, dy),
+            nan_like(B)]
+    got = pfg.pfg_lstm_per_example_grads(net, dev(inp.X), dev(inp.labels), out=outs)
+    torch.cuda.synchronize()
+    idx = list(range(B)) if examples is None else list(examples)
+    ref = olstm.per_example_grads(onet, inp.X[idx], inp.labels[idx])
+    worst = 0.0
+    for name, g, r in zip(NAMES, got, ref):
+        gh = g.cpu().numpy()
+        assert np.isfinite(gh).all(), f"{name} was not written in full"
+        e = slice_rel_err(gh[idx], r, lead=0 if name == "loss" else 1)
+        say(f"  {tag} {name} rel err {e:.3e}")
+        worst = max(worst, e)
+    assert worst <= TOL_F32, f"{tag}: max relative error {worst:.3e}"
+    return net, got
+
+
+def check_lstm_jacobian(inp, tag, seeds=None, bias=True):
+    onet, net = nets(inp, bias)
+    B, T, dx = inp.X.shape
+    ref = olstm.jacobian_input(onet, inp.X, seeds=seeds)
+    S = ref.shape[1]
+    J = pfg.pfg_lstm_jacobian_input(net, dev(inp.X), seeds=None if seeds is None else dev(seeds),
+                                    out=nan_like(B, S, T, dx))
+    torch.cuda.synchronize()
+    e = slice_rel_err(J.cpu().numpy(), ref, lead=2)
+    say(f"  {tag} J rel err {e:.3e}")
+    assert e <= TOL_F32
+    return net, J
+
+
+LSTM_SHAPES = [
+    # dx, H, dy, T, B
+    (3, 4, 2, 5, 2),
+    (1, 1, 1, 1, 1),            # the smallest model; a single step has no recurrent term
+    (5, 7, 3, 1, 4),            # one step
+    (33, 65, 10, 4, 9),         # one past the tile edges
+    (20, 36, 40, 6, 17),        # more than 32 outputs: separate loss head
+    (16, 32, 8, 18, 5),         # more steps than one pass of the weight-gradient kernel holds
+    (64, 96, 12, 3, 130),       # enough rows for the tiled kernels in the input projection
+]
+
+
+@pytest.mark.parametrize("dx,H,dy,T,B", LSTM_SHAPES, ids=[f"dx{s[0]}-H{s[1]}-dy{s[2]}-T{s[3]}-B{s[4]}"
+                                                         for s in LSTM_SHAPES])
+def test_lstm_odd_shapes_grads_and_jacobian(dx, H, dy, T, B):
+    say(f"LSTM odd shape dx={dx} H={H} dy={dy} T={T} B={B}")
+    w = wl.LstmWorkload("odd", 300 + dx + H + T, "lstm_per_example_grads", dx, H, dy, T, B)
+    inp = wl.make_lstm_inputs(w, bias_scale=0.3)
+    check_lstm_grads(inp, "lstm-odd")
+    rng = np.random.default_rng(B + T)
+    shared = rng.standard_normal((3, dy)).astype(np.float32)
+    per_ex = rng.standard_normal((B, 2, dy)).astype(np.float32)
+    for name, seeds in (("identity", None), ("shared", shared), ("per-example", per_ex)):
+        check_lstm_jacobian(inp, f"lstm-odd[{name}]", seeds=seeds)
+
+
+def test_lstm_without_biases_and_skipped_outputs():
+    w = wl.LstmWorkload("nobias", 340, "lstm_per_example_grads", 6, 10, 4, 5, 7)
+    inp = wl.make_lstm_inputs(w)
+    net, full = check_lstm_grads(inp, "lstm-nobias", bias=False)
+    check_lstm_jacobian(inp, "lstm-nobias", bias=False)
+    X, labels = dev(inp.X), dev(inp.labels)
+    # only the readout gradients: the sweep through the steps is skipped
+    dW, db, dWout, dbout, loss = pfg.pfg_lstm_per_example_grads(net, X, labels, want_dW=False,
+                                                                want_db=False)
+    torch.cuda.synchronize()
+    assert dW is None and db is None
+    assert torch.equal(dWout, full[2]) and torch.equal(dbout, full[3]) and torch.equal(loss, full[4])
+    # only the recurrent weights' gradient
+    dW, db, dWout, dbout, loss = pfg.pfg_lstm_per_example_grads(net, X, labels, want_db=False,
+                                                                want_dWout=False, want_dbout=False,
+                                                                want_loss=False)
+    torch.cuda.synchronize()
+    assert db is None and dWout is None and dbout is None and loss is None
+    assert torch.equal(dW, full[0])
+
+
+def test_c7_lstm_grads_full_size():
+    w = wl.LSTM_WORKLOADS["c7_lstm_grads"]
+    say("c7_lstm_grads: full size (256 sequences of 10 steps), every element")
+    inp = wl.make_lstm_inputs(w)
+    net, got = check_lstm_grads(inp, "c7")
+    # iteration independence: permuting the batch permutes the results bit for bit
+    perm = np.random.default_rng(7).permutation(w.B)
+    got_p = pfg.pfg_lstm_per_example_grads(net, dev(inp.X[perm]), dev(inp.labels[perm]))
+    torch.cuda.synchronize()
+    tperm = torch.from_numpy(perm).to("cuda:0")
+    for name, a, b in zip(NAMES, got_p, got):
+        assert torch.equal(a, b[tperm]), f"{name} depends on the position in the batch"
+
+
+def test_c8_lstm_jacobian_reduced_every_element_and_full_size_sampled_rows():
+    w = wl.LSTM_WORKLOADS["c8_lstm_jacobian"]
+    say("c8 reduced (B=5, 72 outputs): every element")
+    inp = wl.make_lstm_inputs(w, B=5, dx=40, H=72, dy=72, T=6, bias_scale=0.2)
+    check_lstm_jacobian(inp, "c8-reduced")
+    say("c8_lstm_jacobian: full size, sampled rows (b, s)")
+    inp = wl.make_lstm_inputs(w)
+    onet, net = nets(inp)
+    J = pfg.pfg_lstm_jacobian_input(net, dev(inp.X), out=nan_like(w.B, w.S, w.T, w.dx))
+    torch.cuda.synchronize()
+    assert not torch.isnan(J).any().item(), "the Jacobian was not written in full"
+    rng = np.random.default_rng(8)
+    picks = {(0, 0), (w.B - 1, w.S - 1), (0, w.S - 1), (w.B - 1, 0), (17, 63), (17, 64)}
+    while len(picks) < 48:
+        picks.add((int(rng.integers(0, w.B)), int(rng.integers(0, w.S))))
+    worst = 0.0
+    for b, s in sorted(picks):
+        seed = np.zeros(w.dy)
+        seed[s] = 1.0
+        ref = olstm.body_jacobian_input_row(onet, inp.X[b], seed)
+        worst = max(worst, slice_rel_err(J[b, s].cpu().numpy(), ref, lead=0))
+    say(f"  c8 J sampled rel err {worst:.3e} over {len(picks)} rows")
+    assert worst <= TOL_F32
+
+
+def test_lstm_calls_replay_from_a_graph():
+    w = wl.LstmWorkload("graph", 341, "lstm_per_example_grads", 12, 20, 6, 4, 9)
+    inp = wl.make_lstm_inputs(w, bias_scale=0.2)
+    _, net = nets(inp)
+    X, labels = dev(inp.X), dev(inp.labels)
+    eager = pfg.pfg_lstm_per_example_grads(net, X, labels)
+    J_eager = pfg.pfg_lstm_jacobian_input(net, X)
+    torch.cuda.synchronize()
+    outs = [torch.empty_like(t) for t in eager]
+    J = torch.empty_like(J_eager)
+    ws_g = torch.empty(pfg.pfg_lstm_workspace_bytes(net, "per_example_grads", 9), dtype=torch.uint8,
+                       device="cuda:0")
+    ws_j = torch.empty(pfg.pfg_lstm_workspace_bytes(net, "jacobian_input", 9, 6), dtype=torch.uint8,
+                       device="cuda:0")
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(stream):
+        pfg.pfg_lstm_per_example_grads(net, X, labels, out=outs, workspace=ws_g)
+        pfg.pfg_lstm_jacobian_input(net, X, out=J, workspace=ws_j)
+    stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        pfg.pfg_lstm_per_example_grads(net, X, labels, out=outs, workspace=ws_g)
+        pfg.pfg_lstm_jacobian_input(net, X, out=J, workspace=ws_j)
+    for rep in range(3):
+        for t in outs + [J]:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(outs, eager)) and torch.equal(J, J_eager)
+
+
+def test_lstm_rejects_bad_arguments():
+    w = wl.LstmWorkload("bad", 342, "lstm_per_example_grads", 4, 6, 3, 2, 2)
+    inp = wl.make_lstm_inputs(w)
+    _, net = nets(inp)
+    X = dev(inp.X)
+    with pytest.raises(pfg.PfgError) as ei:
+        pfg.pfg_lstm_jacobian_input(net, X, S=5)              # identity seeds need S == output_size
+    assert ei.value.code == pfg.PFG_ERR_SHAPE
+    small = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(pfg.PfgError) as ei:
+        pfg.pfg_lstm_per_example_grads(net, X, dev(inp.labels), workspace=small)
+    assert ei.value.code == pfg.PFG_ERR_WORKSPACE
