@@ -278,6 +278,77 @@ def main():
             f"{rec['roofline']['frac']:.3f}")
         return rec, inp
 
+    def measure_lstm(name, steps, warmup):
+        w = wl.LSTM_WORKLOADS[name]
+        log(f"[bench] {name}: uploading inputs")
+        inp = wl.make_lstm_inputs(w)
+        net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, w.T)
+        X = torch.from_numpy(inp.X).to(dev)
+        labels = torch.from_numpy(inp.labels).to(dev)
+        f32 = dict(dtype=torch.float32, device=dev)
+        B, S, T, dx, H, dy = w.B, w.S, w.T, w.dx, w.H, w.dy
+        if w.call == "lstm_per_example_grads":
+            outs = [torch.empty(sh, **f32) for sh in ((B, dx + H, 4 * H), (B, 4 * H), (B, H, dy),
+                                                      (B, dy), (B,))]
+            ws = torch.empty(pfg.pfg_lstm_workspace_bytes(net, "per_example_grads", B),
+                             dtype=torch.uint8, device=dev)
+            step = lambda: pfg.pfg_lstm_per_example_grads(net, X, labels, out=outs, workspace=ws)
+            values = sum(t.numel() for t in outs)
+        else:
+            J = torch.empty((B, S, T, dx), **f32)
+            ws = torch.empty(pfg.pfg_lstm_workspace_bytes(net, "jacobian_input", B, S),
+                             dtype=torch.uint8, device=dev)
+            step = lambda: pfg.pfg_lstm_jacobian_input(net, X, out=J, workspace=ws)
+            values = J.numel()
+        step()
+        torch.cuda.synchronize()
+        log(f"[bench] {name}: timing {steps} steps")
+        sec = timed(step, steps, warmup)
+        sec_graph = None
+        if not args.no_graph:
+            try:
+                sec_graph = timed_graph(step, steps, warmup)
+            except Exception as e:
+                log(f"[bench] {name}: graph replay not measured ({e})")
+        kt = kernel_times(step, steps)
+        if w.call == "lstm_per_example_grads":
+            # the weight gradient is the one large output: 4 bytes per value of dW
+            fam = "outer_sum"
+            nbytes = 4 * B * (dx + H) * 4 * H
+            per_ms = kt[fam]["ms_per_step"] / kt[fam]["launches_per_step"]
+            gbs = nbytes / kt[fam]["ms_per_step"] / 1e6
+            roof = {"kernel": fam, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                    "bytes_per_launch": nbytes / kt[fam]["launches_per_step"], "ms_per_launch": per_ms,
+                    "launches_per_step": kt[fam]["launches_per_step"]}
+        else:
+            rows = B * S
+            fams = ("lstm_gemm_jacobian", "lstm_gemm_cotangent")
+            flops = T * 2 * rows * 4 * H * dx + (T - 1) * 2 * rows * 4 * H * H
+            ms = sum(kt[f]["ms_per_step"] for f in fams)
+            launches = sum(kt[f]["launches_per_step"] for f in fams)
+            tf = flops / ms / 1e9
+            roof = {"kernel": "+".join(fams), "bound": "mfma", "achieved": tf,
+                    "peak": MFMA_PEAK_TFLOPS["f32"], "unit": "TFLOP/s",
+                    "frac": tf / MFMA_PEAK_TFLOPS["f32"], "traffic": None,
+                    "flops_per_launch": flops / launches, "ms_per_launch": ms / launches,
+                    "launches_per_step": launches}
+        rec = {"workload": name, "call": w.call, "input_size": dx, "state_size": H, "output_size": dy,
+               "unrolled_steps": T, "dtype": "f32", "B": B, "S": S, "steps": steps,
+               "ms_per_step": sec * 1e3,
+               "ms_per_step_graph_replay": None if sec_graph is None else sec_graph * 1e3,
+               "output_values": values, "output_GB": values * 4 / 1e9, "kernels": kt,
+               "kernel_ms_sum": sum(v["ms_per_step"] for v in kt.values()),
+               "launches_per_step": sum(v["launches_per_step"] for v in kt.values()),
+               "roofline": roof}
+        if w.call == "lstm_per_example_grads":
+            rec["per_example_grads_per_sec"] = B / sec
+        else:
+            rec["jacobian_rows_per_sec"] = B * S / sec
+            rec["jacobian_entries_per_sec"] = values / sec
+        log(f"[bench] {name}: {rec['ms_per_step']:.4f} ms/step, roofline frac {roof['frac']:.3f}")
+        return rec, inp
+
     if args.copy_reference:
         # out = src + 1 over 64 Mi float32: reads 256 MiB and writes 256 MiB per launch
         n = 64 * 1024 * 1024
@@ -291,7 +362,8 @@ def main():
         return
 
     if args.workload:
-        rec, _ = measure(args.workload, args.steps, args.warmup)
+        fn = measure_lstm if args.workload in wl.LSTM_WORKLOADS else measure
+        rec, _ = fn(args.workload, args.steps, args.warmup)
         print(json.dumps(rec), flush=True)
         return
 
@@ -323,9 +395,12 @@ def main():
                             ("c4_gelu_bf16_grads", max(3, args.steps // 20)),
                             ("c2_mnist_mlp_grad_norms", args.steps),
                             ("c4_gelu_bf16_grad_norms", max(3, args.steps // 4)),
-                            ("c6_tanh_hessian", max(3, args.steps // 20))):
+                            ("c6_tanh_hessian", max(3, args.steps // 20)),
+                            ("c7_lstm_grads", max(3, args.steps // 2)),
+                            ("c8_lstm_jacobian", max(3, args.steps // 10))):
             try:
-                others[name], _ = measure(name, steps, max(1, min(args.warmup, steps // 2)))
+                fn = measure_lstm if name in wl.LSTM_WORKLOADS else measure
+                others[name], _ = fn(name, steps, max(1, min(args.warmup, steps // 2)))
             except Exception as e:
                 others[name] = {"error": str(e)}
             torch.cuda.empty_cache()

@@ -199,6 +199,59 @@ def test_hessian_workspace_and_rejections(lib):
     assert "float32" in lib.pfg_last_error().decode()
 
 
+def make_lstm(dx=128, H=256, dy=10, T=10, dtype=0, W=FAKE, W_out=FAKE):
+    return pfg.pfg_lstm(dx, H, dy, T, W, None, W_out, None, dtype)
+
+
+def lstm_ws(lib, net, op, B, S):
+    n = ctypes.c_size_t(0)
+    rc = lib.pfg_lstm_workspace_bytes(ctypes.byref(net), op, B, S, ctypes.byref(n))
+    return rc, n.value
+
+
+def test_lstm_workspace_and_rejections(lib):
+    net = make_lstm()
+    B, T, H, dy = 256, 10, 256, 10
+    fwd = 2 * up(4 * B * T * 4 * H) + up(4 * B * 4 * H) + 2 * up(4 * B * T * H)
+    grads = fwd + 2 * up(4 * B * dy) + 2 * up(4 * B * H) + up(4 * B * T * 4 * H)
+    assert lstm_ws(lib, net, 0, B, 1) == (0, grads)
+    assert lstm_ws(lib, net, 0, B, 99) == (0, grads)          # S is ignored
+    jac_net = make_lstm(dy=128)
+    B, S = 64, 128
+    fwd = 2 * up(4 * B * T * 4 * H) + up(4 * B * 4 * H) + 2 * up(4 * B * T * H)
+    assert lstm_ws(lib, jac_net, 1, B, S) == (0, fwd + up(4 * S * H) + 2 * up(4 * B * S * H) +
+                                              up(4 * B * S * 4 * H))
+    assert lstm_ws(lib, net, 2, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
+    assert lstm_ws(lib, net, 0, 0, 1)[0] == pfg.PFG_ERR_SHAPE
+    assert lstm_ws(lib, net, 1, 1, 0)[0] == pfg.PFG_ERR_SHAPE
+    assert lstm_ws(lib, net, 1, 1 << 20, 1 << 20)[0] == pfg.PFG_ERR_OVERFLOW
+    assert lstm_ws(lib, make_lstm(H=0), 0, 1, 1)[0] == pfg.PFG_ERR_SHAPE
+    assert lstm_ws(lib, make_lstm(T=0), 0, 1, 1)[0] == pfg.PFG_ERR_SHAPE
+    assert lstm_ws(lib, make_lstm(dtype=1), 0, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
+    assert lstm_ws(lib, make_lstm(W=None), 0, 1, 1)[0] == pfg.PFG_ERR_NULL
+    assert lstm_ws(lib, make_lstm(W_out=None), 0, 1, 1)[0] == pfg.PFG_ERR_NULL
+    n = ctypes.c_size_t(0)
+    assert lib.pfg_lstm_workspace_bytes(None, 0, 1, 1, ctypes.byref(n)) == pfg.PFG_ERR_NULL
+    assert lib.pfg_lstm_workspace_bytes(ctypes.byref(net), 0, 1, 1, None) == pfg.PFG_ERR_NULL
+
+    big = 1 << 40
+    r = ctypes.byref(net)
+    gr = lib.pfg_lstm_per_example_grads
+    assert gr(r, None, FAKE, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert gr(r, FAKE, None, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert gr(r, FAKE, FAKE, 0, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+    assert gr(r, FAKE, FAKE, 2, FAKE, FAKE, FAKE, FAKE, FAKE, None, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert gr(r, FAKE, FAKE, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 4, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert gr(r, FAKE, FAKE, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, None) == pfg.PFG_ERR_WORKSPACE
+    ja = lib.pfg_lstm_jacobian_input
+    assert ja(r, None, 2, None, 10, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert ja(r, FAKE, 2, None, 10, 0, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert ja(r, FAKE, 2, None, 7, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE       # identity seeds
+    assert "identity" in lib.pfg_last_error().decode()
+    assert ja(r, FAKE, 2, FAKE, 3, 5, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE       # stride < S * dy
+    assert ja(r, FAKE, 2, None, 10, 0, FAKE, FAKE, 8, None) == pfg.PFG_ERR_WORKSPACE
+
+
 def test_last_error_is_cleared_by_a_good_call(lib):
     net = make_net([4, 3, 2])
     assert ws_bytes(lib, net, 9, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
