@@ -323,7 +323,8 @@ def main():
                     "launches_per_step": kt[fam]["launches_per_step"]}
         else:
             rows = B * S
-            fams = ("lstm_gemm_jacobian", "lstm_gemm_cotangent")
+            # one product per step: [dx_t | dh_{t-1}] = dz_t [W_x ; W_h]^T (no dh for the first step)
+            fams = ("lstm_gemm_reverse",)
             flops = T * 2 * rows * 4 * H * dx + (T - 1) * 2 * rows * 4 * H * H
             ms = sum(kt[f]["ms_per_step"] for f in fams)
             launches = sum(kt[f]["launches_per_step"] for f in fams)

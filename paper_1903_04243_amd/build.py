@@ -13,11 +13,14 @@ OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["gemm.hip", "gemm_skinny.hip", "writer.hip", "elementwise.hip", "lstm.hip", "pfg.hip",
            "pfg_lstm.hip"]
 HEADERS = [os.path.join(CSRC, "common.h"), os.path.join(CSRC, "gemm_device.h"),
-           os.path.join(os.path.dirname(HERE), "include", "pfg.h")]
+           os.path.join(CSRC, "host.h"), os.path.join(os.path.dirname(HERE), "include", "pfg.h")]
 # packed-fp32 arithmetic is switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument"]
+         "-Wno-unused-command-line-argument", "-Rpass-analysis=kernel-resource-usage",
+         # an array indexed at run time must show up as scratch (and be refused below), not be moved
+         # silently into LDS, which costs a read of the dispatch packet at every kernel start
+         "-mllvm", "-disable-promote-alloca-to-lds"]
 
 
 def _hipcc() -> str:
@@ -52,6 +55,21 @@ def build(force: bool = False, verbose: bool = False) -> str:
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + r.stdout + r.stderr)
+        # A kernel that needs scratch memory (an array indexed at run time, or register spills) pays
+        # for it on every launch, which the latency-bound kernels here cannot afford: refuse it.
+        name, bad = None, []
+        for line in r.stderr.splitlines():
+            if "Function Name:" in line:
+                name = line.split("Function Name:")[1].split("[")[0].strip()
+            elif "ScratchSize [bytes/lane]:" in line:
+                size = int(line.split("ScratchSize [bytes/lane]:")[1].split("[")[0])
+                if size:
+                    bad.append(f"{name}: {size} bytes of scratch per lane")
+        if bad:
+            out = cmd[-1]
+            if os.path.exists(out) and out.endswith(".o"):
+                os.remove(out)
+            raise RuntimeError("kernels that use scratch memory in " + cmd[-3] + ":\n" + "\n".join(bad))
 
     with ThreadPoolExecutor(max_workers=4) as ex:
         list(ex.map(run, jobs))

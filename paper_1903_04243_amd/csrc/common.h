@@ -34,9 +34,13 @@ enum Epilogue : int {
   EPI_BIAS = 1,      // C = acc + bias                      (last forward layer: logits)
   EPI_FORWARD = 2,   // z = acc + bias; C = phi(z); C2 = phi'(z)   (hidden forward layer)
   EPI_MASK = 3,      // C = acc * emask[m / S, n]           (cotangent step)
-  EPI_HEAD = 4       // y = acc + bias (N <= 32, optional C = y); C2 = softmax(y) - onehot(label);
+  EPI_HEAD = 4,      // y = acc + bias (N <= 32, optional C = y); C2 = softmax(y) - onehot(label);
                      // loss = -log softmax(y)[label]       (last forward layer fused with the head,
                      // and optionally with the cotangent step through that layer)
+  EPI_LSTM_BWD = 5   // columns n < n_split: C = acc.  A column n >= n_split is dh[m, k], k = n - n_split,
+                     // the cotangent of the hidden state entering LSTM step lstm_step + 1; it is not
+                     // stored but carried through the reverse cell update of step lstm_step at once
+                     // (writes that step's dz row and the running dc).
 };
 
 // One matrix product  C[M, N] = Aeff[M, K] * Weff[K, N]  with fused prologue and epilogue.
@@ -84,6 +88,14 @@ struct GemmArgs {
   // W + z * batch_W (float32 weights only) and C + z * batch_C (strides in elements).  EPI_NONE only.
   int32_t nbatch;
   int64_t batch_A, batch_scale, batch_W, batch_C;
+  // EPI_LSTM_BWD (row m belongs to example m / S, whose gates and cell states are shared by its S rows)
+  int32_t n_split;
+  int32_t lstm_H, lstm_T, lstm_step;
+  const float *lstm_gates;   // [B, T, 4H] gate activations i, g, f, o
+  const float *lstm_cs;      // [B, T, H] cell states
+  float *lstm_dc;            // [M, H] running cotangent of the cell state, updated in place
+  float *lstm_dz;            // row m at lstm_dz + m * lstm_dz_ld, 4H wide: dz of step lstm_step
+  int64_t lstm_dz_ld;
 };
 
 // Picks the LDS-tiled kernel or the small-problem kernel.
@@ -166,11 +178,17 @@ hipError_t launch_lstm_cell_backward(const float *dh, int64_t dh_batch_stride, f
                                      int32_t H, int32_t T, int32_t t, float *dz, int64_t dz_row_stride,
                                      hipStream_t stream);
 
-// out[b * out_bs + i * d_out + j] = sum_{t < nt} a[b * a_bs + t * a_ts + i] * g[b * g_bs + t * g_ts + j]
-// for i < d_in, j < d_out (float32; nt <= 0 writes zeros)
-hipError_t launch_outer_sum(const float *a, int64_t a_bs, int64_t a_ts, const float *g, int64_t g_bs,
-                            int64_t g_ts, int32_t nt, int64_t B, int32_t d_in, int32_t d_out,
-                            float *out, int64_t out_bs, hipStream_t stream);
+// One or two row blocks of a per-example matrix, each a sum of outer products over steps:
+//   out[b * out_bs + i * d_out + j] = sum_{t < nt} a[b * a_bs + t * a_ts + i] * g[b * g_bs + t * g_ts + j]
+// for i < d_in, j < d_out (float32; nt <= 0 writes zeros).  `out` of a job points at its first row.
+struct OuterSumJob {
+  const float *a; int64_t a_bs, a_ts;
+  const float *g; int64_t g_bs, g_ts;
+  int32_t nt, d_in;
+  float *out;
+};
+hipError_t launch_outer_sum(const OuterSumJob *jobs, int njobs, int64_t B, int32_t d_out,
+                            int64_t out_bs, hipStream_t stream);
 
 // out[b, j] = sum_{t < T} g[b, t, j]
 hipError_t launch_sum_steps(const float *g, int64_t B, int32_t T, int32_t d, float *out,

@@ -25,18 +25,20 @@ using namespace dev;
 
 // WGM x WGN: arrangement of the workgroup's waves over the tile (2 x 2, or 4 x 2 for the largest).
 template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs gk) {
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) {
   constexpr int kThreads = 64 * WGM * WGN;
   constexpr bool BF16 = (AMODE != A_F32);
   constexpr int ELEM = BF16 ? 2 : 4;
   // batched product: the second grid index selects the product; its operands sit at fixed strides
-  GemmArgs g = gk;
-  if (gk.nbatch > 1) {
+  const void *gA = g.A, *gW = g.W;
+  const float *gScale = g.a_scale;
+  float *gC = g.C;
+  if (g.nbatch > 1) {
     const int64_t z = blockIdx.y;
-    g.A = static_cast<const char *>(gk.A) + z * gk.batch_A * (AMODE == A_BF16 ? 2 : 4);
-    g.W = static_cast<const char *>(gk.W) + z * gk.batch_W * ELEM;
-    if (gk.a_scale) g.a_scale = gk.a_scale + z * gk.batch_scale;
-    g.C = gk.C + z * gk.batch_C;
+    gA = static_cast<const char *>(g.A) + z * g.batch_A * (AMODE == A_BF16 ? 2 : 4);
+    gW = static_cast<const char *>(g.W) + z * g.batch_W * ELEM;
+    if (g.a_scale) gScale = g.a_scale + z * g.batch_scale;
+    gC = g.C + z * g.batch_C;
   }
   constexpr int EPC = 16 / ELEM;            // elements per 16-byte chunk
   constexpr int BK = BKB / ELEM;            // k elements per stage
@@ -77,14 +79,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs gk)
   const int n0 = tile_n * BN;
   const int M = g.M, N = g.N, K = g.K;
 
-  const bool a_vec_ok = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
+  const bool a_vec_ok = ((reinterpret_cast<uintptr_t>(gA) & 15) == 0) &&
                         ((g.lda * (AMODE == A_BF16 ? 2 : 4)) % 16 == 0) &&
                         ((g.a_batch_stride * (AMODE == A_BF16 ? 2 : 4)) % 16 == 0);
-  const bool s_vec_ok = g.a_scale && ((reinterpret_cast<uintptr_t>(g.a_scale) & 15) == 0) &&
+  const bool s_vec_ok = gScale && ((reinterpret_cast<uintptr_t>(gScale) & 15) == 0) &&
                         ((g.ld_scale * 4) % 16 == 0);
-  const bool w_vec_ok = ((reinterpret_cast<uintptr_t>(g.W) & 15) == 0) &&
+  const bool w_vec_ok = ((reinterpret_cast<uintptr_t>(gW) & 15) == 0) &&
                         ((g.ldw * ELEM) % 16 == 0);
-  const bool scaled = (g.a_scale != nullptr);
+  const bool scaled = (gScale != nullptr);
 
   // ---- per-thread staging assignments ----
   const void *a_row[A_CHUNKS];
@@ -105,10 +107,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs gk)
       const int64_t b = mc / g.S, s = mc % g.S;
       const int64_t off = b * g.a_batch_stride + s * g.lda;
       if constexpr (AMODE == A_BF16)
-        a_row[c] = static_cast<const __bf16 *>(g.A) + off;
+        a_row[c] = static_cast<const __bf16 *>(gA) + off;
       else
-        a_row[c] = static_cast<const float *>(g.A) + off;
-      if (scaled) a_srow[c] = g.a_scale + b * g.ld_scale;
+        a_row[c] = static_cast<const float *>(gA) + off;
+      if (scaled) a_srow[c] = gScale + b * g.ld_scale;
     }
   }
 
@@ -132,9 +134,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs gk)
       if (FAST || n < N) {
         const int nc = FAST ? min(n, N - 1) : n;
         if constexpr (BF16)
-          w_row[c] = static_cast<const __bf16 *>(g.W) + (int64_t)nc * g.ldw;
+          w_row[c] = static_cast<const __bf16 *>(gW) + (int64_t)nc * g.ldw;
         else
-          w_row[c] = static_cast<const float *>(g.W) + (int64_t)nc * g.ldw;
+          w_row[c] = static_cast<const float *>(gW) + (int64_t)nc * g.ldw;
       }
     } else if constexpr (WTR) {
       constexpr int NGR = BN / 8;                  // 16-byte pieces per tile row
@@ -174,19 +176,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs gk)
       const int k = kbase + w_k[c];
       const int64_t roff = (int64_t)min(k, K - 1) * g.ldw;
       if constexpr (BF16)
-        rw[c] = load8_bf16_fast(static_cast<const __bf16 *>(g.W) + roff, w_n[c], N);
+        rw[c] = load8_bf16_fast(static_cast<const __bf16 *>(gW) + roff, w_n[c], N);
       else
         rw[c] = __builtin_bit_cast(
-            u32x4, load4_f32_fast(static_cast<const float *>(g.W) + roff, w_n[c], N));
+            u32x4, load4_f32_fast(static_cast<const float *>(gW) + roff, w_n[c], N));
     } else {
       const int k = kbase + w_k[c];
       u32x4 v = {0u, 0u, 0u, 0u};
       if (k < K) {
         if constexpr (BF16) {
-          const __bf16 *row = static_cast<const __bf16 *>(g.W) + (int64_t)k * g.ldw;
+          const __bf16 *row = static_cast<const __bf16 *>(gW) + (int64_t)k * g.ldw;
           v = load8_bf16(w_n[c] < N ? row : nullptr, w_n[c], N, w_vec_ok);
         } else {
-          const float *row = static_cast<const float *>(g.W) + (int64_t)k * g.ldw;
+          const float *row = static_cast<const float *>(gW) + (int64_t)k * g.ldw;
           v = __builtin_bit_cast(u32x4, load4_f32(w_n[c] < N ? row : nullptr, w_n[c], N, w_vec_ok));
         }
       }
@@ -379,6 +381,42 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs gk)
   // ---- epilogue: accumulator element r of lane (half, l32) is row 8 (r / 4) + 4 half + r % 4,
   // column l32 of its 32 x 32 tile ----
   const int epi = g.epilogue;
+  if constexpr (AMODE == A_F32) {
+    if (epi == EPI_LSTM_BWD) {
+      // The reverse cell update is long; running it from the unrolled register loop below would
+      // replicate it 16 TM TN times.  The tile goes through LDS (free after the last stage) and a
+      // rolled loop finishes it, consecutive threads on consecutive columns.
+      constexpr int TS = BN + 1;
+      static_assert(BM * TS * 4 <= 2 * STAGE, "the output tile must fit the staging buffers");
+      float *tile = reinterpret_cast<float *>(smem);
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            tile[(wm + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3)) * TS + wn + j * 32 + l32] =
+                acc[i][j][r];
+      __syncthreads();
+      for (int e = tid; e < BM * BN; e += kThreads) {
+        const int row = e / BN, col = e % BN;
+        const int m = m0 + row, n = n0 + col;
+        if (m >= M || n >= N) continue;
+        const float v = tile[row * TS + col];
+        if (n < g.n_split) {
+          if (g.streaming)
+            __builtin_nontemporal_store(v, gC + (int64_t)m * g.ldc + n);
+          else
+            gC[(int64_t)m * g.ldc + n] = v;
+        } else {
+          lstm_reverse_cell(g.lstm_gates, g.lstm_cs, g.lstm_dc, g.lstm_dz, g.lstm_dz_ld, g.lstm_H,
+                            g.lstm_T, g.lstm_step, g.S, m, n - g.n_split, v);
+        }
+      }
+      return;
+    }
+  }
   float bias[TN];
   bool n_ok[TN];
 #pragma unroll
@@ -409,7 +447,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs gk)
         if (epi == EPI_FORWARD) {
           const float z = v + bias[j];
           g.C2[o] = act_deriv(g.act, z);
-          if (g.C == nullptr) continue;       // only phi'(z) is wanted
+          if (gC == nullptr) continue;       // only phi'(z) is wanted
           v = act_value(g.act, z);
         } else if (epi == EPI_BIAS) {
           v += bias[j];
@@ -417,9 +455,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs gk)
           v *= mrow[n];
         }
         if (g.streaming)
-          __builtin_nontemporal_store(v, g.C + o);
+          __builtin_nontemporal_store(v, gC + o);
         else
-          g.C[o] = v;
+          gC[o] = v;
       }
     }
   }
@@ -471,6 +509,8 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
 
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipSuccess;
+  if (g.epilogue == EPI_LSTM_BWD && (g.N - g.n_split != g.lstm_H || g.n_split < 0 || g.bf16))
+    return hipErrorInvalidValue;
   if (g.nbatch > 1 && (g.epilogue != EPI_NONE || g.nbatch > 65535))
     return hipErrorInvalidValue;
   // Fewer than 128 tiles of 64 x 64 cannot occupy the chip: such products (M = B rows, or a

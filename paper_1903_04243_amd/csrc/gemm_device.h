@@ -40,6 +40,30 @@ __device__ __forceinline__ float act_deriv2(int act, float z) {
   }
 }
 
+// Reverse LSTM cell update of step t for row m (example m / S), unit k, given dh = the cotangent of
+// that step's hidden state:
+//   dc   += dh * o * (1 - tanh(c_t)^2)
+//   dz_o  = dh * tanh(c_t) * o (1 - o)
+//   dz_i  = dc * g * i (1 - i),  dz_g = dc * i * (1 - g^2),  dz_f = dc * c_{t-1} * f (1 - f)
+//   dc_{t-1} = dc * f
+__device__ __forceinline__ void lstm_reverse_cell(const float *gates, const float *cs, float *dc,
+                                                  float *dz, int64_t dz_ld, int H, int T, int t,
+                                                  int S, int m, int k, float dh) {
+  const int64_t b = m / S;
+  const float *grow = gates + (b * T + t) * 4 * (int64_t)H;
+  const float i = grow[k], g = grow[H + k], f = grow[2 * H + k], o = grow[3 * H + k];
+  const float tc = tanhf(cs[(b * T + t) * (int64_t)H + k]);
+  const float cprev = t > 0 ? cs[(b * T + t - 1) * (int64_t)H + k] : 0.f;
+  float *dcp = dc + (int64_t)m * H + k;
+  const float dct = *dcp + dh * o * (1.f - tc * tc);
+  float *out = dz + (int64_t)m * dz_ld;
+  out[k] = dct * g * i * (1.f - i);
+  out[H + k] = dct * i * (1.f - g * g);
+  out[2 * H + k] = dct * cprev * f * (1.f - f);
+  out[3 * H + k] = dh * tc * o * (1.f - o);
+  *dcp = dct * f;
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
   bf16x2 v = {(__bf16)lo, (__bf16)hi};

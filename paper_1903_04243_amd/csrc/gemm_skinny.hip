@@ -200,7 +200,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   const bool all_in = row_in && (nn + Q <= N);
   const int64_t off = (int64_t)m * g.ldc + nn;
   const bool want_bias = (epi == EPI_BIAS || epi == EPI_FORWARD || epi == EPI_HEAD) && g.bias;
-  float aux[Q];                                  // bias (added) or mask (multiplied)
+  // Q-wide register vectors (not arrays: an array indexed inside a rolled loop would be moved out
+  // of registers)
+  typedef float fq __attribute__((ext_vector_type(Q)));
+  fq aux;                                        // bias (added) or mask (multiplied)
 #pragma unroll
   for (int q = 0; q < Q; ++q) aux[q] = (epi == EPI_MASK) ? 1.f : 0.f;
   if (row_in) {
@@ -213,7 +216,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
     } else if (epi == EPI_MASK) {
       const float *mp = g.emask + (int64_t)(m / g.S) * g.ld_emask + nn;
       if (all_in && ((reinterpret_cast<uintptr_t>(mp) & (4 * Q - 1)) == 0)) {
-        typedef float fq __attribute__((ext_vector_type(Q)));
         const fq mv = *reinterpret_cast<const fq *>(mp);
 #pragma unroll
         for (int q = 0; q < Q; ++q) aux[q] = mv[q];
@@ -274,7 +276,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   // its Q results, again as one vector when possible.  One pass, no loop: with so few waves the
   // latency of every dependent global access counts.
   {
-    float v[Q];
+    fq v;
 #pragma unroll
     for (int q = 0; q < Q; ++q) v[q] = 0.f;
 #pragma unroll
@@ -290,7 +292,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
         if (row_in && nn + q < N && g.C && second == 0) g.C[off + q] = v[q];
       }
     } else if (row_in) {
-      float out2[Q];
+      fq out2;
       if (epi == EPI_FORWARD) {
 #pragma unroll 1
         for (int q = 0; q < Q; ++q) {              // rolled: the activation code is long
@@ -305,7 +307,26 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
 #pragma unroll
         for (int q = 0; q < Q; ++q) v[q] *= aux[q];
       }
-      typedef float fq __attribute__((ext_vector_type(Q)));
+      if (epi == EPI_LSTM_BWD && nn + Q > g.n_split) {
+        // this thread's columns reach into the hidden-state cotangent: element by element, with
+        // constant indices into v[] (an index known only at run time would move the array out of
+        // registers)
+        auto finish = [&](int q, float val) {
+          if (nn + q >= N) return;
+          if (nn + q < g.n_split)
+            g.C[off + q] = val;
+          else
+            lstm_reverse_cell(g.lstm_gates, g.lstm_cs, g.lstm_dc, g.lstm_dz, g.lstm_dz_ld, g.lstm_H,
+                              g.lstm_T, g.lstm_step, g.S, m, nn + q - g.n_split, val);
+        };
+        finish(0, v[0]);
+        finish(1, v[1]);
+        if constexpr (Q == 4) {
+          finish(2, v[2]);
+          finish(3, v[3]);
+        }
+        return;     // nothing follows the epilogue for this kind of product
+      }
       const bool vec_c = all_in && g.C && ((reinterpret_cast<uintptr_t>(g.C + off) & (4 * Q - 1)) == 0);
       const bool vec_c2 = all_in && (epi == EPI_FORWARD) &&
                           ((reinterpret_cast<uintptr_t>(g.C2 + off) & (4 * Q - 1)) == 0);

@@ -72,52 +72,71 @@ __global__ __launch_bounds__(kThreads) void lstm_cell_backward_kernel(
 
 // out[b, i, j] = sum_{t < nt} a[b * a_bs + t * a_ts + i] * g[b * g_bs + t * g_ts + j]
 // (Section 3.4's both-operands-stacked matmul with a contraction over the time steps).  A lane keeps
-// its four columns of all nt cotangent rows in registers and walks the rows i of its chunk, whose
-// a values are uniform over the workgroup.  kMaxSteps steps per pass; later passes add to the result.
+// its four columns of all nt cotangent rows in registers and walks the rows i of its chunk; the a
+// values of the chunk (uniform over the workgroup) are fetched once into LDS.  kMaxSteps steps per
+// pass; later passes add to the result.  One launch covers up to two row blocks of the same
+// per-example matrix (here: the input rows and the recurrent rows of the LSTM weight gradient).
 constexpr int kMaxSteps = 16;
 constexpr int kRowsPerBlock = 16;
 
-struct OuterSumArgs {
+struct OuterSumPart {
   const float *a; int64_t a_bs, a_ts;
   const float *g; int64_t g_bs, g_ts;
   float *out;            // example b at out + b * out_bs, [d_in, d_out]
+  int d_in, nt;
+  int row_chunks;        // ceil(d_in / kRowsPerBlock)
+};
+
+struct OuterSumArgs {
+  OuterSumPart part[2];
+  int nparts;
   int64_t out_bs;
-  int d_in, d_out, nt;
+  int d_out;
   int accumulate;        // add to out instead of overwriting it
   int vec;               // d_out % 4 == 0 and g, out 16-byte aligned with aligned strides
 };
 
 __global__ __launch_bounds__(kThreads) void outer_sum_kernel(const OuterSumArgs p) {
+  __shared__ float a_s[kMaxSteps][kRowsPerBlock];
   const int64_t b = blockIdx.y;
   const int col_chunks = (p.d_out + 4 * kThreads - 1) / (4 * kThreads);
-  const int cchunk = blockIdx.x % col_chunks, rchunk = blockIdx.x / col_chunks;
+  const int cchunk = blockIdx.x % col_chunks;
+  int rchunk = blockIdx.x / col_chunks;
+  const bool second = (p.nparts > 1) && (rchunk >= p.part[0].row_chunks);
+  const OuterSumPart &q = p.part[second ? 1 : 0];
+  if (second) rchunk -= p.part[0].row_chunks;
   const int i0 = rchunk * kRowsPerBlock;
-  const int i1 = min(p.d_in, i0 + kRowsPerBlock);
-  const float *a = p.a + b * p.a_bs;
-  const float *g = p.g + b * p.g_bs;
-  float *out = p.out + b * p.out_bs;
+  const int nrows = min(q.d_in - i0, kRowsPerBlock);
+  const float *a = q.a + b * q.a_bs;
+  const float *g = q.g + b * q.g_bs;
+  float *out = q.out + b * p.out_bs;
+  // the chunk's a values: one coalesced fetch of nt rows of 16 values
+  for (int e = threadIdx.x; e < kMaxSteps * kRowsPerBlock; e += kThreads) {
+    const int t = e / kRowsPerBlock, r = e % kRowsPerBlock;
+    a_s[t][r] = (t < q.nt && r < nrows) ? a[t * q.a_ts + i0 + r] : 0.f;
+  }
+  __syncthreads();
   const int j = (cchunk * kThreads + threadIdx.x) * 4;
   if (j >= p.d_out) return;
   f32x4 gv[kMaxSteps];
 #pragma unroll
   for (int t = 0; t < kMaxSteps; ++t) {
     gv[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (t < p.nt) {
+    if (t < q.nt) {
       if (p.vec) {
-        gv[t] = *reinterpret_cast<const f32x4 *>(g + t * p.g_ts + j);
+        gv[t] = *reinterpret_cast<const f32x4 *>(g + t * q.g_ts + j);
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if (j + e < p.d_out) gv[t][e] = g[t * p.g_ts + j + e];
+          if (j + e < p.d_out) gv[t][e] = g[t * q.g_ts + j + e];
       }
     }
   }
-  for (int i = i0; i < i1; ++i) {
+  for (int r = 0; r < nrows; ++r) {
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int t = 0; t < kMaxSteps; ++t)
-      if (t < p.nt) acc += a[t * p.a_ts + i] * gv[t];
-    float *o = out + (int64_t)i * p.d_out + j;
+    for (int t = 0; t < kMaxSteps; ++t) acc += a_s[t][r] * gv[t];     // steps past nt hold zeros
+    float *o = out + (int64_t)(i0 + r) * p.d_out + j;
     if (p.vec) {
       if (p.accumulate)
         *reinterpret_cast<f32x4 *>(o) = *reinterpret_cast<const f32x4 *>(o) + acc;
@@ -166,30 +185,44 @@ hipError_t launch_lstm_cell_backward(const float *dh, int64_t dh_batch_stride, f
   return hipGetLastError();
 }
 
-hipError_t launch_outer_sum(const float *a, int64_t a_bs, int64_t a_ts, const float *g, int64_t g_bs,
-                            int64_t g_ts, int32_t nt, int64_t B, int32_t d_in, int32_t d_out,
-                            float *out, int64_t out_bs, hipStream_t stream) {
-  if (B <= 0 || d_in <= 0 || d_out <= 0) return hipSuccess;
+hipError_t launch_outer_sum(const OuterSumJob *jobs, int njobs, int64_t B, int32_t d_out,
+                            int64_t out_bs, hipStream_t stream) {
+  if (B <= 0 || d_out <= 0 || njobs <= 0) return hipSuccess;
+  if (njobs > 2) return hipErrorInvalidValue;
   auto aligned = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-  const int vec = d_out % 4 == 0 && aligned(g) && aligned(out) && g_bs % 4 == 0 && g_ts % 4 == 0 &&
-                  out_bs % 4 == 0;
+  int vec = d_out % 4 == 0 && out_bs % 4 == 0;
+  int max_nt = 0;
+  for (int k = 0; k < njobs; ++k) {
+    vec = vec && aligned(jobs[k].g) && aligned(jobs[k].out) && jobs[k].g_bs % 4 == 0 &&
+          jobs[k].g_ts % 4 == 0;
+    max_nt = jobs[k].nt > max_nt ? jobs[k].nt : max_nt;
+  }
   const int col_chunks = (d_out + 4 * kThreads - 1) / (4 * kThreads);
-  const int row_chunks = (d_in + kRowsPerBlock - 1) / kRowsPerBlock;
-  if (nt < 0) nt = 0;        // no step contributes: the block is written as zeros
   for (int64_t b0 = 0; b0 < B; b0 += 32768) {          // the second grid index holds 65535 at most
     const int64_t nb = B - b0 < 32768 ? B - b0 : 32768;
     int t0 = 0;
     do {
-      OuterSumArgs p{a + b0 * a_bs + (int64_t)t0 * a_ts, a_bs, a_ts,
-                     g + b0 * g_bs + (int64_t)t0 * g_ts, g_bs, g_ts,
-                     out + b0 * out_bs, out_bs, d_in, d_out,
-                     nt - t0 < kMaxSteps ? nt - t0 : kMaxSteps, t0 > 0, vec};
+      OuterSumArgs p{};
+      int row_chunks = 0;
+      for (int k = 0; k < njobs; ++k) {
+        const OuterSumJob &jb = jobs[k];
+        int nt = jb.nt - t0;                           // a job with no step left contributes zeros
+        nt = nt < 0 ? 0 : (nt > kMaxSteps ? kMaxSteps : nt);
+        OuterSumPart &q = p.part[k];
+        q.a = jb.a + b0 * jb.a_bs + (int64_t)t0 * jb.a_ts; q.a_bs = jb.a_bs; q.a_ts = jb.a_ts;
+        q.g = jb.g + b0 * jb.g_bs + (int64_t)t0 * jb.g_ts; q.g_bs = jb.g_bs; q.g_ts = jb.g_ts;
+        q.out = jb.out + b0 * out_bs;
+        q.d_in = jb.d_in; q.nt = nt;
+        q.row_chunks = (jb.d_in + kRowsPerBlock - 1) / kRowsPerBlock;
+        row_chunks += q.row_chunks;
+      }
+      p.nparts = njobs; p.out_bs = out_bs; p.d_out = d_out; p.accumulate = t0 > 0; p.vec = vec;
       PFG_KERNEL(outer_sum_kernel, dim3((unsigned)(col_chunks * row_chunks), (unsigned)nb),
                  dim3(kThreads), 0, stream, p);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
       t0 += kMaxSteps;
-    } while (t0 < nt);
+    } while (t0 < max_nt);
   }
   return hipSuccess;
 }

@@ -58,7 +58,7 @@ int check_lstm_seeds(const pfg_lstm *net, const float *seeds, int64_t S, int64_t
 struct LstmPlan {
   size_t total = 0;
   size_t zx = 0, zh = 0, gates = 0, cs = 0, hs = 0;   // forward
-  size_t y = 0, dy = 0, dh = 0, dc = 0, dz = 0, P = 0;
+  size_t y = 0, dy = 0, dh = 0, dc = 0, dz = 0, dz2 = 0, P = 0;
   size_t take(size_t bytes) {
     const size_t at = total;
     total += (bytes + 255) / 256 * 256;
@@ -85,7 +85,8 @@ LstmPlan make_lstm_plan(const pfg_lstm *net, int op, int64_t B, int64_t S) {
     p.P = p.take(f * S * H);                // loop-invariant seeds pulled through the readout
     p.dh = p.take(f * rows * H);
     p.dc = p.take(f * rows * H);
-    p.dz = p.take(f * rows * 4 * H);        // one step at a time
+    p.dz = p.take(f * rows * 4 * H);        // one step at a time, two buffers used alternately:
+    p.dz2 = p.take(f * rows * 4 * H);       // a step's product reads one and fills the other
   }
   return p;
 }
@@ -135,17 +136,36 @@ int lstm_forward(const pfg_lstm *net, const void *X, int64_t B, void *ws, const 
   return PFG_OK;
 }
 
-// dh_{t-1} = dz_t W_h^T on `rows` rows of dz (row stride ld_dz).
-int recurrent_cotangent(const pfg_lstm *net, const float *dz, int64_t ld_dz, int64_t rows, float *dh,
-                        hipStream_t stream) {
-  const int32_t dx = net->input_size, H = net->state_size;
+// One reverse step as a single product.  With dz_t on `rows` rows (row m at dz + m * ld_dz):
+//   [dx_t | dh_{t-1}] = dz_t [W_x ; W_h]^T
+// The dx_t columns (only if J is given) go straight to their slot of the output; the dh_{t-1}
+// columns are not stored: the epilogue carries each of them through the reverse cell update of
+// step t - 1 and writes dz_{t-1} (row m at dz_prev + m * ld_dz_prev) and the running dc.
+int reverse_step(const pfg_lstm *net, int t, const float *dz, int64_t ld_dz, int64_t rows, int64_t S,
+                 float *J, float *dz_prev, int64_t ld_dz_prev, float *dc, void *ws, const LstmPlan &p,
+                 hipStream_t stream) {
+  const int32_t dx = net->input_size, H = net->state_size, T = net->steps;
+  const float *W = static_cast<const float *>(net->W);
   GemmArgs g{};
-  g.A = dz; g.lda = ld_dz; g.a_batch_stride = ld_dz; g.S = 1; g.a_is_f32 = 1;
-  g.W = static_cast<const float *>(net->W) + (int64_t)dx * 4 * H; g.ldw = 4 * H; g.w_kn = 0;
-  g.M = (int32_t)rows; g.N = H; g.K = 4 * H;
-  g.epilogue = EPI_NONE;
-  g.C = dh; g.ldc = H;
-  PFG_LAUNCH("lstm_gemm_cotangent", launch_gemm(g, stream));
+  g.A = dz; g.lda = ld_dz; g.a_batch_stride = S * ld_dz; g.S = (int32_t)S; g.a_is_f32 = 1;
+  g.ldw = 4 * H; g.w_kn = 0;
+  g.M = (int32_t)rows; g.K = 4 * H;
+  if (J) {
+    g.C = J + (int64_t)t * dx; g.ldc = (int64_t)T * dx; g.streaming = 1;
+  }
+  if (t == 0) {                       // nothing precedes the first step: only dx_1 is wanted
+    g.W = W; g.N = dx; g.epilogue = EPI_NONE;
+    PFG_LAUNCH("lstm_gemm_reverse", launch_gemm(g, stream));
+    return PFG_OK;
+  }
+  g.W = J ? W : W + (int64_t)dx * 4 * H;
+  g.n_split = J ? dx : 0;
+  g.N = g.n_split + H;
+  g.epilogue = EPI_LSTM_BWD;
+  g.lstm_H = H; g.lstm_T = T; g.lstm_step = t - 1;
+  g.lstm_gates = ws_at(ws, p.gates); g.lstm_cs = ws_at(ws, p.cs);
+  g.lstm_dc = dc; g.lstm_dz = dz_prev; g.lstm_dz_ld = ld_dz_prev;
+  PFG_LAUNCH("lstm_gemm_reverse", launch_gemm(g, stream));
   return PFG_OK;
 }
 
@@ -222,22 +242,23 @@ int pfg_lstm_per_example_grads(const pfg_lstm *net, const void *X, const int32_t
     PFG_LAUNCH("lstm_gemm_cotangent", launch_gemm(g, stream));
   }
   const int64_t ld_dz = (int64_t)T * 4 * H;
-  for (int t = T - 1; t >= 0; --t) {
-    PFG_LAUNCH("lstm_cell_backward",
-               launch_lstm_cell_backward(dh, H, dc, t == T - 1, ws_at(ws, p.gates), ws_at(ws, p.cs), B,
-                                         1, H, T, t, dz + (int64_t)t * 4 * H, ld_dz, stream));
-    if (t > 0 && (rc = recurrent_cotangent(net, dz + (int64_t)t * 4 * H, ld_dz, B, dh, stream))) return rc;
-  }
+  PFG_LAUNCH("lstm_cell_backward",
+             launch_lstm_cell_backward(dh, H, dc, 1, ws_at(ws, p.gates), ws_at(ws, p.cs), B, 1, H, T,
+                                       T - 1, dz + (int64_t)(T - 1) * 4 * H, ld_dz, stream));
+  for (int t = T - 1; t >= 1; --t)
+    if ((rc = reverse_step(net, t, dz + (int64_t)t * 4 * H, ld_dz, B, 1, nullptr,
+                           dz + (int64_t)(t - 1) * 4 * H, ld_dz, dc, ws, p, stream)))
+      return rc;
   if (dW_out) {
     // Both operands are stacked and the weights are shared by the steps: per example a product
     // with the step index as contraction.  Rows of x: all T steps of x_t^T dz_t.  Rows of h: steps
     // 2..T of h_{t-1}^T dz_t (h_0 = 0 contributes nothing).
     const int64_t out_bs = (int64_t)(dx + H) * 4 * H;
-    PFG_LAUNCH("outer_sum", launch_outer_sum(static_cast<const float *>(X), (int64_t)T * dx, dx, dz, ld_dz,
-                                             4 * H, T, B, dx, 4 * H, dW_out, out_bs, stream));
-    PFG_LAUNCH("outer_sum", launch_outer_sum(ws_at(ws, p.hs), (int64_t)T * H, H, dz + 4 * H, ld_dz,
-                                             4 * H, T - 1, B, H, 4 * H, dW_out + (int64_t)dx * 4 * H,
-                                             out_bs, stream));
+    OuterSumJob jobs[2] = {
+        {static_cast<const float *>(X), (int64_t)T * dx, dx, dz, ld_dz, 4 * H, T, dx, dW_out},
+        {ws_at(ws, p.hs), (int64_t)T * H, H, dz + 4 * H, ld_dz, 4 * H, T - 1, H,
+         dW_out + (int64_t)dx * 4 * H}};
+    PFG_LAUNCH("outer_sum", launch_outer_sum(jobs, 2, B, 4 * H, out_bs, stream));
   }
   if (db_out) PFG_LAUNCH("sum_steps", launch_sum_steps(dz, B, T, 4 * H, db_out, stream));
   return PFG_OK;
@@ -283,22 +304,17 @@ int pfg_lstm_jacobian_input(const pfg_lstm *net, const void *X, int64_t B, const
     dh_first = g.C; dh_first_bs = shared ? 0 : S * (int64_t)H;
   }
 
+  float *dzs[2] = {dz, ws_at(ws, p.dz2)};
+  int cur = 0;
+  PFG_LAUNCH("lstm_cell_backward",
+             launch_lstm_cell_backward(dh_first, dh_first_bs, dc, 1, ws_at(ws, p.gates),
+                                       ws_at(ws, p.cs), rows, (int32_t)S, H, T, T - 1, dzs[cur], 4 * H,
+                                       stream));
   for (int t = T - 1; t >= 0; --t) {
-    const bool first = (t == T - 1);
-    PFG_LAUNCH("lstm_cell_backward",
-               launch_lstm_cell_backward(first ? dh_first : dh, first ? dh_first_bs : S * (int64_t)H, dc,
-                                         first, ws_at(ws, p.gates), ws_at(ws, p.cs), rows, (int32_t)S,
-                                         H, T, t, dz, 4 * H, stream));
-    // J[b, s, t, :] = dz_t W_x^T, streamed straight into its slot of the output
-    GemmArgs g{};
-    g.A = dz; g.lda = 4 * H; g.a_batch_stride = 4 * H; g.S = 1; g.a_is_f32 = 1;
-    g.W = net->W; g.ldw = 4 * H; g.w_kn = 0;
-    g.M = (int32_t)rows; g.N = dx; g.K = 4 * H;
-    g.epilogue = EPI_NONE;
-    g.C = J_out + (int64_t)t * dx; g.ldc = (int64_t)T * dx;
-    g.streaming = 1;
-    PFG_LAUNCH("lstm_gemm_jacobian", launch_gemm(g, stream));
-    if (t > 0 && (rc = recurrent_cotangent(net, dz, 4 * H, rows, dh, stream))) return rc;
+    if ((rc = reverse_step(net, t, dzs[cur], 4 * H, rows, S, J_out, dzs[cur ^ 1], 4 * H, dc, ws, p,
+                           stream)))
+      return rc;
+    cur ^= 1;
   }
   return PFG_OK;
 }

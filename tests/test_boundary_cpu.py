@@ -220,7 +220,7 @@ def test_lstm_workspace_and_rejections(lib):
     B, S = 64, 128
     fwd = 2 * up(4 * B * T * 4 * H) + up(4 * B * 4 * H) + 2 * up(4 * B * T * H)
     assert lstm_ws(lib, jac_net, 1, B, S) == (0, fwd + up(4 * S * H) + 2 * up(4 * B * S * H) +
-                                              up(4 * B * S * 4 * H))
+                                              2 * up(4 * B * S * 4 * H))
     assert lstm_ws(lib, net, 2, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
     assert lstm_ws(lib, net, 0, 0, 1)[0] == pfg.PFG_ERR_SHAPE
     assert lstm_ws(lib, net, 1, 1, 0)[0] == pfg.PFG_ERR_SHAPE
