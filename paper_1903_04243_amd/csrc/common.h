@@ -37,6 +37,9 @@ enum Epilogue : int {
   EPI_HEAD = 4,      // y = acc + bias (N <= 32, optional C = y); C2 = softmax(y) - onehot(label);
                      // loss = -log softmax(y)[label]       (last forward layer fused with the head,
                      // and optionally with the cotangent step through that layer)
+  EPI_LSTM_FWD = 6,  // small-problem kernel only, W = W_h [H, 4H]: acc = h_{t-1} W_h; a workgroup takes
+                     // 8 hidden units with all four of their gate columns, adds x_t W_x + b (lstm_zx)
+                     // and applies the LSTM cell update of step lstm_step (writes gates, c_t, h_t)
   EPI_LSTM_BWD = 5   // columns n < n_split: C = acc.  A column n >= n_split is dh[m, k], k = n - n_split,
                      // the cotangent of the hidden state entering LSTM step lstm_step + 1; it is not
                      // stored but carried through the reverse cell update of step lstm_step at once
@@ -96,6 +99,11 @@ struct GemmArgs {
   float *lstm_dc;            // [M, H] running cotangent of the cell state, updated in place
   float *lstm_dz;            // row m at lstm_dz + m * lstm_dz_ld, 4H wide: dz of step lstm_step
   int64_t lstm_dz_ld;
+  // EPI_LSTM_FWD (M = B rows)
+  const float *lstm_zx;      // [B, T, 4H]: x_t W_x + b for every step
+  float *lstm_gates_w;       // [B, T, 4H], receives step lstm_step
+  float *lstm_cs_w;          // [B, T, H], step lstm_step - 1 is read, step lstm_step written
+  float *lstm_hs_w;          // [B, T, H], receives step lstm_step
 };
 
 // Picks the LDS-tiled kernel or the small-problem kernel.

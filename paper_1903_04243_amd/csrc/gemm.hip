@@ -516,7 +516,8 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
   // Fewer than 128 tiles of 64 x 64 cannot occupy the chip: such products (M = B rows, or a
   // narrow output) go to the kernel that splits the contraction over the waves of a workgroup.
   const int64_t tiles64 = (int64_t)(g.nbatch > 1 ? g.nbatch : 1) * ((g.M + 63) / 64) * ((g.N + 63) / 64);
-  if (g.epilogue == EPI_HEAD || tiles64 < 128) return launch_gemm_skinny(g, stream);
+  if (g.epilogue == EPI_HEAD || g.epilogue == EPI_LSTM_FWD || tiles64 < 128)
+    return launch_gemm_skinny(g, stream);
   if (!g.bf16) {
     return g.w_kn ? launch_tiles<A_F32, true>(g, stream) : launch_tiles<A_F32, false>(g, stream);
   }

@@ -90,6 +90,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   const bool is_head = (g.epilogue == EPI_HEAD);
   const int second = blockIdx.x / tiles_m;
   const int n0 = is_head ? 0 : second * 32;
+  // EPI_LSTM_FWD: the tile's 32 columns are the four gate columns of the 8 hidden units
+  // 8 * second .. 8 * second + 7 (column gate * H + unit of W_h), not 32 consecutive columns
+  const bool lstm_fwd = (AMODE == A_F32) && WKN && (g.epilogue == EPI_LSTM_FWD);
 
   const bool a_vec_ok = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
                         ((g.lda * (AMODE == A_BF16 ? 2 : 4)) % 16 == 0) &&
@@ -121,8 +124,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
       if (scaled) a_srow = g.a_scale + b * g.ld_scale;
     }
   }
-  const int n = n0 + l32;
-  const bool n_in = n < N;
+  const int n = lstm_fwd ? (l32 >> 3) * g.lstm_H + 8 * second + (l32 & 7) : n0 + l32;
+  const bool n_in = lstm_fwd ? (8 * second + (l32 & 7) < g.lstm_H) : (n < N);
   const void *w_row = nullptr;           // !WKN: row n of W [N, K]
   if constexpr (!WKN) {
     if (FAST || n_in) {
@@ -227,6 +230,21 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
     }
   }
 
+  // EPI_LSTM_FWD: thread (row, unit) = (tid / 8, tid % 8) of the first 256 threads finishes one
+  // cell; what it adds to the product is requested here, ahead of the contraction
+  f32x4 lstm_z = {0.f, 0.f, 0.f, 0.f};
+  float lstm_cprev = 0.f;
+  const int lstm_m = m0 + (tid >> 3), lstm_k = 8 * second + (tid & 7);
+  const bool lstm_live = lstm_fwd && tid < 256 && lstm_m < M && lstm_k < g.lstm_H;
+  if constexpr (AMODE == A_F32 && WKN) {
+    if (lstm_live) {
+      const int H = g.lstm_H, T = g.lstm_T, t = g.lstm_step;
+      const float *zrow = g.lstm_zx + ((int64_t)lstm_m * T + t) * 4 * H + lstm_k;
+      lstm_z = f32x4{zrow[0], zrow[H], zrow[2 * H], zrow[3 * H]};
+      if (t > 0) lstm_cprev = g.lstm_cs_w[((int64_t)lstm_m * T + t - 1) * H + lstm_k];
+    }
+  }
+
   f32x16 acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -275,6 +293,30 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   // the bias / mask values it needs in one go (a vector load when alignment allows) and writes
   // its Q results, again as one vector when possible.  One pass, no loop: with so few waves the
   // latency of every dependent global access counts.
+  if constexpr (AMODE == A_F32 && WKN) {
+    if (lstm_fwd) {
+      if (lstm_live) {
+        const int H = g.lstm_H, T = g.lstm_T, t = g.lstm_step;
+        const int r = tid >> 3, u = tid & 7;
+        f32x4 z = lstm_z;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          z[0] += red[w][r][u];
+          z[1] += red[w][r][8 + u];
+          z[2] += red[w][r][16 + u];
+          z[3] += red[w][r][24 + u];
+        }
+        const float gi = 1.f / (1.f + __expf(-z[0])), gg = tanhf(z[1]);
+        const float gf = 1.f / (1.f + __expf(-z[2])), go = 1.f / (1.f + __expf(-z[3]));
+        const float c = gf * lstm_cprev + gi * gg;
+        float *grow = g.lstm_gates_w + ((int64_t)lstm_m * T + t) * 4 * H + lstm_k;
+        grow[0] = gi; grow[H] = gg; grow[2 * H] = gf; grow[3 * H] = go;
+        g.lstm_cs_w[((int64_t)lstm_m * T + t) * H + lstm_k] = c;
+        g.lstm_hs_w[((int64_t)lstm_m * T + t) * H + lstm_k] = go * tanhf(c);
+      }
+      return;
+    }
+  }
   {
     fq v;
 #pragma unroll
@@ -412,6 +454,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
 template <int AMODE, bool WKN, int NW>
 hipError_t launch_nw(const GemmArgs &g, hipStream_t stream) {
   int64_t tiles = (int64_t)((g.M + 31) / 32) * ((g.N + 31) / 32);
+  if (g.epilogue == EPI_LSTM_FWD) tiles = (int64_t)((g.M + 31) / 32) * ((g.lstm_H + 7) / 8);
   if (g.epilogue == EPI_HEAD && g.head_gprev) {
     // share the fused cotangent step of each row tile out over up to 8 workgroups
     int groups = g.K / 64;
@@ -443,6 +486,8 @@ hipError_t launch_mode(const GemmArgs &g, hipStream_t stream) {
 hipError_t launch_gemm_skinny(const GemmArgs &g, hipStream_t stream) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipSuccess;
   if (g.epilogue == EPI_HEAD && g.N > 32) return hipErrorInvalidValue;
+  if (g.epilogue == EPI_LSTM_FWD && (g.bf16 || !g.w_kn || g.N != 4 * g.lstm_H || g.nbatch > 1))
+    return hipErrorInvalidValue;
   if (g.nbatch > 1) {
     // small batched products: one launch per product (this kernel has no batch index)
     const int a_elem = (g.bf16 && !g.a_is_f32) ? 2 : 4, w_elem = g.bf16 ? 2 : 4;

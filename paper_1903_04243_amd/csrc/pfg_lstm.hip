@@ -118,7 +118,24 @@ int lstm_forward(const pfg_lstm *net, const void *X, int64_t B, void *ws, const 
     PFG_LAUNCH("lstm_gemm_input", launch_gemm(g, stream));
   }
   float *hs = ws_at(ws, p.hs);
+  // With few rows (B up to a few hundred) every kernel on this sequential path is bound by launch
+  // and memory latency, so the cell update rides in the epilogue of the recurrent product: one
+  // launch per step instead of two.  Large batches use the LDS-tiled product and a separate cell kernel.
+  const bool fused = (int64_t)((B + 63) / 64) * ((4 * (int64_t)H + 63) / 64) < 128;
   for (int t = 0; t < T; ++t) {
+    if (t > 0 && fused) {
+      GemmArgs g{};
+      g.A = hs + (int64_t)(t - 1) * H; g.lda = (int64_t)T * H; g.a_batch_stride = (int64_t)T * H;
+      g.S = 1; g.a_is_f32 = 1;
+      g.W = W + (int64_t)dx * 4 * H; g.ldw = 4 * H; g.w_kn = 1;
+      g.M = (int32_t)B; g.N = 4 * H; g.K = H;
+      g.epilogue = EPI_LSTM_FWD;
+      g.lstm_H = H; g.lstm_T = T; g.lstm_step = t;
+      g.lstm_zx = ws_at(ws, p.zx); g.lstm_gates_w = ws_at(ws, p.gates);
+      g.lstm_cs_w = ws_at(ws, p.cs); g.lstm_hs_w = hs;
+      PFG_LAUNCH("lstm_step", launch_gemm(g, stream));
+      continue;
+    }
     if (t > 0) {
       GemmArgs g{};
       g.A = hs + (int64_t)(t - 1) * H; g.lda = (int64_t)T * H; g.a_batch_stride = (int64_t)T * H;
