@@ -46,6 +46,19 @@ __device__ __forceinline__ float act_deriv2(int act, float z) {
 //   dz_o  = dh * tanh(c_t) * o (1 - o)
 //   dz_i  = dc * g * i (1 - i),  dz_g = dc * i * (1 - g^2),  dz_f = dc * c_{t-1} * f (1 - f)
 //   dc_{t-1} = dc * f
+// The same update on values already in registers.
+struct LstmCellIn { float i, g, f, o, c, cprev, dc; };
+__device__ __forceinline__ void lstm_reverse_cell_store(const LstmCellIn &v, float dh, float *dz_row,
+                                                        float *dcp, int H, int k) {
+  const float tc = tanhf(v.c);
+  const float dct = v.dc + dh * v.o * (1.f - tc * tc);
+  dz_row[k] = dct * v.g * v.i * (1.f - v.i);
+  dz_row[H + k] = dct * v.i * (1.f - v.g * v.g);
+  dz_row[2 * H + k] = dct * v.cprev * v.f * (1.f - v.f);
+  dz_row[3 * H + k] = dh * tc * v.o * (1.f - v.o);
+  *dcp = dct * v.f;
+}
+
 __device__ __forceinline__ void lstm_reverse_cell(const float *gates, const float *cs, float *dc,
                                                   float *dz, int64_t dz_ld, int H, int T, int t,
                                                   int S, int m, int k, float dh) {

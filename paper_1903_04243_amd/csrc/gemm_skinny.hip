@@ -64,13 +64,16 @@ __device__ __forceinline__ void head_cotangent(const GemmArgs &g, const float (*
   }
 }
 
-template <int AMODE, bool WKN, int NW, bool FAST>
+// LSTM: the instantiation that carries the two LSTM epilogues (float32 only).  They live in a
+// separate instantiation so that the kernels of the dense-network path stay as small as they were:
+// with a handful of waves per launch, every extra instruction on the way shows in the run time.
+template <int AMODE, bool WKN, int NW, bool FAST, bool LSTM = false>
 __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) {
   constexpr bool BF16 = (AMODE != A_F32);
   constexpr int ELEM = BF16 ? 2 : 4;
   constexpr int EPC = 16 / ELEM;       // k elements one lane feeds to the MFMA(s) of a slice
   constexpr int KSLICE = 2 * EPC;      // k elements per slice (two lane halves)
-  constexpr int R = 4;                 // slices in flight per wave
+  constexpr int R = 4;                 // slices in flight per wave (8 was measured slower)
   constexpr int NT = 64 * NW;
 
   __shared__ __align__(16) float red[NW][32][36];   // row stride 144 B: 16-byte aligned rows
@@ -92,7 +95,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   const int n0 = is_head ? 0 : second * 32;
   // EPI_LSTM_FWD: the tile's 32 columns are the four gate columns of the 8 hidden units
   // 8 * second .. 8 * second + 7 (column gate * H + unit of W_h), not 32 consecutive columns
-  const bool lstm_fwd = (AMODE == A_F32) && WKN && (g.epilogue == EPI_LSTM_FWD);
+  const bool lstm_fwd = LSTM && WKN && (g.epilogue == EPI_LSTM_FWD);
 
   const bool a_vec_ok = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
                         ((g.lda * (AMODE == A_BF16 ? 2 : 4)) % 16 == 0) &&
@@ -236,12 +239,39 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   float lstm_cprev = 0.f;
   const int lstm_m = m0 + (tid >> 3), lstm_k = 8 * second + (tid & 7);
   const bool lstm_live = lstm_fwd && tid < 256 && lstm_m < M && lstm_k < g.lstm_H;
-  if constexpr (AMODE == A_F32 && WKN) {
+  if constexpr (LSTM && WKN) {
     if (lstm_live) {
       const int H = g.lstm_H, T = g.lstm_T, t = g.lstm_step;
       const float *zrow = g.lstm_zx + ((int64_t)lstm_m * T + t) * 4 * H + lstm_k;
       lstm_z = f32x4{zrow[0], zrow[H], zrow[2 * H], zrow[3 * H]};
       if (t > 0) lstm_cprev = g.lstm_cs_w[((int64_t)lstm_m * T + t - 1) * H + lstm_k];
+    }
+  }
+
+  // EPI_LSTM_BWD: the gate values, cell states and running dc of this thread's Q elements are
+  // requested ahead of the contraction too
+  LstmCellIn lb0{}, lb1{}, lb2{}, lb3{};
+  if constexpr (LSTM && !WKN) {
+    if (epi == EPI_LSTM_BWD && row_in) {
+      const int H = g.lstm_H, T = g.lstm_T, t = g.lstm_step;
+      const int64_t b = m / g.S;
+      const float *grow = g.lstm_gates + (b * T + t) * 4 * (int64_t)H;
+      const float *crow = g.lstm_cs + (b * T + t) * (int64_t)H;
+      const float *dcrow = g.lstm_dc + (int64_t)m * H;
+      auto fetch = [&](int q, LstmCellIn &v) {
+        const int k = nn + q - g.n_split;
+        if (k < 0 || nn + q >= N) return;
+        v.i = grow[k]; v.g = grow[H + k]; v.f = grow[2 * H + k]; v.o = grow[3 * H + k];
+        v.c = crow[k];
+        v.cprev = t > 0 ? crow[k - H] : 0.f;
+        v.dc = dcrow[k];
+      };
+      fetch(0, lb0);
+      fetch(1, lb1);
+      if constexpr (Q == 4) {
+        fetch(2, lb2);
+        fetch(3, lb3);
+      }
     }
   }
 
@@ -293,7 +323,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   // the bias / mask values it needs in one go (a vector load when alignment allows) and writes
   // its Q results, again as one vector when possible.  One pass, no loop: with so few waves the
   // latency of every dependent global access counts.
-  if constexpr (AMODE == A_F32 && WKN) {
+  if constexpr (LSTM && WKN) {
     if (lstm_fwd) {
       if (lstm_live) {
         const int H = g.lstm_H, T = g.lstm_T, t = g.lstm_step;
@@ -349,23 +379,25 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
 #pragma unroll
         for (int q = 0; q < Q; ++q) v[q] *= aux[q];
       }
-      if (epi == EPI_LSTM_BWD && nn + Q > g.n_split) {
+      if (LSTM && epi == EPI_LSTM_BWD && nn + Q > g.n_split) {
         // this thread's columns reach into the hidden-state cotangent: element by element, with
         // constant indices into v[] (an index known only at run time would move the array out of
         // registers)
-        auto finish = [&](int q, float val) {
+        auto finish = [&](int q, float val, const LstmCellIn &in) {
           if (nn + q >= N) return;
-          if (nn + q < g.n_split)
+          if (nn + q < g.n_split) {
             g.C[off + q] = val;
-          else
-            lstm_reverse_cell(g.lstm_gates, g.lstm_cs, g.lstm_dc, g.lstm_dz, g.lstm_dz_ld, g.lstm_H,
-                              g.lstm_T, g.lstm_step, g.S, m, nn + q - g.n_split, val);
+          } else {
+            const int k = nn + q - g.n_split;
+            lstm_reverse_cell_store(in, val, g.lstm_dz + (int64_t)m * g.lstm_dz_ld,
+                                    g.lstm_dc + (int64_t)m * g.lstm_H + k, g.lstm_H, k);
+          }
         };
-        finish(0, v[0]);
-        finish(1, v[1]);
+        finish(0, v[0], lb0);
+        finish(1, v[1], lb1);
         if constexpr (Q == 4) {
-          finish(2, v[2]);
-          finish(3, v[3]);
+          finish(2, v[2], lb2);
+          finish(3, v[3], lb3);
         }
         return;     // nothing follows the epilogue for this kind of product
       }
@@ -462,6 +494,19 @@ hipError_t launch_nw(const GemmArgs &g, hipStream_t stream) {
     tiles *= groups;
   }
   // the element-wise column loads of the [K, N] layout put no condition on W
+  const bool lstm = (g.epilogue == EPI_LSTM_FWD || g.epilogue == EPI_LSTM_BWD);
+  if constexpr (AMODE == A_F32) {
+    if (lstm) {
+      if (fast_loads_ok(g, !WKN))
+        PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, true, true>), dim3((unsigned)tiles),
+                   dim3(64 * NW), 0, stream, g);
+      else
+        PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, false, true>), dim3((unsigned)tiles),
+                   dim3(64 * NW), 0, stream, g);
+      return hipGetLastError();
+    }
+  }
+  if (lstm) return hipErrorInvalidValue;     // the LSTM epilogues exist in float32 only
   if (fast_loads_ok(g, !WKN))
     PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, true>), dim3((unsigned)tiles),
                        dim3(64 * NW), 0, stream, g);
