@@ -153,3 +153,20 @@ def body_jacobian_input_row(net: Lstm, x, seed_row) -> np.ndarray:
     _load().lstmo_body_jacobian_input_row(ctypes.byref(net.c), _dp(_seq(net, x)), _dp(seed_row),
                                           _dp(row))
     return row
+
+
+def varlen_forward(net: Lstm, X, lengths):
+    """Every sequence iterated to its own length.  X [sum(lengths), dx] holds the tokens back to
+    back.  Returns (h [B, H], y [B, dy]): the last hidden state of each sequence and its readout."""
+    lengths = np.asarray(lengths, dtype=np.int64)
+    assert lengths.ndim == 1 and (lengths >= 1).all()
+    B = lengths.size
+    offsets = np.zeros(B + 1, dtype=np.int64)
+    np.cumsum(lengths, out=offsets[1:])
+    X = _f64(X)
+    assert X.shape == (int(offsets[-1]), net.dx)
+    h, y = np.empty((B, net.H)), np.empty((B, net.dy))
+    _load().lstmo_varlen_forward(ctypes.byref(net.c), _dp(X),
+                                 offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                 ctypes.c_int64(B), _dp(h), _dp(y))
+    return h, y

@@ -278,3 +278,58 @@ void lstmo_jacobian_input(const lstmo_net *net, const double *X, int64_t B, cons
     tape_free(tp);
   }
 }
+
+/* ---------------------------------------------------------------------------------------
+ * Sequences of different lengths (Section 6.2, the auto-batching LSTM workload: every sequence is
+ * iterated to its own length, inputs are not padded).  The body of the parallel-for holds a
+ * sequential while loop (Section 3.7):
+ *      h, c <- 0;  t <- 0
+ *      while t < len_i:  h, c <- cell(x_i[t], h, c);  t <- t + 1
+ *      return h, y = h Wout + bout
+ * Executed literally: one sequence at a time, each to its own length.  X holds the tokens of all
+ * sequences back to back ([sum of lengths, dx]); sequence i starts at row offsets[i] and has
+ * offsets[i + 1] - offsets[i] >= 1 tokens (net->T is not used).  h_out is [B, H], y_out [B, dy].
+ * ------------------------------------------------------------------------------------- */
+void lstmo_body_varlen_forward(const lstmo_net *net, const double *x, int64_t len, double *h_out,
+                               double *y_out) {
+  const int dx = net->dx, H = net->H, dy = net->dy, G = 4 * net->H;
+  double *h = (double *)calloc((size_t)H, sizeof(double));
+  double *c = (double *)calloc((size_t)H, sizeof(double));
+  double *hn = (double *)malloc(sizeof(double) * (size_t)H);
+  double *z = (double *)malloc(sizeof(double) * (size_t)G);
+  int64_t t = 0;
+  while (t < len) {
+    const double *xt = x + (size_t)t * dx;
+    for (int col = 0; col < G; ++col) {
+      double s = net->b ? net->b[col] : 0.0;
+      for (int r = 0; r < dx; ++r) s += xt[r] * net->W[(size_t)r * G + col];
+      for (int r = 0; r < H; ++r) s += h[r] * net->W[(size_t)(dx + r) * G + col];
+      z[col] = s;
+    }
+    for (int k = 0; k < H; ++k) {
+      const double i = sigmoid(z[k]), g = tanh(z[H + k]), f = sigmoid(z[2 * H + k]),
+                   o = sigmoid(z[3 * H + k]);
+      c[k] = f * c[k] + i * g;
+      hn[k] = o * tanh(c[k]);
+    }
+    memcpy(h, hn, sizeof(double) * (size_t)H);
+    t = t + 1;
+  }
+  if (h_out) memcpy(h_out, h, sizeof(double) * (size_t)H);
+  if (y_out)
+    for (int j = 0; j < dy; ++j) {
+      double s = net->bout ? net->bout[j] : 0.0;
+      for (int k = 0; k < H; ++k) s += h[k] * net->Wout[(size_t)k * dy + j];
+      y_out[j] = s;
+    }
+  free(h); free(c); free(hn); free(z);
+}
+
+void lstmo_varlen_forward(const lstmo_net *net, const double *X, const int64_t *offsets, int64_t B,
+                          double *h_out, double *y_out) {
+#pragma omp parallel for schedule(dynamic)
+  for (int64_t i = 0; i < B; ++i)
+    lstmo_body_varlen_forward(net, X + (size_t)offsets[i] * net->dx, offsets[i + 1] - offsets[i],
+                              h_out ? h_out + (size_t)i * net->H : NULL,
+                              y_out ? y_out + (size_t)i * net->dy : NULL);
+}

@@ -229,3 +229,50 @@ def test_jacobian_seed_forms_and_rows():
     # d y / d x_T = Wout^T diag-chain through the last cell only; check it against one-step FD
     zero_out = lstm.Lstm(net.W, net.b, np.zeros_like(net.Wout), net.bout, net.T)
     assert not lstm.jacobian_input(zero_out, X).any()
+
+
+# --------------------------------------------------------------------------------------------
+# Sequences of different lengths (the while loop inside the parallel-for, Section 3.7).
+# --------------------------------------------------------------------------------------------
+def test_varlen_forward_matches_the_library_cell_sequence_by_sequence():
+    rng = np.random.default_rng(71)
+    net = rand_lstm(rng, 4, 6, 3, 1)
+    lengths = np.array([3, 1, 7, 2, 7, 5])
+    X = rng.standard_normal((int(lengths.sum()), 4))
+    h, y = lstm.varlen_forward(net, X, lengths)
+    cell, Wout, bout, _ = torch_cell(net)
+    start = 0
+    for b, n in enumerate(lengths):
+        hb = torch.zeros(1, 6, dtype=torch.float64)
+        cb = torch.zeros(1, 6, dtype=torch.float64)
+        with torch.no_grad():
+            for t in range(n):
+                hb, cb = cell(torch.from_numpy(X[start + t:start + t + 1]), (hb, cb))
+            want_y = hb[0] @ Wout + bout
+        np.testing.assert_allclose(h[b], hb[0].numpy(), rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(y[b], want_y.numpy(), rtol=1e-12, atol=1e-14)
+        start += n
+
+
+def test_varlen_forward_reduces_to_the_fixed_length_model_and_ignores_the_batch_order():
+    rng = np.random.default_rng(72)
+    T = 5
+    net = rand_lstm(rng, 3, 4, 2, T)
+    X = rng.standard_normal((4, T, 3))
+    h, y = lstm.varlen_forward(net, X.reshape(4 * T, 3), [T] * 4)
+    for b in range(4):
+        hs, _ = lstm.states(net, X[b])
+        np.testing.assert_array_equal(h[b], hs[-1])
+        np.testing.assert_array_equal(y[b], lstm.forward(net, X[b]))
+    # a sequence's result depends on its own tokens only: truncating it to n tokens gives the
+    # state after n steps, whatever the other sequences in the batch are
+    lengths = [2, 5, 1, 4]
+    packed = np.concatenate([X[b, :n] for b, n in enumerate(lengths)])
+    hv, _ = lstm.varlen_forward(net, packed, lengths)
+    for b, n in enumerate(lengths):
+        hs, _ = lstm.states(net, X[b])
+        np.testing.assert_array_equal(hv[b], hs[n - 1])
+    order = [2, 0, 3, 1]
+    packed_p = np.concatenate([X[b, :lengths[b]] for b in order])
+    hp, _ = lstm.varlen_forward(net, packed_p, [lengths[b] for b in order])
+    np.testing.assert_array_equal(hp, hv[order])

@@ -118,6 +118,12 @@ LSTM_MUTANTS = [
     ("jacobian_row_stacking", "J + ((size_t)b * S + s) * nx);", "J + ((size_t)s * B + b) * nx);"),
     ("seed_stride_ignored", "row = seeds + (size_t)b * seed_batch_stride + (size_t)s * dy;",
      "row = seeds + (size_t)s * dy;"),
+    ("varlen_runs_one_step_too_many", "while (t < len) {", "while (t <= len - 1 + (len > 1)) {"),
+    ("varlen_state_not_carried", "c[k] = f * c[k] + i * g;", "c[k] = i * g;"),
+    ("varlen_recurrent_term_dropped",
+     "for (int r = 0; r < H; ++r) s += h[r] * net->W[(size_t)(dx + r) * G + col];", ""),
+    ("varlen_sequence_offset", "X + (size_t)offsets[i] * net->dx, offsets[i + 1] - offsets[i],",
+     "X + (size_t)offsets[i] * net->dx + (i > 0 ? net->dx : 0), offsets[i + 1] - offsets[i],"),
 ]
 
 
