@@ -212,6 +212,26 @@ int pfg_lstm_jacobian_input(const pfg_lstm *net, const void *X, int64_t B, const
                             int64_t S, int64_t seed_batch_stride, float *J_out, void *workspace,
                             size_t workspace_bytes, void *hip_stream);
 
+/* Sequences of different lengths (the auto-batching LSTM workload of Section 6.2: every sequence
+ * is iterated to its own length, inputs are not padded).  The body of the parallel-for holds a
+ * sequential while loop, "while t < length_i: (h, c) = cell(x_i[t], h, c)"; its vectorised form
+ * (Section 3.7) keeps the set of iterations that are still active and runs each step on those only.
+ * The loop condition depends on the lengths and the step counter alone, so all active sets are
+ * known before the loop starts: the sequences are ordered by decreasing length once, which makes
+ * every active set a prefix of that order, and the results are put back in the caller's order at
+ * the end.  net->steps is ignored.
+ *   X               DEVICE [sum of lengths, input_size]: the tokens of sequence 0, then sequence 1, ...
+ *   lengths         HOST   [B] int32, each >= 1 (read before the call returns)
+ *   total_tokens    sum of lengths (checked)
+ *   h_out           DEVICE [B, state_size] or NULL: hidden state of each sequence after its last token
+ *   y_out           DEVICE [B, output_size] or NULL: h_out W_out + b_out
+ * The call copies three small index arrays to the workspace with an asynchronous copy on the
+ * stream; do not capture it into a graph. */
+int pfg_lstm_varlen_workspace_bytes(const pfg_lstm *net, int64_t B, int64_t total_tokens, size_t *bytes);
+int pfg_lstm_varlen_forward(const pfg_lstm *net, const void *X, const int32_t *lengths, int64_t B,
+                            int64_t total_tokens, float *h_out, float *y_out, void *workspace,
+                            size_t workspace_bytes, void *hip_stream);
+
 /* Text of the last error on the calling thread ("" if none).  Valid until the next call into the
  * library from that thread. */
 const char *pfg_last_error(void);

@@ -27,6 +27,7 @@ OP = {"per_example_grads": 0, "jacobian_input": 1, "jacobian_weights": 2, "grad_
 EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_jacobian_input",
            "pfg_jacobian_weights", "pfg_per_example_grad_norms", "pfg_hessian_input",
            "pfg_lstm_workspace_bytes", "pfg_lstm_per_example_grads", "pfg_lstm_jacobian_input",
+           "pfg_lstm_varlen_workspace_bytes", "pfg_lstm_varlen_forward",
            "pfg_last_error", "pfg_timing_enable", "pfg_timing_reset",
            "pfg_timing_query", "pfg_timing_names", "pfg_version"]
 
@@ -93,6 +94,9 @@ def load_library() -> ctypes.CDLL:
         lib.pfg_lstm_per_example_grads.argtypes = [lstmp, vp, vp, i64, vp, vp, vp, vp, vp, vp,
                                                    ctypes.c_size_t, vp]
         lib.pfg_lstm_jacobian_input.argtypes = [lstmp, vp, i64, vp, i64, i64, vp, vp, ctypes.c_size_t, vp]
+        lib.pfg_lstm_varlen_workspace_bytes.argtypes = [lstmp, i64, i64, ctypes.POINTER(ctypes.c_size_t)]
+        lib.pfg_lstm_varlen_forward.argtypes = [lstmp, vp, ctypes.POINTER(ctypes.c_int32), i64, i64, vp,
+                                                vp, vp, ctypes.c_size_t, vp]
         lib.pfg_last_error.restype = ctypes.c_char_p
         lib.pfg_timing_enable.argtypes = [i32]
         lib.pfg_timing_query.argtypes = [ctypes.c_char_p, ctypes.POINTER(i64),
@@ -406,6 +410,36 @@ def pfg_lstm_jacobian_input(net: Lstm, X, seeds=None, S: Optional[int] = None, o
         ctypes.byref(net.c), X.data_ptr(), B, None if seeds is None else seeds.data_ptr(), S,
         stride, J.data_ptr(), workspace.data_ptr(), ws_bytes, _stream_ptr()))
     return J
+
+
+def pfg_lstm_varlen_workspace_bytes(net: Lstm, B: int, total_tokens: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().pfg_lstm_varlen_workspace_bytes(ctypes.byref(net.c), B, total_tokens,
+                                                          ctypes.byref(n)))
+    return int(n.value)
+
+
+def pfg_lstm_varlen_forward(net: Lstm, X, lengths, want_h: bool = True, want_y: bool = True,
+                            out_h=None, out_y=None, workspace=None):
+    """Sequences of different lengths, tokens back to back in X [sum(lengths), dx]; ``lengths`` is a
+    host sequence of ints.  Returns (h [B, H] or None, y [B, dy] or None)."""
+    import numpy as np
+    import torch
+    lengths = np.ascontiguousarray(np.asarray(lengths, dtype=np.int32))
+    B, total = int(lengths.size), int(lengths.sum())
+    if X.dtype != torch.float32 or not X.is_contiguous() or tuple(X.shape) != (total, net.dx):
+        raise ValueError("X must be a contiguous float32 [sum(lengths), input_size] tensor")
+    f32 = dict(dtype=torch.float32, device=net.device)
+    h = out_h if out_h is not None else (torch.empty((B, net.H), **f32) if want_h else None)
+    y = out_y if out_y is not None else (torch.empty((B, net.dy), **f32) if want_y else None)
+    if workspace is None:
+        workspace = torch.empty(pfg_lstm_varlen_workspace_bytes(net, B, total), dtype=torch.uint8,
+                                device=net.device)
+    _check(load_library().pfg_lstm_varlen_forward(
+        ctypes.byref(net.c), X.data_ptr(), lengths.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), B,
+        total, None if h is None else h.data_ptr(), None if y is None else y.data_ptr(),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr()))
+    return h, y
 
 
 def pfg_timing_enable(on: bool) -> None:

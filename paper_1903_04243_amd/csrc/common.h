@@ -99,11 +99,14 @@ struct GemmArgs {
   float *lstm_dc;            // [M, H] running cotangent of the cell state, updated in place
   float *lstm_dz;            // row m at lstm_dz + m * lstm_dz_ld, 4H wide: dz of step lstm_step
   int64_t lstm_dz_ld;
-  // EPI_LSTM_FWD (M = B rows)
-  const float *lstm_zx;      // [B, T, 4H]: x_t W_x + b for every step
-  float *lstm_gates_w;       // [B, T, 4H], receives step lstm_step
-  float *lstm_cs_w;          // [B, T, H], step lstm_step - 1 is read, step lstm_step written
-  float *lstm_hs_w;          // [B, T, H], receives step lstm_step
+  // EPI_LSTM_FWD (M rows, one per active sequence)
+  const float *lstm_zx;         // x_t W_x + b, 4H wide rows; row of (m, step): lstm_zx_rows ?
+  const int32_t *lstm_zx_rows;  //   lstm_zx_rows[m] + step (sequences stored back to back) : m * T + step
+  float *lstm_gates_w;          // [M, T, 4H], receives step lstm_step; nullptr: gates are not kept
+  float *lstm_cs_w;             // cell state of (m, step) at lstm_cs_w + m * lstm_state_ld + step * lstm_state_ts
+  float *lstm_hs_w;             // hidden state, same addressing (the product's A operand is read elsewhere)
+  int64_t lstm_state_ld, lstm_state_ts;   // [M, T, H] history: T * H and H; state updated in place: H and 0
+  int32_t lstm_has_prev;        // 0: c_{step-1} is zero and is not read
 };
 
 // Picks the LDS-tiled kernel or the small-problem kernel.
@@ -171,6 +174,11 @@ hipError_t launch_norm_finalize(const float *sq, int64_t ld_sq, int32_t L, int64
 
 // out[0 .. n) = 0
 hipError_t launch_fill_zero(float *out, int64_t n, hipStream_t stream);
+
+// out[order[j], :] = (parity[j] odd ? src_odd : src_even)[j, :]   for j < rows, d columns
+hipError_t launch_scatter_rows(const float *src_even, const float *src_odd, const int32_t *parity,
+                               const int32_t *order, int64_t rows, int32_t d, float *out,
+                               hipStream_t stream);
 
 // LSTM cell update of step t for every (b, k): zx [B, T, 4H] holds x_t W_x + b, zh [B, 4H] holds
 // h_{t-1} W_h (nullptr at the first step); writes step t of gates [B, T, 4H], cs and hs [B, T, H].

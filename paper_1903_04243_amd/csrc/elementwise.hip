@@ -223,6 +223,22 @@ __global__ __launch_bounds__(kThreads) void fill_zero_kernel(float *out, int64_t
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += step) out[i] = 0.f;
 }
 
+// The stitching step after a loop with a shrinking set of active iterations (Section 3.7): row j
+// of the compacted state goes back to the slot of the iteration it belongs to.
+__global__ __launch_bounds__(kThreads) void scatter_rows_kernel(const float *src_even, const float *src_odd,
+                                                                const int32_t *parity,
+                                                                const int32_t *order, int64_t rows,
+                                                                int d, float *out) {
+  const int64_t total = rows * d;
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += step) {
+    const int64_t j = i / d;
+    const int k = (int)(i - j * d);
+    const float *src = (parity[j] & 1) ? src_odd : src_even;
+    out[(int64_t)order[j] * d + k] = src[j * d + k];
+  }
+}
+
 inline unsigned capped_blocks(int64_t work_items) {
   const int64_t blocks = (work_items + kThreads - 1) / kThreads;
   return (unsigned)(blocks < (1 << 20) ? blocks : (1 << 20));
@@ -265,6 +281,15 @@ hipError_t launch_norm_finalize(const float *sq, int64_t ld_sq, int32_t L, int64
   if (B <= 0) return hipSuccess;
   PFG_KERNEL(norm_finalize_kernel, dim3((unsigned)((B + kThreads - 1) / kThreads)), dim3(kThreads), 0,
              stream, sq, ld_sq, L, B, norm);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter_rows(const float *src_even, const float *src_odd, const int32_t *parity,
+                               const int32_t *order, int64_t rows, int32_t d, float *out,
+                               hipStream_t stream) {
+  if (rows <= 0 || d <= 0) return hipSuccess;
+  PFG_KERNEL(scatter_rows_kernel, dim3(capped_blocks(rows * d)), dim3(kThreads), 0, stream, src_even,
+             src_odd, parity, order, rows, d, out);
   return hipGetLastError();
 }
 

@@ -242,9 +242,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   if constexpr (LSTM && WKN) {
     if (lstm_live) {
       const int H = g.lstm_H, T = g.lstm_T, t = g.lstm_step;
-      const float *zrow = g.lstm_zx + ((int64_t)lstm_m * T + t) * 4 * H + lstm_k;
+      const int64_t zr = g.lstm_zx_rows ? (int64_t)g.lstm_zx_rows[lstm_m] + t : (int64_t)lstm_m * T + t;
+      const float *zrow = g.lstm_zx + zr * 4 * H + lstm_k;
       lstm_z = f32x4{zrow[0], zrow[H], zrow[2 * H], zrow[3 * H]};
-      if (t > 0) lstm_cprev = g.lstm_cs_w[((int64_t)lstm_m * T + t - 1) * H + lstm_k];
+      if (g.lstm_has_prev)
+        lstm_cprev = g.lstm_cs_w[lstm_m * g.lstm_state_ld + (t - 1) * g.lstm_state_ts + lstm_k];
     }
   }
 
@@ -339,10 +341,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
         const float gi = 1.f / (1.f + __expf(-z[0])), gg = tanhf(z[1]);
         const float gf = 1.f / (1.f + __expf(-z[2])), go = 1.f / (1.f + __expf(-z[3]));
         const float c = gf * lstm_cprev + gi * gg;
-        float *grow = g.lstm_gates_w + ((int64_t)lstm_m * T + t) * 4 * H + lstm_k;
-        grow[0] = gi; grow[H] = gg; grow[2 * H] = gf; grow[3 * H] = go;
-        g.lstm_cs_w[((int64_t)lstm_m * T + t) * H + lstm_k] = c;
-        g.lstm_hs_w[((int64_t)lstm_m * T + t) * H + lstm_k] = go * tanhf(c);
+        if (g.lstm_gates_w) {
+          float *grow = g.lstm_gates_w + ((int64_t)lstm_m * T + t) * 4 * H + lstm_k;
+          grow[0] = gi; grow[H] = gg; grow[2 * H] = gf; grow[3 * H] = go;
+        }
+        const int64_t at = lstm_m * g.lstm_state_ld + t * g.lstm_state_ts + lstm_k;
+        g.lstm_cs_w[at] = c;
+        g.lstm_hs_w[at] = go * tanhf(c);
       }
       return;
     }

@@ -1,6 +1,8 @@
 // C ABI of the unrolled LSTM: argument checks, workspace layout and the order in which the kernels
 // are enqueued.  No arithmetic of the method happens on the host.
 #include <algorithm>
+#include <numeric>
+#include <vector>
 
 #include "../../include/pfg.h"
 #include "common.h"
@@ -133,6 +135,7 @@ int lstm_forward(const pfg_lstm *net, const void *X, int64_t B, void *ws, const 
       g.lstm_H = H; g.lstm_T = T; g.lstm_step = t;
       g.lstm_zx = ws_at(ws, p.zx); g.lstm_gates_w = ws_at(ws, p.gates);
       g.lstm_cs_w = ws_at(ws, p.cs); g.lstm_hs_w = hs;
+      g.lstm_state_ld = (int64_t)T * H; g.lstm_state_ts = H; g.lstm_has_prev = 1;
       PFG_LAUNCH("lstm_step", launch_gemm(g, stream));
       continue;
     }
@@ -186,9 +189,153 @@ int reverse_step(const pfg_lstm *net, int t, const float *dz, int64_t ld_dz, int
   return PFG_OK;
 }
 
+struct VarlenPlan {
+  size_t total = 0;
+  size_t zx = 0, state = 0, hfin = 0, idx = 0;
+  size_t take(size_t bytes) {
+    const size_t at = total;
+    total += (bytes + 255) / 256 * 256;
+    return at;
+  }
+};
+
+VarlenPlan make_varlen_plan(const pfg_lstm *net, int64_t B, int64_t tokens) {
+  const size_t H = net->state_size, f = sizeof(float);
+  VarlenPlan p;
+  p.zx = p.take(f * tokens * 4 * H);
+  p.state = p.take(f * 3 * B * H);          // h (two buffers used alternately) and c, zeroed together
+  p.hfin = p.take(f * B * H);               // last states in the caller's order, if h_out is not given
+  p.idx = p.take(sizeof(int32_t) * 3 * B);  // first token row, original index, length of sorted row j
+  return p;
+}
+
+int check_varlen_sizes(const pfg_lstm *net, int64_t B, int64_t tokens) {
+  if (B < 1) return fail(PFG_ERR_SHAPE, "B = %lld must be at least 1", (long long)B);
+  if (tokens < B) return fail(PFG_ERR_SHAPE, "total_tokens = %lld is less than B = %lld", (long long)tokens, (long long)B);
+  const int64_t H = net->state_size;
+  if (B > kMaxRows || tokens > kMaxRows || 4 * H > kMaxElems / tokens || B * H > ((int64_t)1 << 38))
+    return fail(PFG_ERR_OVERFLOW, "B = %lld sequences with %lld tokens exceed the indexing limits",
+                (long long)B, (long long)tokens);
+  return PFG_OK;
+}
+
 }  // namespace
 
 extern "C" {
+
+int pfg_lstm_varlen_workspace_bytes(const pfg_lstm *net, int64_t B, int64_t total_tokens, size_t *bytes) {
+  clear_error();
+  int rc = check_lstm(net);
+  if (rc) return rc;
+  if (!bytes) return fail(PFG_ERR_NULL, "bytes is NULL");
+  if ((rc = check_varlen_sizes(net, B, total_tokens))) return rc;
+  *bytes = make_varlen_plan(net, B, total_tokens).total;
+  return PFG_OK;
+}
+
+int pfg_lstm_varlen_forward(const pfg_lstm *net, const void *X, const int32_t *lengths, int64_t B,
+                            int64_t total_tokens, float *h_out, float *y_out, void *workspace,
+                            size_t workspace_bytes, void *hip_stream) {
+  clear_error();
+  int rc = check_lstm(net);
+  if (rc) return rc;
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!lengths) return fail(PFG_ERR_NULL, "lengths is NULL");
+  if (!h_out && !y_out) return fail(PFG_ERR_NULL, "h_out and y_out are both NULL");
+  if ((rc = check_varlen_sizes(net, B, total_tokens))) return rc;
+  int64_t sum = 0;
+  int32_t longest = 0;
+  for (int64_t b = 0; b < B; ++b) {
+    if (lengths[b] < 1) return fail(PFG_ERR_SHAPE, "lengths[%lld] = %d must be at least 1", (long long)b, lengths[b]);
+    sum += lengths[b];
+    longest = std::max(longest, lengths[b]);
+  }
+  if (sum != total_tokens)
+    return fail(PFG_ERR_SHAPE, "the lengths add up to %lld, total_tokens is %lld", (long long)sum, (long long)total_tokens);
+  const VarlenPlan p = make_varlen_plan(net, B, total_tokens);
+  if (!workspace) return fail(PFG_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", p.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(PFG_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  if (workspace_bytes < p.total)
+    return fail(PFG_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, p.total);
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int32_t dx = net->input_size, H = net->state_size, dy = net->output_size;
+  const float *W = static_cast<const float *>(net->W);
+  void *ws = workspace;
+
+  // ---- active sets of all steps, from the lengths alone (host; index logic only) ----
+  // order: sequences by decreasing length (ties by index); step t is active for the first
+  // active[t] rows of that order.
+  std::vector<int32_t> order(B);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return lengths[a] > lengths[b]; });
+  std::vector<int64_t> first(B + 1, 0);
+  for (int64_t b = 0; b < B; ++b) first[b + 1] = first[b] + lengths[b];
+  // the staging array outlives the call (the copy below may read it after the call returns)
+  thread_local std::vector<int32_t> staged;
+  staged.resize(3 * B);
+  for (int64_t j = 0; j < B; ++j) {
+    staged[j] = (int32_t)first[order[j]];
+    staged[B + j] = order[j];
+    staged[2 * B + j] = lengths[order[j]];
+  }
+  std::vector<int64_t> active(longest);
+  {
+    int64_t n = B;
+    for (int32_t t = 0; t < longest; ++t) {
+      while (n > 0 && staged[2 * B + n - 1] <= t) --n;
+      active[t] = n;
+    }
+  }
+  int32_t *idx = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + p.idx);
+  hipError_t e = hipMemcpyAsync(idx, staged.data(), sizeof(int32_t) * 3 * B, hipMemcpyHostToDevice, stream);
+  if (e != hipSuccess) return fail(PFG_ERR_DEVICE, "index upload: %s", hipGetErrorString(e));
+  const int32_t *tok_row = idx, *orig = idx + B, *len_sorted = idx + 2 * B;
+
+  // ---- input projections of all tokens in one product (no padding: M = total_tokens) ----
+  {
+    GemmArgs g{};
+    g.A = X; g.lda = dx; g.a_batch_stride = dx; g.S = 1; g.a_is_f32 = 1;
+    g.W = W; g.ldw = 4 * H; g.w_kn = 1;
+    g.M = (int32_t)total_tokens; g.N = 4 * H; g.K = dx;
+    g.bias = net->b; g.epilogue = EPI_BIAS;
+    g.C = ws_at(ws, p.zx); g.ldc = 4 * H;
+    PFG_LAUNCH("lstm_gemm_input", launch_gemm(g, stream));
+  }
+  float *hbuf[2] = {ws_at(ws, p.state), ws_at(ws, p.state) + B * (int64_t)H};
+  float *c = ws_at(ws, p.state) + 2 * B * (int64_t)H;
+  PFG_LAUNCH("fill_zero", launch_fill_zero(ws_at(ws, p.state), 3 * B * (int64_t)H, stream));
+
+  // ---- the while loop: step t runs on the active prefix only; h_t goes to buffer t % 2 ----
+  for (int32_t t = 0; t < longest; ++t) {
+    GemmArgs g{};
+    g.A = hbuf[(t + 1) & 1]; g.lda = H; g.a_batch_stride = H; g.S = 1; g.a_is_f32 = 1;
+    g.W = W + (int64_t)dx * 4 * H; g.ldw = 4 * H; g.w_kn = 1;
+    g.M = (int32_t)active[t]; g.N = 4 * H; g.K = H;
+    g.epilogue = EPI_LSTM_FWD;
+    g.lstm_H = H; g.lstm_T = 1; g.lstm_step = t;
+    g.lstm_zx = ws_at(ws, p.zx); g.lstm_zx_rows = tok_row;
+    g.lstm_gates_w = nullptr;
+    g.lstm_cs_w = c; g.lstm_hs_w = hbuf[t & 1];
+    g.lstm_state_ld = H; g.lstm_state_ts = 0; g.lstm_has_prev = 1;
+    PFG_LAUNCH("lstm_step", launch_gemm(g, stream));
+  }
+
+  // ---- back to the caller's order: row j's last state sits in buffer (length - 1) % 2 ----
+  // (parity[j] = length of sorted row j; odd lengths end in buffer 0)
+  float *hfin = h_out ? h_out : ws_at(ws, p.hfin);
+  PFG_LAUNCH("scatter_rows", launch_scatter_rows(hbuf[1], hbuf[0], len_sorted, orig, B, H, hfin, stream));
+  if (y_out) {
+    GemmArgs g{};
+    g.A = hfin; g.lda = H; g.a_batch_stride = H; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->W_out; g.ldw = dy; g.w_kn = 1;
+    g.M = (int32_t)B; g.N = dy; g.K = H;
+    g.bias = net->b_out; g.epilogue = EPI_BIAS;
+    g.C = y_out; g.ldc = dy;
+    PFG_LAUNCH("lstm_gemm_readout", launch_gemm(g, stream));
+  }
+  return PFG_OK;
+}
 
 int pfg_lstm_workspace_bytes(const pfg_lstm *net, int op, int64_t B, int64_t S, size_t *bytes) {
   clear_error();

@@ -158,7 +158,7 @@ def output_values(w: Workload, B: Optional[int] = None) -> int:
 class LstmWorkload:
     name: str
     index: int
-    call: str                      # "lstm_per_example_grads" | "lstm_jacobian_input"
+    call: str                      # "lstm_per_example_grads" | "lstm_jacobian_input" | "lstm_varlen_forward"
     dx: int
     H: int
     dy: int
@@ -171,6 +171,8 @@ LSTM_WORKLOADS: Dict[str, LstmWorkload] = {
     w.name: w for w in [
         LstmWorkload("c7_lstm_grads", 6, "lstm_per_example_grads", 128, 256, 10, 10, 256),
         LstmWorkload("c8_lstm_jacobian", 7, "lstm_jacobian_input", 128, 256, 128, 10, 64, S=128),
+        # sequences of different lengths, each iterated to its own length (T = the longest allowed)
+        LstmWorkload("c9_lstm_varlen", 8, "lstm_varlen_forward", 128, 256, 10, 100, 1024),
     ]
 }
 
@@ -202,3 +204,19 @@ def make_lstm_inputs(w: LstmWorkload, B: Optional[int] = None, dx=None, H=None, 
     X = rng.standard_normal(size=(B, T, dx)).astype(np.float32)
     labels = rng.integers(0, dy, size=(B,)).astype(np.int32)
     return LstmInputs(w, W, b, Wout, bout, X, labels)
+
+
+def make_varlen_inputs(w: LstmWorkload, B: Optional[int] = None, dx=None, H=None, dy=None,
+                       max_len: Optional[int] = None, bias_scale: float = 0.0,
+                       seed: Optional[int] = None):
+    """Weights as in make_lstm_inputs; lengths uniform in 1..max_len (inclusive), tokens standard
+    normal, stored back to back.  Returns (LstmInputs with X = [sum(lengths), dx], lengths int32)."""
+    B = w.B if B is None else B
+    max_len = w.T if max_len is None else max_len
+    base = make_lstm_inputs(w, B=1, dx=dx, H=H, dy=dy, T=1, bias_scale=bias_scale, seed=seed)
+    rng = np.random.Generator(np.random.Philox((BASE_SEED + w.index if seed is None else seed) + 500000))
+    lengths = rng.integers(1, max_len + 1, size=(B,)).astype(np.int32)
+    X = rng.standard_normal(size=(int(lengths.sum()), base.W.shape[0] - base.Wout.shape[0])).astype(np.float32)
+    base.X = X
+    base.labels = np.zeros(B, dtype=np.int32)
+    return base, lengths

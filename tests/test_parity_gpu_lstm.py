@@ -207,3 +207,94 @@ def test_lstm_rejects_bad_arguments():
     with pytest.raises(pfg.PfgError) as ei:
         pfg.pfg_lstm_per_example_grads(net, X, dev(inp.labels), workspace=small)
     assert ei.value.code == pfg.PFG_ERR_WORKSPACE
+
+
+# --------------------------------------------------------------------------------------------
+# Sequences of different lengths: the loop with a shrinking set of active sequences.
+# --------------------------------------------------------------------------------------------
+def check_varlen(inp, lengths, tag, bias=True):
+    b, bout = (inp.b, inp.bout) if bias else (None, None)
+    onet = olstm.Lstm(inp.W, b, inp.Wout, bout, 1)
+    net = pfg.Lstm.from_numpy(inp.W, b, inp.Wout, bout, 1)
+    B = len(lengths)
+    h, y = pfg.pfg_lstm_varlen_forward(net, dev(inp.X), lengths, out_h=nan_like(B, net.H),
+                                       out_y=nan_like(B, net.dy))
+    torch.cuda.synchronize()
+    rh, ry = olstm.varlen_forward(onet, inp.X, lengths)
+    eh = slice_rel_err(h.cpu().numpy(), rh)
+    ey = slice_rel_err(y.cpu().numpy(), ry)
+    say(f"  {tag}: h rel err {eh:.3e}, y rel err {ey:.3e} ({B} sequences, {int(np.sum(lengths))} tokens)")
+    assert max(eh, ey) <= TOL_F32
+    return net, h, y
+
+
+VARLEN_SHAPES = [
+    # dx, H, dy, max_len, B
+    (3, 4, 2, 5, 6),
+    (1, 1, 1, 1, 1),
+    (5, 7, 3, 9, 1),             # a single sequence
+    (33, 65, 10, 12, 40),        # one past the tile edges; more sequences than one row tile
+    (16, 32, 40, 30, 100),
+]
+
+
+@pytest.mark.parametrize("dx,H,dy,max_len,B", VARLEN_SHAPES,
+                         ids=[f"dx{s[0]}-H{s[1]}-dy{s[2]}-L{s[3]}-B{s[4]}" for s in VARLEN_SHAPES])
+def test_varlen_forward_odd_shapes(dx, H, dy, max_len, B):
+    w = wl.LstmWorkload("oddv", 400 + dx + H + max_len, "lstm_varlen_forward", dx, H, dy, max_len, B)
+    inp, lengths = wl.make_varlen_inputs(w, bias_scale=0.3)
+    check_varlen(inp, lengths, f"varlen dx={dx} H={H} L<={max_len}")
+
+
+def test_varlen_forward_special_length_patterns():
+    w = wl.LstmWorkload("patv", 430, "lstm_varlen_forward", 6, 12, 4, 8, 9)
+    inp, _ = wl.make_varlen_inputs(w, bias_scale=0.2, B=9, max_len=8)
+    rng = np.random.default_rng(43)
+    for name, lengths in (("all equal", [5] * 9), ("all one", [1] * 9),
+                          ("increasing", list(range(1, 10))), ("one long", [1, 1, 1, 1, 20, 1, 1, 1, 1]),
+                          ("ties", [3, 7, 3, 7, 1, 3, 7, 1, 2])):
+        lengths = np.asarray(lengths, dtype=np.int32)
+        inp.X = rng.standard_normal((int(lengths.sum()), 6)).astype(np.float32)
+        net, h, y = check_varlen(inp, lengths, f"varlen[{name}]", bias=(name != "ties"))
+    # only one of the two outputs, and each sequence's result does not depend on its neighbours:
+    # the same sequences in another order give the same rows, bit for bit
+    order = np.array([4, 0, 8, 2, 6, 1, 3, 7, 5])
+    starts = np.concatenate([[0], np.cumsum(lengths)])
+    Xp = np.concatenate([inp.X[starts[b]:starts[b + 1]] for b in order])
+    hp, none_y = pfg.pfg_lstm_varlen_forward(net, dev(Xp), lengths[order], want_y=False)
+    torch.cuda.synchronize()
+    assert none_y is None
+    assert torch.equal(hp, h[torch.from_numpy(order).to("cuda:0")])
+
+
+def test_c9_lstm_varlen_full_size_sampled_sequences():
+    w = wl.LSTM_WORKLOADS["c9_lstm_varlen"]
+    inp, lengths = wl.make_varlen_inputs(w)
+    say(f"c9_lstm_varlen: {w.B} sequences of 1..{w.T} tokens ({int(lengths.sum())} tokens), sampled sequences")
+    onet = olstm.Lstm(inp.W, inp.b, inp.Wout, inp.bout, 1)
+    net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, 1)
+    h, y = pfg.pfg_lstm_varlen_forward(net, dev(inp.X), lengths, out_h=nan_like(w.B, w.H),
+                                       out_y=nan_like(w.B, w.dy))
+    torch.cuda.synchronize()
+    assert torch.isfinite(h).all().item() and torch.isfinite(y).all().item()
+    starts = np.concatenate([[0], np.cumsum(lengths)])
+    picks = sorted({0, w.B - 1, int(np.argmax(lengths)), int(np.argmin(lengths))} |
+                   set(np.random.default_rng(9).integers(0, w.B, size=60).tolist()))
+    Xs = np.concatenate([inp.X[starts[b]:starts[b + 1]] for b in picks])
+    rh, ry = olstm.varlen_forward(onet, Xs, lengths[picks])
+    eh = slice_rel_err(h.cpu().numpy()[picks], rh)
+    ey = slice_rel_err(y.cpu().numpy()[picks], ry)
+    say(f"  c9: h rel err {eh:.3e}, y rel err {ey:.3e} over {len(picks)} sequences")
+    assert max(eh, ey) <= TOL_F32
+
+
+def test_varlen_forward_rejects_bad_lengths():
+    w = wl.LstmWorkload("badv", 431, "lstm_varlen_forward", 4, 6, 3, 5, 4)
+    inp, lengths = wl.make_varlen_inputs(w)
+    net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, 1)
+    bad = lengths.copy()
+    bad[1] = 0
+    X = dev(np.zeros((int(bad.sum()), 4), dtype=np.float32))
+    with pytest.raises(pfg.PfgError) as ei:
+        pfg.pfg_lstm_varlen_forward(net, X, bad)
+    assert ei.value.code == pfg.PFG_ERR_SHAPE
