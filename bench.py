@@ -278,8 +278,50 @@ def main():
             f"{rec['roofline']['frac']:.3f}")
         return rec, inp
 
+    def measure_varlen(name, steps, warmup):
+        w = wl.LSTM_WORKLOADS[name]
+        log(f"[bench] {name}: uploading inputs")
+        inp, lengths = wl.make_varlen_inputs(w)
+        net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, 1)
+        X = torch.from_numpy(inp.X).to(dev)
+        B, H, dx, dy = w.B, w.H, w.dx, w.dy
+        tokens = int(lengths.sum())
+        f32 = dict(dtype=torch.float32, device=dev)
+        h, y = torch.empty((B, H), **f32), torch.empty((B, dy), **f32)
+        ws = torch.empty(pfg.pfg_lstm_varlen_workspace_bytes(net, B, tokens), dtype=torch.uint8,
+                         device=dev)
+        step = lambda: pfg.pfg_lstm_varlen_forward(net, X, lengths, out_h=h, out_y=y, workspace=ws)
+        step()
+        torch.cuda.synchronize()
+        log(f"[bench] {name}: timing {steps} steps")
+        sec = timed(step, steps, warmup)
+        kt = kernel_times(step, steps)
+        # every token passes the recurrent product once: 2 * H * 4H flops, plus its input projection
+        flops = tokens * (2 * H * 4 * H)
+        fam = "lstm_step"
+        tf = flops / kt[fam]["ms_per_step"] / 1e9
+        roof = {"kernel": fam, "bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["f32"],
+                "unit": "TFLOP/s", "frac": tf / MFMA_PEAK_TFLOPS["f32"], "traffic": None,
+                "flops_per_launch": flops / kt[fam]["launches_per_step"],
+                "ms_per_launch": kt[fam]["ms_per_step"] / kt[fam]["launches_per_step"],
+                "launches_per_step": kt[fam]["launches_per_step"],
+                "note": "a chain of max(length) dependent launches on a shrinking batch: bound by "
+                        "launch and memory latency, not by either roofline"}
+        rec = {"workload": name, "call": w.call, "input_size": dx, "state_size": H, "output_size": dy,
+               "dtype": "f32", "B": B, "tokens": tokens, "longest": int(lengths.max()), "steps": steps,
+               "ms_per_step": sec * 1e3, "ms_per_step_graph_replay": None,
+               "tokens_per_sec": tokens / sec, "sequences_per_sec": B / sec, "kernels": kt,
+               "kernel_ms_sum": sum(v["ms_per_step"] for v in kt.values()),
+               "launches_per_step": sum(v["launches_per_step"] for v in kt.values()),
+               "roofline": roof}
+        log(f"[bench] {name}: {rec['ms_per_step']:.4f} ms/step, {rec['tokens_per_sec'] / 1e6:.1f} M tokens/s, "
+            f"roofline frac {roof['frac']:.3f}")
+        return rec, inp
+
     def measure_lstm(name, steps, warmup):
         w = wl.LSTM_WORKLOADS[name]
+        if w.call == "lstm_varlen_forward":
+            return measure_varlen(name, steps, warmup)
         log(f"[bench] {name}: uploading inputs")
         inp = wl.make_lstm_inputs(w)
         net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, w.T)
@@ -398,7 +440,8 @@ def main():
                             ("c4_gelu_bf16_grad_norms", max(3, args.steps // 4)),
                             ("c6_tanh_hessian", max(3, args.steps // 20)),
                             ("c7_lstm_grads", max(3, args.steps // 2)),
-                            ("c8_lstm_jacobian", max(3, args.steps // 10))):
+                            ("c8_lstm_jacobian", max(3, args.steps // 10)),
+                            ("c9_lstm_varlen", max(3, args.steps // 10))):
             try:
                 fn = measure_lstm if name in wl.LSTM_WORKLOADS else measure
                 others[name], _ = fn(name, steps, max(1, min(args.warmup, steps // 2)))

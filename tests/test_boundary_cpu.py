@@ -252,6 +252,31 @@ def test_lstm_workspace_and_rejections(lib):
     assert ja(r, FAKE, 2, None, 10, 0, FAKE, FAKE, 8, None) == pfg.PFG_ERR_WORKSPACE
 
 
+def test_lstm_varlen_workspace_and_rejections(lib):
+    net = make_lstm()
+    B, tokens, H = 1024, 51957, 256
+    n = ctypes.c_size_t(0)
+    r = ctypes.byref(net)
+    assert lib.pfg_lstm_varlen_workspace_bytes(r, B, tokens, ctypes.byref(n)) == 0
+    assert n.value == up(4 * tokens * 4 * H) + up(4 * 3 * B * H) + up(4 * B * H) + up(4 * 3 * B)
+    assert lib.pfg_lstm_varlen_workspace_bytes(r, 0, 5, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
+    assert lib.pfg_lstm_varlen_workspace_bytes(r, 8, 7, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE   # a length < 1
+    assert lib.pfg_lstm_varlen_workspace_bytes(r, 8, 1 << 40, ctypes.byref(n)) == pfg.PFG_ERR_OVERFLOW
+    assert lib.pfg_lstm_varlen_workspace_bytes(r, 8, 9, None) == pfg.PFG_ERR_NULL
+    fn = lib.pfg_lstm_varlen_forward
+    big = 1 << 40
+    lens = (ctypes.c_int32 * 3)(2, 1, 4)
+    assert fn(r, None, lens, 3, 7, FAKE, FAKE, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r, FAKE, None, 3, 7, FAKE, FAKE, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r, FAKE, lens, 3, 7, None, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r, FAKE, lens, 3, 8, FAKE, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE       # sum mismatch
+    assert "add up" in lib.pfg_last_error().decode()
+    zero = (ctypes.c_int32 * 3)(2, 0, 5)
+    assert fn(r, FAKE, zero, 3, 7, FAKE, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+    assert fn(r, FAKE, lens, 3, 7, FAKE, FAKE, None, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(r, FAKE, lens, 3, 7, FAKE, FAKE, FAKE, 64, None) == pfg.PFG_ERR_WORKSPACE
+
+
 def test_last_error_is_cleared_by_a_good_call(lib):
     net = make_net([4, 3, 2])
     assert ws_bytes(lib, net, 9, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
