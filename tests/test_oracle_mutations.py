@@ -5,6 +5,7 @@ touches the GPU."""
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 import pytest
 
@@ -68,21 +69,6 @@ MUTANTS = [
 ]
 
 
-@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
-def test_pins_catch_planted_mistake(tmp_path, oracle, name, old, new):
-    src = open(SRC).read()
-    assert src.count(old) >= 1, f"pattern for {name} not found in the oracle source"
-    mutated = tmp_path / "pfg_oracle_mutant.c"
-    mutated.write_text(src.replace(old, new))
-    lib = tmp_path / "libpfg_oracle_mutant.so"
-    oracle.compile_source(str(mutated), str(lib))
-    env = dict(os.environ, PFG_ORACLE_LIB=str(lib))
-    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests",
-                        "test_oracle_pins.py"), "-x", "-q", "-p", "no:cacheprovider"],
-                       env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
-    assert r.returncode != 0, f"mutant {name} passed every pin:\n{r.stdout[-2000:]}"
-
-
 LSTM_SRC = os.path.join(ROOT, "oracle", "lstm_oracle.c")
 
 LSTM_MUTANTS = [
@@ -127,16 +113,46 @@ LSTM_MUTANTS = [
 ]
 
 
-@pytest.mark.parametrize("name,old,new", LSTM_MUTANTS, ids=[m[0] for m in LSTM_MUTANTS])
-def test_lstm_pins_catch_planted_mistake(tmp_path, oracle, name, old, new):
-    src = open(LSTM_SRC).read()
-    assert src.count(old) >= 1, f"pattern for {name} not found in the oracle source"
-    mutated = tmp_path / "lstm_oracle_mutant.c"
-    mutated.write_text(src.replace(old, new))
-    lib = tmp_path / "liblstm_oracle_mutant.so"
-    oracle.compile_source(str(mutated), str(lib))
-    env = dict(os.environ, PFG_LSTM_ORACLE_LIB=str(lib))
-    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests",
-                        "test_oracle_lstm_pins.py"), "-x", "-q", "-p", "no:cacheprovider"],
-                       env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
-    assert r.returncode != 0, f"mutant {name} passed every pin:\n{r.stdout[-2000:]}"
+def run_mutants(oracle, tmp_path, source, mutants, env_var, pins_file):
+    """Build every mutant and run the pin file against it, a few at a time; returns the names of
+    the mutants that survived (passed every pin)."""
+    src = open(source).read()
+    for name, old, _ in mutants:
+        assert src.count(old) >= 1, f"pattern for {name} not found in {os.path.basename(source)}"
+
+    def one(m):
+        name, old, new = m
+        mutated = tmp_path / f"{name}.c"
+        mutated.write_text(src.replace(old, new))
+        lib = tmp_path / f"lib{name}.so"
+        oracle.compile_source(str(mutated), str(lib))
+        env = dict(os.environ, OMP_NUM_THREADS="2")
+        env[env_var] = str(lib)
+        r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", pins_file),
+                            "-x", "-q", "-p", "no:cacheprovider"],
+                           env=env, cwd=ROOT, capture_output=True, text=True, timeout=600)
+        return name, r.returncode, r.stdout[-1500:]
+
+    with ThreadPoolExecutor(max_workers=6) as pool:
+        results = list(pool.map(one, mutants))
+    return [(name, out) for name, rc, out in results if rc == 0]
+
+
+def test_dense_pins_catch_every_planted_mistake(tmp_path, oracle):
+    survivors = run_mutants(oracle, tmp_path, SRC, MUTANTS, "PFG_ORACLE_LIB", "test_oracle_pins.py")
+    assert not survivors, "mutants that passed every pin: " + ", ".join(n for n, _ in survivors)
+
+
+def test_lstm_pins_catch_every_planted_mistake(tmp_path, oracle):
+    survivors = run_mutants(oracle, tmp_path, LSTM_SRC, LSTM_MUTANTS, "PFG_LSTM_ORACLE_LIB",
+                            "test_oracle_lstm_pins.py")
+    assert not survivors, "mutants that passed every pin: " + ", ".join(n for n, _ in survivors)
+
+
+def test_the_unmutated_oracles_pass_their_pins():
+    # the check above would be empty if the pin files failed for another reason
+    for pins in ("test_oracle_pins.py", "test_oracle_lstm_pins.py"):
+        r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", pins), "-x",
+                            "-q", "-p", "no:cacheprovider"], cwd=ROOT, capture_output=True, text=True,
+                           timeout=600)
+        assert r.returncode == 0, r.stdout[-1500:]
