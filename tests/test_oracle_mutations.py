@@ -113,6 +113,44 @@ LSTM_MUTANTS = [
 ]
 
 
+CONV_SRC = os.path.join(ROOT, "oracle", "conv_oracle.c")
+
+CONV_MUTANTS = [
+    ("conv_filter_flipped", "const int yy = y + ky - p, xs = xx + kx - p;\n              if (yy < 0 || yy >= hi || xs < 0 || xs >= wi) continue;      /* zero padding */",
+     "const int yy = y - ky + p, xs = xx - kx + p;\n              if (yy < 0 || yy >= hi || xs < 0 || xs >= wi) continue;"),
+    ("conv_padding_off_by_one", "const int k = net->kernel[i], p = (k - 1) / 2;\n    const double *W = net->Wc[i];\n    const double *bias",
+     "const int k = net->kernel[i], p = (k - 1) / 2 - 1;\n    const double *W = net->Wc[i];\n    const double *bias"),
+    ("conv_weight_index_transposed",
+     "s += in[((size_t)yy * wi + xs) * ci + c] * W[(((size_t)ky * k + kx) * ci + c) * co + o];\n            }\n          t.z",
+     "s += in[((size_t)yy * wi + xs) * ci + c] * W[(((size_t)kx * k + ky) * ci + c) * co + o];\n            }\n          t.z"),
+    ("conv_bias_dropped", "double s = bias ? bias[o] : 0.0;", "double s = 0.0;"),
+    ("pool_takes_minimum", "if (a > best) { best = a; where = (int32_t)at; }",
+     "if (best < 0.0 || a < best) { best = a; where = (int32_t)at; }"),
+    ("pool_before_relu", "const double a = t.z[i][at] > 0.0 ? t.z[i][at] : 0.0;", "const double a = t.z[i][at];"),
+    ("pool_window_stride", "const size_t at = ((size_t)(2 * y + dy) * wi + (2 * xx + dx)) * co + o;",
+     "const size_t at = ((size_t)(y + dy) * wi + (xx + dx)) * co + o;"),
+    ("flatten_order", "out[((size_t)y * wo + xx) * co + o] = best;", "out[((size_t)o * ho + y) * wo + xx] = best;"),
+    ("unpool_to_whole_window", "if (t.z[i][at] > 0.0) dz[at] = dout_buf[cell];          /* relu'(z) at the chosen entry */",
+     "if (t.z[i][at] > 0.0) { dz[at] = dout_buf[cell]; if (at >= (int32_t)co && t.z[i][at - co] > 0.0) dz[at - co] = dout_buf[cell]; }"),
+    ("conv_relu_mask_dropped", "if (t.z[i][at] > 0.0) dz[at] = dout_buf[cell];", "dz[at] = dout_buf[cell];"),
+    ("filter_gradient_shift", "s += in[((size_t)yy * wi + xs) * ci + c] * dz[((size_t)y * wi + xx) * co + o];",
+     "s += in[((size_t)y * wi + xx) * ci + c] * dz[((size_t)yy * wi + xs) * co + o];"),
+    ("conv_bias_gradient_not_summed", "for (int xx = 0; xx < wi; ++xx) s += dz[((size_t)y * wi + xx) * co + o];",
+     "for (int xx = 0; xx < wi; ++xx) s = dz[((size_t)y * wi + xx) * co + o];"),
+    ("input_cotangent_not_accumulated", "din[((size_t)yy * wi + xs) * ci + c] += s;", "din[((size_t)yy * wi + xs) * ci + c] = s;"),
+    ("input_cotangent_filter_flipped",
+     "s += dz[((size_t)y * wi + xx) * co + o] * W[(((size_t)ky * k + kx) * ci + c) * co + o];",
+     "s += dz[((size_t)y * wi + xx) * co + o] * W[(((size_t)(k - 1 - ky) * k + (k - 1 - kx)) * ci + c) * co + o];"),
+    ("dense_input_cotangent_masked", "gprev[r] = (l > 1) ? (t.dz[l - 2][r] > 0.0 ? s : 0.0) : s;",
+     "gprev[r] = (t.dz[l > 1 ? l - 2 : 0][r < net->dims[1] ? r : 0] > 0.0 ? s : 0.0);"),
+    ("dense_uses_preactivation", "const double *ain = (l == 1) ? t.flat : t.da[l - 2];",
+     "const double *ain = (l == 1) ? t.flat : t.dz[l - 2];"),
+    ("head_sign", "g[label] -= 1.0;", "g[label] += 1.0;"),
+    ("per_example_slice_offset", "if (dWc && dWc[j]) dWci[j] = dWc[j] + (size_t)i * nW;",
+     "if (dWc && dWc[j]) dWci[j] = dWc[j] + (size_t)(B - 1 - i) * nW;"),
+]
+
+
 def run_mutants(oracle, tmp_path, source, mutants, env_var, pins_file):
     """Build every mutant and run the pin file against it, a few at a time; returns the names of
     the mutants that survived (passed every pin)."""
@@ -149,9 +187,15 @@ def test_lstm_pins_catch_every_planted_mistake(tmp_path, oracle):
     assert not survivors, "mutants that passed every pin: " + ", ".join(n for n, _ in survivors)
 
 
+def test_conv_pins_catch_every_planted_mistake(tmp_path, oracle):
+    survivors = run_mutants(oracle, tmp_path, CONV_SRC, CONV_MUTANTS, "PFG_CONV_ORACLE_LIB",
+                            "test_oracle_conv_pins.py")
+    assert not survivors, "mutants that passed every pin: " + ", ".join(n for n, _ in survivors)
+
+
 def test_the_unmutated_oracles_pass_their_pins():
     # the check above would be empty if the pin files failed for another reason
-    for pins in ("test_oracle_pins.py", "test_oracle_lstm_pins.py"):
+    for pins in ("test_oracle_pins.py", "test_oracle_lstm_pins.py", "test_oracle_conv_pins.py"):
         r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", pins), "-x",
                             "-q", "-p", "no:cacheprovider"], cwd=ROOT, capture_output=True, text=True,
                            timeout=600)
