@@ -232,6 +232,40 @@ int pfg_lstm_varlen_forward(const pfg_lstm *net, const void *X, const int32_t *l
                             int64_t total_tokens, float *h_out, float *y_out, void *workspace,
                             size_t workspace_bytes, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Convolutional network of the paper's MNIST benchmarks (Section 6.1: conv-relu-maxpool blocks
+ * followed by dense layers; the dropout of that model is a stateful random op and is left out).
+ * Images are [height, width, channels], channel index fastest.  Conv block i:
+ *      z[y, x, co] = bc[co] + sum_{ky, kx, ci} in[y + ky - p, x + kx - p, ci] * Wc[ky, kx, ci, co]
+ *      p = (k - 1) / 2, k odd, zero outside the image; a = relu(z); 2 x 2 max-pooling, stride 2
+ *      (the height and width entering every block must be even)
+ * The last block's output, flattened in (y, x, c) order, is the input of `dense`
+ * (dense.dims[0] must equal its size; dense.dtype must be PFG_F32).
+ * ---------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t height, width, channels;
+  int32_t num_conv;          /* >= 1 */
+  const int32_t *kernel;     /* HOST [num_conv], odd                                          */
+  const int32_t *filters;    /* HOST [num_conv] output channels                               */
+  const void *const *Wc;     /* HOST array of num_conv device pointers, [k, k, c_in, c_out]   */
+  const void *const *bc;     /* HOST array of device pointers or NULL; NULL entry = zero bias */
+  pfg_mlp dense;
+} pfg_convnet;
+
+int pfg_convnet_workspace_bytes(const pfg_convnet *net, int64_t B, size_t *bytes);
+
+/* Per-example gradients (Section 5.3) of ell_b = -log softmax(y_b)[labels[b]] for every parameter.
+ * A convolution's filter is shared by all positions of an image, so an example's filter gradient
+ * is a sum over the positions (one product per example); different examples stay separate.
+ *   X        [B, height, width, channels] float32
+ *   dWc_out  HOST array of num_conv device pointers, entry i is [B, k, k, c_in, c_out]; NULL skips
+ *   dbc_out  HOST array of num_conv device pointers, entry i is [B, c_out]; NULL skips
+ *   dW_out, db_out, loss_out   for the dense layers, as for pfg_per_example_grads */
+int pfg_convnet_per_example_grads(const pfg_convnet *net, const void *X, const int32_t *labels,
+                                  int64_t B, float *const *dWc_out, float *const *dbc_out,
+                                  float *const *dW_out, float *const *db_out, float *loss_out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Text of the last error on the calling thread ("" if none).  Valid until the next call into the
  * library from that thread. */
 const char *pfg_last_error(void);

@@ -28,6 +28,7 @@ EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_jacobian_input",
            "pfg_jacobian_weights", "pfg_per_example_grad_norms", "pfg_hessian_input",
            "pfg_lstm_workspace_bytes", "pfg_lstm_per_example_grads", "pfg_lstm_jacobian_input",
            "pfg_lstm_varlen_workspace_bytes", "pfg_lstm_varlen_forward",
+           "pfg_convnet_workspace_bytes", "pfg_convnet_per_example_grads",
            "pfg_last_error", "pfg_timing_enable", "pfg_timing_reset",
            "pfg_timing_query", "pfg_timing_names", "pfg_version"]
 
@@ -60,6 +61,20 @@ class pfg_lstm(ctypes.Structure):
         ("W_out", ctypes.c_void_p),
         ("b_out", ctypes.c_void_p),
         ("dtype", ctypes.c_int32),
+    ]
+
+
+class pfg_convnet(ctypes.Structure):
+    _fields_ = [
+        ("height", ctypes.c_int32),
+        ("width", ctypes.c_int32),
+        ("channels", ctypes.c_int32),
+        ("num_conv", ctypes.c_int32),
+        ("kernel", ctypes.POINTER(ctypes.c_int32)),
+        ("filters", ctypes.POINTER(ctypes.c_int32)),
+        ("Wc", ctypes.POINTER(ctypes.c_void_p)),
+        ("bc", ctypes.POINTER(ctypes.c_void_p)),
+        ("dense", pfg_mlp),
     ]
 
 
@@ -97,6 +112,11 @@ def load_library() -> ctypes.CDLL:
         lib.pfg_lstm_varlen_workspace_bytes.argtypes = [lstmp, i64, i64, ctypes.POINTER(ctypes.c_size_t)]
         lib.pfg_lstm_varlen_forward.argtypes = [lstmp, vp, ctypes.POINTER(ctypes.c_int32), i64, i64, vp,
                                                 vp, vp, ctypes.c_size_t, vp]
+        convp = ctypes.POINTER(pfg_convnet)
+        lib.pfg_convnet_workspace_bytes.argtypes = [convp, i64, ctypes.POINTER(ctypes.c_size_t)]
+        lib.pfg_convnet_per_example_grads.argtypes = [convp, vp, vp, i64, ctypes.POINTER(vp),
+                                                      ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                                      ctypes.POINTER(vp), vp, vp, ctypes.c_size_t, vp]
         lib.pfg_last_error.restype = ctypes.c_char_p
         lib.pfg_timing_enable.argtypes = [i32]
         lib.pfg_timing_query.argtypes = [ctypes.c_char_p, ctypes.POINTER(i64),
@@ -440,6 +460,90 @@ def pfg_lstm_varlen_forward(net: Lstm, X, lengths, want_h: bool = True, want_y: 
         total, None if h is None else h.data_ptr(), None if y is None else y.data_ptr(),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr()))
     return h, y
+
+
+class ConvNet:
+    """Device-resident convolutional network: conv blocks (Wc[i] [k, k, c_in, c_out], bc[i] [c_out]
+    or None; "same" convolution + ReLU + 2 x 2 max-pooling) followed by the dense layers of an
+    ``Mlp`` (float32, ReLU) whose input width equals the flattened output of the last block."""
+
+    def __init__(self, height: int, width: int, channels: int, Wc: Sequence, bc: Optional[Sequence],
+                 dense: Mlp):
+        import torch
+        self.height, self.width, self.channels = int(height), int(width), int(channels)
+        self.Wc = list(Wc)
+        self.nc = len(self.Wc)
+        self.bc = [None] * self.nc if bc is None else list(bc)
+        for t in self.Wc + [b for b in self.bc if b is not None]:
+            if t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
+                raise ValueError("conv weights must be contiguous float32 GPU tensors")
+        self.kernel = [int(W.shape[0]) for W in self.Wc]
+        self.filters = [int(W.shape[3]) for W in self.Wc]
+        c = self.channels
+        for i, W in enumerate(self.Wc):
+            if tuple(W.shape) != (self.kernel[i], self.kernel[i], c, self.filters[i]):
+                raise ValueError(f"Wc[{i}] has shape {tuple(W.shape)}")
+            if self.bc[i] is not None and tuple(self.bc[i].shape) != (self.filters[i],):
+                raise ValueError(f"bc[{i}] has shape {tuple(self.bc[i].shape)}")
+            c = self.filters[i]
+        self.dense = dense
+        self.device = dense.device
+        self._kernel = (ctypes.c_int32 * self.nc)(*self.kernel)
+        self._filters = (ctypes.c_int32 * self.nc)(*self.filters)
+        self._Wc = (ctypes.c_void_p * self.nc)(*[W.data_ptr() for W in self.Wc])
+        self._bc = (ctypes.c_void_p * self.nc)(*[None if b is None else b.data_ptr() for b in self.bc])
+        self.c = pfg_convnet(self.height, self.width, self.channels, self.nc, self._kernel,
+                             self._filters, self._Wc, self._bc, dense.c)
+
+    @staticmethod
+    def from_numpy(height, width, channels, Wc, bc, Ws, bs, device: str = "cuda:0") -> "ConvNet":
+        import torch
+        up = lambda a: None if a is None else torch.from_numpy(a).to(device)
+        dense = Mlp.from_numpy(Ws, bs, "relu", "f32", device=device)
+        return ConvNet(height, width, channels, [up(W) for W in Wc],
+                       None if bc is None else [up(b) for b in bc], dense)
+
+
+def pfg_convnet_workspace_bytes(net: ConvNet, B: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().pfg_convnet_workspace_bytes(ctypes.byref(net.c), B, ctypes.byref(n)))
+    return int(n.value)
+
+
+def pfg_convnet_per_example_grads(net: ConvNet, X, labels, want_dWc: Optional[Sequence[bool]] = None,
+                                  want_dbc: bool = True, want_dW: Optional[Sequence[bool]] = None,
+                                  want_db: bool = True, want_loss: bool = True, out=None,
+                                  workspace=None):
+    """Returns (dWc list [B, k, k, c_in, c_out], dbc list [B, c_out], dW list [B, d_l, d_{l+1}],
+    db list [B, d_{l+1}], loss [B]); entries / lists that are not wanted are None.  ``out`` may hold
+    caller tensors in that structure."""
+    import torch
+    if (X.dtype != torch.float32 or not X.is_contiguous() or X.dim() != 4 or
+            tuple(X.shape[1:]) != (net.height, net.width, net.channels)):
+        raise ValueError("X must be a contiguous float32 [B, height, width, channels] tensor")
+    B = X.shape[0]
+    if labels.dtype != torch.int32 or tuple(labels.shape) != (B,) or not labels.is_contiguous():
+        raise ValueError("labels must be a contiguous int32 [B] tensor")
+    f32 = dict(dtype=torch.float32, device=net.device)
+    dn = net.dense
+    if out is not None:
+        dWc, dbc, dW, db, loss = out
+    else:
+        wc = [True] * net.nc if want_dWc is None else list(want_dWc)
+        wd = [True] * dn.L if want_dW is None else list(want_dW)
+        dWc = [torch.empty((B,) + tuple(net.Wc[i].shape), **f32) if wc[i] else None for i in range(net.nc)]
+        dbc = [torch.empty((B, net.filters[i]), **f32) for i in range(net.nc)] if want_dbc else None
+        dW = [torch.empty((B, dn.dims[l], dn.dims[l + 1]), **f32) if wd[l] else None for l in range(dn.L)]
+        db = [torch.empty((B, dn.dims[l + 1]), **f32) for l in range(dn.L)] if want_db else None
+        loss = torch.empty((B,), **f32) if want_loss else None
+    if workspace is None:
+        workspace = torch.empty(pfg_convnet_workspace_bytes(net, B), dtype=torch.uint8, device=net.device)
+    _check(load_library().pfg_convnet_per_example_grads(
+        ctypes.byref(net.c), X.data_ptr(), labels.data_ptr(), B, _ptrs(dWc),
+        _ptrs(dbc) if dbc is not None else None, _ptrs(dW), _ptrs(db) if db is not None else None,
+        None if loss is None else loss.data_ptr(), workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _stream_ptr()))
+    return dWc, dbc, dW, db, loss
 
 
 def pfg_timing_enable(on: bool) -> None:

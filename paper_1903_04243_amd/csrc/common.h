@@ -210,4 +210,23 @@ hipError_t launch_outer_sum(const OuterSumJob *jobs, int njobs, int64_t B, int32
 hipError_t launch_sum_steps(const float *g, int64_t B, int32_t T, int32_t d, float *out,
                             hipStream_t stream);
 
+// Patches of a "same"-size k x k convolution over in [B, h, w, c]: P [B h w, k k c] (one row per
+// output position) and / or PT [B, k k c, h w] (the same values per example with the position index
+// fastest); either may be null.
+hipError_t launch_im2col(const float *in, int64_t B, int32_t h, int32_t w, int32_t c, int32_t k,
+                         float *P, float *PT, hipStream_t stream);
+
+// pooled [B, h/2, w/2, c] = max over 2 x 2 windows of relu(z [B, h, w, c]); which = index 0..3 of the
+// window entry that gave it
+hipError_t launch_relu_pool(const float *z, int64_t B, int32_t h, int32_t w, int32_t c, float *pooled,
+                            uint8_t *which, hipStream_t stream);
+
+// dz [B, h, w, c] from the cotangent of the pooled output (relu' and the window selection applied)
+hipError_t launch_unpool_mask(const float *dpooled, const float *pooled, const uint8_t *which, int64_t B,
+                              int32_t h, int32_t w, int32_t c, float *dz, hipStream_t stream);
+
+// din [B, h, w, c] = gather of the patch cotangents dP [B h w, k k c]
+hipError_t launch_col2im(const float *dP, int64_t B, int32_t h, int32_t w, int32_t c, int32_t k,
+                         float *din, hipStream_t stream);
+
 }  // namespace pfg

@@ -1,0 +1,171 @@
+// Kernels of the convolutional blocks that are not matrix products.  Images are [B, h, w, c] with
+// the channel index fastest.  A "same"-size k x k convolution becomes a product once every output
+// position has its k * k * c input patch laid out as a row (Section 3.4's convolution rule folds the
+// example index into the batch of positions: rows (b, y, x)); the per-example filter gradient is a
+// product per example over the positions, for which the patches are also kept with the position
+// index fastest.
+#include "common.h"
+
+namespace pfg {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+inline unsigned capped_blocks(int64_t work_items) {
+  const int64_t blocks = (work_items + kThreads - 1) / kThreads;
+  return (unsigned)(blocks < (1 << 20) ? blocks : (1 << 20));
+}
+
+// P[(b, y, x), (ky, kx, c)] = in[b, y + ky - p, x + kx - p, c] (zero outside the image).
+// ROWS_ARE_POSITIONS: P is [B h w, k k c] (consecutive threads walk a patch); otherwise the
+// transposed per-example layout [B, k k c, h w] (consecutive threads walk the positions).
+template <bool ROWS_ARE_POSITIONS>
+__global__ __launch_bounds__(kThreads) void im2col_kernel(const float *in, int64_t B, int h, int w, int c,
+                                                          int k, float *out) {
+  const int p = (k - 1) / 2, hw = h * w, kkc = k * k * c;
+  const int64_t total = B * hw * kkc;
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += step) {
+    int64_t b;
+    int pos, e;
+    if (ROWS_ARE_POSITIONS) {
+      const int64_t row = i / kkc;
+      e = (int)(i - row * kkc);
+      b = row / hw;
+      pos = (int)(row - b * hw);
+    } else {
+      const int64_t row = i / hw;
+      pos = (int)(i - row * hw);
+      b = row / kkc;
+      e = (int)(row - b * kkc);
+    }
+    const int y = pos / w, x = pos - y * w;
+    const int kyx = e / c, ch = e - kyx * c;
+    const int ky = kyx / k, kx = kyx - ky * k;
+    const int yy = y + ky - p, xx = x + kx - p;
+    float v = 0.f;
+    if (yy >= 0 && yy < h && xx >= 0 && xx < w) v = in[((b * h + yy) * w + xx) * c + ch];
+    out[i] = v;
+  }
+}
+
+// a = relu(z); pooled = max of each 2 x 2 window, which = position of the first maximum in the
+// order (0,0), (0,1), (1,0), (1,1).  One thread per pooled cell, channel fastest.
+__global__ __launch_bounds__(kThreads) void relu_pool_kernel(const float *z, int64_t B, int h, int w, int c,
+                                                             float *pooled, uint8_t *which) {
+  const int ho = h / 2, wo = w / 2;
+  const int64_t total = B * ho * wo * c;
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += step) {
+    const int ch = (int)(i % c);
+    int64_t r = i / c;
+    const int xo = (int)(r % wo);
+    r /= wo;
+    const int yo = (int)(r % ho);
+    const int64_t b = r / ho;
+    float best = -1.f;
+    int arg = 0;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const float v = z[((b * h + 2 * yo + (d >> 1)) * w + 2 * xo + (d & 1)) * c + ch];
+      const float a = v > 0.f ? v : 0.f;
+      if (a > best) { best = a; arg = d; }
+    }
+    pooled[i] = best;
+    which[i] = (uint8_t)arg;
+  }
+}
+
+// Cotangent of the conv pre-activations from the cotangent of the pooled output: the window entry
+// that gave the maximum receives it if it was positive (relu'), the others receive zero.  Every
+// entry of dz is written.
+__global__ __launch_bounds__(kThreads) void unpool_mask_kernel(const float *dpooled, const float *pooled,
+                                                               const uint8_t *which, int64_t B, int h,
+                                                               int w, int c, float *dz) {
+  const int ho = h / 2, wo = w / 2;
+  const int64_t total = B * ho * wo * c;
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += step) {
+    const int ch = (int)(i % c);
+    int64_t r = i / c;
+    const int xo = (int)(r % wo);
+    r /= wo;
+    const int yo = (int)(r % ho);
+    const int64_t b = r / ho;
+    const float g = pooled[i] > 0.f ? dpooled[i] : 0.f;
+    const int arg = which[i];
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+      dz[((b * h + 2 * yo + (d >> 1)) * w + 2 * xo + (d & 1)) * c + ch] = (d == arg) ? g : 0.f;
+  }
+}
+
+// din[b, yy, xx, ch] = sum over the patches that contain the pixel of their cotangent entry:
+// dP[(b, yy - ky + p, xx - kx + p), (ky, kx, ch)].  A gather in a fixed order (no atomics).
+__global__ __launch_bounds__(kThreads) void col2im_kernel(const float *dP, int64_t B, int h, int w, int c,
+                                                          int k, float *din) {
+  const int p = (k - 1) / 2, kkc = k * k * c;
+  const int64_t total = B * h * w * c;
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += step) {
+    const int ch = (int)(i % c);
+    int64_t r = i / c;
+    const int xx = (int)(r % w);
+    r /= w;
+    const int yy = (int)(r % h);
+    const int64_t b = r / h;
+    float s = 0.f;
+    for (int ky = 0; ky < k; ++ky) {
+      const int y = yy - ky + p;
+      if (y < 0 || y >= h) continue;
+      for (int kx = 0; kx < k; ++kx) {
+        const int x = xx - kx + p;
+        if (x < 0 || x >= w) continue;
+        s += dP[((b * h + y) * w + x) * (int64_t)kkc + (ky * k + kx) * c + ch];
+      }
+    }
+    din[i] = s;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_im2col(const float *in, int64_t B, int32_t h, int32_t w, int32_t c, int32_t k,
+                         float *P, float *PT, hipStream_t stream) {
+  const int64_t total = B * h * w * k * k * c;
+  if (total <= 0) return hipSuccess;
+  if (P) PFG_KERNEL(im2col_kernel<true>, dim3(capped_blocks(total)), dim3(kThreads), 0, stream, in, B, h,
+                    w, c, k, P);
+  if (PT) PFG_KERNEL(im2col_kernel<false>, dim3(capped_blocks(total)), dim3(kThreads), 0, stream, in, B,
+                     h, w, c, k, PT);
+  return hipGetLastError();
+}
+
+hipError_t launch_relu_pool(const float *z, int64_t B, int32_t h, int32_t w, int32_t c, float *pooled,
+                            uint8_t *which, hipStream_t stream) {
+  const int64_t total = B * (h / 2) * (w / 2) * c;
+  if (total <= 0) return hipSuccess;
+  PFG_KERNEL(relu_pool_kernel, dim3(capped_blocks(total)), dim3(kThreads), 0, stream, z, B, h, w, c,
+             pooled, which);
+  return hipGetLastError();
+}
+
+hipError_t launch_unpool_mask(const float *dpooled, const float *pooled, const uint8_t *which, int64_t B,
+                              int32_t h, int32_t w, int32_t c, float *dz, hipStream_t stream) {
+  const int64_t total = B * (h / 2) * (w / 2) * c;
+  if (total <= 0) return hipSuccess;
+  PFG_KERNEL(unpool_mask_kernel, dim3(capped_blocks(total)), dim3(kThreads), 0, stream, dpooled, pooled,
+             which, B, h, w, c, dz);
+  return hipGetLastError();
+}
+
+hipError_t launch_col2im(const float *dP, int64_t B, int32_t h, int32_t w, int32_t c, int32_t k,
+                         float *din, hipStream_t stream) {
+  const int64_t total = B * h * w * c;
+  if (total <= 0) return hipSuccess;
+  PFG_KERNEL(col2im_kernel, dim3(capped_blocks(total)), dim3(kThreads), 0, stream, dP, B, h, w, c, k, din);
+  return hipGetLastError();
+}
+
+}  // namespace pfg

@@ -644,6 +644,227 @@ int pfg_hessian_input(const pfg_mlp *net, const void *X, int64_t B, const float 
   return PFG_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+struct ConvBlock {
+  int h, w, ci, co, k;     // input size and channels, output channels, kernel size
+  size_t P, PT, z, pooled, which, dz;
+};
+
+struct ConvPlan {
+  size_t total = 0;
+  std::vector<ConvBlock> blocks;
+  size_t dout[2] = {0, 0};     // cotangents of pooled outputs, used alternately
+  size_t dense = 0;            // sub-workspace of the dense layers
+  size_t dense_bytes = 0;
+  size_t take(size_t bytes) {
+    const size_t at = total;
+    total += (bytes + 255) / 256 * 256;
+    return at;
+  }
+};
+
+int check_convnet(const pfg_convnet *net, int64_t B) {
+  if (!net) return fail(PFG_ERR_NULL, "net is NULL");
+  if (net->num_conv < 1 || net->num_conv > 64)
+    return fail(PFG_ERR_SHAPE, "num_conv = %d is outside [1, 64]", net->num_conv);
+  if (!net->kernel || !net->filters) return fail(PFG_ERR_NULL, "net->kernel or net->filters is NULL");
+  if (net->height < 1 || net->width < 1 || net->channels < 1)
+    return fail(PFG_ERR_SHAPE, "image size %d x %d x %d", net->height, net->width, net->channels);
+  int rc = check_net(&net->dense);
+  if (rc) return rc;
+  if (net->dense.dtype != PFG_F32)
+    return fail(PFG_ERR_UNSUPPORTED, "the convolutional path is float32 only (dtype %d given)", net->dense.dtype);
+  if (B < 1 || B > 65535) return fail(PFG_ERR_SHAPE, "B = %lld is outside [1, 65535]", (long long)B);
+  int64_t h = net->height, w = net->width, c = net->channels;
+  for (int i = 0; i < net->num_conv; ++i) {
+    const int64_t k = net->kernel[i], f = net->filters[i];
+    if (k < 1 || k % 2 == 0 || k > 31) return fail(PFG_ERR_SHAPE, "kernel[%d] = %lld must be odd and at most 31", i, (long long)k);
+    if (f < 1 || f > (1 << 16)) return fail(PFG_ERR_SHAPE, "filters[%d] = %lld is out of range", i, (long long)f);
+    if (h % 2 || w % 2) return fail(PFG_ERR_SHAPE, "conv block %d sees a %lld x %lld image; both must be even", i, (long long)h, (long long)w);
+    if (h * w * k * k * c > 0x7fffffffLL / 2 || B * h * w > kMaxRows || B * h * w * k * k * c > kMaxElems)
+      return fail(PFG_ERR_OVERFLOW, "conv block %d is too large for B = %lld", i, (long long)B);
+    h /= 2; w /= 2; c = f;
+  }
+  if (h * w * c != net->dense.dims[0])
+    return fail(PFG_ERR_SHAPE, "the conv blocks produce %lld features, dense.dims[0] is %d", (long long)(h * w * c), net->dense.dims[0]);
+  return PFG_OK;
+}
+
+ConvPlan make_conv_plan(const pfg_convnet *net, int64_t B) {
+  ConvPlan p;
+  const size_t f = sizeof(float);
+  int h = net->height, w = net->width, c = net->channels;
+  size_t widest_pooled = 0;
+  for (int i = 0; i < net->num_conv; ++i) {
+    ConvBlock blk{};
+    blk.h = h; blk.w = w; blk.ci = c; blk.co = net->filters[i]; blk.k = net->kernel[i];
+    const size_t hw = (size_t)h * w, kkc = (size_t)blk.k * blk.k * c, cells = (size_t)(h / 2) * (w / 2) * blk.co;
+    blk.P = p.take(f * B * hw * kkc);
+    blk.PT = p.take(f * B * hw * kkc);
+    blk.z = p.take(f * B * hw * blk.co);
+    blk.dz = p.take(f * B * hw * blk.co);
+    blk.pooled = p.take(f * B * cells);
+    blk.which = p.take(B * cells);
+    widest_pooled = std::max(widest_pooled, B * cells);
+    p.blocks.push_back(blk);
+    h /= 2; w /= 2; c = blk.co;
+  }
+  p.dout[0] = p.take(f * widest_pooled);
+  p.dout[1] = p.take(f * widest_pooled);
+  p.dense_bytes = make_plan(&net->dense, PFG_OP_PER_EXAMPLE_GRADS, B, 1).total;
+  p.dense = p.take(p.dense_bytes);
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pfg_convnet_workspace_bytes(const pfg_convnet *net, int64_t B, size_t *bytes) {
+  g_err[0] = 0;
+  int rc = check_convnet(net, B);
+  if (rc) return rc;
+  if (!bytes) return fail(PFG_ERR_NULL, "bytes is NULL");
+  if ((rc = check_elems(&net->dense, B))) return rc;
+  *bytes = make_conv_plan(net, B).total;
+  return PFG_OK;
+}
+
+int pfg_convnet_per_example_grads(const pfg_convnet *net, const void *X, const int32_t *labels,
+                                  int64_t B, float *const *dWc_out, float *const *dbc_out,
+                                  float *const *dW_out, float *const *db_out, float *loss_out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  int rc = check_convnet(net, B);
+  if (rc) return rc;
+  if ((rc = check_weights(&net->dense))) return rc;
+  if (!net->Wc) return fail(PFG_ERR_NULL, "net->Wc is NULL");
+  for (int i = 0; i < net->num_conv; ++i)
+    if (!net->Wc[i]) return fail(PFG_ERR_NULL, "net->Wc[%d] is NULL", i);
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
+  if ((rc = check_elems(&net->dense, B))) return rc;
+  const ConvPlan cp = make_conv_plan(net, B);
+  if (!workspace) return fail(PFG_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", cp.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(PFG_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  if (workspace_bytes < cp.total)
+    return fail(PFG_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, cp.total);
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  void *ws = workspace;
+  const pfg_mlp *dn = &net->dense;
+  const int L = dn->num_layers, nc = net->num_conv;
+  const int32_t *d = dn->dims;
+
+  // ---- conv blocks, forward: patches, one product over the rows (b, y, x), relu + pooling ----
+  const float *in = static_cast<const float *>(X);
+  for (int i = 0; i < nc; ++i) {
+    const ConvBlock &blk = cp.blocks[i];
+    const int64_t rows = B * blk.h * blk.w;
+    const int kkc = blk.k * blk.k * blk.ci;
+    const bool want_filter = dWc_out && dWc_out[i];
+    PFG_LAUNCH("im2col", launch_im2col(in, B, blk.h, blk.w, blk.ci, blk.k, at(ws, blk.P),
+                                       want_filter ? at(ws, blk.PT) : nullptr, stream));
+    GemmArgs g{};
+    g.A = at(ws, blk.P); g.lda = kkc; g.a_batch_stride = kkc; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->Wc[i]; g.ldw = blk.co; g.w_kn = 1;
+    g.M = (int32_t)rows; g.N = blk.co; g.K = kkc;
+    g.bias = net->bc ? net->bc[i] : nullptr;
+    g.epilogue = EPI_BIAS;
+    g.C = at(ws, blk.z); g.ldc = blk.co;
+    PFG_LAUNCH("conv_gemm_forward", launch_gemm(g, stream));
+    PFG_LAUNCH("relu_pool", launch_relu_pool(at(ws, blk.z), B, blk.h, blk.w, blk.co, at(ws, blk.pooled),
+                                             reinterpret_cast<uint8_t *>(static_cast<char *>(ws) + blk.which),
+                                             stream));
+    in = at(ws, blk.pooled);
+  }
+  const float *feat = in;       // [B, d_0]
+
+  // ---- dense layers: forward, loss head, cotangent chain down to layer 1 ----
+  void *dws = static_cast<char *>(ws) + cp.dense;
+  const Plan p = make_plan(dn, PFG_OP_PER_EXAMPLE_GRADS, B, 1);
+  std::vector<float *> G(L + 1, nullptr);
+  for (int l = 1; l <= L; ++l) G[l] = (db_out && db_out[l - 1]) ? db_out[l - 1] : at(dws, p.G[l]);
+  bool top_step_done = false;
+  if (d[L] <= 32) {
+    top_step_done = (L >= 2);
+    const HeadFusion hf{labels, G[L], loss_out, top_step_done ? G[L - 1] : nullptr};
+    if ((rc = forward(dn, feat, B, L, dws, p, true, stream, &hf))) return rc;
+  } else {
+    if ((rc = forward(dn, feat, B, L, dws, p, true, stream))) return rc;
+    PFG_LAUNCH("head", launch_head_softmax_ce(at(dws, p.logits), labels, B, d[L], G[L], loss_out, stream));
+  }
+  for (int l = top_step_done ? L - 1 : L; l > 1; --l)
+    if ((rc = cotangent_step(dn, l, G[l], B, 1, G[l - 1], dws, p, stream))) return rc;
+  {
+    std::vector<OuterArgs> jobs;
+    for (int l = 1; l <= L; ++l)
+      if (dW_out && dW_out[l - 1]) jobs.push_back(outer_job(dn, l, feat, G[l], B, 1, dW_out[l - 1], dws, p));
+    std::stable_sort(jobs.begin(), jobs.end(), [](const OuterArgs &x, const OuterArgs &y) {
+      return (int64_t)x.d_in * x.d_out > (int64_t)y.d_in * y.d_out;
+    });
+    if (!jobs.empty()) PFG_LAUNCH("outer_product", launch_outer(jobs.data(), (int)jobs.size(), stream));
+  }
+  bool any_conv = false;
+  for (int i = 0; i < nc; ++i) any_conv = any_conv || (dWc_out && dWc_out[i]) || (dbc_out && dbc_out[i]);
+  if (!any_conv) return PFG_OK;
+
+  // cotangent of the flattened features: G_1 W_1^T (nothing masks it: the pooling step follows)
+  float *dout = at(ws, cp.dout[0]);
+  int which_dout = 0;
+  {
+    GemmArgs g{};
+    g.A = G[1]; g.lda = d[1]; g.a_batch_stride = d[1]; g.S = 1; g.a_is_f32 = 1;
+    g.W = dn->W[0]; g.ldw = d[1]; g.w_kn = 0;
+    g.M = (int32_t)B; g.N = d[0]; g.K = d[1];
+    g.epilogue = EPI_NONE; g.C = dout; g.ldc = d[0];
+    PFG_LAUNCH("gemm_cotangent", launch_gemm(g, stream));
+  }
+
+  // ---- conv blocks, reverse ----
+  for (int i = nc - 1; i >= 0; --i) {
+    const ConvBlock &blk = cp.blocks[i];
+    const int hw = blk.h * blk.w, kkc = blk.k * blk.k * blk.ci;
+    const int64_t rows = B * hw;
+    float *dz = at(ws, blk.dz);
+    PFG_LAUNCH("unpool_mask", launch_unpool_mask(dout, at(ws, blk.pooled),
+                                                 reinterpret_cast<const uint8_t *>(static_cast<char *>(ws) + blk.which),
+                                                 B, blk.h, blk.w, blk.co, dz, stream));
+    if (dbc_out && dbc_out[i])
+      PFG_LAUNCH("sum_positions", launch_sum_steps(dz, B, hw, blk.co, dbc_out[i], stream));
+    if (dWc_out && dWc_out[i]) {
+      // both operands stacked (Section 3.4): for each example [k k c_in, h w] x [h w, c_out]
+      GemmArgs g{};
+      g.A = at(ws, blk.PT); g.lda = hw; g.a_batch_stride = 0; g.S = kkc; g.a_is_f32 = 1;
+      g.W = dz; g.ldw = blk.co; g.w_kn = 1;
+      g.M = kkc; g.N = blk.co; g.K = hw;
+      g.epilogue = EPI_NONE;
+      g.C = dWc_out[i]; g.ldc = blk.co; g.streaming = 1;
+      g.nbatch = (int32_t)B;
+      g.batch_A = (int64_t)kkc * hw; g.batch_W = (int64_t)hw * blk.co; g.batch_C = (int64_t)kkc * blk.co;
+      PFG_LAUNCH("conv_gemm_filter", launch_gemm(g, stream));
+    }
+    bool lower = false;
+    for (int j = 0; j < i; ++j) lower = lower || (dWc_out && dWc_out[j]) || (dbc_out && dbc_out[j]);
+    if (!lower) break;
+    // cotangent of the patches, dP = dz Wc^T (into the patch buffer, no longer needed), gathered
+    // back to the image that entered this block = the pooled output of the block below
+    GemmArgs g{};
+    g.A = dz; g.lda = blk.co; g.a_batch_stride = blk.co; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->Wc[i]; g.ldw = blk.co; g.w_kn = 0;
+    g.M = (int32_t)rows; g.N = kkc; g.K = blk.co;
+    g.epilogue = EPI_NONE; g.C = at(ws, blk.P); g.ldc = kkc;
+    PFG_LAUNCH("conv_gemm_cotangent", launch_gemm(g, stream));
+    which_dout ^= 1;
+    dout = at(ws, cp.dout[which_dout]);
+    PFG_LAUNCH("col2im", launch_col2im(at(ws, blk.P), B, blk.h, blk.w, blk.ci, blk.k, dout, stream));
+  }
+  return PFG_OK;
+}
+
 int pfg_jacobian_input(const pfg_mlp *net, const void *X, int64_t B, const float *seeds, int64_t S,
                        int64_t seed_batch_stride, float *J_out, void *workspace,
                        size_t workspace_bytes, void *hip_stream) {

@@ -220,3 +220,62 @@ def make_varlen_inputs(w: LstmWorkload, B: Optional[int] = None, dx=None, H=None
     base.X = X
     base.labels = np.zeros(B, dtype=np.int32)
     return base, lengths
+
+
+# --------------------------------------------------------------------------------------------
+# Convolutional workload: the MNIST model of the paper's benchmarks (two conv-relu-maxpool blocks,
+# then linear-relu-linear), on seeded MNIST-shaped inputs.
+# --------------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class ConvWorkload:
+    name: str
+    index: int
+    height: int
+    width: int
+    channels: int
+    blocks: Tuple[Tuple[int, int], ...]     # (kernel size, filters) per conv block
+    dense: Tuple[int, ...]                  # widths after the flattened features
+    B: int
+
+
+CONV_WORKLOADS: Dict[str, ConvWorkload] = {
+    w.name: w for w in [
+        ConvWorkload("c10_mnist_convnet_grads", 9, 28, 28, 1, ((5, 32), (5, 64)), (1024, 10), 128),
+    ]
+}
+
+
+@dataclass
+class ConvInputs:
+    workload: ConvWorkload
+    Wc: List[np.ndarray]
+    bc: List[np.ndarray]
+    Ws: List[np.ndarray]
+    bs: List[np.ndarray]
+    X: np.ndarray            # [B, height, width, channels]
+    labels: np.ndarray
+
+
+def make_conv_inputs(w: ConvWorkload, B: Optional[int] = None, height=None, width=None, channels=None,
+                     blocks=None, dense=None, bias_scale: float = 0.0,
+                     seed: Optional[int] = None) -> ConvInputs:
+    """Weights N(0, 1 / fan_in), images uniform in [0, 1), labels uniform; draw order conv filters
+    and biases block by block, dense weights and biases layer by layer, X, labels."""
+    B = w.B if B is None else B
+    h = w.height if height is None else height
+    wd = w.width if width is None else width
+    c = w.channels if channels is None else channels
+    blocks = w.blocks if blocks is None else blocks
+    dense = w.dense if dense is None else dense
+    rng = np.random.Generator(np.random.Philox(BASE_SEED + w.index if seed is None else seed))
+    Wc, bc = [], []
+    hh, ww, cc = h, wd, c
+    for k, f in blocks:
+        Wc.append((rng.standard_normal((k, k, cc, f)) / np.sqrt(k * k * cc)).astype(np.float32))
+        bc.append((rng.standard_normal(f) * bias_scale).astype(np.float32))
+        hh, ww, cc = hh // 2, ww // 2, f
+    dims = (hh * ww * cc,) + tuple(dense)
+    Ws, bs = draw_weights(rng, dims, "normal_fan_in", bias_scale)
+    X = rng.uniform(0.0, 1.0, size=(B, h, wd, c)).astype(np.float32)
+    labels = rng.integers(0, dims[-1], size=(B,)).astype(np.int32)
+    return ConvInputs(w, Wc, bc, Ws, bs, X, labels)

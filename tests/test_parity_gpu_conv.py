@@ -1,0 +1,178 @@
+"""GPU parity for the convolutional network: per-example gradients from the HIP library, called
+through its C ABI, against the float64 CPU oracle (oracle/conv_oracle.c) on the same seeded inputs.
+Error measure as in test_parity_gpu.py: per example and per tensor max|gpu - ref| / max|ref|, at
+most 1e-4; slices that are exactly zero in the reference must be exactly zero on the GPU.
+
+Decisions taken on floating-point values (the sign of a pre-activation under ReLU, which entry of
+a pooling window is largest) are taken in float32 on the GPU and in float64 by the oracle.  With
+tens of thousands of units per image some example always has a unit within float32 round-off of
+such a boundary, where the two sides may legitimately decide differently.  The test therefore
+computes, with a float64 library convolution (not the oracle), each example's distance to the
+nearest decision boundary and compares element by element the examples whose distance is at least
+2e-6 (round-off of these pre-activations is ~1e-7); it requires that most examples qualify and
+that every output of the others is finite.
+"""
+import numpy as np
+import pytest
+
+from parity_util import TOL_F32, slice_rel_err
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import torch.nn.functional as F  # noqa: E402
+
+import paper_1903_04243_amd as pfg  # noqa: E402
+from paper_1903_04243_amd import workloads as wl  # noqa: E402
+
+from gpu_helpers import dev, say  # noqa: E402
+from oracle import conv as oconv  # noqa: E402
+
+MARGIN = 2e-6
+
+
+@pytest.fixture(scope="module", autouse=True)
+def gpu_ready():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    pfg.load_library()
+    yield
+
+
+def decision_margins(inp):
+    """Per example: the smallest distance of any ReLU input from zero and of any pooling window's
+    largest entry from its runner-up (float64, library convolution)."""
+    a = torch.from_numpy(inp.X.astype(np.float64)).permute(0, 3, 1, 2)
+    B = a.shape[0]
+    m = torch.full((B,), float("inf"), dtype=torch.float64)
+    for W, b in zip(inp.Wc, inp.bc):
+        k = W.shape[0]
+        z = F.conv2d(a, torch.from_numpy(W.astype(np.float64)).permute(3, 2, 0, 1),
+                     torch.from_numpy(b.astype(np.float64)), padding=(k - 1) // 2)
+        m = torch.minimum(m, z.abs().flatten(1).min(dim=1).values)
+        r = torch.relu(z)
+        win = F.unfold(r, 2, stride=2).reshape(B, r.shape[1], 4, -1)          # [B, C, 4, cells]
+        top = win.topk(2, dim=2).values
+        gap = torch.where(top[:, :, 0] > 0, top[:, :, 0] - top[:, :, 1], torch.full_like(top[:, :, 0], float("inf")))
+        m = torch.minimum(m, gap.flatten(1).min(dim=1).values)
+        a = F.max_pool2d(r, 2)
+    h = a.permute(0, 2, 3, 1).reshape(B, -1)
+    for l, (W, b) in enumerate(zip(inp.Ws, inp.bs)):
+        h = h @ torch.from_numpy(W.astype(np.float64)) + torch.from_numpy(b.astype(np.float64))
+        if l < len(inp.Ws) - 1:
+            m = torch.minimum(m, h.abs().min(dim=1).values)
+            h = torch.relu(h)
+    return m.numpy()
+
+
+def nan_like(*shape):
+    return torch.full(shape, float("nan"), dtype=torch.float32, device="cuda:0")
+
+
+def check_conv(inp, tag, examples=None, min_checked=0.5):
+    B, h, w, c = inp.X.shape
+    onet = oconv.ConvNet(h, w, c, inp.Wc, inp.bc, inp.Ws, inp.bs)
+    net = pfg.ConvNet.from_numpy(h, w, c, inp.Wc, inp.bc, inp.Ws, inp.bs)
+    dn = net.dense
+    out = ([nan_like(B, *W.shape) for W in inp.Wc], [nan_like(B, W.shape[3]) for W in inp.Wc],
+           [nan_like(B, dn.dims[l], dn.dims[l + 1]) for l in range(dn.L)],
+           [nan_like(B, dn.dims[l + 1]) for l in range(dn.L)], nan_like(B))
+    dWc, dbc, dW, db, loss = pfg.pfg_convnet_per_example_grads(net, dev(inp.X), dev(inp.labels), out=out)
+    torch.cuda.synchronize()
+    got = [t.cpu().numpy() for t in dWc + dbc + dW + db] + [loss.cpu().numpy()]
+    names = ([f"dWc{i + 1}" for i in range(net.nc)] + [f"dbc{i + 1}" for i in range(net.nc)] +
+             [f"dW{l + 1}" for l in range(dn.L)] + [f"db{l + 1}" for l in range(dn.L)] + ["loss"])
+    for n, a in zip(names, got):
+        assert np.isfinite(a).all(), f"{n} was not written in full"
+    margins = decision_margins(inp)
+    idx = [b for b in (range(B) if examples is None else examples) if margins[b] >= MARGIN]
+    total = B if examples is None else len(list(examples))
+    say(f"  {tag}: {len(idx)} of {total} examples are at least {MARGIN:g} from every decision boundary")
+    assert len(idx) >= min_checked * total
+    rdWc, rdbc, rdW, rdb, rloss = oconv.per_example_grads(onet, inp.X[idx], inp.labels[idx])
+    ref = rdWc + rdbc + rdW + rdb + [rloss]
+    worst = 0.0
+    for n, a, r in zip(names, got, ref):
+        e = slice_rel_err(a[idx], r, lead=0 if n == "loss" else 1)
+        say(f"  {tag} {n} rel err {e:.3e}")
+        worst = max(worst, e)
+    assert worst <= TOL_F32, f"{tag}: max relative error {worst:.3e}"
+    return net, (dWc, dbc, dW, db, loss)
+
+
+CONV_SHAPES = [
+    # height, width, channels, blocks, dense, B
+    (4, 4, 1, ((3, 2),), (3,), 2),
+    (8, 8, 2, ((3, 3), (3, 5)), (6, 4), 3),
+    (2, 2, 1, ((1, 1),), (2,), 1),                       # the smallest: a 1 x 1 filter, one window
+    (12, 8, 3, ((5, 4), (3, 6)), (9, 40), 5),            # non-square, more than 32 classes
+    (16, 16, 1, ((5, 8), (5, 16), (3, 8)), (10,), 4),    # three blocks
+    (20, 12, 2, ((7, 5),), (33, 7), 70),                 # a 7 x 7 filter; enough rows for the tiled kernels
+]
+
+
+@pytest.mark.parametrize("h,w,c,blocks,dense,B", CONV_SHAPES,
+                         ids=[f"{s[0]}x{s[1]}x{s[2]}-{len(s[3])}blocks-B{s[5]}" for s in CONV_SHAPES])
+def test_convnet_odd_shapes(h, w, c, blocks, dense, B):
+    say(f"convnet {h}x{w}x{c} blocks={blocks} dense={dense} B={B}")
+    wk = wl.ConvWorkload("oddc", 500 + h + w + B, h, w, c, blocks, dense, B)
+    inp = wl.make_conv_inputs(wk, bias_scale=0.2)
+    check_conv(inp, "conv-odd")
+
+
+def test_convnet_skipped_outputs_and_batch_order():
+    wk = wl.ConvWorkload("skipc", 540, 8, 8, 2, ((3, 4), (3, 6)), (8, 5), 6)
+    inp = wl.make_conv_inputs(wk, bias_scale=0.2)
+    net, full = check_conv(inp, "conv-skip")
+    X, labels = dev(inp.X), dev(inp.labels)
+    # only the dense gradients: the reverse pass through the conv blocks is skipped
+    dWc, dbc, dW, db, loss = pfg.pfg_convnet_per_example_grads(net, X, labels, want_dWc=[False, False],
+                                                               want_dbc=False)
+    torch.cuda.synchronize()
+    assert dbc is None and dWc == [None, None]
+    assert all(torch.equal(a, b) for a, b in zip(dW + db + [loss], full[2] + full[3] + [full[4]]))
+    # only the top conv block's filter gradient: the sweep stops above the first block
+    dWc, dbc, dW, db, loss = pfg.pfg_convnet_per_example_grads(net, X, labels, want_dWc=[False, True],
+                                                               want_dbc=False, want_dW=[False, False],
+                                                               want_db=False, want_loss=False)
+    torch.cuda.synchronize()
+    assert dWc[0] is None and torch.equal(dWc[1], full[0][1])
+    # iteration independence: a permuted batch gives the permuted results, bit for bit
+    perm = np.random.default_rng(54).permutation(6)
+    outp = pfg.pfg_convnet_per_example_grads(net, dev(inp.X[perm]), dev(inp.labels[perm]))
+    torch.cuda.synchronize()
+    tperm = torch.from_numpy(perm).to("cuda:0")
+    assert torch.equal(outp[0][0], full[0][0][tperm]) and torch.equal(outp[0][1], full[0][1][tperm])
+    assert torch.equal(outp[2][0], full[2][0][tperm]) and torch.equal(outp[4], full[4][tperm])
+
+
+def test_c10_mnist_convnet_full_size():
+    wk = wl.CONV_WORKLOADS["c10_mnist_convnet_grads"]
+    say("c10_mnist_convnet_grads: full size (128 images, 28 x 28), sampled examples element by element")
+    inp = wl.make_conv_inputs(wk)
+    picks = sorted(set([0, wk.B - 1] + np.random.default_rng(10).integers(0, wk.B, size=24).tolist()))
+    net, out = check_conv(inp, "c10", examples=picks)
+    # a property that holds for every example: the first dense layer's gradient is the outer
+    # product of the conv features and that layer's bias gradient, so its rows are multiples of db1
+    dW1, db1 = out[2][0], out[3][0]
+    j = db1.abs().argmax(dim=1)
+    rows = torch.arange(wk.B, device="cuda:0")
+    feat = dW1[rows, :, j] / db1[rows, j].unsqueeze(1)
+    recon = feat.unsqueeze(2) * db1.unsqueeze(1)
+    dev_rel = ((recon - dW1).abs().amax(dim=(1, 2)) / dW1.abs().amax(dim=(1, 2)).clamp_min(1e-30)).max().item()
+    say(f"  c10 dW1 rank-one consistency {dev_rel:.3e}")
+    assert dev_rel < 1e-4
+
+
+def test_convnet_rejects_bad_arguments():
+    wk = wl.ConvWorkload("badc", 541, 6, 6, 1, ((3, 2),), (4,), 2)      # 6 -> 3: fine for one block
+    inp = wl.make_conv_inputs(wk)
+    net = pfg.ConvNet.from_numpy(6, 6, 1, inp.Wc, inp.bc, inp.Ws, inp.bs)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(pfg.PfgError) as ei:
+        pfg.pfg_convnet_per_example_grads(net, dev(inp.X), dev(inp.labels), workspace=small)
+    assert ei.value.code == pfg.PFG_ERR_WORKSPACE
+    # a dense input width that does not match the conv output
+    bad = pfg.ConvNet.from_numpy(6, 6, 1, inp.Wc, inp.bc, [np.zeros((7, 4), np.float32)], None)
+    with pytest.raises(pfg.PfgError) as ei:
+        pfg.pfg_convnet_workspace_bytes(bad, 2)
+    assert ei.value.code == pfg.PFG_ERR_SHAPE
