@@ -318,7 +318,70 @@ def main():
             f"roofline frac {roof['frac']:.3f}")
         return rec, inp
 
+    def measure_conv(name, steps, warmup):
+        w = wl.CONV_WORKLOADS[name]
+        log(f"[bench] {name}: uploading inputs")
+        inp = wl.make_conv_inputs(w)
+        net = pfg.ConvNet.from_numpy(w.height, w.width, w.channels, inp.Wc, inp.bc, inp.Ws, inp.bs)
+        X = torch.from_numpy(inp.X).to(dev)
+        labels = torch.from_numpy(inp.labels).to(dev)
+        f32 = dict(dtype=torch.float32, device=dev)
+        B, dn = w.B, net.dense
+        out = ([torch.empty((B,) + W.shape, **f32) for W in inp.Wc],
+               [torch.empty((B, W.shape[3]), **f32) for W in inp.Wc],
+               [torch.empty((B, dn.dims[l], dn.dims[l + 1]), **f32) for l in range(dn.L)],
+               [torch.empty((B, dn.dims[l + 1]), **f32) for l in range(dn.L)], torch.empty((B,), **f32))
+        ws = torch.empty(pfg.pfg_convnet_workspace_bytes(net, B), dtype=torch.uint8, device=dev)
+        step = lambda: pfg.pfg_convnet_per_example_grads(net, X, labels, out=out, workspace=ws)
+        step()
+        torch.cuda.synchronize()
+        log(f"[bench] {name}: timing {steps} steps")
+        sec = timed(step, steps, warmup)
+        sec_graph = None
+        if not args.no_graph:
+            try:
+                sec_graph = timed_graph(step, steps, warmup)
+            except Exception as e:
+                log(f"[bench] {name}: graph replay not measured ({e})")
+        kt = kernel_times(step, steps)
+        values = sum(t.numel() for group in out[:4] for t in group) + B
+        # the dense weight gradients are the large output (4 bytes per value, written once)
+        fam = "outer_product"
+        nbytes = 4 * B * sum(dn.dims[l] * dn.dims[l + 1] for l in range(dn.L))
+        per_ms = kt[fam]["ms_per_step"] / kt[fam]["launches_per_step"]
+        gbs = nbytes / kt[fam]["ms_per_step"] / 1e6
+        roof = {"kernel": fam, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                "bytes_per_launch": nbytes / kt[fam]["launches_per_step"], "ms_per_launch": per_ms,
+                "launches_per_step": kt[fam]["launches_per_step"]}
+        # the conv products, against the fp32 MFMA peak
+        hh, ww, cc = w.height, w.width, w.channels
+        conv_flops = {"conv_gemm_forward": 0, "conv_gemm_filter": 0, "conv_gemm_cotangent": 0}
+        for i, (k, f) in enumerate(w.blocks):
+            per = 2 * B * hh * ww * k * k * cc * f
+            conv_flops["conv_gemm_forward"] += per
+            conv_flops["conv_gemm_filter"] += per
+            if i > 0:
+                conv_flops["conv_gemm_cotangent"] += per
+            hh, ww, cc = hh // 2, ww // 2, f
+        conv_report = {fam2: {"flops_per_step": fl, "TFLOP/s": fl / kt[fam2]["ms_per_step"] / 1e9,
+                              "mfma_frac": fl / kt[fam2]["ms_per_step"] / 1e9 / MFMA_PEAK_TFLOPS["f32"]}
+                       for fam2, fl in conv_flops.items() if fam2 in kt and fl}
+        rec = {"workload": name, "call": "convnet_per_example_grads", "image": [w.height, w.width, w.channels],
+               "blocks": [list(b) for b in w.blocks], "dense": list(w.dense), "dtype": "f32", "B": B,
+               "steps": steps, "ms_per_step": sec * 1e3,
+               "ms_per_step_graph_replay": None if sec_graph is None else sec_graph * 1e3,
+               "output_values": values, "output_GB": values * 4 / 1e9,
+               "per_example_grads_per_sec": B / sec, "kernels": kt,
+               "kernel_ms_sum": sum(v["ms_per_step"] for v in kt.values()),
+               "launches_per_step": sum(v["launches_per_step"] for v in kt.values()),
+               "conv_products": conv_report, "roofline": roof}
+        log(f"[bench] {name}: {rec['ms_per_step']:.4f} ms/step, roofline frac {roof['frac']:.3f}")
+        return rec, inp
+
     def measure_lstm(name, steps, warmup):
+        if name in wl.CONV_WORKLOADS:
+            return measure_conv(name, steps, warmup)
         w = wl.LSTM_WORKLOADS[name]
         if w.call == "lstm_varlen_forward":
             return measure_varlen(name, steps, warmup)
@@ -405,7 +468,7 @@ def main():
         return
 
     if args.workload:
-        fn = measure_lstm if args.workload in wl.LSTM_WORKLOADS else measure
+        fn = measure_lstm if (args.workload in wl.LSTM_WORKLOADS or args.workload in wl.CONV_WORKLOADS) else measure
         rec, _ = fn(args.workload, args.steps, args.warmup)
         print(json.dumps(rec), flush=True)
         return
@@ -441,9 +504,10 @@ def main():
                             ("c6_tanh_hessian", max(3, args.steps // 20)),
                             ("c7_lstm_grads", max(3, args.steps // 2)),
                             ("c8_lstm_jacobian", max(3, args.steps // 10)),
-                            ("c9_lstm_varlen", max(3, args.steps // 10))):
+                            ("c9_lstm_varlen", max(3, args.steps // 10)),
+                            ("c10_mnist_convnet_grads", max(3, args.steps // 10))):
             try:
-                fn = measure_lstm if name in wl.LSTM_WORKLOADS else measure
+                fn = measure_lstm if (name in wl.LSTM_WORKLOADS or name in wl.CONV_WORKLOADS) else measure
                 others[name], _ = fn(name, steps, max(1, min(args.warmup, steps // 2)))
             except Exception as e:
                 others[name] = {"error": str(e)}

@@ -18,35 +18,39 @@ inline unsigned capped_blocks(int64_t work_items) {
 }
 
 // P[(b, y, x), (ky, kx, c)] = in[b, y + ky - p, x + kx - p, c] (zero outside the image).
-// ROWS_ARE_POSITIONS: P is [B h w, k k c] (consecutive threads walk a patch); otherwise the
-// transposed per-example layout [B, k k c, h w] (consecutive threads walk the positions).
+// ROWS_ARE_POSITIONS: P is [B h w, k k c] (a workgroup row walks a patch); otherwise the transposed
+// per-example layout [B, k k c, h w] (a workgroup row walks the positions).  The second grid index
+// is the example, the first a chunk of kRows rows of that example's matrix; the threads of one row
+// slot take consecutive entries, so the divisions that locate a row are done once per slot and the
+// rest is 32-bit arithmetic.
+constexpr int kRows = 4;      // row slots per workgroup (64 threads each)
+
 template <bool ROWS_ARE_POSITIONS>
-__global__ __launch_bounds__(kThreads) void im2col_kernel(const float *in, int64_t B, int h, int w, int c,
-                                                          int k, float *out) {
+__global__ __launch_bounds__(kThreads) void im2col_kernel(const float *in, int h, int w, int c, int k,
+                                                          float *out) {
   const int p = (k - 1) / 2, hw = h * w, kkc = k * k * c;
-  const int64_t total = B * hw * kkc;
-  const int64_t step = (int64_t)gridDim.x * kThreads;
-  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += step) {
-    int64_t b;
-    int pos, e;
-    if (ROWS_ARE_POSITIONS) {
-      const int64_t row = i / kkc;
-      e = (int)(i - row * kkc);
-      b = row / hw;
-      pos = (int)(row - b * hw);
-    } else {
-      const int64_t row = i / hw;
-      pos = (int)(i - row * hw);
-      b = row / kkc;
-      e = (int)(row - b * kkc);
+  const int nrows = ROWS_ARE_POSITIONS ? hw : kkc, ncols = ROWS_ARE_POSITIONS ? kkc : hw;
+  const int64_t b = blockIdx.y;
+  const int row = blockIdx.x * kRows + (threadIdx.x >> 6);
+  if (row >= nrows) return;
+  const float *img = in + b * (int64_t)hw * c;
+  float *orow = out + (b * nrows + row) * (int64_t)ncols;
+  if (ROWS_ARE_POSITIONS) {
+    const int y = row / w, x = row - y * w;
+    for (int e = threadIdx.x & 63; e < ncols; e += 64) {
+      const int kyx = e / c, ch = e - kyx * c;
+      const int ky = kyx / k, kx = kyx - ky * k;
+      const int yy = y + ky - p, xx = x + kx - p;
+      orow[e] = (yy >= 0 && yy < h && xx >= 0 && xx < w) ? img[(yy * w + xx) * c + ch] : 0.f;
     }
-    const int y = pos / w, x = pos - y * w;
-    const int kyx = e / c, ch = e - kyx * c;
+  } else {
+    const int kyx = row / c, ch = row - kyx * c;
     const int ky = kyx / k, kx = kyx - ky * k;
-    const int yy = y + ky - p, xx = x + kx - p;
-    float v = 0.f;
-    if (yy >= 0 && yy < h && xx >= 0 && xx < w) v = in[((b * h + yy) * w + xx) * c + ch];
-    out[i] = v;
+    for (int pos = threadIdx.x & 63; pos < ncols; pos += 64) {
+      const int y = pos / w, x = pos - y * w;
+      const int yy = y + ky - p, xx = x + kx - p;
+      orow[pos] = (yy >= 0 && yy < h && xx >= 0 && xx < w) ? img[(yy * w + xx) * c + ch] : 0.f;
+    }
   }
 }
 
@@ -133,12 +137,15 @@ __global__ __launch_bounds__(kThreads) void col2im_kernel(const float *dP, int64
 
 hipError_t launch_im2col(const float *in, int64_t B, int32_t h, int32_t w, int32_t c, int32_t k,
                          float *P, float *PT, hipStream_t stream) {
-  const int64_t total = B * h * w * k * k * c;
-  if (total <= 0) return hipSuccess;
-  if (P) PFG_KERNEL(im2col_kernel<true>, dim3(capped_blocks(total)), dim3(kThreads), 0, stream, in, B, h,
-                    w, c, k, P);
-  if (PT) PFG_KERNEL(im2col_kernel<false>, dim3(capped_blocks(total)), dim3(kThreads), 0, stream, in, B,
-                     h, w, c, k, PT);
+  const int64_t hw = (int64_t)h * w, kkc = (int64_t)k * k * c;
+  if (B <= 0 || hw <= 0 || kkc <= 0) return hipSuccess;
+  if (B > 65535) return hipErrorInvalidValue;
+  if (P)
+    PFG_KERNEL(im2col_kernel<true>, dim3((unsigned)((hw + kRows - 1) / kRows), (unsigned)B), dim3(kThreads),
+               0, stream, in, h, w, c, k, P);
+  if (PT)
+    PFG_KERNEL(im2col_kernel<false>, dim3((unsigned)((kkc + kRows - 1) / kRows), (unsigned)B),
+               dim3(kThreads), 0, stream, in, h, w, c, k, PT);
   return hipGetLastError();
 }
 

@@ -150,16 +150,26 @@ __global__ __launch_bounds__(kThreads) void outer_sum_kernel(const OuterSumArgs 
   }
 }
 
-// out[b, j] = sum_t g[b, t, j]
-__global__ __launch_bounds__(kThreads) void sum_steps_kernel(const float *g, int64_t B, int T, int d,
+// out[b, j] = sum_t g[b, t, j].  One workgroup per (b, group of up to 64 columns); its threads form
+// 256 / columns row slots that each add every (256 / columns)-th row, then the slots are added in a
+// fixed order.  Rows are read 128 or 256 bytes at a time by adjacent lanes.
+__global__ __launch_bounds__(kThreads) void sum_steps_kernel(const float *g, int T, int d, int cols,
                                                              float *out) {
-  const int64_t id = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (id >= B * d) return;
-  const int64_t b = id / d;
-  const int j = (int)(id - b * d);
+  __shared__ float part[kThreads];
+  const int64_t b = blockIdx.y;
+  const int j0 = blockIdx.x * cols;
+  const int slots = kThreads / cols;
+  const int slot = threadIdx.x / cols, j = j0 + threadIdx.x % cols;
   float s = 0.f;
-  for (int t = 0; t < T; ++t) s += g[(b * T + t) * (int64_t)d + j];
-  out[id] = s;
+  if (j < d && slot < slots)
+    for (int t = slot; t < T; t += slots) s += g[(b * T + t) * (int64_t)d + j];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  if (threadIdx.x < cols && j < d) {
+    float total = 0.f;
+    for (int r = 0; r < slots; ++r) total += part[r * cols + threadIdx.x];
+    out[b * d + j] = total;
+  }
 }
 
 inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads); }
@@ -229,9 +239,18 @@ hipError_t launch_outer_sum(const OuterSumJob *jobs, int njobs, int64_t B, int32
 
 hipError_t launch_sum_steps(const float *g, int64_t B, int32_t T, int32_t d, float *out,
                             hipStream_t stream) {
-  if (B <= 0) return hipSuccess;
-  PFG_KERNEL(sum_steps_kernel, dim3(blocks_for(B * d)), dim3(kThreads), 0, stream, g, B, T, d, out);
-  return hipGetLastError();
+  if (B <= 0 || d <= 0) return hipSuccess;
+  int cols = 64;                       // 64, 32 or 16 columns per workgroup, not more than needed
+  while (cols > 16 && cols / 2 >= d) cols /= 2;
+  const unsigned groups = (unsigned)((d + cols - 1) / cols);
+  for (int64_t b0 = 0; b0 < B; b0 += 32768) {
+    const int64_t nb = B - b0 < 32768 ? B - b0 : 32768;
+    PFG_KERNEL(sum_steps_kernel, dim3(groups, (unsigned)nb), dim3(kThreads), 0, stream,
+               g + b0 * T * (int64_t)d, T, d, cols, out + b0 * d);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace pfg
