@@ -277,6 +277,48 @@ def test_lstm_varlen_workspace_and_rejections(lib):
     assert fn(r, FAKE, lens, 3, 7, FAKE, FAKE, FAKE, 64, None) == pfg.PFG_ERR_WORKSPACE
 
 
+def make_convnet(h=28, w=28, c=1, kernel=(5, 5), filters=(32, 64), dense=(3136, 1024, 10), Wc_null=None,
+                 dtype=0):
+    nc = len(kernel)
+    k = (ctypes.c_int32 * nc)(*kernel)
+    f = (ctypes.c_int32 * nc)(*filters)
+    Wc = (ctypes.c_void_p * nc)(*[None if Wc_null == i else FAKE for i in range(nc)])
+    dn = make_net(list(dense), act=1, dtype=dtype)
+    net = pfg.pfg_convnet(h, w, c, nc, k, f, Wc, None, dn)
+    net._keep = (k, f, Wc, dn)
+    return net
+
+
+def test_convnet_workspace_and_rejections(lib):
+    net = make_convnet()
+    B = 128
+    n = ctypes.c_size_t(0)
+    assert lib.pfg_convnet_workspace_bytes(ctypes.byref(net), B, ctypes.byref(n)) == 0
+    dense = ws_bytes(lib, net.dense, 0, B, 1)[1]
+    blk1 = (2 * up(4 * B * 784 * 25) + 2 * up(4 * B * 784 * 32) + up(4 * B * 196 * 32) + up(B * 196 * 32))
+    blk2 = (2 * up(4 * B * 196 * 800) + 2 * up(4 * B * 196 * 64) + up(4 * B * 49 * 64) + up(B * 49 * 64))
+    assert n.value == blk1 + blk2 + 2 * up(4 * B * 196 * 32) + dense
+    r = lambda net_: ctypes.byref(net_)
+    assert lib.pfg_convnet_workspace_bytes(None, B, ctypes.byref(n)) == pfg.PFG_ERR_NULL
+    assert lib.pfg_convnet_workspace_bytes(r(net), B, None) == pfg.PFG_ERR_NULL
+    assert lib.pfg_convnet_workspace_bytes(r(net), 0, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
+    assert lib.pfg_convnet_workspace_bytes(r(make_convnet(kernel=(4, 5))), B, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
+    assert "odd" in lib.pfg_last_error().decode()
+    assert lib.pfg_convnet_workspace_bytes(r(make_convnet(h=30)), B, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE    # 30 -> 15, odd
+    assert lib.pfg_convnet_workspace_bytes(r(make_convnet(dense=(3000, 10))), B, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
+    assert "features" in lib.pfg_last_error().decode()
+    assert lib.pfg_convnet_workspace_bytes(r(make_convnet(dtype=1)), B, ctypes.byref(n)) == pfg.PFG_ERR_UNSUPPORTED
+    fn = lib.pfg_convnet_per_example_grads
+    big = 1 << 40
+    o2 = (ctypes.c_void_p * 2)(FAKE, FAKE)
+    assert fn(r(net), None, FAKE, 4, o2, o2, o2, o2, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r(net), FAKE, None, 4, o2, o2, o2, o2, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r(make_convnet(Wc_null=1)), FAKE, FAKE, 4, o2, o2, o2, o2, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r(net), FAKE, FAKE, 4, o2, o2, o2, o2, None, None, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(r(net), FAKE, FAKE, 4, o2, o2, o2, o2, None, FAKE, 1024, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(r(net), FAKE, FAKE, 1 << 20, o2, o2, o2, o2, None, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+
+
 def test_last_error_is_cleared_by_a_good_call(lib):
     net = make_net([4, 3, 2])
     assert ws_bytes(lib, net, 9, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
