@@ -206,9 +206,11 @@ struct OuterSumJob {
 hipError_t launch_outer_sum(const OuterSumJob *jobs, int njobs, int64_t B, int32_t d_out,
                             int64_t out_bs, hipStream_t stream);
 
-// out[b, j] = sum_{t < T} g[b, t, j]
+// out[b, j] = sum_{t < T} g[b, t, j].  scratch (optional): min(B, 32768) * kSumPieces * d floats, used
+// to sum long columns in pieces when there are few of them.
+constexpr int kSumPieces = 8;
 hipError_t launch_sum_steps(const float *g, int64_t B, int32_t T, int32_t d, float *out,
-                            hipStream_t stream);
+                            float *scratch, hipStream_t stream);
 
 // Patches of a "same"-size k x k convolution over in [B, h, w, c]: P [B h w, k k c] (one row per
 // output position) and / or PT [B, k k c, h w] (the same values per example with the position index

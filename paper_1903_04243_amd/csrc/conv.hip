@@ -35,7 +35,34 @@ __global__ __launch_bounds__(kThreads) void im2col_kernel(const float *in, int h
   if (row >= nrows) return;
   const float *img = in + b * (int64_t)hw * c;
   float *orow = out + (b * nrows + row) * (int64_t)ncols;
-  if (ROWS_ARE_POSITIONS) {
+  const bool aligned = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+  if (ROWS_ARE_POSITIONS && c % 4 == 0 && aligned) {
+    // four channels at a time: a 16-byte piece never straddles two filter taps
+    const int y = row / w, x = row - y * w;
+    for (int e = (threadIdx.x & 63) * 4; e < ncols; e += 256) {
+      const int kyx = e / c, ch = e - kyx * c;
+      const int ky = kyx / k, kx = kyx - ky * k;
+      const int yy = y + ky - p, xx = x + kx - p;
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (yy >= 0 && yy < h && xx >= 0 && xx < w)
+        v = *reinterpret_cast<const f32x4 *>(img + (yy * w + xx) * c + ch);
+      *reinterpret_cast<f32x4 *>(orow + e) = v;
+    }
+  } else if (!ROWS_ARE_POSITIONS && hw % 4 == 0 && aligned) {
+    // four positions at a time: strided reads, one 16-byte store
+    const int kyx = row / c, ch = row - kyx * c;
+    const int ky = kyx / k, kx = kyx - ky * k;
+    for (int pos = (threadIdx.x & 63) * 4; pos < ncols; pos += 256) {
+      f32x4 v;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int y = (pos + q) / w, x = (pos + q) - y * w;
+        const int yy = y + ky - p, xx = x + kx - p;
+        v[q] = (yy >= 0 && yy < h && xx >= 0 && xx < w) ? img[(yy * w + xx) * c + ch] : 0.f;
+      }
+      *reinterpret_cast<f32x4 *>(orow + pos) = v;
+    }
+  } else if (ROWS_ARE_POSITIONS) {
     const int y = row / w, x = row - y * w;
     for (int e = threadIdx.x & 63; e < ncols; e += 64) {
       const int kyx = e / c, ch = e - kyx * c;

@@ -153,22 +153,27 @@ __global__ __launch_bounds__(kThreads) void outer_sum_kernel(const OuterSumArgs 
 // out[b, j] = sum_t g[b, t, j].  One workgroup per (b, group of up to 64 columns); its threads form
 // 256 / columns row slots that each add every (256 / columns)-th row, then the slots are added in a
 // fixed order.  Rows are read 128 or 256 bytes at a time by adjacent lanes.
+// With pieces > 1 the third grid index selects a piece of the T rows and the result is a partial
+// sum, written as row (b, piece) of out [B, pieces, d] (a second pass of the same kernel adds them).
 __global__ __launch_bounds__(kThreads) void sum_steps_kernel(const float *g, int T, int d, int cols,
-                                                             float *out) {
+                                                             int pieces, float *out) {
   __shared__ float part[kThreads];
   const int64_t b = blockIdx.y;
+  const int piece = blockIdx.z;
+  const int per = (T + pieces - 1) / pieces;
+  const int t0 = piece * per, t1 = min(T, t0 + per);
   const int j0 = blockIdx.x * cols;
   const int slots = kThreads / cols;
   const int slot = threadIdx.x / cols, j = j0 + threadIdx.x % cols;
   float s = 0.f;
-  if (j < d && slot < slots)
-    for (int t = slot; t < T; t += slots) s += g[(b * T + t) * (int64_t)d + j];
+  if (j < d)
+    for (int t = t0 + slot; t < t1; t += slots) s += g[(b * T + t) * (int64_t)d + j];
   part[threadIdx.x] = s;
   __syncthreads();
   if (threadIdx.x < cols && j < d) {
     float total = 0.f;
     for (int r = 0; r < slots; ++r) total += part[r * cols + threadIdx.x];
-    out[b * d + j] = total;
+    out[(b * pieces + piece) * (int64_t)d + j] = total;
   }
 }
 
@@ -238,15 +243,21 @@ hipError_t launch_outer_sum(const OuterSumJob *jobs, int njobs, int64_t B, int32
 }
 
 hipError_t launch_sum_steps(const float *g, int64_t B, int32_t T, int32_t d, float *out,
-                            hipStream_t stream) {
+                            float *scratch, hipStream_t stream) {
   if (B <= 0 || d <= 0) return hipSuccess;
   int cols = 64;                       // 64, 32 or 16 columns per workgroup, not more than needed
   while (cols > 16 && cols / 2 >= d) cols /= 2;
   const unsigned groups = (unsigned)((d + cols - 1) / cols);
+  // many rows and few workgroups: sum kSumPieces pieces of the rows separately first
+  const int pieces = (scratch && T >= 256 && B * groups < 2048) ? kSumPieces : 1;
   for (int64_t b0 = 0; b0 < B; b0 += 32768) {
     const int64_t nb = B - b0 < 32768 ? B - b0 : 32768;
-    PFG_KERNEL(sum_steps_kernel, dim3(groups, (unsigned)nb), dim3(kThreads), 0, stream,
-               g + b0 * T * (int64_t)d, T, d, cols, out + b0 * d);
+    float *first_out = pieces > 1 ? scratch : out + b0 * d;
+    PFG_KERNEL(sum_steps_kernel, dim3(groups, (unsigned)nb, (unsigned)pieces), dim3(kThreads), 0, stream,
+               g + b0 * T * (int64_t)d, T, d, cols, pieces, first_out);
+    if (pieces > 1)
+      PFG_KERNEL(sum_steps_kernel, dim3(groups, (unsigned)nb, 1u), dim3(kThreads), 0, stream, scratch,
+                 pieces, d, cols, 1, out + b0 * d);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

@@ -657,6 +657,7 @@ struct ConvPlan {
   size_t total = 0;
   std::vector<ConvBlock> blocks;
   size_t dout[2] = {0, 0};     // cotangents of pooled outputs, used alternately
+  size_t psum = 0;             // partial sums over positions (bias gradients)
   size_t dense = 0;            // sub-workspace of the dense layers
   size_t dense_bytes = 0;
   size_t take(size_t bytes) {
@@ -714,6 +715,9 @@ ConvPlan make_conv_plan(const pfg_convnet *net, int64_t B) {
   }
   p.dout[0] = p.take(f * widest_pooled);
   p.dout[1] = p.take(f * widest_pooled);
+  size_t widest_co = 0;
+  for (const ConvBlock &blk : p.blocks) widest_co = std::max(widest_co, (size_t)blk.co);
+  p.psum = p.take(f * B * kSumPieces * widest_co);
   p.dense_bytes = make_plan(&net->dense, PFG_OP_PER_EXAMPLE_GRADS, B, 1).total;
   p.dense = p.take(p.dense_bytes);
   return p;
@@ -834,7 +838,7 @@ int pfg_convnet_per_example_grads(const pfg_convnet *net, const void *X, const i
                                                  reinterpret_cast<const uint8_t *>(static_cast<char *>(ws) + blk.which),
                                                  B, blk.h, blk.w, blk.co, dz, stream));
     if (dbc_out && dbc_out[i])
-      PFG_LAUNCH("sum_positions", launch_sum_steps(dz, B, hw, blk.co, dbc_out[i], stream));
+      PFG_LAUNCH("sum_positions", launch_sum_steps(dz, B, hw, blk.co, dbc_out[i], at(ws, cp.psum), stream));
     if (dWc_out && dWc_out[i]) {
       // both operands stacked (Section 3.4): for each example [k k c_in, h w] x [h w, c_out]
       GemmArgs g{};

@@ -424,7 +424,7 @@ int pfg_lstm_per_example_grads(const pfg_lstm *net, const void *X, const int32_t
          dW_out + (int64_t)dx * 4 * H}};
     PFG_LAUNCH("outer_sum", launch_outer_sum(jobs, 2, B, 4 * H, out_bs, stream));
   }
-  if (db_out) PFG_LAUNCH("sum_steps", launch_sum_steps(dz, B, T, 4 * H, db_out, stream));
+  if (db_out) PFG_LAUNCH("sum_steps", launch_sum_steps(dz, B, T, 4 * H, db_out, nullptr, stream));
   return PFG_OK;
 }
 

@@ -297,7 +297,7 @@ def test_convnet_workspace_and_rejections(lib):
     dense = ws_bytes(lib, net.dense, 0, B, 1)[1]
     blk1 = (2 * up(4 * B * 784 * 25) + 2 * up(4 * B * 784 * 32) + up(4 * B * 196 * 32) + up(B * 196 * 32))
     blk2 = (2 * up(4 * B * 196 * 800) + 2 * up(4 * B * 196 * 64) + up(4 * B * 49 * 64) + up(B * 49 * 64))
-    assert n.value == blk1 + blk2 + 2 * up(4 * B * 196 * 32) + dense
+    assert n.value == blk1 + blk2 + 2 * up(4 * B * 196 * 32) + up(4 * B * 8 * 64) + dense
     r = lambda net_: ctypes.byref(net_)
     assert lib.pfg_convnet_workspace_bytes(None, B, ctypes.byref(n)) == pfg.PFG_ERR_NULL
     assert lib.pfg_convnet_workspace_bytes(r(net), B, None) == pfg.PFG_ERR_NULL
