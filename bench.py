@@ -167,7 +167,12 @@ def main():
                 elem * d[l - 1] * d[l] + (elem if l == 1 else 4) * B * d[l - 1] +
                 (8 if l < L else 4) * B * d[l] for l in range(1, L + 1))}}
         if w.call == "hessian_input":
-            return {"gemm_hessian": {"flops": 2 * B * S * d[0] * d[0] * sum(d[1:-1])}}
+            # each H[b, s] is symmetric: with 128 x 128 tiles only the T (T + 1) / 2 tiles on and above
+            # the diagonal of its T x T tiles are computed (the rest are mirrored), so these are the
+            # flops the kernel executes, not 2 B S d_0^2 K
+            full = 2 * B * S * d[0] * d[0] * sum(d[1:-1])
+            T = d[0] // 128
+            return {"gemm_hessian": {"flops": full * (T + 1) // (2 * T) if d[0] % 128 == 0 else full}}
         if w.call == "jacobian_input":
             rows = B * S
             cot = sum(2 * rows * d[l] * d[l - 1] for l in range(2, len(d) - 1))

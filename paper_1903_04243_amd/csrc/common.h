@@ -91,6 +91,11 @@ struct GemmArgs {
   // W + z * batch_W (float32 weights only) and C + z * batch_C (strides in elements).  EPI_NONE only.
   int32_t nbatch;
   int64_t batch_A, batch_scale, batch_W, batch_C;
+  // Symmetric blocks: sym_n > 0 says that N == sym_n, M is a multiple of sym_n and every
+  // sym_n x sym_n block of rows of C is a symmetric matrix.  The LDS-tiled kernel then computes only
+  // the tiles on and above each block's diagonal and writes the others as their mirror images
+  // (float32, EPI_NONE, sym_n a multiple of 128; other kernels ignore the hint and compute everything).
+  int32_t sym_n;
   // EPI_LSTM_BWD (row m belongs to example m / S, whose gates and cell states are shared by its S rows)
   int32_t n_split;
   int32_t lstm_H, lstm_T, lstm_step;

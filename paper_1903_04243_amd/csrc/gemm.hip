@@ -70,11 +70,27 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   // that a band of A rows is fetched into one L2 once and reused there for all its N tiles.
   const int tiles_m = (g.M + BM - 1) / BM;
   const int tiles_n = (g.N + BN - 1) / BN;
-  const int total = tiles_m * tiles_n;
-  int t = blockIdx.x;
-  if (total % 8 == 0) t = (t % 8) * (total / 8) + t / 8;
-  const int tile_m = t / tiles_n;
-  const int tile_n = t % tiles_n;
+  int tile_m, tile_n;
+  bool mirror = false;       // symmetric blocks: this tile also stands for its mirror image
+  if (AMODE == A_F32 && BM == BN && g.sym_n > 0) {
+    // tiles on and above the diagonal of each sym_n x sym_n block: row ti of a block has the
+    // tiles tn = ti .. T - 1
+    const int T = g.sym_n / BM, tri = T * (T + 1) / 2;
+    const int total = (g.M / g.sym_n) * tri;
+    int t = blockIdx.x;
+    if (total % 8 == 0) t = (t % 8) * (total / 8) + t / 8;
+    int p = t % tri, ti = 0;
+    while (p >= T - ti) { p -= T - ti; ++ti; }
+    tile_m = (t / tri) * T + ti;
+    tile_n = ti + p;
+    mirror = p > 0;
+  } else {
+    const int total = tiles_m * tiles_n;
+    int t = blockIdx.x;
+    if (total % 8 == 0) t = (t % 8) * (total / 8) + t / 8;
+    tile_m = t / tiles_n;
+    tile_n = t % tiles_n;
+  }
   const int m0 = tile_m * BM;
   const int n0 = tile_n * BN;
   const int M = g.M, N = g.N, K = g.K;
@@ -461,6 +477,35 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
       }
     }
   }
+  if constexpr (AMODE == A_F32 && BM == BN) {
+    if (mirror) {
+      // C[block + n, i] = C[block + i, n]: the tile goes through LDS and is written transposed,
+      // consecutive threads on consecutive columns (all tiles are full in this mode)
+      constexpr int TS = BN + 1;
+      static_assert(BM * TS * 4 <= 2 * STAGE, "the output tile must fit the staging buffers");
+      float *tile = reinterpret_cast<float *>(smem);
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            tile[(wm + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3)) * TS + wn + j * 32 + l32] =
+                acc[i][j][r];
+      __syncthreads();
+      const int block0 = (m0 / g.sym_n) * g.sym_n, i0 = m0 - block0;
+      for (int e = tid; e < BM * BN; e += kThreads) {
+        const int col = e / BM, row = e % BM;          // element (row, col) of the tile
+        const float v = tile[row * TS + col];
+        float *dst = gC + (int64_t)(block0 + n0 + col) * g.ldc + i0 + row;
+        if (g.streaming)
+          __builtin_nontemporal_store(v, dst);
+        else
+          *dst = v;
+      }
+    }
+  }
 }
 
 template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2>
@@ -478,7 +523,11 @@ hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int64_t tiles = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  int64_t tiles = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  if (AMODE == A_F32 && BM == BN && g.sym_n > 0) {
+    const int64_t T = g.sym_n / BM;
+    tiles = (g.M / g.sym_n) * (T * (T + 1) / 2);
+  }
   const unsigned nbatch = g.nbatch > 1 ? (unsigned)g.nbatch : 1u;
   PFG_KERNEL(kern, dim3((unsigned)tiles, nbatch), dim3(kThreads), smem, stream, g);
   return hipGetLastError();
@@ -509,6 +558,8 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
 
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipSuccess;
+  if (g.sym_n > 0 && (g.epilogue != EPI_NONE || g.bf16 || g.N != g.sym_n || g.M % g.sym_n || g.sym_n % 128))
+    return hipErrorInvalidValue;
   if (g.epilogue == EPI_LSTM_BWD && (g.N - g.n_split != g.lstm_H || g.n_split < 0 || g.bf16))
     return hipErrorInvalidValue;
   if (g.nbatch > 1 && (g.epilogue != EPI_NONE || g.nbatch > 65535))

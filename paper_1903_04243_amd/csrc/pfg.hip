@@ -639,6 +639,9 @@ int pfg_hessian_input(const pfg_mlp *net, const void *X, int64_t B, const float 
     g.streaming = 1;
     g.nbatch = (int32_t)nb;
     g.batch_A = n * ktot; g.batch_scale = S * ktot; g.batch_W = n * ktot; g.batch_C = S * n * n;
+    // second derivatives commute: each H[b, s] is symmetric, so the tiles below its diagonal are
+    // mirror images of those above and need not be computed
+    if (n % 128 == 0) g.sym_n = (int32_t)n;
     PFG_LAUNCH("gemm_hessian", launch_gemm(g, stream));
   }
   return PFG_OK;

@@ -205,6 +205,29 @@ def test_hessian_reduced_every_element_tiled_kernels(oracle):
     assert e <= TOL_F32
 
 
+@pytest.mark.parametrize("dims,B", [((128, 48, 40, 8), 4), ((256, 64, 48, 8), 8), ((384, 32, 4), 16)],
+                         ids=["n128-64x64-tiles", "n256-128x128-tiles", "n384-three-tiles-a-side"])
+def test_hessian_mirrored_tiles_every_element(oracle, dims, B):
+    # input widths that are multiples of 128 with enough work for the LDS-tiled kernel: only the
+    # tiles on and above the diagonal of each Hessian are computed, the others are mirror images;
+    # every element against the oracle
+    w = wl.Workload("symh", 270 + dims[0], "hessian_input", dims, "tanh", "f32", B, "normal",
+                    "normal_fan_in")
+    inp = draw(w, bias_scale=0.1)
+    ref = oracle.hessian_input(oracle.Net(inp.Ws, inp.bs, "tanh"), inp.X)
+    H = pfg.pfg_hessian_input(gpu_net(inp, "tanh", "f32"), gpu_x(inp, "f32"),
+                              out=nan_like(B, dims[-1], dims[0], dims[0]))
+    torch.cuda.synchronize()
+    e = slice_rel_err(H.cpu().numpy(), ref, lead=2)
+    say(f"  mirrored-tile Hessian {dims} B={B}: rel err {e:.3e}")
+    assert e <= TOL_F32
+    # mirrored tiles are exact copies; tiles on the diagonal are symmetric to rounding only
+    scale = H.abs().amax(dim=(2, 3), keepdim=True)
+    assert ((H - H.transpose(2, 3)).abs() / scale).max().item() <= 1e-5
+    far = slice(0, 64), slice(dims[0] - 64, dims[0])          # a corner block and its mirror image
+    assert torch.equal(H[:, :, far[0], far[1]], H[:, :, far[1], far[0]].transpose(2, 3))
+
+
 def test_c6_tanh_hessian_full_size_sampled_columns(oracle):
     w = wl.WORKLOADS["c6_tanh_hessian"]
     say("c6_tanh_hessian: full size, sampled columns H[b, s, :, j]")
