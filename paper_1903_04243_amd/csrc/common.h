@@ -117,6 +117,9 @@ struct GemmArgs {
 // Picks the LDS-tiled kernel or the small-problem kernel.
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream);
 hipError_t launch_gemm_skinny(const GemmArgs &g, hipStream_t stream);
+// 16 x 16 tiles for the smallest float32 products (used by launch_gemm_skinny when it applies)
+bool small16_applies(const GemmArgs &g);
+hipError_t launch_gemm_small16(const GemmArgs &g, hipStream_t stream);
 
 // out[m, i, j] = a[m / S, i] * g[m, j]   for m < M, i < d_in, j < d_out   (float32 out)
 struct OuterArgs {

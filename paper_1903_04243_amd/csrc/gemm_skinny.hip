@@ -538,6 +538,7 @@ hipError_t launch_gemm_skinny(const GemmArgs &g, hipStream_t stream) {
   if (g.epilogue == EPI_HEAD && g.N > 32) return hipErrorInvalidValue;
   if (g.epilogue == EPI_LSTM_FWD && (g.bf16 || !g.w_kn || g.N != 4 * g.lstm_H || g.nbatch > 1))
     return hipErrorInvalidValue;
+  if (small16_applies(g)) return launch_gemm_small16(g, stream);
   if (g.nbatch > 1) {
     // small batched products: one launch per product (this kernel has no batch index)
     const int a_elem = (g.bf16 && !g.a_is_f32) ? 2 : 4, w_elem = g.bf16 ? 2 : 4;
