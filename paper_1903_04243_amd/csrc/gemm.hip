@@ -543,7 +543,8 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
   // (256 x 128 tiles on 8 waves were measured slower than 128 x 128 on 4: 4.82 against 4.46 ms
   // on the 65536 x 2048 x 2048 cotangent product; the wider barrier costs more than the saved loads.
   // 128 x 128 on 8 waves of 32 x 64 each: 75 % of the MFMA peak against 79.5 %.)
-  if (big >= 256)
+  // a 128-wide tile on an output of 64 columns or fewer would be half empty
+  if (big >= 256 && g.N > 64)
     return fast ? launch_one<AMODE, WKN, 2, 2, 128, true>(g, stream)
                 : launch_one<AMODE, WKN, 2, 2, 128, false>(g, stream);
   if constexpr (AMODE != A_F32) {
