@@ -4,8 +4,9 @@ Only ``tests/``, ``__graft_entry__.smoke()`` and the CPU-baseline leg of ``bench
 this package.  It is independent of the HIP library: it neither imports nor is imported by it.
 
 The arithmetic lives in ``pfg_oracle.c`` (dense networks; plain C, literal loops over examples and
-seed rows), ``lstm_oracle.c`` (the unrolled LSTM, wrapped by ``oracle.lstm``) and
-``conv_oracle.c`` (the small convolutional network, wrapped by ``oracle.conv``); this module only
+seed rows), ``lstm_oracle.c`` (the unrolled LSTM, wrapped by ``oracle.lstm``), ``conv_oracle.c`` (the small
+convolutional network, wrapped by ``oracle.conv``) and ``cond_oracle.c`` (a loop body with a
+conditional, wrapped by ``oracle.cond``); this module only
 builds them with gcc, loads the first through ctypes and marshals numpy arrays.
 Every array that crosses this boundary is float64 (labels: int32).
 """
@@ -49,9 +50,10 @@ def build(force: bool = False) -> str:
     """Compile the C oracles with gcc (OpenMP only parallelises the outermost pfor index)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         compile_source(_SRC, _LIB)
-    from . import conv, lstm
+    from . import cond, conv, lstm
     lstm.build(force)
     conv.build(force)
+    cond.build(force)
     return _LIB
 
 

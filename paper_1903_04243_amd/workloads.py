@@ -279,3 +279,52 @@ def make_conv_inputs(w: ConvWorkload, B: Optional[int] = None, height=None, widt
     X = rng.uniform(0.0, 1.0, size=(B, h, wd, c)).astype(np.float32)
     labels = rng.integers(0, dims[-1], size=(B,)).astype(np.int32)
     return ConvInputs(w, Wc, bc, Ws, bs, X, labels)
+
+
+# --------------------------------------------------------------------------------------------
+# A loop body with a conditional (Section 3.6): a shared dense part, a per-row condition and two
+# dense branches of different cost.
+# --------------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class CondWorkload:
+    name: str
+    index: int
+    pre: Tuple[int, ...]         # widths d_0 .. d_T of the shared part
+    then_dims: Tuple[int, ...]   # widths after d_T of the then branch
+    else_dims: Tuple[int, ...]   # widths after d_T of the else branch (same last width)
+    act: str
+    n: int
+
+
+COND_WORKLOADS: Dict[str, CondWorkload] = {
+    w.name: w for w in [
+        CondWorkload("c11_cond_two_branches", 10, (784, 512), (1024, 1024, 10), (10,), "relu", 8192),
+    ]
+}
+
+
+@dataclass
+class CondInputs:
+    workload: CondWorkload
+    pre: Tuple[List[np.ndarray], List[np.ndarray]]          # (weights, biases)
+    then_net: Tuple[List[np.ndarray], List[np.ndarray]]
+    else_net: Tuple[List[np.ndarray], List[np.ndarray]]
+    w: np.ndarray            # [d_T]
+    c0: float
+    X: np.ndarray            # [n, d_0]
+
+
+def make_cond_inputs(w: CondWorkload, n: Optional[int] = None, pre=None, then_dims=None, else_dims=None,
+                     bias_scale: float = 0.0, c0: float = 0.0, seed: Optional[int] = None) -> CondInputs:
+    """Weights N(0, 1 / fan_in), condition vector N(0, 1 / d_T), X standard normal; draw order: shared
+    part, then branch, else branch (weights and biases layer by layer), condition vector, X."""
+    n = w.n if n is None else n
+    pre = tuple(w.pre if pre is None else pre)
+    then_dims = tuple(w.then_dims if then_dims is None else then_dims)
+    else_dims = tuple(w.else_dims if else_dims is None else else_dims)
+    rng = np.random.Generator(np.random.Philox(BASE_SEED + w.index if seed is None else seed))
+    nets = [draw_weights(rng, dims, "normal_fan_in", bias_scale)
+            for dims in (pre, (pre[-1],) + then_dims, (pre[-1],) + else_dims)]
+    wv = (rng.standard_normal(pre[-1]) / np.sqrt(pre[-1])).astype(np.float32)
+    X = rng.standard_normal((n, pre[0])).astype(np.float32)
+    return CondInputs(w, nets[0], nets[1], nets[2], wv, float(c0), X)

@@ -151,6 +151,40 @@ CONV_MUTANTS = [
 ]
 
 
+COND_SRC = os.path.join(ROOT, "oracle", "cond_oracle.c")
+
+COND_MUTANTS = [
+    ("condition_not_strict", "c = s > 0.0;", "c = s >= 0.0;"),
+    ("condition_flipped", "c = s > 0.0;", "c = s < 0.0;"),
+    ("condition_offset_dropped", "double s = net->c0;\n    for (int k = 0; k < dT; ++k) s += t[k] * net->w[k];\n    c =",
+     "double s = 0.0;\n    for (int k = 0; k < dT; ++k) s += t[k] * net->w[k];\n    c ="),
+    ("condition_reads_one_component", "for (int k = 0; k < dT; ++k) s += t[k] * net->w[k];\n    c =",
+     "for (int k = 0; k < 1; ++k) s += t[k] * net->w[k];\n    c ="),
+    ("branches_swapped", "if (c)\n    mlp_forward(net->then_net, t, 0, r);\n  else\n    mlp_forward(net->else_net, t, 0, r);",
+     "if (c)\n    mlp_forward(net->else_net, t, 0, r);\n  else\n    mlp_forward(net->then_net, t, 0, r);"),
+    ("else_branch_is_then", "else\n    mlp_forward(net->else_net, t, 0, r);", "else\n    mlp_forward(net->then_net, t, 0, r);"),
+    ("invariant_flag_ignored", "if (invariant < 0) {", "if (1) {"),
+    ("invariant_flag_inverted", "c = invariant != 0;", "c = invariant == 0;"),
+    ("shared_part_without_last_activation", "mlp_forward(net->pre, x, 1, t);", "mlp_forward(net->pre, x, 0, t);"),
+    ("branch_with_last_activation", "mlp_forward(which ? net->then_net : net->else_net, t, 0, r);",
+     "mlp_forward(which ? net->then_net : net->else_net, t, 1, r);"),
+    ("body_branch_with_last_activation", "if (c)\n    mlp_forward(net->then_net, t, 0, r);", "if (c)\n    mlp_forward(net->then_net, t, 1, r);"),
+    ("bias_dropped", "double z = b ? b[j] : 0.0;", "double z = 0.0;"),
+    ("weight_transposed", "z += cur[k] * W[(size_t)k * dout + j];", "z += cur[k] * W[(size_t)j * din + k];"),
+    ("hidden_activation_dropped", "nxt[j] = (l < m->L || last_act) ? act_value(m->act, z) : z;",
+     "nxt[j] = (l == m->L && last_act) ? act_value(m->act, z) : z;"),
+    ("branch_reads_input_not_shared_part", "condo_pre(net, x, t);\n  mlp_forward(which ? net->then_net",
+     "condo_pre(net, x, t); memcpy(t, x, sizeof(double) * (size_t)(dT < net->pre->dims[0] ? dT : net->pre->dims[0]));\n  mlp_forward(which ? net->then_net"),
+    ("row_stacking", "const int c = condo_body(net, X + i * d0, invariant, R + i * dout);",
+     "const int c = condo_body(net, X + i * d0, invariant, R + (n - 1 - i) * dout);"),
+    ("condition_stacking", "if (cond) cond[i] = c;", "if (cond) cond[n - 1 - i] = c;"),
+    ("score_offset_dropped", "double s = net->c0;\n  for (int k = 0; k < dT; ++k) s += t[k] * net->w[k];\n  free(t);",
+     "double s = 0.0;\n  for (int k = 0; k < dT; ++k) s += t[k] * net->w[k];\n  free(t);"),
+    ("gelu_is_tanh_form", "return z * 0.5 * (1.0 + erf(z / sqrt(2.0)));",
+     "return z * 0.5 * (1.0 + tanh(0.7978845608 * (z + 0.044715 * z * z * z)));"),
+]
+
+
 def run_mutants(oracle, tmp_path, source, mutants, env_var, pins_file):
     """Build every mutant and run the pin file against it, a few at a time; returns the names of
     the mutants that survived (passed every pin)."""
@@ -193,9 +227,16 @@ def test_conv_pins_catch_every_planted_mistake(tmp_path, oracle):
     assert not survivors, "mutants that passed every pin: " + ", ".join(n for n, _ in survivors)
 
 
+def test_cond_pins_catch_every_planted_mistake(tmp_path, oracle):
+    survivors = run_mutants(oracle, tmp_path, COND_SRC, COND_MUTANTS, "PFG_COND_ORACLE_LIB",
+                            "test_oracle_cond_pins.py")
+    assert not survivors, "mutants that passed every pin: " + ", ".join(n for n, _ in survivors)
+
+
 def test_the_unmutated_oracles_pass_their_pins():
     # the check above would be empty if the pin files failed for another reason
-    for pins in ("test_oracle_pins.py", "test_oracle_lstm_pins.py", "test_oracle_conv_pins.py"):
+    for pins in ("test_oracle_pins.py", "test_oracle_lstm_pins.py", "test_oracle_conv_pins.py",
+                 "test_oracle_cond_pins.py"):
         r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", pins), "-x",
                             "-q", "-p", "no:cacheprovider"], cwd=ROOT, capture_output=True, text=True,
                            timeout=600)
