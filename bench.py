@@ -384,9 +384,58 @@ def main():
         log(f"[bench] {name}: {rec['ms_per_step']:.4f} ms/step, roofline frac {roof['frac']:.3f}")
         return rec, inp
 
+    def measure_cond(name, steps, warmup):
+        w = wl.COND_WORKLOADS[name]
+        log(f"[bench] {name}: uploading inputs")
+        inp = wl.make_cond_inputs(w)
+        net = pfg.Cond.from_numpy(inp.pre, inp.w, inp.c0, inp.then_net, inp.else_net, w.act)
+        X = torch.from_numpy(inp.X).to(dev)
+        n = w.n
+        out = (torch.empty((n, net.dout), dtype=torch.float32, device=dev),
+               torch.empty((n,), dtype=torch.int32, device=dev), torch.empty((2,), dtype=torch.int32, device=dev))
+        ws = torch.empty(pfg.pfg_cond_workspace_bytes(net, n), dtype=torch.uint8, device=dev)
+        step = lambda: pfg.pfg_cond_forward(net, X, out=out, workspace=ws)
+        step()
+        torch.cuda.synchronize()
+        n_then, n_else = out[2].tolist()
+        log(f"[bench] {name}: {n_then} then rows, {n_else} else rows; timing {steps} steps")
+        sec = timed(step, steps, warmup)
+        sec_graph = None
+        if not args.no_graph:
+            try:
+                sec_graph = timed_graph(step, steps, warmup)
+            except Exception as e:
+                log(f"[bench] {name}: graph replay not measured ({e})")
+        kt = kernel_times(step, steps)
+        per_row = lambda dims: 2 * sum(dims[l] * dims[l + 1] for l in range(len(dims) - 1))
+        dT = w.pre[-1]
+        flops = {"cond_gemm_pre": n * per_row(w.pre), "cond_gemm_then": n_then * per_row((dT,) + w.then_dims),
+                 "cond_gemm_else": n_else * per_row((dT,) + w.else_dims)}
+        # the roofline counts the rows a branch really has, not the n rows its products are launched for
+        fam = max(flops, key=flops.get)
+        tf = flops[fam] / kt[fam]["ms_per_step"] / 1e9
+        roof = {"kernel": fam, "bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["f32"],
+                "unit": "TFLOP/s", "frac": tf / MFMA_PEAK_TFLOPS["f32"], "traffic": None,
+                "flops_per_step": flops[fam], "launches_per_step": kt[fam]["launches_per_step"],
+                "ms_per_launch": kt[fam]["ms_per_step"] / kt[fam]["launches_per_step"]}
+        both = n * (per_row(w.pre) + per_row((dT,) + w.then_dims) + per_row((dT,) + w.else_dims))
+        rec = {"workload": name, "call": "cond_forward", "pre": list(w.pre), "then": list(w.then_dims),
+               "else": list(w.else_dims), "act": w.act, "dtype": "f32", "n": n, "n_then": n_then,
+               "n_else": n_else, "steps": steps, "ms_per_step": sec * 1e3,
+               "ms_per_step_graph_replay": None if sec_graph is None else sec_graph * 1e3,
+               "rows_per_sec": n / sec, "kernels": kt,
+               "kernel_ms_sum": sum(v["ms_per_step"] for v in kt.values()),
+               "launches_per_step": sum(v["launches_per_step"] for v in kt.values()),
+               "flops_per_step": sum(flops.values()),
+               "flops_if_both_branches_ran_on_every_row": both, "roofline": roof}
+        log(f"[bench] {name}: {rec['ms_per_step']:.4f} ms/step, roofline frac {roof['frac']:.3f}")
+        return rec, inp
+
     def measure_lstm(name, steps, warmup):
         if name in wl.CONV_WORKLOADS:
             return measure_conv(name, steps, warmup)
+        if name in wl.COND_WORKLOADS:
+            return measure_cond(name, steps, warmup)
         w = wl.LSTM_WORKLOADS[name]
         if w.call == "lstm_varlen_forward":
             return measure_varlen(name, steps, warmup)
@@ -473,7 +522,7 @@ def main():
         return
 
     if args.workload:
-        fn = measure_lstm if (args.workload in wl.LSTM_WORKLOADS or args.workload in wl.CONV_WORKLOADS) else measure
+        fn = measure if args.workload in wl.WORKLOADS else measure_lstm
         rec, _ = fn(args.workload, args.steps, args.warmup)
         print(json.dumps(rec), flush=True)
         return
@@ -510,9 +559,10 @@ def main():
                             ("c7_lstm_grads", max(3, args.steps // 2)),
                             ("c8_lstm_jacobian", max(3, args.steps // 10)),
                             ("c9_lstm_varlen", max(3, args.steps // 10)),
-                            ("c10_mnist_convnet_grads", max(3, args.steps // 10))):
+                            ("c10_mnist_convnet_grads", max(3, args.steps // 10)),
+                            ("c11_cond_two_branches", max(3, args.steps // 4))):
             try:
-                fn = measure_lstm if (name in wl.LSTM_WORKLOADS or name in wl.CONV_WORKLOADS) else measure
+                fn = measure if name in wl.WORKLOADS else measure_lstm
                 others[name], _ = fn(name, steps, max(1, min(args.warmup, steps // 2)))
             except Exception as e:
                 others[name] = {"error": str(e)}

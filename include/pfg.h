@@ -266,6 +266,45 @@ int pfg_convnet_per_example_grads(const pfg_convnet *net, const void *X, const i
                                   float *const *dW_out, float *const *db_out, float *loss_out,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * A parallel-for whose body holds a conditional (Section 3.6).  Iteration i computes
+ *      t = phi_pre(pre(x_i))                 a dense network; its activation is applied after the
+ *                                            last layer too
+ *      c = (sum_k t[k] * cond_w[k] + cond_c > 0)
+ *      r = c ? then_net(t) : else_net(t)     two dense networks with input width d_T (the output
+ *                                            width of pre) and the same output width
+ * The vectorised form evaluates the condition for all iterations, builds the index sets I_then and
+ * I_else (each in increasing order), runs each branch on the rows of its own set only and puts
+ * the results back at the rows they belong to.  Here the sets and their sizes stay on the device:
+ * the first product of a branch reads its rows of t through the index set, its last product
+ * stores its rows through it, and the products take their row count from device memory, so there
+ * is no separate subsetting or scatter pass and no synchronisation with the host.  A branch whose
+ * set is empty does no work.  When the condition does not depend on the iteration
+ * (invariant_cond = 0 or 1), it is not evaluated and the chosen branch runs on all rows without
+ * index sets.  All three networks must be PFG_F32.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct {
+  pfg_mlp pre;
+  const void *cond_w;     /* DEVICE [d_T] float32 */
+  float cond_c;
+  pfg_mlp then_net;
+  pfg_mlp else_net;
+} pfg_cond;
+
+#define PFG_COND_PER_ITERATION (-1)
+
+int pfg_cond_workspace_bytes(const pfg_cond *net, int64_t n, size_t *bytes);
+
+/*   X              [n, d_0] float32
+ *   invariant_cond PFG_COND_PER_ITERATION, or 0 / 1 for a loop-invariant condition of that value
+ *   R_out          [n, d_out]: every row is written by exactly one branch
+ *   cond_out       [n] int32 or NULL: 1 where the then branch ran
+ *   counts_out     DEVICE [2] int32 or NULL: sizes of I_then and I_else
+ * n is limited to 2^24 rows. */
+int pfg_cond_forward(const pfg_cond *net, const void *X, int64_t n, int invariant_cond, float *R_out,
+                     int32_t *cond_out, int32_t *counts_out, void *workspace, size_t workspace_bytes,
+                     void *hip_stream);
+
 /* Text of the last error on the calling thread ("" if none).  Valid until the next call into the
  * library from that thread. */
 const char *pfg_last_error(void);

@@ -29,6 +29,7 @@ EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_jacobian_input",
            "pfg_lstm_workspace_bytes", "pfg_lstm_per_example_grads", "pfg_lstm_jacobian_input",
            "pfg_lstm_varlen_workspace_bytes", "pfg_lstm_varlen_forward",
            "pfg_convnet_workspace_bytes", "pfg_convnet_per_example_grads",
+           "pfg_cond_workspace_bytes", "pfg_cond_forward",
            "pfg_last_error", "pfg_timing_enable", "pfg_timing_reset",
            "pfg_timing_query", "pfg_timing_names", "pfg_version"]
 
@@ -78,7 +79,18 @@ class pfg_convnet(ctypes.Structure):
     ]
 
 
+class pfg_cond(ctypes.Structure):
+    _fields_ = [
+        ("pre", pfg_mlp),
+        ("cond_w", ctypes.c_void_p),
+        ("cond_c", ctypes.c_float),
+        ("then_net", pfg_mlp),
+        ("else_net", pfg_mlp),
+    ]
+
+
 LSTM_OP = {"per_example_grads": 0, "jacobian_input": 1}
+PFG_COND_PER_ITERATION = -1
 
 _lib = None
 
@@ -117,6 +129,9 @@ def load_library() -> ctypes.CDLL:
         lib.pfg_convnet_per_example_grads.argtypes = [convp, vp, vp, i64, ctypes.POINTER(vp),
                                                       ctypes.POINTER(vp), ctypes.POINTER(vp),
                                                       ctypes.POINTER(vp), vp, vp, ctypes.c_size_t, vp]
+        condp = ctypes.POINTER(pfg_cond)
+        lib.pfg_cond_workspace_bytes.argtypes = [condp, i64, ctypes.POINTER(ctypes.c_size_t)]
+        lib.pfg_cond_forward.argtypes = [condp, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.pfg_last_error.restype = ctypes.c_char_p
         lib.pfg_timing_enable.argtypes = [i32]
         lib.pfg_timing_query.argtypes = [ctypes.c_char_p, ctypes.POINTER(i64),
@@ -544,6 +559,60 @@ def pfg_convnet_per_example_grads(net: ConvNet, X, labels, want_dWc: Optional[Se
         None if loss is None else loss.data_ptr(), workspace.data_ptr(),
         workspace.numel() * workspace.element_size(), _stream_ptr()))
     return dWc, dbc, dW, db, loss
+
+
+class Cond:
+    """Loop body with a conditional: ``t = phi_pre(pre(x))``; ``then_net(t)`` where
+    ``t . cond_w + cond_c > 0``, ``else_net(t)`` elsewhere.  The three parts are float32 ``Mlp``
+    objects; ``cond_w`` is a float32 [d_T] GPU tensor."""
+
+    def __init__(self, pre: Mlp, cond_w, cond_c: float, then_net: Mlp, else_net: Mlp):
+        import torch
+        if cond_w is not None and (cond_w.dtype != torch.float32 or not cond_w.is_contiguous() or
+                                   not cond_w.is_cuda or tuple(cond_w.shape) != (pre.dims[-1],)):
+            raise ValueError("cond_w must be a contiguous float32 [d_T] GPU tensor")
+        self.pre, self.then_net, self.else_net = pre, then_net, else_net
+        self.cond_w, self.cond_c = cond_w, float(cond_c)
+        self.device = pre.device
+        self.d0, self.dT, self.dout = pre.dims[0], pre.dims[-1], then_net.dims[-1]
+        self.c = pfg_cond(pre.c, None if cond_w is None else cond_w.data_ptr(), self.cond_c, then_net.c,
+                          else_net.c)
+
+    @staticmethod
+    def from_numpy(pre, cond_w, cond_c, then_net, else_net, act: str, device: str = "cuda:0") -> "Cond":
+        """pre, then_net, else_net: (weights, biases) pairs of numpy arrays."""
+        import torch
+        nets = [Mlp.from_numpy(Ws, bs, act, "f32", device=device) for Ws, bs in (pre, then_net, else_net)]
+        return Cond(nets[0], torch.from_numpy(cond_w).to(device), cond_c, nets[1], nets[2])
+
+
+def pfg_cond_workspace_bytes(net: Cond, n: int) -> int:
+    b = ctypes.c_size_t(0)
+    _check(load_library().pfg_cond_workspace_bytes(ctypes.byref(net.c), n, ctypes.byref(b)))
+    return int(b.value)
+
+
+def pfg_cond_forward(net: Cond, X, invariant_cond: int = PFG_COND_PER_ITERATION, want_cond: bool = True,
+                     want_counts: bool = True, out=None, workspace=None):
+    """Returns (R [n, d_out], cond [n] int32 or None, counts [2] int32 or None); ``out`` may hold
+    caller tensors in that structure."""
+    import torch
+    if X.dtype != torch.float32 or not X.is_contiguous() or X.dim() != 2 or X.shape[1] != net.d0:
+        raise ValueError("X must be a contiguous float32 [n, d_0] tensor")
+    n = X.shape[0]
+    if out is not None:
+        R, cond, counts = out
+    else:
+        R = torch.empty((n, net.dout), dtype=torch.float32, device=net.device)
+        cond = torch.empty((n,), dtype=torch.int32, device=net.device) if want_cond else None
+        counts = torch.empty((2,), dtype=torch.int32, device=net.device) if want_counts else None
+    if workspace is None:
+        workspace = torch.empty(pfg_cond_workspace_bytes(net, n), dtype=torch.uint8, device=net.device)
+    _check(load_library().pfg_cond_forward(
+        ctypes.byref(net.c), X.data_ptr(), n, int(invariant_cond), R.data_ptr(),
+        None if cond is None else cond.data_ptr(), None if counts is None else counts.data_ptr(),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr()))
+    return R, cond, counts
 
 
 def pfg_timing_enable(on: bool) -> None:

@@ -32,7 +32,8 @@ enum Act : int { ACT_IDENTITY = 0, ACT_RELU = 1, ACT_TANH = 2, ACT_GELU = 3 };
 enum Epilogue : int {
   EPI_NONE = 0,      // C = acc
   EPI_BIAS = 1,      // C = acc + bias                      (last forward layer: logits)
-  EPI_FORWARD = 2,   // z = acc + bias; C = phi(z); C2 = phi'(z)   (hidden forward layer)
+  EPI_FORWARD = 2,   // z = acc + bias; C = phi(z); C2 = phi'(z)   (hidden forward layer; either of C
+                     // and C2 may be null)
   EPI_MASK = 3,      // C = acc * emask[m / S, n]           (cotangent step)
   EPI_HEAD = 4,      // y = acc + bias (N <= 32, optional C = y); C2 = softmax(y) - onehot(label);
                      // loss = -log softmax(y)[label]       (last forward layer fused with the head,
@@ -112,6 +113,14 @@ struct GemmArgs {
   float *lstm_hs_w;             // hidden state, same addressing (the product's A operand is read elsewhere)
   int64_t lstm_state_ld, lstm_state_ts;   // [M, T, H] history: T * H and H; state updated in place: H and 0
   int32_t lstm_has_prev;        // 0: c_{step-1} is zero and is not read
+  // Rows chosen on the device (the index sets of a conditional, Section 3.6).  When `sub` is set the
+  // product runs on rows m < sub[0] only (sub[0] <= M; M still sizes the grid).  With sub_gather, row
+  // m of the A operand is row sub_rows[sub[1] + m] of A; with sub_scatter, row m of the result is
+  // stored at row sub_rows[sub[1] + m] of C (and C2).  float32 operands, S == 1, no batching;
+  // EPI_NONE, EPI_BIAS and EPI_FORWARD only.
+  const int32_t *sub;           // {row count, offset into sub_rows}
+  const int32_t *sub_rows;
+  int32_t sub_gather, sub_scatter;
 };
 
 // Picks the LDS-tiled kernel or the small-problem kernel.
@@ -238,5 +247,17 @@ hipError_t launch_unpool_mask(const float *dpooled, const float *pooled, const u
 // din [B, h, w, c] = gather of the patch cotangents dP [B h w, k k c]
 hipError_t launch_col2im(const float *dP, int64_t B, int32_t h, int32_t w, int32_t c, int32_t k,
                          float *din, hipStream_t stream);
+
+// Conditional inside the parallel-for: flags[j] = (T[j, :] . w + c0 > 0) for j < n (T has d columns,
+// row stride ldt), then rows[] = the flagged row indices in increasing order followed by the others
+// in increasing order, meta = {n_then, 0, n_else, n_then} (two GemmArgs::sub descriptors).
+// cnt needs cond_count_groups(n) entries.  cond_out [n] (the flags) and counts_out [2] are optional.
+int64_t cond_count_groups(int64_t n);
+hipError_t launch_cond_partition(const float *T, int64_t ldt, int32_t n, int32_t d, const float *w,
+                                 float c0, int32_t *flags, int32_t *cnt, int32_t *rows, int32_t *meta,
+                                 int32_t *cond_out, int32_t *counts_out, hipStream_t stream);
+// Loop-invariant condition: cond_out[j] = flag, counts_out = {n, 0} or {0, n} (both optional)
+hipError_t launch_cond_invariant(int32_t n, int32_t flag, int32_t *cond_out, int32_t *counts_out,
+                                 hipStream_t stream);
 
 }  // namespace pfg

@@ -1,0 +1,151 @@
+// Kernels of the conditional inside a parallel-for (Section 3.6): the condition of every iteration
+// is evaluated at once, then the flags are turned into the two index sets I_then and I_else, each in
+// increasing order of the iteration index.  Both sets live in one array: the then-rows at the
+// front, the else-rows behind them; `meta` tells the products that follow where each set starts and
+// how long it is, so that the host never has to read a count back.
+#include "common.h"
+
+namespace pfg {
+
+namespace {
+
+constexpr int kGroup = 32;       // rows whose set flags are counted together
+constexpr int kPlace = 1024;     // rows per workgroup of the placing kernel (a multiple of kGroup)
+
+// flags[j] = (T[j, :] . w + c0 > 0); cnt[j / kGroup] = set flags in the group.  16 lanes share a row
+// (each sums every 16th piece of the row, then a fixed xor tree joins the 16 partial sums); a
+// workgroup of 256 threads takes one group of 32 rows in two passes.
+__global__ __launch_bounds__(256) void cond_flags_kernel(const float *T, int64_t ldt, int n, int d,
+                                                         const float *w, float c0, int32_t *flags,
+                                                         int32_t *cnt) {
+  __shared__ int s_cnt;
+  if (threadIdx.x == 0) s_cnt = 0;
+  __syncthreads();
+  const int slot = threadIdx.x >> 4, l16 = threadIdx.x & 15;
+  const bool vec = ((reinterpret_cast<uintptr_t>(T) | reinterpret_cast<uintptr_t>(w)) & 15) == 0 &&
+                   ldt % 4 == 0 && d % 4 == 0;
+  int mine = 0;
+  for (int pass = 0; pass < kGroup / 16; ++pass) {
+    const int row = blockIdx.x * kGroup + pass * 16 + slot;
+    float s = 0.f;
+    if (row < n) {
+      const float *t = T + (int64_t)row * ldt;
+      if (vec) {
+        for (int k = 4 * l16; k < d; k += 64) {
+          const f32x4 a = *reinterpret_cast<const f32x4 *>(t + k);
+          const f32x4 b = *reinterpret_cast<const f32x4 *>(w + k);
+          s += a[0] * b[0] + a[1] * b[1] + a[2] * b[2] + a[3] * b[3];
+        }
+      } else {
+        for (int k = l16; k < d; k += 16) s += t[k] * w[k];
+      }
+    }
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 16);
+    if (l16 == 0 && row < n) {
+      const int f = (s + c0 > 0.f) ? 1 : 0;
+      flags[row] = f;
+      mine += f;
+    }
+  }
+  if (l16 == 0 && mine) atomicAdd(&s_cnt, mine);      // integers: the order does not matter
+  __syncthreads();
+  if (threadIdx.x == 0) cnt[blockIdx.x] = s_cnt;
+}
+
+// Row j with a set flag goes to rows[(set flags before j)], a row with a clear flag to
+// rows[n_then + (clear flags before j)].  A workgroup places kPlace consecutive rows: it sums the
+// group counts in front of its rows (and all of them, for n_then), ranks its own rows with a
+// ballot per wave, and writes.  meta = {n_then, 0, n_else, n_then}: count and offset of each set.
+__global__ __launch_bounds__(kPlace) void cond_place_kernel(const int32_t *flags, const int32_t *cnt,
+                                                            int n, int32_t *rows, int32_t *meta,
+                                                            int32_t *cond_out, int32_t *counts_out) {
+  constexpr int kWaves = kPlace / 64;
+  __shared__ int s_before[kWaves], s_total[kWaves], s_wave[kWaves];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ngroups = (n + kGroup - 1) / kGroup;
+  const int first_group = blockIdx.x * (kPlace / kGroup);
+  int before = 0, total = 0;
+  for (int g = tid; g < ngroups; g += kPlace) {
+    const int c = cnt[g];
+    total += c;
+    if (g < first_group) before += c;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    before += __shfl_xor(before, off, 64);
+    total += __shfl_xor(total, off, 64);
+  }
+  const int j = blockIdx.x * kPlace + tid;
+  const int f = (j < n) ? flags[j] : 0;
+  const unsigned long long set = __ballot(f != 0);
+  const int rank_in_wave = __popcll(set & ((1ull << lane) - 1ull));
+  if (lane == 0) {
+    s_before[wave] = before;
+    s_total[wave] = total;
+    s_wave[wave] = __popcll(set);
+  }
+  __syncthreads();
+  int then_before = 0, n_then = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    then_before += s_before[w];
+    n_then += s_total[w];
+    if (w < wave) then_before += s_wave[w];
+  }
+  if (j < n) {
+    const int r = then_before + rank_in_wave;            // set flags in front of row j
+    rows[f ? r : n_then + (j - r)] = j;
+    if (cond_out) cond_out[j] = f;
+  }
+  if (blockIdx.x == 0 && tid == 0) {
+    meta[0] = n_then;
+    meta[1] = 0;
+    meta[2] = n - n_then;
+    meta[3] = n_then;
+    if (counts_out) {
+      counts_out[0] = n_then;
+      counts_out[1] = n - n_then;
+    }
+  }
+}
+
+// out[0 .. n) = value (int32)
+__global__ __launch_bounds__(256) void fill_int_kernel(int32_t *out, int n, int32_t value) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) out[i] = value;
+}
+
+// counts_out = {n or 0, 0 or n} for a loop-invariant condition
+__global__ void invariant_counts_kernel(int32_t *counts_out, int n, int flag) {
+  if (threadIdx.x == 0) {
+    counts_out[0] = flag ? n : 0;
+    counts_out[1] = flag ? 0 : n;
+  }
+}
+
+}  // namespace
+
+int64_t cond_count_groups(int64_t n) { return (n + kGroup - 1) / kGroup; }
+
+hipError_t launch_cond_partition(const float *T, int64_t ldt, int32_t n, int32_t d, const float *w,
+                                 float c0, int32_t *flags, int32_t *cnt, int32_t *rows, int32_t *meta,
+                                 int32_t *cond_out, int32_t *counts_out, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  PFG_KERNEL(cond_flags_kernel, dim3((unsigned)((n + kGroup - 1) / kGroup)), dim3(256), 0, stream, T, ldt,
+             n, d, w, c0, flags, cnt);
+  PFG_KERNEL(cond_place_kernel, dim3((unsigned)((n + kPlace - 1) / kPlace)), dim3(kPlace), 0, stream, flags,
+             cnt, n, rows, meta, cond_out, counts_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_cond_invariant(int32_t n, int32_t flag, int32_t *cond_out, int32_t *counts_out,
+                                 hipStream_t stream) {
+  if (cond_out && n > 0)
+    PFG_KERNEL(fill_int_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, cond_out, n,
+               flag ? 1 : 0);
+  if (counts_out) PFG_KERNEL(invariant_counts_kernel, dim3(1), dim3(64), 0, stream, counts_out, n, flag);
+  return hipGetLastError();
+}
+
+}  // namespace pfg

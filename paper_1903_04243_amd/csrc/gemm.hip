@@ -24,7 +24,10 @@ namespace {
 using namespace dev;
 
 // WGM x WGN: arrangement of the workgroup's waves over the tile (2 x 2, or 4 x 2 for the largest).
-template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2>
+// SUB: the instantiation for rows chosen on the device (GemmArgs::sub; float32, W in [K, N] layout),
+// kept apart so that the others carry none of its loads and branches (inside the unrolled epilogue
+// they cost a store-bound product a quarter of its speed).
+template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2, bool SUB = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) {
   constexpr int kThreads = 64 * WGM * WGN;
   constexpr bool BF16 = (AMODE != A_F32);
@@ -84,6 +87,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
     tile_m = (t / tri) * T + ti;
     tile_n = ti + p;
     mirror = p > 0;
+  } else if (SUB) {
+    // Rows chosen on the device: only the first tiles along M are live, how many is not known to
+    // the host.  Row tiles are dealt to the XCDs in turn (tile_m = 8 i + xcd), so that the live ones
+    // spread over all eight whatever their number; an XCD still walks the N tiles of a row tile
+    // one after the other.  The grid is rounded up to whole rounds of eight row tiles.
+    const int xcd = blockIdx.x % 8, idx = blockIdx.x / 8;
+    tile_m = (idx / tiles_n) * 8 + xcd;
+    tile_n = idx % tiles_n;
+    if (tile_m >= tiles_m) return;
   } else {
     const int total = tiles_m * tiles_n;
     int t = blockIdx.x;
@@ -93,7 +105,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   }
   const int m0 = tile_m * BM;
   const int n0 = tile_n * BN;
-  const int M = g.M, N = g.N, K = g.K;
+  // rows chosen on the device: the live row count comes from memory, tiles past it have nothing to do
+  const int M = SUB ? g.sub[0] : g.M, N = g.N, K = g.K;
+  if (SUB && m0 >= M) return;
+  const int sub_off = SUB ? g.sub[1] : 0;
 
   const bool a_vec_ok = ((reinterpret_cast<uintptr_t>(gA) & 15) == 0) &&
                         ((g.lda * (AMODE == A_BF16 ? 2 : 4)) % 16 == 0) &&
@@ -119,7 +134,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
     a_row[c] = nullptr;
     a_srow[c] = nullptr;
     if (FAST || m < M) {
-      const int mc = FAST ? min(m, M - 1) : m;     // FAST: rows past the end re-read the last row
+      int mc = FAST ? min(m, M - 1) : m;           // FAST: rows past the end re-read the last row
+      if (SUB && g.sub_gather) mc = g.sub_rows[sub_off + mc];
       const int64_t b = mc / g.S, s = mc % g.S;
       const int64_t off = b * g.a_batch_stride + s * g.lda;
       if constexpr (AMODE == A_BF16)
@@ -454,15 +470,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
       const int m = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
       if (m >= M) continue;
       const float *mrow = (epi == EPI_MASK) ? g.emask + (int64_t)(m / g.S) * g.ld_emask : nullptr;
+      const int64_t orow = (SUB && g.sub_scatter) ? g.sub_rows[sub_off + m] : m;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         if (!n_ok[j]) continue;
         const int n = n0 + wn + j * 32 + l32;
         float v = acc[i][j][r];
-        const int64_t o = (int64_t)m * g.ldc + n;
+        const int64_t o = orow * g.ldc + n;
         if (epi == EPI_FORWARD) {
           const float z = v + bias[j];
-          g.C2[o] = act_deriv(g.act, z);
+          if (g.C2) g.C2[o] = act_deriv(g.act, z);
           if (gC == nullptr) continue;       // only phi'(z) is wanted
           v = act_value(g.act, z);
         } else if (epi == EPI_BIAS) {
@@ -508,14 +525,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   }
 }
 
-template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2>
+template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2, bool SUB = false>
 hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
   constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
   constexpr int kThreads = 64 * WGM * WGN;
   constexpr bool WTR = WKN && (AMODE != A_F32);
   constexpr int BK = BKB / (AMODE != A_F32 ? 2 : 4);
   constexpr int smem = 2 * (BM * (BKB + 16) + (WTR ? BK * (BN * 2 + 16) : BN * (BKB + 16)));
-  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB, FAST, WGM, WGN>;
+  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB, FAST, WGM, WGN, SUB>;
   static bool attr_set = false;   // benign race: the attribute is idempotent
   if (!attr_set && smem > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -528,6 +545,7 @@ hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
     const int64_t T = g.sym_n / BM;
     tiles = (g.M / g.sym_n) * (T * (T + 1) / 2);
   }
+  if (SUB) tiles = (int64_t)((g.M + BM - 1) / BM + 7) / 8 * 8 * ((g.N + BN - 1) / BN);
   const unsigned nbatch = g.nbatch > 1 ? (unsigned)g.nbatch : 1u;
   PFG_KERNEL(kern, dim3((unsigned)tiles, nbatch), dim3(kThreads), smem, stream, g);
   return hipGetLastError();
@@ -535,16 +553,29 @@ hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
 
 template <int AMODE, bool WKN>
 hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
-  // Large tiles once they still give the 256 compute units a full wave of workgroups; otherwise
-  // 64 x 64 tiles, so that small-batch products (M = B) spread over more units.
+  // Large tiles once there are two of them for each of the 256 compute units (two workgroups fit a
+  // unit and cover each other's barriers and LDS waits); otherwise 64 x 64 tiles.  With exactly 256
+  // large tiles an 8192 x 784 x 512 product took 94 us, with 1024 small ones 76 us.
   const int64_t nb = g.nbatch > 1 ? g.nbatch : 1;
-  const int64_t big = nb * ((g.M + 127) / 128) * ((g.N + 127) / 128);
+  // rows chosen on the device: the host knows only the upper bound M; half of it is taken as live
+  const int64_t m_est = g.sub ? (g.M + 1) / 2 : g.M;
+  const int64_t big = nb * ((m_est + 127) / 128) * ((g.N + 127) / 128);
   const bool fast = fast_loads_ok(g);
   // (256 x 128 tiles on 8 waves were measured slower than 128 x 128 on 4: 4.82 against 4.46 ms
   // on the 65536 x 2048 x 2048 cotangent product; the wider barrier costs more than the saved loads.
   // 128 x 128 on 8 waves of 32 x 64 each: 75 % of the MFMA peak against 79.5 %.)
   // a 128-wide tile on an output of 64 columns or fewer would be half empty
-  if (big >= 256 && g.N > 64)
+  if constexpr (AMODE == A_F32 && WKN) {
+    if (g.sub) {
+      if (big >= 512 && g.N > 64)
+        return fast ? launch_one<AMODE, WKN, 2, 2, 128, true, 2, 2, true>(g, stream)
+                    : launch_one<AMODE, WKN, 2, 2, 128, false, 2, 2, true>(g, stream);
+      return fast ? launch_one<AMODE, WKN, 1, 1, 128, true, 2, 2, true>(g, stream)
+                  : launch_one<AMODE, WKN, 1, 1, 128, false, 2, 2, true>(g, stream);
+    }
+  }
+  if (g.sub) return hipErrorInvalidValue;     // rows chosen on the device: float32 forward products only
+  if (big >= 512 && g.N > 64)
     return fast ? launch_one<AMODE, WKN, 2, 2, 128, true>(g, stream)
                 : launch_one<AMODE, WKN, 2, 2, 128, false>(g, stream);
   if constexpr (AMODE != A_F32) {
@@ -566,10 +597,19 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
     return hipErrorInvalidValue;
   if (g.nbatch > 1 && (g.epilogue != EPI_NONE || g.nbatch > 65535))
     return hipErrorInvalidValue;
+  if (g.sub && (g.bf16 || !g.a_is_f32 || !g.w_kn || g.S != 1 || g.nbatch > 1 || g.sym_n > 0 || g.a_scale ||
+                (g.epilogue != EPI_NONE && g.epilogue != EPI_BIAS && g.epilogue != EPI_FORWARD) ||
+                ((g.sub_gather || g.sub_scatter) && !g.sub_rows)))
+    return hipErrorInvalidValue;
+  if (!g.sub && (g.sub_gather || g.sub_scatter)) return hipErrorInvalidValue;
   // Fewer than 128 tiles of 64 x 64 cannot occupy the chip: such products (M = B rows, or a
   // narrow output) go to the kernel that splits the contraction over the waves of a workgroup.
   const int64_t tiles64 = (int64_t)(g.nbatch > 1 ? g.nbatch : 1) * ((g.M + 63) / 64) * ((g.N + 63) / 64);
-  if (g.epilogue == EPI_HEAD || g.epilogue == EPI_LSTM_FWD || tiles64 < 128)
+  // A single column tile of at most 32 with a long contraction is bound by reading A: the kernel
+  // whose waves load their operands straight into registers does that with four times as many
+  // workgroups as 64 x 64 tiles would give.
+  const bool narrow = g.N <= 32 && g.K >= 256 && g.nbatch <= 1 && g.sym_n == 0;
+  if (g.epilogue == EPI_HEAD || g.epilogue == EPI_LSTM_FWD || tiles64 < 128 || narrow)
     return launch_gemm_skinny(g, stream);
   if (!g.bf16) {
     return g.w_kn ? launch_tiles<A_F32, true>(g, stream) : launch_tiles<A_F32, false>(g, stream);

@@ -67,7 +67,8 @@ __device__ __forceinline__ void head_cotangent(const GemmArgs &g, const float (*
 // LSTM: the instantiation that carries the two LSTM epilogues (float32 only).  They live in a
 // separate instantiation so that the kernels of the dense-network path stay as small as they were:
 // with a handful of waves per launch, every extra instruction on the way shows in the run time.
-template <int AMODE, bool WKN, int NW, bool FAST, bool LSTM = false>
+// SUB: the instantiation for rows chosen on the device (GemmArgs::sub), apart for the same reason.
+template <int AMODE, bool WKN, int NW, bool FAST, bool LSTM = false, bool SUB = false>
 __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) {
   constexpr bool BF16 = (AMODE != A_F32);
   constexpr int ELEM = BF16 ? 2 : 4;
@@ -85,9 +86,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   const int wave = tid >> 6;
   const int half = lane >> 5;
   const int l32 = lane & 31;
-  const int M = g.M, N = g.N, K = g.K;
-  const int tiles_m = (M + 31) / 32;
+  const int N = g.N, K = g.K;
+  const int tiles_m = (g.M + 31) / 32;
   const int m0 = (blockIdx.x % tiles_m) * 32;
+  // rows chosen on the device: the live row count comes from memory, tiles past it have nothing to do
+  const int M = SUB ? g.sub[0] : g.M;
+  if (SUB && m0 >= M) return;
+  const int sub_off = SUB ? g.sub[1] : 0;
   // EPI_HEAD has a single column tile (N <= 32); the second grid index then counts the workgroups
   // that share out the fused cotangent step of one row tile (each recomputes the tile's logits)
   const bool is_head = (g.epilogue == EPI_HEAD);
@@ -117,7 +122,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   {
     const int m = m0 + l32;
     if (FAST || m < M) {
-      const int mc = FAST ? min(m, M - 1) : m;     // FAST: rows past the end re-read the last row
+      int mc = FAST ? min(m, M - 1) : m;           // FAST: rows past the end re-read the last row
+      if (SUB && g.sub_gather) mc = g.sub_rows[sub_off + mc];
       const int64_t b = mc / g.S, s = mc % g.S;
       const int64_t off = b * g.a_batch_stride + s * g.lda;
       if constexpr (AMODE == A_BF16)
@@ -204,7 +210,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   const int m = m0 + row, nn = n0 + col;
   const bool row_in = m < M;
   const bool all_in = row_in && (nn + Q <= N);
-  const int64_t off = (int64_t)m * g.ldc + nn;
+  const int64_t off = (int64_t)((SUB && g.sub_scatter && row_in) ? g.sub_rows[sub_off + m] : m) * g.ldc + nn;
   const bool want_bias = (epi == EPI_BIAS || epi == EPI_FORWARD || epi == EPI_HEAD) && g.bias;
   // Q-wide register vectors (not arrays: an array indexed inside a rolled loop would be moved out
   // of registers)
@@ -409,7 +415,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
       const bool vec_c = all_in && g.C && ((reinterpret_cast<uintptr_t>(g.C + off) & (4 * Q - 1)) == 0);
       const bool vec_c2 = all_in && (epi == EPI_FORWARD) &&
                           ((reinterpret_cast<uintptr_t>(g.C2 + off) & (4 * Q - 1)) == 0);
-      if (epi == EPI_FORWARD) {
+      if (epi == EPI_FORWARD && g.C2) {
         if (vec_c2) {
           fq o2;
 #pragma unroll
@@ -512,6 +518,18 @@ hipError_t launch_nw(const GemmArgs &g, hipStream_t stream) {
     }
   }
   if (lstm) return hipErrorInvalidValue;     // the LSTM epilogues exist in float32 only
+  if constexpr (AMODE == A_F32) {
+    if (g.sub) {
+      if (fast_loads_ok(g, !WKN))
+        PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, true, false, true>), dim3((unsigned)tiles),
+                   dim3(64 * NW), 0, stream, g);
+      else
+        PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, false, false, true>), dim3((unsigned)tiles),
+                   dim3(64 * NW), 0, stream, g);
+      return hipGetLastError();
+    }
+  }
+  if (g.sub) return hipErrorInvalidValue;    // rows chosen on the device: float32 only
   if (fast_loads_ok(g, !WKN))
     PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, true>), dim3((unsigned)tiles),
                        dim3(64 * NW), 0, stream, g);

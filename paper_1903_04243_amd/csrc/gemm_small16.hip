@@ -5,7 +5,8 @@
 // from global memory straight to MFMA registers, partial tiles are summed in a fixed order through
 // LDS -- with 16 x 16 tiles on v_mfma_f32_16x16x4_f32, i.e. four times as many workgroups.
 // float32 operands only; epilogues EPI_NONE, EPI_BIAS, EPI_FORWARD, EPI_MASK and (LSTM
-// instantiation) EPI_LSTM_BWD; no A scaling, no batching.
+// instantiation) EPI_LSTM_BWD; no A scaling, no batching.  Rows chosen on the device (GemmArgs::sub)
+// are supported.
 //
 // Operand layout of the 16 x 16 x 4 MFMA: lane l supplies A[l % 16][l / 16] and B[l / 16][l % 16] and
 // receives D[4 (l / 16) + r][l % 16] in accumulator register r.  A lane loads 16 bytes = four
@@ -22,20 +23,28 @@ using namespace dev;
 
 constexpr int kRing = 4;      // slices in flight per wave
 
-template <bool WKN, int NW, bool LSTM>
+// SUB: the instantiation for rows chosen on the device (GemmArgs::sub), kept apart so that the
+// others carry none of its loads and branches.
+template <bool WKN, int NW, bool LSTM, bool SUB>
 __global__ __launch_bounds__(64 * NW) void gemm_small16_kernel(const GemmArgs g) {
   __shared__ float red[NW][16][17];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, kq = lane >> 4;
-  const int M = g.M, N = g.N, K = g.K;
-  const int tiles_m = (M + 15) / 16;
+  const int N = g.N, K = g.K;
+  const int tiles_m = (g.M + 15) / 16;
   const int m0 = (blockIdx.x % tiles_m) * 16, n0 = (blockIdx.x / tiles_m) * 16;
   const int epi = g.epilogue;
+  // rows chosen on the device: the live row count comes from memory, tiles past it have nothing to do
+  const int M = SUB ? g.sub[0] : g.M;
+  if (SUB && m0 >= M) return;
+  const int sub_off = SUB ? g.sub[1] : 0;
 
   // operand rows of this lane (clamped: what out-of-range rows and columns produce is not stored)
-  const int mc = min(m0 + r16, M - 1), nc = min(n0 + r16, N - 1);
+  int mc = min(m0 + r16, M - 1);
+  if (SUB && g.sub_gather) mc = g.sub_rows[sub_off + mc];
+  const int nc = min(n0 + r16, N - 1);
   const float *a_row = static_cast<const float *>(g.A) + (int64_t)(mc / g.S) * g.a_batch_stride +
                        (int64_t)(mc % g.S) * g.lda;
   const float *W = static_cast<const float *>(g.W);
@@ -130,7 +139,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_small16_kernel(const GemmArgs g)
 #pragma unroll
   for (int w = 0; w < NW; ++w) v += red[w][erow][ecol];
 
-  const int64_t off = (int64_t)em * g.ldc + en;
+  const int64_t off = (int64_t)((SUB && g.sub_scatter) ? g.sub_rows[sub_off + em] : em) * g.ldc + en;
   if constexpr (LSTM) {
     if (epi == EPI_LSTM_BWD) {
       if (en < g.n_split) {
@@ -145,7 +154,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_small16_kernel(const GemmArgs g)
   }
   if (epi == EPI_FORWARD) {
     const float z = v + aux;
-    g.C2[off] = act_deriv(g.act, z);
+    if (g.C2) g.C2[off] = act_deriv(g.act, z);
     if (g.C == nullptr) return;
     v = act_value(g.act, z);
   } else if (epi == EPI_BIAS) {
@@ -159,14 +168,14 @@ __global__ __launch_bounds__(64 * NW) void gemm_small16_kernel(const GemmArgs g)
     g.C[off] = v;
 }
 
-template <bool WKN, bool LSTM>
+template <bool WKN, bool LSTM, bool SUB = false>
 hipError_t launch16(const GemmArgs &g, hipStream_t stream) {
   const int64_t tiles = (int64_t)((g.M + 15) / 16) * ((g.N + 15) / 16);
   // eight waves once each gets at least two slices of 16 k, else four
   if ((g.K + 15) / 16 >= 16)
-    PFG_KERNEL((gemm_small16_kernel<WKN, 8, LSTM>), dim3((unsigned)tiles), dim3(512), 0, stream, g);
+    PFG_KERNEL((gemm_small16_kernel<WKN, 8, LSTM, SUB>), dim3((unsigned)tiles), dim3(512), 0, stream, g);
   else
-    PFG_KERNEL((gemm_small16_kernel<WKN, 4, LSTM>), dim3((unsigned)tiles), dim3(256), 0, stream, g);
+    PFG_KERNEL((gemm_small16_kernel<WKN, 4, LSTM, SUB>), dim3((unsigned)tiles), dim3(256), 0, stream, g);
   return hipGetLastError();
 }
 
@@ -174,6 +183,7 @@ hipError_t launch16(const GemmArgs &g, hipStream_t stream) {
 
 bool small16_applies(const GemmArgs &g) {
   if (g.bf16 || g.a_scale || g.nbatch > 1 || !g.a_is_f32) return false;
+  if (g.sub && g.epilogue == EPI_LSTM_BWD) return false;
   if (g.epilogue != EPI_NONE && g.epilogue != EPI_BIAS && g.epilogue != EPI_FORWARD &&
       g.epilogue != EPI_MASK && g.epilogue != EPI_LSTM_BWD)
     return false;
@@ -186,6 +196,7 @@ hipError_t launch_gemm_small16(const GemmArgs &g, hipStream_t stream) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipSuccess;
   if (g.epilogue == EPI_LSTM_BWD)
     return g.w_kn ? launch16<true, true>(g, stream) : launch16<false, true>(g, stream);
+  if (g.sub) return g.w_kn ? launch16<true, false, true>(g, stream) : launch16<false, false, true>(g, stream);
   return g.w_kn ? launch16<true, false>(g, stream) : launch16<false, false>(g, stream);
 }
 

@@ -2,6 +2,7 @@
 // name under which the kernels being enqueued are timed, and the launch-and-check macro.
 #pragma once
 
+#include "../../include/pfg.h"
 #include "common.h"
 
 namespace pfg {
@@ -14,6 +15,11 @@ void set_timing_family(const char *name);
 
 constexpr int64_t kMaxRows = 0x7fffffffLL;          // folded iteration index m = b * S + s
 constexpr int64_t kMaxElems = (int64_t)1 << 46;     // per tensor
+
+// Checks of a dense network that every entry point shares: sizes, activation, dtype, then the
+// weight pointers.  Both return a pfg_status and record the error text.
+int check_mlp(const pfg_mlp *net);
+int check_mlp_weights(const pfg_mlp *net);
 
 inline float *ws_at(void *ws, size_t off) {
   return reinterpret_cast<float *>(static_cast<char *>(ws) + off);

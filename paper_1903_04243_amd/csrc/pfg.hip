@@ -103,6 +103,15 @@ int check_weights(const pfg_mlp *net) {
   return PFG_OK;
 }
 
+}  // namespace
+
+namespace pfg {
+int check_mlp(const pfg_mlp *net) { return check_net(net); }
+int check_mlp_weights(const pfg_mlp *net) { return check_weights(net); }
+}  // namespace pfg
+
+namespace {
+
 int check_rows(int64_t B, int64_t S) {
   if (B < 1) return fail(PFG_ERR_SHAPE, "B = %lld must be at least 1", (long long)B);
   if (S < 1) return fail(PFG_ERR_SHAPE, "S = %lld must be at least 1", (long long)S);
@@ -360,7 +369,7 @@ int weight_sweep(const pfg_mlp *net, const void *X, int64_t B, int64_t S, float 
 
 extern "C" {
 
-int pfg_version(void) { return 101; }
+int pfg_version(void) { return 102; }
 
 const char *pfg_last_error(void) { return g_err; }
 

@@ -294,11 +294,13 @@ class CondWorkload:
     else_dims: Tuple[int, ...]   # widths after d_T of the else branch (same last width)
     act: str
     n: int
+    c0: float = 0.0              # offset of the condition
 
 
 COND_WORKLOADS: Dict[str, CondWorkload] = {
     w.name: w for w in [
-        CondWorkload("c11_cond_two_branches", 10, (784, 512), (1024, 1024, 10), (10,), "relu", 8192),
+        # the offset puts about half of the rows on each side of the condition
+        CondWorkload("c11_cond_two_branches", 10, (784, 512), (1024, 1024, 10), (10,), "relu", 8192, -0.55),
     ]
 }
 
@@ -315,7 +317,8 @@ class CondInputs:
 
 
 def make_cond_inputs(w: CondWorkload, n: Optional[int] = None, pre=None, then_dims=None, else_dims=None,
-                     bias_scale: float = 0.0, c0: float = 0.0, seed: Optional[int] = None) -> CondInputs:
+                     bias_scale: float = 0.0, c0: Optional[float] = None,
+                     seed: Optional[int] = None) -> CondInputs:
     """Weights N(0, 1 / fan_in), condition vector N(0, 1 / d_T), X standard normal; draw order: shared
     part, then branch, else branch (weights and biases layer by layer), condition vector, X."""
     n = w.n if n is None else n
@@ -327,4 +330,4 @@ def make_cond_inputs(w: CondWorkload, n: Optional[int] = None, pre=None, then_di
             for dims in (pre, (pre[-1],) + then_dims, (pre[-1],) + else_dims)]
     wv = (rng.standard_normal(pre[-1]) / np.sqrt(pre[-1])).astype(np.float32)
     X = rng.standard_normal((n, pre[0])).astype(np.float32)
-    return CondInputs(w, nets[0], nets[1], nets[2], wv, float(c0), X)
+    return CondInputs(w, nets[0], nets[1], nets[2], wv, float(w.c0 if c0 is None else c0), X)

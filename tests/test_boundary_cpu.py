@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert set(names) == set(pfg.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
-    assert lib.pfg_version() == 101
+    assert lib.pfg_version() == 102
 
 
 FAKE = 0x1000  # a non-NULL, 256-aligned value; never dereferenced because validation fails first
@@ -317,6 +317,48 @@ def test_convnet_workspace_and_rejections(lib):
     assert fn(r(net), FAKE, FAKE, 4, o2, o2, o2, o2, None, None, big, None) == pfg.PFG_ERR_WORKSPACE
     assert fn(r(net), FAKE, FAKE, 4, o2, o2, o2, o2, None, FAKE, 1024, None) == pfg.PFG_ERR_WORKSPACE
     assert fn(r(net), FAKE, FAKE, 1 << 20, o2, o2, o2, o2, None, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+
+
+def make_cond(pre=(784, 512), then_dims=(1024, 10), else_dims=(10,), dtype=0, w=FAKE, W_null_at=None):
+    parts = [make_net(pre, dtype=dtype), make_net((pre[-1],) + tuple(then_dims), W_null_at=W_null_at),
+             make_net((pre[-1],) + tuple(else_dims))]
+    net = pfg.pfg_cond(parts[0], w, 0.0, parts[1], parts[2])
+    net._keep = parts
+    return net
+
+
+def test_cond_workspace_and_rejections(lib):
+    net = make_cond()
+    n = 1000
+    b = ctypes.c_size_t(0)
+    assert lib.pfg_cond_workspace_bytes(ctypes.byref(net), n, ctypes.byref(b)) == 0
+    # shared-part output, two hidden buffers of the widest hidden layer, flags, group counts, index
+    # sets, the two {count, offset} descriptors
+    assert b.value == (up(4 * n * 512) + 2 * up(4 * n * 1024) + up(4 * n) + up(4 * ((n + 31) // 32)) +
+                       up(4 * n) + up(16))
+    r = lambda net_: ctypes.byref(net_)
+    assert lib.pfg_cond_workspace_bytes(None, n, ctypes.byref(b)) == pfg.PFG_ERR_NULL
+    assert lib.pfg_cond_workspace_bytes(r(net), n, None) == pfg.PFG_ERR_NULL
+    assert lib.pfg_cond_workspace_bytes(r(net), 0, ctypes.byref(b)) == pfg.PFG_ERR_SHAPE
+    assert lib.pfg_cond_workspace_bytes(r(net), (1 << 24) + 1, ctypes.byref(b)) == pfg.PFG_ERR_OVERFLOW
+    assert lib.pfg_cond_workspace_bytes(r(make_cond(dtype=1)), n, ctypes.byref(b)) == pfg.PFG_ERR_UNSUPPORTED
+    assert lib.pfg_cond_workspace_bytes(r(make_cond(else_dims=(11,))), n, ctypes.byref(b)) == pfg.PFG_ERR_SHAPE
+    assert "same output width" in lib.pfg_last_error().decode()
+    bad = make_cond()
+    bad.then_net = make_net((500, 10))
+    assert lib.pfg_cond_workspace_bytes(r(bad), n, ctypes.byref(b)) == pfg.PFG_ERR_SHAPE
+    assert "outputs of pre" in lib.pfg_last_error().decode()
+    fn = lib.pfg_cond_forward
+    big = 1 << 40
+    assert fn(r(net), None, n, -1, FAKE, None, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r(net), FAKE, n, -1, None, None, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r(make_cond(w=None)), FAKE, n, -1, FAKE, None, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert "cond_w" in lib.pfg_last_error().decode()
+    assert fn(r(make_cond(W_null_at=1)), FAKE, n, -1, FAKE, None, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r(net), FAKE, n, 2, FAKE, None, None, FAKE, big, None) == pfg.PFG_ERR_UNSUPPORTED
+    assert fn(r(net), FAKE, n, -1, FAKE, None, None, None, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(r(net), FAKE, n, -1, FAKE, None, None, FAKE + 16, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(r(net), FAKE, n, -1, FAKE, None, None, FAKE, 4096, None) == pfg.PFG_ERR_WORKSPACE
 
 
 def test_last_error_is_cleared_by_a_good_call(lib):
