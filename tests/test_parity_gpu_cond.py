@@ -175,6 +175,47 @@ def test_cond_skipped_outputs_and_row_order():
     assert np.array_equal(Rs.cpu().numpy(), R[:45]) and ks.tolist() == [int(cond[:45].sum()), 45 - int(cond[:45].sum())]
 
 
+def test_cond_replays_from_a_graph_with_other_data():
+    """The launch sequence does not depend on the data: a call captured once into a HIP graph is
+    replayed on other inputs (other index sets, other set sizes, one replay with an empty set) and
+    must reproduce the eager results bit for bit every time."""
+    wk = wl.CondWorkload("graphq", 760, (20, 48), (96, 7), (7,), "tanh", 900)
+    inp = wl.make_cond_inputs(wk, bias_scale=0.2)
+    net = gpu_net(inp, "tanh")
+    rng = np.random.default_rng(76)
+    batches = [inp.X, rng.standard_normal(inp.X.shape).astype(np.float32),
+               (inp.X + 2.0 * np.sign(inp.w[:1])).astype(np.float32),
+               np.repeat(inp.X[:1], 900, axis=0)]                    # all rows equal: one set is empty
+    eager = []
+    for Xb in batches:
+        R, c, k = pfg.pfg_cond_forward(net, dev(Xb))
+        torch.cuda.synchronize()
+        eager.append((R.clone(), c.clone(), k.clone()))
+    assert len({tuple(e[2].tolist()) for e in eager}) >= 3            # the set sizes really differ
+    assert 0 in eager[3][2].tolist()
+    Xs = dev(batches[0]).clone()
+    out = (torch.empty_like(eager[0][0]), torch.empty_like(eager[0][1]), torch.empty_like(eager[0][2]))
+    ws = torch.empty(pfg.pfg_cond_workspace_bytes(net, 900), dtype=torch.uint8, device="cuda:0")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pfg.pfg_cond_forward(net, Xs, out=out, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pfg.pfg_cond_forward(net, Xs, out=out, workspace=ws)
+    for replay in (0, 1, 2, 3, 1, 0):
+        Xs.copy_(dev(batches[replay]))
+        out[0].fill_(float("nan"))                                    # eager work between the replays
+        pfg.pfg_cond_forward(net, dev(batches[(replay + 1) % 4]))     # an eager call in between
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want, name in zip(out, eager[replay], ("R", "cond", "counts")):
+            assert torch.equal(got, want), f"replay of batch {replay}: {name} differs"
+
+
 def test_c11_cond_full_size():
     wk = wl.COND_WORKLOADS["c11_cond_two_branches"]
     say(f"{wk.name}: full size ({wk.n} rows), sampled rows element by element")
