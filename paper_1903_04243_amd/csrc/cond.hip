@@ -53,23 +53,41 @@ __global__ __launch_bounds__(256) void cond_flags_kernel(const float *T, int64_t
   if (threadIdx.x == 0) cnt[blockIdx.x] = s_cnt;
 }
 
+// blk[b] = sum of the kPlace / kGroup group counts of block b (the rows one placing workgroup takes).
+// Only used for many rows, where every placing workgroup summing all group counts would cost more
+// than this extra launch.
+__global__ __launch_bounds__(256) void cond_block_counts_kernel(const int32_t *cnt, int ngroups, int nblocks,
+                                                                int32_t *blk) {
+  constexpr int kPer = kPlace / kGroup;
+  const int b = blockIdx.x * 256 + threadIdx.x;
+  if (b >= nblocks) return;
+  int s = 0;
+  for (int g = b * kPer; g < min((b + 1) * kPer, ngroups); ++g) s += cnt[g];
+  blk[b] = s;
+}
+
 // Row j with a set flag goes to rows[(set flags before j)], a row with a clear flag to
 // rows[n_then + (clear flags before j)].  A workgroup places kPlace consecutive rows: it sums the
-// group counts in front of its rows (and all of them, for n_then), ranks its own rows with a
-// ballot per wave, and writes.  meta = {n_then, 0, n_else, n_then}: count and offset of each set.
+// counts in front of its rows (and all of them, for n_then) -- group counts, or block counts when
+// blk is given --, ranks its own rows with a ballot per wave, and writes.
+// meta = {n_then, 0, n_else, n_then}: count and offset of each set.
 __global__ __launch_bounds__(kPlace) void cond_place_kernel(const int32_t *flags, const int32_t *cnt,
-                                                            int n, int32_t *rows, int32_t *meta,
-                                                            int32_t *cond_out, int32_t *counts_out) {
+                                                            const int32_t *blk, int n, int32_t *rows,
+                                                            int32_t *meta, int32_t *cond_out,
+                                                            int32_t *counts_out) {
   constexpr int kWaves = kPlace / 64;
   __shared__ int s_before[kWaves], s_total[kWaves], s_wave[kWaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int ngroups = (n + kGroup - 1) / kGroup;
-  const int first_group = blockIdx.x * (kPlace / kGroup);
+  // counts to add up: one per block of kPlace rows, or one per group of kGroup rows
+  const int32_t *c = blk ? blk : cnt;
+  const int per = blk ? kPlace : kGroup;
+  const int ncounts = (n + per - 1) / per;
+  const int first = blockIdx.x * (kPlace / per);          // first count that belongs to this workgroup
   int before = 0, total = 0;
-  for (int g = tid; g < ngroups; g += kPlace) {
-    const int c = cnt[g];
-    total += c;
-    if (g < first_group) before += c;
+  for (int g = tid; g < ncounts; g += kPlace) {
+    const int v = c[g];
+    total += v;
+    if (g < first) before += v;
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
@@ -126,16 +144,24 @@ __global__ void invariant_counts_kernel(int32_t *counts_out, int n, int flag) {
 
 }  // namespace
 
-int64_t cond_count_groups(int64_t n) { return (n + kGroup - 1) / kGroup; }
+// counts kept in `cnt`: one per group of kGroup rows, followed by one per block of kPlace rows
+int64_t cond_count_groups(int64_t n) { return (n + kGroup - 1) / kGroup + (n + kPlace - 1) / kPlace; }
 
 hipError_t launch_cond_partition(const float *T, int64_t ldt, int32_t n, int32_t d, const float *w,
                                  float c0, int32_t *flags, int32_t *cnt, int32_t *rows, int32_t *meta,
                                  int32_t *cond_out, int32_t *counts_out, hipStream_t stream) {
   if (n <= 0) return hipSuccess;
-  PFG_KERNEL(cond_flags_kernel, dim3((unsigned)((n + kGroup - 1) / kGroup)), dim3(256), 0, stream, T, ldt,
-             n, d, w, c0, flags, cnt);
-  PFG_KERNEL(cond_place_kernel, dim3((unsigned)((n + kPlace - 1) / kPlace)), dim3(kPlace), 0, stream, flags,
-             cnt, n, rows, meta, cond_out, counts_out);
+  const int ngroups = (n + kGroup - 1) / kGroup, nblocks = (n + kPlace - 1) / kPlace;
+  PFG_KERNEL(cond_flags_kernel, dim3((unsigned)ngroups), dim3(256), 0, stream, T, ldt, n, d, w, c0, flags, cnt);
+  // beyond 64 Ki rows (2048 group counts) the placing workgroups add up block counts instead
+  int32_t *blk = nullptr;
+  if (n > (1 << 16)) {
+    blk = cnt + ngroups;
+    PFG_KERNEL(cond_block_counts_kernel, dim3((unsigned)((nblocks + 255) / 256)), dim3(256), 0, stream, cnt,
+               ngroups, nblocks, blk);
+  }
+  PFG_KERNEL(cond_place_kernel, dim3((unsigned)nblocks), dim3(kPlace), 0, stream, flags, cnt, blk, n, rows, meta,
+             cond_out, counts_out);
   return hipGetLastError();
 }
 

@@ -332,9 +332,9 @@ def test_cond_workspace_and_rejections(lib):
     n = 1000
     b = ctypes.c_size_t(0)
     assert lib.pfg_cond_workspace_bytes(ctypes.byref(net), n, ctypes.byref(b)) == 0
-    # shared-part output, two hidden buffers of the widest hidden layer, flags, group counts, index
+    # shared-part output, two hidden buffers of the widest hidden layer, flags, group and block counts, index
     # sets, the two {count, offset} descriptors
-    assert b.value == (up(4 * n * 512) + 2 * up(4 * n * 1024) + up(4 * n) + up(4 * ((n + 31) // 32)) +
+    assert b.value == (up(4 * n * 512) + 2 * up(4 * n * 1024) + up(4 * n) + up(4 * ((n + 31) // 32 + (n + 1023) // 1024)) +
                        up(4 * n) + up(16))
     r = lambda net_: ctypes.byref(net_)
     assert lib.pfg_cond_workspace_bytes(None, n, ctypes.byref(b)) == pfg.PFG_ERR_NULL

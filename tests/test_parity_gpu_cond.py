@@ -105,6 +105,7 @@ COND_SHAPES = [
     ((64, 128), (256, 16), (16,), "tanh", 1),                 # a single iteration
     ((24, 512), (512,), (96, 512), "relu", 1100),             # wide enough for the LDS-tiled kernel
     ((12, 16), (8,), (8,), "identity", 1025),
+    ((6, 8), (12, 5), (5,), "tanh", 70001),                   # many rows: block counts in the placing step
 ]
 
 
