@@ -563,7 +563,9 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
   const bool fast = fast_loads_ok(g);
   // (256 x 128 tiles on 8 waves were measured slower than 128 x 128 on 4: 4.82 against 4.46 ms
   // on the 65536 x 2048 x 2048 cotangent product; the wider barrier costs more than the saved loads.
-  // 128 x 128 on 8 waves of 32 x 64 each: 75 % of the MFMA peak against 79.5 %.)
+  // 128 x 128 on 8 waves of 32 x 64 each: 75 % of the MFMA peak against 79.5 %.  128 x 64 tiles in
+  // place of 64 x 64: within 6 % either way on plain products, and a third slower where the long
+  // reverse-cell epilogue follows.)
   // a 128-wide tile on an output of 64 columns or fewer would be half empty
   if constexpr (AMODE == A_F32 && WKN) {
     if (g.sub) {
