@@ -499,9 +499,13 @@ hipError_t launch_nw(const GemmArgs &g, hipStream_t stream) {
   int64_t tiles = (int64_t)((g.M + 31) / 32) * ((g.N + 31) / 32);
   if (g.epilogue == EPI_LSTM_FWD) tiles = (int64_t)((g.M + 31) / 32) * ((g.lstm_H + 7) / 8);
   if (g.epilogue == EPI_HEAD && g.head_gprev) {
-    // share the fused cotangent step of each row tile out over up to 8 workgroups
+    // share the fused cotangent step of each row tile out over several workgroups of at least 64
+    // columns each: up to 8, or more while the launch stays within one workgroup per compute unit
+    // (a workgroup walks its rows one after the other, so fewer columns mean more row bands)
+    const int row_tiles = (g.M + 31) / 32;
+    const int cap = 256 / row_tiles > 8 ? 256 / row_tiles : 8;
     int groups = g.K / 64;
-    groups = groups < 1 ? 1 : (groups > 8 ? 8 : groups);
+    groups = groups < 1 ? 1 : (groups > cap ? cap : groups);
     tiles *= groups;
   }
   // the element-wise column loads of the [K, N] layout put no condition on W
