@@ -449,6 +449,103 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
       return;
     }
   }
+  // Results leave through LDS: in the accumulator layout a lane holds one column of 16 rows, so
+  // direct stores are 4 bytes per lane, which HBM takes at a fraction of the rate of 16-byte stores
+  // (a product with a short contraction is all epilogue: the 25088 x 800 x 64 cotangent product of
+  // the conv net took 71 us for 80 MB, 46 us this way).  The tile is laid out row-major in the
+  // staging buffers, free after the last stage; each thread then finishes four consecutive columns
+  // of a row (bias, activation or mask on 16-byte operands) and stores them at once.  Needs rows
+  // of C (C2, the mask) that start 16-byte aligned; anything else takes the direct path below.
+  constexpr int TSV = BN + 4;      // row stride in floats: 16-byte aligned rows
+  if constexpr (BM * TSV * 4 <= 2 * STAGE) {
+    auto aligned16 = [](const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) == 0; };
+    const bool plain = (epi == EPI_NONE || epi == EPI_BIAS || epi == EPI_FORWARD || epi == EPI_MASK);
+    const bool rows_ok = g.ldc % 4 == 0 && aligned16(gC) && (epi != EPI_FORWARD || aligned16(g.C2)) &&
+                         (epi != EPI_MASK || (g.ld_emask % 4 == 0 && aligned16(g.emask)));
+    if (plain && rows_ok) {
+      float *tile = reinterpret_cast<float *>(smem);
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            tile[(wm + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3)) * TSV + wn + j * 32 + l32] =
+                acc[i][j][r];
+      __syncthreads();
+      const bool add_bias = (epi == EPI_BIAS || epi == EPI_FORWARD) && g.bias;
+      for (int e = tid; e < BM * (BN / 4); e += kThreads) {
+        const int row = e / (BN / 4), col = (e % (BN / 4)) * 4;
+        const int m = m0 + row, n = n0 + col;
+        if (m >= M || n >= N) continue;
+        const int64_t orow = (SUB && g.sub_scatter) ? g.sub_rows[sub_off + m] : m;
+        const int64_t o = orow * g.ldc + n;
+        const bool whole = n + 4 <= N;
+        f32x4 v = *reinterpret_cast<const f32x4 *>(tile + row * TSV + col);
+        if (add_bias) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int nq = min(n + q, N - 1);
+            v[q] += g.bf16 ? (float)static_cast<const __bf16 *>(g.bias)[nq]
+                           : static_cast<const float *>(g.bias)[nq];
+          }
+        }
+        if (epi == EPI_MASK) {
+          const float *mrow = g.emask + (int64_t)(m / g.S) * g.ld_emask + n;
+          if (whole) {
+            v *= *reinterpret_cast<const f32x4 *>(mrow);
+          } else {
+            for (int q = 0; n + q < N; ++q) v[q] *= mrow[q];
+          }
+        }
+        if (epi == EPI_FORWARD) {
+          f32x4 d;
+#pragma unroll 1
+          for (int q = 0; q < 4; ++q) {            // rolled: the activation code is long
+            const float z = v[q];
+            d[q] = act_deriv(g.act, z);
+            v[q] = act_value(g.act, z);
+          }
+          if (g.C2) {
+            if (whole) {
+              *reinterpret_cast<f32x4 *>(g.C2 + o) = d;
+            } else {
+              for (int q = 0; n + q < N; ++q) g.C2[o + q] = d[q];
+            }
+          }
+          if (gC == nullptr) continue;       // only phi'(z) is wanted
+        }
+        float *dst = gC + o;
+        if (whole) {
+          if (g.streaming)
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(dst));
+          else
+            *reinterpret_cast<f32x4 *>(dst) = v;
+        } else {
+          for (int q = 0; n + q < N; ++q) dst[q] = v[q];
+        }
+      }
+      if constexpr (AMODE == A_F32 && BM == BN) {
+        if (mirror) {
+          // C[block + n, i] = C[block + i, n]: the same tile written transposed (all tiles are full
+          // in this mode); consecutive threads take consecutive rows of a tile column, which are
+          // consecutive addresses of the mirror image
+          const int block0 = (m0 / g.sym_n) * g.sym_n, i0 = m0 - block0;
+          for (int e = tid; e < BM * BN; e += kThreads) {
+            const int col = e / BM, row = e % BM;
+            const float v = tile[row * TSV + col];
+            float *dst = gC + (int64_t)(block0 + n0 + col) * g.ldc + i0 + row;
+            if (g.streaming)
+              __builtin_nontemporal_store(v, dst);
+            else
+              *dst = v;
+          }
+        }
+      }
+      return;
+    }
+  }
   float bias[TN];
   bool n_ok[TN];
 #pragma unroll
