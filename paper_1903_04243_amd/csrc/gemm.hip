@@ -418,7 +418,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
       // The reverse cell update is long; running it from the unrolled register loop below would
       // replicate it 16 TM TN times.  The tile goes through LDS (free after the last stage) and a
       // rolled loop finishes it, consecutive threads on consecutive columns.
-      constexpr int TS = BN + 1;
+      // Four consecutive columns per thread on 16-byte operands when every row involved starts
+      // 16-byte aligned (the usual case); element by element otherwise.
+      constexpr int TS = BN + 4;
       static_assert(BM * TS * 4 <= 2 * STAGE, "the output tile must fit the staging buffers");
       float *tile = reinterpret_cast<float *>(smem);
       __syncthreads();
@@ -431,6 +433,29 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
             tile[(wm + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3)) * TS + wn + j * 32 + l32] =
                 acc[i][j][r];
       __syncthreads();
+      auto aligned16 = [](const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) == 0; };
+      const bool vec = g.n_split % 4 == 0 && g.lstm_H % 4 == 0 && g.ldc % 4 == 0 && g.lstm_dz_ld % 4 == 0 &&
+                       aligned16(gC) && aligned16(g.lstm_gates) && aligned16(g.lstm_cs) &&
+                       aligned16(g.lstm_dc) && aligned16(g.lstm_dz);
+      if (vec) {
+        for (int e = tid; e < BM * (BN / 4); e += kThreads) {
+          const int row = e / (BN / 4), col = (e % (BN / 4)) * 4;
+          const int m = m0 + row, n = n0 + col;
+          if (m >= M || n >= N) continue;            // N is a multiple of 4 here: whole groups only
+          const f32x4 v = *reinterpret_cast<const f32x4 *>(tile + row * TS + col);
+          if (n < g.n_split) {
+            f32x4 *dst = reinterpret_cast<f32x4 *>(gC + (int64_t)m * g.ldc + n);
+            if (g.streaming)
+              __builtin_nontemporal_store(v, dst);
+            else
+              *dst = v;
+          } else {
+            lstm_reverse_cell4(g.lstm_gates, g.lstm_cs, g.lstm_dc, g.lstm_dz, g.lstm_dz_ld, g.lstm_H,
+                               g.lstm_T, g.lstm_step, g.S, m, n - g.n_split, v);
+          }
+        }
+        return;
+      }
       for (int e = tid; e < BM * BN; e += kThreads) {
         const int row = e / BN, col = e % BN;
         const int m = m0 + row, n = n0 + col;

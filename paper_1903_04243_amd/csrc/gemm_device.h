@@ -77,6 +77,33 @@ __device__ __forceinline__ void lstm_reverse_cell(const float *gates, const floa
   *dcp = dct * f;
 }
 
+// The same update for four consecutive hidden units k .. k + 3 on 16-byte operands (all row starts
+// and k must be 16-byte aligned: H, dz_ld multiples of 4).
+__device__ __forceinline__ void lstm_reverse_cell4(const float *gates, const float *cs, float *dc,
+                                                   float *dz, int64_t dz_ld, int H, int T, int t,
+                                                   int S, int m, int k, f32x4 dh) {
+  const int64_t b = m / S;
+  const float *grow = gates + (b * T + t) * 4 * (int64_t)H + k;
+  const f32x4 i = *reinterpret_cast<const f32x4 *>(grow);
+  const f32x4 g = *reinterpret_cast<const f32x4 *>(grow + H);
+  const f32x4 f = *reinterpret_cast<const f32x4 *>(grow + 2 * H);
+  const f32x4 o = *reinterpret_cast<const f32x4 *>(grow + 3 * H);
+  const f32x4 c = *reinterpret_cast<const f32x4 *>(cs + (b * T + t) * (int64_t)H + k);
+  f32x4 cprev = {0.f, 0.f, 0.f, 0.f};
+  if (t > 0) cprev = *reinterpret_cast<const f32x4 *>(cs + (b * T + t - 1) * (int64_t)H + k);
+  f32x4 *dcp = reinterpret_cast<f32x4 *>(dc + (int64_t)m * H + k);
+  f32x4 tc;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) tc[q] = tanhf(c[q]);
+  const f32x4 dct = *dcp + dh * o * (1.f - tc * tc);
+  float *out = dz + (int64_t)m * dz_ld + k;
+  *reinterpret_cast<f32x4 *>(out) = dct * g * i * (1.f - i);
+  *reinterpret_cast<f32x4 *>(out + H) = dct * i * (1.f - g * g);
+  *reinterpret_cast<f32x4 *>(out + 2 * H) = dct * cprev * f * (1.f - f);
+  *reinterpret_cast<f32x4 *>(out + 3 * H) = dh * tc * o * (1.f - o);
+  *dcp = dct * f;
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
   bf16x2 v = {(__bf16)lo, (__bf16)hi};
