@@ -81,6 +81,65 @@ __global__ __launch_bounds__(kThreads) void im2col_kernel(const float *in, int h
   }
 }
 
+// The position-fastest layout PT [B, k k c, h w] for images with several channels.  Reading the image
+// position by position for one channel touches one value per 4 c bytes; instead a workgroup takes
+// one filter tap of one example and a run of kPosRun positions, reads their c channels (contiguous
+// in the image) into LDS and writes them out transposed, c rows of kPosRun consecutive positions.
+constexpr int kPosRun = 64;
+constexpr int kMaxTiledC = 128;      // LDS: kPosRun x (c + 1) floats
+
+__global__ __launch_bounds__(kThreads) void im2col_pt_tiled_kernel(const float *in, int h, int w, int c, int k,
+                                                                   float *out) {
+  __shared__ float tile[kPosRun * (kMaxTiledC + 1)];
+  const int p = (k - 1) / 2, hw = h * w, kkc = k * k * c;
+  const int tap = blockIdx.x, pos0 = blockIdx.y * kPosRun;
+  const int64_t b = blockIdx.z;
+  const int ky = tap / k, kx = tap - ky * k;
+  const int npos = min(kPosRun, hw - pos0);
+  const float *img = in + b * (int64_t)hw * c;
+  const int ts = c + 1;
+  const bool vec = c % 4 == 0 && hw % 4 == 0 &&
+                   ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+  if (vec) {
+    // 16 bytes of channels per load, 16 bytes of positions per store
+    const int c4 = c / 4;
+    for (int idx = threadIdx.x; idx < npos * c4; idx += kThreads) {
+      const int pl = idx / c4, ch = (idx - pl * c4) * 4;
+      const int pos = pos0 + pl;
+      const int y = pos / w, x = pos - y * w;
+      const int yy = y + ky - p, xx = x + kx - p;
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (yy >= 0 && yy < h && xx >= 0 && xx < w) v = *reinterpret_cast<const f32x4 *>(img + (yy * w + xx) * c + ch);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) tile[pl * ts + ch + q] = v[q];
+    }
+    __syncthreads();
+    float *obase = out + (b * kkc + (int64_t)tap * c) * hw + pos0;
+    for (int idx = threadIdx.x; idx < c * (kPosRun / 4); idx += kThreads) {
+      const int ch = idx / (kPosRun / 4), pl = (idx - ch * (kPosRun / 4)) * 4;
+      if (pl >= npos) continue;                    // npos is a multiple of 4 here
+      f32x4 v;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) v[q] = tile[(pl + q) * ts + ch];
+      *reinterpret_cast<f32x4 *>(obase + (int64_t)ch * hw + pl) = v;
+    }
+    return;
+  }
+  for (int idx = threadIdx.x; idx < npos * c; idx += kThreads) {
+    const int pl = idx / c, ch = idx - pl * c;
+    const int pos = pos0 + pl;
+    const int y = pos / w, x = pos - y * w;
+    const int yy = y + ky - p, xx = x + kx - p;
+    tile[pl * ts + ch] = (yy >= 0 && yy < h && xx >= 0 && xx < w) ? img[(yy * w + xx) * c + ch] : 0.f;
+  }
+  __syncthreads();
+  float *obase = out + (b * kkc + (int64_t)tap * c) * hw + pos0;
+  for (int idx = threadIdx.x; idx < c * kPosRun; idx += kThreads) {
+    const int ch = idx / kPosRun, pl = idx - ch * kPosRun;
+    if (pl < npos) obase[(int64_t)ch * hw + pl] = tile[pl * ts + ch];
+  }
+}
+
 // a = relu(z); pooled = max of each 2 x 2 window, which = position of the first maximum in the
 // order (0,0), (0,1), (1,0), (1,1).  One thread per pooled cell, channel fastest.
 __global__ __launch_bounds__(kThreads) void relu_pool_kernel(const float *z, int64_t B, int h, int w, int c,
@@ -88,6 +147,37 @@ __global__ __launch_bounds__(kThreads) void relu_pool_kernel(const float *z, int
   const int ho = h / 2, wo = w / 2;
   const int64_t total = B * ho * wo * c;
   const int64_t step = (int64_t)gridDim.x * kThreads;
+  if (c % 4 == 0 && ((reinterpret_cast<uintptr_t>(z) | reinterpret_cast<uintptr_t>(pooled)) & 15) == 0 &&
+      (reinterpret_cast<uintptr_t>(which) & 3) == 0) {
+    // four channels per thread: 16-byte loads and stores, the four window indices as one word
+    const int c4 = c / 4;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total / 4; i += step) {
+      const int ch = (int)(i % c4) * 4;
+      int64_t r = i / c4;
+      const int xo = (int)(r % wo);
+      r /= wo;
+      const int yo = (int)(r % ho);
+      const int64_t b = r / ho;
+      f32x4 best = {-1.f, -1.f, -1.f, -1.f};
+      uint32_t arg = 0;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(
+            z + ((b * h + 2 * yo + (d >> 1)) * w + 2 * xo + (d & 1)) * c + ch);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float a = v[q] > 0.f ? v[q] : 0.f;
+          if (a > best[q]) {
+            best[q] = a;
+            arg = (arg & ~(0xffu << (8 * q))) | ((uint32_t)d << (8 * q));
+          }
+        }
+      }
+      *reinterpret_cast<f32x4 *>(pooled + 4 * i) = best;
+      *reinterpret_cast<uint32_t *>(which + 4 * i) = arg;
+    }
+    return;
+  }
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += step) {
     const int ch = (int)(i % c);
     int64_t r = i / c;
@@ -117,6 +207,31 @@ __global__ __launch_bounds__(kThreads) void unpool_mask_kernel(const float *dpoo
   const int ho = h / 2, wo = w / 2;
   const int64_t total = B * ho * wo * c;
   const int64_t step = (int64_t)gridDim.x * kThreads;
+  if (c % 4 == 0 && (reinterpret_cast<uintptr_t>(which) & 3) == 0 &&
+      ((reinterpret_cast<uintptr_t>(dpooled) | reinterpret_cast<uintptr_t>(pooled) |
+        reinterpret_cast<uintptr_t>(dz)) & 15) == 0) {
+    const int c4 = c / 4;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total / 4; i += step) {
+      const int ch = (int)(i % c4) * 4;
+      int64_t r = i / c4;
+      const int xo = (int)(r % wo);
+      r /= wo;
+      const int yo = (int)(r % ho);
+      const int64_t b = r / ho;
+      const f32x4 p = *reinterpret_cast<const f32x4 *>(pooled + 4 * i);
+      const f32x4 dp = *reinterpret_cast<const f32x4 *>(dpooled + 4 * i);
+      const uint32_t arg = *reinterpret_cast<const uint32_t *>(which + 4 * i);
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        f32x4 out;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          out[q] = (((arg >> (8 * q)) & 0xffu) == (uint32_t)d && p[q] > 0.f) ? dp[q] : 0.f;
+        *reinterpret_cast<f32x4 *>(dz + ((b * h + 2 * yo + (d >> 1)) * w + 2 * xo + (d & 1)) * c + ch) = out;
+      }
+    }
+    return;
+  }
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += step) {
     const int ch = (int)(i % c);
     int64_t r = i / c;
@@ -139,6 +254,30 @@ __global__ __launch_bounds__(kThreads) void col2im_kernel(const float *dP, int64
   const int p = (k - 1) / 2, kkc = k * k * c;
   const int64_t total = B * h * w * c;
   const int64_t step = (int64_t)gridDim.x * kThreads;
+  if (c % 4 == 0 && ((reinterpret_cast<uintptr_t>(dP) | reinterpret_cast<uintptr_t>(din)) & 15) == 0) {
+    // four channels per thread, the same taps in the same order
+    const int c4 = c / 4;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total / 4; i += step) {
+      const int ch = (int)(i % c4) * 4;
+      int64_t r = i / c4;
+      const int xx = (int)(r % w);
+      r /= w;
+      const int yy = (int)(r % h);
+      const int64_t b = r / h;
+      f32x4 s = {0.f, 0.f, 0.f, 0.f};
+      for (int ky = 0; ky < k; ++ky) {
+        const int y = yy - ky + p;
+        if (y < 0 || y >= h) continue;
+        for (int kx = 0; kx < k; ++kx) {
+          const int x = xx - kx + p;
+          if (x < 0 || x >= w) continue;
+          s += *reinterpret_cast<const f32x4 *>(dP + ((b * h + y) * w + x) * (int64_t)kkc + (ky * k + kx) * c + ch);
+        }
+      }
+      *reinterpret_cast<f32x4 *>(din + 4 * i) = s;
+    }
+    return;
+  }
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += step) {
     const int ch = (int)(i % c);
     int64_t r = i / c;
@@ -170,9 +309,15 @@ hipError_t launch_im2col(const float *in, int64_t B, int32_t h, int32_t w, int32
   if (P)
     PFG_KERNEL(im2col_kernel<true>, dim3((unsigned)((hw + kRows - 1) / kRows), (unsigned)B), dim3(kThreads),
                0, stream, in, h, w, c, k, P);
-  if (PT)
-    PFG_KERNEL(im2col_kernel<false>, dim3((unsigned)((kkc + kRows - 1) / kRows), (unsigned)B),
-               dim3(kThreads), 0, stream, in, h, w, c, k, PT);
+  if (PT) {
+    const int64_t runs = (hw + kPosRun - 1) / kPosRun;
+    if (c >= 8 && c <= kMaxTiledC && runs <= 65535)
+      PFG_KERNEL(im2col_pt_tiled_kernel, dim3((unsigned)(k * k), (unsigned)runs, (unsigned)B), dim3(kThreads), 0,
+                 stream, in, h, w, c, k, PT);
+    else
+      PFG_KERNEL(im2col_kernel<false>, dim3((unsigned)((kkc + kRows - 1) / kRows), (unsigned)B),
+                 dim3(kThreads), 0, stream, in, h, w, c, k, PT);
+  }
   return hipGetLastError();
 }
 
