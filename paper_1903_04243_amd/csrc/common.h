@@ -113,6 +113,11 @@ struct GemmArgs {
   float *lstm_hs_w;             // hidden state, same addressing (the product's A operand is read elsewhere)
   int64_t lstm_state_ld, lstm_state_ts;   // [M, T, H] history: T * H and H; state updated in place: H and 0
   int32_t lstm_has_prev;        // 0: c_{step-1} is zero and is not read
+  // a_km == 1: the A operand is stored transposed, [K, M] row-major with row stride lda (row k holds
+  // A[0 .. M, k]); a product can then contract over the ROWS of a matrix it also uses row by row
+  // elsewhere.  LDS-tiled kernel only; float32, no scale, S == 1, EPI_NONE, M a multiple of 4 and
+  // 16-byte aligned rows (see akm_supported).
+  int32_t a_km;
   // Rows chosen on the device (the index sets of a conditional, Section 3.6).  When `sub` is set the
   // product runs on rows m < sub[0] only (sub[0] <= M; M still sizes the grid).  With sub_gather, row
   // m of the A operand is row sub_rows[sub[1] + m] of A; with sub_scatter, row m of the result is
@@ -125,6 +130,9 @@ struct GemmArgs {
 
 // Picks the LDS-tiled kernel or the small-problem kernel.
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream);
+// May this product (with a_km set) be launched?  Alignment, sizes, and enough tiles for the
+// LDS-tiled kernel, the only one that reads a transposed A.
+bool akm_supported(const GemmArgs &g);
 hipError_t launch_gemm_skinny(const GemmArgs &g, hipStream_t stream);
 // 16 x 16 tiles for the smallest float32 products (used by launch_gemm_skinny when it applies)
 bool small16_applies(const GemmArgs &g);

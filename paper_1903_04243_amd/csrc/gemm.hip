@@ -27,8 +27,11 @@ using namespace dev;
 // SUB: the instantiation for rows chosen on the device (GemmArgs::sub; float32, W in [K, N] layout),
 // kept apart so that the others carry none of its loads and branches (inside the unrolled epilogue
 // they cost a store-bound product a quarter of its speed).
-template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2, bool SUB = false>
+// AKM: the instantiation that reads A stored as [K, M] (float32, FAST loads only).
+template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2, bool SUB = false,
+          bool AKM = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) {
+  static_assert(!AKM || (AMODE == A_F32 && FAST && !SUB), "transposed A: float32, FAST loads, no row subsets");
   constexpr int kThreads = 64 * WGM * WGN;
   constexpr bool BF16 = (AMODE != A_F32);
   constexpr int ELEM = BF16 ? 2 : 4;
@@ -124,9 +127,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   const float *a_srow[A_CHUNKS];
   int a_lds[A_CHUNKS];
   int a_k[A_CHUNKS];
+  int a_m[A_CHUNKS];             // AKM: first row m of the chunk (global)
 #pragma unroll
   for (int c = 0; c < A_CHUNKS; ++c) {
     const int id = tid + kThreads * c;
+    if constexpr (AKM) {
+      // A is [K, M]: a chunk is 16 bytes along m at one k and is scattered into the [m][k] LDS
+      // layout element by element (as for float32 weights in [K, N] layout)
+      const int kl = id % BK, mg = id / BK;
+      a_k[c] = kl;
+      a_m[c] = m0 + mg * EPC;
+      a_lds[c] = (mg * EPC) * STRIDE + kl * ELEM;
+      a_row[c] = nullptr;
+      a_srow[c] = nullptr;
+      continue;
+    }
+    a_m[c] = 0;
     const int row = id / CPR, kc = id % CPR;
     const int m = m0 + row;
     a_lds[c] = row * STRIDE + kc * 16;
@@ -193,7 +209,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   // sc: does the A operand carry a scale (passed as a literal where the caller has branched on
   // it once, so that no per-chunk select remains)
   auto fetch_a_chunk = [&](int c, int kt, bool sc) {
-    ra[c] = fetch_a<AMODE, FAST>(a_row[c], a_srow[c], sc, kt * BK + a_k[c], K, a_vec_ok, s_vec_ok);
+    if constexpr (AKM) {
+      // 16 bytes along m of row k; both indices clamped (zeroed in stash if out of range)
+      const int k = kt * BK + a_k[c];
+      ra[c].v = load4_f32_fast(static_cast<const float *>(gA) + (int64_t)min(k, K - 1) * g.lda, a_m[c], M);
+    } else {
+      ra[c] = fetch_a<AMODE, FAST>(a_row[c], a_srow[c], sc, kt * BK + a_k[c], K, a_vec_ok, s_vec_ok);
+    }
   };
   auto fetch_w_chunk = [&](int c, int kt) {
     const int kbase = kt * BK;
@@ -232,8 +254,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   // here, not when issued).
   auto stash_a_chunk = [&](int c, int buf, int kt, bool sc) {
     unsigned char *sA = smem + buf * STAGE;
-    *reinterpret_cast<u32x4 *>(sA + a_lds[c]) =
-        finish_a<AMODE>(ra[c], sc, FAST && (kt * BK + a_k[c] >= K));
+    if constexpr (AKM) {
+      const bool past = (kt * BK + a_k[c] >= K) || (a_m[c] >= M);
+      const u32x4 v = past ? u32x4{0u, 0u, 0u, 0u} : __builtin_bit_cast(u32x4, ra[c].v);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) *reinterpret_cast<uint32_t *>(sA + a_lds[c] + e * STRIDE) = v[e];
+    } else {
+      *reinterpret_cast<u32x4 *>(sA + a_lds[c]) =
+          finish_a<AMODE>(ra[c], sc, FAST && (kt * BK + a_k[c] >= K));
+    }
   };
   auto stash_w_chunk = [&](int c, int buf, int kt) {
     unsigned char *sW = smem + buf * STAGE + BM * STRIDE;
@@ -647,14 +676,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   }
 }
 
-template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2, bool SUB = false>
+template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2, bool SUB = false,
+          bool AKM = false>
 hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
   constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
   constexpr int kThreads = 64 * WGM * WGN;
   constexpr bool WTR = WKN && (AMODE != A_F32);
   constexpr int BK = BKB / (AMODE != A_F32 ? 2 : 4);
   constexpr int smem = 2 * (BM * (BKB + 16) + (WTR ? BK * (BN * 2 + 16) : BN * (BKB + 16)));
-  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB, FAST, WGM, WGN, SUB>;
+  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB, FAST, WGM, WGN, SUB, AKM>;
   static bool attr_set = false;   // benign race: the attribute is idempotent
   if (!attr_set && smem > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -699,6 +729,15 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
     }
   }
   if (g.sub) return hipErrorInvalidValue;     // rows chosen on the device: float32 forward products only
+  if constexpr (AMODE == A_F32 && WKN) {
+    if (g.a_km) {
+      // 64 x 64 tiles only (the 128 x 128 arrangement runs out of registers with the scattered
+      // staging of both operands)
+      if (!fast) return hipErrorInvalidValue;
+      return launch_one<AMODE, WKN, 1, 1, 128, true, 2, 2, false, true>(g, stream);
+    }
+  }
+  if (g.a_km) return hipErrorInvalidValue;    // transposed A: float32 with W in [K, N] layout only
   if (big >= 512 && g.N > 64)
     return fast ? launch_one<AMODE, WKN, 2, 2, 128, true>(g, stream)
                 : launch_one<AMODE, WKN, 2, 2, 128, false>(g, stream);
@@ -713,6 +752,19 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
 
 }  // namespace
 
+bool akm_supported(const GemmArgs &g) {
+  if (!g.a_km) return true;
+  auto aligned = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  if (g.bf16 || !g.a_is_f32 || !g.w_kn || g.a_scale || g.S != 1 || g.sub || g.sym_n > 0 ||
+      g.epilogue != EPI_NONE)
+    return false;
+  if (g.K < 4 || g.K % 4 || g.M < 4 || g.M % 4 || g.lda % 4 || !aligned(g.A) || (g.nbatch > 1 && g.batch_A % 4)) return false;
+  // the W side of the FAST loads
+  if (!aligned(g.W) || g.ldw % 4 || g.N % 4 || g.N < 4 || (g.nbatch > 1 && g.batch_W % 4)) return false;
+  const int64_t tiles64 = (int64_t)(g.nbatch > 1 ? g.nbatch : 1) * ((g.M + 63) / 64) * ((g.N + 63) / 64);
+  return tiles64 >= 128;
+}
+
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipSuccess;
   if (g.sym_n > 0 && (g.epilogue != EPI_NONE || g.bf16 || g.N != g.sym_n || g.M % g.sym_n || g.sym_n % 128))
@@ -726,6 +778,10 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
                 ((g.sub_gather || g.sub_scatter) && !g.sub_rows)))
     return hipErrorInvalidValue;
   if (!g.sub && (g.sub_gather || g.sub_scatter)) return hipErrorInvalidValue;
+  if (g.a_km) {
+    if (!akm_supported(g)) return hipErrorInvalidValue;
+    return launch_tiles<A_F32, true>(g, stream);
+  }
   // Fewer than 128 tiles of 64 x 64 cannot occupy the chip: such products (M = B rows, or a
   // narrow output) go to the kernel that splits the contraction over the waves of a workgroup.
   const int64_t tiles64 = (int64_t)(g.nbatch > 1 ? g.nbatch : 1) * ((g.M + 63) / 64) * ((g.N + 63) / 64);

@@ -775,6 +775,34 @@ int pfg_convnet_per_example_grads(const pfg_convnet *net, const void *X, const i
   const int L = dn->num_layers, nc = net->num_conv;
   const int32_t *d = dn->dims;
 
+  // The per-example filter gradient of block i: both operands stacked (Section 3.4), for each
+  // example [k k c_in, h w] x [h w, c_out].  Its A operand is the example's patch matrix with the
+  // POSITION as the contraction index.  The product reads the position-major patches P as a
+  // transposed operand when it can (transposed = true); otherwise it needs the second copy PT with
+  // the position index fastest, which the forward pass then has to write.
+  auto filter_product = [&](int i, bool transposed) {
+    const ConvBlock &blk = cp.blocks[i];
+    const int hw = blk.h * blk.w, kkc = blk.k * blk.k * blk.ci;
+    GemmArgs g{};
+    if (transposed) {
+      g.A = at(ws, blk.P); g.a_km = 1; g.lda = kkc; g.S = 1;
+    } else {
+      g.A = at(ws, blk.PT); g.lda = hw; g.a_batch_stride = 0; g.S = kkc;
+    }
+    g.a_is_f32 = 1;
+    g.W = at(ws, blk.dz); g.ldw = blk.co; g.w_kn = 1;
+    g.M = kkc; g.N = blk.co; g.K = hw;
+    g.epilogue = EPI_NONE;
+    g.C = dWc_out[i]; g.ldc = blk.co; g.streaming = 1;
+    g.nbatch = (int32_t)B;
+    g.batch_A = (int64_t)kkc * hw; g.batch_W = (int64_t)hw * blk.co; g.batch_C = (int64_t)kkc * blk.co;
+    return g;
+  };
+  auto filter_reads_P = [&](int i) {
+    const GemmArgs g = filter_product(i, true);
+    return g.K % 4 == 0 && akm_supported(g);
+  };
+
   // ---- conv blocks, forward: patches, one product over the rows (b, y, x), relu + pooling ----
   const float *in = static_cast<const float *>(X);
   for (int i = 0; i < nc; ++i) {
@@ -783,7 +811,7 @@ int pfg_convnet_per_example_grads(const pfg_convnet *net, const void *X, const i
     const int kkc = blk.k * blk.k * blk.ci;
     const bool want_filter = dWc_out && dWc_out[i];
     PFG_LAUNCH("im2col", launch_im2col(in, B, blk.h, blk.w, blk.ci, blk.k, at(ws, blk.P),
-                                       want_filter ? at(ws, blk.PT) : nullptr, stream));
+                                       (want_filter && !filter_reads_P(i)) ? at(ws, blk.PT) : nullptr, stream));
     GemmArgs g{};
     g.A = at(ws, blk.P); g.lda = kkc; g.a_batch_stride = kkc; g.S = 1; g.a_is_f32 = 1;
     g.W = net->Wc[i]; g.ldw = blk.co; g.w_kn = 1;
@@ -851,18 +879,8 @@ int pfg_convnet_per_example_grads(const pfg_convnet *net, const void *X, const i
                                                  B, blk.h, blk.w, blk.co, dz, stream));
     if (dbc_out && dbc_out[i])
       PFG_LAUNCH("sum_positions", launch_sum_steps(dz, B, hw, blk.co, dbc_out[i], at(ws, cp.psum), stream));
-    if (dWc_out && dWc_out[i]) {
-      // both operands stacked (Section 3.4): for each example [k k c_in, h w] x [h w, c_out]
-      GemmArgs g{};
-      g.A = at(ws, blk.PT); g.lda = hw; g.a_batch_stride = 0; g.S = kkc; g.a_is_f32 = 1;
-      g.W = dz; g.ldw = blk.co; g.w_kn = 1;
-      g.M = kkc; g.N = blk.co; g.K = hw;
-      g.epilogue = EPI_NONE;
-      g.C = dWc_out[i]; g.ldc = blk.co; g.streaming = 1;
-      g.nbatch = (int32_t)B;
-      g.batch_A = (int64_t)kkc * hw; g.batch_W = (int64_t)hw * blk.co; g.batch_C = (int64_t)kkc * blk.co;
-      PFG_LAUNCH("conv_gemm_filter", launch_gemm(g, stream));
-    }
+    if (dWc_out && dWc_out[i])
+      PFG_LAUNCH("conv_gemm_filter", launch_gemm(filter_product(i, filter_reads_P(i)), stream));
     bool lower = false;
     for (int j = 0; j < i; ++j) lower = lower || (dWc_out && dWc_out[j]) || (dbc_out && dbc_out[j]);
     if (!lower) break;
