@@ -39,6 +39,8 @@ def main():
                     help="run a plain elementwise copy of known size (scale for HBM counters)")
     ap.add_argument("--workload", default=None,
                     help="measure only this workload and print its record (for profiling runs)")
+    ap.add_argument("--batch", type=int, default=None,
+                    help="with --workload: the same workload at another batch size (rows for the conditional)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this library has no multi-GPU path (parallel-for "
@@ -58,6 +60,14 @@ def main():
         pfg_build.build()
     pfg.load_library()
     dev = "cuda:0"
+
+    def pick(table, name):
+        """The named workload, at the batch size of --batch if that was given."""
+        import dataclasses
+        w = table[name]
+        if args.batch is None or not args.workload:
+            return w
+        return dataclasses.replace(w, **{"n" if hasattr(w, "n") else "B": args.batch})
     torch.cuda.set_device(0)
 
     def upload(w):
@@ -204,7 +214,7 @@ def main():
             gbs = per_launch_bytes / (per_launch_ms * 1e-3) / 1e9
             return {"kernel": fam, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                    "traffic": measured_traffic(w.name) if fam == "outer_product" else None,
+                    "traffic": measured_traffic(w.name) if (fam == "outer_product" and args.batch is None) else None,
                     "bytes_per_launch": per_launch_bytes, "ms_per_launch": per_launch_ms,
                     "launches_per_step": k["launches_per_step"]}
         flops = sum(v["flops"] for v in alg.values())
@@ -218,7 +228,7 @@ def main():
                 "launches_per_step": launches}
 
     def measure(name, steps, warmup):
-        w = wl.WORKLOADS[name]
+        w = pick(wl.WORKLOADS, name)
         log(f"[bench] {name}: uploading inputs")
         inp, net, X, labels = upload(w)
         step = make_step(w, net, X, labels)
@@ -284,7 +294,7 @@ def main():
         return rec, inp
 
     def measure_varlen(name, steps, warmup):
-        w = wl.LSTM_WORKLOADS[name]
+        w = pick(wl.LSTM_WORKLOADS, name)
         log(f"[bench] {name}: uploading inputs")
         inp, lengths = wl.make_varlen_inputs(w)
         net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, 1)
@@ -324,7 +334,7 @@ def main():
         return rec, inp
 
     def measure_conv(name, steps, warmup):
-        w = wl.CONV_WORKLOADS[name]
+        w = pick(wl.CONV_WORKLOADS, name)
         log(f"[bench] {name}: uploading inputs")
         inp = wl.make_conv_inputs(w)
         net = pfg.ConvNet.from_numpy(w.height, w.width, w.channels, inp.Wc, inp.bc, inp.Ws, inp.bs)
@@ -385,7 +395,7 @@ def main():
         return rec, inp
 
     def measure_cond(name, steps, warmup):
-        w = wl.COND_WORKLOADS[name]
+        w = pick(wl.COND_WORKLOADS, name)
         log(f"[bench] {name}: uploading inputs")
         inp = wl.make_cond_inputs(w)
         net = pfg.Cond.from_numpy(inp.pre, inp.w, inp.c0, inp.then_net, inp.else_net, w.act)
@@ -436,7 +446,7 @@ def main():
             return measure_conv(name, steps, warmup)
         if name in wl.COND_WORKLOADS:
             return measure_cond(name, steps, warmup)
-        w = wl.LSTM_WORKLOADS[name]
+        w = pick(wl.LSTM_WORKLOADS, name)
         if w.call == "lstm_varlen_forward":
             return measure_varlen(name, steps, warmup)
         log(f"[bench] {name}: uploading inputs")

@@ -203,13 +203,21 @@ hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, int nt, int64_t
 hipError_t launch_outer(const OuterArgs *jobs, int n, hipStream_t stream) {
   // Workgroup size and store kind, from sweeps of this kernel on MI355X (HBM absorbs plain
   // hipMemset fills at 6.1 to 6.4 TB/s, so that is the practical ceiling).  Many small independent
-  // workgroups do best: 8 KiB each (two stores per lane) for outputs of a few hundred MB, where
-  // non-temporal stores were 0 to 10 % faster than ordinary ones; 16 KiB each and ordinary stores
-  // for outputs of many GB (6.2 TB/s against 5.8 TB/s non-temporal; 8 KiB: 5.7, 32 KiB: 6.1).
-  // One store per lane is too little: the index prologue then dominates.
+  // workgroups do best: 8 KiB each (two stores per lane) with non-temporal stores.  That holds from
+  // a few hundred MB (0 to 10 % faster than ordinary stores) to several GB as long as a workgroup
+  // covers whole rows (784-512-512-10 at batch 512, 1.4 GB: 6.7 TB/s against 5.7 with 16 KiB and
+  // ordinary stores; at batch 2048, 5.5 GB: 6.3 against 5.6), and it leaves the caches to the
+  // kernels that follow (the conv net's step is 5 % shorter although its writer is not).  Only
+  // many GB of rows wider than a workgroup (4096 columns: a workgroup then writes separate 4 KiB
+  // pieces) do better with 16 KiB each and ordinary stores (6.2 TB/s against 5.7 non-temporal;
+  // 8 KiB: 5.7, 32 KiB: 6.1).  One store per lane is too little: the index prologue then dominates.
   double total_bytes = 0.0;
-  for (int i = 0; i < n; ++i) total_bytes += 4.0 * (double)jobs[i].M * jobs[i].d_in * jobs[i].d_out;
-  const bool huge = total_bytes > 1024.0 * 1024.0 * 1024.0;
+  bool wide = false;
+  for (int i = 0; i < n; ++i) {
+    total_bytes += 4.0 * (double)jobs[i].M * jobs[i].d_in * jobs[i].d_out;
+    wide = wide || (jobs[i].d_out / 4 > kThreads);
+  }
+  const bool huge = wide && total_bytes > 1024.0 * 1024.0 * 1024.0;
   const int nt = huge ? 0 : 1;
   const int64_t target = huge ? 16384 : 8192;
   for (int i = 0; i < n; ++i) {
