@@ -27,7 +27,6 @@ __device__ __forceinline__ float load_a(const void *a, int a_bf16, int64_t idx) 
 struct OuterJob {
   OuterArgs o;
   int32_t vec;              // 1: 16-byte stores (d_out % 4 == 0, out 16-byte aligned); 0: scalar
-  int32_t nt;               // 1: non-temporal stores
   int32_t V;                // vec: d_out / 4 vector columns
   int32_t slabs;            // vec: column slabs of up to THREADS vectors
   int32_t chunks;           // row chunks (vec) or flat element chunks (scalar) per iteration m
@@ -55,8 +54,11 @@ __device__ __forceinline__ void outer_vec4(const OuterJob &jb, uint32_t x, int64
   const int V = jb.V;
   uint32_t chunk = x, slab = 0;
   if (jb.slabs > 1) {
-    chunk = x % (uint32_t)jb.chunks;
-    slab = x / (uint32_t)jb.chunks;
+    // consecutive workgroups take consecutive slabs of the same rows, so that the launch as a
+    // whole writes memory in address order (rows walked first put neighbouring workgroups a power
+    // of two apart: 65 % instead of 80 % of the HBM peak on 4096-wide rows)
+    slab = x % (uint32_t)jb.slabs;
+    chunk = x / (uint32_t)jb.slabs;
   }
 
   int vc, r0, rstep;
@@ -85,16 +87,9 @@ __device__ __forceinline__ void outer_vec4(const OuterJob &jb, uint32_t x, int64
   const int i_end = min(i_begin + jb.per_chunk, o.d_in);
   f32x4 *obase = reinterpret_cast<f32x4 *>(o.out + m * (int64_t)o.d_in * o.d_out) + vc;
 
-  if (jb.nt) {
-    for (int i = i_begin + r0; i < i_end; i += rstep) {
-      const float av = load_a(o.a, o.a_bf16, abase + i);
-      __builtin_nontemporal_store(gv * av, obase + (int64_t)i * V);
-    }
-  } else {
-    for (int i = i_begin + r0; i < i_end; i += rstep) {
-      const float av = load_a(o.a, o.a_bf16, abase + i);
-      obase[(int64_t)i * V] = gv * av;
-    }
+  for (int i = i_begin + r0; i < i_end; i += rstep) {
+    const float av = load_a(o.a, o.a_bf16, abase + i);
+    __builtin_nontemporal_store(gv * av, obase + (int64_t)i * V);
   }
 }
 
@@ -164,8 +159,7 @@ int64_t plan_job(const OuterArgs &o, OuterJob &jb, int64_t target) {
 }
 
 // One launch per group of jobs with the same iteration count (normally all of them).
-hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, int nt, int64_t target,
-                        hipStream_t stream) {
+hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, int64_t target, hipStream_t stream) {
   int at = 0;
   while (at < n) {
     OuterBatch batch{};
@@ -181,7 +175,6 @@ hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, int nt, int64_t
         --at;                                                    // start a new launch with it
         break;
       }
-      jb.nt = nt;
       jb.x_begin = (uint32_t)xs;
       xs += nx;
       ++batch.n;
@@ -201,32 +194,21 @@ hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, int nt, int64_t
 }  // namespace
 
 hipError_t launch_outer(const OuterArgs *jobs, int n, hipStream_t stream) {
-  // Workgroup size and store kind, from sweeps of this kernel on MI355X (HBM absorbs plain
-  // hipMemset fills at 6.1 to 6.4 TB/s, so that is the practical ceiling).  Many small independent
-  // workgroups do best: 8 KiB each (two stores per lane) with non-temporal stores.  That holds from
-  // a few hundred MB (0 to 10 % faster than ordinary stores) to several GB as long as a workgroup
-  // covers whole rows (784-512-512-10 at batch 512, 1.4 GB: 6.7 TB/s against 5.7 with 16 KiB and
-  // ordinary stores; at batch 2048, 5.5 GB: 6.3 against 5.6), and it leaves the caches to the
-  // kernels that follow (the conv net's step is 5 % shorter although its writer is not).  Only
-  // many GB of rows wider than a workgroup (4096 columns: a workgroup then writes separate 4 KiB
-  // pieces) do better with 16 KiB each and ordinary stores (6.2 TB/s against 5.7 non-temporal;
-  // 8 KiB: 5.7, 32 KiB: 6.1).  One store per lane is too little: the index prologue then dominates.
-  double total_bytes = 0.0;
-  bool wide = false;
-  for (int i = 0; i < n; ++i) {
-    total_bytes += 4.0 * (double)jobs[i].M * jobs[i].d_in * jobs[i].d_out;
-    wide = wide || (jobs[i].d_out / 4 > kThreads);
-  }
-  const bool huge = wide && total_bytes > 1024.0 * 1024.0 * 1024.0;
-  const int nt = huge ? 0 : 1;
-  const int64_t target = huge ? 16384 : 8192;
+  // Workgroup size and store kind, from sweeps of this kernel on MI355X (a purely sequential fill
+  // with 16-byte stores reaches 6.0 to 6.7 TB/s there, hipMemset 6.0 to 6.5).  Many small
+  // independent workgroups do best: 8 KiB each (two stores per lane), non-temporal stores, for
+  // every shape and size tried (85 MB to 34 GB; rows of 1 KiB to 16 KiB).  Non-temporal stores
+  // also leave the caches to the kernels that follow (the conv net's step is 5 % shorter although
+  // its writer is not).  16 KiB per workgroup: 5 to 15 % slower; 4 KiB (one store per lane): the
+  // index prologue dominates.
+  const int64_t target = 8192;
   for (int i = 0; i < n; ++i) {
     if (jobs[i].M <= 0) continue;
     if ((int64_t)jobs[i].d_in * jobs[i].d_out > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     bool seen = false;
     for (int k = 0; k < i; ++k) seen = seen || (jobs[k].M == jobs[i].M);
     if (seen) continue;
-    hipError_t e = launch_class(jobs, n, jobs[i].M, nt, target, stream);
+    hipError_t e = launch_class(jobs, n, jobs[i].M, target, stream);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
