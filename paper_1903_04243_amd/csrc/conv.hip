@@ -81,6 +81,38 @@ __global__ __launch_bounds__(kThreads) void im2col_kernel(const float *in, int h
   }
 }
 
+// P [B h w, k k c] as one flat array when a patch row is not a whole number of 16-byte pieces (a
+// single-channel image: rows of k k values): consecutive threads take consecutive groups of four
+// values, whichever rows they fall in, so the stores stay 16 bytes wide and contiguous.
+__global__ __launch_bounds__(kThreads) void im2col_flat_kernel(const float *in, int64_t B, int h, int w, int c,
+                                                               int k, float *out) {
+  const int p = (k - 1) / 2, hw = h * w, kkc = k * k * c;
+  const int64_t total = B * hw * (int64_t)kkc;
+  const int64_t step = (int64_t)gridDim.x * kThreads * 4;
+  for (int64_t e0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4; e0 < total; e0 += step) {
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int64_t e = e0 + q;
+      if (e >= total) break;
+      const int64_t row = e / kkc;
+      const int t = (int)(e - row * kkc);
+      const int kyx = t / c, ch = t - kyx * c;
+      const int ky = kyx / k, kx = kyx - ky * k;
+      const int64_t b = row / hw;
+      const int pos = (int)(row - b * hw);
+      const int y = pos / w, x = pos - y * w;
+      const int yy = y + ky - p, xx = x + kx - p;
+      if (yy >= 0 && yy < h && xx >= 0 && xx < w) v[q] = in[(b * hw + yy * w + xx) * c + ch];
+    }
+    if (e0 + 4 <= total) {
+      *reinterpret_cast<f32x4 *>(out + e0) = v;
+    } else {
+      for (int q = 0; e0 + q < total; ++q) out[e0 + q] = v[q];
+    }
+  }
+}
+
 // The position-fastest layout PT [B, k k c, h w] for images with several channels.  Reading the image
 // position by position for one channel touches one value per 4 c bytes; instead a workgroup takes
 // one filter tap of one example and a run of kPosRun positions, reads their c channels (contiguous
@@ -306,9 +338,14 @@ hipError_t launch_im2col(const float *in, int64_t B, int32_t h, int32_t w, int32
   const int64_t hw = (int64_t)h * w, kkc = (int64_t)k * k * c;
   if (B <= 0 || hw <= 0 || kkc <= 0) return hipSuccess;
   if (B > 65535) return hipErrorInvalidValue;
-  if (P)
-    PFG_KERNEL(im2col_kernel<true>, dim3((unsigned)((hw + kRows - 1) / kRows), (unsigned)B), dim3(kThreads),
-               0, stream, in, h, w, c, k, P);
+  if (P) {
+    if (c % 4 != 0 && (reinterpret_cast<uintptr_t>(P) & 15) == 0)
+      PFG_KERNEL(im2col_flat_kernel, dim3(capped_blocks((B * hw * kkc + 3) / 4)), dim3(kThreads), 0, stream, in,
+                 B, h, w, c, k, P);
+    else
+      PFG_KERNEL(im2col_kernel<true>, dim3((unsigned)((hw + kRows - 1) / kRows), (unsigned)B), dim3(kThreads),
+                 0, stream, in, h, w, c, k, P);
+  }
   if (PT) {
     const int64_t runs = (hw + kPosRun - 1) / kPosRun;
     if (c >= 8 && c <= kMaxTiledC && runs <= 65535)
