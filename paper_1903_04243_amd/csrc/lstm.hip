@@ -249,7 +249,7 @@ hipError_t launch_sum_steps(const float *g, int64_t B, int32_t T, int32_t d, flo
   while (cols > 16 && cols / 2 >= d) cols /= 2;
   const unsigned groups = (unsigned)((d + cols - 1) / cols);
   // many rows and few workgroups: sum kSumPieces pieces of the rows separately first
-  const int pieces = (scratch && T >= 256 && B * groups < 2048) ? kSumPieces : 1;
+  const int pieces = (scratch && T >= 128 && B * groups < 2048) ? kSumPieces : 1;
   for (int64_t b0 = 0; b0 < B; b0 += 32768) {
     const int64_t nb = B - b0 < 32768 ? B - b0 : 32768;
     float *first_out = pieces > 1 ? scratch : out + b0 * d;

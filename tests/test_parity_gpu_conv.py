@@ -108,6 +108,7 @@ CONV_SHAPES = [
     (16, 16, 1, ((5, 8), (5, 16), (3, 8)), (10,), 4),    # three blocks
     (20, 12, 2, ((7, 5),), (33, 7), 70),                 # a 7 x 7 filter; enough rows for the tiled kernels
     (8, 12, 4, ((3, 12), (3, 8)), (11, 6), 140),         # filter gradients read the patches transposed
+    (8, 8, 8, ((3, 64),), (9,), 70),                     # the same with a wide filter bank
 ]
 
 
