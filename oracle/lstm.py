@@ -109,6 +109,18 @@ def per_example_grads(net: Lstm, X, labels, want_dW: bool = True):
     return dW, db, dWout, dbout, ls
 
 
+def per_example_grad_norms(net: Lstm, X, labels):
+    """(sq [B, 4] = squared norms of dW, db, dWout, dbout; norm [B]; loss [B])."""
+    X = _f64(X)
+    B = X.shape[0]
+    assert X.shape == (B, net.T, net.dx)
+    labels = _labels(net, labels, B)
+    sq, norm, ls = np.empty((B, 4)), np.empty(B), np.empty(B)
+    _load().lstmo_per_example_grad_norms(ctypes.byref(net.c), _dp(X), labels.ctypes.data_as(_c_int32_p),
+                                         ctypes.c_int64(B), _dp(sq), _dp(norm), _dp(ls))
+    return sq, norm, ls
+
+
 def body_per_example_grads(net: Lstm, x, label: int):
     dW = np.empty((net.dx + net.H, 4 * net.H))
     db = np.empty(4 * net.H)

@@ -243,6 +243,35 @@ void lstmo_per_example_grads(const lstmo_net *net, const double *X, const int32_
 
 /* Section 5.1: one iteration of the Jacobian parfor is the gradient of one scalar of the output,
  * here <seed_row, y>, with respect to the whole input sequence; J_row is [T, dx]. */
+/* Norms of one example's gradient (the statistic per-example clipping needs, Section 5.3): the
+ * gradient itself is formed by the body above and its squares are summed, tensor by tensor:
+ *   sq[0] = |dW|^2, sq[1] = |db|^2, sq[2] = |dWout|^2, sq[3] = |dbout|^2,  norm = sqrt(sum). */
+void lstmo_body_grad_norm(const lstmo_net *net, const double *x, int label, double *sq, double *norm,
+                          double *loss) {
+  const size_t G = 4 * (size_t)net->H;
+  const size_t nW = (size_t)(net->dx + net->H) * G, nWo = (size_t)net->H * net->dy;
+  double *dW = (double *)malloc(sizeof(double) * nW), *db = (double *)malloc(sizeof(double) * G);
+  double *dWout = (double *)malloc(sizeof(double) * nWo), *dbout = (double *)malloc(sizeof(double) * net->dy);
+  lstmo_body_per_example_grads(net, x, label, dW, db, dWout, dbout, loss);
+  double s[4] = {0.0, 0.0, 0.0, 0.0};
+  for (size_t e = 0; e < nW; ++e) s[0] += dW[e] * dW[e];
+  for (size_t e = 0; e < G; ++e) s[1] += db[e] * db[e];
+  for (size_t e = 0; e < nWo; ++e) s[2] += dWout[e] * dWout[e];
+  for (int e = 0; e < net->dy; ++e) s[3] += dbout[e] * dbout[e];
+  if (sq) for (int k = 0; k < 4; ++k) sq[k] = s[k];
+  if (norm) *norm = sqrt(s[0] + s[1] + s[2] + s[3]);
+  free(dW); free(db); free(dWout); free(dbout);
+}
+
+void lstmo_per_example_grad_norms(const lstmo_net *net, const double *X, const int32_t *labels, int64_t B,
+                                  double *sq, double *norm, double *loss) {
+  const size_t nx = (size_t)net->T * net->dx;
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < B; ++i)
+    lstmo_body_grad_norm(net, X + (size_t)i * nx, labels[i], sq ? sq + 4 * i : NULL, norm ? norm + i : NULL,
+                         loss ? loss + i : NULL);
+}
+
 void lstmo_body_jacobian_input_row(const lstmo_net *net, const double *x, const double *seed_row,
                                    double *J_row) {
   tape_t tp = tape_alloc(net);

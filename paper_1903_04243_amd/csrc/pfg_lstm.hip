@@ -351,27 +351,19 @@ int pfg_lstm_workspace_bytes(const pfg_lstm *net, int op, int64_t B, int64_t S, 
   return PFG_OK;
 }
 
-int pfg_lstm_per_example_grads(const pfg_lstm *net, const void *X, const int32_t *labels, int64_t B,
-                               float *dW_out, float *db_out, float *dWout_out, float *dbout_out,
-                               float *loss_out, void *workspace, size_t workspace_bytes,
-                               void *hip_stream) {
-  clear_error();
-  int rc = check_lstm(net);
+}  // extern "C"
+
+namespace {
+
+// Forward pass, readout and loss head (d ell / d y into gy), and -- if with_steps -- the reverse
+// sweep that leaves dz_t of every step in the workspace (row b of step t at dz + b * T * 4H + t * 4H).
+int lstm_forward_and_reverse(const pfg_lstm *net, const void *X, const int32_t *labels, int64_t B, float *gy,
+                             float *loss_out, bool with_steps, void *ws, const LstmPlan &p,
+                             hipStream_t stream) {
+  const int32_t H = net->state_size, T = net->steps, dy = net->output_size;
+  int rc = lstm_forward(net, X, B, ws, p, stream);
   if (rc) return rc;
-  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
-  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
-  if ((rc = check_lstm_rows(net, B, 1, true))) return rc;
-  const LstmPlan p = make_lstm_plan(net, PFG_LSTM_OP_PER_EXAMPLE_GRADS, B, 1);
-  if ((rc = check_ws(p, workspace, workspace_bytes))) return rc;
-
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const int32_t dx = net->input_size, H = net->state_size, T = net->steps, dy = net->output_size;
-  void *ws = workspace;
-  if ((rc = lstm_forward(net, X, B, ws, p, stream))) return rc;
-
-  // readout and loss head on the last state; d ell / d y lands in the caller's dbout when given
   const float *hT = ws_at(ws, p.hs) + (int64_t)(T - 1) * H;
-  float *gy = dbout_out ? dbout_out : ws_at(ws, p.dy);
   {
     GemmArgs g{};
     g.A = hT; g.lda = (int64_t)T * H; g.a_batch_stride = (int64_t)T * H; g.S = 1; g.a_is_f32 = 1;
@@ -387,13 +379,7 @@ int pfg_lstm_per_example_grads(const pfg_lstm *net, const void *X, const int32_t
       PFG_LAUNCH("head", launch_head_softmax_ce(ws_at(ws, p.y), labels, B, dy, gy, loss_out, stream));
     }
   }
-  if (dWout_out) {
-    OuterArgs o{};
-    o.a = hT; o.lda = (int64_t)T * H; o.a_bf16 = 0; o.g = gy; o.ldg = dy; o.out = dWout_out;
-    o.M = B; o.S = 1; o.d_in = H; o.d_out = dy;
-    PFG_LAUNCH("outer_product", launch_outer(&o, 1, stream));
-  }
-  if (!dW_out && !db_out) return PFG_OK;
+  if (!with_steps) return PFG_OK;
 
   // dh_T = (d ell / d y) W_out^T, then back through the steps; dz of every step is kept
   float *dh = ws_at(ws, p.dh), *dc = ws_at(ws, p.dc), *dz = ws_at(ws, p.dz);
@@ -413,6 +399,43 @@ int pfg_lstm_per_example_grads(const pfg_lstm *net, const void *X, const int32_t
     if ((rc = reverse_step(net, t, dz + (int64_t)t * 4 * H, ld_dz, B, 1, nullptr,
                            dz + (int64_t)(t - 1) * 4 * H, ld_dz, dc, ws, p, stream)))
       return rc;
+  return PFG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pfg_lstm_per_example_grads(const pfg_lstm *net, const void *X, const int32_t *labels, int64_t B,
+                               float *dW_out, float *db_out, float *dWout_out, float *dbout_out,
+                               float *loss_out, void *workspace, size_t workspace_bytes,
+                               void *hip_stream) {
+  clear_error();
+  int rc = check_lstm(net);
+  if (rc) return rc;
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
+  if ((rc = check_lstm_rows(net, B, 1, true))) return rc;
+  const LstmPlan p = make_lstm_plan(net, PFG_LSTM_OP_PER_EXAMPLE_GRADS, B, 1);
+  if ((rc = check_ws(p, workspace, workspace_bytes))) return rc;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int32_t dx = net->input_size, H = net->state_size, T = net->steps, dy = net->output_size;
+  void *ws = workspace;
+  // d ell / d y lands in the caller's dbout when given
+  float *gy = dbout_out ? dbout_out : ws_at(ws, p.dy);
+  if ((rc = lstm_forward_and_reverse(net, X, labels, B, gy, loss_out, dW_out || db_out, ws, p, stream)))
+    return rc;
+  const float *hT = ws_at(ws, p.hs) + (int64_t)(T - 1) * H;
+  if (dWout_out) {
+    OuterArgs o{};
+    o.a = hT; o.lda = (int64_t)T * H; o.a_bf16 = 0; o.g = gy; o.ldg = dy; o.out = dWout_out;
+    o.M = B; o.S = 1; o.d_in = H; o.d_out = dy;
+    PFG_LAUNCH("outer_product", launch_outer(&o, 1, stream));
+  }
+  if (!dW_out && !db_out) return PFG_OK;
+  float *dz = ws_at(ws, p.dz);
+  const int64_t ld_dz = (int64_t)T * 4 * H;
   if (dW_out) {
     // Both operands are stacked and the weights are shared by the steps: per example a product
     // with the step index as contraction.  Rows of x: all T steps of x_t^T dz_t.  Rows of h: steps

@@ -128,6 +128,49 @@ def test_per_example_grads_against_autograd_through_the_library_cell():
         assert loss[b] == pytest.approx(float(ell.detach()), rel=1e-12)
 
 
+def test_grad_norms_against_autograd_and_the_gram_identity():
+    """The norm of an example's gradient, (a) from autograd through the library cell, tensor by
+    tensor, and (b) without any gradient tensor: the weight gradient is sum_t u_t^T dz_t, so its
+    squared norm is sum_{t,t'} (u_t . u_t') (dz_t . dz_t'), with u_t = [x_t, h_{t-1}] from the library
+    cell and dz_t recovered from autograd's gradient with respect to the step's pre-activations."""
+    rng = np.random.default_rng(64)
+    net = rand_lstm(rng, 3, 5, 4, 6)
+    B = 4
+    X = rng.standard_normal((B, 6, 3))
+    labels = rng.integers(0, 4, size=B)
+    sq, norm, loss = lstm.per_example_grad_norms(net, X, labels)
+    for b in range(B):
+        cell, Wout, bout, cols = torch_cell(net, requires_grad=True)
+        y, hs, _ = torch_run(net, cell, Wout, bout, torch.from_numpy(X[b]))
+        ell = -torch.log_softmax(y, dim=0)[int(labels[b])]
+        g_ih, g_hh, g_b, g_Wout, g_bout = torch.autograd.grad(
+            ell, [cell.weight_ih, cell.weight_hh, cell.bias_ih, Wout, bout])
+        want = [float((g_ih ** 2).sum() + (g_hh ** 2).sum()), float((g_b ** 2).sum()),
+                float((g_Wout ** 2).sum()), float((g_bout ** 2).sum())]
+        np.testing.assert_allclose(sq[b], want, rtol=1e-10)
+        assert norm[b] == pytest.approx(math.sqrt(sum(want)), rel=1e-12)
+        assert loss[b] == pytest.approx(float(ell.detach()), rel=1e-12)
+        # (b) the Gram form: dz_t as the gradient with respect to a zero offset added to step t's
+        # pre-activations (an extra bias used at that step only)
+        cell2, Wout2, bout2, _ = torch_cell(net)
+        offs = [torch.zeros(4 * net.H, dtype=torch.float64, requires_grad=True) for _ in range(net.T)]
+        h = torch.zeros(net.H, dtype=torch.float64)
+        c = torch.zeros(net.H, dtype=torch.float64)
+        us = []
+        xb = torch.from_numpy(X[b])
+        for t in range(net.T):
+            us.append(torch.cat([xb[t], h]).detach().numpy())
+            z = cell2.weight_ih @ xb[t] + cell2.weight_hh @ h + cell2.bias_ih + offs[t]
+            i, f, g, o = z.split(net.H)                    # torch's gate order
+            c = torch.sigmoid(f) * c + torch.sigmoid(i) * torch.tanh(g)
+            h = torch.sigmoid(o) * torch.tanh(c)
+        ell2 = -torch.log_softmax(h @ Wout2 + bout2, dim=0)[int(labels[b])]
+        dzs = [d.numpy() for d in torch.autograd.grad(ell2, offs)]
+        gram = sum(float(us[t] @ us[u]) * float(dzs[t] @ dzs[u]) for t in range(net.T) for u in range(net.T))
+        assert sq[b, 0] == pytest.approx(gram, rel=1e-10)
+        assert sq[b, 1] == pytest.approx(float(np.sum(np.sum(dzs, axis=0) ** 2)), rel=1e-10)
+
+
 def test_per_example_grads_by_central_finite_differences():
     rng = np.random.default_rng(64)
     net = rand_lstm(rng, 3, 4, 3, 5)

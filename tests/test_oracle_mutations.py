@@ -72,6 +72,14 @@ MUTANTS = [
 LSTM_SRC = os.path.join(ROOT, "oracle", "lstm_oracle.c")
 
 LSTM_MUTANTS = [
+    ("norm_cross_term", "for (size_t e = 0; e < nW; ++e) s[0] += dW[e] * dW[e];",
+     "for (size_t e = 0; e < nW; ++e) s[0] += dW[e] * dW[(e + 1) % nW];"),
+    ("norm_bias_block_dropped", "if (norm) *norm = sqrt(s[0] + s[1] + s[2] + s[3]);",
+     "if (norm) *norm = sqrt(s[0] + s[2] + s[3]);"),
+    ("norm_blocks_swapped", "for (size_t e = 0; e < nWo; ++e) s[2] += dWout[e] * dWout[e];",
+     "for (size_t e = 0; e < nWo; ++e) s[3] += dWout[e] * dWout[e];"),
+    ("norm_stacking", "sq ? sq + 4 * i : NULL, norm ? norm + i : NULL,",
+     "sq ? sq + 4 * (B - 1 - i) : NULL, norm ? norm + i : NULL,"),
     ("gate_order_g_and_f", "g = tanh(z[H + k]), f = sigmoid(z[2 * H + k]),",
      "g = tanh(z[2 * H + k]), f = sigmoid(z[H + k]),"),
     ("forget_gate_dropped", "const double c = f * (cprev ? cprev[k] : 0.0) + i * g;",
