@@ -463,6 +463,11 @@ def main():
                              dtype=torch.uint8, device=dev)
             step = lambda: pfg.pfg_lstm_per_example_grads(net, X, labels, out=outs, workspace=ws)
             values = sum(t.numel() for t in outs)
+        elif w.call == "lstm_per_example_grad_norms":
+            outs = (torch.empty((B, 4), **f32), torch.empty((B,), **f32), torch.empty((B,), **f32))
+            ws = torch.empty(pfg.pfg_lstm_workspace_bytes(net, "grad_norms", B), dtype=torch.uint8, device=dev)
+            step = lambda: pfg.pfg_lstm_per_example_grad_norms(net, X, labels, out=outs, workspace=ws)
+            values = 6 * B
         else:
             J = torch.empty((B, S, T, dx), **f32)
             ws = torch.empty(pfg.pfg_lstm_workspace_bytes(net, "jacobian_input", B, S),
@@ -490,6 +495,16 @@ def main():
                     "frac": gbs / HBM_PEAK_GBS, "traffic": None,
                     "bytes_per_launch": nbytes / kt[fam]["launches_per_step"], "ms_per_launch": per_ms,
                     "launches_per_step": kt[fam]["launches_per_step"]}
+        elif w.call == "lstm_per_example_grad_norms":
+            # no large output: the step is the sequential sweep; priced like the dense norm workloads
+            # by the bytes the Gram kernel reads (x, h and dz of every step, once)
+            fam = "lstm_grad_sqnorms"
+            nbytes = 4 * B * T * (dx + H + 4 * H)
+            gbs = nbytes / kt[fam]["ms_per_step"] / 1e6
+            roof = {"kernel": fam, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": gbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": nbytes,
+                    "ms_per_launch": kt[fam]["ms_per_step"], "launches_per_step": kt[fam]["launches_per_step"],
+                    "note": "latency-bound chain of steps; the Gram kernel is a small part of it"}
         else:
             rows = B * S
             # one product per step: [dx_t | dh_{t-1}] = dz_t [W_x ; W_h]^T (no dh for the first step)
@@ -513,6 +528,8 @@ def main():
                "roofline": roof}
         if w.call == "lstm_per_example_grads":
             rec["per_example_grads_per_sec"] = B / sec
+        elif w.call == "lstm_per_example_grad_norms":
+            rec["per_example_grad_norms_per_sec"] = B / sec
         else:
             rec["jacobian_rows_per_sec"] = B * S / sec
             rec["jacobian_entries_per_sec"] = values / sec
@@ -567,6 +584,7 @@ def main():
                             ("c4_gelu_bf16_grad_norms", max(3, args.steps // 4)),
                             ("c6_tanh_hessian", max(3, args.steps // 20)),
                             ("c7_lstm_grads", max(3, args.steps // 2)),
+                            ("c7_lstm_grad_norms", max(3, args.steps // 2)),
                             ("c8_lstm_jacobian", max(3, args.steps // 10)),
                             ("c9_lstm_varlen", max(3, args.steps // 10)),
                             ("c10_mnist_convnet_grads", max(3, args.steps // 10)),

@@ -184,7 +184,11 @@ typedef struct {
   int32_t dtype;        /* PFG_F32                                          */
 } pfg_lstm;
 
-typedef enum { PFG_LSTM_OP_PER_EXAMPLE_GRADS = 0, PFG_LSTM_OP_JACOBIAN_INPUT = 1 } pfg_lstm_op;
+typedef enum {
+  PFG_LSTM_OP_PER_EXAMPLE_GRADS = 0,
+  PFG_LSTM_OP_JACOBIAN_INPUT = 1,
+  PFG_LSTM_OP_GRAD_NORMS = 2
+} pfg_lstm_op;
 
 /* Workspace bytes of an LSTM op (S is ignored by PFG_LSTM_OP_PER_EXAMPLE_GRADS); a multiple of
  * 256, never 0. */
@@ -204,6 +208,20 @@ int pfg_lstm_per_example_grads(const pfg_lstm *net, const void *X, const int32_t
                                float *dW_out, float *db_out, float *dWout_out, float *dbout_out,
                                float *loss_out, void *workspace, size_t workspace_bytes,
                                void *hip_stream);
+
+/* Norms of the per-example gradients above without writing the gradients out (as
+ * pfg_per_example_grad_norms does for the dense network).  The weight gradient is a sum over the
+ * steps of outer products, dW[b] = sum_t u_t[b]^T dz_t[b], so its squared Frobenius norm is
+ *      |dW[b]|^2 = sum_{t, t'} (u_t[b] . u_t'[b]) (dz_t[b] . dz_t'[b])
+ * -- two steps x steps Gram matrices per example instead of an [input_size + state_size,
+ * 4 state_size] matrix --, and likewise |db[b]|^2 = sum_{t, t'} dz_t[b] . dz_t'[b].
+ *      sq_out[b, 0..3] = |dW[b]|^2, |db[b]|^2, |dWout[b]|^2, |dbout[b]|^2
+ *      norm_out[b]     = sqrt of their sum
+ * steps is limited to 64.  sq_out [B, 4] or NULL; norm_out [B] or NULL (at least one of the two);
+ * loss_out [B] or NULL. */
+int pfg_lstm_per_example_grad_norms(const pfg_lstm *net, const void *X, const int32_t *labels, int64_t B,
+                                    float *sq_out, float *norm_out, float *loss_out, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream);
 
 /* Input Jacobian (Section 5.1 nested in the loop over examples, Section 3.7):
  *      J_out[b, s, t, i] = d <seed row s of example b, y_b> / d x_b[t, i]     [B, S, steps, input_size]

@@ -27,6 +27,7 @@ OP = {"per_example_grads": 0, "jacobian_input": 1, "jacobian_weights": 2, "grad_
 EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_jacobian_input",
            "pfg_jacobian_weights", "pfg_per_example_grad_norms", "pfg_hessian_input",
            "pfg_lstm_workspace_bytes", "pfg_lstm_per_example_grads", "pfg_lstm_jacobian_input",
+           "pfg_lstm_per_example_grad_norms",
            "pfg_lstm_varlen_workspace_bytes", "pfg_lstm_varlen_forward",
            "pfg_convnet_workspace_bytes", "pfg_convnet_per_example_grads",
            "pfg_cond_workspace_bytes", "pfg_cond_forward",
@@ -89,7 +90,7 @@ class pfg_cond(ctypes.Structure):
     ]
 
 
-LSTM_OP = {"per_example_grads": 0, "jacobian_input": 1}
+LSTM_OP = {"per_example_grads": 0, "jacobian_input": 1, "grad_norms": 2}
 PFG_COND_PER_ITERATION = -1
 
 _lib = None
@@ -121,6 +122,7 @@ def load_library() -> ctypes.CDLL:
         lib.pfg_lstm_per_example_grads.argtypes = [lstmp, vp, vp, i64, vp, vp, vp, vp, vp, vp,
                                                    ctypes.c_size_t, vp]
         lib.pfg_lstm_jacobian_input.argtypes = [lstmp, vp, i64, vp, i64, i64, vp, vp, ctypes.c_size_t, vp]
+        lib.pfg_lstm_per_example_grad_norms.argtypes = [lstmp, vp, vp, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.pfg_lstm_varlen_workspace_bytes.argtypes = [lstmp, i64, i64, ctypes.POINTER(ctypes.c_size_t)]
         lib.pfg_lstm_varlen_forward.argtypes = [lstmp, vp, ctypes.POINTER(ctypes.c_int32), i64, i64, vp,
                                                 vp, vp, ctypes.c_size_t, vp]
@@ -419,6 +421,30 @@ def pfg_lstm_per_example_grads(net: Lstm, X, labels, want_dW: bool = True, want_
         ctypes.byref(net.c), X.data_ptr(), labels.data_ptr(), B, ptr(outs[0]), ptr(outs[1]),
         ptr(outs[2]), ptr(outs[3]), ptr(outs[4]), workspace.data_ptr(), ws_bytes, _stream_ptr()))
     return tuple(outs)
+
+
+def pfg_lstm_per_example_grad_norms(net: Lstm, X, labels, want_sq: bool = True, want_norm: bool = True,
+                                    want_loss: bool = True, out=None, workspace=None):
+    """Returns (sq [B, 4] = squared norms of dW, db, dWout, dbout; norm [B]; loss [B]); entries that
+    are not wanted are None.  ``out`` may hold caller tensors in that structure."""
+    import torch
+    _check_seq(net, X)
+    B = X.shape[0]
+    if labels.dtype != torch.int32 or tuple(labels.shape) != (B,) or not labels.is_contiguous():
+        raise ValueError("labels must be a contiguous int32 [B] tensor")
+    f32 = dict(dtype=torch.float32, device=net.device)
+    if out is not None:
+        sq, norm, loss = out
+    else:
+        sq = torch.empty((B, 4), **f32) if want_sq else None
+        norm = torch.empty((B,), **f32) if want_norm else None
+        loss = torch.empty((B,), **f32) if want_loss else None
+    workspace, ws_bytes = _lstm_workspace(net, "grad_norms", B, 1, workspace)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(load_library().pfg_lstm_per_example_grad_norms(
+        ctypes.byref(net.c), X.data_ptr(), labels.data_ptr(), B, ptr(sq), ptr(norm), ptr(loss),
+        workspace.data_ptr(), ws_bytes, _stream_ptr()))
+    return sq, norm, loss
 
 
 def pfg_lstm_jacobian_input(net: Lstm, X, seeds=None, S: Optional[int] = None, out=None,

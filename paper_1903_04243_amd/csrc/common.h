@@ -231,6 +231,14 @@ struct OuterSumJob {
 hipError_t launch_outer_sum(const OuterSumJob *jobs, int njobs, int64_t B, int32_t d_out,
                             int64_t out_bs, hipStream_t stream);
 
+// Squared norms of the per-example LSTM gradient from Gram matrices over the steps (T <= 64):
+//   sq[b, 0..3] = |dW[b]|^2, |db[b]|^2, |dWout[b]|^2, |dbout[b]|^2;  norm[b] = sqrt of their sum
+// X [B, T, dx], hs [B, T, H], dz [B, T, 4H], gy [B, dy]; sq and norm are optional.
+constexpr int kLstmNormMaxSteps = 64;
+hipError_t launch_lstm_grad_sqnorms(const float *X, const float *hs, const float *dz, const float *gy,
+                                    int64_t B, int32_t T, int32_t dx, int32_t H, int32_t dy, float *sq,
+                                    float *norm, hipStream_t stream);
+
 // out[b, j] = sum_{t < T} g[b, t, j].  scratch (optional): min(B, 32768) * kSumPieces * d floats, used
 // to sum long columns in pieces when there are few of them.
 constexpr int kSumPieces = 8;

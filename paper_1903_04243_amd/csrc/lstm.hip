@@ -177,6 +177,86 @@ __global__ __launch_bounds__(kThreads) void sum_steps_kernel(const float *g, int
   }
 }
 
+// One wave's share of sum_k a[k] * b[k]: lanes stride over the n values (16 bytes at a time when both
+// rows allow it); the caller adds the lanes up.
+__device__ __forceinline__ float lane_dot(const float *a, const float *b, int n, int lane) {
+  float s = 0.f;
+  if (n % 4 == 0 && ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15) == 0) {
+    for (int k = 4 * lane; k < n; k += 256) {
+      const f32x4 x = *reinterpret_cast<const f32x4 *>(a + k), y = *reinterpret_cast<const f32x4 *>(b + k);
+      s += x[0] * y[0] + x[1] * y[1] + x[2] * y[2] + x[3] * y[3];
+    }
+  } else {
+    for (int k = lane; k < n; k += 64) s += a[k] * b[k];
+  }
+  return s;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// Squared norms of one example's LSTM gradient without the gradient.  The same W acts at every step,
+// dW[b] = sum_t u_t^T dz_t with u_t = [x_t, h_{t-1}], so
+//     |dW[b]|^2 = sum_{t, t'} (u_t . u_t') (dz_t . dz_t')      and      |db[b]|^2 = sum_{t, t'} dz_t . dz_t':
+// two T x T Gram matrices per example instead of a [dx + H, 4H] matrix.  The readout gradient is an
+// outer product: |dWout[b]|^2 = |h_T|^2 |dy|^2, |dbout[b]|^2 = |dy|^2.  One workgroup per example; a
+// wave takes every sixteenth pair (t <= t'), everything is added in a fixed order.
+constexpr int kMaxNormSteps = 64;
+
+constexpr int kNormThreads = 1024;     // 16 waves: the pairs are many short, latency-bound dot products
+
+__global__ __launch_bounds__(kNormThreads) void lstm_grad_sqnorms_kernel(const float *X, const float *hs,
+                                                                         const float *dz, const float *gy,
+                                                                         int T, int dx, int H, int dy,
+                                                                         float *sq, float *norm) {
+  __shared__ float pw[kMaxNormSteps * (kMaxNormSteps + 1) / 2], pb[kMaxNormSteps * (kMaxNormSteps + 1) / 2];
+  __shared__ float tail[2];
+  const int64_t b = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float *xb = X + b * T * (int64_t)dx, *hb = hs + b * T * (int64_t)H, *zb = dz + b * T * (int64_t)(4 * H);
+  const int pairs = T * (T + 1) / 2;
+  for (int p = wave; p < pairs; p += kNormThreads / 64) {
+    int t = 0, r = p;
+    while (r >= T - t) { r -= T - t; ++t; }
+    const int u = t + r;                                   // the pair (t, u), t <= u
+    float gz = lane_dot(zb + (int64_t)t * 4 * H, zb + (int64_t)u * 4 * H, 4 * H, lane);
+    float gu = lane_dot(xb + (int64_t)t * dx, xb + (int64_t)u * dx, dx, lane);
+    if (t >= 1) gu += lane_dot(hb + (int64_t)(t - 1) * H, hb + (int64_t)(u - 1) * H, H, lane);   // h_0 = 0
+    gz = wave_sum(gz);
+    gu = wave_sum(gu);
+    if (lane == 0) {
+      const float twice = (t == u) ? 1.f : 2.f;           // the pair (u, t) contributes the same
+      pw[p] = twice * gu * gz;
+      pb[p] = twice * gz;
+    }
+  }
+  if (wave == 0) {
+    const float *hT = hb + (int64_t)(T - 1) * H;
+    const float v = wave_sum(lane_dot(hT, hT, H, lane));
+    if (lane == 0) tail[0] = v;
+  } else if (wave == 1) {
+    const float *g = gy + b * dy;
+    const float v = wave_sum(lane_dot(g, g, dy, lane));
+    if (lane == 0) tail[1] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float sw = 0.f, sb = 0.f;
+    for (int p = 0; p < pairs; ++p) {
+      sw += pw[p];
+      sb += pb[p];
+    }
+    const float so = tail[0] * tail[1], sbo = tail[1];
+    if (sq) {
+      sq[4 * b] = sw; sq[4 * b + 1] = sb; sq[4 * b + 2] = so; sq[4 * b + 3] = sbo;
+    }
+    if (norm) norm[b] = sqrtf(sw + sb + so + sbo);
+  }
+}
+
 inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads); }
 
 }  // namespace
@@ -240,6 +320,16 @@ hipError_t launch_outer_sum(const OuterSumJob *jobs, int njobs, int64_t B, int32
     } while (t0 < max_nt);
   }
   return hipSuccess;
+}
+
+hipError_t launch_lstm_grad_sqnorms(const float *X, const float *hs, const float *dz, const float *gy,
+                                    int64_t B, int32_t T, int32_t dx, int32_t H, int32_t dy, float *sq,
+                                    float *norm, hipStream_t stream) {
+  if (B <= 0) return hipSuccess;
+  if (T > kMaxNormSteps || B > 0x7fffffffLL) return hipErrorInvalidValue;
+  PFG_KERNEL(lstm_grad_sqnorms_kernel, dim3((unsigned)B), dim3(kNormThreads), 0, stream, X, hs, dz, gy, T, dx, H,
+             dy, sq, norm);
+  return hipGetLastError();
 }
 
 hipError_t launch_sum_steps(const float *g, int64_t B, int32_t T, int32_t d, float *out,

@@ -369,7 +369,7 @@ int weight_sweep(const pfg_mlp *net, const void *X, int64_t B, int64_t S, float 
 
 extern "C" {
 
-int pfg_version(void) { return 102; }
+int pfg_version(void) { return 103; }
 
 const char *pfg_last_error(void) { return g_err; }
 

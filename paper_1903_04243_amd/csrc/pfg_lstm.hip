@@ -76,7 +76,7 @@ LstmPlan make_lstm_plan(const pfg_lstm *net, int op, int64_t B, int64_t S) {
   p.gates = p.take(f * B * T * 4 * H);
   p.cs = p.take(f * B * T * H);
   p.hs = p.take(f * B * T * H);
-  if (op == PFG_LSTM_OP_PER_EXAMPLE_GRADS) {
+  if (op == PFG_LSTM_OP_PER_EXAMPLE_GRADS || op == PFG_LSTM_OP_GRAD_NORMS) {
     p.y = p.take(f * B * dy);
     p.dy = p.take(f * B * dy);
     p.dh = p.take(f * B * H);
@@ -342,9 +342,9 @@ int pfg_lstm_workspace_bytes(const pfg_lstm *net, int op, int64_t B, int64_t S, 
   int rc = check_lstm(net);
   if (rc) return rc;
   if (!bytes) return fail(PFG_ERR_NULL, "bytes is NULL");
-  if (op != PFG_LSTM_OP_PER_EXAMPLE_GRADS && op != PFG_LSTM_OP_JACOBIAN_INPUT)
+  if (op != PFG_LSTM_OP_PER_EXAMPLE_GRADS && op != PFG_LSTM_OP_JACOBIAN_INPUT && op != PFG_LSTM_OP_GRAD_NORMS)
     return fail(PFG_ERR_UNSUPPORTED, "unknown LSTM op %d", op);
-  const bool grads = (op == PFG_LSTM_OP_PER_EXAMPLE_GRADS);
+  const bool grads = (op != PFG_LSTM_OP_JACOBIAN_INPUT);
   if (grads) S = 1;
   if ((rc = check_lstm_rows(net, B, S, grads))) return rc;
   *bytes = make_lstm_plan(net, op, B, S).total;
@@ -448,6 +448,32 @@ int pfg_lstm_per_example_grads(const pfg_lstm *net, const void *X, const int32_t
     PFG_LAUNCH("outer_sum", launch_outer_sum(jobs, 2, B, 4 * H, out_bs, stream));
   }
   if (db_out) PFG_LAUNCH("sum_steps", launch_sum_steps(dz, B, T, 4 * H, db_out, nullptr, stream));
+  return PFG_OK;
+}
+
+int pfg_lstm_per_example_grad_norms(const pfg_lstm *net, const void *X, const int32_t *labels, int64_t B,
+                                    float *sq_out, float *norm_out, float *loss_out, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream) {
+  clear_error();
+  int rc = check_lstm(net);
+  if (rc) return rc;
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
+  if (!sq_out && !norm_out) return fail(PFG_ERR_NULL, "sq_out and norm_out are both NULL");
+  if (net->steps > kLstmNormMaxSteps)
+    return fail(PFG_ERR_UNSUPPORTED, "gradient norms take at most %d steps (%d given)", kLstmNormMaxSteps,
+                net->steps);
+  if ((rc = check_lstm_rows(net, B, 1, true))) return rc;
+  const LstmPlan p = make_lstm_plan(net, PFG_LSTM_OP_GRAD_NORMS, B, 1);
+  if ((rc = check_ws(p, workspace, workspace_bytes))) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  void *ws = workspace;
+  float *gy = ws_at(ws, p.dy);
+  if ((rc = lstm_forward_and_reverse(net, X, labels, B, gy, loss_out, true, ws, p, stream))) return rc;
+  PFG_LAUNCH("lstm_grad_sqnorms",
+             launch_lstm_grad_sqnorms(static_cast<const float *>(X), ws_at(ws, p.hs), ws_at(ws, p.dz), gy, B,
+                                      net->steps, net->input_size, net->state_size, net->output_size, sq_out,
+                                      norm_out, stream));
   return PFG_OK;
 }
 

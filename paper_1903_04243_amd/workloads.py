@@ -158,7 +158,8 @@ def output_values(w: Workload, B: Optional[int] = None) -> int:
 class LstmWorkload:
     name: str
     index: int
-    call: str                      # "lstm_per_example_grads" | "lstm_jacobian_input" | "lstm_varlen_forward"
+    call: str                      # "lstm_per_example_grads" | "lstm_per_example_grad_norms" |
+                                   # "lstm_jacobian_input" | "lstm_varlen_forward"
     dx: int
     H: int
     dy: int
@@ -170,6 +171,8 @@ class LstmWorkload:
 LSTM_WORKLOADS: Dict[str, LstmWorkload] = {
     w.name: w for w in [
         LstmWorkload("c7_lstm_grads", 6, "lstm_per_example_grads", 128, 256, 10, 10, 256),
+        # the same batch as c7, gradient norms only
+        LstmWorkload("c7_lstm_grad_norms", 6, "lstm_per_example_grad_norms", 128, 256, 10, 10, 256),
         LstmWorkload("c8_lstm_jacobian", 7, "lstm_jacobian_input", 128, 256, 128, 10, 64, S=128),
         # sequences of different lengths, each iterated to its own length (T = the longest allowed)
         LstmWorkload("c9_lstm_varlen", 8, "lstm_varlen_forward", 128, 256, 10, 100, 1024),

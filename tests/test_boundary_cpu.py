@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert set(names) == set(pfg.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
-    assert lib.pfg_version() == 102
+    assert lib.pfg_version() == 103
 
 
 FAKE = 0x1000  # a non-NULL, 256-aligned value; never dereferenced because validation fails first
@@ -221,7 +221,8 @@ def test_lstm_workspace_and_rejections(lib):
     fwd = 2 * up(4 * B * T * 4 * H) + up(4 * B * 4 * H) + 2 * up(4 * B * T * H)
     assert lstm_ws(lib, jac_net, 1, B, S) == (0, fwd + up(4 * S * H) + 2 * up(4 * B * S * H) +
                                               2 * up(4 * B * S * 4 * H))
-    assert lstm_ws(lib, net, 2, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
+    assert lstm_ws(lib, net, 2, 256, 1) == (0, grads)         # gradient norms: the same sweep, no outputs
+    assert lstm_ws(lib, net, 3, 1, 1)[0] == pfg.PFG_ERR_UNSUPPORTED
     assert lstm_ws(lib, net, 0, 0, 1)[0] == pfg.PFG_ERR_SHAPE
     assert lstm_ws(lib, net, 1, 1, 0)[0] == pfg.PFG_ERR_SHAPE
     assert lstm_ws(lib, net, 1, 1 << 20, 1 << 20)[0] == pfg.PFG_ERR_OVERFLOW
@@ -243,6 +244,12 @@ def test_lstm_workspace_and_rejections(lib):
     assert gr(r, FAKE, FAKE, 2, FAKE, FAKE, FAKE, FAKE, FAKE, None, big, None) == pfg.PFG_ERR_WORKSPACE
     assert gr(r, FAKE, FAKE, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 4, big, None) == pfg.PFG_ERR_WORKSPACE
     assert gr(r, FAKE, FAKE, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, None) == pfg.PFG_ERR_WORKSPACE
+    nr = lib.pfg_lstm_per_example_grad_norms
+    assert nr(r, None, FAKE, 2, FAKE, FAKE, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert nr(r, FAKE, FAKE, 2, None, None, FAKE, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert "both NULL" in lib.pfg_last_error().decode()
+    assert nr(ctypes.byref(make_lstm(T=65)), FAKE, FAKE, 2, FAKE, None, None, FAKE, big, None) == pfg.PFG_ERR_UNSUPPORTED
+    assert nr(r, FAKE, FAKE, 2, FAKE, None, None, FAKE, 64, None) == pfg.PFG_ERR_WORKSPACE
     ja = lib.pfg_lstm_jacobian_input
     assert ja(r, None, 2, None, 10, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_NULL
     assert ja(r, FAKE, 2, None, 10, 0, None, FAKE, big, None) == pfg.PFG_ERR_NULL

@@ -61,6 +61,29 @@ def check_lstm_grads(inp, tag, bias=True, examples=None):
     return net, got
 
 
+def check_lstm_norms(inp, tag, bias=True, examples=None):
+    """Squared norms per tensor and the total norm against the oracle (which forms the gradient and
+    sums its squares); every entry is a sum of squares, compared entry by entry."""
+    onet, net = nets(inp, bias)
+    B = inp.X.shape[0]
+    out = (nan_like(B, 4), nan_like(B), nan_like(B))
+    sq, norm, loss = pfg.pfg_lstm_per_example_grad_norms(net, dev(inp.X), dev(inp.labels), out=out)
+    torch.cuda.synchronize()
+    idx = list(range(B)) if examples is None else list(examples)
+    rsq, rnorm, rloss = olstm.per_example_grad_norms(onet, inp.X[idx], inp.labels[idx])
+    worst = 0.0
+    for name, g, r in (("sq", sq, rsq), ("norm", norm, rnorm), ("loss", loss, rloss)):
+        gh = g.cpu().numpy().astype(np.float64)
+        assert np.isfinite(gh).all(), f"{name} was not written in full"
+        zero = r == 0.0
+        assert (gh[idx][zero] == 0.0).all()
+        e = float((np.abs(gh[idx] - r)[~zero] / np.abs(r)[~zero]).max()) if (~zero).any() else 0.0
+        say(f"  {tag} {name} rel err {e:.3e}")
+        worst = max(worst, e)
+    assert worst <= TOL_F32, f"{tag}: max relative error {worst:.3e}"
+    return net, (sq, norm, loss)
+
+
 def check_lstm_jacobian(inp, tag, seeds=None, bias=True):
     onet, net = nets(inp, bias)
     B, T, dx = inp.X.shape
@@ -95,6 +118,7 @@ def test_lstm_odd_shapes_grads_and_jacobian(dx, H, dy, T, B):
     w = wl.LstmWorkload("odd", 300 + dx + H + T, "lstm_per_example_grads", dx, H, dy, T, B)
     inp = wl.make_lstm_inputs(w, bias_scale=0.3)
     check_lstm_grads(inp, "lstm-odd")
+    check_lstm_norms(inp, "lstm-odd-norms")
     rng = np.random.default_rng(B + T)
     shared = rng.standard_normal((3, dy)).astype(np.float32)
     per_ex = rng.standard_normal((B, 2, dy)).astype(np.float32)
@@ -135,6 +159,26 @@ def test_c7_lstm_grads_full_size():
     tperm = torch.from_numpy(perm).to("cuda:0")
     for name, a, b in zip(NAMES, got_p, got):
         assert torch.equal(a, b[tperm]), f"{name} depends on the position in the batch"
+
+
+def test_c7_lstm_grad_norms_full_size_and_consistency_with_the_gradients():
+    w = wl.LSTM_WORKLOADS["c7_lstm_grads"]
+    inp = wl.make_lstm_inputs(w)
+    picks = sorted(set([0, w.B - 1] + np.random.default_rng(7).integers(0, w.B, size=14).tolist()))
+    net, (sq, norm, loss) = check_lstm_norms(inp, "c7-norms", examples=picks)
+    # every example: the norms agree with the squares of the gradients the library itself writes
+    dW, db, dWout, dbout, loss2 = pfg.pfg_lstm_per_example_grads(net, dev(inp.X), dev(inp.labels))
+    torch.cuda.synchronize()
+    want = torch.stack([t.double().pow(2).flatten(1).sum(1) for t in (dW, db, dWout, dbout)], dim=1)
+    rel = ((sq.double() - want).abs() / want).max().item()
+    say(f"  c7-norms: all {w.B} examples against the squares of the written gradients: {rel:.3e}")
+    assert rel <= TOL_F32 and torch.equal(loss, loss2)
+    # without biases and with skipped outputs
+    _, (sq2, norm2, loss3) = check_lstm_norms(wl.make_lstm_inputs(wl.LstmWorkload("nb", 345, "lstm_per_example_grads", 6, 10, 4, 5, 7)),
+                                              "lstm-norms-nobias", bias=False)
+    only = pfg.pfg_lstm_per_example_grad_norms(net, dev(inp.X), dev(inp.labels), want_sq=False, want_loss=False)
+    torch.cuda.synchronize()
+    assert only[0] is None and only[2] is None and torch.equal(only[1], norm)
 
 
 def test_c8_lstm_jacobian_reduced_every_element_and_full_size_sampled_rows():
