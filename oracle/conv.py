@@ -130,3 +130,20 @@ def per_example_grads(net: ConvNet, X, labels, want_dW: Optional[Sequence[bool]]
                                     ctypes.c_int64(B), _ptr_array(dWc), _ptr_array(dbc),
                                     _ptr_array(dW), _ptr_array(db), _dp(ls))
     return dWc, dbc, dW, db, ls
+
+
+def per_example_grad_norms(net: ConvNet, X, labels):
+    """(sq [B, num_conv + L], norm [B], loss [B]): squared norm of every parameter block's
+    per-example gradient (a block = a filter or weight matrix together with its bias, when it has
+    one; conv blocks first), and the norm of the whole gradient."""
+    X = _f64(X)
+    B = X.shape[0]
+    assert X.shape == (B, net.height, net.width, net.channels)
+    labels = np.ascontiguousarray(np.asarray(labels, dtype=np.int32))
+    assert labels.shape == (B,) and labels.min(initial=0) >= 0 and labels.max(initial=0) < net.dims[-1]
+    sq = np.empty((B, net.nc + net.L))
+    norm = np.empty(B)
+    ls = np.empty(B)
+    _load().convo_per_example_grad_norms(ctypes.byref(net.c), _dp(X), labels.ctypes.data_as(_c_int32_p),
+                                         ctypes.c_int64(B), _dp(sq), _dp(norm), _dp(ls))
+    return sq, norm, ls

@@ -305,3 +305,57 @@ void convo_per_example_grads(const convo_net *net, const double *X, const int32_
     free(a);
   }
 }
+
+/* Squared norms of one example's gradient, one figure per parameter block: column i < num_conv is
+ * the filter of conv block i together with its bias (when the block has one), column num_conv + l
+ * the dense layer l + 1 likewise.  The gradient is formed first and its squares are summed: the
+ * definition, with no shortcut through the factors. */
+void convo_body_grad_norm(const convo_net *net, const double *x, int label, double *sq, double *norm,
+                          double *loss) {
+  const int L = net->L, nc = net->num_conv;
+  double **a = (double **)calloc((size_t)(2 * nc + 2 * L), sizeof(double *));
+  size_t *cnt = (size_t *)calloc((size_t)(2 * nc + 2 * L), sizeof(size_t));
+  double **dWc = a, **dbc = a + nc, **dW = a + 2 * nc, **db = a + 2 * nc + L;
+  for (int i = 0; i < nc; ++i) {
+    int hi, wi, ci, co;
+    block_dims(net, i, &hi, &wi, &ci, &co);
+    cnt[i] = (size_t)net->kernel[i] * net->kernel[i] * ci * co;
+    cnt[nc + i] = (size_t)co;
+  }
+  for (int l = 1; l <= L; ++l) {
+    cnt[2 * nc + l - 1] = (size_t)net->dims[l - 1] * net->dims[l];
+    cnt[2 * nc + L + l - 1] = (size_t)net->dims[l];
+  }
+  for (int j = 0; j < 2 * nc + 2 * L; ++j) a[j] = (double *)malloc(sizeof(double) * cnt[j]);
+  convo_body_per_example_grads(net, x, label, dWc, dbc, dW, db, loss);
+  double total = 0.0;
+  for (int i = 0; i < nc; ++i) {
+    double s = 0.0;
+    for (size_t e = 0; e < cnt[i]; ++e) s += dWc[i][e] * dWc[i][e];
+    if (net->bc && net->bc[i])
+      for (size_t e = 0; e < cnt[nc + i]; ++e) s += dbc[i][e] * dbc[i][e];
+    if (sq) sq[i] = s;
+    total += s;
+  }
+  for (int l = 0; l < L; ++l) {
+    double s = 0.0;
+    for (size_t e = 0; e < cnt[2 * nc + l]; ++e) s += dW[l][e] * dW[l][e];
+    if (net->b && net->b[l])
+      for (size_t e = 0; e < cnt[2 * nc + L + l]; ++e) s += db[l][e] * db[l][e];
+    if (sq) sq[nc + l] = s;
+    total += s;
+  }
+  if (norm) *norm = sqrt(total);
+  for (int j = 0; j < 2 * nc + 2 * L; ++j) free(a[j]);
+  free(a); free(cnt);
+}
+
+void convo_per_example_grad_norms(const convo_net *net, const double *X, const int32_t *labels,
+                                  int64_t B, double *sq, double *norm, double *loss) {
+  const size_t nx = (size_t)net->height * net->width * net->channels;
+  const int cols = net->num_conv + net->L;
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < B; ++i)
+    convo_body_grad_norm(net, X + (size_t)i * nx, labels[i], sq ? sq + (size_t)cols * i : NULL,
+                         norm ? norm + i : NULL, loss ? loss + i : NULL);
+}

@@ -176,3 +176,69 @@ def test_a_centre_tap_filter_is_the_identity_and_a_dead_block_has_no_gradient():
     dead = conv.ConvNet(4, 4, 1, [Wc], [np.array([-5.0])], [dense], None)
     dWc, dbc, _, _, _ = conv.per_example_grads(dead, x[None], [1])
     assert not dWc[0].any() and not dbc[0].any()
+
+
+def autograd_block_sqnorms(net, x, label):
+    """Squared gradient norm of every parameter block (conv blocks first) from autograd through
+    the library convolution and pooling; a block without a bias counts its weights only."""
+    params = {
+        "Wc": [torch.from_numpy(W).clone().requires_grad_(True) for W in net.Wc],
+        "bc": [None if v is None else torch.from_numpy(v).clone().requires_grad_(True) for v in net.bc],
+        "Ws": [torch.from_numpy(W).clone().requires_grad_(True) for W in net.Ws],
+        "bs": [None if v is None else torch.from_numpy(v).clone().requires_grad_(True) for v in net.bs],
+    }
+    y, _ = torch_forward(net, torch.from_numpy(x), params)
+    ell = -torch.log_softmax(y, dim=0)[int(label)]
+    ell.backward()
+    out = []
+    for W, v in list(zip(params["Wc"], params["bc"])) + list(zip(params["Ws"], params["bs"])):
+        s = float((W.grad ** 2).sum())
+        if v is not None:
+            s += float((v.grad ** 2).sum())
+        out.append(s)
+    return out, float(ell.detach())
+
+
+@pytest.mark.parametrize("bias", ["all", "none", "mixed"])
+def test_grad_norms_against_autograd_through_the_library_ops(bias):
+    rng = np.random.default_rng(86)
+    net = rand_net(rng, 8, 8, 2, [(3, 3), (3, 5)], [6, 4], bias=(bias != "none"))
+    if bias == "mixed":      # first conv block and last dense layer lose their bias
+        net = conv.ConvNet(8, 8, 2, net.Wc, [None, net.bc[1]], net.Ws, [net.bs[0], None])
+    B = 4
+    X = rng.standard_normal((B, 8, 8, 2))
+    labels = rng.integers(0, 4, size=B)
+    sq, norm, loss = conv.per_example_grad_norms(net, X, labels)
+    assert sq.shape == (B, 4)
+    for b in range(B):
+        want, ell = autograd_block_sqnorms(net, X[b], labels[b])
+        np.testing.assert_allclose(sq[b], want, rtol=1e-10)
+        assert norm[b] == pytest.approx(math.sqrt(sum(want)), rel=1e-10)
+        assert loss[b] == pytest.approx(ell, rel=1e-12)
+    # every column differs from the others: a misplaced column cannot pass by symmetry
+    assert len(set(np.round(sq[0] / sq[0].max(), 6))) == 4
+
+
+def test_grad_norms_dense_factorisation_and_stacking():
+    rng = np.random.default_rng(87)
+    net = rand_net(rng, 4, 4, 2, [(3, 3)], [5, 3])
+    B = 6
+    X = rng.standard_normal((B, 4, 4, 2))
+    labels = rng.integers(0, 3, size=B)
+    sq, norm, loss = conv.per_example_grad_norms(net, X, labels)
+    for b in range(B):
+        feat = conv.features(net, X[b])
+        p = scipy.special.softmax(conv.forward(net, X[b]))
+        p[labels[b]] -= 1.0                                   # cotangent of the logits
+        # last dense layer: (|a|^2 + 1) |delta|^2 with a = relu of the first dense layer
+        a1 = np.maximum(feat @ net.Ws[0] + net.bs[0], 0.0)
+        assert sq[b, 2] == pytest.approx((a1 @ a1 + 1.0) * (p @ p), rel=1e-12)
+        d1 = (net.Ws[1] @ p) * (a1 > 0)
+        assert sq[b, 1] == pytest.approx((feat @ feat + 1.0) * (d1 @ d1), rel=1e-12)
+    np.testing.assert_allclose(norm, np.sqrt(sq.sum(axis=1)), rtol=1e-14)
+    perm = rng.permutation(B)
+    sq2, norm2, loss2 = conv.per_example_grad_norms(net, X[perm], labels[perm])
+    np.testing.assert_array_equal(sq2, sq[perm])
+    np.testing.assert_array_equal(norm2, norm[perm])
+    np.testing.assert_array_equal(loss2, loss[perm])
+    assert len(set(norm.tolist())) == B

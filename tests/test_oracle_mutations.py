@@ -124,6 +124,18 @@ LSTM_MUTANTS = [
 CONV_SRC = os.path.join(ROOT, "oracle", "conv_oracle.c")
 
 CONV_MUTANTS = [
+    ("norm_cross_term", "for (size_t e = 0; e < cnt[i]; ++e) s += dWc[i][e] * dWc[i][e];",
+     "for (size_t e = 0; e < cnt[i]; ++e) s += dWc[i][e] * dWc[i][(e + 1) % cnt[i]];"),
+    ("norm_conv_bias_dropped", "for (size_t e = 0; e < cnt[nc + i]; ++e) s += dbc[i][e] * dbc[i][e];", ""),
+    ("norm_absent_conv_bias_counted", "if (net->bc && net->bc[i])\n      for (size_t e = 0; e < cnt[nc + i]; ++e)",
+     "for (size_t e = 0; e < cnt[nc + i]; ++e)"),
+    ("norm_absent_dense_bias_counted", "if (net->b && net->b[l])\n      for (size_t e = 0; e < cnt[2 * nc + L + l]; ++e)",
+     "for (size_t e = 0; e < cnt[2 * nc + L + l]; ++e)"),
+    ("norm_dense_columns_first", "if (sq) sq[nc + l] = s;", "if (sq) sq[l] = s;"),
+    ("norm_dense_weights_of_wrong_layer", "for (size_t e = 0; e < cnt[2 * nc + l]; ++e) s += dW[l][e] * dW[l][e];",
+     "for (size_t e = 0; e < cnt[2 * nc]; ++e) s += dW[0][e] * dW[0][e];"),
+    ("norm_not_a_root", "if (norm) *norm = sqrt(total);", "if (norm) *norm = total;"),
+    ("norm_stacking", "sq ? sq + (size_t)cols * i : NULL,", "sq ? sq + (size_t)cols * (B - 1 - i) : NULL,"),
     ("conv_filter_flipped", "const int yy = y + ky - p, xs = xx + kx - p;\n              if (yy < 0 || yy >= hi || xs < 0 || xs >= wi) continue;      /* zero padding */",
      "const int yy = y - ky + p, xs = xx - kx + p;\n              if (yy < 0 || yy >= hi || xs < 0 || xs >= wi) continue;"),
     ("conv_padding_off_by_one", "const int k = net->kernel[i], p = (k - 1) / 2;\n    const double *W = net->Wc[i];\n    const double *bias",
