@@ -346,8 +346,14 @@ def main():
                [torch.empty((B, W.shape[3]), **f32) for W in inp.Wc],
                [torch.empty((B, dn.dims[l], dn.dims[l + 1]), **f32) for l in range(dn.L)],
                [torch.empty((B, dn.dims[l + 1]), **f32) for l in range(dn.L)], torch.empty((B,), **f32))
-        ws = torch.empty(pfg.pfg_convnet_workspace_bytes(net, B), dtype=torch.uint8, device=dev)
-        step = lambda: pfg.pfg_convnet_per_example_grads(net, X, labels, out=out, workspace=ws)
+        norms = (w.call == "convnet_per_example_grad_norms")
+        if norms:
+            out = (torch.empty((B, net.nc + dn.L), **f32), torch.empty((B,), **f32), torch.empty((B,), **f32))
+            ws = torch.empty(pfg.pfg_convnet_grad_norms_workspace_bytes(net, B), dtype=torch.uint8, device=dev)
+            step = lambda: pfg.pfg_convnet_per_example_grad_norms(net, X, labels, out=out, workspace=ws)
+        else:
+            ws = torch.empty(pfg.pfg_convnet_workspace_bytes(net, B), dtype=torch.uint8, device=dev)
+            step = lambda: pfg.pfg_convnet_per_example_grads(net, X, labels, out=out, workspace=ws)
         step()
         torch.cuda.synchronize()
         log(f"[bench] {name}: timing {steps} steps")
@@ -359,16 +365,19 @@ def main():
             except Exception as e:
                 log(f"[bench] {name}: graph replay not measured ({e})")
         kt = kernel_times(step, steps)
-        values = sum(t.numel() for group in out[:4] for t in group) + B
-        # the dense weight gradients are the large output (4 bytes per value, written once)
-        fam = "outer_product"
-        nbytes = 4 * B * sum(dn.dims[l] * dn.dims[l + 1] for l in range(dn.L))
-        per_ms = kt[fam]["ms_per_step"] / kt[fam]["launches_per_step"]
-        gbs = nbytes / kt[fam]["ms_per_step"] / 1e6
-        roof = {"kernel": fam, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": gbs / HBM_PEAK_GBS, "traffic": None,
-                "bytes_per_launch": nbytes / kt[fam]["launches_per_step"], "ms_per_launch": per_ms,
-                "launches_per_step": kt[fam]["launches_per_step"]}
+        if norms:
+            values = sum(t.numel() for t in out)
+        else:
+            values = sum(t.numel() for group in out[:4] for t in group) + B
+            # the dense weight gradients are the large output (4 bytes per value, written once)
+            fam = "outer_product"
+            nbytes = 4 * B * sum(dn.dims[l] * dn.dims[l + 1] for l in range(dn.L))
+            per_ms = kt[fam]["ms_per_step"] / kt[fam]["launches_per_step"]
+            gbs = nbytes / kt[fam]["ms_per_step"] / 1e6
+            roof = {"kernel": fam, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                    "bytes_per_launch": nbytes / kt[fam]["launches_per_step"], "ms_per_launch": per_ms,
+                    "launches_per_step": kt[fam]["launches_per_step"]}
         # the conv products, against the fp32 MFMA peak
         hh, ww, cc = w.height, w.width, w.channels
         conv_flops = {"conv_gemm_forward": 0, "conv_gemm_filter": 0, "conv_gemm_cotangent": 0}
@@ -382,7 +391,16 @@ def main():
         conv_report = {fam2: {"flops_per_step": fl, "TFLOP/s": fl / kt[fam2]["ms_per_step"] / 1e9,
                               "mfma_frac": fl / kt[fam2]["ms_per_step"] / 1e9 / MFMA_PEAK_TFLOPS["f32"]}
                        for fam2, fl in conv_flops.items() if fam2 in kt and fl}
-        rec = {"workload": name, "call": "convnet_per_example_grads", "image": [w.height, w.width, w.channels],
+        if norms:
+            # no large output is left: the slowest of the conv products is the kernel to price
+            fam = max(conv_report, key=lambda f2: kt[f2]["ms_per_step"])
+            tf = conv_report[fam]["TFLOP/s"]
+            roof = {"kernel": fam, "bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["f32"],
+                    "unit": "TFLOP/s", "frac": tf / MFMA_PEAK_TFLOPS["f32"], "traffic": None,
+                    "flops_per_launch": conv_report[fam]["flops_per_step"] / kt[fam]["launches_per_step"],
+                    "ms_per_launch": kt[fam]["ms_per_step"] / kt[fam]["launches_per_step"],
+                    "launches_per_step": kt[fam]["launches_per_step"]}
+        rec = {"workload": name, "call": w.call, "image": [w.height, w.width, w.channels],
                "blocks": [list(b) for b in w.blocks], "dense": list(w.dense), "dtype": "f32", "B": B,
                "steps": steps, "ms_per_step": sec * 1e3,
                "ms_per_step_graph_replay": None if sec_graph is None else sec_graph * 1e3,
@@ -588,6 +606,7 @@ def main():
                             ("c8_lstm_jacobian", max(3, args.steps // 10)),
                             ("c9_lstm_varlen", max(3, args.steps // 10)),
                             ("c10_mnist_convnet_grads", max(3, args.steps // 10)),
+                            ("c10_mnist_convnet_grad_norms", max(3, args.steps // 10)),
                             ("c11_cond_two_branches", max(3, args.steps // 4))):
             try:
                 fn = measure if name in wl.WORKLOADS else measure_lstm

@@ -284,6 +284,25 @@ int pfg_convnet_per_example_grads(const pfg_convnet *net, const void *X, const i
                                   float *const *dW_out, float *const *db_out, float *loss_out,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Norms of the per-example gradients above without writing the gradients out.  One figure per
+ * parameter block, conv blocks first: column i < num_conv is the filter of conv block i together
+ * with its bias (when net->bc and net->bc[i] are non-NULL), column num_conv + l - 1 the dense layer
+ * l with its bias likewise.  A dense layer's gradient is an outer product, so its norm comes from
+ * the two factors as for pfg_per_example_grad_norms; a filter gradient is a sum of such products
+ * over the positions (Section 5.3 with the matmul case of Section 3.4), which has no such
+ * shortcut: it is formed in the workspace and its squares are summed there.
+ *      sq_blocks_out[b, j] = squared norm of block j of example b's gradient
+ *      norm_out[b]         = sqrt(sum_j sq_blocks_out[b, j])
+ *   X, labels, loss_out   as for pfg_convnet_per_example_grads
+ *   sq_blocks_out [B, num_conv + L] or NULL;  norm_out [B] or NULL (at least one is required)
+ * The workspace is larger than that of the gradients by the filter and bias gradients of all
+ * examples (B * k * k * c_in * c_out floats per block). */
+int pfg_convnet_grad_norms_workspace_bytes(const pfg_convnet *net, int64_t B, size_t *bytes);
+int pfg_convnet_per_example_grad_norms(const pfg_convnet *net, const void *X, const int32_t *labels,
+                                       int64_t B, float *sq_blocks_out, float *norm_out,
+                                       float *loss_out, void *workspace, size_t workspace_bytes,
+                                       void *hip_stream);
+
 /* ------------------------------------------------------------------------------------------
  * A parallel-for whose body holds a conditional (Section 3.6).  Iteration i computes
  *      t = phi_pre(pre(x_i))                 a dense network; its activation is applied after the

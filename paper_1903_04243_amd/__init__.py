@@ -30,6 +30,7 @@ EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_jacobian_input",
            "pfg_lstm_per_example_grad_norms",
            "pfg_lstm_varlen_workspace_bytes", "pfg_lstm_varlen_forward",
            "pfg_convnet_workspace_bytes", "pfg_convnet_per_example_grads",
+           "pfg_convnet_grad_norms_workspace_bytes", "pfg_convnet_per_example_grad_norms",
            "pfg_cond_workspace_bytes", "pfg_cond_forward",
            "pfg_last_error", "pfg_timing_enable", "pfg_timing_reset",
            "pfg_timing_query", "pfg_timing_names", "pfg_version"]
@@ -131,6 +132,9 @@ def load_library() -> ctypes.CDLL:
         lib.pfg_convnet_per_example_grads.argtypes = [convp, vp, vp, i64, ctypes.POINTER(vp),
                                                       ctypes.POINTER(vp), ctypes.POINTER(vp),
                                                       ctypes.POINTER(vp), vp, vp, ctypes.c_size_t, vp]
+        lib.pfg_convnet_grad_norms_workspace_bytes.argtypes = [convp, i64, ctypes.POINTER(ctypes.c_size_t)]
+        lib.pfg_convnet_per_example_grad_norms.argtypes = [convp, vp, vp, i64, vp, vp, vp, vp,
+                                                           ctypes.c_size_t, vp]
         condp = ctypes.POINTER(pfg_cond)
         lib.pfg_cond_workspace_bytes.argtypes = [condp, i64, ctypes.POINTER(ctypes.c_size_t)]
         lib.pfg_cond_forward.argtypes = [condp, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -585,6 +589,42 @@ def pfg_convnet_per_example_grads(net: ConvNet, X, labels, want_dWc: Optional[Se
         None if loss is None else loss.data_ptr(), workspace.data_ptr(),
         workspace.numel() * workspace.element_size(), _stream_ptr()))
     return dWc, dbc, dW, db, loss
+
+
+def pfg_convnet_grad_norms_workspace_bytes(net: ConvNet, B: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().pfg_convnet_grad_norms_workspace_bytes(ctypes.byref(net.c), B, ctypes.byref(n)))
+    return int(n.value)
+
+
+def pfg_convnet_per_example_grad_norms(net: ConvNet, X, labels, want_sq: bool = True,
+                                       want_norm: bool = True, want_loss: bool = True, out=None,
+                                       workspace=None):
+    """Returns (sq [B, num_conv + L] = squared gradient norm of every parameter block, conv blocks
+    first; norm [B]; loss [B]); entries that are not wanted are None.  ``out`` may hold caller
+    tensors in that structure."""
+    import torch
+    if (X.dtype != torch.float32 or not X.is_contiguous() or X.dim() != 4 or
+            tuple(X.shape[1:]) != (net.height, net.width, net.channels)):
+        raise ValueError("X must be a contiguous float32 [B, height, width, channels] tensor")
+    B = X.shape[0]
+    if labels.dtype != torch.int32 or tuple(labels.shape) != (B,) or not labels.is_contiguous():
+        raise ValueError("labels must be a contiguous int32 [B] tensor")
+    f32 = dict(dtype=torch.float32, device=net.device)
+    if out is not None:
+        sq, norm, loss = out
+    else:
+        sq = torch.empty((B, net.nc + net.dense.L), **f32) if want_sq else None
+        norm = torch.empty((B,), **f32) if want_norm else None
+        loss = torch.empty((B,), **f32) if want_loss else None
+    if workspace is None:
+        workspace = torch.empty(pfg_convnet_grad_norms_workspace_bytes(net, B), dtype=torch.uint8,
+                                device=net.device)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(load_library().pfg_convnet_per_example_grad_norms(
+        ctypes.byref(net.c), X.data_ptr(), labels.data_ptr(), B, ptr(sq), ptr(norm), ptr(loss),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr()))
+    return sq, norm, loss
 
 
 class Cond:

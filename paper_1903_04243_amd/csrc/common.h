@@ -178,17 +178,19 @@ hipError_t launch_scale_rows(const void *in, int32_t in_bf16, int64_t in_batch_s
                              const float *mask, int64_t ld_mask, int64_t B, int64_t S, int32_t d,
                              float *out, int64_t ld_out, hipStream_t stream);
 
-// Squared gradient norms of the dense layers of a launch (at most kNormLayers per launch):
-//   sq[b * ld_sq + layer] = (|a[b, :]|^2 + (has_bias ? 1 : 0)) * |g[b, :]|^2
+// Squared gradient norms of the parameter blocks of a launch (at most kNormLayers per launch):
+//   sq[b * ld_sq + index] = (|a[b, :]|^2 + (has_bias ? 1 : 0)) * |g[b, :]|^2       a dense layer
+//   sq[b * ld_sq + index] = |a[b, :]|^2 + (g ? |g[b, :]|^2 : 0)      sum_mode: a gradient at hand
 // and, if norm is given, norm[b] = sqrt(sum over the launch's layers) (the launch must then cover
 // every layer).  sq may be null when norm is given.
 constexpr int kNormLayers = 16;
 struct NormLayer {
   const void *a;      // [B, d_in] float32 or bf16
-  const float *g;     // [B, d_out]
+  const float *g;     // [B, d_out]; may be null in sum_mode
   int32_t d_in, d_out;
   int32_t a_bf16, has_bias;
   int32_t index;      // column of sq
+  int32_t sum_mode;
 };
 hipError_t launch_grad_sqnorms(const NormLayer *layers, int n, int64_t B, float *sq, int64_t ld_sq,
                                float *norm, hipStream_t stream);

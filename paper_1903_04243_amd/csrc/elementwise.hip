@@ -159,7 +159,19 @@ __device__ __forceinline__ float row_sumsq(const float *row, int d, int tid) {
   float s = 0.f;
   if ((reinterpret_cast<uintptr_t>(row) & 15) == 0 && d % 4 == 0) {
     const f32x4 *r4 = reinterpret_cast<const f32x4 *>(row);
-    for (int i = tid; i < d / 4; i += kThreads) {
+    const int n4 = d / 4;
+    int i = tid;
+    // long rows: four loads in flight per thread, four partial sums folded in a fixed order
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    for (; i + 3 * kThreads < n4; i += 4 * kThreads) {
+      const f32x4 v0 = r4[i], v1 = r4[i + kThreads], v2 = r4[i + 2 * kThreads], v3 = r4[i + 3 * kThreads];
+      s += v0[0] * v0[0] + v0[1] * v0[1] + v0[2] * v0[2] + v0[3] * v0[3];
+      s1 += v1[0] * v1[0] + v1[1] * v1[1] + v1[2] * v1[2] + v1[3] * v1[3];
+      s2 += v2[0] * v2[0] + v2[1] * v2[1] + v2[2] * v2[2] + v2[3] * v2[3];
+      s3 += v3[0] * v3[0] + v3[1] * v3[1] + v3[2] * v3[2] + v3[3] * v3[3];
+    }
+    s = (s + s1) + (s2 + s3);
+    for (; i < n4; i += kThreads) {
       const f32x4 v = r4[i];
       s += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
     }
@@ -177,7 +189,9 @@ struct NormBatch {
 // The gradient of a dense layer for one example is the outer product of the layer's input row and
 // its cotangent row (the both-operands-stacked matmul case of Section 3.4 with contraction
 // length 1), so its squared Frobenius norm is the product of the two rows' squared norms; the
-// bias gradient is the cotangent row itself.  One workgroup per example, sums in a fixed order.
+// bias gradient is the cotangent row itself.  A block whose gradient has been formed (sum_mode: a
+// convolution's filter, summed over the positions) contributes the sum of its squares instead.
+// One workgroup per example, sums in a fixed order.
 __global__ __launch_bounds__(kThreads) void grad_sqnorms_kernel(const NormBatch nb, float *sq,
                                                                 int64_t ld_sq, float *norm) {
   __shared__ float part[2][kWavesPerBlock];
@@ -193,7 +207,7 @@ __global__ __launch_bounds__(kThreads) void grad_sqnorms_kernel(const NormBatch 
     } else {
       sa = row_sumsq(static_cast<const float *>(ly.a) + b * ly.d_in, ly.d_in, tid);
     }
-    sg = row_sumsq(ly.g + b * ly.d_out, ly.d_out, tid);
+    if (ly.g) sg = row_sumsq(ly.g + b * ly.d_out, ly.d_out, tid);
     sa = wave_sum(sa);
     sg = wave_sum(sg);
     __syncthreads();                       // the previous layer's partial sums have been read
@@ -202,7 +216,7 @@ __global__ __launch_bounds__(kThreads) void grad_sqnorms_kernel(const NormBatch 
     float ta = 0.f, tg = 0.f;
 #pragma unroll
     for (int w = 0; w < kWavesPerBlock; ++w) { ta += part[0][w]; tg += part[1][w]; }
-    const float v = (ta + (ly.has_bias ? 1.f : 0.f)) * tg;
+    const float v = ly.sum_mode ? ta + tg : (ta + (ly.has_bias ? 1.f : 0.f)) * tg;
     if (sq && tid == 0) sq[b * ld_sq + ly.index] = v;
     total += v;
   }

@@ -369,7 +369,7 @@ int weight_sweep(const pfg_mlp *net, const void *X, int64_t B, int64_t S, float 
 
 extern "C" {
 
-int pfg_version(void) { return 103; }
+int pfg_version(void) { return 104; }
 
 const char *pfg_last_error(void) { return g_err; }
 
@@ -663,6 +663,7 @@ namespace {
 struct ConvBlock {
   int h, w, ci, co, k;     // input size and channels, output channels, kernel size
   size_t P, PT, z, pooled, which, dz;
+  size_t gW = 0, gb = 0;   // norms only: this block's per-example filter and bias gradients
 };
 
 struct ConvPlan {
@@ -672,6 +673,7 @@ struct ConvPlan {
   size_t psum = 0;             // partial sums over positions (bias gradients)
   size_t dense = 0;            // sub-workspace of the dense layers
   size_t dense_bytes = 0;
+  size_t sq = 0;               // norms only: [B, num_conv + L] squared norms when the caller wants none
   size_t take(size_t bytes) {
     const size_t at = total;
     total += (bytes + 255) / 256 * 256;
@@ -706,7 +708,7 @@ int check_convnet(const pfg_convnet *net, int64_t B) {
   return PFG_OK;
 }
 
-ConvPlan make_conv_plan(const pfg_convnet *net, int64_t B) {
+ConvPlan make_conv_plan(const pfg_convnet *net, int64_t B, bool norms = false) {
   ConvPlan p;
   const size_t f = sizeof(float);
   int h = net->height, w = net->width, c = net->channels;
@@ -722,6 +724,10 @@ ConvPlan make_conv_plan(const pfg_convnet *net, int64_t B) {
     blk.pooled = p.take(f * B * cells);
     blk.which = p.take(B * cells);
     widest_pooled = std::max(widest_pooled, B * cells);
+    if (norms) {
+      blk.gW = p.take(f * B * kkc * blk.co);
+      blk.gb = p.take(f * B * blk.co);
+    }
     p.blocks.push_back(blk);
     h /= 2; w /= 2; c = blk.co;
   }
@@ -732,8 +738,49 @@ ConvPlan make_conv_plan(const pfg_convnet *net, int64_t B) {
   p.psum = p.take(f * B * kSumPieces * widest_co);
   p.dense_bytes = make_plan(&net->dense, PFG_OP_PER_EXAMPLE_GRADS, B, 1).total;
   p.dense = p.take(p.dense_bytes);
+  if (norms) p.sq = p.take(f * B * (net->num_conv + net->dense.num_layers));
   return p;
 }
+
+// The squared norms wanted from the sweep instead of the gradients themselves.
+struct ConvNorms {
+  float *sq_blocks;   // [B, num_conv + L] or null
+  float *norm;        // [B] or null
+};
+
+int check_convnet_call(const pfg_convnet *net, const void *X, const int32_t *labels, int64_t B,
+                       const ConvPlan &cp, void *workspace, size_t workspace_bytes) {
+  int rc = check_weights(&net->dense);
+  if (rc) return rc;
+  if (!net->Wc) return fail(PFG_ERR_NULL, "net->Wc is NULL");
+  for (int i = 0; i < net->num_conv; ++i)
+    if (!net->Wc[i]) return fail(PFG_ERR_NULL, "net->Wc[%d] is NULL", i);
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
+  if (!workspace) return fail(PFG_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", cp.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(PFG_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  if (workspace_bytes < cp.total)
+    return fail(PFG_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, cp.total);
+  return PFG_OK;
+}
+
+// A filter gradient of one example must fit a row index of the norm kernel and the scratch block
+// of all examples the element limit of the products.
+int check_convnet_norms(const pfg_convnet *net, int64_t B) {
+  int64_t c = net->channels;
+  for (int i = 0; i < net->num_conv; ++i) {
+    const int64_t k = net->kernel[i], f = net->filters[i];
+    if (k * k * c * f > 0x7fffffffLL || B * k * k * c * f > kMaxElems)
+      return fail(PFG_ERR_OVERFLOW, "the filter gradients of conv block %d are too large for B = %lld", i, (long long)B);
+    c = f;
+  }
+  return PFG_OK;
+}
+
+int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, int64_t B,
+                  float *const *dWc_out, float *const *dbc_out, float *const *dW_out,
+                  float *const *db_out, float *loss_out, const ConvNorms *norms, const ConvPlan &cp,
+                  void *workspace, hipStream_t stream);
 
 }  // namespace
 
@@ -756,20 +803,57 @@ int pfg_convnet_per_example_grads(const pfg_convnet *net, const void *X, const i
   g_err[0] = 0;
   int rc = check_convnet(net, B);
   if (rc) return rc;
-  if ((rc = check_weights(&net->dense))) return rc;
-  if (!net->Wc) return fail(PFG_ERR_NULL, "net->Wc is NULL");
-  for (int i = 0; i < net->num_conv; ++i)
-    if (!net->Wc[i]) return fail(PFG_ERR_NULL, "net->Wc[%d] is NULL", i);
-  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
-  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
   if ((rc = check_elems(&net->dense, B))) return rc;
   const ConvPlan cp = make_conv_plan(net, B);
-  if (!workspace) return fail(PFG_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", cp.total);
-  if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(PFG_ERR_WORKSPACE, "workspace is not 256-byte aligned");
-  if (workspace_bytes < cp.total)
-    return fail(PFG_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, cp.total);
+  if ((rc = check_convnet_call(net, X, labels, B, cp, workspace, workspace_bytes))) return rc;
+  return convnet_sweep(net, X, labels, B, dWc_out, dbc_out, dW_out, db_out, loss_out, nullptr, cp,
+                       workspace, static_cast<hipStream_t>(hip_stream));
+}
 
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+int pfg_convnet_grad_norms_workspace_bytes(const pfg_convnet *net, int64_t B, size_t *bytes) {
+  g_err[0] = 0;
+  int rc = check_convnet(net, B);
+  if (rc) return rc;
+  if (!bytes) return fail(PFG_ERR_NULL, "bytes is NULL");
+  if ((rc = check_elems(&net->dense, B))) return rc;
+  if ((rc = check_convnet_norms(net, B))) return rc;
+  *bytes = make_conv_plan(net, B, true).total;
+  return PFG_OK;
+}
+
+int pfg_convnet_per_example_grad_norms(const pfg_convnet *net, const void *X, const int32_t *labels,
+                                       int64_t B, float *sq_blocks_out, float *norm_out,
+                                       float *loss_out, void *workspace, size_t workspace_bytes,
+                                       void *hip_stream) {
+  g_err[0] = 0;
+  int rc = check_convnet(net, B);
+  if (rc) return rc;
+  if ((rc = check_elems(&net->dense, B))) return rc;
+  if ((rc = check_convnet_norms(net, B))) return rc;
+  if (!sq_blocks_out && !norm_out) return fail(PFG_ERR_NULL, "sq_blocks_out and norm_out are both NULL");
+  const ConvPlan cp = make_conv_plan(net, B, true);
+  if ((rc = check_convnet_call(net, X, labels, B, cp, workspace, workspace_bytes))) return rc;
+  // the filter and bias gradients go to the workspace; only their squared sums leave it
+  const int nc = net->num_conv;
+  std::vector<float *> gW(nc), gb(nc);
+  for (int i = 0; i < nc; ++i) {
+    gW[i] = at(workspace, cp.blocks[i].gW);
+    gb[i] = (net->bc && net->bc[i]) ? at(workspace, cp.blocks[i].gb) : nullptr;
+  }
+  const ConvNorms norms{sq_blocks_out, norm_out};
+  return convnet_sweep(net, X, labels, B, gW.data(), gb.data(), nullptr, nullptr, loss_out, &norms, cp,
+                       workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"
+
+namespace {
+
+int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, int64_t B,
+                  float *const *dWc_out, float *const *dbc_out, float *const *dW_out,
+                  float *const *db_out, float *loss_out, const ConvNorms *norms, const ConvPlan &cp,
+                  void *workspace, hipStream_t stream) {
+  int rc = PFG_OK;
   void *ws = workspace;
   const pfg_mlp *dn = &net->dense;
   const int L = dn->num_layers, nc = net->num_conv;
@@ -793,7 +877,7 @@ int pfg_convnet_per_example_grads(const pfg_convnet *net, const void *X, const i
     g.W = at(ws, blk.dz); g.ldw = blk.co; g.w_kn = 1;
     g.M = kkc; g.N = blk.co; g.K = hw;
     g.epilogue = EPI_NONE;
-    g.C = dWc_out[i]; g.ldc = blk.co; g.streaming = 1;
+    g.C = dWc_out[i]; g.ldc = blk.co; g.streaming = norms ? 0 : 1;   // the norm kernel reads it back
     g.nbatch = (int32_t)B;
     g.batch_A = (int64_t)kkc * hw; g.batch_W = (int64_t)hw * blk.co; g.batch_C = (int64_t)kkc * blk.co;
     return g;
@@ -896,8 +980,46 @@ int pfg_convnet_per_example_grads(const pfg_convnet *net, const void *X, const i
     dout = at(ws, cp.dout[which_dout]);
     PFG_LAUNCH("col2im", launch_col2im(at(ws, blk.P), B, blk.h, blk.w, blk.ci, blk.k, dout, stream));
   }
+  if (!norms) return PFG_OK;
+
+  // ---- squared norms: a conv block's is the sum of squares of the filter and bias gradients
+  // formed above; a dense layer's comes from its two factors, the outer product never formed ----
+  const int cols = nc + L;
+  std::vector<NormLayer> layers(cols);
+  for (int i = 0; i < nc; ++i) {
+    const ConvBlock &blk = cp.blocks[i];
+    NormLayer &ly = layers[i];
+    ly.a = dWc_out[i];
+    ly.g = dbc_out[i];             // null for a block without a bias
+    ly.d_in = blk.k * blk.k * blk.ci * blk.co;
+    ly.d_out = blk.co;
+    ly.sum_mode = 1;
+    ly.index = i;
+  }
+  for (int l = 1; l <= L; ++l) {
+    NormLayer &ly = layers[nc + l - 1];
+    ly.a = (l == 1) ? feat : at(dws, p.act[l - 1]);
+    ly.g = G[l];
+    ly.d_in = d[l - 1];
+    ly.d_out = d[l];
+    ly.has_bias = (bias_of(dn, l) != nullptr);
+    ly.index = nc + l - 1;
+  }
+  if (cols <= kNormLayers) {
+    PFG_LAUNCH("grad_norms", launch_grad_sqnorms(layers.data(), cols, B, norms->sq_blocks, cols, norms->norm, stream));
+  } else {
+    float *sq = norms->sq_blocks ? norms->sq_blocks : at(ws, cp.sq);
+    for (int l0 = 0; l0 < cols; l0 += kNormLayers)
+      PFG_LAUNCH("grad_norms", launch_grad_sqnorms(layers.data() + l0, std::min(kNormLayers, cols - l0), B,
+                                                   sq, cols, nullptr, stream));
+    if (norms->norm) PFG_LAUNCH("grad_norms", launch_norm_finalize(sq, cols, cols, B, norms->norm, stream));
+  }
   return PFG_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 int pfg_jacobian_input(const pfg_mlp *net, const void *X, int64_t B, const float *seeds, int64_t S,
                        int64_t seed_batch_stride, float *J_out, void *workspace,

@@ -239,11 +239,15 @@ class ConvWorkload:
     blocks: Tuple[Tuple[int, int], ...]     # (kernel size, filters) per conv block
     dense: Tuple[int, ...]                  # widths after the flattened features
     B: int
+    call: str = "convnet_per_example_grads"
 
 
 CONV_WORKLOADS: Dict[str, ConvWorkload] = {
     w.name: w for w in [
         ConvWorkload("c10_mnist_convnet_grads", 9, 28, 28, 1, ((5, 32), (5, 64)), (1024, 10), 128),
+        # the same inputs; only the norms of the gradients leave the device
+        ConvWorkload("c10_mnist_convnet_grad_norms", 9, 28, 28, 1, ((5, 32), (5, 64)), (1024, 10), 128,
+                     "convnet_per_example_grad_norms"),
     ]
 }
 

@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert set(names) == set(pfg.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
-    assert lib.pfg_version() == 103
+    assert lib.pfg_version() == 104
 
 
 FAKE = 0x1000  # a non-NULL, 256-aligned value; never dereferenced because validation fails first
@@ -324,6 +324,33 @@ def test_convnet_workspace_and_rejections(lib):
     assert fn(r(net), FAKE, FAKE, 4, o2, o2, o2, o2, None, None, big, None) == pfg.PFG_ERR_WORKSPACE
     assert fn(r(net), FAKE, FAKE, 4, o2, o2, o2, o2, None, FAKE, 1024, None) == pfg.PFG_ERR_WORKSPACE
     assert fn(r(net), FAKE, FAKE, 1 << 20, o2, o2, o2, o2, None, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+
+
+def test_convnet_grad_norms_workspace_and_rejections(lib):
+    net = make_convnet()
+    B = 128
+    n, n0 = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    r = lambda net_: ctypes.byref(net_)
+    assert lib.pfg_convnet_workspace_bytes(r(net), B, ctypes.byref(n0)) == 0
+    assert lib.pfg_convnet_grad_norms_workspace_bytes(r(net), B, ctypes.byref(n)) == 0
+    # the gradients' workspace plus every block's filter and bias gradients and the [B, 2 + 2] sums
+    extra = up(4 * B * 25 * 32) + up(4 * B * 32) + up(4 * B * 800 * 64) + up(4 * B * 64) + up(4 * B * 4)
+    assert n.value == n0.value + extra
+    assert lib.pfg_convnet_grad_norms_workspace_bytes(None, B, ctypes.byref(n)) == pfg.PFG_ERR_NULL
+    assert lib.pfg_convnet_grad_norms_workspace_bytes(r(net), B, None) == pfg.PFG_ERR_NULL
+    assert lib.pfg_convnet_grad_norms_workspace_bytes(r(net), 0, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
+    assert lib.pfg_convnet_grad_norms_workspace_bytes(r(make_convnet(kernel=(5, 6))), B, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
+    fn = lib.pfg_convnet_per_example_grad_norms
+    big = 1 << 40
+    assert fn(r(net), None, FAKE, 4, FAKE, FAKE, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r(net), FAKE, None, 4, FAKE, FAKE, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r(net), FAKE, FAKE, 4, None, None, FAKE, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert "both NULL" in lib.pfg_last_error().decode()
+    assert fn(r(make_convnet(Wc_null=0)), FAKE, FAKE, 4, FAKE, None, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r(net), FAKE, FAKE, 4, FAKE, None, None, None, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(r(net), FAKE, FAKE, 4, FAKE, None, None, FAKE, n0.value // 32, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(r(net), FAKE, FAKE, 4, FAKE, None, None, FAKE + 8, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert "aligned" in lib.pfg_last_error().decode()
 
 
 def make_cond(pre=(784, 512), then_dims=(1024, 10), else_dims=(10,), dtype=0, w=FAKE, W_null_at=None):

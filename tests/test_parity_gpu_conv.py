@@ -165,6 +165,106 @@ def test_c10_mnist_convnet_full_size():
     assert dev_rel < 1e-4
 
 
+def check_conv_norms(inp, tag, examples=None, min_checked=0.5, drop_bias=()):
+    """Gradient norms without the gradients against the oracle's (the gradient formed, its
+    squares summed); drop_bias names parameter blocks (conv blocks first) that lose their bias."""
+    B, h, w, c = inp.X.shape
+    nc = len(inp.Wc)
+    bc = [None if i in drop_bias else v for i, v in enumerate(inp.bc)]
+    bs = [None if nc + l in drop_bias else v for l, v in enumerate(inp.bs)]
+    onet = oconv.ConvNet(h, w, c, inp.Wc, bc, inp.Ws, bs)
+    net = pfg.ConvNet.from_numpy(h, w, c, inp.Wc, bc, inp.Ws, bs)
+    cols = nc + net.dense.L
+    out = (nan_like(B, cols), nan_like(B), nan_like(B))
+    sq, norm, loss = pfg.pfg_convnet_per_example_grad_norms(net, dev(inp.X), dev(inp.labels), out=out)
+    torch.cuda.synchronize()
+    got = [t.cpu().numpy() for t in (sq, norm, loss)]
+    for n, a in zip(("sq", "norm", "loss"), got):
+        assert np.isfinite(a).all(), f"{n} was not written in full"
+    biased = type(inp)(inp.workload, inp.Wc, [np.zeros_like(v) if b is None else b for v, b in zip(inp.bc, bc)],
+                       inp.Ws, [np.zeros_like(v) if b is None else b for v, b in zip(inp.bs, bs)], inp.X, inp.labels)
+    margins = decision_margins(biased)
+    idx = [b for b in (range(B) if examples is None else examples) if margins[b] >= MARGIN]
+    total = B if examples is None else len(list(examples))
+    say(f"  {tag}: {len(idx)} of {total} examples are at least {MARGIN:g} from every decision boundary")
+    assert len(idx) >= min_checked * total
+    rsq, rnorm, rloss = oconv.per_example_grad_norms(onet, inp.X[idx], inp.labels[idx])
+    worst = 0.0
+    for j in range(cols):                       # every column against its own scale
+        e = float(np.max(np.abs(got[0][idx, j] - rsq[:, j]) / np.maximum(np.abs(rsq[:, j]), 1e-300)))
+        say(f"  {tag} sq[:, {j}] rel err {e:.3e}")
+        worst = max(worst, e)
+    e = float(np.max(np.abs(got[1][idx] - rnorm) / rnorm))
+    say(f"  {tag} norm rel err {e:.3e}")
+    worst = max(worst, e, slice_rel_err(got[2][idx], rloss, lead=0))
+    assert worst <= TOL_F32, f"{tag}: max relative error {worst:.3e}"
+    return net, (sq, norm, loss)
+
+
+NORM_SHAPES = [
+    # height, width, channels, blocks, dense, B, parameter blocks without a bias
+    (4, 4, 1, ((3, 2),), (3,), 2, ()),
+    (8, 8, 2, ((3, 3), (3, 5)), (6, 4), 3, (0, 3)),
+    (2, 2, 1, ((1, 1),), (2,), 1, ()),
+    (12, 8, 3, ((5, 4), (3, 6)), (9, 40), 5, (1,)),
+    (16, 16, 1, ((5, 8), (5, 16), (3, 8)), (10,), 4, ()),
+    (20, 12, 2, ((7, 5),), (33, 7), 70, (0, 1, 2)),
+    (8, 12, 4, ((3, 12), (3, 8)), (11, 6), 140, ()),
+    (8, 8, 8, ((3, 64),), (9,), 70, ()),
+]
+
+
+@pytest.mark.parametrize("h,w,c,blocks,dense,B,drop", NORM_SHAPES,
+                         ids=[f"{s[0]}x{s[1]}x{s[2]}-{len(s[3])}blocks-B{s[5]}" for s in NORM_SHAPES])
+def test_convnet_grad_norms_odd_shapes(h, w, c, blocks, dense, B, drop):
+    say(f"convnet norms {h}x{w}x{c} blocks={blocks} dense={dense} B={B} without bias: {drop}")
+    wk = wl.ConvWorkload("oddn", 600 + h + w + B, h, w, c, blocks, dense, B)
+    inp = wl.make_conv_inputs(wk, bias_scale=0.2)
+    check_conv_norms(inp, "conv-norms-odd", drop_bias=drop)
+
+
+def test_convnet_grad_norms_agree_with_the_gradients_and_skip_outputs():
+    wk = wl.ConvWorkload("normc", 560, 8, 8, 2, ((3, 4), (3, 6)), (8, 5), 9)
+    inp = wl.make_conv_inputs(wk, bias_scale=0.2)
+    net, (sq, norm, loss) = check_conv_norms(inp, "conv-norms")
+    X, labels = dev(inp.X), dev(inp.labels)
+    # the same sweep produced the gradients: their squared sums agree to rounding for EVERY example
+    dWc, dbc, dW, db, loss_g = pfg.pfg_convnet_per_example_grads(net, X, labels)
+    torch.cuda.synchronize()
+    want = torch.stack([(a.double() ** 2).flatten(1).sum(1) + (b.double() ** 2).sum(1)
+                        for a, b in zip(dWc + dW, dbc + db)], dim=1)
+    assert ((sq.double() - want).abs() / want).max().item() < 1e-5
+    assert torch.equal(loss, loss_g)
+    # either output alone
+    only_norm = pfg.pfg_convnet_per_example_grad_norms(net, X, labels, want_sq=False, want_loss=False)
+    only_sq = pfg.pfg_convnet_per_example_grad_norms(net, X, labels, want_norm=False)
+    torch.cuda.synchronize()
+    assert only_norm[0] is None and only_norm[2] is None and torch.equal(only_norm[1], norm)
+    assert only_sq[1] is None and torch.equal(only_sq[0], sq)
+    with pytest.raises(pfg.PfgError) as ei:
+        pfg.pfg_convnet_per_example_grad_norms(net, X, labels, want_sq=False, want_norm=False)
+    assert ei.value.code == pfg.PFG_ERR_NULL
+    # the gradients' workspace is too small for the norms
+    small = torch.empty(pfg.pfg_convnet_workspace_bytes(net, wk.B), dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(pfg.PfgError) as ei:
+        pfg.pfg_convnet_per_example_grad_norms(net, X, labels, workspace=small)
+    assert ei.value.code == pfg.PFG_ERR_WORKSPACE
+
+
+def test_c10_mnist_convnet_grad_norms_full_size():
+    wk = wl.CONV_WORKLOADS["c10_mnist_convnet_grad_norms"]
+    say("c10_mnist_convnet_grad_norms: full size (128 images, 28 x 28), sampled examples")
+    inp = wl.make_conv_inputs(wk)
+    picks = sorted(set([0, wk.B - 1] + np.random.default_rng(11).integers(0, wk.B, size=24).tolist()))
+    net, (sq, norm, loss) = check_conv_norms(inp, "c10-norms", examples=picks)
+    # properties that hold for every example
+    assert torch.isfinite(sq).all() and (sq >= 0).all()
+    assert ((norm.double() ** 2 - sq.double().sum(1)).abs() / sq.double().sum(1)).max().item() < 1e-5
+    # the last layer's block from the softmax alone: (|a|^2 + 1) |p - onehot|^2 >= |p - onehot|^2
+    p_label = torch.exp(-loss.double())
+    assert (sq[:, -1].double() >= (1.0 - p_label) ** 2 * (1 - 1e-5)).all()
+
+
 def test_convnet_rejects_bad_arguments():
     wk = wl.ConvWorkload("badc", 541, 6, 6, 1, ((3, 2),), (4,), 2)      # 6 -> 3: fine for one block
     inp = wl.make_conv_inputs(wk)
