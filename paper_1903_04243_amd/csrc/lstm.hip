@@ -73,11 +73,11 @@ __global__ __launch_bounds__(kThreads) void lstm_cell_backward_kernel(
 // out[b, i, j] = sum_{t < nt} a[b * a_bs + t * a_ts + i] * g[b * g_bs + t * g_ts + j]
 // (Section 3.4's both-operands-stacked matmul with a contraction over the time steps).  A lane keeps
 // its four columns of all nt cotangent rows in registers and walks the rows i of its chunk; the a
-// values of the chunk (uniform over the workgroup) are fetched once into LDS.  kMaxSteps steps per
-// pass; later passes add to the result.  One launch covers up to two row blocks of the same
+// values of the chunk (uniform over the workgroup) are fetched once into LDS.  At most kMaxSteps
+// steps per pass; later passes add to the result.  One launch covers up to two row blocks of the same
 // per-example matrix (here: the input rows and the recurrent rows of the LSTM weight gradient).
 constexpr int kMaxSteps = 16;
-constexpr int kRowsPerBlock = 8;     // measured best of 4 / 8 / 16 / 32 on the 384 x 1024 gradient
+constexpr int kRowsPerBlock = 4;     // measured best of 2 / 4 / 8 / 16 on the 384 x 1024 gradient
 
 struct OuterSumPart {
   const float *a; int64_t a_bs, a_ts;
@@ -96,8 +96,11 @@ struct OuterSumArgs {
   int vec;               // d_out % 4 == 0 and g, out 16-byte aligned with aligned strides
 };
 
+// NT: the steps of a pass rounded up to a multiple of 4 (a step past nt holds zeros), so that short
+// loops over the steps pay for the steps they have.
+template <int NT>
 __global__ __launch_bounds__(kThreads) void outer_sum_kernel(const OuterSumArgs p) {
-  __shared__ float a_s[kMaxSteps][kRowsPerBlock];
+  __shared__ __align__(16) float a_s[kRowsPerBlock][NT];
   const int64_t b = blockIdx.y;
   const int col_chunks = (p.d_out + 4 * kThreads - 1) / (4 * kThreads);
   const int cchunk = blockIdx.x % col_chunks;
@@ -110,17 +113,17 @@ __global__ __launch_bounds__(kThreads) void outer_sum_kernel(const OuterSumArgs 
   const float *a = q.a + b * q.a_bs;
   const float *g = q.g + b * q.g_bs;
   float *out = q.out + b * p.out_bs;
-  // the chunk's a values: one coalesced fetch of nt rows of 16 values
-  for (int e = threadIdx.x; e < kMaxSteps * kRowsPerBlock; e += kThreads) {
+  // the chunk's a values: adjacent lanes fetch adjacent rows of one step; kept step-fastest
+  for (int e = threadIdx.x; e < NT * kRowsPerBlock; e += kThreads) {
     const int t = e / kRowsPerBlock, r = e % kRowsPerBlock;
-    a_s[t][r] = (t < q.nt && r < nrows) ? a[t * q.a_ts + i0 + r] : 0.f;
+    a_s[r][t] = (t < q.nt && r < nrows) ? a[t * q.a_ts + i0 + r] : 0.f;
   }
   __syncthreads();
   const int j = (cchunk * kThreads + threadIdx.x) * 4;
   if (j >= p.d_out) return;
-  f32x4 gv[kMaxSteps];
+  f32x4 gv[NT];
 #pragma unroll
-  for (int t = 0; t < kMaxSteps; ++t) {
+  for (int t = 0; t < NT; ++t) {
     gv[t] = f32x4{0.f, 0.f, 0.f, 0.f};
     if (t < q.nt) {
       if (p.vec) {
@@ -135,7 +138,11 @@ __global__ __launch_bounds__(kThreads) void outer_sum_kernel(const OuterSumArgs 
   for (int r = 0; r < nrows; ++r) {
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int t = 0; t < kMaxSteps; ++t) acc += a_s[t][r] * gv[t];     // steps past nt hold zeros
+    for (int t4 = 0; t4 < NT; t4 += 4) {
+      const f32x4 av = *reinterpret_cast<const f32x4 *>(&a_s[r][t4]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc += av[e] * gv[t4 + e];           // steps past nt hold zeros
+    }
     float *o = out + (int64_t)(i0 + r) * p.d_out + j;
     if (p.vec) {
       if (p.accumulate)
@@ -312,8 +319,12 @@ hipError_t launch_outer_sum(const OuterSumJob *jobs, int njobs, int64_t B, int32
         row_chunks += q.row_chunks;
       }
       p.nparts = njobs; p.out_bs = out_bs; p.d_out = d_out; p.accumulate = t0 > 0; p.vec = vec;
-      PFG_KERNEL(outer_sum_kernel, dim3((unsigned)(col_chunks * row_chunks), (unsigned)nb),
-                 dim3(kThreads), 0, stream, p);
+      const dim3 grid((unsigned)(col_chunks * row_chunks), (unsigned)nb);
+      const int pass_nt = max_nt - t0;
+      if (pass_nt <= 4)       PFG_KERNEL(outer_sum_kernel<4>, grid, dim3(kThreads), 0, stream, p);
+      else if (pass_nt <= 8)  PFG_KERNEL(outer_sum_kernel<8>, grid, dim3(kThreads), 0, stream, p);
+      else if (pass_nt <= 12) PFG_KERNEL(outer_sum_kernel<12>, grid, dim3(kThreads), 0, stream, p);
+      else                    PFG_KERNEL(outer_sum_kernel<kMaxSteps>, grid, dim3(kThreads), 0, stream, p);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
       t0 += kMaxSteps;
