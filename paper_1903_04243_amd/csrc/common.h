@@ -178,6 +178,16 @@ hipError_t launch_scale_rows(const void *in, int32_t in_bf16, int64_t in_batch_s
                              const float *mask, int64_t ld_mask, int64_t B, int64_t S, int32_t d,
                              float *out, int64_t ld_out, hipStream_t stream);
 
+// A product with few output tiles and a long contraction (M = B rows against a wide layer) re-reads
+// its operands once per tile of the other operand and keeps few compute units busy.  Cutting the
+// contraction into Z pieces, one batch entry of the tiled kernel each, gives Z times the
+// workgroups on large tiles; a second kernel adds the Z partial results [Z, M, N] (float32, from
+// the caller) in a fixed order and applies the epilogue.  The functions below return the Z to use,
+// 1 when the product should be launched as it is.
+int split_k_shape(int64_t M, int64_t N, int64_t K);   // from the shape alone (for sizing the partials)
+int split_k_factor(const GemmArgs &g);                // 1 also when an operand's alignment rules it out
+hipError_t launch_gemm_split(const GemmArgs &g, int Z, float *partials, hipStream_t stream);
+
 // Squared gradient norms of the parameter blocks of a launch (at most kNormLayers per launch):
 //   sq[b * ld_sq + index] = (|a[b, :]|^2 + (has_bias ? 1 : 0)) * |g[b, :]|^2       a dense layer
 //   sq[b * ld_sq + index] = |a[b, :]|^2 + (g ? |g[b, :]|^2 : 0)      sum_mode: a gradient at hand
@@ -261,6 +271,13 @@ hipError_t launch_relu_pool(const float *z, int64_t B, int32_t h, int32_t w, int
 // dz [B, h, w, c] from the cotangent of the pooled output (relu' and the window selection applied)
 hipError_t launch_unpool_mask(const float *dpooled, const float *pooled, const uint8_t *which, int64_t B,
                               int32_t h, int32_t w, int32_t c, float *dz, hipStream_t stream);
+
+// The same in one launch with db [B, c] = sum over the positions of dz; only for the shapes and
+// alignments unpool_mask_sum_applies accepts.
+bool unpool_mask_sum_applies(const float *dpooled, const float *pooled, const uint8_t *which, int64_t B,
+                             int32_t h, int32_t w, int32_t c, const float *dz, const float *db);
+hipError_t launch_unpool_mask_sum(const float *dpooled, const float *pooled, const uint8_t *which, int64_t B,
+                                  int32_t h, int32_t w, int32_t c, float *dz, float *db, hipStream_t stream);
 
 // din [B, h, w, c] = gather of the patch cotangents dP [B h w, k k c]
 hipError_t launch_col2im(const float *dP, int64_t B, int32_t h, int32_t w, int32_t c, int32_t k,

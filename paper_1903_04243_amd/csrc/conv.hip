@@ -279,6 +279,53 @@ __global__ __launch_bounds__(kThreads) void unpool_mask_kernel(const float *dpoo
   }
 }
 
+// The same with the bias gradient db[b, ch] = sum over the positions of dz[b, ., ., ch] produced on
+// the way.  A window hands its cotangent to at most one of its entries, so the sum runs over the
+// pooled cells.  One workgroup per example; a thread stays with one group of four channels (the
+// threads in use are a multiple of the number of groups), and the threads of a group are added in a
+// fixed order through LDS, so the result does not depend on timing.  c % 4 == 0, c <= 4 kThreads,
+// 16-byte aligned operands.
+__global__ __launch_bounds__(kThreads) void unpool_mask_sum_kernel(const float *dpooled, const float *pooled,
+                                                                   const uint8_t *which, int h, int w, int c,
+                                                                   float *dz, float *db) {
+  __shared__ f32x4 part[kThreads];
+  const int64_t b = blockIdx.x;
+  const int ho = h / 2, wo = w / 2, c4 = c / 4;
+  const int units = ho * wo * c4;
+  const int lanes = (kThreads / c4) * c4;
+  const int tid = threadIdx.x;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  if (tid < lanes) {
+    const int ch = (tid % c4) * 4;
+    for (int u = tid; u < units; u += lanes) {
+      const int cell = u / c4;
+      const int xo = cell % wo, yo = cell / wo;
+      const int64_t i = b * units + u;
+      const f32x4 p = *reinterpret_cast<const f32x4 *>(pooled + 4 * i);
+      const f32x4 dp = *reinterpret_cast<const f32x4 *>(dpooled + 4 * i);
+      const uint32_t arg = *reinterpret_cast<const uint32_t *>(which + 4 * i);
+      f32x4 live;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) live[q] = p[q] > 0.f ? dp[q] : 0.f;
+      acc += live;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        f32x4 out;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) out[q] = (((arg >> (8 * q)) & 0xffu) == (uint32_t)d) ? live[q] : 0.f;
+        *reinterpret_cast<f32x4 *>(dz + ((b * h + 2 * yo + (d >> 1)) * w + 2 * xo + (d & 1)) * c + ch) = out;
+      }
+    }
+  }
+  part[tid] = acc;
+  __syncthreads();
+  if (tid < c4) {
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int t = tid; t < lanes; t += c4) s += part[t];
+    *reinterpret_cast<f32x4 *>(db + b * c + 4 * tid) = s;
+  }
+}
+
 // din[b, yy, xx, ch] = sum over the patches that contain the pixel of their cotangent entry:
 // dP[(b, yy - ky + p, xx - kx + p), (ky, kx, ch)].  A gather in a fixed order (no atomics).
 __global__ __launch_bounds__(kThreads) void col2im_kernel(const float *dP, int64_t B, int h, int w, int c,
@@ -373,6 +420,25 @@ hipError_t launch_unpool_mask(const float *dpooled, const float *pooled, const u
   if (total <= 0) return hipSuccess;
   PFG_KERNEL(unpool_mask_kernel, dim3(capped_blocks(total)), dim3(kThreads), 0, stream, dpooled, pooled,
              which, B, h, w, c, dz);
+  return hipGetLastError();
+}
+
+bool unpool_mask_sum_applies(const float *dpooled, const float *pooled, const uint8_t *which, int64_t B,
+                             int32_t h, int32_t w, int32_t c, const float *dz, const float *db) {
+  // a workgroup per example: worth it once the examples alone give the chip enough workgroups
+  if (B < 32 || B > 0x7fffffffLL || c % 4 != 0 || c > 4 * kThreads) return false;
+  if ((int64_t)(h / 2) * (w / 2) * (c / 4) > 0x7fffffffLL) return false;
+  return (reinterpret_cast<uintptr_t>(which) & 3) == 0 &&
+         ((reinterpret_cast<uintptr_t>(dpooled) | reinterpret_cast<uintptr_t>(pooled) |
+           reinterpret_cast<uintptr_t>(dz) | reinterpret_cast<uintptr_t>(db)) & 15) == 0;
+}
+
+hipError_t launch_unpool_mask_sum(const float *dpooled, const float *pooled, const uint8_t *which, int64_t B,
+                                  int32_t h, int32_t w, int32_t c, float *dz, float *db, hipStream_t stream) {
+  if (B <= 0 || (int64_t)(h / 2) * (w / 2) * c <= 0) return hipSuccess;
+  if (!unpool_mask_sum_applies(dpooled, pooled, which, B, h, w, c, dz, db)) return hipErrorInvalidValue;
+  PFG_KERNEL(unpool_mask_sum_kernel, dim3((unsigned)B), dim3(kThreads), 0, stream, dpooled, pooled, which,
+             h, w, c, dz, db);
   return hipGetLastError();
 }
 

@@ -134,6 +134,33 @@ __global__ __launch_bounds__(kThreads) void act_from_z_kernel(const float *z, in
   }
 }
 
+// Second half of a product whose contraction was cut into Z pieces (see launch_gemm_split): adds
+// the Z partial results [Z, M, N] in a fixed order and applies the epilogue of the whole product.
+__global__ __launch_bounds__(kThreads) void split_finish_kernel(const float *part, int Z, int64_t mn, int N,
+                                                                const void *bias, int bias_bf16, int epilogue,
+                                                                int act, float *C, float *C2, int64_t ldc) {
+  const int64_t step = (int64_t)gridDim.x * kThreads;
+  for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < mn / 4; q += step) {
+    const int64_t i = 4 * q;
+    const int64_t m = i / N;
+    const int n = (int)(i - m * N);
+    f32x4 v = *reinterpret_cast<const f32x4 *>(part + i);
+    for (int z = 1; z < Z; ++z) v += *reinterpret_cast<const f32x4 *>(part + z * mn + i);
+    if (bias && epilogue != EPI_NONE) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        v[e] += bias_bf16 ? (float)static_cast<const __bf16 *>(bias)[n + e] : static_cast<const float *>(bias)[n + e];
+    }
+    f32x4 out = v, out2 = v;
+    if (epilogue == EPI_FORWARD) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { out[e] = dev::act_value(act, v[e]); out2[e] = dev::act_deriv(act, v[e]); }
+    }
+    if (C) *reinterpret_cast<f32x4 *>(C + m * ldc + n) = out;
+    if (C2 && epilogue == EPI_FORWARD) *reinterpret_cast<f32x4 *>(C2 + m * ldc + n) = out2;
+  }
+}
+
 // out[(b, s), j] = in[b, s, j] * mask[b, j]: the mask of a layer does not depend on the inner
 // iteration index s and is broadcast over it (Section 3.4: loop-invariant operands are not stacked).
 __global__ __launch_bounds__(kThreads) void scale_rows_kernel(const void *in, int in_bf16,
@@ -276,6 +303,44 @@ hipError_t launch_scale_rows(const void *in, int32_t in_bf16, int64_t in_batch_s
   if (rows <= 0 || d <= 0) return hipSuccess;
   PFG_KERNEL(scale_rows_kernel, dim3(capped_blocks(rows * d)), dim3(kThreads), 0, stream, in, in_bf16,
              in_batch_stride, ld_in, mask, ld_mask, rows, S, d, out, ld_out);
+  return hipGetLastError();
+}
+
+int split_k_factor(const GemmArgs &g) {
+  auto aligned = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
+  if (g.bf16 || !g.a_is_f32 || g.a_scale || g.nbatch > 1 || g.sub || g.sym_n > 0 || g.a_km || g.S != 1) return 1;
+  if (g.epilogue != EPI_NONE && g.epilogue != EPI_BIAS && g.epilogue != EPI_FORWARD) return 1;
+  if (!g.w_kn) return 1;       // weights in [N, K] layout (cotangent steps): measured no faster when cut
+  if (g.ldc % 4 || g.lda % 4 || g.ldw % 4) return 1;
+  if (!aligned(g.A) || !aligned(g.W) || (g.C && !aligned(g.C)) || (g.C2 && !aligned(g.C2))) return 1;
+  return split_k_shape(g.M, g.N, g.K);
+}
+
+int split_k_shape(int64_t M, int64_t N, int64_t K) {
+  if (M < 64 || N < 256 || N % 4 || K < 1024) return 1;
+  const int64_t tiles64 = ((M + 63) / 64) * ((N + 63) / 64);
+  if (tiles64 >= 128) return 1;                  // the tiled kernel already fills the chip
+  for (int Z = 8; Z >= 2; Z /= 2)
+    if (K % (4 * Z) == 0 && K / Z >= 256 && Z * tiles64 <= 512) return Z;
+  return 1;
+}
+
+hipError_t launch_gemm_split(const GemmArgs &g, int Z, float *partials, hipStream_t stream) {
+  if (Z < 2 || Z != split_k_factor(g) || !partials) return hipErrorInvalidValue;
+  const int Kz = g.K / Z;
+  GemmArgs b = g;
+  b.K = Kz;
+  b.nbatch = Z;
+  b.batch_A = Kz;                                       // piece z: columns z Kz .. of A,
+  b.batch_W = (int64_t)Kz * g.ldw;                      // rows z Kz .. of W [K, N]
+  b.batch_C = (int64_t)g.M * g.N;
+  b.C = partials; b.ldc = g.N; b.C2 = nullptr;
+  b.epilogue = EPI_NONE; b.bias = nullptr; b.streaming = 0;
+  hipError_t e = launch_gemm(b, stream);
+  if (e != hipSuccess) return e;
+  const int64_t mn = (int64_t)g.M * g.N;
+  PFG_KERNEL(split_finish_kernel, dim3(capped_blocks(mn / 4)), dim3(kThreads), 0, stream, partials, Z, mn, g.N,
+             g.bias, g.bf16, g.epilogue, g.act, g.C, g.C2, g.ldc);
   return hipGetLastError();
 }
 

@@ -170,6 +170,7 @@ struct Plan {
   size_t total = 0;
   std::vector<size_t> act, dphi, d2phi, G;   // indexed by layer l (1-based; entry 0 unused)
   size_t logits = 0, P = 0, ping = 0, pong = 0, sq = 0, U = 0, Cc = 0;
+  size_t splitk = 0;                  // partial results of a product cut along its contraction, or 0
   int64_t ktot = 0;                   // Hessian: sum of the hidden widths
   std::vector<int64_t> koff;          // Hessian: column offset of hidden layer l in U and Cc
   size_t take(size_t bytes) {
@@ -222,6 +223,15 @@ Plan make_plan(const pfg_mlp *net, int op, int64_t B, int64_t S) {
     p.logits = p.take(sizeof(float) * B * d[L]);
     for (int l = 1; l <= L; ++l) p.G[l] = p.take(sizeof(float) * rows * d[l]);
     if (op == PFG_OP_GRAD_NORMS) p.sq = p.take(sizeof(float) * B * L);
+    if (net->dtype == PFG_F32 && rows == B) {
+      // the largest [Z, B, width] block a forward layer needs
+      size_t most = 0;
+      for (int l = 1; l <= L; ++l) {
+        const int z = split_k_shape(B, d[l], d[l - 1]);
+        if (z > 1) most = std::max(most, sizeof(float) * z * B * d[l]);
+      }
+      if (most) p.splitk = p.take(most);
+    }
   }
   if (p.total == 0) p.total = 256;
   return p;
@@ -288,7 +298,11 @@ int forward(const pfg_mlp *net, const void *X, int64_t B, int upto, void *ws, co
       g.epilogue = EPI_BIAS;
       g.C = at(ws, p.logits);
     }
-    PFG_LAUNCH("gemm_forward", launch_gemm(g, stream));
+    const int Z = p.splitk ? split_k_factor(g) : 1;
+    if (Z > 1)
+      PFG_LAUNCH("gemm_forward", launch_gemm_split(g, Z, at(ws, p.splitk), stream));
+    else
+      PFG_LAUNCH("gemm_forward", launch_gemm(g, stream));
   }
   return PFG_OK;
 }
@@ -958,11 +972,16 @@ int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, 
     const int hw = blk.h * blk.w, kkc = blk.k * blk.k * blk.ci;
     const int64_t rows = B * hw;
     float *dz = at(ws, blk.dz);
-    PFG_LAUNCH("unpool_mask", launch_unpool_mask(dout, at(ws, blk.pooled),
-                                                 reinterpret_cast<const uint8_t *>(static_cast<char *>(ws) + blk.which),
-                                                 B, blk.h, blk.w, blk.co, dz, stream));
-    if (dbc_out && dbc_out[i])
-      PFG_LAUNCH("sum_positions", launch_sum_steps(dz, B, hw, blk.co, dbc_out[i], at(ws, cp.psum), stream));
+    const uint8_t *which = reinterpret_cast<const uint8_t *>(static_cast<char *>(ws) + blk.which);
+    float *dbc = dbc_out ? dbc_out[i] : nullptr;
+    if (dbc && unpool_mask_sum_applies(dout, at(ws, blk.pooled), which, B, blk.h, blk.w, blk.co, dz, dbc)) {
+      PFG_LAUNCH("unpool_mask", launch_unpool_mask_sum(dout, at(ws, blk.pooled), which, B, blk.h, blk.w,
+                                                     blk.co, dz, dbc, stream));
+    } else {
+      PFG_LAUNCH("unpool_mask", launch_unpool_mask(dout, at(ws, blk.pooled), which, B, blk.h, blk.w, blk.co,
+                                                   dz, stream));
+      if (dbc) PFG_LAUNCH("sum_positions", launch_sum_steps(dz, B, hw, blk.co, dbc, at(ws, cp.psum), stream));
+    }
     if (dWc_out && dWc_out[i])
       PFG_LAUNCH("conv_gemm_filter", launch_gemm(filter_product(i, filter_reads_P(i)), stream));
     bool lower = false;

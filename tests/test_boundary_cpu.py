@@ -65,6 +65,11 @@ def test_workspace_sizes(lib):
     assert n == expect
     # per-example gradients ignore S
     assert ws_bytes(lib, net, 0, B, 77) == (0, expect)
+    # few rows, a wide layer and a long contraction: room for the 8 partial results [8, B, 1024] of
+    # the first forward product, which is cut along its contraction
+    wide = make_net([3136, 1024, 10])
+    assert ws_bytes(lib, wide, 0, B, 1) == (0, 2 * up(4 * B * 1024) + up(4 * B * 10) + up(4 * B * 1024) +
+                                            up(4 * B * 10) + up(4 * 8 * B * 1024))
     net3 = make_net([1024, 2048, 2048, 1024], act=2)
     rc, n = ws_bytes(lib, net3, 1, 64, 1024)
     assert rc == 0

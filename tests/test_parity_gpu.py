@@ -332,6 +332,25 @@ def test_large_batch_takes_the_tiled_kernels(oracle, dtype):
     assert e <= tol
 
 
+def test_long_contractions_are_cut_into_pieces(oracle):
+    # few rows against wide layers with long contractions: the forward products (K = 2048 and 1024)
+    # are computed as 8 and 4 partial products that a second kernel adds; 96 rows leave a ragged
+    # row tile
+    dims, B, act = (2048, 1024, 1280, 10), 96, "tanh"
+    say(f"split contraction: dims {dims} B={B}")
+    w = wl.Workload("splitk", 61, "per_example_grads", dims, act, "f32", B, "normal", "normal_fan_in")
+    inp = draw(w, bias_scale=0.2)
+    check_grads(oracle, inp, act, "f32", TOL_F32, want_dW=[False, True, True], tag="splitk")
+    onet = oracle.Net(inp.Ws, inp.bs, act)
+    net = gpu_net(inp, act, "f32")
+    rsq, _ = oracle.per_example_grad_norms(onet, inp.X, inp.labels)
+    sq, norm, _ = pfg.pfg_per_example_grad_norms(net, gpu_x(inp, "f32"), dev(inp.labels))
+    torch.cuda.synchronize()
+    e = float(np.max(np.abs(sq.cpu().numpy() - rsq) / rsq))
+    say(f"  splitk norms rel err {e:.3e}")
+    assert e <= TOL_F32
+
+
 def test_deep_network_and_wide_seed_block(oracle):
     # five layers; weight Jacobian with shared seeds S = 40 > d_L, all layers, softmax head
     dims, B, act = (24, 48, 40, 56, 32, 20), 9, "tanh"
