@@ -251,6 +251,19 @@ def test_convnet_grad_norms_agree_with_the_gradients_and_skip_outputs():
     assert ei.value.code == pfg.PFG_ERR_WORKSPACE
 
 
+def test_convnet_grad_norms_with_more_blocks_than_one_launch_takes():
+    # 2 conv blocks + 17 dense layers = 19 parameter blocks: the norm kernel takes 16 per launch, the
+    # whole-gradient norm then comes from a finishing kernel (from the workspace when no per-block
+    # output is asked for)
+    wk = wl.ConvWorkload("deepn", 561, 8, 8, 1, ((3, 2), (3, 3)), (6,) * 16 + (4,), 5)
+    inp = wl.make_conv_inputs(wk, bias_scale=0.3)
+    net, (sq, norm, loss) = check_conv_norms(inp, "conv-norms-deep", min_checked=0.2)
+    assert sq.shape == (5, 19)
+    only_norm = pfg.pfg_convnet_per_example_grad_norms(net, dev(inp.X), dev(inp.labels), want_sq=False)
+    torch.cuda.synchronize()
+    assert only_norm[0] is None and torch.equal(only_norm[1], norm)
+
+
 def test_c10_mnist_convnet_grad_norms_full_size():
     wk = wl.CONV_WORKLOADS["c10_mnist_convnet_grad_norms"]
     say("c10_mnist_convnet_grad_norms: full size (128 images, 28 x 28), sampled examples")
