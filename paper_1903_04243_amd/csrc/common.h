@@ -184,9 +184,17 @@ hipError_t launch_scale_rows(const void *in, int32_t in_bf16, int64_t in_batch_s
 // workgroups on large tiles; a second kernel adds the Z partial results [Z, M, N] (float32, from
 // the caller) in a fixed order and applies the epilogue.  The functions below return the Z to use,
 // 1 when the product should be launched as it is.
-int split_k_shape(int64_t M, int64_t N, int64_t K);   // from the shape alone (for sizing the partials)
+int split_k_shape(int64_t M, int64_t N, int64_t K, int bf16);   // from the shape alone (for sizing the partials)
 int split_k_factor(const GemmArgs &g);                // 1 also when an operand's alignment rules it out
 hipError_t launch_gemm_split(const GemmArgs &g, int Z, float *partials, hipStream_t stream);
+
+// The loss head of a last layer with a long contraction and few rows: Z partial products of the
+// logits (batch entries of the tiled kernel, partials [Z, M, N] float32 from the caller), then one
+// kernel that adds them and does what EPI_HEAD does after its product.  g as for EPI_HEAD.  The
+// functions return the Z to use, 1 when the fused head should run.
+int head_split_shape(int64_t M, int64_t N, int64_t K);
+int head_split_pieces(const GemmArgs &g);
+hipError_t launch_head_split(const GemmArgs &g, int Z, float *partials, hipStream_t stream);
 
 // Squared gradient norms of the parameter blocks of a launch (at most kNormLayers per launch):
 //   sq[b * ld_sq + index] = (|a[b, :]|^2 + (has_bias ? 1 : 0)) * |g[b, :]|^2       a dense layer

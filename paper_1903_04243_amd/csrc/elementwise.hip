@@ -308,20 +308,26 @@ hipError_t launch_scale_rows(const void *in, int32_t in_bf16, int64_t in_batch_s
 
 int split_k_factor(const GemmArgs &g) {
   auto aligned = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
-  if (g.bf16 || !g.a_is_f32 || g.a_scale || g.nbatch > 1 || g.sub || g.sym_n > 0 || g.a_km || g.S != 1) return 1;
+  if (g.a_scale || g.nbatch > 1 || g.sub || g.sym_n > 0 || g.a_km || g.S != 1) return 1;
+  if (!g.bf16 && !g.a_is_f32) return 1;
   if (g.epilogue != EPI_NONE && g.epilogue != EPI_BIAS && g.epilogue != EPI_FORWARD) return 1;
   if (!g.w_kn) return 1;       // weights in [N, K] layout (cotangent steps): measured no faster when cut
-  if (g.ldc % 4 || g.lda % 4 || g.ldw % 4) return 1;
+  if (g.ldc % 4 || g.lda % 8 || g.ldw % 8) return 1;
   if (!aligned(g.A) || !aligned(g.W) || (g.C && !aligned(g.C)) || (g.C2 && !aligned(g.C2))) return 1;
-  return split_k_shape(g.M, g.N, g.K);
+  return split_k_shape(g.M, g.N, g.K, g.bf16);
 }
 
-int split_k_shape(int64_t M, int64_t N, int64_t K) {
-  if (M < 64 || N < 256 || N % 4 || K < 1024) return 1;
+int split_k_shape(int64_t M, int64_t N, int64_t K, int bf16) {
+  if (M < 64 || N < 256 || N % 8 || K < 1024) return 1;
   const int64_t tiles64 = ((M + 63) / 64) * ((N + 63) / 64);
-  if (tiles64 >= 128) return 1;                  // the tiled kernel already fills the chip
-  for (int Z = 8; Z >= 2; Z /= 2)
-    if (K % (4 * Z) == 0 && K / Z >= 256 && Z * tiles64 <= 512) return Z;
+  if (tiles64 < 128) {                            // too few tiles for the chip: up to 8 pieces
+    for (int Z = 8; Z >= 2; Z /= 2)
+      if (K % (8 * Z) == 0 && K / Z >= 256 && Z * tiles64 <= 512) return Z;
+    return 1;
+  }
+  // bf16 products with one workgroup per compute unit are bound by the instruction issue of its
+  // single wave per SIMD; two pieces give every unit a second workgroup
+  if (bf16 && tiles64 <= 256 && K >= 2048 && K % 128 == 0) return 2;
   return 1;
 }
 

@@ -17,53 +17,6 @@ namespace {
 
 using namespace dev;
 
-// Cotangent step through the last layer for the 32 rows of a head tile, on the vector ALUs (the
-// contraction is only N <= 32 = 4 N4 long):
-//     g_prev[m, i] = phi'(z[m, i]) * sum_j delta[m, j] * W[i, j]
-// The columns i of one tile are shared out over the `groups` workgroups that computed the same
-// tile (group index `cg`); inside a workgroup a thread owns one column and one band of rows
-// (consecutive threads store consecutive i of a row).  It keeps W[i, :] in registers; delta rows
-// come from LDS (zero beyond N); the mask value of the next row is requested while the current
-// one is computed.
-template <int N4, int NT>
-__device__ __forceinline__ void head_cotangent(const GemmArgs &g, const float (*hd)[32], int m0,
-                                               int tile_rows, int tid, int cg, int groups) {
-  const int K = g.K, N = g.N;
-  const int cols = (K + groups - 1) / groups;            // columns of this workgroup
-  const int c_begin = cg * cols, c_end = min(c_begin + cols, K);
-  const int bands = cols >= NT ? 1 : NT / cols;          // row bands worked on side by side
-  const int band = cols >= NT ? 0 : tid / cols;
-  const int c_first = c_begin + (cols >= NT ? tid : tid - band * cols);
-  if (band >= bands) return;
-  const int rows_per_band = (tile_rows + bands - 1) / bands;
-  const int r_begin = band * rows_per_band, r_end = min(r_begin + rows_per_band, tile_rows);
-  if (r_begin >= r_end) return;
-#pragma unroll 1
-  for (int i = c_first; i < c_end; i += NT) {
-    float w[4 * N4];
-#pragma unroll
-    for (int j = 0; j < 4 * N4; ++j) {
-      const int64_t at = (int64_t)i * g.ldw + min(j, N - 1);      // clamped: delta is 0 there
-      w[j] = g.bf16 ? (float)static_cast<const __bf16 *>(g.W)[at] : static_cast<const float *>(g.W)[at];
-    }
-    const float *mcol = g.head_mask + (int64_t)m0 * K + i;
-    float *gcol = g.head_gprev + (int64_t)m0 * K + i;
-    float nxt = mcol[(int64_t)r_begin * K];
-#pragma unroll 1
-    for (int r = r_begin; r < r_end; ++r) {
-      const float cur = nxt;
-      nxt = mcol[(int64_t)min(r + 1, r_end - 1) * K];
-      float acc = 0.f;
-#pragma unroll
-      for (int j4 = 0; j4 < N4; ++j4) {
-        const f32x4 dv = *reinterpret_cast<const f32x4 *>(&hd[r][4 * j4]);
-        acc += dv[0] * w[4 * j4] + dv[1] * w[4 * j4 + 1] + dv[2] * w[4 * j4 + 2] + dv[3] * w[4 * j4 + 3];
-      }
-      gcol[(int64_t)r * K] = acc * cur;
-    }
-  }
-}
-
 // LSTM: the instantiation that carries the two LSTM epilogues (float32 only).  They live in a
 // separate instantiation so that the kernels of the dense-network path stay as small as they were:
 // with a handful of waves per launch, every extra instruction on the way shows in the run time.

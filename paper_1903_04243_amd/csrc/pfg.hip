@@ -171,6 +171,7 @@ struct Plan {
   std::vector<size_t> act, dphi, d2phi, G;   // indexed by layer l (1-based; entry 0 unused)
   size_t logits = 0, P = 0, ping = 0, pong = 0, sq = 0, U = 0, Cc = 0;
   size_t splitk = 0;                  // partial results of a product cut along its contraction, or 0
+  size_t head_part = 0;               // partial logits of a head whose contraction is cut, or 0
   int64_t ktot = 0;                   // Hessian: sum of the hidden widths
   std::vector<int64_t> koff;          // Hessian: column offset of hidden layer l in U and Cc
   size_t take(size_t bytes) {
@@ -223,11 +224,15 @@ Plan make_plan(const pfg_mlp *net, int op, int64_t B, int64_t S) {
     p.logits = p.take(sizeof(float) * B * d[L]);
     for (int l = 1; l <= L; ++l) p.G[l] = p.take(sizeof(float) * rows * d[l]);
     if (op == PFG_OP_GRAD_NORMS) p.sq = p.take(sizeof(float) * B * L);
-    if (net->dtype == PFG_F32 && rows == B) {
+    if (rows == B && L >= 2) {
+      const int z = head_split_shape(B, d[L], d[L - 1]);
+      if (z > 1) p.head_part = p.take(sizeof(float) * z * B * d[L]);
+    }
+    if (rows == B) {
       // the largest [Z, B, width] block a forward layer needs
       size_t most = 0;
       for (int l = 1; l <= L; ++l) {
-        const int z = split_k_shape(B, d[l], d[l - 1]);
+        const int z = split_k_shape(B, d[l], d[l - 1], net->dtype == PFG_BF16);
         if (z > 1) most = std::max(most, sizeof(float) * z * B * d[l]);
       }
       if (most) p.splitk = p.take(most);
@@ -299,7 +304,10 @@ int forward(const pfg_mlp *net, const void *X, int64_t B, int upto, void *ws, co
       g.C = at(ws, p.logits);
     }
     const int Z = p.splitk ? split_k_factor(g) : 1;
-    if (Z > 1)
+    const int Zh = (p.head_part && g.epilogue == EPI_HEAD) ? head_split_pieces(g) : 1;
+    if (Zh > 1)
+      PFG_LAUNCH("gemm_forward", launch_head_split(g, Zh, at(ws, p.head_part), stream));
+    else if (Z > 1)
       PFG_LAUNCH("gemm_forward", launch_gemm_split(g, Z, at(ws, p.splitk), stream));
     else
       PFG_LAUNCH("gemm_forward", launch_gemm(g, stream));

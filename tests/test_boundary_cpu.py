@@ -70,6 +70,12 @@ def test_workspace_sizes(lib):
     wide = make_net([3136, 1024, 10])
     assert ws_bytes(lib, wide, 0, B, 1) == (0, 2 * up(4 * B * 1024) + up(4 * B * 10) + up(4 * B * 1024) +
                                             up(4 * B * 10) + up(4 * 8 * B * 1024))
+    # bf16, 256 rows against 4096-wide layers: 32 partial logits [32, B, 10] of the head, whose
+    # contraction is cut, and the 2 partial results [2, B, 4096] of a forward product
+    big = make_net([4096, 4096, 4096, 10], act=3, dtype=1)
+    Bb = 256
+    assert ws_bytes(lib, big, 0, Bb, 1) == (0, 4 * up(4 * Bb * 4096) + up(4 * Bb * 10) + 2 * up(4 * Bb * 4096) +
+                                            up(4 * Bb * 10) + up(4 * 32 * Bb * 10) + up(4 * 2 * Bb * 4096))
     net3 = make_net([1024, 2048, 2048, 1024], act=2)
     rc, n = ws_bytes(lib, net3, 1, 64, 1024)
     assert rc == 0

@@ -351,6 +351,27 @@ def test_long_contractions_are_cut_into_pieces(oracle):
     assert e <= TOL_F32
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_head_with_a_long_contraction_is_cut_into_pieces(oracle, dtype):
+    # a 2048-wide last hidden layer and 200 rows: the logits are 32 partial products of 64 columns
+    # each, added by the kernel that then does softmax, loss and the cotangent step; the last row
+    # tile holds 8 rows, 7 classes leave most of a 32-column tile empty
+    dims, B, act = (96, 2048, 7), 200, "gelu"
+    say(f"split head: dims {dims} B={B} {dtype}")
+    w = wl.Workload("splithead", 62, "per_example_grads", dims, act, dtype, B, "normal", "normal_fan_in")
+    inp = draw(w, bias_scale=0.2)
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16
+    check_grads(oracle, inp, act, dtype, tol, want_dW=[False, True], tag=f"splithead-{dtype}")
+    # only the last layer's weight gradient wanted: no cotangent step rides on the head
+    dW, db, loss = pfg.pfg_per_example_grads(gpu_net(inp, act, dtype), gpu_x(inp, dtype), dev(inp.labels),
+                                             want_dW=[False, True], want_db=False)
+    torch.cuda.synchronize()
+    ref_dW, _, ref_loss = oracle.per_example_grads(oracle.Net(inp.Ws, inp.bs, act), inp.X, inp.labels,
+                                                   want_dW=[False, True])
+    assert slice_rel_err(dW[1].cpu().numpy(), ref_dW[1]) <= tol
+    assert slice_rel_err(loss.cpu().numpy(), ref_loss, lead=0) <= tol
+
+
 def test_deep_network_and_wide_seed_block(oracle):
     # five layers; weight Jacobian with shared seeds S = 40 > d_L, all layers, softmax head
     dims, B, act = (24, 48, 40, 56, 32, 20), 9, "tanh"
