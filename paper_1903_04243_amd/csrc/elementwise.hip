@@ -318,7 +318,9 @@ int split_k_factor(const GemmArgs &g) {
 }
 
 int split_k_shape(int64_t M, int64_t N, int64_t K, int bf16) {
-  if (M < 64 || N < 256 || N % 8 || K < 1024) return 1;
+  // fewer than 64 rows: measured a gain for bf16 weights only (4096 x 4096 at 8 to 48 rows: 55 -> 30 us
+  // per product; a float32 3136 x 1024 layer got 5 us slower)
+  if (M < (bf16 ? 1 : 64) || N < 256 || N % 8 || K < 1024) return 1;
   const int64_t tiles64 = ((M + 63) / 64) * ((N + 63) / 64);
   if (tiles64 < 128) {                            // too few tiles for the chip: up to 8 pieces
     for (int Z = 8; Z >= 2; Z /= 2)

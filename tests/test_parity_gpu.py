@@ -351,6 +351,17 @@ def test_long_contractions_are_cut_into_pieces(oracle):
     assert e <= TOL_F32
 
 
+def test_bf16_few_rows_against_a_long_contraction(oracle):
+    # 5 rows, bf16: the first forward product (K = 1024, 512 columns) is cut into 4 pieces although
+    # it has less than one full row tile; 150 rows: 3 row tiles, the last one ragged
+    for B in (5, 150):
+        dims, act = (1024, 512, 10), "tanh"
+        say(f"bf16 split contraction: dims {dims} B={B}")
+        w = wl.Workload("splitbf", 63, "per_example_grads", dims, act, "bf16", B, "normal", "normal_fan_in")
+        inp = draw(w, bias_scale=0.2)
+        check_grads(oracle, inp, act, "bf16", TOL_BF16, want_dW=[False, True], tag=f"splitbf-B{B}")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_head_with_a_long_contraction_is_cut_into_pieces(oracle, dtype):
     # a 2048-wide last hidden layer and 200 rows: the logits are 32 partial products of 64 columns
