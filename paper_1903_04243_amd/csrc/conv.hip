@@ -4,6 +4,8 @@
 // example index into the batch of positions: rows (b, y, x)); the per-example filter gradient is a
 // product per example over the positions, for which the patches are also kept with the position
 // index fastest.
+#include <algorithm>
+
 #include "common.h"
 
 namespace pfg {
@@ -109,6 +111,94 @@ __global__ __launch_bounds__(kThreads) void im2col_flat_kernel(const float *in, 
       *reinterpret_cast<f32x4 *>(out + e0) = v;
     } else {
       for (int q = 0; e0 + q < total; ++q) out[e0 + q] = v[q];
+    }
+  }
+}
+
+// Both layouts of a small image's patches in one launch, through LDS: a workgroup copies the whole
+// image of its example into LDS (h w c <= kLdsImage floats) and writes one slab of P[b] and of PT[b]
+// as flat runs of 16-byte stores, finding the source of each value by counting (tap, channel,
+// position) up from the slab's first entry instead of dividing per value.  For images whose patch
+// rows are not whole 16-byte pieces (a single channel), where the other kernels gather value by
+// value from global memory.  P[b] and PT[b] must be 16-byte aligned (h w k k c a multiple of 4).
+constexpr int kLdsImage = 8192;
+
+// n / d for 0 <= n < 2^24 and d >= 1 with the reciprocal given: the float product is off by one at
+// most, which the remainder shows (a 32-bit division by a run-time divisor costs ten times as much,
+// and the kernel below is made of them)
+__device__ __forceinline__ int div_small(int n, int d, float inv) {
+  int q = (int)((float)n * inv);
+  const int r = n - q * d;
+  if (r < 0) --q;
+  if (r >= d) ++q;
+  return q;
+}
+
+__global__ __launch_bounds__(kThreads) void im2col_lds_kernel(const float *in, int h, int w, int c, int k,
+                                                              float *P, float *PT) {
+  __shared__ float img[kLdsImage];
+  const int p = (k - 1) / 2, hw = h * w, kkc = k * k * c, n = hw * c;
+  const float inv_kkc = 1.f / (float)kkc, inv_hw = 1.f / (float)hw, inv_w = 1.f / (float)w, inv_c = 1.f / (float)c,
+              inv_k = 1.f / (float)k;
+  const int64_t b = blockIdx.y;
+  const float *src = in + b * n;
+  for (int i = threadIdx.x; i < n; i += kThreads) img[i] = src[i];
+  __syncthreads();
+  const int total = hw * kkc;                       // values of P[b] (and of PT[b])
+  const int per = ((total / 4 + gridDim.x - 1) / gridDim.x) * 4;
+  const int e_begin = blockIdx.x * per, e_end = min(total, e_begin + per);
+  if (P) {
+    float *out = P + b * total;
+    for (int e0 = e_begin + 4 * threadIdx.x; e0 < e_end; e0 += 4 * kThreads) {
+      // entry e0 of [h w, k k c]: position, tap and channel; then counted up
+      int pos = div_small(e0, kkc, inv_kkc), t = e0 - pos * kkc;
+      int y = div_small(pos, w, inv_w), x = pos - y * w;
+      int kyx = div_small(t, c, inv_c), ch = t - kyx * c;
+      int ky = div_small(kyx, k, inv_k), kx = kyx - ky * k;
+      f32x4 v;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int yy = y + ky - p, xx = x + kx - p;
+        v[q] = (yy >= 0 && yy < h && xx >= 0 && xx < w) ? img[(yy * w + xx) * c + ch] : 0.f;
+        if (++ch == c) {
+          ch = 0;
+          if (++kx == k) {
+            kx = 0;
+            if (++ky == k) {
+              ky = 0;
+              if (++x == w) { x = 0; ++y; }
+            }
+          }
+        }
+      }
+      *reinterpret_cast<f32x4 *>(out + e0) = v;
+    }
+  }
+  if (PT) {
+    float *out = PT + b * total;
+    for (int e0 = e_begin + 4 * threadIdx.x; e0 < e_end; e0 += 4 * kThreads) {
+      // entry e0 of [k k c, h w]
+      int t = div_small(e0, hw, inv_hw), pos = e0 - t * hw;
+      int y = div_small(pos, w, inv_w), x = pos - y * w;
+      int kyx = div_small(t, c, inv_c), ch = t - kyx * c;
+      int ky = div_small(kyx, k, inv_k), kx = kyx - ky * k;
+      f32x4 v;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int yy = y + ky - p, xx = x + kx - p;
+        v[q] = (yy >= 0 && yy < h && xx >= 0 && xx < w) ? img[(yy * w + xx) * c + ch] : 0.f;
+        if (++x == w) {
+          x = 0;
+          if (++y == h) {
+            y = 0;
+            if (++ch == c) {
+              ch = 0;
+              if (++kx == k) { kx = 0; ++ky; }
+            }
+          }
+        }
+      }
+      *reinterpret_cast<f32x4 *>(out + e0) = v;
     }
   }
 }
@@ -385,6 +475,15 @@ hipError_t launch_im2col(const float *in, int64_t B, int32_t h, int32_t w, int32
   const int64_t hw = (int64_t)h * w, kkc = (int64_t)k * k * c;
   if (B <= 0 || hw <= 0 || kkc <= 0) return hipSuccess;
   if (B > 65535) return hipErrorInvalidValue;
+  auto aligned = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
+  if (c % 4 != 0 && hw * c <= kLdsImage && (hw * kkc) % 4 == 0 && hw * kkc < (1 << 24) && aligned(P) && aligned(PT)) {
+    // enough workgroups for the chip, slabs of at least 1024 values
+    int64_t slabs = (1024 + B - 1) / B;
+    slabs = std::max<int64_t>(1, std::min<int64_t>(slabs, hw * kkc / 1024));
+    PFG_KERNEL(im2col_lds_kernel, dim3((unsigned)slabs, (unsigned)B), dim3(kThreads), 0, stream, in, h, w, c, k,
+               P, PT);
+    return hipGetLastError();
+  }
   if (P) {
     if (c % 4 != 0 && (reinterpret_cast<uintptr_t>(P) & 15) == 0)
       PFG_KERNEL(im2col_flat_kernel, dim3(capped_blocks((B * hw * kkc + 3) / 4)), dim3(kThreads), 0, stream, in,
