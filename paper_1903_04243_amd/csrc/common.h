@@ -136,6 +136,7 @@ bool akm_supported(const GemmArgs &g);
 hipError_t launch_gemm_skinny(const GemmArgs &g, hipStream_t stream);
 // 16 x 16 tiles for the smallest float32 products (used by launch_gemm_skinny when it applies)
 bool small16_applies(const GemmArgs &g);
+bool small16_batched_applies(const GemmArgs &g);   // a batched product (nbatch > 1) it takes in one launch
 hipError_t launch_gemm_small16(const GemmArgs &g, hipStream_t stream);
 
 // out[m, i, j] = a[m / S, i] * g[m, j]   for m < M, i < d_in, j < d_out   (float32 out)

@@ -792,7 +792,7 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
   // (the small-problem kernels have no batch index and take a batched product one launch per entry:
   // from 8 entries on, one launch of the tiled kernel on few workgroups is the shorter way)
   const bool few_tiles = tiles64 < 128 && g.nbatch < 8;
-  if (g.epilogue == EPI_HEAD || g.epilogue == EPI_LSTM_FWD || few_tiles || narrow)
+  if (g.epilogue == EPI_HEAD || g.epilogue == EPI_LSTM_FWD || few_tiles || narrow || small16_batched_applies(g))
     return launch_gemm_skinny(g, stream);
   if (!g.bf16) {
     return g.w_kn ? launch_tiles<A_F32, true>(g, stream) : launch_tiles<A_F32, false>(g, stream);

@@ -25,9 +25,19 @@ constexpr int kRing = 4;      // slices in flight per wave
 
 // SUB: the instantiation for rows chosen on the device (GemmArgs::sub), kept apart so that the
 // others carry none of its loads and branches.
-template <bool WKN, int NW, bool LSTM, bool SUB>
+// BATCH: the instantiation for batched products (the second grid index selects the entry; operands
+// at fixed strides, EPI_NONE), apart for the same reason.
+template <bool WKN, int NW, bool LSTM, bool SUB, bool BATCH = false>
 __global__ __launch_bounds__(64 * NW) void gemm_small16_kernel(const GemmArgs g) {
   __shared__ float red[NW][16][17];
+  const float *gA = static_cast<const float *>(g.A), *gW = static_cast<const float *>(g.W);
+  float *gC = g.C;
+  if constexpr (BATCH) {
+    const int64_t z = blockIdx.y;
+    gA += z * g.batch_A;
+    gW += z * g.batch_W;
+    gC += z * g.batch_C;
+  }
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -45,13 +55,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_small16_kernel(const GemmArgs g)
   int mc = min(m0 + r16, M - 1);
   if (SUB && g.sub_gather) mc = g.sub_rows[sub_off + mc];
   const int nc = min(n0 + r16, N - 1);
-  const float *a_row = static_cast<const float *>(g.A) + (int64_t)(mc / g.S) * g.a_batch_stride +
+  const float *a_row = gA + (int64_t)(mc / g.S) * g.a_batch_stride +
                        (int64_t)(mc % g.S) * g.lda;
-  const float *W = static_cast<const float *>(g.W);
+  const float *W = gW;
   const float *w_row = WKN ? W + nc : W + (int64_t)nc * g.ldw;      // column nc of [K, N] / row nc of [N, K]
-  const bool a_vec = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) && (g.lda % 4 == 0) &&
+  const bool a_vec = ((reinterpret_cast<uintptr_t>(gA) & 15) == 0) && (g.lda % 4 == 0) &&
                      (g.a_batch_stride % 4 == 0) && (K % 4 == 0);
-  const bool w_vec = !WKN && ((reinterpret_cast<uintptr_t>(g.W) & 15) == 0) && (g.ldw % 4 == 0) &&
+  const bool w_vec = !WKN && ((reinterpret_cast<uintptr_t>(gW) & 15) == 0) && (g.ldw % 4 == 0) &&
                      (K % 4 == 0);
 
   // Epilogue assignment: thread t < 256 finishes element (t / 16, t % 16); what it needs from global
@@ -143,7 +153,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_small16_kernel(const GemmArgs g)
   if constexpr (LSTM) {
     if (epi == EPI_LSTM_BWD) {
       if (en < g.n_split) {
-        g.C[off] = v;
+        gC[off] = v;
       } else {
         const int k = en - g.n_split;
         lstm_reverse_cell_store(cell, v, g.lstm_dz + (int64_t)em * g.lstm_dz_ld,
@@ -163,14 +173,25 @@ __global__ __launch_bounds__(64 * NW) void gemm_small16_kernel(const GemmArgs g)
     v *= aux;
   }
   if (g.streaming)
-    __builtin_nontemporal_store(v, g.C + off);
+    __builtin_nontemporal_store(v, gC + off);
   else
-    g.C[off] = v;
+    gC[off] = v;
 }
 
 template <bool WKN, bool LSTM, bool SUB = false>
 hipError_t launch16(const GemmArgs &g, hipStream_t stream) {
   const int64_t tiles = (int64_t)((g.M + 15) / 16) * ((g.N + 15) / 16);
+  if constexpr (!LSTM && !SUB) {
+    if (g.nbatch > 1) {
+      const dim3 grid((unsigned)tiles, (unsigned)g.nbatch);
+      if ((g.K + 15) / 16 >= 16)
+        PFG_KERNEL((gemm_small16_kernel<WKN, 8, false, false, true>), grid, dim3(512), 0, stream, g);
+      else
+        PFG_KERNEL((gemm_small16_kernel<WKN, 4, false, false, true>), grid, dim3(256), 0, stream, g);
+      return hipGetLastError();
+    }
+  }
+  if (g.nbatch > 1) return hipErrorInvalidValue;
   // eight waves once each gets at least two slices of 16 k, else four
   if ((g.K + 15) / 16 >= 16)
     PFG_KERNEL((gemm_small16_kernel<WKN, 8, LSTM, SUB>), dim3((unsigned)tiles), dim3(512), 0, stream, g);
@@ -181,8 +202,20 @@ hipError_t launch16(const GemmArgs &g, hipStream_t stream) {
 
 }  // namespace
 
+// Batched products with tiny outputs (at most 16 tiles of 16 x 16 per entry) and a contraction long
+// enough to share out over the waves: one launch, an entry per second grid index.  (The per-example
+// filter gradient of a first conv block, [k k c_in, h w] x [h w, c_out], is of this kind.)
+bool small16_batched_applies(const GemmArgs &g) {
+  if (g.nbatch <= 1 || g.nbatch > 65535 || g.bf16 || g.a_scale || !g.a_is_f32 || g.sub || g.sym_n > 0 || g.a_km)
+    return false;
+  if (g.epilogue != EPI_NONE) return false;
+  const int64_t tiles16 = (int64_t)((g.M + 15) / 16) * ((g.N + 15) / 16);
+  return tiles16 <= 16 && g.K >= 64;
+}
+
 bool small16_applies(const GemmArgs &g) {
-  if (g.bf16 || g.a_scale || g.nbatch > 1 || !g.a_is_f32) return false;
+  if (g.nbatch > 1) return small16_batched_applies(g);
+  if (g.bf16 || g.a_scale || !g.a_is_f32) return false;
   if (g.sub && g.epilogue == EPI_LSTM_BWD) return false;
   if (g.epilogue != EPI_NONE && g.epilogue != EPI_BIAS && g.epilogue != EPI_FORWARD &&
       g.epilogue != EPI_MASK && g.epilogue != EPI_LSTM_BWD)
