@@ -107,7 +107,7 @@ LSTM_SHAPES = [
     (20, 36, 40, 6, 17),        # more than 32 outputs: separate loss head
     (16, 32, 8, 18, 5),         # more steps than one pass of the weight-gradient kernel holds
     (64, 96, 12, 3, 130),       # enough rows for the tiled kernels in the input projection
-    (16, 128, 5, 3, 1000),      # a large batch: tiled recurrent products and a separate cell kernel
+    (16, 128, 5, 3, 2100),      # a large batch: tiled recurrent products and a separate cell kernel
 ]
 
 
