@@ -322,15 +322,19 @@ int split_k_shape(int64_t M, int64_t N, int64_t K, int bf16) {
   // per product; a float32 3136 x 1024 layer got 5 us slower)
   if (M < (bf16 ? 1 : 64) || N < 256 || N % 8 || K < 1024) return 1;
   const int64_t tiles64 = ((M + 63) / 64) * ((N + 63) / 64);
-  if (tiles64 < 128) {                            // too few tiles for the chip: up to 8 pieces
+  if (tiles64 < 128) {
+    // too few tiles for the chip: up to 8 pieces of at least 256, if that makes 128 workgroups or
+    // more (with fewer the small-problem kernels are the better choice: 64 rows against
+    // 1024 x 1024 weights took 25 us in four pieces on 64 workgroups, 15 us there)
     for (int Z = 8; Z >= 2; Z /= 2)
-      if (K % (8 * Z) == 0 && K / Z >= 256 && Z * tiles64 <= 512) return Z;
+      if (K % (8 * Z) == 0 && K / Z >= 256 && Z * tiles64 <= 512 && Z * tiles64 >= 128) return Z;
     return 1;
   }
-  // bf16 products with one workgroup per compute unit are bound by the instruction issue of its
-  // single wave per SIMD; two pieces give every unit a second workgroup
-  if (bf16 && tiles64 <= 256 && K >= 2048 && K % 128 == 0) return 2;
-  return 1;
+  // 128 to 256 tiles: the tiled kernel would run one workgroup on some or all of the 256 units.
+  // bf16 products are then bound by the instruction issue of a single wave per SIMD, float32
+  // products leave units idle; two pieces give every unit two workgroups.
+  if (bf16) return (tiles64 <= 256 && K >= 2048 && K % 128 == 0) ? 2 : 1;
+  return (tiles64 < 256 && K % 16 == 0) ? 2 : 1;
 }
 
 hipError_t launch_gemm_split(const GemmArgs &g, int Z, float *partials, hipStream_t stream) {
