@@ -135,6 +135,7 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream);
 bool akm_supported(const GemmArgs &g);
 hipError_t launch_gemm_skinny(const GemmArgs &g, hipStream_t stream);
 // 16 x 16 tiles for the smallest float32 products (used by launch_gemm_skinny when it applies)
+bool lstm_step_tiled_applies(const GemmArgs &g);   // EPI_LSTM_FWD on enough rows for the LDS-tiled kernel
 bool small16_applies(const GemmArgs &g);
 bool small16_batched_applies(const GemmArgs &g);   // a batched product (nbatch > 1) it takes in one launch
 hipError_t launch_gemm_small16(const GemmArgs &g, hipStream_t stream);

@@ -23,15 +23,21 @@ namespace {
 
 using namespace dev;
 
+
 // WGM x WGN: arrangement of the workgroup's waves over the tile (2 x 2, or 4 x 2 for the largest).
 // SUB: the instantiation for rows chosen on the device (GemmArgs::sub; float32, W in [K, N] layout),
 // kept apart so that the others carry none of its loads and branches (inside the unrolled epilogue
 // they cost a store-bound product a quarter of its speed).
 // AKM: the instantiation that reads A stored as [K, M] (float32, FAST loads only).
+// LSTMF: the instantiation with the LSTM cell update in its epilogue (EPI_LSTM_FWD; float32, W in
+// [K, N] layout, FAST loads, 64 x 64 tiles): a tile's 64 columns are the four gate columns of 16
+// hidden units (gate * H + unit of W_h), not 64 consecutive columns.
 template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2, bool SUB = false,
-          bool AKM = false>
+          bool AKM = false, bool LSTMF = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) {
   static_assert(!AKM || (AMODE == A_F32 && FAST && !SUB), "transposed A: float32, FAST loads, no row subsets");
+  static_assert(!LSTMF || (AMODE == A_F32 && WKN && FAST && !SUB && !AKM && TM == 1 && TN == 1 && WGM == 2 && WGN == 2),
+                "fused LSTM step: float32, [K, N] weights, FAST loads, 64 x 64 tiles");
   constexpr int kThreads = 64 * WGM * WGN;
   constexpr bool BF16 = (AMODE != A_F32);
   constexpr int ELEM = BF16 ? 2 : 4;
@@ -75,7 +81,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   // every XCD a contiguous run of tiles that walks the N tiles of one M tile before moving on, so
   // that a band of A rows is fetched into one L2 once and reused there for all its N tiles.
   const int tiles_m = (g.M + BM - 1) / BM;
-  const int tiles_n = (g.N + BN - 1) / BN;
+  const int tiles_n = LSTMF ? (g.lstm_H + 15) / 16 : (g.N + BN - 1) / BN;
   int tile_m, tile_n;
   bool mirror = false;       // symmetric blocks: this tile also stands for its mirror image
   if (AMODE == A_F32 && BM == BN && g.sym_n > 0) {
@@ -197,6 +203,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
       const int kl = id % BK, ng = id / BK;
       w_k[c] = kl;
       w_n[c] = n0 + ng * EPC;
+      if constexpr (LSTMF) {
+        // tile column 4 ng: gate (4 ng) / 16 of unit 16 tile_n + (4 ng) % 16; a chunk of four units
+        // past the state size (H is a multiple of 4 here) is marked as out of range
+        const int unit = 16 * tile_n + ((ng * EPC) & 15);
+        w_n[c] = unit < g.lstm_H ? ((ng * EPC) >> 4) * g.lstm_H + unit : N;
+      }
       w_lds[c] = (ng * EPC) * STRIDE + kl * ELEM;
       w_row[c] = nullptr;
     }
@@ -442,6 +454,42 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   // ---- epilogue: accumulator element r of lane (half, l32) is row 8 (r / 4) + 4 half + r % 4,
   // column l32 of its 32 x 32 tile ----
   const int epi = g.epilogue;
+  if constexpr (LSTMF) {
+    // The tile holds h_{t-1} W_h for 64 rows and the four gates of 16 units.  It goes through LDS;
+    // a thread then finishes cells (row, unit), consecutive threads on consecutive units: adds
+    // x_t W_x + b, applies the gates, writes them (if kept), c_t and h_t.
+    constexpr int TS = BN + 4;
+    static_assert(BM * TS * 4 <= 2 * STAGE, "the output tile must fit the staging buffers");
+    float *tile = reinterpret_cast<float *>(smem);
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      tile[(wm + 8 * (r >> 2) + 4 * half + (r & 3)) * TS + wn + l32] = acc[0][0][r];
+    __syncthreads();
+    const int H = g.lstm_H, T = g.lstm_T, t = g.lstm_step;
+    for (int e = tid; e < BM * 16; e += kThreads) {
+      const int row = e >> 4, u = e & 15;
+      const int m = m0 + row, k = 16 * tile_n + u;
+      if (m >= M || k >= H) continue;
+      const int64_t zr = g.lstm_zx_rows ? (int64_t)g.lstm_zx_rows[m] + t : (int64_t)m * T + t;
+      const float *zrow = g.lstm_zx + zr * 4 * H + k;
+      const float *trow = tile + row * TS + u;
+      const float z0 = trow[0] + zrow[0], z1 = trow[16] + zrow[H], z2 = trow[32] + zrow[2 * H],
+                  z3 = trow[48] + zrow[3 * H];
+      const float cprev = g.lstm_has_prev ? g.lstm_cs_w[m * g.lstm_state_ld + (t - 1) * g.lstm_state_ts + k] : 0.f;
+      const float gi = 1.f / (1.f + __expf(-z0)), gg = tanhf(z1);
+      const float gf = 1.f / (1.f + __expf(-z2)), go = 1.f / (1.f + __expf(-z3));
+      const float c = gf * cprev + gi * gg;
+      if (g.lstm_gates_w) {
+        float *grow = g.lstm_gates_w + ((int64_t)m * T + t) * 4 * H + k;
+        grow[0] = gi; grow[H] = gg; grow[2 * H] = gf; grow[3 * H] = go;
+      }
+      const int64_t at = m * g.lstm_state_ld + t * g.lstm_state_ts + k;
+      g.lstm_cs_w[at] = c;
+      g.lstm_hs_w[at] = go * tanhf(c);
+    }
+    return;
+  }
   if constexpr (AMODE == A_F32) {
     if (epi == EPI_LSTM_BWD) {
       // The reverse cell update is long; running it from the unrolled register loop below would
@@ -677,14 +725,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
 }
 
 template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2, bool SUB = false,
-          bool AKM = false>
+          bool AKM = false, bool LSTMF = false>
 hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
   constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
   constexpr int kThreads = 64 * WGM * WGN;
   constexpr bool WTR = WKN && (AMODE != A_F32);
   constexpr int BK = BKB / (AMODE != A_F32 ? 2 : 4);
   constexpr int smem = 2 * (BM * (BKB + 16) + (WTR ? BK * (BN * 2 + 16) : BN * (BKB + 16)));
-  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB, FAST, WGM, WGN, SUB, AKM>;
+  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB, FAST, WGM, WGN, SUB, AKM, LSTMF>;
   static bool attr_set = false;   // benign race: the attribute is idempotent
   if (!attr_set && smem > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -693,6 +741,7 @@ hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
     attr_set = true;
   }
   int64_t tiles = (int64_t)((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  if (LSTMF) tiles = (int64_t)((g.M + BM - 1) / BM) * ((g.lstm_H + 15) / 16);
   if (AMODE == A_F32 && BM == BN && g.sym_n > 0) {
     const int64_t T = g.sym_n / BM;
     tiles = (g.M / g.sym_n) * (T * (T + 1) / 2);
@@ -752,6 +801,14 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
 
 }  // namespace
 
+// The fused LSTM step on many rows: the small-problem kernel's 32 x 32 tiles re-read W_h once per
+// 32 rows; measured with a state of 256, the LDS-tiled kernel with the same epilogue is level with
+// it at 768 rows and ahead beyond (512 rows: 3 us per step behind, 960 rows: 4 us ahead).
+bool lstm_step_tiled_applies(const GemmArgs &g) {
+  return g.epilogue == EPI_LSTM_FWD && g.M >= 768 && !g.bf16 && g.a_is_f32 && g.w_kn && g.nbatch <= 1 && !g.sub &&
+         g.S == 1 && !g.a_scale && g.lstm_H % 4 == 0 && g.N == 4 * g.lstm_H && fast_loads_ok(g);
+}
+
 bool akm_supported(const GemmArgs &g) {
   if (!g.a_km) return true;
   auto aligned = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
@@ -791,6 +848,8 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
   const bool narrow = g.N <= 32 && g.K >= 256 && g.nbatch <= 1 && g.sym_n == 0;
   // (the small-problem kernels have no batch index and take a batched product one launch per entry:
   // from 8 entries on, one launch of the tiled kernel on few workgroups is the shorter way)
+  if (lstm_step_tiled_applies(g))
+    return launch_one<A_F32, true, 1, 1, 128, true, 2, 2, false, false, true>(g, stream);
   const bool few_tiles = tiles64 < 128 && g.nbatch < 8;
   if (g.epilogue == EPI_HEAD || g.epilogue == EPI_LSTM_FWD || few_tiles || narrow || small16_batched_applies(g))
     return launch_gemm_skinny(g, stream);

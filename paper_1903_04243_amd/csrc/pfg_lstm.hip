@@ -122,12 +122,12 @@ int lstm_forward(const pfg_lstm *net, const void *X, int64_t B, void *ws, const 
   float *hs = ws_at(ws, p.hs);
   // With few rows every kernel on this sequential path is bound by launch and memory latency, so
   // the cell update rides in the epilogue of the recurrent product: one launch per step instead of
-  // two.  Large batches use the LDS-tiled product and a separate cell kernel; measured with a state
-  // of 256 the two meet at about 1000 rows (512 rows: 0.243 against 0.286 ms for ten steps and
-  // their reverse sweep; 2048 rows: 0.700 against 0.679 ms).
-  const bool fused = (int64_t)((B + 63) / 64) * ((4 * (int64_t)H + 63) / 64) < 256;
+  // two: the small-problem kernel up to about 1000 rows (measured with a state of 256), the
+  // LDS-tiled kernel with the same epilogue beyond.  Only a large batch whose state size is not a
+  // multiple of 4 takes the LDS-tiled product and a separate cell kernel.
+  const bool few_rows = (int64_t)((B + 63) / 64) * ((4 * (int64_t)H + 63) / 64) < 256;
   for (int t = 0; t < T; ++t) {
-    if (t > 0 && fused) {
+    if (t > 0) {
       GemmArgs g{};
       g.A = hs + (int64_t)(t - 1) * H; g.lda = (int64_t)T * H; g.a_batch_stride = (int64_t)T * H;
       g.S = 1; g.a_is_f32 = 1;
@@ -138,8 +138,11 @@ int lstm_forward(const pfg_lstm *net, const void *X, int64_t B, void *ws, const 
       g.lstm_zx = ws_at(ws, p.zx); g.lstm_gates_w = ws_at(ws, p.gates);
       g.lstm_cs_w = ws_at(ws, p.cs); g.lstm_hs_w = hs;
       g.lstm_state_ld = (int64_t)T * H; g.lstm_state_ts = H; g.lstm_has_prev = 1;
-      PFG_LAUNCH("lstm_step", launch_gemm(g, stream));
-      continue;
+      // fused on few rows (small-problem kernel) and on many when the tiled kernel takes the step
+      if (few_rows || lstm_step_tiled_applies(g)) {
+        PFG_LAUNCH("lstm_step", launch_gemm(g, stream));
+        continue;
+      }
     }
     if (t > 0) {
       GemmArgs g{};

@@ -107,7 +107,8 @@ LSTM_SHAPES = [
     (20, 36, 40, 6, 17),        # more than 32 outputs: separate loss head
     (16, 32, 8, 18, 5),         # more steps than one pass of the weight-gradient kernel holds
     (64, 96, 12, 3, 130),       # enough rows for the tiled kernels in the input projection
-    (16, 128, 5, 3, 2100),      # a large batch: tiled recurrent products and a separate cell kernel
+    (16, 128, 5, 3, 2100),      # a large batch: the cell update in the epilogue of the tiled product
+    (8, 30, 4, 3, 8200),        # a large batch, state size not a multiple of 4: tiled product, separate cell kernel
 ]
 
 
