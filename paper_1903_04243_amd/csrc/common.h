@@ -118,6 +118,15 @@ struct GemmArgs {
   // elsewhere.  LDS-tiled kernel only; float32, no scale, S == 1, EPI_NONE, M a multiple of 4 and
   // 16-byte aligned rows (see akm_supported).
   int32_t a_km;
+  // conv_k > 0: the A operand is the patch matrix of an image batch that is never written out.  A
+  // points at the images [nbatch or B, conv_h, conv_w, conv_c] (channel fastest, conv_c a multiple
+  // of 4, 16-byte aligned); the value at (row (b, y, x), column (ky, kx, c)) is
+  // image[b, y + ky - p, x + kx - p, c], p = (conv_k - 1) / 2, zero outside the image.  Without a_km
+  // the rows m = (b, y, x) run over all images and K = conv_k^2 conv_c; with a_km (and nbatch images,
+  // image z at A + z * batch_A) the product contracts over the positions, M = conv_k^2 conv_c and
+  // K = conv_h conv_w.  LDS-tiled kernel, 64 x 64 tiles, float32, FAST-load conditions on W (see
+  // conv_gather_supported).
+  int32_t conv_k, conv_h, conv_w, conv_c;
   // Rows chosen on the device (the index sets of a conditional, Section 3.6).  When `sub` is set the
   // product runs on rows m < sub[0] only (sub[0] <= M; M still sizes the grid).  With sub_gather, row
   // m of the A operand is row sub_rows[sub[1] + m] of A; with sub_scatter, row m of the result is
@@ -135,6 +144,7 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream);
 bool akm_supported(const GemmArgs &g);
 hipError_t launch_gemm_skinny(const GemmArgs &g, hipStream_t stream);
 // 16 x 16 tiles for the smallest float32 products (used by launch_gemm_skinny when it applies)
+bool conv_gather_supported(const GemmArgs &g);     // may this product (conv_k > 0) be launched?
 bool lstm_step_tiled_applies(const GemmArgs &g);   // EPI_LSTM_FWD on enough rows for the LDS-tiled kernel
 bool small16_applies(const GemmArgs &g);
 bool small16_batched_applies(const GemmArgs &g);   // a batched product (nbatch > 1) it takes in one launch

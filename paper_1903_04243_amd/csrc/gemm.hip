@@ -32,9 +32,13 @@ using namespace dev;
 // LSTMF: the instantiation with the LSTM cell update in its epilogue (EPI_LSTM_FWD; float32, W in
 // [K, N] layout, FAST loads, 64 x 64 tiles): a tile's 64 columns are the four gate columns of 16
 // hidden units (gate * H + unit of W_h), not 64 consecutive columns.
+// GATHER: the instantiations whose A operand is the patch matrix of an image batch, gathered from
+// the images while staging (GemmArgs::conv_k; with AKM the contraction runs over the positions).
 template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2, bool SUB = false,
-          bool AKM = false, bool LSTMF = false>
+          bool AKM = false, bool LSTMF = false, bool GATHER = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) {
+  static_assert(!GATHER || (AMODE == A_F32 && WKN && FAST && !SUB && !LSTMF && TM == 1 && TN == 1),
+                "gathered patches: float32, [K, N] weights, FAST loads, 64 x 64 tiles");
   static_assert(!AKM || (AMODE == A_F32 && FAST && !SUB), "transposed A: float32, FAST loads, no row subsets");
   static_assert(!LSTMF || (AMODE == A_F32 && WKN && FAST && !SUB && !AKM && TM == 1 && TN == 1 && WGM == 2 && WGN == 2),
                 "fused LSTM step: float32, [K, N] weights, FAST loads, 64 x 64 tiles");
@@ -134,9 +138,51 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   int a_lds[A_CHUNKS];
   int a_k[A_CHUNKS];
   int a_m[A_CHUNKS];             // AKM: first row m of the chunk (global)
+  int a_yx[A_CHUNKS];            // GATHER: (y << 16) | x of the chunk's position, or (ky << 16) | kx of its tap (AKM)
+  bool a_live[A_CHUNKS];         // GATHER: does the chunk fetched last lie inside the image and the operand
+  // small quotients by float reciprocals (operands below 2^24; off by one at most, then corrected)
+  const float inv_c = GATHER ? 1.f / (float)g.conv_c : 0.f, inv_kw = GATHER ? 1.f / (float)g.conv_k : 0.f,
+              inv_w = GATHER ? 1.f / (float)g.conv_w : 0.f;
+  auto qdiv = [](int n, int d, float inv) {
+    int q = (int)((float)n * inv);
+    const int r = n - q * d;
+    if (r < 0) --q;
+    if (r >= d) ++q;
+    return q;
+  };
 #pragma unroll
   for (int c = 0; c < A_CHUNKS; ++c) {
     const int id = tid + kThreads * c;
+    if constexpr (GATHER && AKM) {
+      // the chunk's four rows m are four channels of one filter tap: fixed for the whole product
+      const int kl = id % BK, mg = id / BK;
+      a_k[c] = kl;
+      a_m[c] = m0 + mg * EPC;
+      a_lds[c] = (mg * EPC) * STRIDE + kl * ELEM;
+      const int tap = qdiv(a_m[c], g.conv_c, inv_c), ci = a_m[c] - tap * g.conv_c;
+      const int ky = qdiv(tap, g.conv_k, inv_kw), kx = tap - ky * g.conv_k;
+      a_yx[c] = (ky << 16) | kx;
+      a_row[c] = static_cast<const float *>(gA) + ci;
+      a_srow[c] = nullptr;
+      continue;
+    }
+    if constexpr (GATHER && !AKM) {
+      // the chunk's row m is one position of one image: fixed for the whole product
+      const int row = id / CPR, kc = id % CPR;
+      const int m = min(m0 + row, M - 1);
+      a_lds[c] = row * STRIDE + kc * 16;
+      a_k[c] = kc * EPC;
+      a_m[c] = m0 + row;
+      const int hw = g.conv_h * g.conv_w;
+      const int b = m / hw, pos = m - b * hw;
+      const int y = qdiv(pos, g.conv_w, inv_w), x = pos - y * g.conv_w;
+      a_yx[c] = (y << 16) | x;
+      a_row[c] = static_cast<const float *>(gA) + ((int64_t)b * hw + pos) * g.conv_c;
+      a_srow[c] = nullptr;
+      continue;
+    }
+    a_yx[c] = 0;
+    a_live[c] = false;
     if constexpr (AKM) {
       // A is [K, M]: a chunk is 16 bytes along m at one k and is scattered into the [m][k] LDS
       // layout element by element (as for float32 weights in [K, N] layout)
@@ -221,6 +267,34 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   // sc: does the A operand carry a scale (passed as a literal where the caller has branched on
   // it once, so that no per-chunk select remains)
   auto fetch_a_chunk = [&](int c, int kt, bool sc) {
+    if constexpr (GATHER) {
+      const int p = (g.conv_k - 1) / 2;
+      int y, x, ky, kx, ci;
+      bool live;
+      if constexpr (AKM) {
+        const int k = kt * BK + a_k[c];            // the position
+        y = qdiv(k, g.conv_w, inv_w); x = k - y * g.conv_w;
+        ky = a_yx[c] >> 16; kx = a_yx[c] & 0xffff; ci = 0;
+        live = k < K && a_m[c] < M;
+      } else {
+        const int k = kt * BK + a_k[c];            // (tap, channel)
+        const int tap = qdiv(k, g.conv_c, inv_c);
+        ci = k - tap * g.conv_c;
+        ky = qdiv(tap, g.conv_k, inv_kw); kx = tap - ky * g.conv_k;
+        y = a_yx[c] >> 16; x = a_yx[c] & 0xffff;
+        live = k < K && a_m[c] < M;
+      }
+      const int yy = y + ky - p, xx = x + kx - p;
+      live = live && yy >= 0 && yy < g.conv_h && xx >= 0 && xx < g.conv_w;
+      // the load itself is unconditional, from a pixel inside the image (no branch in the loop);
+      // what it brings for a patch entry outside the image is dropped when the chunk is stored
+      const int yc = min(max(yy, 0), g.conv_h - 1), xc = min(max(xx, 0), g.conv_w - 1);
+      const float *base = AKM ? static_cast<const float *>(a_row[c])
+                              : static_cast<const float *>(a_row[c]) - ((int64_t)y * g.conv_w + x) * g.conv_c;
+      ra[c].v = *reinterpret_cast<const f32x4 *>(base + ((int64_t)yc * g.conv_w + xc) * g.conv_c + ci);
+      a_live[c] = live;
+      return;
+    }
     if constexpr (AKM) {
       // 16 bytes along m of row k; both indices clamped (zeroed in stash if out of range)
       const int k = kt * BK + a_k[c];
@@ -266,8 +340,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   // here, not when issued).
   auto stash_a_chunk = [&](int c, int buf, int kt, bool sc) {
     unsigned char *sA = smem + buf * STAGE;
+    if constexpr (GATHER && !AKM) {
+      *reinterpret_cast<u32x4 *>(sA + a_lds[c]) =
+          a_live[c] ? __builtin_bit_cast(u32x4, ra[c].v) : u32x4{0u, 0u, 0u, 0u};
+      return;
+    }
     if constexpr (AKM) {
-      const bool past = (kt * BK + a_k[c] >= K) || (a_m[c] >= M);
+      const bool past = GATHER ? !a_live[c] : (kt * BK + a_k[c] >= K) || (a_m[c] >= M);
       const u32x4 v = past ? u32x4{0u, 0u, 0u, 0u} : __builtin_bit_cast(u32x4, ra[c].v);
 #pragma unroll
       for (int e = 0; e < 4; ++e) *reinterpret_cast<uint32_t *>(sA + a_lds[c] + e * STRIDE) = v[e];
@@ -725,14 +804,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
 }
 
 template <int AMODE, bool WKN, int TM, int TN, int BKB, bool FAST, int WGM = 2, int WGN = 2, bool SUB = false,
-          bool AKM = false, bool LSTMF = false>
+          bool AKM = false, bool LSTMF = false, bool GATHER = false>
 hipError_t launch_one(const GemmArgs &g, hipStream_t stream) {
   constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
   constexpr int kThreads = 64 * WGM * WGN;
   constexpr bool WTR = WKN && (AMODE != A_F32);
   constexpr int BK = BKB / (AMODE != A_F32 ? 2 : 4);
   constexpr int smem = 2 * (BM * (BKB + 16) + (WTR ? BK * (BN * 2 + 16) : BN * (BKB + 16)));
-  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB, FAST, WGM, WGN, SUB, AKM, LSTMF>;
+  auto kern = gemm_kernel<AMODE, WKN, TM, TN, BKB, FAST, WGM, WGN, SUB, AKM, LSTMF, GATHER>;
   static bool attr_set = false;   // benign race: the attribute is idempotent
   if (!attr_set && smem > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -809,6 +888,24 @@ bool lstm_step_tiled_applies(const GemmArgs &g) {
          g.S == 1 && !g.a_scale && g.lstm_H % 4 == 0 && g.N == 4 * g.lstm_H && fast_loads_ok(g);
 }
 
+bool conv_gather_supported(const GemmArgs &g) {
+  if (g.conv_k <= 0) return true;
+  auto aligned = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  const int64_t hw = (int64_t)g.conv_h * g.conv_w, kkc = (int64_t)g.conv_k * g.conv_k * g.conv_c;
+  if (g.conv_k % 2 == 0 || g.conv_c < 4 || g.conv_c % 4 || g.conv_h < 1 || g.conv_w < 1 || g.conv_h > 65535 ||
+      g.conv_w > 65535 || hw >= (1 << 24) || kkc >= (1 << 24))
+    return false;
+  if (g.bf16 || !g.a_is_f32 || !g.w_kn || g.a_scale || g.S != 1 || g.sub || g.sym_n > 0 || !aligned(g.A)) return false;
+  if (!aligned(g.W) || g.ldw % 4 || g.N % 4 || g.N < 4) return false;
+  if (g.a_km) {
+    if (g.epilogue != EPI_NONE || g.M != kkc || g.K != hw) return false;
+    if (g.nbatch > 1 && (g.batch_A % 4 || g.batch_W % 4)) return false;
+  } else {
+    if ((g.epilogue != EPI_NONE && g.epilogue != EPI_BIAS) || g.K != kkc || g.M % hw || g.nbatch > 1) return false;
+  }
+  return true;
+}
+
 bool akm_supported(const GemmArgs &g) {
   if (!g.a_km) return true;
   auto aligned = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
@@ -835,6 +932,11 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
                 ((g.sub_gather || g.sub_scatter) && !g.sub_rows)))
     return hipErrorInvalidValue;
   if (!g.sub && (g.sub_gather || g.sub_scatter)) return hipErrorInvalidValue;
+  if (g.conv_k > 0) {
+    if (!conv_gather_supported(g)) return hipErrorInvalidValue;
+    return g.a_km ? launch_one<A_F32, true, 1, 1, 128, true, 2, 2, false, true, false, true>(g, stream)
+                  : launch_one<A_F32, true, 1, 1, 128, true, 2, 2, false, false, false, true>(g, stream);
+  }
   if (g.a_km) {
     if (!akm_supported(g)) return hipErrorInvalidValue;
     return launch_tiles<A_F32, true>(g, stream);

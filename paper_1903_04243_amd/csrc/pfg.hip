@@ -908,24 +908,54 @@ int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, 
     const GemmArgs g = filter_product(i, true);
     return g.K % 4 == 0 && akm_supported(g);
   };
+  // The input image of every block (X, then the pooled outputs), and whether the block's products
+  // gather their patches from it themselves: the forward product over the rows (b, y, x) and the
+  // filter-gradient product over the positions then need no patch matrix at all (channel counts
+  // that are multiples of 4, enough tiles for the tiled kernel).
+  std::vector<const float *> image(nc);
+  auto forward_product = [&](int i, bool gathered) {
+    const ConvBlock &blk = cp.blocks[i];
+    const int kkc = blk.k * blk.k * blk.ci;
+    GemmArgs g{};
+    if (gathered) {
+      g.A = image[i]; g.conv_k = blk.k; g.conv_h = blk.h; g.conv_w = blk.w; g.conv_c = blk.ci;
+    } else {
+      g.A = at(ws, blk.P);
+    }
+    g.lda = kkc; g.a_batch_stride = kkc; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->Wc[i]; g.ldw = blk.co; g.w_kn = 1;
+    g.M = (int32_t)(B * blk.h * blk.w); g.N = blk.co; g.K = kkc;
+    g.bias = net->bc ? net->bc[i] : nullptr;
+    g.epilogue = EPI_BIAS;
+    g.C = at(ws, blk.z); g.ldc = blk.co;
+    return g;
+  };
+  auto gathered_filter_product = [&](int i) {
+    const ConvBlock &blk = cp.blocks[i];
+    GemmArgs g = filter_product(i, true);
+    g.A = image[i]; g.conv_k = blk.k; g.conv_h = blk.h; g.conv_w = blk.w; g.conv_c = blk.ci;
+    g.batch_A = (int64_t)blk.h * blk.w * blk.ci;
+    return g;
+  };
+  auto gathers = [&](int i) {
+    const ConvBlock &blk = cp.blocks[i];
+    if (blk.ci % 4 != 0 || image[i] == nullptr) return false;
+    const int64_t tiles = ((B * blk.h * blk.w + 63) / 64) * ((blk.co + 63) / 64);
+    return tiles >= 128 && conv_gather_supported(forward_product(i, true)) &&
+           conv_gather_supported(gathered_filter_product(i));
+  };
 
   // ---- conv blocks, forward: patches, one product over the rows (b, y, x), relu + pooling ----
   const float *in = static_cast<const float *>(X);
   for (int i = 0; i < nc; ++i) {
     const ConvBlock &blk = cp.blocks[i];
-    const int64_t rows = B * blk.h * blk.w;
-    const int kkc = blk.k * blk.k * blk.ci;
+    image[i] = in;
     const bool want_filter = dWc_out && dWc_out[i];
-    PFG_LAUNCH("im2col", launch_im2col(in, B, blk.h, blk.w, blk.ci, blk.k, at(ws, blk.P),
-                                       (want_filter && !filter_reads_P(i)) ? at(ws, blk.PT) : nullptr, stream));
-    GemmArgs g{};
-    g.A = at(ws, blk.P); g.lda = kkc; g.a_batch_stride = kkc; g.S = 1; g.a_is_f32 = 1;
-    g.W = net->Wc[i]; g.ldw = blk.co; g.w_kn = 1;
-    g.M = (int32_t)rows; g.N = blk.co; g.K = kkc;
-    g.bias = net->bc ? net->bc[i] : nullptr;
-    g.epilogue = EPI_BIAS;
-    g.C = at(ws, blk.z); g.ldc = blk.co;
-    PFG_LAUNCH("conv_gemm_forward", launch_gemm(g, stream));
+    const bool gathered = gathers(i);
+    if (!gathered)
+      PFG_LAUNCH("im2col", launch_im2col(in, B, blk.h, blk.w, blk.ci, blk.k, at(ws, blk.P),
+                                         (want_filter && !filter_reads_P(i)) ? at(ws, blk.PT) : nullptr, stream));
+    PFG_LAUNCH("conv_gemm_forward", launch_gemm(forward_product(i, gathered), stream));
     PFG_LAUNCH("relu_pool", launch_relu_pool(at(ws, blk.z), B, blk.h, blk.w, blk.co, at(ws, blk.pooled),
                                              reinterpret_cast<uint8_t *>(static_cast<char *>(ws) + blk.which),
                                              stream));
@@ -991,7 +1021,8 @@ int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, 
       if (dbc) PFG_LAUNCH("sum_positions", launch_sum_steps(dz, B, hw, blk.co, dbc, at(ws, cp.psum), stream));
     }
     if (dWc_out && dWc_out[i])
-      PFG_LAUNCH("conv_gemm_filter", launch_gemm(filter_product(i, filter_reads_P(i)), stream));
+      PFG_LAUNCH("conv_gemm_filter", launch_gemm(gathers(i) ? gathered_filter_product(i)
+                                                            : filter_product(i, filter_reads_P(i)), stream));
     bool lower = false;
     for (int j = 0; j < i; ++j) lower = lower || (dWc_out && dWc_out[j]) || (dbc_out && dbc_out[j]);
     if (!lower) break;

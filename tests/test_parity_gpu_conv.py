@@ -109,6 +109,7 @@ CONV_SHAPES = [
     (20, 12, 2, ((7, 5),), (33, 7), 70),                 # a 7 x 7 filter; enough rows for the tiled kernels
     (8, 12, 4, ((3, 12), (3, 8)), (11, 6), 140),         # filter gradients read the patches transposed
     (8, 8, 8, ((3, 64),), (9,), 70),                     # the same with a wide filter bank
+    (10, 6, 8, ((5, 16),), (12,), 300),                  # products that gather their patches from the image (c % 4 == 0, many rows)
 ]
 
 
@@ -211,6 +212,7 @@ NORM_SHAPES = [
     (20, 12, 2, ((7, 5),), (33, 7), 70, (0, 1, 2)),
     (8, 12, 4, ((3, 12), (3, 8)), (11, 6), 140, ()),
     (8, 8, 8, ((3, 64),), (9,), 70, ()),
+    (10, 6, 8, ((5, 16),), (12,), 300, (0,)),
 ]
 
 
