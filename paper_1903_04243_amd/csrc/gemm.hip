@@ -866,7 +866,10 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
     }
   }
   if (g.a_km) return hipErrorInvalidValue;    // transposed A: float32 with W in [K, N] layout only
-  if (big >= 512 && g.N > 64)
+  // (and with a contraction of one or two stages a product is all prologue and epilogue, which four
+  // small workgroups per unit overlap better than two large ones: the 25088 x 800 x 64 cotangent
+  // product of the conv net took 48 us on 128 x 128 tiles, 39 us on 64 x 64)
+  if (big >= 512 && g.N > 64 && g.K > 128)
     return fast ? launch_one<AMODE, WKN, 2, 2, 128, true>(g, stream)
                 : launch_one<AMODE, WKN, 2, 2, 128, false>(g, stream);
   if constexpr (AMODE != A_F32) {
