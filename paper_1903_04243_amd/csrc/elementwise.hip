@@ -332,9 +332,10 @@ int split_k_shape(int64_t M, int64_t N, int64_t K, int bf16) {
   }
   // 128 to 256 tiles: the tiled kernel would run one workgroup on some or all of the 256 units.
   // bf16 products are then bound by the instruction issue of a single wave per SIMD, float32
-  // products leave units idle; two pieces give every unit two workgroups.
+  // products leave units idle; two pieces give every unit two workgroups.  (float32 products of
+  // 128 to 191 tiles go to the small-problem kernels instead, see launch_gemm.)
   if (bf16) return (tiles64 <= 256 && K >= 2048 && K % 128 == 0) ? 2 : 1;
-  return (tiles64 < 256 && K % 16 == 0) ? 2 : 1;
+  return (tiles64 >= 192 && tiles64 < 256 && K % 16 == 0) ? 2 : 1;
 }
 
 hipError_t launch_gemm_split(const GemmArgs &g, int Z, float *partials, hipStream_t stream) {

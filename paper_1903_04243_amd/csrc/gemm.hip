@@ -955,7 +955,11 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
   // from 8 entries on, one launch of the tiled kernel on few workgroups is the shorter way)
   if (lstm_step_tiled_applies(g))
     return launch_one<A_F32, true, 1, 1, 128, true, 2, 2, false, false, true>(g, stream);
-  const bool few_tiles = tiles64 < 128 && g.nbatch < 8;
+  // float32, 128 to 191 tiles: the tiled kernel would run on that many of the 256 units, the
+  // small-problem kernels spread the same product over four times as many workgroups (1024 rows
+  // against 784 x 512 weights: 31 against 45 us; from about 200 tiles on the tiled kernel is level)
+  const bool few_tiles = (tiles64 < 128 && g.nbatch < 8) ||
+                         (tiles64 < 192 && g.nbatch <= 1 && !g.bf16 && g.a_is_f32 && g.sym_n == 0);
   if (g.epilogue == EPI_HEAD || g.epilogue == EPI_LSTM_FWD || few_tiles || narrow || small16_batched_applies(g))
     return launch_gemm_skinny(g, stream);
   if (!g.bf16) {

@@ -352,9 +352,9 @@ def test_long_contractions_are_cut_into_pieces(oracle):
 
 
 def test_float32_product_with_one_workgroup_per_unit_is_cut_in_two(oracle):
-    # 520 rows against 1024 x 1024 weights: 144 tiles of 64 x 64, which the tiled kernel would run
-    # on 144 of the 256 units; the product is computed as two pieces instead
-    dims, B, act = (1024, 1024, 10), 520, "gelu"
+    # 800 rows against 1024 x 1024 weights: 208 tiles of 64 x 64, which the tiled kernel would run
+    # on 208 of the 256 units; the product is computed as two pieces instead
+    dims, B, act = (1024, 1024, 10), 800, "gelu"
     say(f"two-piece product: dims {dims} B={B}")
     w = wl.Workload("split2", 64, "per_example_grads", dims, act, "f32", B, "normal", "normal_fan_in")
     inp = draw(w, bias_scale=0.2)
