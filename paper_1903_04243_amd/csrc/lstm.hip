@@ -73,10 +73,11 @@ __global__ __launch_bounds__(kThreads) void lstm_cell_backward_kernel(
 // out[b, i, j] = sum_{t < nt} a[b * a_bs + t * a_ts + i] * g[b * g_bs + t * g_ts + j]
 // (Section 3.4's both-operands-stacked matmul with a contraction over the time steps).  A lane keeps
 // its four columns of all nt cotangent rows in registers and walks the rows i of its chunk; the a
-// values of the chunk (uniform over the workgroup) are fetched once into LDS.  At most kMaxSteps
-// steps per pass; later passes add to the result.  One launch covers up to two row blocks of the same
+// values of the chunk (uniform over the workgroup) are fetched once into LDS.  At most kPassSteps
+// steps per launch; later launches add to the result.  One launch covers up to two row blocks of the same
 // per-example matrix (here: the input rows and the recurrent rows of the LSTM weight gradient).
-constexpr int kMaxSteps = 16;
+constexpr int kMaxSteps = 16;      // steps whose cotangent values a lane holds at a time
+constexpr int kPassSteps = 64;     // steps of one launch (runs of kMaxSteps); more take further launches
 constexpr int kRowsPerBlock = 4;     // measured best of 2 / 4 / 8 / 16 on the 384 x 1024 gradient
 
 struct OuterSumPart {
@@ -100,7 +101,10 @@ struct OuterSumArgs {
 // loops over the steps pay for the steps they have.
 template <int NT>
 __global__ __launch_bounds__(kThreads) void outer_sum_kernel(const OuterSumArgs p) {
-  __shared__ __align__(16) float a_s[kRowsPerBlock][NT];
+  // a pass of more than kMaxSteps steps (only with NT == kMaxSteps) is walked in runs of NT steps
+  // with the sums kept in registers, so that the result is still written once
+  constexpr int NTL = (NT == kMaxSteps) ? kPassSteps : NT;
+  __shared__ __align__(16) float a_s[kRowsPerBlock][NTL];
   const int64_t b = blockIdx.y;
   const int col_chunks = (p.d_out + 4 * kThreads - 1) / (4 * kThreads);
   const int cchunk = blockIdx.x % col_chunks;
@@ -114,45 +118,54 @@ __global__ __launch_bounds__(kThreads) void outer_sum_kernel(const OuterSumArgs 
   const float *g = q.g + b * q.g_bs;
   float *out = q.out + b * p.out_bs;
   // the chunk's a values: adjacent lanes fetch adjacent rows of one step; kept step-fastest
-  for (int e = threadIdx.x; e < NT * kRowsPerBlock; e += kThreads) {
+  for (int e = threadIdx.x; e < NTL * kRowsPerBlock; e += kThreads) {
     const int t = e / kRowsPerBlock, r = e % kRowsPerBlock;
     a_s[r][t] = (t < q.nt && r < nrows) ? a[t * q.a_ts + i0 + r] : 0.f;
   }
   __syncthreads();
   const int j = (cchunk * kThreads + threadIdx.x) * 4;
   if (j >= p.d_out) return;
-  f32x4 gv[NT];
+  f32x4 acc[kRowsPerBlock];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    gv[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (t < q.nt) {
-      if (p.vec) {
-        gv[t] = *reinterpret_cast<const f32x4 *>(g + t * q.g_ts + j);
-      } else {
+  for (int r = 0; r < kRowsPerBlock; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int t0 = 0; t0 < NTL && t0 < q.nt; t0 += NT) {
+    f32x4 gv[NT];
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          if (j + e < p.d_out) gv[t][e] = g[t * q.g_ts + j + e];
+    for (int t = 0; t < NT; ++t) {
+      gv[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (t0 + t < q.nt) {
+        if (p.vec) {
+          gv[t] = *reinterpret_cast<const f32x4 *>(g + (t0 + t) * q.g_ts + j);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (j + e < p.d_out) gv[t][e] = g[(t0 + t) * q.g_ts + j + e];
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < kRowsPerBlock; ++r) {
+#pragma unroll
+      for (int t4 = 0; t4 < NT; t4 += 4) {
+        const f32x4 av = *reinterpret_cast<const f32x4 *>(&a_s[r][t0 + t4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[r] += av[e] * gv[t4 + e];      // steps past nt hold zeros
       }
     }
   }
-  for (int r = 0; r < nrows; ++r) {
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int t4 = 0; t4 < NT; t4 += 4) {
-      const f32x4 av = *reinterpret_cast<const f32x4 *>(&a_s[r][t4]);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc += av[e] * gv[t4 + e];           // steps past nt hold zeros
-    }
+  for (int r = 0; r < kRowsPerBlock; ++r) {
+    if (r >= nrows) break;
     float *o = out + (int64_t)(i0 + r) * p.d_out + j;
     if (p.vec) {
       if (p.accumulate)
-        *reinterpret_cast<f32x4 *>(o) = *reinterpret_cast<const f32x4 *>(o) + acc;
+        *reinterpret_cast<f32x4 *>(o) = *reinterpret_cast<const f32x4 *>(o) + acc[r];
       else
-        __builtin_nontemporal_store(acc, reinterpret_cast<f32x4 *>(o));
+        __builtin_nontemporal_store(acc[r], reinterpret_cast<f32x4 *>(o));
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        if (j + e < p.d_out) o[e] = p.accumulate ? o[e] + acc[e] : acc[e];
+        if (j + e < p.d_out) o[e] = p.accumulate ? o[e] + acc[r][e] : acc[r][e];
     }
   }
 }
@@ -309,7 +322,7 @@ hipError_t launch_outer_sum(const OuterSumJob *jobs, int njobs, int64_t B, int32
       for (int k = 0; k < njobs; ++k) {
         const OuterSumJob &jb = jobs[k];
         int nt = jb.nt - t0;                           // a job with no step left contributes zeros
-        nt = nt < 0 ? 0 : (nt > kMaxSteps ? kMaxSteps : nt);
+        nt = nt < 0 ? 0 : (nt > kPassSteps ? kPassSteps : nt);
         OuterSumPart &q = p.part[k];
         q.a = jb.a + b0 * jb.a_bs + (int64_t)t0 * jb.a_ts; q.a_bs = jb.a_bs; q.a_ts = jb.a_ts;
         q.g = jb.g + b0 * jb.g_bs + (int64_t)t0 * jb.g_ts; q.g_bs = jb.g_bs; q.g_ts = jb.g_ts;
@@ -327,7 +340,7 @@ hipError_t launch_outer_sum(const OuterSumJob *jobs, int njobs, int64_t B, int32
       else                    PFG_KERNEL(outer_sum_kernel<kMaxSteps>, grid, dim3(kThreads), 0, stream, p);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
-      t0 += kMaxSteps;
+      t0 += kPassSteps;
     } while (t0 < max_nt);
   }
   return hipSuccess;

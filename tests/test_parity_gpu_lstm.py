@@ -105,7 +105,8 @@ LSTM_SHAPES = [
     (5, 7, 3, 1, 4),            # one step
     (33, 65, 10, 4, 9),         # one past the tile edges
     (20, 36, 40, 6, 17),        # more than 32 outputs: separate loss head
-    (16, 32, 8, 18, 5),         # more steps than one pass of the weight-gradient kernel holds
+    (16, 32, 8, 18, 5),         # more steps than a lane of the weight-gradient kernel holds at a time
+    (6, 12, 4, 70, 3),          # more steps than one launch of that kernel takes: a second one adds to the result
     (64, 96, 12, 3, 130),       # enough rows for the tiled kernels in the input projection
     (16, 128, 5, 3, 2100),      # a large batch: the cell update in the epilogue of the tiled product
     (8, 30, 4, 3, 8200),        # a large batch, state size not a multiple of 4: tiled product, separate cell kernel
@@ -119,7 +120,13 @@ def test_lstm_odd_shapes_grads_and_jacobian(dx, H, dy, T, B):
     w = wl.LstmWorkload("odd", 300 + dx + H + T, "lstm_per_example_grads", dx, H, dy, T, B)
     inp = wl.make_lstm_inputs(w, bias_scale=0.3)
     check_lstm_grads(inp, "lstm-odd")
-    check_lstm_norms(inp, "lstm-odd-norms")
+    if T <= 64:
+        check_lstm_norms(inp, "lstm-odd-norms")
+    else:                       # the Gram-matrix kernel holds at most 64 steps
+        net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, T)
+        with pytest.raises(pfg.PfgError) as ei:
+            pfg.pfg_lstm_per_example_grad_norms(net, dev(inp.X), dev(inp.labels))
+        assert ei.value.code == pfg.PFG_ERR_UNSUPPORTED
     rng = np.random.default_rng(B + T)
     shared = rng.standard_normal((3, dy)).astype(np.float32)
     per_ex = rng.standard_normal((B, 2, dy)).astype(np.float32)
