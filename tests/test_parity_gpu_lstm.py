@@ -287,6 +287,7 @@ VARLEN_SHAPES = [
     (5, 7, 3, 9, 1),             # a single sequence
     (33, 65, 10, 12, 40),        # one past the tile edges; more sequences than one row tile
     (16, 32, 40, 30, 100),
+    (16, 64, 5, 12, 900),        # the first steps have more than 768 active rows: the tiled fused step
 ]
 
 

@@ -201,3 +201,34 @@ def test_convnet_grads_and_norms_random_shapes(h, w, c, blocks, dense, B):
             float(np.max(np.abs(norm.cpu().numpy()[idx] - rnorm) / rnorm)))
     say(f"  rel err {e:.3e} on {len(idx)} of {B} examples")
     assert e <= TOL_F32
+
+
+def cond_cases(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        pre = tuple(int(rng.choice([6, 24, 64, 200])) for _ in range(int(rng.integers(2, 4))))
+        dout = int(rng.choice([3, 8, 40]))
+        then_dims = tuple(int(rng.choice([16, 96, 512])) for _ in range(int(rng.integers(0, 3)))) + (dout,)
+        else_dims = tuple(int(rng.choice([12, 64])) for _ in range(int(rng.integers(0, 2)))) + (dout,)
+        out.append((pre, then_dims, else_dims, str(rng.choice(["tanh", "gelu"])), int(rng.choice([5, 90, 1500, 9000]))))
+    return out
+
+
+@pytest.mark.parametrize("pre,then_dims,else_dims,act,n", cond_cases(31, 6), ids=lambda v: str(v).replace(" ", ""))
+def test_cond_random_shapes(pre, then_dims, else_dims, act, n):
+    from test_parity_gpu_cond import check_cond
+    say(f"random cond pre={pre} then={then_dims} else={else_dims} {act} n={n}")
+    wk = wl.CondWorkload("rndq", 1300 + n, pre, then_dims, else_dims, act, n)
+    inp = wl.make_cond_inputs(wk, bias_scale=0.2)
+    check_cond(inp, act, "cond-rnd", expect_split=n >= 64)
+
+
+@pytest.mark.parametrize("dx,H,dy,max_len,B", [(7, 20, 3, 25, 300), (32, 128, 10, 6, 1000), (4, 8, 2, 60, 17)],
+                         ids=lambda v: str(v))
+def test_varlen_random_shapes(dx, H, dy, max_len, B):
+    from test_parity_gpu_lstm import check_varlen
+    say(f"random varlen dx={dx} H={H} dy={dy} L<={max_len} B={B}")
+    w = wl.LstmWorkload("rndv", 1400 + H + B, "lstm_varlen_forward", dx, H, dy, max_len, B)
+    inp, lengths = wl.make_varlen_inputs(w, bias_scale=0.3)
+    check_varlen(inp, lengths, f"varlen-rnd dx={dx} H={H} L<={max_len}")
