@@ -101,9 +101,68 @@ struct OuterSumArgs {
 // loops over the steps pay for the steps they have.
 template <int NT>
 __global__ __launch_bounds__(kThreads) void outer_sum_kernel(const OuterSumArgs p) {
-  // a pass of more than kMaxSteps steps (only with NT == kMaxSteps) is walked in runs of NT steps
-  // with the sums kept in registers, so that the result is still written once
-  constexpr int NTL = (NT == kMaxSteps) ? kPassSteps : NT;
+  __shared__ __align__(16) float a_s[kRowsPerBlock][NT];
+  const int64_t b = blockIdx.y;
+  const int col_chunks = (p.d_out + 4 * kThreads - 1) / (4 * kThreads);
+  const int cchunk = blockIdx.x % col_chunks;
+  int rchunk = blockIdx.x / col_chunks;
+  const bool second = (p.nparts > 1) && (rchunk >= p.part[0].row_chunks);
+  const OuterSumPart &q = p.part[second ? 1 : 0];
+  if (second) rchunk -= p.part[0].row_chunks;
+  const int i0 = rchunk * kRowsPerBlock;
+  const int nrows = min(q.d_in - i0, kRowsPerBlock);
+  const float *a = q.a + b * q.a_bs;
+  const float *g = q.g + b * q.g_bs;
+  float *out = q.out + b * p.out_bs;
+  // the chunk's a values: adjacent lanes fetch adjacent rows of one step; kept step-fastest
+  for (int e = threadIdx.x; e < NT * kRowsPerBlock; e += kThreads) {
+    const int t = e / kRowsPerBlock, r = e % kRowsPerBlock;
+    a_s[r][t] = (t < q.nt && r < nrows) ? a[t * q.a_ts + i0 + r] : 0.f;
+  }
+  __syncthreads();
+  const int j = (cchunk * kThreads + threadIdx.x) * 4;
+  if (j >= p.d_out) return;
+  f32x4 gv[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    gv[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (t < q.nt) {
+      if (p.vec) {
+        gv[t] = *reinterpret_cast<const f32x4 *>(g + t * q.g_ts + j);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (j + e < p.d_out) gv[t][e] = g[t * q.g_ts + j + e];
+      }
+    }
+  }
+  for (int r = 0; r < nrows; ++r) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t4 = 0; t4 < NT; t4 += 4) {
+      const f32x4 av = *reinterpret_cast<const f32x4 *>(&a_s[r][t4]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc += av[e] * gv[t4 + e];           // steps past nt hold zeros
+    }
+    float *o = out + (int64_t)(i0 + r) * p.d_out + j;
+    if (p.vec) {
+      if (p.accumulate)
+        *reinterpret_cast<f32x4 *>(o) = *reinterpret_cast<const f32x4 *>(o) + acc;
+      else
+        __builtin_nontemporal_store(acc, reinterpret_cast<f32x4 *>(o));
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (j + e < p.d_out) o[e] = p.accumulate ? o[e] + acc[e] : acc[e];
+    }
+  }
+}
+
+// More than kMaxSteps steps in one launch: walked in runs of kMaxSteps steps with the sums of the
+// workgroup's rows kept in registers, so that the result is still written once.  (Kept apart from
+// the kernel above, which is 3 % faster on a single run.)
+__global__ __launch_bounds__(kThreads) void outer_sum_runs_kernel(const OuterSumArgs p) {
+  constexpr int NT = kMaxSteps, NTL = kPassSteps;
   __shared__ __align__(16) float a_s[kRowsPerBlock][NTL];
   const int64_t b = blockIdx.y;
   const int col_chunks = (p.d_out + 4 * kThreads - 1) / (4 * kThreads);
@@ -337,7 +396,8 @@ hipError_t launch_outer_sum(const OuterSumJob *jobs, int njobs, int64_t B, int32
       if (pass_nt <= 4)       PFG_KERNEL(outer_sum_kernel<4>, grid, dim3(kThreads), 0, stream, p);
       else if (pass_nt <= 8)  PFG_KERNEL(outer_sum_kernel<8>, grid, dim3(kThreads), 0, stream, p);
       else if (pass_nt <= 12) PFG_KERNEL(outer_sum_kernel<12>, grid, dim3(kThreads), 0, stream, p);
-      else                    PFG_KERNEL(outer_sum_kernel<kMaxSteps>, grid, dim3(kThreads), 0, stream, p);
+      else if (pass_nt <= kMaxSteps) PFG_KERNEL(outer_sum_kernel<kMaxSteps>, grid, dim3(kThreads), 0, stream, p);
+      else                    PFG_KERNEL(outer_sum_runs_kernel, grid, dim3(kThreads), 0, stream, p);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
       t0 += kPassSteps;
