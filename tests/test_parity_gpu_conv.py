@@ -280,6 +280,47 @@ def test_c10_mnist_convnet_grad_norms_full_size():
     assert (sq[:, -1].double() >= (1.0 - p_label) ** 2 * (1 - 1e-5)).all()
 
 
+def test_convnet_calls_replay_from_a_graph():
+    # gradients and gradient norms of one network captured into one HIP graph (the library records
+    # kernel launches only) and replayed with eager work and synchronisations in between: every
+    # replay reproduces the eager results bit for bit.  The shape takes the products that gather
+    # their patches from the image, the fused unpool + bias kernel and the split filter products.
+    wk = wl.ConvWorkload("graphc", 560, 12, 12, 4, ((3, 8), (3, 16)), (24, 7), 96)
+    inp = wl.make_conv_inputs(wk, bias_scale=0.2)
+    B, h, w, c = inp.X.shape
+    net = pfg.ConvNet.from_numpy(h, w, c, inp.Wc, inp.bc, inp.Ws, inp.bs)
+    X, labels = dev(inp.X), dev(inp.labels)
+    eager = pfg.pfg_convnet_per_example_grads(net, X, labels)
+    eager_n = pfg.pfg_convnet_per_example_grad_norms(net, X, labels)
+    torch.cuda.synchronize()
+    flat = lambda o: list(o[0]) + list(o[1]) + list(o[2]) + list(o[3]) + [o[4]]
+    out = tuple([torch.empty_like(t) for t in part] if isinstance(part, list) else torch.empty_like(part)
+                for part in eager)
+    out_n = tuple(torch.empty_like(t) for t in eager_n)
+    ws = torch.empty(pfg.pfg_convnet_workspace_bytes(net, B), dtype=torch.uint8, device="cuda:0")
+    ws_n = torch.empty(pfg.pfg_convnet_grad_norms_workspace_bytes(net, B), dtype=torch.uint8,
+                       device="cuda:0")
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(stream):
+        pfg.pfg_convnet_per_example_grads(net, X, labels, out=out, workspace=ws)
+        pfg.pfg_convnet_per_example_grad_norms(net, X, labels, out=out_n, workspace=ws_n)
+    stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        pfg.pfg_convnet_per_example_grads(net, X, labels, out=out, workspace=ws)
+        pfg.pfg_convnet_per_example_grad_norms(net, X, labels, out=out_n, workspace=ws_n)
+    for rep in range(3):
+        for t in flat(out) + list(out_n):
+            t.fill_(float("nan"))
+        pfg.pfg_convnet_per_example_grad_norms(net, X, labels)     # an eager call in between
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(flat(out), flat(eager))), f"replay {rep}: gradients"
+        assert all(torch.equal(a, b) for a, b in zip(out_n, eager_n)), f"replay {rep}: norms"
+
+
 def test_convnet_rejects_bad_arguments():
     wk = wl.ConvWorkload("badc", 541, 6, 6, 1, ((3, 2),), (4,), 2)      # 6 -> 3: fine for one block
     inp = wl.make_conv_inputs(wk)
