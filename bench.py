@@ -381,13 +381,24 @@ def main():
         # the conv products, against the fp32 MFMA peak
         hh, ww, cc = w.height, w.width, w.channels
         conv_flops = {"conv_gemm_forward": 0, "conv_gemm_filter": 0, "conv_gemm_cotangent": 0}
+        direct = 0
         for i, (k, f) in enumerate(w.blocks):
             per = 2 * B * hh * ww * k * k * cc * f
-            conv_flops["conv_gemm_forward"] += per
+            # a block with few taps per output goes from the image to the pooled output in one plain
+            # ALU kernel (the library's rule, restated; the launch counts below check it): its
+            # forward flops are not the matrix cores'
+            taps = k * k * cc
+            if taps <= 64 and f % 4 == 0 and taps * f <= 4096 and (k + 1) * (ww + k - 1) * cc <= 4096:
+                direct += 1
+            else:
+                conv_flops["conv_gemm_forward"] += per
             conv_flops["conv_gemm_filter"] += per
             if i > 0:
                 conv_flops["conv_gemm_cotangent"] += per
             hh, ww, cc = hh // 2, ww // 2, f
+        seen = kt.get("conv_relu_pool", {}).get("launches_per_step", 0)
+        if round(seen) != direct:
+            raise RuntimeError(f"{direct} conv blocks expected in the image-to-pooled-output kernel, {seen} launched")
         conv_report = {fam2: {"flops_per_step": fl, "TFLOP/s": fl / kt[fam2]["ms_per_step"] / 1e9,
                               "mfma_frac": fl / kt[fam2]["ms_per_step"] / 1e9 / MFMA_PEAK_TFLOPS["f32"]}
                        for fam2, fl in conv_flops.items() if fam2 in kt and fl}

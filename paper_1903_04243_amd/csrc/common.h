@@ -283,6 +283,15 @@ hipError_t launch_sum_steps(const float *g, int64_t B, int32_t T, int32_t d, flo
 hipError_t launch_im2col(const float *in, int64_t B, int32_t h, int32_t w, int32_t c, int32_t k,
                          float *P, float *PT, hipStream_t stream);
 
+// A conv block whose outputs sum over few taps (k k c_in <= 64, a multiple of four filters, the
+// filter bank and a band of the padded image in LDS): forward product + bias, relu and 2 x 2 pooling
+// in one kernel that reads the image itself; pooled / which as launch_relu_pool writes them.
+bool conv_relu_pool_applies(const float *in, const float *Wc, const float *bias, int64_t B, int32_t h, int32_t w,
+                            int32_t ci, int32_t k, int32_t co, const float *pooled, const uint8_t *which);
+hipError_t launch_conv_relu_pool(const float *in, const float *Wc, const float *bias, int64_t B, int32_t h,
+                                 int32_t w, int32_t ci, int32_t k, int32_t co, float *pooled, uint8_t *which,
+                                 hipStream_t stream);
+
 // pooled [B, h/2, w/2, c] = max over 2 x 2 windows of relu(z [B, h, w, c]); which = index 0..3 of the
 // window entry that gave it
 hipError_t launch_relu_pool(const float *z, int64_t B, int32_t h, int32_t w, int32_t c, float *pooled,

@@ -468,6 +468,96 @@ __global__ __launch_bounds__(kThreads) void col2im_kernel(const float *dP, int64
   }
 }
 
+
+// ---- a conv block with FEW input values per output (first layers on images: one or a few ----
+// channels, a small filter): forward product, relu and 2 x 2 pooling in one kernel, no patch
+// matrix and no pre-activation in memory.  A workgroup takes a band of pooled rows of one example:
+// the zero-padded band of the image and the whole filter bank sit in LDS, a work item is one pooled
+// cell and four filters (its four window positions, 16 sums, each over the taps in the order
+// (dy, dx, channel) of the filter layout).  Output as relu_pool_kernel writes it.
+constexpr int kDirectWeights = 4096;   // floats of LDS for the filter bank
+constexpr int kDirectPatch = 4096;     // floats of LDS for the padded band of the image
+constexpr int kDirectTaps = 64;        // k k c_in up to this: beyond, the matrix cores win
+
+__global__ __launch_bounds__(kThreads) void conv_relu_pool_kernel(const float *in, const float *Wc,
+                                                                  const float *bias, int h, int w, int ci, int k,
+                                                                  int co, int band, float *pooled,
+                                                                  uint8_t *which) {
+  __shared__ __align__(16) float wts[kDirectWeights];
+  __shared__ float patch[kDirectPatch];
+  const int p = (k - 1) / 2, ho = h / 2, wo = w / 2, kkc = k * k * ci;
+  const int bands = (ho + band - 1) / band;
+  const int64_t b = blockIdx.x / bands;
+  const int yo0 = (int)(blockIdx.x % bands) * band;
+  const int rows_o = min(band, ho - yo0);
+  const int pr = 2 * rows_o + k - 1, pw = w + k - 1, pwc = pw * ci;   // the padded band: rows, columns
+  for (int i = threadIdx.x; i < kkc * co / 4; i += kThreads)
+    reinterpret_cast<f32x4 *>(wts)[i] = reinterpret_cast<const f32x4 *>(Wc)[i];
+  const float *src = in + b * h * w * ci;
+  for (int i = threadIdx.x; i < pr * pwc; i += kThreads) {
+    const int r = i / pwc, rem = i - r * pwc, q = rem / ci;
+    const int y = 2 * yo0 - p + r, x = q - p;
+    patch[i] = (y >= 0 && y < h && x >= 0 && x < w) ? src[(y * w + x) * ci + (rem - q * ci)] : 0.f;
+  }
+  __syncthreads();
+  const int co4 = co / 4, kc = k * ci;
+  const int items = rows_o * wo * co4;
+  for (int it = threadIdx.x; it < items; it += kThreads) {
+    const int fq = it % co4, cell = it / co4;
+    const int yl = cell / wo, xo = cell - yl * wo;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    const f32x4 bv = bias ? *reinterpret_cast<const f32x4 *>(bias + 4 * fq) : zero;
+    f32x4 acc[4] = {bv, bv, bv, bv};
+    // tap (dy, dx, c) of window position (py, px): patch row 2 yl + py + dy, column 2 xo + px + dx;
+    // for one dy the offsets dx ci + c run through 0 .. k ci - 1, and so do the filter's rows
+    const float *origin = patch + (2 * yl * pw + 2 * xo) * ci;
+    const float *wp = wts + 4 * fq;
+    for (int dy = 0; dy < k; ++dy) {
+      const float *q0 = origin + dy * pwc;
+      const float *wrow = wp + dy * kc * co;
+#pragma unroll 5
+      for (int t = 0; t < kc; ++t) {
+        const f32x4 wv = *reinterpret_cast<const f32x4 *>(wrow + t * co);
+        const float v00 = q0[t], v01 = q0[t + ci], v10 = q0[t + pwc], v11 = q0[t + pwc + ci];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          acc[0][q] = fmaf(v00, wv[q], acc[0][q]);
+          acc[1][q] = fmaf(v01, wv[q], acc[1][q]);
+          acc[2][q] = fmaf(v10, wv[q], acc[2][q]);
+          acc[3][q] = fmaf(v11, wv[q], acc[3][q]);
+        }
+      }
+    }
+    f32x4 best = {-1.f, -1.f, -1.f, -1.f};
+    uint32_t arg = 0;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float a = acc[d][q] > 0.f ? acc[d][q] : 0.f;
+        if (a > best[q]) {
+          best[q] = a;
+          arg = (arg & ~(0xffu << (8 * q))) | ((uint32_t)d << (8 * q));
+        }
+      }
+    }
+    const int64_t group = ((b * ho + yo0 + yl) * wo + xo) * co4 + fq;   // four channels of a pooled cell
+    *reinterpret_cast<f32x4 *>(pooled + 4 * group) = best;
+    *reinterpret_cast<uint32_t *>(which + 4 * group) = arg;
+  }
+}
+
+// pooled rows per workgroup: about 1024 workgroups over the batch (measured best of 256 .. 2048), a band that fits the LDS buffer
+// (0: none does)
+int direct_band(int64_t B, int h, int w, int ci, int k) {
+  const int ho = h / 2;
+  const int64_t per_example = std::max<int64_t>(1, std::min<int64_t>(ho, (1024 + B - 1) / B));
+  int band = (int)((ho + per_example - 1) / per_example);
+  const int64_t pwc = (int64_t)(w + k - 1) * ci;
+  while (band > 1 && (2 * band + k - 1) * pwc > kDirectPatch) --band;
+  return (2 * band + k - 1) * pwc > kDirectPatch ? 0 : band;
+}
+
 }  // namespace
 
 hipError_t launch_im2col(const float *in, int64_t B, int32_t h, int32_t w, int32_t c, int32_t k,
@@ -510,6 +600,29 @@ hipError_t launch_relu_pool(const float *z, int64_t B, int32_t h, int32_t w, int
   if (total <= 0) return hipSuccess;
   PFG_KERNEL(relu_pool_kernel, dim3(capped_blocks(total)), dim3(kThreads), 0, stream, z, B, h, w, c,
              pooled, which);
+  return hipGetLastError();
+}
+
+bool conv_relu_pool_applies(const float *in, const float *Wc, const float *bias, int64_t B, int32_t h, int32_t w,
+                            int32_t ci, int32_t k, int32_t co, const float *pooled, const uint8_t *which) {
+  if (!in || !Wc || !pooled || !which || B < 1 || h < 2 || w < 2 || h % 2 || w % 2) return false;
+  const int64_t kkc = (int64_t)k * k * ci;
+  if (co % 4 != 0 || kkc > kDirectTaps || kkc * co > kDirectWeights) return false;
+  const int band = direct_band(B, h, w, ci, k);
+  if (band < 1 || B * ((h / 2 + band - 1) / band) > 0x7fffffffLL) return false;
+  return (reinterpret_cast<uintptr_t>(which) & 3) == 0 &&
+         ((reinterpret_cast<uintptr_t>(Wc) | reinterpret_cast<uintptr_t>(bias) |
+           reinterpret_cast<uintptr_t>(pooled)) & 15) == 0;
+}
+
+hipError_t launch_conv_relu_pool(const float *in, const float *Wc, const float *bias, int64_t B, int32_t h,
+                                 int32_t w, int32_t ci, int32_t k, int32_t co, float *pooled, uint8_t *which,
+                                 hipStream_t stream) {
+  if (!conv_relu_pool_applies(in, Wc, bias, B, h, w, ci, k, co, pooled, which)) return hipErrorInvalidValue;
+  const int band = direct_band(B, h, w, ci, k);
+  const int64_t bands = (h / 2 + band - 1) / band;
+  PFG_KERNEL(conv_relu_pool_kernel, dim3((unsigned)(B * bands)), dim3(kThreads), 0, stream, in, Wc, bias, h, w,
+             ci, k, co, band, pooled, which);
   return hipGetLastError();
 }
 

@@ -952,13 +952,28 @@ int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, 
     image[i] = in;
     const bool want_filter = dWc_out && dWc_out[i];
     const bool gathered = gathers(i);
-    if (!gathered)
-      PFG_LAUNCH("im2col", launch_im2col(in, B, blk.h, blk.w, blk.ci, blk.k, at(ws, blk.P),
-                                         (want_filter && !filter_reads_P(i)) ? at(ws, blk.PT) : nullptr, stream));
-    PFG_LAUNCH("conv_gemm_forward", launch_gemm(forward_product(i, gathered), stream));
-    PFG_LAUNCH("relu_pool", launch_relu_pool(at(ws, blk.z), B, blk.h, blk.w, blk.co, at(ws, blk.pooled),
-                                             reinterpret_cast<uint8_t *>(static_cast<char *>(ws) + blk.which),
-                                             stream));
+    uint8_t *which = reinterpret_cast<uint8_t *>(static_cast<char *>(ws) + blk.which);
+    const float *bias = net->bc ? static_cast<const float *>(net->bc[i]) : nullptr;
+    const float *filt = static_cast<const float *>(net->Wc[i]);
+    // few taps per output: one kernel from the image to the pooled output, and patches only for
+    // the filter gradient, in the layout that product reads
+    const bool direct = conv_relu_pool_applies(in, filt, bias, B, blk.h, blk.w, blk.ci, blk.k, blk.co,
+                                               at(ws, blk.pooled), which);
+    const bool filter_P = want_filter && !gathered && filter_reads_P(i);
+    const bool filter_PT = want_filter && !gathered && !filter_reads_P(i);
+    const bool forward_P = !gathered && !direct;
+    if (forward_P || filter_P || filter_PT)
+      PFG_LAUNCH("im2col", launch_im2col(in, B, blk.h, blk.w, blk.ci, blk.k,
+                                         (forward_P || filter_P) ? at(ws, blk.P) : nullptr,
+                                         filter_PT ? at(ws, blk.PT) : nullptr, stream));
+    if (direct) {
+      PFG_LAUNCH("conv_relu_pool", launch_conv_relu_pool(in, filt, bias, B, blk.h, blk.w, blk.ci, blk.k,
+                                                         blk.co, at(ws, blk.pooled), which, stream));
+    } else {
+      PFG_LAUNCH("conv_gemm_forward", launch_gemm(forward_product(i, gathered), stream));
+      PFG_LAUNCH("relu_pool", launch_relu_pool(at(ws, blk.z), B, blk.h, blk.w, blk.co, at(ws, blk.pooled), which,
+                                               stream));
+    }
     in = at(ws, blk.pooled);
   }
   const float *feat = in;       // [B, d_0]

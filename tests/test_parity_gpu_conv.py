@@ -110,6 +110,9 @@ CONV_SHAPES = [
     (8, 12, 4, ((3, 12), (3, 8)), (11, 6), 140),         # filter gradients read the patches transposed
     (8, 8, 8, ((3, 64),), (9,), 70),                     # the same with a wide filter bank
     (10, 6, 8, ((5, 16),), (12,), 300),                  # products that gather their patches from the image (c % 4 == 0, many rows)
+    (12, 20, 3, ((3, 4), (1, 8)), (5,), 37),             # few taps per output: both blocks go from image to pooled output in one kernel
+    (28, 6, 1, ((7, 8),), (6,), 600),                    # the same with one workgroup per example (14 pooled rows in a band)
+    (20, 8, 1, ((5, 12),), (7,), 90),                    # bands of 2 pooled rows and a ragged last one (5 rows)
 ]
 
 
@@ -213,6 +216,7 @@ NORM_SHAPES = [
     (8, 12, 4, ((3, 12), (3, 8)), (11, 6), 140, ()),
     (8, 8, 8, ((3, 64),), (9,), 70, ()),
     (10, 6, 8, ((5, 16),), (12,), 300, (0,)),
+    (12, 20, 3, ((3, 4), (1, 8)), (5,), 37, (1,)),       # image-to-pooled-output kernel, one block without a bias
 ]
 
 
