@@ -388,7 +388,7 @@ def main():
             # ALU kernel (the library's rule, restated; the launch counts below check it): its
             # forward flops are not the matrix cores'
             taps = k * k * cc
-            if taps <= 64 and f % 4 == 0 and taps * f <= 4096 and (k + 1) * (ww + k - 1) * cc <= 4096:
+            if taps <= 56 and f % 4 == 0 and taps * f <= 4096 and (k + 1) * (ww + k - 1) * cc <= 4096:
                 direct += 1
             else:
                 conv_flops["conv_gemm_forward"] += per

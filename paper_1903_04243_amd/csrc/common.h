@@ -283,7 +283,7 @@ hipError_t launch_sum_steps(const float *g, int64_t B, int32_t T, int32_t d, flo
 hipError_t launch_im2col(const float *in, int64_t B, int32_t h, int32_t w, int32_t c, int32_t k,
                          float *P, float *PT, hipStream_t stream);
 
-// A conv block whose outputs sum over few taps (k k c_in <= 64, a multiple of four filters, the
+// A conv block whose outputs sum over few taps (k k c_in <= 56, a multiple of four filters, the
 // filter bank and a band of the padded image in LDS): forward product + bias, relu and 2 x 2 pooling
 // in one kernel that reads the image itself; pooled / which as launch_relu_pool writes them.
 bool conv_relu_pool_applies(const float *in, const float *Wc, const float *bias, int64_t B, int32_t h, int32_t w,

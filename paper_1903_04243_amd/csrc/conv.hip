@@ -477,7 +477,7 @@ __global__ __launch_bounds__(kThreads) void col2im_kernel(const float *dP, int64
 // (dy, dx, channel) of the filter layout).  Output as relu_pool_kernel writes it.
 constexpr int kDirectWeights = 4096;   // floats of LDS for the filter bank
 constexpr int kDirectPatch = 4096;     // floats of LDS for the padded band of the image
-constexpr int kDirectTaps = 64;        // k k c_in up to this: beyond, the matrix cores win
+constexpr int kDirectTaps = 56;        // k k c_in up to this: from 64 taps on the matrix cores win
 
 __global__ __launch_bounds__(kThreads) void conv_relu_pool_kernel(const float *in, const float *Wc,
                                                                   const float *bias, int h, int w, int ci, int k,
