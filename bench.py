@@ -4,9 +4,11 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--only-primary] [--no-cpu-baseline]
 
 A step is one call of the library on one batch of seeded synthetic input that is already
-resident in HBM.  The headline line is the MNIST-shaped per-example-gradient workload
-(784 -> 512 -> 512 -> 10, ReLU, float32, batch 128); the other measured workloads are reported
-under "other_workloads" in the same JSON line.  Per-kernel durations come from HIP events the
+resident in HBM.  The last line of stdout is the headline record: the largest per-example-gradient
+workload that fits one GPU (4096 -> 4096 -> 4096 -> 10, GELU, bf16 inputs and weights, float32
+accumulation and output, batch 256: 34.4 GB written per step), with its roofline and the CPU
+baseline; the other dense workloads appear in it as short entries.  The full records of every
+workload go to gpurun_out/bench_detail.json and, a workload a line, to stderr.  Per-kernel durations come from HIP events the
 library records on the call's stream in a second, instrumented pass over the same steps.
 """
 import argparse
@@ -30,8 +32,8 @@ def log(msg):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--only-primary", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="do not also time a HIP-graph replay")
@@ -583,63 +585,107 @@ def main():
         print(json.dumps(rec), flush=True)
         return
 
-    primary = "c2_mnist_mlp_grads"
+    # The headline is the largest configuration that fits one GPU: c4 (4096-4096-4096-10, GELU, bf16
+    # inputs and weights, float32 accumulation and output, batch 256, 34.4 GB written per step).
+    primary = "c4_gelu_bf16_grads"
     rec, inp = measure(primary, args.steps, args.warmup)
+    detail = {primary: rec}
 
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
         w = wl.WORKLOADS[primary]
         onet = oracle.Net(inp.Ws, inp.bs, w.act)
-        log("[bench] cpu_baseline: float64 oracle on the same batch")
-        oracle.per_example_grads(onet, inp.X[:8], inp.labels[:8])     # load / page in
+        cores = oracle.num_threads()
+        n_sub = min(w.B, max(8, cores))           # one example per thread and pass; ~0.5 GB of float64 each
+        log(f"[bench] cpu_baseline: float64 oracle on the first {n_sub} examples of {primary}")
+        oracle.per_example_grads(onet, inp.X[:1], inp.labels[:1])     # load / page in
         passes, t_cpu = 0, 0.0
-        while passes < 3 or (t_cpu < 12.0 and passes < 2000):
+        while passes < 2 or (t_cpu < 12.0 and passes < 2000):
             t0 = time.perf_counter()
-            oracle.per_example_grads(onet, inp.X, inp.labels)
+            out = oracle.per_example_grads(onet, inp.X[:n_sub], inp.labels[:n_sub])
             t_cpu += time.perf_counter() - t0
+            del out
             passes += 1
-        cpu = {"value": w.B * passes / t_cpu, "unit": "grads/s", "cores": oracle.num_threads(),
-               "kind": "oracle",
-               "sample": f"{passes} passes over the full batch of {w.B} examples of {primary} "
-                         f"(float64, OpenMP over examples), {t_cpu:.2f} s wall"}
+        cpu = {"value": n_sub * passes / t_cpu, "unit": "grads/s", "cores": cores, "kind": "oracle",
+               "sample": f"{passes} passes over the first {n_sub} of {w.B} examples of {primary} "
+                         f"(float64, OpenMP over examples, gradients kept in host memory, no "
+                         f"comparison or copies timed), {t_cpu:.1f} s wall"}
+        log(f"[bench] cpu_baseline: {cpu['value']:.2f} grads/s on {cores} threads")
 
-    others = {}
+    failed = []
     if not args.only_primary:
-        for name, steps in (("c5_nested_weight_jacobian", args.steps),
-                            ("c3_tanh_jacobian", max(3, args.steps // 20)),
-                            ("c4_gelu_bf16_grads", max(3, args.steps // 20)),
-                            ("c2_mnist_mlp_grad_norms", args.steps),
-                            ("c4_gelu_bf16_grad_norms", max(3, args.steps // 4)),
-                            ("c6_tanh_hessian", max(3, args.steps // 20)),
-                            ("c7_lstm_grads", max(3, args.steps // 2)),
-                            ("c7_lstm_grad_norms", max(3, args.steps // 2)),
-                            ("c8_lstm_jacobian", max(3, args.steps // 10)),
-                            ("c9_lstm_varlen", max(3, args.steps // 10)),
-                            ("c10_mnist_convnet_grads", max(3, args.steps // 10)),
-                            ("c10_mnist_convnet_grad_norms", max(3, args.steps // 10)),
-                            ("c11_cond_two_branches", max(3, args.steps // 4))):
+        for name, steps in (("c2_mnist_mlp_grads", max(20, args.steps * 10)),
+                            ("c5_nested_weight_jacobian", max(20, args.steps * 10)),
+                            ("c3_tanh_jacobian", max(3, args.steps)),
+                            ("c2_mnist_mlp_grad_norms", max(20, args.steps * 10)),
+                            ("c4_gelu_bf16_grad_norms", max(3, args.steps * 2)),
+                            ("c6_tanh_hessian", max(3, args.steps)),
+                            ("c7_lstm_grads", max(3, args.steps * 5)),
+                            ("c7_lstm_grad_norms", max(3, args.steps * 5)),
+                            ("c8_lstm_jacobian", max(3, args.steps)),
+                            ("c9_lstm_varlen", max(3, args.steps)),
+                            ("c10_mnist_convnet_grads", max(3, args.steps)),
+                            ("c10_mnist_convnet_grad_norms", max(3, args.steps)),
+                            ("c11_cond_two_branches", max(3, args.steps * 2))):
             try:
                 fn = measure if name in wl.WORKLOADS else measure_lstm
-                others[name], _ = fn(name, steps, max(1, min(args.warmup, steps // 2)))
+                detail[name], _ = fn(name, steps, max(1, min(max(args.warmup, 10), steps // 2)))
             except Exception as e:
-                others[name] = {"error": str(e)}
+                log(f"[bench] {name}: FAILED: {e}")
+                detail[name] = {"error": str(e)}
+                failed.append(name)
             torch.cuda.empty_cache()
 
+    # The full records (per-kernel tables of every workload) go to a file and, one workload a line,
+    # to stderr; the last line of stdout is the compact headline record.
+    out_dir = os.path.join(ROOT, "gpurun_out")
+    try:
+        os.makedirs(out_dir, exist_ok=True)
+        with open(os.path.join(out_dir, "bench_detail.json"), "w") as f:
+            json.dump(detail, f, indent=1)
+    except OSError as e:
+        log(f"[bench] detail file not written: {e}")
+    for name, r in detail.items():
+        log("[bench-detail] " + json.dumps({name: r}))
+
+    def brief(r):
+        if "error" in r:
+            return {"error": r["error"][:80]}
+        b = {"ms_per_step": round(r["ms_per_step"], 5), "frac": round(r["roofline"]["frac"], 4),
+             "bound": r["roofline"]["bound"]}
+        for key in ("per_example_grads_per_sec", "jacobian_entries_per_sec", "jacobian_rows_per_sec"):
+            if key in r:
+                b[key] = float(f"{r[key]:.4g}")
+        return b
+
     w = wl.WORKLOADS[primary]
+    roof = rec["roofline"]
     line = {
         "metric": "per_example_grads_per_sec", "value": rec["per_example_grads_per_sec"],
         "unit": "grads/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": rec["ms_per_step"], "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16 in / f32 acc", "data": "synthetic",
         "config": {"workload": primary, "call": w.call, "dims": list(w.dims), "act": w.act,
-                   "batch": w.B, "output_GB_per_step": rec["output_GB"]},
-        "roofline": rec["roofline"], "cpu_baseline": cpu,
-        "ms_per_step_graph_replay": rec["ms_per_step_graph_replay"],
-        "ms_single_call": rec["ms_single_call"], "small_products": rec["small_products"],
-        "kernels": rec["kernels"], "other_workloads": others,
+                   "batch": w.B, "output_GB_per_step": round(rec["output_GB"], 3)},
+        "roofline": {"kernel": roof["kernel"], "bound": roof["bound"], "achieved": roof["achieved"],
+                     "peak": roof["peak"], "unit": roof["unit"], "frac": roof["frac"],
+                     "traffic": roof["traffic"],
+                     "traffic_source": None if roof["traffic"] is None else
+                     "stored rocprofv3 counters (profiles/outer_product_hbm_traffic.txt), not re-measured in this run",
+                     "bytes_per_launch": roof["bytes_per_launch"], "ms_per_launch": roof["ms_per_launch"],
+                     "scope": "kernel only (HIP events around the dispatch); the whole step is ms_per_step"},
+        "cpu_baseline": cpu,
+        "whole_step_hbm_frac": rec["output_GB"] / (rec["ms_per_step"] * 1e-3) / HBM_PEAK_GBS,
+        "other_configs": {k: brief(detail[k]) for k in ("c2_mnist_mlp_grads", "c3_tanh_jacobian",
+                                                         "c5_nested_weight_jacobian") if k in detail},
+        "detail": "gpurun_out/bench_detail.json and the [bench-detail] lines on stderr",
     }
-    print(json.dumps(line), flush=True)
+    text = json.dumps(line)
+    assert len(text) < 2048, len(text)
+    print(text, flush=True)
+    if failed:
+        sys.exit(f"bench.py: workloads failed: {', '.join(failed)}")
 
 
 if __name__ == "__main__":

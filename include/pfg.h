@@ -353,7 +353,9 @@ const char *pfg_last_error(void);
  * time in milliseconds since the last reset; it returns PFG_ERR_SHAPE if no launch of that
  * family was recorded.  pfg_timing_names writes the recorded family names, separated by '\n',
  * into buf (truncated to cap bytes including the final NUL).  Do not enable timing while the
- * stream is being captured into a graph. */
+ * stream is being captured into a graph.  The switch and the totals are process-wide: the facility
+ * is meant for one measuring thread; calls from several threads are safe (the switch is atomic,
+ * the records are locked) but their launches are summed into the same families. */
 int pfg_timing_enable(int on);
 int pfg_timing_reset(void);
 int pfg_timing_query(const char *name, int64_t *launches, double *total_ms);

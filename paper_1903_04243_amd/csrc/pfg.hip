@@ -1,6 +1,7 @@
 // C ABI of libpfg: argument checks, workspace layout and the order in which the kernels of the
 // three operations are enqueued.  No arithmetic of the method happens on the host.
 #include <algorithm>
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -40,7 +41,7 @@ using namespace pfg;
 // ------------------------------------------------------------------------------------------
 struct TimedLaunch { const char *name; hipEvent_t start, stop; };
 std::mutex g_timing_mu;
-bool g_timing_on = false;
+std::atomic<bool> g_timing_on{false};
 std::vector<TimedLaunch> g_pending;
 std::map<std::string, std::pair<int64_t, double>> g_totals;
 void drain_pending() {
@@ -63,7 +64,7 @@ void drain_pending() {
 
 namespace pfg {
 bool timing_next_events(hipEvent_t *start, hipEvent_t *stop) {
-  if (!g_timing_on) return false;
+  if (!g_timing_on.load(std::memory_order_relaxed)) return false;
   if (hipEventCreate(start) != hipSuccess) return false;
   if (hipEventCreate(stop) != hipSuccess) { (void)hipEventDestroy(*start); return false; }
   std::lock_guard<std::mutex> lk(g_timing_mu);
@@ -396,7 +397,7 @@ int pfg_version(void) { return 104; }
 const char *pfg_last_error(void) { return g_err; }
 
 int pfg_timing_enable(int on) {
-  g_timing_on = (on != 0);
+  g_timing_on.store(on != 0, std::memory_order_relaxed);
   return PFG_OK;
 }
 
