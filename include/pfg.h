@@ -130,6 +130,24 @@ int pfg_jacobian_weights(const pfg_mlp *net, const void *X, int64_t B, int head,
                          float *const *JW_out, float *const *Jb_out, void *workspace,
                          size_t workspace_bytes, void *hip_stream);
 
+/* pfg_per_example_grads for callers that cannot allocate device memory or have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, kernels and results as pfg_per_example_grads, without the workspace: the
+ * intermediate tensors live in a buffer of PFG_STATIC_SCRATCH_BYTES that is part of the library's
+ * device image (one copy per GPU, resident from the time the library is loaded on that GPU until
+ * the process ends).  The call allocates and frees no device memory.
+ *   - A network and batch that need more (pfg_workspace_bytes reports the figure) are rejected
+ *     with PFG_ERR_WORKSPACE before anything is enqueued.
+ *   - All calls on one GPU share that GPU's buffer: calls that overlap on one GPU (two streams, two
+ *     threads) race; calls on one stream are ordered by the stream.  Nothing in the buffer has to
+ *     be zero at entry and nothing is kept between calls.
+ *   - The first call on a GPU looks up the buffer's address (no allocation, but a runtime query):
+ *     make one call outside graph capture before capturing. */
+#define PFG_STATIC_SCRATCH_BYTES (64u << 20)
+int pfg_per_example_grads_static(const pfg_mlp *net, const void *X, const int32_t *labels, int64_t B,
+                                 float *const *dW_out, float *const *db_out, float *loss_out,
+                                 void *hip_stream);
+
 /* Norms of the per-example gradients of Section 5.3 without writing the gradients out (the
  * statistic that per-example clipping and importance weighting need).  The gradient of layer l
  * for example b is the product of a column a_{l-1}[b, :] and a row delta_l[b, :] -- the matmul

@@ -24,7 +24,8 @@ HEAD = {"logits": 0, "softmax": 1}
 OP = {"per_example_grads": 0, "jacobian_input": 1, "jacobian_weights": 2, "grad_norms": 3,
       "hessian_input": 4}
 
-EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_jacobian_input",
+EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_per_example_grads_static",
+           "pfg_jacobian_input",
            "pfg_jacobian_weights", "pfg_per_example_grad_norms", "pfg_hessian_input",
            "pfg_lstm_workspace_bytes", "pfg_lstm_per_example_grads", "pfg_lstm_jacobian_input",
            "pfg_lstm_per_example_grad_norms",
@@ -113,6 +114,8 @@ def load_library() -> ctypes.CDLL:
         lib.pfg_workspace_bytes.argtypes = [netp, i32, i64, i64, ctypes.POINTER(ctypes.c_size_t)]
         lib.pfg_per_example_grads.argtypes = [netp, vp, vp, i64, ctypes.POINTER(vp),
                                               ctypes.POINTER(vp), vp, vp, ctypes.c_size_t, vp]
+        lib.pfg_per_example_grads_static.argtypes = [netp, vp, vp, i64, ctypes.POINTER(vp),
+                                                     ctypes.POINTER(vp), vp, vp]
         lib.pfg_jacobian_input.argtypes = [netp, vp, i64, vp, i64, i64, vp, vp, ctypes.c_size_t, vp]
         lib.pfg_jacobian_weights.argtypes = [netp, vp, i64, i32, vp, i64, i64, ctypes.POINTER(vp),
                                              ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
@@ -258,6 +261,24 @@ def pfg_per_example_grads(net: Mlp, X, labels, want_dW: Optional[Sequence[bool]]
         _ptrs(db) if db is not None else None, None if loss is None else loss.data_ptr(),
         workspace.data_ptr(), ws_bytes, _stream_ptr()))
     return dW, db, loss
+
+
+PFG_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def pfg_per_example_grads_static(net: Mlp, X, labels, out_dW, out_db=None, out_loss=None):
+    """pfg_per_example_grads on the library's built-in scratch buffer: every output is the
+    caller's, nothing is allocated here or in the library."""
+    import torch
+    _check_x(net, X)
+    B = X.shape[0]
+    if labels.dtype != torch.int32 or tuple(labels.shape) != (B,) or not labels.is_contiguous():
+        raise ValueError("labels must be a contiguous int32 [B] tensor")
+    _check(load_library().pfg_per_example_grads_static(
+        ctypes.byref(net.c), X.data_ptr(), labels.data_ptr(), B, _ptrs(out_dW),
+        _ptrs(out_db) if out_db is not None else None,
+        None if out_loss is None else out_loss.data_ptr(), _stream_ptr()))
+    return out_dW, out_db, out_loss
 
 
 def _seed_args(net: Mlp, B: int, seeds, S: Optional[int]):

@@ -390,6 +390,85 @@ int weight_sweep(const pfg_mlp *net, const void *X, int64_t B, int64_t S, float 
 
 }  // namespace
 
+// Device memory of pfg_per_example_grads_static: what the other entry points take as their
+// workspace argument (activations, masks, cotangents, partial products).  One copy per GPU, held
+// from the moment the library is loaded on it until the process ends.  The name below is only a
+// host-side handle; the address on the current GPU comes from hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[PFG_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on the current device, looked up once per device.
+int static_scratch(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(PFG_ERR_DEVICE, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(PFG_ERR_DEVICE, "device index %d is outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      return fail(PFG_ERR_DEVICE, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return PFG_OK;
+}
+
+int per_example_grads_impl(const pfg_mlp *net, const void *X, const int32_t *labels, int64_t B,
+                           float *const *dW_out, float *const *db_out, float *loss_out,
+                           void *workspace, size_t workspace_bytes, bool use_static,
+                           void *hip_stream) {
+  g_err[0] = 0;
+  int rc = check_net(net);
+  if (rc) return rc;
+  if ((rc = check_weights(net))) return rc;
+  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
+  if ((rc = check_rows(B, 1))) return rc;
+  if ((rc = check_elems(net, B))) return rc;
+  const Plan p = make_plan(net, PFG_OP_PER_EXAMPLE_GRADS, B, 1);
+  if (use_static) {
+    if (p.total > (size_t)PFG_STATIC_SCRATCH_BYTES)
+      return fail(PFG_ERR_WORKSPACE,
+                  "this network and batch need %zu bytes of scratch memory, the built-in buffer holds %zu: "
+                  "use pfg_per_example_grads with a workspace", p.total, (size_t)PFG_STATIC_SCRATCH_BYTES);
+    if ((rc = static_scratch(&workspace))) return rc;
+    workspace_bytes = PFG_STATIC_SCRATCH_BYTES;
+  }
+  if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int L = net->num_layers;
+  const int32_t *d = net->dims;
+
+  // delta_l lives in the caller's db_out[l-1] when given (db_l = delta_l), else in the workspace
+  std::vector<float *> G(L + 1, nullptr);
+  for (int l = 1; l <= L; ++l)
+    G[l] = (db_out && db_out[l - 1]) ? db_out[l - 1] : at(workspace, p.G[l]);
+
+  bool top_step_done = false;
+  if (d[L] <= 32) {
+    // a whole row of logits fits one output tile: the loss head, and the cotangent step through
+    // the last layer if a lower layer's gradient is wanted, ride on the last forward layer
+    top_step_done = (L >= 2) && (lowest_requested(net, dW_out, db_out) < L);
+    const HeadFusion hf{labels, G[L], loss_out, top_step_done ? G[L - 1] : nullptr};
+    if ((rc = forward(net, X, B, L, workspace, p, true, stream, &hf))) return rc;
+  } else {
+    if ((rc = forward(net, X, B, L, workspace, p, true, stream))) return rc;
+    PFG_LAUNCH("head", launch_head_softmax_ce(at(workspace, p.logits), labels, B, d[L], G[L],
+                                              loss_out, stream));
+  }
+  return weight_sweep(net, X, B, 1, dW_out, db_out, G, workspace, p, stream, top_step_done);
+}
+
+}  // namespace
+
 extern "C" {
 
 int pfg_version(void) { return 104; }
@@ -453,39 +532,15 @@ int pfg_workspace_bytes(const pfg_mlp *net, int op, int64_t B, int64_t S, size_t
 int pfg_per_example_grads(const pfg_mlp *net, const void *X, const int32_t *labels, int64_t B,
                           float *const *dW_out, float *const *db_out, float *loss_out,
                           void *workspace, size_t workspace_bytes, void *hip_stream) {
-  g_err[0] = 0;
-  int rc = check_net(net);
-  if (rc) return rc;
-  if ((rc = check_weights(net))) return rc;
-  if (!X) return fail(PFG_ERR_NULL, "X is NULL");
-  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
-  if ((rc = check_rows(B, 1))) return rc;
-  if ((rc = check_elems(net, B))) return rc;
-  const Plan p = make_plan(net, PFG_OP_PER_EXAMPLE_GRADS, B, 1);
-  if ((rc = check_workspace(p, workspace, workspace_bytes))) return rc;
+  return per_example_grads_impl(net, X, labels, B, dW_out, db_out, loss_out, workspace,
+                                workspace_bytes, false, hip_stream);
+}
 
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const int L = net->num_layers;
-  const int32_t *d = net->dims;
-
-  // delta_l lives in the caller's db_out[l-1] when given (db_l = delta_l), else in the workspace
-  std::vector<float *> G(L + 1, nullptr);
-  for (int l = 1; l <= L; ++l)
-    G[l] = (db_out && db_out[l - 1]) ? db_out[l - 1] : at(workspace, p.G[l]);
-
-  bool top_step_done = false;
-  if (d[L] <= 32) {
-    // a whole row of logits fits one output tile: the loss head, and the cotangent step through
-    // the last layer if a lower layer's gradient is wanted, ride on the last forward layer
-    top_step_done = (L >= 2) && (lowest_requested(net, dW_out, db_out) < L);
-    const HeadFusion hf{labels, G[L], loss_out, top_step_done ? G[L - 1] : nullptr};
-    if ((rc = forward(net, X, B, L, workspace, p, true, stream, &hf))) return rc;
-  } else {
-    if ((rc = forward(net, X, B, L, workspace, p, true, stream))) return rc;
-    PFG_LAUNCH("head", launch_head_softmax_ce(at(workspace, p.logits), labels, B, d[L], G[L],
-                                              loss_out, stream));
-  }
-  return weight_sweep(net, X, B, 1, dW_out, db_out, G, workspace, p, stream, top_step_done);
+int pfg_per_example_grads_static(const pfg_mlp *net, const void *X, const int32_t *labels, int64_t B,
+                                 float *const *dW_out, float *const *db_out, float *loss_out,
+                                 void *hip_stream) {
+  return per_example_grads_impl(net, X, labels, B, dW_out, db_out, loss_out, nullptr, 0, true,
+                                hip_stream);
 }
 
 int pfg_per_example_grad_norms(const pfg_mlp *net, const void *X, const int32_t *labels, int64_t B,

@@ -438,3 +438,19 @@ def test_bf16_rounding_of_inputs():
     bits, back = bf16_round(y)
     t = torch.from_numpy(y).to(torch.bfloat16)
     np.testing.assert_array_equal(back, t.to(torch.float32).numpy())
+
+
+def test_static_scratch_entry_point_rejects_before_any_device_call(lib):
+    # argument checks and the size limit are host logic: nothing below reaches the GPU runtime
+    lib.pfg_per_example_grads_static.restype = ctypes.c_int
+    big = make_net([64, 8192, 8192, 10])
+    rc, need = ws_bytes(lib, big, 0, 1024, 1)
+    assert rc == 0 and need > pfg.PFG_STATIC_SCRATCH_BYTES
+    rc = lib.pfg_per_example_grads_static(ctypes.byref(big), FAKE, FAKE, 1024, None, None, None, None)
+    assert rc == pfg.PFG_ERR_WORKSPACE
+    assert b"built-in buffer" in lib.pfg_last_error()
+    assert lib.pfg_per_example_grads_static(ctypes.byref(big), None, FAKE, 8, None, None, None, None) == pfg.PFG_ERR_NULL
+    assert lib.pfg_per_example_grads_static(ctypes.byref(big), FAKE, FAKE, 0, None, None, None, None) == pfg.PFG_ERR_SHAPE
+    header = open(os.path.join(ROOT, "include", "pfg.h")).read()
+    m = re.search(r"#define PFG_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", header)
+    assert m and int(m.group(1)) << int(m.group(2)) == pfg.PFG_STATIC_SCRATCH_BYTES
