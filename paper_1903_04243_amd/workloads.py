@@ -338,3 +338,79 @@ def make_cond_inputs(w: CondWorkload, n: Optional[int] = None, pre=None, then_di
     wv = (rng.standard_normal(pre[-1]) / np.sqrt(pre[-1])).astype(np.float32)
     X = rng.standard_normal((n, pre[0])).astype(np.float32)
     return CondInputs(w, nets[0], nets[1], nets[2], wv, float(w.c0 if c0 is None else c0), X)
+
+
+# --------------------------------------------------------------------------------------------
+# Integer-valued inputs: every hidden pre-activation is a small integer, exact in bfloat16,
+# float32 and float64 alike, so that ReLU kinks (z == 0), pooling ties and condition scores of
+# exactly 0 occur often and are decided on identical values by every implementation.
+# --------------------------------------------------------------------------------------------
+def _sparse_ints(rng: np.random.Generator, shape, density: float, lo: int, hi: int) -> np.ndarray:
+    vals = rng.integers(lo, hi + 1, size=shape)
+    keep = rng.uniform(size=shape) < density
+    return (vals * keep).astype(np.float32)
+
+
+def draw_integer_weights(rng: np.random.Generator, dims, density: float, last_scale: float,
+                         bias: bool = True):
+    """Hidden layers: entries in {-1, 0, 1} (non-zero with probability `density`), integer biases in
+    {-1, 0, 1}; last layer: the same integers times `last_scale` (a power of two keeps them exact)."""
+    Ws, bs = [], []
+    L = len(dims) - 1
+    for l in range(1, L + 1):
+        scale = last_scale if l == L else 1.0
+        Ws.append(_sparse_ints(rng, (dims[l - 1], dims[l]), density, -1, 1) * np.float32(scale))
+        bs.append((rng.integers(-1, 2, size=(dims[l],)) * scale * (1.0 if bias else 0.0)).astype(np.float32))
+    return Ws, bs
+
+
+def make_integer_inputs(dims, B: int, seed: int, density: float = 0.25, last_scale: float = 1.0 / 16,
+                        x_range: int = 2, dtype: str = "f32") -> Inputs:
+    """A dense network with integer-valued weights and inputs (X uniform in -x_range..x_range)."""
+    dims = tuple(dims)
+    rng = np.random.Generator(np.random.Philox(seed))
+    Ws, bs = draw_integer_weights(rng, dims, density, last_scale)
+    X = rng.integers(-x_range, x_range + 1, size=(B, dims[0])).astype(np.float32)
+    labels = rng.integers(0, dims[-1], size=(B,)).astype(np.int32)
+    w = Workload("integer", 0, "per_example_grads", dims, "relu", dtype, B, "integer", "integer")
+    inp = Inputs(w, Ws, bs, X, labels)
+    if dtype == "bf16":
+        Wr = [bf16_round(W) for W in Ws]
+        br = [bf16_round(b) for b in bs]
+        Xr = bf16_round(X)
+        for (bits, back), orig in zip(Wr + br + [Xr], Ws + bs + [X]):
+            assert np.array_equal(back, orig), "integer inputs must be exact in bfloat16"
+        inp.Ws_bits, inp.bs_bits, inp.X_bits = [r[0] for r in Wr], [r[0] for r in br], Xr[0]
+    return inp
+
+
+def make_integer_conv_inputs(height: int, width: int, channels: int, blocks, dense, B: int, seed: int,
+                             density: float = 0.3, last_scale: float = 1.0 / 16) -> ConvInputs:
+    """Integer images in 0..3, filters in {-1, 0, 1}, integer biases: equal entries inside a pooling
+    window and pre-activations of exactly 0 are frequent."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    Wc, bc = [], []
+    hh, ww, cc = height, width, channels
+    for k, f in blocks:
+        Wc.append(_sparse_ints(rng, (k, k, cc, f), density, -1, 1))
+        bc.append(rng.integers(-1, 2, size=(f,)).astype(np.float32))
+        hh, ww, cc = hh // 2, ww // 2, f
+    dims = (hh * ww * cc,) + tuple(dense)
+    Ws, bs = draw_integer_weights(rng, dims, density / 4, last_scale)
+    X = rng.integers(0, 4, size=(B, height, width, channels)).astype(np.float32)
+    labels = rng.integers(0, dims[-1], size=(B,)).astype(np.int32)
+    w = ConvWorkload("integer", 0, height, width, channels, tuple(blocks), tuple(dense), B)
+    return ConvInputs(w, Wc, bc, Ws, bs, X, labels)
+
+
+def make_integer_cond_inputs(pre, then_dims, else_dims, n: int, seed: int, density: float = 0.25,
+                             c0: float = 0.0) -> CondInputs:
+    """Integer-valued shared part, condition vector and branches: many rows have a score of exactly 0."""
+    pre, then_dims, else_dims = tuple(pre), tuple(then_dims), tuple(else_dims)
+    rng = np.random.Generator(np.random.Philox(seed))
+    nets = [draw_integer_weights(rng, dims, density, 1.0)
+            for dims in (pre, (pre[-1],) + then_dims, (pre[-1],) + else_dims)]
+    wv = _sparse_ints(rng, (pre[-1],), 0.5, -1, 1)
+    X = rng.integers(-2, 3, size=(n, pre[0])).astype(np.float32)
+    w = CondWorkload("integer", 0, pre, then_dims, else_dims, "relu", n, c0)
+    return CondInputs(w, nets[0], nets[1], nets[2], wv, float(c0), X)
