@@ -39,6 +39,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="do not also time a HIP-graph replay")
     ap.add_argument("--copy-reference", action="store_true",
                     help="run a plain elementwise copy of known size (scale for HBM counters)")
+    ap.add_argument("--fill-reference", action="store_true",
+                    help="measure plain sequential fills of several sizes (the practical HBM write ceiling)")
     ap.add_argument("--workload", default=None,
                     help="measure only this workload and print its record (for profiling runs)")
     ap.add_argument("--batch", type=int, default=None,
@@ -165,10 +167,20 @@ def main():
         pfg.pfg_timing_reset()
         return out
 
+    def is_wide(M, d_in, d_out):
+        return (d_out % 4 == 0 and d_out >= 1024 and M <= 65535 and d_in <= 65535 and
+                4 * M * d_in * d_out >= (128 << 20))
+
     def algorithmic(w):
         """Algorithmic work of the dominant kernels of one step."""
         d, B, S = w.dims, w.B, w.S
         if w.call == "per_example_grads":
+            # large outputs with wide rows leave in a kernel of their own (the library's rule, restated;
+            # the roofline below fails loudly if the launches disagree with it)
+            wide = [l for l in range(1, len(d)) if is_wide(B, d[l - 1], d[l])]
+            if wide:
+                return {"outer_product_wide": {"bytes": 4 * B * sum(d[l - 1] * d[l] for l in wide),
+                                               "launches": len(wide)}}
             return {"outer_product": {"bytes": 4 * B * sum(d[l - 1] * d[l] for l in range(1, len(d)))}}
         if w.call == "grad_norms":
             # no large output: the forward products dominate; each reads its weights once, reads
@@ -211,12 +223,15 @@ def main():
         fam = next(iter(alg))
         if "bytes" in alg[fam]:
             k = kt[fam]
+            if "launches" in alg[fam] and round(k["launches_per_step"]) != alg[fam]["launches"]:
+                raise RuntimeError(f"{alg[fam]['launches']} launches of {fam} expected per step, "
+                                   f"{k['launches_per_step']} recorded")
             per_launch_bytes = alg[fam]["bytes"] / k["launches_per_step"]
             per_launch_ms = k["ms_per_step"] / k["launches_per_step"]
             gbs = per_launch_bytes / (per_launch_ms * 1e-3) / 1e9
             return {"kernel": fam, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                    "traffic": measured_traffic(w.name) if (fam == "outer_product" and args.batch is None) else None,
+                    "traffic": measured_traffic(w.name) if (fam.startswith("outer_product") and args.batch is None) else None,
                     "bytes_per_launch": per_launch_bytes, "ms_per_launch": per_launch_ms,
                     "launches_per_step": k["launches_per_step"]}
         flops = sum(v["flops"] for v in alg.values())
@@ -371,9 +386,13 @@ def main():
             values = sum(t.numel() for t in out)
         else:
             values = sum(t.numel() for group in out[:4] for t in group) + B
-            # the dense weight gradients are the large output (4 bytes per value, written once)
-            fam = "outer_product"
-            nbytes = 4 * B * sum(dn.dims[l] * dn.dims[l + 1] for l in range(dn.L))
+            # the dense weight gradients are the large output (4 bytes per value, written once); wide
+            # layers leave in a kernel of their own, which is then the one to price
+            wide = [l for l in range(dn.L) if is_wide(B, dn.dims[l], dn.dims[l + 1])]
+            fam = "outer_product_wide" if wide else "outer_product"
+            nbytes = 4 * B * sum(dn.dims[l] * dn.dims[l + 1] for l in (wide or range(dn.L)))
+            if wide and round(kt[fam]["launches_per_step"]) != len(wide):
+                raise RuntimeError(f"{len(wide)} launches of {fam} expected, {kt[fam]['launches_per_step']} recorded")
             per_ms = kt[fam]["ms_per_step"] / kt[fam]["launches_per_step"]
             gbs = nbytes / kt[fam]["ms_per_step"] / 1e6
             roof = {"kernel": fam, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -577,6 +596,38 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_reference": "torch.add(src, 1.0, out=dst)", "launches": args.steps,
                           "read_bytes_per_launch": 4 * n, "write_bytes_per_launch": 4 * n}))
+        return
+
+    if args.fill_reference:
+        # what the device's memory absorbs from the plainest write stream, at the output sizes of the
+        # measured workloads: the library's sequential fill (16-byte non-temporal stores, 8 KiB per
+        # workgroup), torch's fill_ and torch's zero_ (a memset)
+        rows = []
+        for nbytes in (85 << 20, 268435456, 342360064, 1 << 30, 1681915904, 8 << 30, 34401681408):
+            buf = torch.empty(nbytes // 4, dtype=torch.float32, device=dev)
+            reps = max(3, min(args.steps, int(2e11 // nbytes)))
+            rec = {"bytes": nbytes, "launches": reps}
+            for name, fn in (("pfg_fill_reference", lambda: pfg.pfg_fill_reference(buf, 1.0)),
+                             ("torch_fill_", lambda: buf.fill_(1.0)), ("torch_zero_", lambda: buf.zero_())):
+                for _ in range(2):
+                    fn()
+                start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                best, total = float("inf"), 0.0
+                for _ in range(reps):
+                    start.record()
+                    fn()
+                    stop.record()
+                    stop.synchronize()
+                    ms = start.elapsed_time(stop)
+                    best, total = min(best, ms), total + ms
+                rec[name] = {"avg_GBps": nbytes * reps / total / 1e6, "best_GBps": nbytes / best / 1e6,
+                             "avg_us": total / reps * 1e3}
+            log(f"[bench] fill {nbytes / 1e6:.0f} MB: " + ", ".join(
+                f"{k} {v['avg_GBps']:.0f} GB/s" for k, v in rec.items() if isinstance(v, dict)))
+            rows.append(rec)
+            del buf
+            torch.cuda.empty_cache()
+        print(json.dumps({"fill_reference": rows, "hbm_peak_GBps": HBM_PEAK_GBS}), flush=True)
         return
 
     if args.workload:

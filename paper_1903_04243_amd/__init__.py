@@ -34,7 +34,7 @@ EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_per_example_grad
            "pfg_convnet_grad_norms_workspace_bytes", "pfg_convnet_per_example_grad_norms",
            "pfg_cond_workspace_bytes", "pfg_cond_forward",
            "pfg_last_error", "pfg_timing_enable", "pfg_timing_reset",
-           "pfg_timing_query", "pfg_timing_names", "pfg_version"]
+           "pfg_timing_query", "pfg_timing_names", "pfg_fill_reference", "pfg_version"]
 
 
 class PfgError(RuntimeError):
@@ -141,6 +141,7 @@ def load_library() -> ctypes.CDLL:
         condp = ctypes.POINTER(pfg_cond)
         lib.pfg_cond_workspace_bytes.argtypes = [condp, i64, ctypes.POINTER(ctypes.c_size_t)]
         lib.pfg_cond_forward.argtypes = [condp, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.pfg_fill_reference.argtypes = [vp, i64, ctypes.c_float, vp]
         lib.pfg_last_error.restype = ctypes.c_char_p
         lib.pfg_timing_enable.argtypes = [i32]
         lib.pfg_timing_query.argtypes = [ctypes.c_char_p, ctypes.POINTER(i64),
@@ -700,6 +701,14 @@ def pfg_cond_forward(net: Cond, X, invariant_cond: int = PFG_COND_PER_ITERATION,
         None if cond is None else cond.data_ptr(), None if counts is None else counts.data_ptr(),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr()))
     return R, cond, counts
+
+
+def pfg_fill_reference(out, value: float = 0.0) -> None:
+    """Fill a contiguous float32 GPU tensor with the library's plain sequential store stream."""
+    import torch
+    if out.dtype != torch.float32 or not out.is_contiguous() or not out.is_cuda:
+        raise ValueError("out must be a contiguous float32 GPU tensor")
+    _check(load_library().pfg_fill_reference(out.data_ptr(), out.numel(), float(value), _stream_ptr()))
 
 
 def pfg_timing_enable(on: bool) -> None:

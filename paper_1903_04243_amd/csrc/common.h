@@ -166,6 +166,9 @@ struct OuterArgs {
 // Enqueues the n outer products in as few launches as possible (normally one).
 hipError_t launch_outer(const OuterArgs *jobs, int n, hipStream_t stream);
 
+// out[0 .. n) = value as a plain sequential stream of 16-byte non-temporal stores (measurement aid)
+hipError_t launch_fill_reference(float *out, int64_t n, float value, hipStream_t stream);
+
 // delta[b, :] = softmax(y[b, :]) - onehot(labels[b]);  loss[b] = -log softmax(y[b])[labels[b]]
 hipError_t launch_head_softmax_ce(const float *y, const int32_t *labels, int64_t B, int32_t n,
                                   float *delta, float *loss, hipStream_t stream);

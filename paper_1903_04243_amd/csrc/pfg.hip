@@ -511,6 +511,15 @@ int pfg_timing_names(char *buf, size_t cap) {
   return PFG_OK;
 }
 
+int pfg_fill_reference(float *out, int64_t n, float value, void *hip_stream) {
+  g_err[0] = 0;
+  if (!out) return fail(PFG_ERR_NULL, "out is NULL");
+  if (n < 0 || (n & 3)) return fail(PFG_ERR_SHAPE, "n = %lld must be a non-negative multiple of 4", (long long)n);
+  if (reinterpret_cast<uintptr_t>(out) & 15) return fail(PFG_ERR_SHAPE, "out is not 16-byte aligned");
+  PFG_LAUNCH("fill_reference", launch_fill_reference(out, n, value, static_cast<hipStream_t>(hip_stream)));
+  return PFG_OK;
+}
+
 int pfg_workspace_bytes(const pfg_mlp *net, int op, int64_t B, int64_t S, size_t *bytes) {
   g_err[0] = 0;
   int rc = check_net(net);

@@ -9,7 +9,10 @@
 // 16-byte non-temporal store per row; consecutive lanes cover consecutive 16-byte pieces of a row
 // and a workgroup walks a contiguous run of rows of one iteration m.  The outer products of all
 // layers of a call share one launch.
+#include <vector>
+
 #include "common.h"
+#include "host.h"
 
 namespace pfg {
 
@@ -130,6 +133,52 @@ __global__ __launch_bounds__(THREADS) void outer_product_kernel(const OuterBatch
     outer_flat<THREADS>(jb, x - jb.x_begin, m);
 }
 
+// Wide rows of a large output (d_out >= 1024, at least kWideBytes in all): a kernel of its own with
+// next to no prologue.  A workgroup is one 4 KiB slab of one row -- grid = (slabs, rows, iterations),
+// so no index is ever divided -- and every lane issues a single 16-byte store.  Measured on plain
+// fills and on this product (17 GB, rows of 16 KiB): 4 KiB per workgroup streams at 6.6 to 7.0 TB/s,
+// 8 KiB at 6.1 to 6.4, 16 KiB at 5.8 to 6.2; the general kernel above cannot go below 8 KiB because
+// its prologue (job table, chunk arithmetic) then costs more than its stores.
+constexpr int64_t kWideBytes = (int64_t)128 << 20;
+
+template <bool A_BF16, bool SEEDS>
+__global__ __launch_bounds__(kThreads) void outer_wide_kernel(const void *__restrict__ a, int64_t lda,
+                                                              const float *__restrict__ g, int64_t ldg,
+                                                              float *__restrict__ out, int d_in, int V,
+                                                              int S) {
+  const int vc = blockIdx.x * kThreads + threadIdx.x;
+  const uint32_t i = blockIdx.y;
+  const int64_t m = blockIdx.z;
+  if (vc >= V) return;
+  const f32x4 gv = *reinterpret_cast<const f32x4 *>(g + m * ldg + 4 * vc);
+  const int64_t arow = (SEEDS ? (int64_t)((uint32_t)m / (uint32_t)S) : m) * lda + i;
+  const float av = A_BF16 ? (float)static_cast<const __bf16 *>(a)[arow] : static_cast<const float *>(a)[arow];
+  f32x4 *o = reinterpret_cast<f32x4 *>(out) + (m * d_in + i) * (int64_t)V + vc;
+  __builtin_nontemporal_store(gv * av, o);
+}
+
+bool wide_applies(const OuterArgs &o) {
+  if (o.d_out % 4 || o.d_out < 4 * kThreads || o.M > 65535 || o.d_in > 65535) return false;
+  if ((reinterpret_cast<uintptr_t>(o.out) | reinterpret_cast<uintptr_t>(o.g)) & 15) return false;
+  if (o.ldg & 3) return false;
+  return o.M * (int64_t)o.d_in * o.d_out * 4 >= kWideBytes;
+}
+
+hipError_t launch_wide(const OuterArgs &o, hipStream_t stream) {
+  const int V = o.d_out / 4;
+  const dim3 grid((unsigned)((V + kThreads - 1) / kThreads), (unsigned)o.d_in, (unsigned)o.M);
+#define PFG_WIDE(BF, SD)                                                                              \
+  PFG_KERNEL((outer_wide_kernel<BF, SD>), grid, dim3(kThreads), 0, stream, o.a, o.lda, o.g, o.ldg, o.out, \
+             o.d_in, V, o.S)
+  if (o.a_bf16) {
+    if (o.S == 1) PFG_WIDE(true, false); else PFG_WIDE(true, true);
+  } else {
+    if (o.S == 1) PFG_WIDE(false, false); else PFG_WIDE(false, true);
+  }
+#undef PFG_WIDE
+  return hipGetLastError();
+}
+
 // Cuts one iteration of an outer product into workgroups; returns how many.
 int64_t plan_job(const OuterArgs &o, OuterJob &jb, int64_t target) {
   constexpr int threads = kThreads;
@@ -191,7 +240,30 @@ hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, int64_t target,
   return hipSuccess;
 }
 
+// The plainest write stream there is, for measuring what HBM absorbs: out[0 .. n) = value with one
+// 16-byte non-temporal store per lane and store, workgroups of 8 KiB in address order (the
+// granularity the outer-product kernel uses).  n is a multiple of 4, out 16-byte aligned.
+__global__ __launch_bounds__(kThreads) void fill_reference_kernel(float *out, int64_t nvec, float value) {
+  const int64_t base = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * (2 * kThreads) + threadIdx.x;
+  const f32x4 v = {value, value, value, value};
+  f32x4 *o = reinterpret_cast<f32x4 *>(out);
+  if (base < nvec) __builtin_nontemporal_store(v, o + base);
+  if (base + kThreads < nvec) __builtin_nontemporal_store(v, o + base + kThreads);
+}
+
 }  // namespace
+
+hipError_t launch_fill_reference(float *out, int64_t n, float value, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  if ((n & 3) || (reinterpret_cast<uintptr_t>(out) & 15)) return hipErrorInvalidValue;
+  const int64_t nvec = n / 4;
+  const int64_t groups = (nvec + 2 * kThreads - 1) / (2 * kThreads);
+  const unsigned gx = (unsigned)(groups < 65535 ? groups : 65535);
+  const int64_t gy = (groups + gx - 1) / gx;
+  if (gy > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+  PFG_KERNEL(fill_reference_kernel, dim3(gx, (unsigned)gy), dim3(kThreads), 0, stream, out, nvec, value);
+  return hipGetLastError();
+}
 
 hipError_t launch_outer(const OuterArgs *jobs, int n, hipStream_t stream) {
   // Workgroup size and store kind, from sweeps of this kernel on MI355X (a purely sequential fill
@@ -202,6 +274,21 @@ hipError_t launch_outer(const OuterArgs *jobs, int n, hipStream_t stream) {
   // its writer is not).  16 KiB per workgroup: 5 to 15 % slower; 4 KiB (one store per lane): the
   // index prologue dominates.
   const int64_t target = 8192;
+  // large outputs with wide rows leave in launches of their own (see outer_wide_kernel)
+  std::vector<OuterArgs> rest;
+  rest.reserve(n);
+  for (int i = 0; i < n; ++i) {
+    if (jobs[i].M > 0 && jobs[i].d_in > 0 && wide_applies(jobs[i])) {
+      set_timing_family("outer_product_wide");
+      hipError_t e = launch_wide(jobs[i], stream);
+      if (e != hipSuccess) return e;
+    } else {
+      rest.push_back(jobs[i]);
+    }
+  }
+  set_timing_family("outer_product");
+  jobs = rest.data();
+  n = (int)rest.size();
   for (int i = 0; i < n; ++i) {
     if (jobs[i].M <= 0) continue;
     if ((int64_t)jobs[i].d_in * jobs[i].d_out > 0x7fffffffLL) return hipErrorInvalidConfiguration;
