@@ -262,7 +262,10 @@ int pfg_lstm_jacobian_input(const pfg_lstm *net, const void *X, int64_t B, const
  *   h_out           DEVICE [B, state_size] or NULL: hidden state of each sequence after its last token
  *   y_out           DEVICE [B, output_size] or NULL: h_out W_out + b_out
  * The call copies three small index arrays to the workspace with an asynchronous copy on the
- * stream; do not capture it into a graph. */
+ * stream (from a host buffer the library keeps per calling thread and guards with an event, so
+ * calls may follow each other without synchronising); do not capture it into a graph.  For lengths
+ * that live on the device, or a loop that also stops on a condition of the state, see
+ * pfg_lstm_while_forward. */
 int pfg_lstm_varlen_workspace_bytes(const pfg_lstm *net, int64_t B, int64_t total_tokens, size_t *bytes);
 int pfg_lstm_varlen_forward(const pfg_lstm *net, const void *X, const int32_t *lengths, int64_t B,
                             int64_t total_tokens, float *h_out, float *y_out, void *workspace,

@@ -182,3 +182,26 @@ def varlen_forward(net: Lstm, X, lengths):
                                  offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
                                  ctypes.c_int64(B), _dp(h), _dp(y))
     return h, y
+
+
+def while_forward(net: Lstm, X, lengths, max_steps: int, halt_w=None, halt_c: float = 0.0):
+    """Every sequence iterated while it has tokens left, the cap max_steps is not reached and the
+    halting score halt_c + <h, halt_w> of its current state is not positive (see lstm_oracle.c).
+    lengths may hold zeros.  Returns (h [B, H], y [B, dy], steps [B] int64)."""
+    lengths = np.asarray(lengths, dtype=np.int64)
+    assert lengths.ndim == 1 and (lengths >= 0).all()
+    B = lengths.size
+    offsets = np.zeros(B + 1, dtype=np.int64)
+    np.cumsum(lengths, out=offsets[1:])
+    X = _f64(X).reshape(-1, net.dx)
+    assert X.shape == (int(offsets[-1]), net.dx)
+    hw = None if halt_w is None else _f64(halt_w)
+    assert hw is None or hw.shape == (net.H,)
+    h, y = np.empty((B, net.H)), np.empty((B, net.dy))
+    steps = np.empty(B, dtype=np.int64)
+    _load().lstmo_while_forward(ctypes.byref(net.c), _dp(X),
+                                offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                ctypes.c_int64(B), ctypes.c_int64(int(max_steps)), _dp(hw),
+                                ctypes.c_double(float(halt_c)), _dp(h), _dp(y),
+                                steps.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)))
+    return h, y, steps

@@ -362,3 +362,67 @@ void lstmo_varlen_forward(const lstmo_net *net, const double *X, const int64_t *
                               h_out ? h_out + (size_t)i * net->H : NULL,
                               y_out ? y_out + (size_t)i * net->dy : NULL);
 }
+
+/* -------------------------------------------------------------------------------------
+ * A while loop whose condition depends on the state, nested in the parallel-for (the loop nest of
+ * Section 3.7, before its conversion: "parfor i: R, T = pre(i); while cond(i, R, T): R = body(i, R, T)").
+ *   pre:  h = c = 0, t = 0; T = the iteration's own tokens x[0 .. len) and its length
+ *   cond: t < len  and  t < max_steps  and  halt_c + sum_k h[k] * halt_w[k] <= 0
+ *         (halt_w == NULL: the score is taken as halt_c alone -- pass halt_c <= 0 to leave only the
+ *         length and the cap)
+ *   body: (h, c) = cell(x[t], h, c); t = t + 1
+ * The condition is evaluated before every trip, also the first one (with h = 0).  After the loop
+ * y = h W_out + b_out; steps_out receives the number of trips the iteration made.
+ * ------------------------------------------------------------------------------------- */
+void lstmo_body_while_forward(const lstmo_net *net, const double *x, int64_t len, int64_t max_steps,
+                              const double *halt_w, double halt_c, double *h_out, double *y_out,
+                              int64_t *steps_out) {
+  const int dx = net->dx, H = net->H, dy = net->dy, G = 4 * net->H;
+  double *h = (double *)calloc((size_t)H, sizeof(double));
+  double *c = (double *)calloc((size_t)H, sizeof(double));
+  double *hn = (double *)malloc(sizeof(double) * (size_t)H);
+  double *z = (double *)malloc(sizeof(double) * (size_t)G);
+  int64_t t = 0;
+  for (;;) {
+    /* cond(i, R, T) */
+    double score = halt_c;
+    if (halt_w)
+      for (int k = 0; k < H; ++k) score += h[k] * halt_w[k];
+    if (!(t < len && t < max_steps && score <= 0.0)) break;
+    /* body(i, R, T) */
+    const double *xt = x + (size_t)t * dx;
+    for (int col = 0; col < G; ++col) {
+      double s = net->b ? net->b[col] : 0.0;
+      for (int r = 0; r < dx; ++r) s += xt[r] * net->W[(size_t)r * G + col];
+      for (int r = 0; r < H; ++r) s += h[r] * net->W[(size_t)(dx + r) * G + col];
+      z[col] = s;
+    }
+    for (int k = 0; k < H; ++k) {
+      const double i = sigmoid(z[k]), g = tanh(z[H + k]), f = sigmoid(z[2 * H + k]),
+                   o = sigmoid(z[3 * H + k]);
+      c[k] = f * c[k] + i * g;
+      hn[k] = o * tanh(c[k]);
+    }
+    memcpy(h, hn, sizeof(double) * (size_t)H);
+    t = t + 1;
+  }
+  if (steps_out) *steps_out = t;
+  if (h_out) memcpy(h_out, h, sizeof(double) * (size_t)H);
+  if (y_out)
+    for (int j = 0; j < dy; ++j) {
+      double s = net->bout ? net->bout[j] : 0.0;
+      for (int k = 0; k < H; ++k) s += h[k] * net->Wout[(size_t)k * dy + j];
+      y_out[j] = s;
+    }
+  free(h); free(c); free(hn); free(z);
+}
+
+void lstmo_while_forward(const lstmo_net *net, const double *X, const int64_t *offsets, int64_t B,
+                         int64_t max_steps, const double *halt_w, double halt_c, double *h_out,
+                         double *y_out, int64_t *steps_out) {
+#pragma omp parallel for schedule(dynamic)
+  for (int64_t i = 0; i < B; ++i)
+    lstmo_body_while_forward(net, X + (size_t)offsets[i] * net->dx, offsets[i + 1] - offsets[i], max_steps,
+                             halt_w, halt_c, h_out ? h_out + (size_t)i * net->H : NULL,
+                             y_out ? y_out + (size_t)i * net->dy : NULL, steps_out ? steps_out + i : NULL);
+}

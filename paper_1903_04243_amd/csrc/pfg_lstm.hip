@@ -276,8 +276,21 @@ int pfg_lstm_varlen_forward(const pfg_lstm *net, const void *X, const int32_t *l
   std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return lengths[a] > lengths[b]; });
   std::vector<int64_t> first(B + 1, 0);
   for (int64_t b = 0; b < B; ++b) first[b + 1] = first[b] + lengths[b];
-  // the staging array outlives the call (the copy below may read it after the call returns)
-  thread_local std::vector<int32_t> staged;
+  // The staging array outlives the call: the asynchronous copy below may read it after the call
+  // has returned.  An event recorded behind that copy guards the array: the next call on this
+  // thread waits for it before it touches the array again (the copy is tiny, the wait all but
+  // always over already).
+  struct Staging {
+    std::vector<int32_t> data;
+    hipEvent_t copied = nullptr;
+    bool pending = false;
+  };
+  thread_local Staging st;
+  if (st.pending) {
+    (void)hipEventSynchronize(st.copied);
+    st.pending = false;
+  }
+  std::vector<int32_t> &staged = st.data;
   staged.resize(3 * B);
   for (int64_t j = 0; j < B; ++j) {
     staged[j] = (int32_t)first[order[j]];
@@ -295,6 +308,12 @@ int pfg_lstm_varlen_forward(const pfg_lstm *net, const void *X, const int32_t *l
   int32_t *idx = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + p.idx);
   hipError_t e = hipMemcpyAsync(idx, staged.data(), sizeof(int32_t) * 3 * B, hipMemcpyHostToDevice, stream);
   if (e != hipSuccess) return fail(PFG_ERR_DEVICE, "index upload: %s", hipGetErrorString(e));
+  if (!st.copied && hipEventCreateWithFlags(&st.copied, hipEventDisableTiming) != hipSuccess) st.copied = nullptr;
+  if (st.copied && hipEventRecord(st.copied, stream) == hipSuccess) {
+    st.pending = true;
+  } else if ((e = hipStreamSynchronize(stream)) != hipSuccess) {   // no event: wait for the copy here
+    return fail(PFG_ERR_DEVICE, "index upload: %s", hipGetErrorString(e));
+  }
   const int32_t *tok_row = idx, *orig = idx + B, *len_sorted = idx + 2 * B;
 
   // ---- input projections of all tokens in one product (no padding: M = total_tokens) ----

@@ -319,3 +319,114 @@ def test_varlen_forward_reduces_to_the_fixed_length_model_and_ignores_the_batch_
     packed_p = np.concatenate([X[b, :lengths[b]] for b in order])
     hp, _ = lstm.varlen_forward(net, packed_p, [lengths[b] for b in order])
     np.testing.assert_array_equal(hp, hv[order])
+
+
+# --------------------------------------------------------------------------------------------
+# A while loop whose condition depends on the state (Section 3.7): t < len, t < max_steps and a
+# halting score of the current hidden state that is not positive.
+# --------------------------------------------------------------------------------------------
+def packed(X, lengths):
+    return np.concatenate([X[b, :n] for b, n in enumerate(lengths)] + [np.zeros((0, X.shape[2]))])
+
+
+def test_while_forward_matches_the_library_cell_under_a_python_while():
+    rng = np.random.default_rng(91)
+    net = rand_lstm(rng, 4, 6, 3, 1)
+    lengths = np.array([3, 0, 9, 2, 9, 5, 1, 7])
+    X = rng.standard_normal((len(lengths), 9, 4))
+    w = rng.standard_normal(6)
+    c0 = -0.15
+    h, y, steps = lstm.while_forward(net, packed(X, lengths), lengths, 6, w, c0)
+    cell, Wout, bout, _ = torch_cell(net)
+    seen = set()
+    for b, n in enumerate(lengths):
+        hb = torch.zeros(1, 6, dtype=torch.float64)
+        cb = torch.zeros(1, 6, dtype=torch.float64)
+        t = 0
+        with torch.no_grad():
+            while True:
+                score = c0 + float(hb[0].numpy() @ w)
+                assert abs(score) > 1e-9                  # the decision is not a matter of round-off
+                if not (t < n and t < 6 and score <= 0.0):
+                    break
+                hb, cb = cell(torch.from_numpy(X[b, t:t + 1]), (hb, cb))
+                t += 1
+            want_y = hb[0] @ Wout + bout
+        assert steps[b] == t
+        np.testing.assert_allclose(h[b], hb[0].numpy(), rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(y[b], want_y.numpy(), rtol=1e-12, atol=1e-14)
+        seen.add("cap" if t == 6 else "len" if t == n else "halt")
+    assert seen == {"cap", "len", "halt"}, seen            # every way of leaving the loop occurs
+
+
+def test_while_forward_stops_at_the_first_positive_score():
+    # an independent definition from the pinned state history: with h_0 = 0 and h_1 .. h_T the states
+    # of the fixed-length model, steps = the first t with score(h_t) > 0, capped by len and max_steps
+    rng = np.random.default_rng(92)
+    T = 8
+    net = rand_lstm(rng, 3, 5, 2, T)
+    B = 12
+    X = rng.standard_normal((B, T, 3))
+    lengths = rng.integers(0, T + 1, size=B)
+    w = rng.standard_normal(5) * 2.0
+    c0 = -0.2
+    for cap in (T + 3, 4):
+        h, y, steps = lstm.while_forward(net, packed(X, lengths), lengths, cap, w, c0)
+        for b in range(B):
+            hs, _ = lstm.states(net, X[b])
+            hist = np.concatenate([np.zeros((1, 5)), hs])              # hist[t] = state after t steps
+            scores = c0 + hist @ w
+            first = next((t for t in range(T + 1) if scores[t] > 0.0), T + 1)
+            want = min(first, int(lengths[b]), cap)
+            assert steps[b] == want
+            np.testing.assert_array_equal(h[b], hist[want])
+            np.testing.assert_allclose(y[b], hist[want] @ net.Wout + net.bout, rtol=1e-13, atol=1e-15)
+    assert len(set(steps.tolist())) >= 3
+
+
+def test_while_forward_special_cases():
+    rng = np.random.default_rng(93)
+    T = 6
+    net = rand_lstm(rng, 3, 4, 2, T)
+    X = rng.standard_normal((5, T, 3))
+    lengths = [2, 6, 1, 4, 6]
+    P = packed(X, lengths)
+    hv, yv = lstm.varlen_forward(net, P, lengths)
+    # no halting vector and a non-positive offset: only the lengths stop the loop
+    h, y, steps = lstm.while_forward(net, P, lengths, 100, None, 0.0)
+    np.testing.assert_array_equal(h, hv)
+    np.testing.assert_array_equal(y, yv)
+    assert steps.tolist() == lengths
+    # a score of exactly 0 does not stop the loop (the loop runs while the score is <= 0) ...
+    h, y, steps = lstm.while_forward(net, P, lengths, 100, np.zeros(4), 0.0)
+    np.testing.assert_array_equal(h, hv)
+    assert steps.tolist() == lengths
+    # ... the smallest positive score does, before the first trip: the state stays zero
+    h, y, steps = lstm.while_forward(net, P, lengths, 100, np.zeros(4), 5e-324)
+    assert steps.tolist() == [0] * 5 and not h.any()
+    np.testing.assert_array_equal(y, np.tile(net.bout, (5, 1)))
+    # the cap on the trip count
+    h, y, steps = lstm.while_forward(net, P, lengths, 3, None, -1.0)
+    assert steps.tolist() == [2, 3, 1, 3, 3]
+    for b in range(5):
+        hs, _ = lstm.states(net, X[b])
+        np.testing.assert_array_equal(h[b], hs[steps[b] - 1])
+    assert lstm.while_forward(net, P, lengths, 0, None, -1.0)[2].tolist() == [0] * 5
+    # the score is affine in the offset and reads the hidden state, not the cell state: with
+    # w = e_k the loop stops at the first t with h_t[k] > -c0
+    w = np.zeros(4)
+    w[2] = 1.0
+    h, y, steps = lstm.while_forward(net, P, lengths, 100, w, 0.05)
+    for b in range(5):
+        hs, _ = lstm.states(net, X[b])
+        hist = np.concatenate([np.zeros((1, 4)), hs])
+        first = next((t for t in range(T + 1) if hist[t, 2] + 0.05 > 0.0), T + 1)
+        assert steps[b] == min(first, lengths[b])
+    # iterations are independent: a permuted batch gives the permuted results
+    order = [3, 0, 4, 2, 1]
+    Pp = np.concatenate([X[b, :lengths[b]] for b in order])
+    wv = rng.standard_normal(4)
+    h1, y1, s1 = lstm.while_forward(net, P, lengths, 100, wv, -0.1)
+    h2, y2, s2 = lstm.while_forward(net, Pp, [lengths[b] for b in order], 100, wv, -0.1)
+    np.testing.assert_array_equal(h2, h1[order])
+    np.testing.assert_array_equal(s2, s1[order])

@@ -116,6 +116,16 @@ LSTM_MUTANTS = [
     ("varlen_state_not_carried", "c[k] = f * c[k] + i * g;", "c[k] = i * g;"),
     ("varlen_recurrent_term_dropped",
      "for (int r = 0; r < H; ++r) s += h[r] * net->W[(size_t)(dx + r) * G + col];", ""),
+    ("while_halting_test_strict", "score <= 0.0)) break;", "score < 0.0)) break;"),
+    ("while_first_trip_unconditional", "if (!(t < len && t < max_steps && score <= 0.0)) break;",
+     "if (t > 0 && !(t < len && t < max_steps && score <= 0.0)) break;"),
+    ("while_cap_off_by_one", "t < max_steps && score", "t <= max_steps && score"),
+    ("while_length_off_by_one", "if (!(t < len && t < max_steps", "if (!(t <= len - (len > 0) && t < max_steps"),
+    ("while_score_offset_dropped", "double score = halt_c;", "double score = 0.0;"),
+    ("while_score_reads_the_cell_state", "score += h[k] * halt_w[k];", "score += c[k] * halt_w[k];"),
+    ("while_steps_stacking", "steps_out ? steps_out + i : NULL);", "steps_out ? steps_out + (B - 1 - i) : NULL);"),
+    ("while_state_stacking", "halt_w, halt_c, h_out ? h_out + (size_t)i * net->H : NULL,",
+     "halt_w, halt_c, h_out ? h_out + (size_t)(B - 1 - i) * net->H : NULL,"),
     ("varlen_sequence_offset", "X + (size_t)offsets[i] * net->dx, offsets[i + 1] - offsets[i],",
      "X + (size_t)offsets[i] * net->dx + (i > 0 ? net->dx : 0), offsets[i + 1] - offsets[i],"),
 ]
