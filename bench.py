@@ -350,6 +350,52 @@ def main():
             f"roofline frac {roof['frac']:.3f}")
         return rec, inp
 
+    def measure_while(name, steps, warmup):
+        w = pick(wl.LSTM_WORKLOADS, name)
+        log(f"[bench] {name}: uploading inputs")
+        inp, lengths, offsets, halt_w, halt_c = wl.make_while_inputs(w)
+        net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, 1)
+        X, off, hw = torch.from_numpy(inp.X).to(dev), torch.from_numpy(offsets).to(dev), torch.from_numpy(halt_w).to(dev)
+        B, H, dx, dy = w.B, w.H, w.dx, w.dy
+        tokens = int(lengths.sum())
+        out = (torch.empty((B, H), dtype=torch.float32, device=dev), torch.empty((B, dy), dtype=torch.float32, device=dev),
+               torch.empty((B,), dtype=torch.int32, device=dev), torch.empty((1,), dtype=torch.int32, device=dev))
+        ws = torch.empty(pfg.pfg_lstm_while_workspace_bytes(net, B, tokens), dtype=torch.uint8, device=dev)
+        step = lambda: pfg.pfg_lstm_while_forward(net, X, off, w.T, halt_w=hw, halt_c=halt_c, out=out, workspace=ws)
+        step()
+        torch.cuda.synchronize()
+        used = int(out[2].sum().item())
+        trips = int(out[3].item())
+        log(f"[bench] {name}: {used} of {tokens} tokens consumed, {trips} trips; timing {steps} steps")
+        sec = timed(step, steps, warmup)
+        sec_graph = None
+        if not args.no_graph:
+            try:
+                sec_graph = timed_graph(step, steps, warmup)
+            except Exception as e:
+                log(f"[bench] {name}: graph replay not measured ({e})")
+        kt = kernel_times(step, steps)
+        flops = used * (2 * H * 4 * H)
+        fam = "lstm_step"
+        tf = flops / kt[fam]["ms_per_step"] / 1e9
+        roof = {"kernel": fam, "bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["f32"],
+                "unit": "TFLOP/s", "frac": tf / MFMA_PEAK_TFLOPS["f32"], "traffic": None,
+                "flops_per_launch": flops / kt[fam]["launches_per_step"],
+                "ms_per_launch": kt[fam]["ms_per_step"] / kt[fam]["launches_per_step"],
+                "launches_per_step": kt[fam]["launches_per_step"],
+                "note": "a chain of dependent launches (condition, then body, per trip) on a shrinking list: "
+                        "bound by launch and memory latency, not by either roofline"}
+        rec = {"workload": name, "call": w.call, "input_size": dx, "state_size": H, "output_size": dy,
+               "dtype": "f32", "B": B, "tokens": tokens, "tokens_consumed": used, "trips": trips,
+               "max_steps": w.T, "steps": steps, "ms_per_step": sec * 1e3,
+               "ms_per_step_graph_replay": None if sec_graph is None else sec_graph * 1e3,
+               "tokens_per_sec": used / sec, "sequences_per_sec": B / sec, "kernels": kt,
+               "kernel_ms_sum": sum(v["ms_per_step"] for v in kt.values()),
+               "launches_per_step": sum(v["launches_per_step"] for v in kt.values()), "roofline": roof}
+        log(f"[bench] {name}: {rec['ms_per_step']:.4f} ms/step, {rec['tokens_per_sec'] / 1e6:.1f} M tokens/s, "
+            f"roofline frac {roof['frac']:.3f}")
+        return rec, inp
+
     def measure_conv(name, steps, warmup):
         w = pick(wl.CONV_WORKLOADS, name)
         log(f"[bench] {name}: uploading inputs")
@@ -499,6 +545,8 @@ def main():
         w = pick(wl.LSTM_WORKLOADS, name)
         if w.call == "lstm_varlen_forward":
             return measure_varlen(name, steps, warmup)
+        if w.call == "lstm_while_forward":
+            return measure_while(name, steps, warmup)
         log(f"[bench] {name}: uploading inputs")
         inp = wl.make_lstm_inputs(w)
         net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, w.T)
@@ -676,6 +724,7 @@ def main():
                             ("c7_lstm_grad_norms", max(3, args.steps * 5)),
                             ("c8_lstm_jacobian", max(3, args.steps)),
                             ("c9_lstm_varlen", max(3, args.steps)),
+                            ("c12_lstm_while", max(3, args.steps)),
                             ("c10_mnist_convnet_grads", max(3, args.steps)),
                             ("c10_mnist_convnet_grad_norms", max(3, args.steps)),
                             ("c11_cond_two_branches", max(3, args.steps * 2))):

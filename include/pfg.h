@@ -271,6 +271,37 @@ int pfg_lstm_varlen_forward(const pfg_lstm *net, const void *X, const int32_t *l
                             int64_t total_tokens, float *h_out, float *y_out, void *workspace,
                             size_t workspace_bytes, void *hip_stream);
 
+/* A while loop whose condition depends on the state, nested in the parallel-for, converted by the
+ * rule of Section 3.7: the vectorised loop keeps the list I of the iterations that are still
+ * active; every trip evaluates the condition on the rows of I only, keeps the rows for which it
+ * holds, and runs the body on those.  Iteration i (one sequence) is
+ *      h = c = 0, t = 0
+ *      while t < length_i and t < max_steps and halt_c + sum_k h[k] * halt_w[k] <= 0:
+ *          (h, c) = cell(x_i[t], h, c);  t = t + 1
+ *      y_i = h W_out + b_out
+ * The condition is evaluated before every trip, also the first (with h = 0); a score of exactly 0
+ * lets the loop go on.  The list, its length and the trip counts live in device memory: the call
+ * enqueues max_steps trips whose kernels read the live length themselves and do nothing once the
+ * list is empty, copies nothing from or to the host and does not synchronise, so it can be captured
+ * into a graph.  net->steps is ignored.
+ *   X             DEVICE [total_tokens, input_size]: the tokens of all sequences
+ *   seq_offsets   DEVICE [B + 1] int32: sequence i owns rows seq_offsets[i] .. seq_offsets[i + 1] - 1
+ *                 of X (length 0 is allowed).  The values are not checked on the host; a range that
+ *                 leaves [0, total_tokens] is cut to it, so no row outside X is ever read
+ *   total_tokens  rows of X (HOST value, sizes the input projection)
+ *   max_steps     HOST, >= 0: cap on the trips of every iteration, and the number of trips enqueued
+ *   halt_w        DEVICE [state_size] float32, or NULL (the score is then halt_c alone)
+ *   h_out         DEVICE [B, state_size] or NULL: the state each iteration left the loop with
+ *   y_out         DEVICE [B, output_size] or NULL
+ *   steps_out     DEVICE [B] int32 or NULL: trips made by each iteration
+ *   trips_out     DEVICE [1] int32 or NULL: trips of the vectorised loop whose list was not empty
+ * (at least one of h_out, y_out, steps_out is required).  The halting decision is taken in float32. */
+int pfg_lstm_while_workspace_bytes(const pfg_lstm *net, int64_t B, int64_t total_tokens, size_t *bytes);
+int pfg_lstm_while_forward(const pfg_lstm *net, const void *X, const int32_t *seq_offsets, int64_t B,
+                           int64_t total_tokens, int32_t max_steps, const float *halt_w, float halt_c,
+                           float *h_out, float *y_out, int32_t *steps_out, int32_t *trips_out,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ------------------------------------------------------------------------------------------
  * Convolutional network of the paper's MNIST benchmarks (Section 6.1: conv-relu-maxpool blocks
  * followed by dense layers; the dropout of that model is a stateful random op and is left out).

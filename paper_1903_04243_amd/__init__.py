@@ -30,6 +30,7 @@ EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_per_example_grad
            "pfg_lstm_workspace_bytes", "pfg_lstm_per_example_grads", "pfg_lstm_jacobian_input",
            "pfg_lstm_per_example_grad_norms",
            "pfg_lstm_varlen_workspace_bytes", "pfg_lstm_varlen_forward",
+           "pfg_lstm_while_workspace_bytes", "pfg_lstm_while_forward",
            "pfg_convnet_workspace_bytes", "pfg_convnet_per_example_grads",
            "pfg_convnet_grad_norms_workspace_bytes", "pfg_convnet_per_example_grad_norms",
            "pfg_cond_workspace_bytes", "pfg_cond_forward",
@@ -130,6 +131,9 @@ def load_library() -> ctypes.CDLL:
         lib.pfg_lstm_varlen_workspace_bytes.argtypes = [lstmp, i64, i64, ctypes.POINTER(ctypes.c_size_t)]
         lib.pfg_lstm_varlen_forward.argtypes = [lstmp, vp, ctypes.POINTER(ctypes.c_int32), i64, i64, vp,
                                                 vp, vp, ctypes.c_size_t, vp]
+        lib.pfg_lstm_while_workspace_bytes.argtypes = [lstmp, i64, i64, ctypes.POINTER(ctypes.c_size_t)]
+        lib.pfg_lstm_while_forward.argtypes = [lstmp, vp, vp, i64, i64, ctypes.c_int32, vp, ctypes.c_float,
+                                               vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         convp = ctypes.POINTER(pfg_convnet)
         lib.pfg_convnet_workspace_bytes.argtypes = [convp, i64, ctypes.POINTER(ctypes.c_size_t)]
         lib.pfg_convnet_per_example_grads.argtypes = [convp, vp, vp, i64, ctypes.POINTER(vp),
@@ -527,6 +531,49 @@ def pfg_lstm_varlen_forward(net: Lstm, X, lengths, want_h: bool = True, want_y: 
         total, None if h is None else h.data_ptr(), None if y is None else y.data_ptr(),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr()))
     return h, y
+
+
+def pfg_lstm_while_workspace_bytes(net: Lstm, B: int, total_tokens: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().pfg_lstm_while_workspace_bytes(ctypes.byref(net.c), B, total_tokens,
+                                                         ctypes.byref(n)))
+    return int(n.value)
+
+
+def pfg_lstm_while_forward(net: Lstm, X, seq_offsets, max_steps: int, halt_w=None, halt_c: float = 0.0,
+                           want_h: bool = True, want_y: bool = True, want_steps: bool = True,
+                           want_trips: bool = True, out=None, workspace=None):
+    """The while loop with a state-dependent condition (see include/pfg.h).  ``X`` [tokens, dx] and
+    ``seq_offsets`` (int32 [B + 1]) are GPU tensors.  Returns (h [B, H], y [B, dy], steps [B] int32,
+    trips [1] int32), entries that are not wanted are None; ``out`` may hold caller tensors in that
+    structure."""
+    import torch
+    if (seq_offsets.dtype != torch.int32 or not seq_offsets.is_contiguous() or not seq_offsets.is_cuda or
+            seq_offsets.dim() != 1 or seq_offsets.numel() < 2):
+        raise ValueError("seq_offsets must be a contiguous int32 [B + 1] GPU tensor")
+    if X.dtype != torch.float32 or not X.is_contiguous() or X.dim() != 2 or X.shape[1] != net.dx:
+        raise ValueError("X must be a contiguous float32 [total_tokens, input_size] tensor")
+    if halt_w is not None and (halt_w.dtype != torch.float32 or not halt_w.is_contiguous() or
+                               tuple(halt_w.shape) != (net.H,)):
+        raise ValueError("halt_w must be a contiguous float32 [state_size] tensor")
+    B, total = seq_offsets.numel() - 1, int(X.shape[0])
+    f32 = dict(dtype=torch.float32, device=net.device)
+    if out is not None:
+        h, y, steps, trips = out
+    else:
+        h = torch.empty((B, net.H), **f32) if want_h else None
+        y = torch.empty((B, net.dy), **f32) if want_y else None
+        steps = torch.empty((B,), dtype=torch.int32, device=net.device) if want_steps else None
+        trips = torch.empty((1,), dtype=torch.int32, device=net.device) if want_trips else None
+    if workspace is None:
+        workspace = torch.empty(pfg_lstm_while_workspace_bytes(net, B, total), dtype=torch.uint8,
+                                device=net.device)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(load_library().pfg_lstm_while_forward(
+        ctypes.byref(net.c), X.data_ptr() if total else None, seq_offsets.data_ptr(), B, total, int(max_steps),
+        ptr(halt_w), float(halt_c), ptr(h), ptr(y), ptr(steps), ptr(trips), workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _stream_ptr()))
+    return h, y, steps, trips
 
 
 class ConvNet:

@@ -327,4 +327,22 @@ hipError_t launch_cond_partition(const float *T, int64_t ldt, int32_t n, int32_t
 hipError_t launch_cond_invariant(int32_t n, int32_t flag, int32_t *cond_out, int32_t *counts_out,
                                  hipStream_t stream);
 
+// The while loop inside a parallel-for (Section 3.7), list of active iterations kept on the device.
+// launch_while_init: I = 0 .. B-1, meta = {B, 0}, steps[i] = max_steps, *trips = 0 (trips optional).
+// launch_while_select, trip t: on the rows of I (meta[0] of them) evaluates
+//     t < length of iteration I[m]  and  c0 + <h[I[m], :], w> <= 0          (w may be null: c0 alone)
+// writes the rows that go on to I_next (order kept) and their number to meta_next = {count, 0}; an
+// iteration that stops gets steps[i] = t; *trips = t + 1 if any row goes on.  Token ranges come from
+// seq_offsets [B + 1], cut to [0, total_tokens].  flags needs B entries, cnt while_count_entries(B).
+// launch_while_state: h_out[i] = 0 if steps[i] == 0, else row i of h_even / h_odd by (steps[i] - 1) % 2.
+int64_t while_count_entries(int64_t B);
+hipError_t launch_while_init(int32_t *I, int32_t *meta, int32_t *steps, int32_t *trips, int32_t B,
+                             int32_t max_steps, hipStream_t stream);
+hipError_t launch_while_select(const int32_t *I, const int32_t *meta, int32_t t, const int32_t *seq_offsets,
+                               int32_t total_tokens, const float *h, int32_t H, const float *w, float c0,
+                               int32_t B, int32_t *flags, int32_t *cnt, int32_t *I_next, int32_t *meta_next,
+                               int32_t *steps, int32_t *trips, hipStream_t stream);
+hipError_t launch_while_state(const int32_t *steps, const float *h_even, const float *h_odd, int64_t B, int32_t H,
+                              float *h_out, hipStream_t stream);
+
 }  // namespace pfg

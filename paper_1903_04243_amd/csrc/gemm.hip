@@ -931,7 +931,8 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
   if (g.nbatch > 1 && (g.epilogue != EPI_NONE || g.nbatch > 65535))
     return hipErrorInvalidValue;
   if (g.sub && (g.bf16 || !g.a_is_f32 || !g.w_kn || g.S != 1 || g.nbatch > 1 || g.sym_n > 0 || g.a_scale ||
-                (g.epilogue != EPI_NONE && g.epilogue != EPI_BIAS && g.epilogue != EPI_FORWARD) ||
+                (g.epilogue != EPI_NONE && g.epilogue != EPI_BIAS && g.epilogue != EPI_FORWARD &&
+                 g.epilogue != EPI_LSTM_FWD) ||
                 ((g.sub_gather || g.sub_scatter) && !g.sub_rows)))
     return hipErrorInvalidValue;
   if (!g.sub && (g.sub_gather || g.sub_scatter)) return hipErrorInvalidValue;

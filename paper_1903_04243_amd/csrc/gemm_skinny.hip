@@ -198,14 +198,18 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   float lstm_cprev = 0.f;
   const int lstm_m = m0 + (tid >> 3), lstm_k = 8 * second + (tid & 7);
   const bool lstm_live = lstm_fwd && tid < 256 && lstm_m < M && lstm_k < g.lstm_H;
+  // rows chosen on the device (the active list of a while loop): row lstm_m of the product is
+  // iteration lstm_p, whose token row and state are read and written in place
+  int64_t lstm_p = lstm_m;
   if constexpr (LSTM && WKN) {
     if (lstm_live) {
+      if (SUB) lstm_p = g.sub_rows[sub_off + lstm_m];
       const int H = g.lstm_H, T = g.lstm_T, t = g.lstm_step;
-      const int64_t zr = g.lstm_zx_rows ? (int64_t)g.lstm_zx_rows[lstm_m] + t : (int64_t)lstm_m * T + t;
+      const int64_t zr = g.lstm_zx_rows ? (int64_t)g.lstm_zx_rows[lstm_p] + t : lstm_p * T + t;
       const float *zrow = g.lstm_zx + zr * 4 * H + lstm_k;
       lstm_z = f32x4{zrow[0], zrow[H], zrow[2 * H], zrow[3 * H]};
       if (g.lstm_has_prev)
-        lstm_cprev = g.lstm_cs_w[lstm_m * g.lstm_state_ld + (t - 1) * g.lstm_state_ts + lstm_k];
+        lstm_cprev = g.lstm_cs_w[lstm_p * g.lstm_state_ld + (t - 1) * g.lstm_state_ts + lstm_k];
     }
   }
 
@@ -301,10 +305,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
         const float gf = 1.f / (1.f + __expf(-z[2])), go = 1.f / (1.f + __expf(-z[3]));
         const float c = gf * lstm_cprev + gi * gg;
         if (g.lstm_gates_w) {
-          float *grow = g.lstm_gates_w + ((int64_t)lstm_m * T + t) * 4 * H + lstm_k;
+          float *grow = g.lstm_gates_w + (lstm_p * T + t) * 4 * H + lstm_k;
           grow[0] = gi; grow[H] = gg; grow[2 * H] = gf; grow[3 * H] = go;
         }
-        const int64_t at = lstm_m * g.lstm_state_ld + t * g.lstm_state_ts + lstm_k;
+        const int64_t at = lstm_p * g.lstm_state_ld + t * g.lstm_state_ts + lstm_k;
         g.lstm_cs_w[at] = c;
         g.lstm_hs_w[at] = go * tanhf(c);
       }
@@ -463,6 +467,19 @@ hipError_t launch_nw(const GemmArgs &g, hipStream_t stream) {
   }
   // the element-wise column loads of the [K, N] layout put no condition on W
   const bool lstm = (g.epilogue == EPI_LSTM_FWD || g.epilogue == EPI_LSTM_BWD);
+  if constexpr (AMODE == A_F32 && WKN) {
+    if (g.epilogue == EPI_LSTM_FWD && g.sub) {
+      // the fused LSTM step on the rows of a device-side list
+      if (fast_loads_ok(g, false))
+        PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, true, true, true>), dim3((unsigned)tiles),
+                   dim3(64 * NW), 0, stream, g);
+      else
+        PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, false, true, true>), dim3((unsigned)tiles),
+                   dim3(64 * NW), 0, stream, g);
+      return hipGetLastError();
+    }
+  }
+  if (lstm && g.sub) return hipErrorInvalidValue;
   if constexpr (AMODE == A_F32) {
     if (lstm) {
       if (fast_loads_ok(g, !WKN))

@@ -214,6 +214,41 @@ VarlenPlan make_varlen_plan(const pfg_lstm *net, int64_t B, int64_t tokens) {
   return p;
 }
 
+struct WhilePlan {
+  size_t total = 0;
+  size_t zx = 0, state = 0, hfin = 0, list = 0, meta = 0, flags = 0, cnt = 0, steps = 0;
+  size_t take(size_t bytes) {
+    const size_t at = total;
+    total += (bytes + 255) / 256 * 256;
+    return at;
+  }
+};
+
+WhilePlan make_while_plan(const pfg_lstm *net, int64_t B, int64_t tokens) {
+  const size_t H = net->state_size, f = sizeof(float), i = sizeof(int32_t);
+  WhilePlan p;
+  p.zx = p.take(f * (tokens > 0 ? tokens : 1) * 4 * H);
+  p.state = p.take(f * 3 * B * H);          // h (two buffers used alternately) and c, zeroed together
+  p.hfin = p.take(f * B * H);               // last states, if h_out is not given
+  p.list = p.take(i * 2 * B);               // the active list of this trip and of the next
+  p.meta = p.take(i * 4);                   // their {length, 0} descriptors
+  p.flags = p.take(i * B);
+  p.cnt = p.take(i * while_count_entries(B));
+  p.steps = p.take(i * B);                  // trip counts, if steps_out is not given
+  return p;
+}
+
+int check_while_sizes(const pfg_lstm *net, int64_t B, int64_t tokens) {
+  if (B < 1) return fail(PFG_ERR_SHAPE, "B = %lld must be at least 1", (long long)B);
+  if (tokens < 0) return fail(PFG_ERR_SHAPE, "total_tokens = %lld is negative", (long long)tokens);
+  const int64_t H = net->state_size;
+  if (B > (1 << 24) || tokens > kMaxRows - (1 << 20) || (tokens > 0 && 4 * H > kMaxElems / tokens) ||
+      B * H > ((int64_t)1 << 38))
+    return fail(PFG_ERR_OVERFLOW, "B = %lld sequences with %lld tokens exceed the indexing limits",
+                (long long)B, (long long)tokens);
+  return PFG_OK;
+}
+
 int check_varlen_sizes(const pfg_lstm *net, int64_t B, int64_t tokens) {
   if (B < 1) return fail(PFG_ERR_SHAPE, "B = %lld must be at least 1", (long long)B);
   if (tokens < B) return fail(PFG_ERR_SHAPE, "total_tokens = %lld is less than B = %lld", (long long)tokens, (long long)B);
@@ -349,6 +384,100 @@ int pfg_lstm_varlen_forward(const pfg_lstm *net, const void *X, const int32_t *l
   // (parity[j] = length of sorted row j; odd lengths end in buffer 0)
   float *hfin = h_out ? h_out : ws_at(ws, p.hfin);
   PFG_LAUNCH("scatter_rows", launch_scatter_rows(hbuf[1], hbuf[0], len_sorted, orig, B, H, hfin, stream));
+  if (y_out) {
+    GemmArgs g{};
+    g.A = hfin; g.lda = H; g.a_batch_stride = H; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->W_out; g.ldw = dy; g.w_kn = 1;
+    g.M = (int32_t)B; g.N = dy; g.K = H;
+    g.bias = net->b_out; g.epilogue = EPI_BIAS;
+    g.C = y_out; g.ldc = dy;
+    PFG_LAUNCH("lstm_gemm_readout", launch_gemm(g, stream));
+  }
+  return PFG_OK;
+}
+
+int pfg_lstm_while_workspace_bytes(const pfg_lstm *net, int64_t B, int64_t total_tokens, size_t *bytes) {
+  clear_error();
+  int rc = check_lstm(net);
+  if (rc) return rc;
+  if (!bytes) return fail(PFG_ERR_NULL, "bytes is NULL");
+  if ((rc = check_while_sizes(net, B, total_tokens))) return rc;
+  *bytes = make_while_plan(net, B, total_tokens).total;
+  return PFG_OK;
+}
+
+int pfg_lstm_while_forward(const pfg_lstm *net, const void *X, const int32_t *seq_offsets, int64_t B,
+                           int64_t total_tokens, int32_t max_steps, const float *halt_w, float halt_c,
+                           float *h_out, float *y_out, int32_t *steps_out, int32_t *trips_out,
+                           void *workspace, size_t workspace_bytes, void *hip_stream) {
+  clear_error();
+  int rc = check_lstm(net);
+  if (rc) return rc;
+  if (!X && total_tokens > 0) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!seq_offsets) return fail(PFG_ERR_NULL, "seq_offsets is NULL");
+  if (!h_out && !y_out && !steps_out) return fail(PFG_ERR_NULL, "h_out, y_out and steps_out are all NULL");
+  if (max_steps < 0 || max_steps > (1 << 20))
+    return fail(PFG_ERR_SHAPE, "max_steps = %d is outside [0, %d]", max_steps, 1 << 20);
+  if ((rc = check_while_sizes(net, B, total_tokens))) return rc;
+  const WhilePlan p = make_while_plan(net, B, total_tokens);
+  if (!workspace) return fail(PFG_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", p.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(PFG_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  if (workspace_bytes < p.total)
+    return fail(PFG_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, p.total);
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int32_t dx = net->input_size, H = net->state_size, dy = net->output_size;
+  const float *W = static_cast<const float *>(net->W);
+  void *ws = workspace;
+  auto ints = [&](size_t off) { return reinterpret_cast<int32_t *>(static_cast<char *>(ws) + off); };
+
+  // ---- the part in front of the loop: input projections of all tokens in one product (they do not
+  // depend on the recurrence), zero states, the list of all iterations ----
+  if (total_tokens > 0 && max_steps > 0) {
+    GemmArgs g{};
+    g.A = X; g.lda = dx; g.a_batch_stride = dx; g.S = 1; g.a_is_f32 = 1;
+    g.W = W; g.ldw = 4 * H; g.w_kn = 1;
+    g.M = (int32_t)total_tokens; g.N = 4 * H; g.K = dx;
+    g.bias = net->b; g.epilogue = EPI_BIAS;
+    g.C = ws_at(ws, p.zx); g.ldc = 4 * H;
+    PFG_LAUNCH("lstm_gemm_input", launch_gemm(g, stream));
+  }
+  float *hbuf[2] = {ws_at(ws, p.state), ws_at(ws, p.state) + B * (int64_t)H};
+  float *c = ws_at(ws, p.state) + 2 * B * (int64_t)H;
+  PFG_LAUNCH("fill_zero", launch_fill_zero(ws_at(ws, p.state), 3 * B * (int64_t)H, stream));
+  int32_t *list[2] = {ints(p.list), ints(p.list) + B};
+  int32_t *meta[2] = {ints(p.meta), ints(p.meta) + 2};
+  int32_t *steps = steps_out ? steps_out : ints(p.steps);
+  PFG_LAUNCH("while_select", launch_while_init(list[0], meta[0], steps, trips_out, (int32_t)B, max_steps, stream));
+
+  // ---- the loop: trip t evaluates the condition on the active rows, keeps those that go on, and
+  // runs the cell on them; h_t goes to buffer t % 2 (a trip reads whole rows of h_{t-1} while other
+  // workgroups write h_t), c is updated in place.  Every kernel takes the live row count from
+  // device memory; once the list is empty the remaining trips find nothing to do. ----
+  for (int32_t t = 0; t < max_steps; ++t) {
+    const int cur = t & 1, nxt = cur ^ 1;
+    PFG_LAUNCH("while_select",
+               launch_while_select(list[cur], meta[cur], t, seq_offsets, (int32_t)total_tokens, hbuf[(t + 1) & 1], H,
+                                   halt_w, halt_c, (int32_t)B, ints(p.flags), ints(p.cnt), list[nxt], meta[nxt],
+                                   steps, trips_out, stream));
+    GemmArgs g{};
+    g.A = hbuf[(t + 1) & 1]; g.lda = H; g.a_batch_stride = H; g.S = 1; g.a_is_f32 = 1;
+    g.W = W + (int64_t)dx * 4 * H; g.ldw = 4 * H; g.w_kn = 1;
+    g.M = (int32_t)B; g.N = 4 * H; g.K = H;
+    g.epilogue = EPI_LSTM_FWD;
+    g.lstm_H = H; g.lstm_T = 1; g.lstm_step = t;
+    g.lstm_zx = ws_at(ws, p.zx); g.lstm_zx_rows = seq_offsets;
+    g.lstm_gates_w = nullptr;
+    g.lstm_cs_w = c; g.lstm_hs_w = hbuf[t & 1];
+    g.lstm_state_ld = H; g.lstm_state_ts = 0; g.lstm_has_prev = 1;
+    g.sub = meta[nxt]; g.sub_rows = list[nxt]; g.sub_gather = 1; g.sub_scatter = 0;
+    PFG_LAUNCH("lstm_step", launch_gemm(g, stream));
+  }
+
+  // ---- behind the loop: every iteration's last state, then the readout on all rows ----
+  float *hfin = h_out ? h_out : ws_at(ws, p.hfin);
+  if (h_out || y_out)
+    PFG_LAUNCH("while_state", launch_while_state(steps, hbuf[0], hbuf[1], B, H, hfin, stream));
   if (y_out) {
     GemmArgs g{};
     g.A = hfin; g.lda = H; g.a_batch_stride = H; g.S = 1; g.a_is_f32 = 1;

@@ -176,6 +176,8 @@ LSTM_WORKLOADS: Dict[str, LstmWorkload] = {
         LstmWorkload("c8_lstm_jacobian", 7, "lstm_jacobian_input", 128, 256, 128, 10, 64, S=128),
         # sequences of different lengths, each iterated to its own length (T = the longest allowed)
         LstmWorkload("c9_lstm_varlen", 8, "lstm_varlen_forward", 128, 256, 10, 100, 1024),
+        # the same sequences under a loop that also stops on a halting score of the hidden state
+        LstmWorkload("c12_lstm_while", 8, "lstm_while_forward", 128, 256, 10, 100, 1024),
     ]
 }
 
@@ -223,6 +225,21 @@ def make_varlen_inputs(w: LstmWorkload, B: Optional[int] = None, dx=None, H=None
     base.X = X
     base.labels = np.zeros(B, dtype=np.int32)
     return base, lengths
+
+
+def make_while_inputs(w: LstmWorkload, **kw):
+    """make_varlen_inputs plus a halting vector N(0, 4 / H) and the offset -0.5 (on c9's sequences
+    29 % of the iterations stop on the score before their tokens run out, 41 148 of 51 957 tokens
+    are consumed).  Returns
+    (LstmInputs, lengths int32, seq_offsets int32 [B + 1], halt_w float32 [H], halt_c)."""
+    inp, lengths = make_varlen_inputs(w, **kw)
+    H = inp.Wout.shape[0]
+    seed = kw.get("seed")
+    rng = np.random.Generator(np.random.Philox((BASE_SEED + w.index if seed is None else seed) + 700000))
+    halt_w = (rng.standard_normal(H) * 2.0 / np.sqrt(H)).astype(np.float32)
+    offsets = np.zeros(lengths.size + 1, dtype=np.int32)
+    np.cumsum(lengths, out=offsets[1:])
+    return inp, lengths, offsets, halt_w, -0.5
 
 
 # --------------------------------------------------------------------------------------------

@@ -295,6 +295,35 @@ def test_lstm_varlen_workspace_and_rejections(lib):
     assert fn(r, FAKE, lens, 3, 7, FAKE, FAKE, FAKE, 64, None) == pfg.PFG_ERR_WORKSPACE
 
 
+def test_lstm_while_workspace_and_rejections(lib):
+    net = make_lstm()
+    B, tokens, H = 1024, 51957, 256
+    n = ctypes.c_size_t(0)
+    r = ctypes.byref(net)
+    assert lib.pfg_lstm_while_workspace_bytes(r, B, tokens, ctypes.byref(n)) == 0
+    groups = (B + 31) // 32 + (B + 1023) // 1024
+    assert n.value == (up(4 * tokens * 4 * H) + up(4 * 3 * B * H) + up(4 * B * H) + up(4 * 2 * B) + up(16) +
+                       up(4 * B) + up(4 * groups) + up(4 * B))
+    assert lib.pfg_lstm_while_workspace_bytes(r, 4, 0, ctypes.byref(n)) == 0          # no tokens at all is allowed
+    assert lib.pfg_lstm_while_workspace_bytes(r, 0, 5, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
+    assert lib.pfg_lstm_while_workspace_bytes(r, 8, -1, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
+    assert lib.pfg_lstm_while_workspace_bytes(r, 8, 1 << 40, ctypes.byref(n)) == pfg.PFG_ERR_OVERFLOW
+    assert lib.pfg_lstm_while_workspace_bytes(r, 1 << 25, 9, ctypes.byref(n)) == pfg.PFG_ERR_OVERFLOW
+    assert lib.pfg_lstm_while_workspace_bytes(r, 8, 9, None) == pfg.PFG_ERR_NULL
+    fn = lib.pfg_lstm_while_forward
+    fn.argtypes = [ctypes.POINTER(pfg.pfg_lstm), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                   ctypes.c_int32, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p,
+                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    big = 1 << 40
+    assert fn(r, None, FAKE, 3, 7, 5, None, 0.0, FAKE, FAKE, FAKE, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r, FAKE, None, 3, 7, 5, None, 0.0, FAKE, FAKE, FAKE, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r, FAKE, FAKE, 3, 7, 5, None, 0.0, None, None, None, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r, FAKE, FAKE, 3, 7, -1, None, 0.0, FAKE, FAKE, FAKE, None, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+    assert "max_steps" in lib.pfg_last_error().decode()
+    assert fn(r, FAKE, FAKE, 3, 7, 5, None, 0.0, FAKE, FAKE, FAKE, None, None, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(r, FAKE, FAKE, 3, 7, 5, None, 0.0, FAKE, FAKE, FAKE, None, FAKE, 64, None) == pfg.PFG_ERR_WORKSPACE
+
+
 def make_convnet(h=28, w=28, c=1, kernel=(5, 5), filters=(32, 64), dense=(3136, 1024, 10), Wc_null=None,
                  dtype=0):
     nc = len(kernel)
