@@ -103,3 +103,31 @@ def forward(net: Cond, X, invariant: int = PER_ITERATION):
     _load().condo_forward(ctypes.byref(net.c), _dp(X), ctypes.c_int64(n), ctypes.c_int(int(invariant)),
                           _dp(R), cond.ctypes.data_as(_c_int32_p))
     return R, cond
+
+
+def per_example_grads(net: Cond, X, labels, invariant: int = PER_ITERATION):
+    """pfor over the rows of X of body = gradients(softmax cross-entropy of the iteration's own
+    result).  Returns a dict with, for each of "pre", "then", "else", the lists dW [n, d_{l-1}, d_l]
+    and db [n, d_l] (an iteration's gradient for the branch it did not take is zero), plus
+    "loss" [n] and "cond" [n] int32."""
+    X = _f64(X)
+    n = X.shape[0]
+    assert X.shape == (n, net.d0)
+    labels = np.ascontiguousarray(np.asarray(labels, dtype=np.int32))
+    assert labels.shape == (n,) and labels.min(initial=0) >= 0 and labels.max(initial=0) < net.dout
+    out, args, keep = {}, [], []
+    for name, m in (("pre", net.pre), ("then", net.then_net), ("else", net.else_net)):
+        dW = [np.empty((n, m.dims[l], m.dims[l + 1])) for l in range(m.L)]
+        db = [np.empty((n, m.dims[l + 1])) for l in range(m.L)]
+        out[name] = (dW, db)
+        for arrs in (dW, db):
+            p = (_c_double_p * m.L)(*[_dp(a) for a in arrs])
+            keep.append(p)
+            args.append(p)
+    loss = np.empty(n)
+    cond = np.empty(n, dtype=np.int32)
+    _load().condo_per_example_grads(ctypes.byref(net.c), _dp(X), labels.ctypes.data_as(_c_int32_p),
+                                    ctypes.c_int64(n), ctypes.c_int(int(invariant)), *args, _dp(loss),
+                                    cond.ctypes.data_as(_c_int32_p))
+    out["loss"], out["cond"] = loss, cond
+    return out

@@ -5,11 +5,13 @@ both branches evaluated for every row, the already pinned dense-network oracle, 
 CPU only.  Nothing here touches the HIP library.
 """
 import json
+import math
 import os
 
 import numpy as np
 import pytest
 import scipy.special
+import torch
 
 import oracle
 from oracle import cond
@@ -145,3 +147,140 @@ def test_condition_uses_offset_and_every_component():
         w2[k] += 0.5
         assert abs(cond.score(cond.Cond(net.pre, w2, 0.25, net.then_net, net.else_net), x) -
                    (base + 0.5 * t[k])) < 1e-13
+
+
+# --------------------------------------------------------------------------------------------
+# Per-example gradients through the conditional (Section 3.6 under Section 5.3).
+# --------------------------------------------------------------------------------------------
+def fixture_value(entry, shape):
+    """An entry of cond_grad_2_2.json: {} is an exact zero, {"unit": multiples} a multiple of a unit."""
+    units = {"q": 1.0 / (1.0 + math.exp(1.0)), "u": 1.0 - 1.0 / (1.0 + math.exp(2.0)), "h": 0.5}
+    if not entry:
+        return np.zeros(shape)
+    (name, mult), = entry.items()
+    return units[name] * np.array(mult, dtype=float)
+
+
+def test_gradient_hand_fixture():
+    g = json.load(open(os.path.join(GOLD, "cond_grad_2_2.json")))
+    mk = lambda Ws, bs: oracle.Net([np.array(W, float) for W in Ws], [np.array(b, float) for b in bs], "relu")
+    net = cond.Cond(mk([g["W_pre"]], [g["b_pre"]]), g["w"], g["c0"], mk(g["then_W"], g["then_b"]),
+                    mk(g["else_W"], g["else_b"]))
+    out = cond.per_example_grads(net, np.array(g["X"], float), g["labels"])
+    assert out["cond"].tolist() == g["cond"]
+    for i in range(4):
+        for name in ("pre", "then", "else"):
+            want_W = fixture_value(g[f"dW_{name}"][i], (2, 2))
+            want_b = fixture_value(g[f"db_{name}"][i], (2,))
+            np.testing.assert_allclose(out[name][0][0][i], want_W, rtol=1e-13, atol=0)
+            np.testing.assert_allclose(out[name][1][0][i], want_b, rtol=1e-13, atol=0)
+        assert out["loss"][i] == pytest.approx(eval(g["loss_formulas"][i], {"log": math.log, "exp": math.exp}),
+                                               rel=1e-13)
+
+
+def torch_net(m, x, last_act, params):
+    act = {"relu": torch.relu, "tanh": torch.tanh, "identity": lambda v: v,
+           "gelu": lambda v: torch.nn.functional.gelu(v)}[m.act]
+    h = x
+    for l in range(m.L):
+        W = torch.from_numpy(m.Ws[l]).clone().requires_grad_(True)
+        b = torch.from_numpy(m.bs[l] if m.bs[l] is not None else np.zeros(m.dims[l + 1])).clone().requires_grad_(True)
+        params.append((W, b))
+        h = h @ W + b
+        if l < m.L - 1 or last_act:
+            h = act(h)
+    return h
+
+
+@pytest.mark.parametrize("act", ["relu", "tanh", "gelu"])
+def test_gradients_match_autograd_through_the_taken_branch(act):
+    rng = np.random.default_rng(21)
+    net = rand_cond(rng, (6, 8, 5), (7, 4), (9, 6, 4), act=act, c0=0.0)
+    n = 14
+    X = rng.standard_normal((n, 6))
+    labels = rng.integers(0, 4, size=n)
+    T = np_mlp(net.pre, X, last_act=True)
+    net = cond.Cond(net.pre, net.w, -float(np.median(T @ net.w)) + 1e-3, net.then_net, net.else_net)
+    out = cond.per_example_grads(net, X, labels)
+    s = T @ net.w + net.c0
+    assert 3 < int((s > 0).sum()) < 11 and np.array_equal(out["cond"], (s > 0).astype(np.int32))
+    for i in range(n):
+        pp, pb = [], []
+        t = torch_net(net.pre, torch.from_numpy(X[i]), True, pp)
+        taken, other = (("then", "else") if s[i] > 0 else ("else", "then"))
+        r = torch_net(net.then_net if s[i] > 0 else net.else_net, t, False, pb)
+        loss = -torch.log_softmax(r, dim=0)[int(labels[i])]
+        loss.backward()
+        assert out["loss"][i] == pytest.approx(float(loss.detach()), rel=1e-12)
+        for l, (W, b) in enumerate(pp):
+            np.testing.assert_allclose(out["pre"][0][l][i], W.grad.numpy(), rtol=1e-10, atol=1e-14)
+            np.testing.assert_allclose(out["pre"][1][l][i], b.grad.numpy(), rtol=1e-10, atol=1e-14)
+        for l, (W, b) in enumerate(pb):
+            np.testing.assert_allclose(out[taken][0][l][i], W.grad.numpy(), rtol=1e-10, atol=1e-14)
+            np.testing.assert_allclose(out[taken][1][l][i], b.grad.numpy(), rtol=1e-10, atol=1e-14)
+        for arrs in out[other]:
+            for a in arrs:
+                assert not a[i].any(), "the branch that was not taken has a non-zero gradient"
+
+
+def test_gradients_with_an_invariant_condition_are_those_of_the_concatenated_network():
+    # loop-invariant condition: every row takes the same branch, so pre followed by that branch is one
+    # dense network (same activation throughout) and the pinned dense oracle gives its gradients
+    rng = np.random.default_rng(22)
+    net = rand_cond(rng, (5, 7), (6, 3), (3,), act="tanh")
+    X = rng.standard_normal((9, 5))
+    labels = rng.integers(0, 3, size=9)
+    for flag, name, br in ((1, "then", net.then_net), (0, "else", net.else_net)):
+        out = cond.per_example_grads(net, X, labels, invariant=flag)
+        assert out["cond"].tolist() == [flag] * 9
+        whole = oracle.Net(net.pre.Ws + br.Ws, net.pre.bs + br.bs, "tanh")
+        dW, db, loss = oracle.per_example_grads(whole, X, labels)
+        got_W, got_b = out["pre"][0] + out[name][0], out["pre"][1] + out[name][1]
+        for l in range(whole.L):
+            np.testing.assert_allclose(got_W[l], dW[l], rtol=1e-12, atol=1e-15)
+            np.testing.assert_allclose(got_b[l], db[l], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(out["loss"], loss, rtol=1e-12)
+        other = "else" if flag else "then"
+        assert not any(a.any() for arrs in out[other] for a in arrs)
+
+
+def test_gradients_match_central_differences_of_the_pinned_forward_pass():
+    rng = np.random.default_rng(23)
+    net = rand_cond(rng, (4, 5), (6, 3), (3,), act="tanh", c0=0.05)
+    X = rng.standard_normal((6, 4))
+    labels = rng.integers(0, 3, size=6)
+    out = cond.per_example_grads(net, X, labels)
+    assert 0 < out["cond"].sum() < 6
+    scores = np.array([cond.score(net, x) for x in X])
+    assert np.abs(scores).min() > 1e-3                     # no row changes branch under the perturbation
+
+    def losses():
+        R, _ = cond.forward(net, X)
+        R = R - R.max(axis=1, keepdims=True)
+        return -(R[np.arange(6), labels] - np.log(np.exp(R).sum(axis=1)))
+
+    h = 1e-6
+    for name, m, which in (("pre", net.pre, 0), ("then", net.then_net, 1), ("else", net.else_net, 0)):
+        for (i, j) in ((0, 1), (m.dims[which] - 1, m.dims[which + 1] - 1)):
+            W = m.Ws[which]
+            keep = W[i, j]
+            W[i, j] = keep + h
+            up = losses()
+            W[i, j] = keep - h
+            dn = losses()
+            W[i, j] = keep
+            np.testing.assert_allclose(out[name][0][which][:, i, j], (up - dn) / (2 * h), rtol=1e-6, atol=1e-9)
+
+
+def test_gradients_permute_with_the_rows():
+    rng = np.random.default_rng(24)
+    net = rand_cond(rng, (5, 6), (4, 3), (3,), act="relu", c0=0.0)
+    X = rng.standard_normal((10, 5))
+    labels = rng.integers(0, 3, size=10)
+    a = cond.per_example_grads(net, X, labels)
+    perm = rng.permutation(10)
+    b = cond.per_example_grads(net, X[perm], labels[perm])
+    for name in ("pre", "then", "else"):
+        for x, y in zip(a[name][0] + a[name][1], b[name][0] + b[name][1]):
+            np.testing.assert_array_equal(y, x[perm])
+    np.testing.assert_array_equal(b["loss"], a["loss"][perm])

@@ -210,6 +210,24 @@ COND_MUTANTS = [
     ("condition_stacking", "if (cond) cond[i] = c;", "if (cond) cond[n - 1 - i] = c;"),
     ("score_offset_dropped", "double s = net->c0;\n  for (int k = 0; k < dT; ++k) s += t[k] * net->w[k];\n  free(t);",
      "double s = 0.0;\n  for (int k = 0; k < dT; ++k) s += t[k] * net->w[k];\n  free(t);"),
+    ("grad_pre_mask_dropped", "g[j] = last_act ? gout[j] * act_deriv(m->act, z[m->L][j]) : gout[j];", "g[j] = gout[j];"),
+    ("grad_hidden_mask_dropped", "gp[i] = (l > 1) ? s * act_deriv(m->act, z[l - 1][i]) : s;", "gp[i] = s;"),
+    ("grad_weight_columns_reversed", "for (int j = 0; j < dout; ++j) s += g[j] * W[(size_t)i * dout + j];",
+     "for (int j = 0; j < dout; ++j) s += g[j] * W[(size_t)i * dout + (dout - 1 - j)];"),
+    ("grad_head_sign", "g[label] -= 1.0;", "g[label] += 1.0;"),
+    ("grad_outer_uses_layer_output", "dW[l - 1][(size_t)i * dout + j] = a[l - 1][i] * g[j];",
+     "dW[l - 1][(size_t)i * dout + j] = a[l - 1][i] * a[l][j];"),
+    ("grad_bias_scaled", "for (int j = 0; j < dout; ++j) db[l - 1][j] = g[j];",
+     "for (int j = 0; j < dout; ++j) db[l - 1][j] = g[j] * a[l - 1][0];"),
+    ("grad_relu_deriv_at_zero", "case CONDO_ACT_RELU: return z > 0.0 ? 1.0 : 0.0;",
+     "case CONDO_ACT_RELU: return z >= 0.0 ? 1.0 : 0.0;"),
+    ("grad_row_stacking", "w[q][l - 1] = dWs[q][l - 1] + (size_t)i * m->dims[l - 1] * m->dims[l];",
+     "w[q][l - 1] = dWs[q][l - 1] + (size_t)(n - 1 - i) * m->dims[l - 1] * m->dims[l];"),
+    ("grad_loss_of_class_zero", "if (loss) *loss = -log(g[label]);", "if (loss) *loss = -log(g[0]);"),
+    ("grad_untaken_branch_gets_the_taken_one", "zero_grads(other, dW_then, db_then);",
+     "zero_grads(other, dW_then, db_then); if (other->dims[1] == taken->dims[1]) memcpy(db_then[0], db_else[0], sizeof(double) * (size_t)other->dims[1]);"),
+    ("grad_tanh_deriv", "case CONDO_ACT_TANH: { const double t = tanh(z); return 1.0 - t * t; }",
+     "case CONDO_ACT_TANH: { const double t = tanh(z); return 1.0 - t; }"),
     ("gelu_is_tanh_form", "return z * 0.5 * (1.0 + erf(z / sqrt(2.0)));",
      "return z * 0.5 * (1.0 + tanh(0.7978845608 * (z + 0.044715 * z * z * z)));"),
 ]
