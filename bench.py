@@ -490,7 +490,61 @@ def main():
         log(f"[bench] {name}: {rec['ms_per_step']:.4f} ms/step, roofline frac {roof['frac']:.3f}")
         return rec, inp
 
+    def measure_cond_grads(name, steps, warmup):
+        w = pick(wl.COND_WORKLOADS, name)
+        log(f"[bench] {name}: uploading inputs")
+        inp = wl.make_cond_inputs(w)
+        net = pfg.Cond.from_numpy(inp.pre, inp.w, inp.c0, inp.then_net, inp.else_net, w.act)
+        X = torch.from_numpy(inp.X).to(dev)
+        n = w.n
+        labels = torch.from_numpy(np.random.Generator(np.random.Philox(wl.BASE_SEED + w.index + 900000))
+                                  .integers(0, net.dout, size=n).astype(np.int32)).to(dev)
+        f32 = dict(dtype=torch.float32, device=dev)
+        out = {}
+        nbytes = 0
+        for nm, m in (("pre", net.pre), ("then", net.then_net), ("else", net.else_net)):
+            out[nm] = ([torch.empty((n, m.dims[l], m.dims[l + 1]), **f32) for l in range(m.L)],
+                       [torch.empty((n, m.dims[l + 1]), **f32) for l in range(m.L)])
+            nbytes += 4 * n * sum(m.dims[l] * m.dims[l + 1] for l in range(m.L))
+        out["loss"] = torch.empty((n,), **f32)
+        out["cond"] = torch.empty((n,), dtype=torch.int32, device=dev)
+        out["counts"] = torch.empty((2,), dtype=torch.int32, device=dev)
+        ws = torch.empty(pfg.pfg_cond_grads_workspace_bytes(net, n), dtype=torch.uint8, device=dev)
+        step = lambda: pfg.pfg_cond_per_example_grads(net, X, labels, out=out, workspace=ws)
+        step()
+        torch.cuda.synchronize()
+        n_then, n_else = out["counts"].tolist()
+        log(f"[bench] {name}: {n_then} then rows, {n_else} else rows; timing {steps} steps")
+        sec = timed(step, steps, warmup)
+        sec_graph = None
+        if not args.no_graph:
+            try:
+                sec_graph = timed_graph(step, steps, warmup)
+            except Exception as e:
+                log(f"[bench] {name}: graph replay not measured ({e})")
+        kt = kernel_times(step, steps)
+        # every gradient slice is written once (products or zeros): 4 bytes per value, all launches of the
+        # outer-product family together
+        fams = [f for f in kt if f.startswith("outer_product")]
+        ms = sum(kt[f]["ms_per_step"] for f in fams)
+        launches = sum(kt[f]["launches_per_step"] for f in fams)
+        gbs = nbytes / ms / 1e6
+        roof = {"kernel": "+".join(sorted(fams)), "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": nbytes / launches,
+                "ms_per_launch": ms / launches, "launches_per_step": launches}
+        rec = {"workload": name, "call": w.call, "pre": list(w.pre), "then": list(w.then_dims),
+               "else": list(w.else_dims), "act": w.act, "dtype": "f32", "n": n, "n_then": n_then, "n_else": n_else,
+               "steps": steps, "ms_per_step": sec * 1e3,
+               "ms_per_step_graph_replay": None if sec_graph is None else sec_graph * 1e3,
+               "output_GB": nbytes / 1e9, "per_example_grads_per_sec": n / sec, "kernels": kt,
+               "kernel_ms_sum": sum(v["ms_per_step"] for v in kt.values()),
+               "launches_per_step": sum(v["launches_per_step"] for v in kt.values()), "roofline": roof}
+        log(f"[bench] {name}: {rec['ms_per_step']:.4f} ms/step, roofline frac {roof['frac']:.3f}")
+        return rec, inp
+
     def measure_cond(name, steps, warmup):
+        if wl.COND_WORKLOADS[name].call == "cond_per_example_grads":
+            return measure_cond_grads(name, steps, warmup)
         w = pick(wl.COND_WORKLOADS, name)
         log(f"[bench] {name}: uploading inputs")
         inp = wl.make_cond_inputs(w)
@@ -727,7 +781,8 @@ def main():
                             ("c12_lstm_while", max(3, args.steps)),
                             ("c10_mnist_convnet_grads", max(3, args.steps)),
                             ("c10_mnist_convnet_grad_norms", max(3, args.steps)),
-                            ("c11_cond_two_branches", max(3, args.steps * 2))):
+                            ("c11_cond_two_branches", max(3, args.steps * 2)),
+                            ("c13_cond_grads", max(3, args.steps))):
             try:
                 fn = measure if name in wl.WORKLOADS else measure_lstm
                 detail[name], _ = fn(name, steps, max(1, min(max(args.warmup, 10), steps // 2)))

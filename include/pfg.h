@@ -394,6 +394,29 @@ int pfg_cond_forward(const pfg_cond *net, const void *X, int64_t n, int invarian
                      int32_t *cond_out, int32_t *counts_out, void *workspace, size_t workspace_bytes,
                      void *hip_stream);
 
+/* Per-example gradients through the conditional (the body of Section 3.6 returning the gradient of
+ * its own loss, Section 5.3): iteration i computes
+ *      ell_i = -log softmax(r_i)[labels[i]]          (not divided by n)
+ * and its gradient with respect to every weight and bias of pre, then_net and else_net.  An
+ * iteration runs one branch, so its gradient with respect to the other branch's parameters is zero
+ * (those slices are written as zeros); the condition selects and passes no gradient to cond_w or
+ * cond_c.  The reverse sweep reuses the index sets of the forward pass: each branch's cotangent
+ * products and outer products run on the rows of its own set, read and store through it, and take
+ * their row count from device memory.
+ *   X, invariant_cond, cond_out, counts_out   as for pfg_cond_forward
+ *   labels        [n] int32, values in [0, d_out)
+ *   dW_pre_out    HOST array of pre.num_layers device pointers, entry l-1 is [n, d_{l-1}, d_l]; a NULL
+ *                 array or entry skips that output.  db_pre_out likewise, entries [n, d_l]
+ *   dW_then_out, db_then_out, dW_else_out, db_else_out   the same for the two branches
+ *   loss_out      [n] or NULL */
+int pfg_cond_grads_workspace_bytes(const pfg_cond *net, int64_t n, size_t *bytes);
+int pfg_cond_per_example_grads(const pfg_cond *net, const void *X, const int32_t *labels, int64_t n,
+                               int invariant_cond, float *const *dW_pre_out, float *const *db_pre_out,
+                               float *const *dW_then_out, float *const *db_then_out,
+                               float *const *dW_else_out, float *const *db_else_out, float *loss_out,
+                               int32_t *cond_out, int32_t *counts_out, void *workspace,
+                               size_t workspace_bytes, void *hip_stream);
+
 /* Text of the last error on the calling thread ("" if none).  Valid until the next call into the
  * library from that thread. */
 const char *pfg_last_error(void);

@@ -34,6 +34,7 @@ EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_per_example_grad
            "pfg_convnet_workspace_bytes", "pfg_convnet_per_example_grads",
            "pfg_convnet_grad_norms_workspace_bytes", "pfg_convnet_per_example_grad_norms",
            "pfg_cond_workspace_bytes", "pfg_cond_forward",
+           "pfg_cond_grads_workspace_bytes", "pfg_cond_per_example_grads",
            "pfg_last_error", "pfg_timing_enable", "pfg_timing_reset",
            "pfg_timing_query", "pfg_timing_names", "pfg_fill_reference", "pfg_version"]
 
@@ -146,6 +147,10 @@ def load_library() -> ctypes.CDLL:
         lib.pfg_cond_workspace_bytes.argtypes = [condp, i64, ctypes.POINTER(ctypes.c_size_t)]
         lib.pfg_cond_forward.argtypes = [condp, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.pfg_fill_reference.argtypes = [vp, i64, ctypes.c_float, vp]
+        pvp = ctypes.POINTER(vp)
+        lib.pfg_cond_grads_workspace_bytes.argtypes = [condp, i64, ctypes.POINTER(ctypes.c_size_t)]
+        lib.pfg_cond_per_example_grads.argtypes = [condp, vp, vp, i64, i32, pvp, pvp, pvp, pvp, pvp, pvp, vp, vp, vp,
+                                                   vp, ctypes.c_size_t, vp]
         lib.pfg_last_error.restype = ctypes.c_char_p
         lib.pfg_timing_enable.argtypes = [i32]
         lib.pfg_timing_query.argtypes = [ctypes.c_char_p, ctypes.POINTER(i64),
@@ -748,6 +753,47 @@ def pfg_cond_forward(net: Cond, X, invariant_cond: int = PFG_COND_PER_ITERATION,
         None if cond is None else cond.data_ptr(), None if counts is None else counts.data_ptr(),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr()))
     return R, cond, counts
+
+
+def pfg_cond_grads_workspace_bytes(net: Cond, n: int) -> int:
+    b = ctypes.c_size_t(0)
+    _check(load_library().pfg_cond_grads_workspace_bytes(ctypes.byref(net.c), n, ctypes.byref(b)))
+    return int(b.value)
+
+
+def pfg_cond_per_example_grads(net: Cond, X, labels, invariant_cond: int = PFG_COND_PER_ITERATION,
+                               want_dW: bool = True, want_db: bool = True, out=None, workspace=None):
+    """Per-example gradients through the conditional.  Returns a dict: for each of "pre", "then",
+    "else" a pair (dW list [n, d_{l-1}, d_l], db list [n, d_l]) -- None when not wanted --, plus
+    "loss" [n], "cond" [n] int32 and "counts" [2] int32.  ``out`` may be such a dict of caller tensors."""
+    import torch
+    if X.dtype != torch.float32 or not X.is_contiguous() or X.dim() != 2 or X.shape[1] != net.d0:
+        raise ValueError("X must be a contiguous float32 [n, d_0] tensor")
+    n = X.shape[0]
+    if labels.dtype != torch.int32 or tuple(labels.shape) != (n,) or not labels.is_contiguous():
+        raise ValueError("labels must be a contiguous int32 [n] tensor")
+    f32 = dict(dtype=torch.float32, device=net.device)
+    if out is None:
+        out = {}
+        for name, m in (("pre", net.pre), ("then", net.then_net), ("else", net.else_net)):
+            dW = [torch.empty((n, m.dims[l], m.dims[l + 1]), **f32) for l in range(m.L)] if want_dW else None
+            db = [torch.empty((n, m.dims[l + 1]), **f32) for l in range(m.L)] if want_db else None
+            out[name] = (dW, db)
+        out["loss"] = torch.empty((n,), **f32)
+        out["cond"] = torch.empty((n,), dtype=torch.int32, device=net.device)
+        out["counts"] = torch.empty((2,), dtype=torch.int32, device=net.device)
+    if workspace is None:
+        workspace = torch.empty(pfg_cond_grads_workspace_bytes(net, n), dtype=torch.uint8, device=net.device)
+    lists = []
+    for name in ("pre", "then", "else"):
+        for arrs in out[name]:
+            lists.append(None if arrs is None else _ptrs(arrs))
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(load_library().pfg_cond_per_example_grads(
+        ctypes.byref(net.c), X.data_ptr(), labels.data_ptr(), n, int(invariant_cond), *lists,
+        ptr(out.get("loss")), ptr(out.get("cond")), ptr(out.get("counts")), workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _stream_ptr()))
+    return out
 
 
 def pfg_fill_reference(out, value: float = 0.0) -> None:

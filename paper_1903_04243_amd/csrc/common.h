@@ -131,7 +131,8 @@ struct GemmArgs {
   // product runs on rows m < sub[0] only (sub[0] <= M; M still sizes the grid).  With sub_gather, row
   // m of the A operand is row sub_rows[sub[1] + m] of A; with sub_scatter, row m of the result is
   // stored at row sub_rows[sub[1] + m] of C (and C2).  float32 operands, S == 1, no batching;
-  // EPI_NONE, EPI_BIAS and EPI_FORWARD only.
+  // EPI_NONE, EPI_BIAS, EPI_FORWARD, EPI_MASK (the mask rows are those of the packed rows m) and, in
+  // the small-problem kernel, EPI_LSTM_FWD.
   const int32_t *sub;           // {row count, offset into sub_rows}
   const int32_t *sub_rows;
   int32_t sub_gather, sub_scatter;
@@ -161,6 +162,14 @@ struct OuterArgs {
   int64_t M;
   int32_t S;
   int32_t d_in, d_out;
+  // Iterations chosen on the device (the index sets of a conditional): when `sub` is set, M is the
+  // length of the list sub_rows and grid index m a position in it; the slice written is that of row
+  // sub_rows[m].  Positions offset .. offset + count - 1 ({count, offset} = sub[0], sub[1]) form the
+  // job's set: position m of it multiplies row (a_gather ? sub_rows[m] : m - offset) of a by row
+  // (g_gather ? sub_rows[m] : m - offset) of g; every other position gets zeros.  S must be 1.
+  const int32_t *sub;
+  const int32_t *sub_rows;
+  int32_t a_gather, g_gather;
 };
 
 // Enqueues the n outer products in as few launches as possible (normally one).
@@ -326,6 +335,15 @@ hipError_t launch_cond_partition(const float *T, int64_t ldt, int32_t n, int32_t
 // Loop-invariant condition: cond_out[j] = flag, counts_out = {n, 0} or {0, n} (both optional)
 hipError_t launch_cond_invariant(int32_t n, int32_t flag, int32_t *cond_out, int32_t *counts_out,
                                  hipStream_t stream);
+
+// rows[m] = m for m < n and meta = {n, 0, 0, n} (flag) or {0, 0, n, 0}: the index sets of a
+// loop-invariant condition, for code that runs through the sets either way
+hipError_t launch_cond_identity_list(int32_t *rows, int32_t *meta, int32_t n, int32_t flag, hipStream_t stream);
+// out[rows[m], :] = src[gather ? rows[m] : m - sub[1], :] if position m lies in the set sub = {count,
+// offset}, else 0; m < n, d columns (a packed or row-indexed block put back at the rows of its set)
+hipError_t launch_cond_scatter_rows(const float *src, int64_t ld_src, int32_t gather, const int32_t *rows,
+                                    const int32_t *sub, int32_t n, int32_t d, float *out, int64_t ld_out,
+                                    hipStream_t stream);
 
 // The while loop inside a parallel-for (Section 3.7), list of active iterations kept on the device.
 // launch_while_init: I = 0 .. B-1, meta = {B, 0}, steps[i] = max_steps, *trips = 0 (trips optional).

@@ -142,7 +142,49 @@ __global__ void invariant_counts_kernel(int32_t *counts_out, int n, int flag) {
   }
 }
 
+// rows[m] = m, meta = the two descriptors of a loop-invariant condition: every row in one set
+__global__ __launch_bounds__(256) void cond_identity_list_kernel(int32_t *rows, int32_t *meta, int n, int flag) {
+  const int m = blockIdx.x * 256 + threadIdx.x;
+  if (m < n) rows[m] = m;
+  if (m == 0) {
+    meta[0] = flag ? n : 0;
+    meta[1] = 0;
+    meta[2] = flag ? 0 : n;
+    meta[3] = flag ? n : 0;
+  }
+}
+
+// out[rows[m], :] = position m of the list lies in the set {sub[1] .. sub[1] + sub[0] - 1} ?
+//                   src[gather ? rows[m] : m - sub[1], :] : 0          for m < n, d columns
+__global__ __launch_bounds__(256) void cond_scatter_rows_kernel(const float *src, int64_t ld_src, int gather,
+                                                                const int32_t *rows, const int32_t *sub, int n,
+                                                                int d, float *out, int64_t ld_out) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (int64_t)n * d) return;
+  const int m = (int)(e / d), j = (int)(e - (int64_t)m * d);
+  const int p = m - sub[1];
+  const int row = rows[m];
+  const bool live = p >= 0 && p < sub[0];
+  out[(int64_t)row * ld_out + j] = live ? src[(int64_t)(gather ? row : p) * ld_src + j] : 0.f;
+}
+
 }  // namespace
+
+hipError_t launch_cond_identity_list(int32_t *rows, int32_t *meta, int32_t n, int32_t flag, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  PFG_KERNEL(cond_identity_list_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, rows, meta, n, flag);
+  return hipGetLastError();
+}
+
+hipError_t launch_cond_scatter_rows(const float *src, int64_t ld_src, int32_t gather, const int32_t *rows,
+                                    const int32_t *sub, int32_t n, int32_t d, float *out, int64_t ld_out,
+                                    hipStream_t stream) {
+  if (n <= 0 || d <= 0) return hipSuccess;
+  const int64_t total = (int64_t)n * d;
+  PFG_KERNEL(cond_scatter_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, src, ld_src,
+             gather, rows, sub, n, d, out, ld_out);
+  return hipGetLastError();
+}
 
 // counts kept in `cnt`: one per group of kGroup rows, followed by one per block of kPlace rows
 int64_t cond_count_groups(int64_t n) { return (n + kGroup - 1) / kGroup + (n + kPlace - 1) / kPlace; }

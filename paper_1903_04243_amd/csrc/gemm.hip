@@ -25,7 +25,7 @@ using namespace dev;
 
 
 // WGM x WGN: arrangement of the workgroup's waves over the tile (2 x 2, or 4 x 2 for the largest).
-// SUB: the instantiation for rows chosen on the device (GemmArgs::sub; float32, W in [K, N] layout),
+// SUB: the instantiation for rows chosen on the device (GemmArgs::sub; float32),
 // kept apart so that the others carry none of its loads and branches (inside the unrolled epilogue
 // they cost a store-bound product a quarter of its speed).
 // AKM: the instantiation that reads A stored as [K, M] (float32, FAST loads only).
@@ -847,7 +847,7 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
   // place of 64 x 64: within 6 % either way on plain products, and a third slower where the long
   // reverse-cell epilogue follows.)
   // a 128-wide tile on an output of 64 columns or fewer would be half empty
-  if constexpr (AMODE == A_F32 && WKN) {
+  if constexpr (AMODE == A_F32) {
     if (g.sub) {
       if (big >= 512 && g.N > 64)
         return fast ? launch_one<AMODE, WKN, 2, 2, 128, true, 2, 2, true>(g, stream)
@@ -856,7 +856,7 @@ hipError_t launch_tiles(const GemmArgs &g, hipStream_t stream) {
                   : launch_one<AMODE, WKN, 1, 1, 128, false, 2, 2, true>(g, stream);
     }
   }
-  if (g.sub) return hipErrorInvalidValue;     // rows chosen on the device: float32 forward products only
+  if (g.sub) return hipErrorInvalidValue;     // rows chosen on the device: float32 only
   if constexpr (AMODE == A_F32 && WKN) {
     if (g.a_km) {
       // 64 x 64 tiles only (the 128 x 128 arrangement runs out of registers with the scattered
@@ -930,9 +930,10 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
     return hipErrorInvalidValue;
   if (g.nbatch > 1 && (g.epilogue != EPI_NONE || g.nbatch > 65535))
     return hipErrorInvalidValue;
-  if (g.sub && (g.bf16 || !g.a_is_f32 || !g.w_kn || g.S != 1 || g.nbatch > 1 || g.sym_n > 0 || g.a_scale ||
+  if (g.sub && (g.bf16 || !g.a_is_f32 || g.S != 1 || g.nbatch > 1 || g.sym_n > 0 || g.a_scale ||
                 (g.epilogue != EPI_NONE && g.epilogue != EPI_BIAS && g.epilogue != EPI_FORWARD &&
-                 g.epilogue != EPI_LSTM_FWD) ||
+                 g.epilogue != EPI_MASK && g.epilogue != EPI_LSTM_FWD) ||
+                (!g.w_kn && g.epilogue != EPI_NONE && g.epilogue != EPI_MASK) ||
                 ((g.sub_gather || g.sub_scatter) && !g.sub_rows)))
     return hipErrorInvalidValue;
   if (!g.sub && (g.sub_gather || g.sub_scatter)) return hipErrorInvalidValue;

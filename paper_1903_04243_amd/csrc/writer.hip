@@ -51,8 +51,11 @@ struct OuterBatch {
 // d_out % 4 == 0, out 16-byte aligned.  V = d_out / 4 vector columns.
 // Workgroup = (m, column slab of up to THREADS vectors, chunk of rows).  When V < THREADS a pass
 // covers THREADS / V rows at once.
+// m: the slice of `out` that is written; ma, mg: the rows of a and g it is the product of; live:
+// false writes zeros instead (a row of a device-side list that lies outside the job's set).
 template <int THREADS>
-__device__ __forceinline__ void outer_vec4(const OuterJob &jb, uint32_t x, int64_t m) {
+__device__ __forceinline__ void outer_vec4(const OuterJob &jb, uint32_t x, int64_t m, int64_t ma, int64_t mg,
+                                           bool live) {
   const OuterArgs &o = jb.o;
   const int V = jb.V;
   uint32_t chunk = x, slab = 0;
@@ -77,7 +80,16 @@ __device__ __forceinline__ void outer_vec4(const OuterJob &jb, uint32_t x, int64
   }
   if (vc >= V) return;
 
-  const float *grow = o.g + m * o.ldg + 4 * vc;
+  const int i_begin = chunk * jb.per_chunk;
+  const int i_end = min(i_begin + jb.per_chunk, o.d_in);
+  f32x4 *obase = reinterpret_cast<f32x4 *>(o.out + m * (int64_t)o.d_in * o.d_out) + vc;
+  if (!live) {
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    for (int i = i_begin + r0; i < i_end; i += rstep) __builtin_nontemporal_store(zero, obase + (int64_t)i * V);
+    return;
+  }
+
+  const float *grow = o.g + mg * o.ldg + 4 * vc;
   f32x4 gv;
   if (((reinterpret_cast<uintptr_t>(o.g) & 15) == 0) && ((o.ldg & 3) == 0)) {
     gv = *reinterpret_cast<const f32x4 *>(grow);
@@ -85,11 +97,7 @@ __device__ __forceinline__ void outer_vec4(const OuterJob &jb, uint32_t x, int64
     gv[0] = grow[0]; gv[1] = grow[1]; gv[2] = grow[2]; gv[3] = grow[3];
   }
 
-  const int64_t abase = (o.S == 1 ? m : (int64_t)((uint32_t)m / (uint32_t)o.S)) * o.lda;
-  const int i_begin = chunk * jb.per_chunk;
-  const int i_end = min(i_begin + jb.per_chunk, o.d_in);
-  f32x4 *obase = reinterpret_cast<f32x4 *>(o.out + m * (int64_t)o.d_in * o.d_out) + vc;
-
+  const int64_t abase = ma * o.lda;
   for (int i = i_begin + r0; i < i_end; i += rstep) {
     const float av = load_a(o.a, o.a_bf16, abase + i);
     __builtin_nontemporal_store(gv * av, obase + (int64_t)i * V);
@@ -98,14 +106,19 @@ __device__ __forceinline__ void outer_vec4(const OuterJob &jb, uint32_t x, int64
 
 // Any d_out, any alignment: one thread per output value of a flattened [d_in * d_out] iteration.
 template <int THREADS>
-__device__ __forceinline__ void outer_flat(const OuterJob &jb, uint32_t chunk, int64_t m) {
+__device__ __forceinline__ void outer_flat(const OuterJob &jb, uint32_t chunk, int64_t m, int64_t ma, int64_t mg,
+                                           bool live) {
   const OuterArgs &o = jb.o;
   const int64_t per_m = (int64_t)o.d_in * o.d_out;
   const int64_t e_begin = (int64_t)chunk * jb.per_chunk;
   const int64_t e_end = min(e_begin + jb.per_chunk, per_m);
-  const int64_t abase = (o.S == 1 ? m : (int64_t)((uint32_t)m / (uint32_t)o.S)) * o.lda;
-  const float *grow = o.g + m * o.ldg;
+  const int64_t abase = ma * o.lda;
+  const float *grow = o.g + mg * o.ldg;
   float *obase = o.out + m * per_m;
+  if (!live) {
+    for (int64_t e = e_begin + threadIdx.x; e < e_end; e += THREADS) obase[e] = 0.f;
+    return;
+  }
   for (int64_t e = e_begin + threadIdx.x; e < e_end; e += THREADS) {
     const uint32_t i = (uint32_t)e / (uint32_t)o.d_out;     // per_m < 2^31 is checked by the host
     const uint32_t j = (uint32_t)e - i * (uint32_t)o.d_out;
@@ -117,7 +130,11 @@ __device__ __forceinline__ void outer_flat(const OuterJob &jb, uint32_t chunk, i
 // blockIdx.x selects the job and the piece of one iteration, blockIdx.y/z the iteration m.  The
 // ramp-up and tail of a streaming kernel are then paid once and small layers fill in between
 // large ones.
-template <int THREADS>
+// SUBSET: the jobs' iterations are the entries of a device-side list (OuterArgs::sub, sub_rows):
+// grid index m is a position in the list, the slice written is that of row sub_rows[m], and
+// positions outside the job's set {offset .. offset + count - 1} get zeros.  Kept in an
+// instantiation of its own: the plain kernel carries none of these loads.
+template <int THREADS, bool SUBSET>
 __global__ __launch_bounds__(THREADS) void outer_product_kernel(const OuterBatch batch) {
   const int64_t m = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
   if (m >= batch.M) return;
@@ -127,10 +144,23 @@ __global__ __launch_bounds__(THREADS) void outer_product_kernel(const OuterBatch
   for (int t = 1; t < kMaxJobs; ++t)
     if (t < batch.n && x >= batch.job[t].x_begin) j = t;
   const OuterJob &jb = batch.job[j];
+  int64_t mo = m, ma, mg = m;
+  bool live = true;
+  if (SUBSET) {
+    const OuterArgs &o = jb.o;
+    const int count = o.sub[0], off = o.sub[1];
+    const int64_t p = m - off;                   // position inside the job's set
+    live = p >= 0 && p < count;
+    mo = o.sub_rows[m];
+    ma = o.a_gather ? mo : p;
+    mg = o.g_gather ? mo : p;
+  } else {
+    ma = jb.o.S == 1 ? m : (int64_t)((uint32_t)m / (uint32_t)jb.o.S);
+  }
   if (jb.vec)
-    outer_vec4<THREADS>(jb, x - jb.x_begin, m);
+    outer_vec4<THREADS>(jb, x - jb.x_begin, mo, ma, mg, live);
   else
-    outer_flat<THREADS>(jb, x - jb.x_begin, m);
+    outer_flat<THREADS>(jb, x - jb.x_begin, mo, ma, mg, live);
 }
 
 // Wide rows of a large output (d_out >= 1024, at least kWideBytes in all): a kernel of its own with
@@ -158,6 +188,7 @@ __global__ __launch_bounds__(kThreads) void outer_wide_kernel(const void *__rest
 }
 
 bool wide_applies(const OuterArgs &o) {
+  if (o.sub) return false;
   if (o.d_out % 4 || o.d_out < 4 * kThreads || o.M > 65535 || o.d_in > 65535) return false;
   if ((reinterpret_cast<uintptr_t>(o.out) | reinterpret_cast<uintptr_t>(o.g)) & 15) return false;
   if (o.ldg & 3) return false;
@@ -208,7 +239,7 @@ int64_t plan_job(const OuterArgs &o, OuterJob &jb, int64_t target) {
 }
 
 // One launch per group of jobs with the same iteration count (normally all of them).
-hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, int64_t target, hipStream_t stream) {
+hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, bool subset, int64_t target, hipStream_t stream) {
   int at = 0;
   while (at < n) {
     OuterBatch batch{};
@@ -216,7 +247,7 @@ hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, int64_t target,
     int64_t xs = 0;
     while (at < n && batch.n < kMaxJobs) {
       const OuterArgs &o = jobs[at++];
-      if (o.M != M || o.d_in <= 0 || o.d_out <= 0) continue;
+      if (o.M != M || (o.sub != nullptr) != subset || o.d_in <= 0 || o.d_out <= 0) continue;
       OuterJob &jb = batch.job[batch.n];
       const int64_t nx = plan_job(o, jb, target);
       if (xs + nx > 0x7fffffffLL) {
@@ -233,7 +264,10 @@ hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, int64_t target,
     const unsigned gz = (unsigned)((M + gy - 1) / gy);
     if (gz > 65535) return hipErrorInvalidConfiguration;
     const dim3 grid((unsigned)xs, gy, gz);
-    PFG_KERNEL(outer_product_kernel<kThreads>, grid, dim3(kThreads), 0, stream, batch);
+    if (subset)
+      PFG_KERNEL((outer_product_kernel<kThreads, true>), grid, dim3(kThreads), 0, stream, batch);
+    else
+      PFG_KERNEL((outer_product_kernel<kThreads, false>), grid, dim3(kThreads), 0, stream, batch);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -292,10 +326,12 @@ hipError_t launch_outer(const OuterArgs *jobs, int n, hipStream_t stream) {
   for (int i = 0; i < n; ++i) {
     if (jobs[i].M <= 0) continue;
     if ((int64_t)jobs[i].d_in * jobs[i].d_out > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const bool subset = jobs[i].sub != nullptr;
+    if (subset && (!jobs[i].sub_rows || jobs[i].S != 1)) return hipErrorInvalidValue;
     bool seen = false;
-    for (int k = 0; k < i; ++k) seen = seen || (jobs[k].M == jobs[i].M);
+    for (int k = 0; k < i; ++k) seen = seen || (jobs[k].M == jobs[i].M && (jobs[k].sub != nullptr) == subset);
     if (seen) continue;
-    hipError_t e = launch_class(jobs, n, jobs[i].M, target, stream);
+    hipError_t e = launch_class(jobs, n, jobs[i].M, subset, target, stream);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

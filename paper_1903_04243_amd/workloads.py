@@ -319,12 +319,16 @@ class CondWorkload:
     act: str
     n: int
     c0: float = 0.0              # offset of the condition
+    call: str = "cond_forward"   # or "cond_per_example_grads"
 
 
 COND_WORKLOADS: Dict[str, CondWorkload] = {
     w.name: w for w in [
         # the offset puts about half of the rows on each side of the condition
         CondWorkload("c11_cond_two_branches", 10, (784, 512), (1024, 1024, 10), (10,), "relu", 8192, -0.55),
+        # per-example gradients through the same conditional (8.0 GB of gradients at 1024 rows)
+        CondWorkload("c13_cond_grads", 10, (784, 512), (1024, 1024, 10), (10,), "relu", 1024, -0.55,
+                     "cond_per_example_grads"),
     ]
 }
 
@@ -421,12 +425,14 @@ def make_integer_conv_inputs(height: int, width: int, channels: int, blocks, den
 
 
 def make_integer_cond_inputs(pre, then_dims, else_dims, n: int, seed: int, density: float = 0.25,
-                             c0: float = 0.0) -> CondInputs:
-    """Integer-valued shared part, condition vector and branches: many rows have a score of exactly 0."""
+                             c0: float = 0.0, branch_last_scale: float = 1.0) -> CondInputs:
+    """Integer-valued shared part, condition vector and branches: many rows have a score of exactly 0.
+    branch_last_scale (a power of two) scales the last layer of both branches."""
     pre, then_dims, else_dims = tuple(pre), tuple(then_dims), tuple(else_dims)
     rng = np.random.Generator(np.random.Philox(seed))
-    nets = [draw_integer_weights(rng, dims, density, 1.0)
-            for dims in (pre, (pre[-1],) + then_dims, (pre[-1],) + else_dims)]
+    nets = [draw_integer_weights(rng, dims, density, scale)
+            for dims, scale in ((pre, 1.0), ((pre[-1],) + then_dims, branch_last_scale),
+                                ((pre[-1],) + else_dims, branch_last_scale))]
     wv = _sparse_ints(rng, (pre[-1],), 0.5, -1, 1)
     X = rng.integers(-2, 3, size=(n, pre[0])).astype(np.float32)
     w = CondWorkload("integer", 0, pre, then_dims, else_dims, "relu", n, c0)
