@@ -702,14 +702,17 @@ def main():
 
     if args.fill_reference:
         # what the device's memory absorbs from the plainest write stream, at the output sizes of the
-        # measured workloads: the library's sequential fill (16-byte non-temporal stores, 8 KiB per
-        # workgroup), torch's fill_ and torch's zero_ (a memset)
+        # measured workloads: the library's sequential fill (16-byte non-temporal stores; 4, 8, 16 and
+        # 64 KiB per workgroup), torch's fill_ and torch's zero_ (a memset)
         rows = []
         for nbytes in (85 << 20, 268435456, 342360064, 1 << 30, 1681915904, 8 << 30, 34401681408):
             buf = torch.empty(nbytes // 4, dtype=torch.float32, device=dev)
             reps = max(3, min(args.steps, int(2e11 // nbytes)))
             rec = {"bytes": nbytes, "launches": reps}
-            for name, fn in (("pfg_fill_reference", lambda: pfg.pfg_fill_reference(buf, 1.0)),
+            for name, fn in (("pfg_fill_4KiB_per_wg", lambda: pfg.pfg_fill_reference(buf, 1.0, 1)),
+                             ("pfg_fill_8KiB_per_wg", lambda: pfg.pfg_fill_reference(buf, 1.0, 2)),
+                             ("pfg_fill_16KiB_per_wg", lambda: pfg.pfg_fill_reference(buf, 1.0, 4)),
+                             ("pfg_fill_64KiB_per_wg", lambda: pfg.pfg_fill_reference(buf, 1.0, 16)),
                              ("torch_fill_", lambda: buf.fill_(1.0)), ("torch_zero_", lambda: buf.zero_())):
                 for _ in range(2):
                     fn()

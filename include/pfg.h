@@ -436,11 +436,12 @@ int pfg_timing_reset(void);
 int pfg_timing_query(const char *name, int64_t *launches, double *total_ms);
 int pfg_timing_names(char *buf, size_t cap);
 
-/* Measurement aid: out[0 .. n) = value, written as the plainest possible stream (one 16-byte
- * non-temporal store per lane and store, workgroups of 8 KiB in address order), to find the rate
- * at which the device's memory absorbs writes; the outer-product kernels are priced against it.
- *   out  DEVICE, 16-byte aligned;  n a multiple of 4 */
-int pfg_fill_reference(float *out, int64_t n, float value, void *hip_stream);
+/* Measurement aid: out[0 .. n) = value, written as the plainest possible stream (16-byte
+ * non-temporal stores, workgroups of 256 lanes in address order), to find the rate at which the
+ * device's memory absorbs writes; the outer-product kernels are priced against it.
+ *   out              DEVICE, 16-byte aligned;  n a multiple of 4
+ *   stores_per_lane  1, 2, 4, 8 or 16: a workgroup writes that many times 4 KiB */
+int pfg_fill_reference(float *out, int64_t n, float value, int stores_per_lane, void *hip_stream);
 
 /* Library version, major * 100 + minor. */
 int pfg_version(void);

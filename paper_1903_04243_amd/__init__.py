@@ -146,7 +146,7 @@ def load_library() -> ctypes.CDLL:
         condp = ctypes.POINTER(pfg_cond)
         lib.pfg_cond_workspace_bytes.argtypes = [condp, i64, ctypes.POINTER(ctypes.c_size_t)]
         lib.pfg_cond_forward.argtypes = [condp, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
-        lib.pfg_fill_reference.argtypes = [vp, i64, ctypes.c_float, vp]
+        lib.pfg_fill_reference.argtypes = [vp, i64, ctypes.c_float, i32, vp]
         pvp = ctypes.POINTER(vp)
         lib.pfg_cond_grads_workspace_bytes.argtypes = [condp, i64, ctypes.POINTER(ctypes.c_size_t)]
         lib.pfg_cond_per_example_grads.argtypes = [condp, vp, vp, i64, i32, pvp, pvp, pvp, pvp, pvp, pvp, vp, vp, vp,
@@ -796,12 +796,14 @@ def pfg_cond_per_example_grads(net: Cond, X, labels, invariant_cond: int = PFG_C
     return out
 
 
-def pfg_fill_reference(out, value: float = 0.0) -> None:
-    """Fill a contiguous float32 GPU tensor with the library's plain sequential store stream."""
+def pfg_fill_reference(out, value: float = 0.0, stores_per_lane: int = 1) -> None:
+    """Fill a contiguous float32 GPU tensor with the library's plain sequential store stream
+    (stores_per_lane times 4 KiB per workgroup)."""
     import torch
     if out.dtype != torch.float32 or not out.is_contiguous() or not out.is_cuda:
         raise ValueError("out must be a contiguous float32 GPU tensor")
-    _check(load_library().pfg_fill_reference(out.data_ptr(), out.numel(), float(value), _stream_ptr()))
+    _check(load_library().pfg_fill_reference(out.data_ptr(), out.numel(), float(value), int(stores_per_lane),
+                                              _stream_ptr()))
 
 
 def pfg_timing_enable(on: bool) -> None:

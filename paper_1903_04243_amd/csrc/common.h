@@ -175,8 +175,9 @@ struct OuterArgs {
 // Enqueues the n outer products in as few launches as possible (normally one).
 hipError_t launch_outer(const OuterArgs *jobs, int n, hipStream_t stream);
 
-// out[0 .. n) = value as a plain sequential stream of 16-byte non-temporal stores (measurement aid)
-hipError_t launch_fill_reference(float *out, int64_t n, float value, hipStream_t stream);
+// out[0 .. n) = value as a plain sequential stream of 16-byte non-temporal stores, stores_per_lane
+// (1, 2, 4, 8 or 16) of them per lane, i.e. that many times 4 KiB per workgroup (measurement aid)
+hipError_t launch_fill_reference(float *out, int64_t n, float value, int stores_per_lane, hipStream_t stream);
 
 // delta[b, :] = softmax(y[b, :]) - onehot(labels[b]);  loss[b] = -log softmax(y[b])[labels[b]]
 hipError_t launch_head_softmax_ce(const float *y, const int32_t *labels, int64_t B, int32_t n,
@@ -219,6 +220,14 @@ hipError_t launch_gemm_split(const GemmArgs &g, int Z, float *partials, hipStrea
 int head_split_shape(int64_t M, int64_t N, int64_t K);
 int head_split_pieces(const GemmArgs &g);
 hipError_t launch_head_split(const GemmArgs &g, int Z, float *partials, hipStream_t stream);
+
+// The loss head of a narrow float32 network on few rows (N <= 16 outputs, K <= 1024 inputs, at most
+// 2048 rows), one workgroup per example.  g as for EPI_HEAD with C == nullptr.  mode 0: softmax
+// cross-entropy (C2 = delta, loss, optional head_gprev / head_mask cotangent step).  mode 1: the N
+// rows of the softmax Jacobian per example, C2 [M * N, ldc] (optional), and their pull-back through
+// the layer, head_gprev [M * N, K] (optional, needs head_mask [M, K]).
+bool head_rows_applies(const GemmArgs &g);
+hipError_t launch_head_rows(const GemmArgs &g, int mode, hipStream_t stream);
 
 // Squared gradient norms of the parameter blocks of a launch (at most kNormLayers per launch):
 //   sq[b * ld_sq + index] = (|a[b, :]|^2 + (has_bias ? 1 : 0)) * |g[b, :]|^2       a dense layer

@@ -306,7 +306,9 @@ int forward(const pfg_mlp *net, const void *X, int64_t B, int upto, void *ws, co
     }
     const int Z = p.splitk ? split_k_factor(g) : 1;
     const int Zh = (p.head_part && g.epilogue == EPI_HEAD) ? head_split_pieces(g) : 1;
-    if (Zh > 1)
+    if (g.epilogue == EPI_HEAD && head_rows_applies(g))
+      PFG_LAUNCH("gemm_forward", launch_head_rows(g, 0, stream));
+    else if (Zh > 1)
       PFG_LAUNCH("gemm_forward", launch_head_split(g, Zh, at(ws, p.head_part), stream));
     else if (Z > 1)
       PFG_LAUNCH("gemm_forward", launch_gemm_split(g, Z, at(ws, p.splitk), stream));
@@ -511,12 +513,16 @@ int pfg_timing_names(char *buf, size_t cap) {
   return PFG_OK;
 }
 
-int pfg_fill_reference(float *out, int64_t n, float value, void *hip_stream) {
+int pfg_fill_reference(float *out, int64_t n, float value, int stores_per_lane, void *hip_stream) {
   g_err[0] = 0;
   if (!out) return fail(PFG_ERR_NULL, "out is NULL");
   if (n < 0 || (n & 3)) return fail(PFG_ERR_SHAPE, "n = %lld must be a non-negative multiple of 4", (long long)n);
   if (reinterpret_cast<uintptr_t>(out) & 15) return fail(PFG_ERR_SHAPE, "out is not 16-byte aligned");
-  PFG_LAUNCH("fill_reference", launch_fill_reference(out, n, value, static_cast<hipStream_t>(hip_stream)));
+  if (stores_per_lane != 1 && stores_per_lane != 2 && stores_per_lane != 4 && stores_per_lane != 8 &&
+      stores_per_lane != 16)
+    return fail(PFG_ERR_UNSUPPORTED, "stores_per_lane = %d is none of 1, 2, 4, 8, 16", stores_per_lane);
+  PFG_LAUNCH("fill_reference",
+             launch_fill_reference(out, n, value, stores_per_lane, static_cast<hipStream_t>(hip_stream)));
   return PFG_OK;
 }
 
@@ -1268,12 +1274,30 @@ int pfg_jacobian_weights(const pfg_mlp *net, const void *X, int64_t B, int head,
   const int L = net->num_layers;
   const int32_t *d = net->dims;
 
-  if ((rc = forward(net, X, B, L, workspace, p, true, stream))) return rc;
-
   std::vector<float *> G(L + 1, nullptr);
   for (int l = 1; l <= L; ++l)
     G[l] = (Jb_out && Jb_out[l - 1]) ? Jb_out[l - 1] : at(workspace, p.G[l]);
 
+  // The rows of the softmax Jacobian of a narrow network: last layer, softmax, seed rows and the
+  // cotangent step through the last layer in one launch, one workgroup per example.
+  if (head == PFG_HEAD_SOFTMAX && !seeds && L >= 2) {
+    GemmArgs g{};
+    g.A = at(workspace, p.act[L - 1]); g.lda = d[L - 1]; g.a_batch_stride = d[L - 1]; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->W[L - 1]; g.ldw = d[L]; g.w_kn = 1; g.bf16 = (net->dtype == PFG_BF16);
+    g.M = (int32_t)B; g.N = d[L]; g.K = d[L - 1];
+    g.bias = bias_of(net, L); g.epilogue = EPI_HEAD;
+    g.C2 = G[L]; g.ldc = d[L];
+    const bool lower = lowest_requested(net, JW_out, Jb_out) < L;
+    g.head_gprev = lower ? G[L - 1] : nullptr;
+    g.head_mask = at(workspace, p.dphi[L - 1]);
+    if (head_rows_applies(g)) {
+      if ((rc = forward(net, X, B, L - 1, workspace, p, true, stream))) return rc;
+      PFG_LAUNCH("gemm_forward", launch_head_rows(g, 1, stream));
+      return weight_sweep(net, X, B, S, JW_out, Jb_out, G, workspace, p, stream, lower);
+    }
+  }
+
+  if ((rc = forward(net, X, B, L, workspace, p, true, stream))) return rc;
   PFG_LAUNCH("seed_rows", launch_seed_rows(at(workspace, p.logits), seeds, seed_batch_stride, B, S,
                                            d[L], head, G[L], stream));
   return weight_sweep(net, X, B, S, JW_out, Jb_out, G, workspace, p, stream);

@@ -274,28 +274,40 @@ hipError_t launch_class(const OuterArgs *jobs, int n, int64_t M, bool subset, in
   return hipSuccess;
 }
 
-// The plainest write stream there is, for measuring what HBM absorbs: out[0 .. n) = value with one
-// 16-byte non-temporal store per lane and store, workgroups of 8 KiB in address order (the
-// granularity the outer-product kernel uses).  n is a multiple of 4, out 16-byte aligned.
+// The plainest write stream there is, for measuring what HBM absorbs: out[0 .. n) = value with PER
+// 16-byte non-temporal stores per lane (a workgroup covers PER * 4 KiB of consecutive addresses,
+// lane t writing pieces t, t + 256, ...), workgroups in address order.  n is a multiple of 4, out
+// 16-byte aligned.
+template <int PER>
 __global__ __launch_bounds__(kThreads) void fill_reference_kernel(float *out, int64_t nvec, float value) {
-  const int64_t base = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * (2 * kThreads) + threadIdx.x;
+  const int64_t base = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * (PER * kThreads) + threadIdx.x;
   const f32x4 v = {value, value, value, value};
   f32x4 *o = reinterpret_cast<f32x4 *>(out);
-  if (base < nvec) __builtin_nontemporal_store(v, o + base);
-  if (base + kThreads < nvec) __builtin_nontemporal_store(v, o + base + kThreads);
+#pragma unroll
+  for (int u = 0; u < PER; ++u)
+    if (base + u * kThreads < nvec) __builtin_nontemporal_store(v, o + base + u * kThreads);
 }
 
 }  // namespace
 
-hipError_t launch_fill_reference(float *out, int64_t n, float value, hipStream_t stream) {
+hipError_t launch_fill_reference(float *out, int64_t n, float value, int stores_per_lane, hipStream_t stream) {
   if (n <= 0) return hipSuccess;
   if ((n & 3) || (reinterpret_cast<uintptr_t>(out) & 15)) return hipErrorInvalidValue;
   const int64_t nvec = n / 4;
-  const int64_t groups = (nvec + 2 * kThreads - 1) / (2 * kThreads);
+  const int64_t per = (int64_t)stores_per_lane * kThreads;
+  const int64_t groups = (nvec + per - 1) / per;
   const unsigned gx = (unsigned)(groups < 65535 ? groups : 65535);
   const int64_t gy = (groups + gx - 1) / gx;
-  if (gy > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-  PFG_KERNEL(fill_reference_kernel, dim3(gx, (unsigned)gy), dim3(kThreads), 0, stream, out, nvec, value);
+  if (gy > 65535) return hipErrorInvalidConfiguration;
+  const dim3 grid(gx, (unsigned)gy);
+  switch (stores_per_lane) {
+    case 1: PFG_KERNEL(fill_reference_kernel<1>, grid, dim3(kThreads), 0, stream, out, nvec, value); break;
+    case 2: PFG_KERNEL(fill_reference_kernel<2>, grid, dim3(kThreads), 0, stream, out, nvec, value); break;
+    case 4: PFG_KERNEL(fill_reference_kernel<4>, grid, dim3(kThreads), 0, stream, out, nvec, value); break;
+    case 8: PFG_KERNEL(fill_reference_kernel<8>, grid, dim3(kThreads), 0, stream, out, nvec, value); break;
+    case 16: PFG_KERNEL(fill_reference_kernel<16>, grid, dim3(kThreads), 0, stream, out, nvec, value); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 
