@@ -408,17 +408,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   auto mma_stage = [&](int buf, auto side) {
     const unsigned char *sA = smem + buf * STAGE + (wm + l32) * STRIDE + half * 16;
     const unsigned char *sW = smem + buf * STAGE + BM * STRIDE + (wn + l32) * STRIDE + half * 16;
-#pragma unroll
-    for (int step = 0; step < CPR / 2; ++step) {
-      u32x4 av[TM], wv[TN];
+    // fragments of step s + 1 are requested before the MFMAs of step s (two register sets used
+    // alternately), so that the matrix pipe does not drain while a step's LDS reads are on their way
+    u32x4 fa[2][TM], fw[2][TN];
+    auto read_frag = [&](int step, int set) {
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        av[i] = *reinterpret_cast<const u32x4 *>(sA + i * 32 * STRIDE + step * 32);
+        fa[set][i] = *reinterpret_cast<const u32x4 *>(sA + i * 32 * STRIDE + step * 32);
       if constexpr (WTR) {
-        // Transposing read: in each group of 16 lanes, lane i passes the address of 4 values of
-        // tile row (i / 4) at columns 4 (i % 4) .. +3, and lane j gets back column j of those four
-        // rows.  Two reads (k .. k+3, k+4 .. k+7) give a lane its 8 consecutive k of column
-        // wn + 32 j + lane % 32; lanes 32..63 take the upper 8 k of the 16-wide slab.
         typedef short s16x4 __attribute__((ext_vector_type(4)));
         typedef __attribute__((address_space(3))) s16x4 *lds_s16x4;
         const int i16 = lane & 15;
@@ -432,13 +429,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
               __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(base + j * 64 + 4 * W_STRIDE));
           typedef short s16x8 __attribute__((ext_vector_type(8)));
           const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-          wv[j] = __builtin_bit_cast(u32x4, both);
+          fw[set][j] = __builtin_bit_cast(u32x4, both);
         }
       } else {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          wv[j] = *reinterpret_cast<const u32x4 *>(sW + j * 32 * STRIDE + step * 32);
+          fw[set][j] = *reinterpret_cast<const u32x4 *>(sW + j * 32 * STRIDE + step * 32);
       }
+    };
+    read_frag(0, 0);
+#pragma unroll
+    for (int step = 0; step < CPR / 2; ++step) {
+      if (step + 1 < CPR / 2) read_frag(step + 1, (step + 1) & 1);
+      u32x4 av[TM], wv[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) av[i] = fa[step & 1][i];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) wv[j] = fw[step & 1][j];
       if constexpr (BF16) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
