@@ -41,6 +41,8 @@ def main():
                     help="run a plain elementwise copy of known size (scale for HBM counters)")
     ap.add_argument("--fill-reference", action="store_true",
                     help="measure plain sequential fills of several sizes (the practical HBM write ceiling)")
+    ap.add_argument("--launch-floor", action="store_true",
+                    help="measure the cost per launch of a chain of dependent near-empty kernels")
     ap.add_argument("--workload", default=None,
                     help="measure only this workload and print its record (for profiling runs)")
     ap.add_argument("--batch", type=int, default=None,
@@ -747,6 +749,29 @@ def main():
             del buf
             torch.cuda.empty_cache()
         print(json.dumps({"fill_reference": rows, "hbm_peak_GBps": HBM_PEAK_GBS}), flush=True)
+        return
+
+    if args.launch_floor:
+        # what a chain of dependent launches costs when the kernels do next to nothing: the library's
+        # fill kernel on 4 KiB (one workgroup), launched back to back on one stream, eagerly and
+        # replayed from a graph; and the same with one workgroup per compute unit (256 x 4 KiB)
+        rows = []
+        for nfloats in (1024, 256 * 1024):
+            buf = torch.empty(nfloats, dtype=torch.float32, device=dev)
+            chain = 100
+            one = lambda: pfg.pfg_fill_reference(buf, 1.0, 1)
+            def step():
+                for _ in range(chain):
+                    one()
+            sec = timed(step, max(20, args.steps), 5)
+            sec_graph = timed_graph(step, max(20, args.steps), 5)
+            kt = kernel_times(step, 20)["fill_reference"]
+            rows.append({"bytes_per_launch": 4 * nfloats, "chain": chain, "us_per_launch_eager": sec / chain * 1e6,
+                         "us_per_launch_graph": sec_graph / chain * 1e6,
+                         "kernel_us": kt["ms_per_step"] / kt["launches_per_step"] * 1e3})
+            log(f"[bench] launch floor, {4 * nfloats} B per launch: {rows[-1]['us_per_launch_eager']:.2f} us eager, "
+                f"{rows[-1]['us_per_launch_graph']:.2f} us from a graph, kernel itself {rows[-1]['kernel_us']:.2f} us")
+        print(json.dumps({"launch_floor": rows}), flush=True)
         return
 
     if args.workload:
