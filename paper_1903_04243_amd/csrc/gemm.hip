@@ -337,8 +337,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
   };
 
   // Registers of chunk c, fetched for stage kt, go to LDS buffer buf (FAST loads are zeroed
-  // here, not when issued).
-  auto stash_a_chunk = [&](int c, int buf, int kt, bool sc) {
+  // here, not when issued).  edge: may stage kt reach past the end of the contraction (only the last
+  // stage can; the steady state of the pipeline passes a literal false and carries no selects).
+  auto stash_a_chunk = [&](int c, int buf, int kt, bool sc, bool edge = true) {
     unsigned char *sA = smem + buf * STAGE;
     if constexpr (GATHER && !AKM) {
       *reinterpret_cast<u32x4 *>(sA + a_lds[c]) =
@@ -346,20 +347,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
       return;
     }
     if constexpr (AKM) {
-      const bool past = GATHER ? !a_live[c] : (kt * BK + a_k[c] >= K) || (a_m[c] >= M);
+      const bool past = GATHER ? !a_live[c] : (edge && kt * BK + a_k[c] >= K) || (a_m[c] >= M);
       const u32x4 v = past ? u32x4{0u, 0u, 0u, 0u} : __builtin_bit_cast(u32x4, ra[c].v);
 #pragma unroll
       for (int e = 0; e < 4; ++e) *reinterpret_cast<uint32_t *>(sA + a_lds[c] + e * STRIDE) = v[e];
     } else {
       *reinterpret_cast<u32x4 *>(sA + a_lds[c]) =
-          finish_a<AMODE>(ra[c], sc, FAST && (kt * BK + a_k[c] >= K));
+          finish_a<AMODE>(ra[c], sc, FAST && edge && (kt * BK + a_k[c] >= K));
     }
   };
-  auto stash_w_chunk = [&](int c, int buf, int kt) {
+  auto stash_w_chunk = [&](int c, int buf, int kt, bool edge = true) {
     unsigned char *sW = smem + buf * STAGE + BM * STRIDE;
     const int kbase = kt * BK;
     if constexpr (FAST) {
-      const bool past = WKN ? (kbase + w_k[c] >= K || w_n[c] >= N) : (kbase + w_k[c] >= K);
+      const bool past_k = edge && kbase + w_k[c] >= K;
+      const bool past = WKN ? (past_k || w_n[c] >= N) : past_k;
       if (past) rw[c] = u32x4{0u, 0u, 0u, 0u};
     }
     if constexpr (!WKN || WTR) {
@@ -486,11 +488,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
     // stand-alone loop of the same shape: 130 -> 140 TFLOP/s).
     constexpr int P = A_CHUNKS + W_CHUNKS;                    // pieces to write, then to fetch
     constexpr int PER_SLOT = (2 * P + SLOTS - 1) / SLOTS;
-    auto piece = [&](int q, int kt, bool do_stash, bool do_fetch, bool sc) {
+    auto piece = [&](int q, int kt, bool do_stash, bool do_fetch, bool sc, bool edge) {
       if (q < P) {
         if (do_stash) {
-          if (q < A_CHUNKS) stash_a_chunk(q, (kt + 1) & 1, kt + 1, sc);
-          else stash_w_chunk(q - A_CHUNKS, (kt + 1) & 1, kt + 1);
+          if (q < A_CHUNKS) stash_a_chunk(q, (kt + 1) & 1, kt + 1, sc, edge);
+          else stash_w_chunk(q - A_CHUNKS, (kt + 1) & 1, kt + 1, edge);
         }
       } else if (q < 2 * P) {
         if (do_fetch) {
@@ -499,32 +501,34 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs g) 
         }
       }
     };
-    auto run_stage = [&](int kt, bool do_stash, bool do_fetch, bool sc) {
+    auto run_stage = [&](int kt, bool do_stash, bool do_fetch, bool sc, bool edge) {
       mma_stage(kt & 1, [&](int slot) {
 #pragma unroll
-        for (int u = 0; u < PER_SLOT; ++u) piece(slot * PER_SLOT + u, kt, do_stash, do_fetch, sc);
+        for (int u = 0; u < PER_SLOT; ++u) piece(slot * PER_SLOT + u, kt, do_stash, do_fetch, sc, edge);
         __builtin_amdgcn_sched_barrier(0);
       });
     };
     if (nk > 1) fetch(1);
     int kt = 0;
     if (scaled) {                    // branch once, outside the loop
-      for (; kt + 2 < nk; ++kt) {    // steady state: no conditions inside
-        run_stage(kt, true, true, true);
+      // steady state: no conditions inside; the stage written to LDS here (kt + 1 <= nk - 2) is never
+      // the last one, so its chunks all lie inside the contraction
+      for (; kt + 2 < nk; ++kt) {
+        run_stage(kt, true, true, true, false);
         __syncthreads();
       }
     } else {
       for (; kt + 2 < nk; ++kt) {
-        run_stage(kt, true, true, false);
+        run_stage(kt, true, true, false, false);
         __syncthreads();
       }
     }
     if (kt + 1 < nk) {
-      run_stage(kt, true, false, scaled);
+      run_stage(kt, true, false, scaled, true);
       __syncthreads();
       ++kt;
     }
-    run_stage(kt, false, false, scaled);
+    run_stage(kt, false, false, scaled, true);
   } else {
     // The last stage is peeled off so that the loop body has no conditional loads.
     for (int kt = 0; kt + 1 < nk; ++kt) {
