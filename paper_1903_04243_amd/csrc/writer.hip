@@ -187,8 +187,32 @@ __global__ __launch_bounds__(kThreads) void outer_wide_kernel(const void *__rest
   __builtin_nontemporal_store(gv * av, o);
 }
 
+// The same for iterations taken from a device-side list (float32 a, no seed axis): grid index z is a
+// position in the list, the slice written is that of row sub_rows[z]; a position outside the job's set
+// {offset .. offset + count - 1} gets zeros.  The list entry and the two descriptor words are
+// wave-uniform loads.
+__global__ __launch_bounds__(kThreads) void outer_wide_subset_kernel(const float *__restrict__ a, int64_t lda,
+                                                                     const float *__restrict__ g, int64_t ldg,
+                                                                     float *__restrict__ out, int d_in, int V,
+                                                                     const int32_t *__restrict__ sub,
+                                                                     const int32_t *__restrict__ sub_rows,
+                                                                     int a_gather, int g_gather) {
+  const int vc = blockIdx.x * kThreads + threadIdx.x;
+  const uint32_t i = blockIdx.y;
+  const int m = blockIdx.z;
+  if (vc >= V) return;
+  const int p = m - sub[1];
+  const int64_t mo = sub_rows[m];
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (p >= 0 && p < sub[0]) {
+    const int64_t ma = a_gather ? mo : p, mg = g_gather ? mo : p;
+    v = *reinterpret_cast<const f32x4 *>(g + mg * ldg + 4 * vc) * a[ma * lda + i];
+  }
+  __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(out) + (mo * d_in + i) * (int64_t)V + vc);
+}
+
 bool wide_applies(const OuterArgs &o) {
-  if (o.sub) return false;
+  if (o.sub && (!o.sub_rows || o.a_bf16 || o.S != 1)) return false;
   if (o.d_out % 4 || o.d_out < 4 * kThreads || o.M > 65535 || o.d_in > 65535) return false;
   if ((reinterpret_cast<uintptr_t>(o.out) | reinterpret_cast<uintptr_t>(o.g)) & 15) return false;
   if (o.ldg & 3) return false;
@@ -198,6 +222,11 @@ bool wide_applies(const OuterArgs &o) {
 hipError_t launch_wide(const OuterArgs &o, hipStream_t stream) {
   const int V = o.d_out / 4;
   const dim3 grid((unsigned)((V + kThreads - 1) / kThreads), (unsigned)o.d_in, (unsigned)o.M);
+  if (o.sub) {
+    PFG_KERNEL(outer_wide_subset_kernel, grid, dim3(kThreads), 0, stream, static_cast<const float *>(o.a), o.lda, o.g,
+               o.ldg, o.out, o.d_in, V, o.sub, o.sub_rows, o.a_gather, o.g_gather);
+    return hipGetLastError();
+  }
 #define PFG_WIDE(BF, SD)                                                                              \
   PFG_KERNEL((outer_wide_kernel<BF, SD>), grid, dim3(kThreads), 0, stream, o.a, o.lda, o.g, o.ldg, o.out, \
              o.d_in, V, o.S)
@@ -321,20 +350,24 @@ hipError_t launch_outer(const OuterArgs *jobs, int n, hipStream_t stream) {
   // index prologue dominates.
   const int64_t target = 8192;
   // large outputs with wide rows leave in launches of their own (see outer_wide_kernel)
-  std::vector<OuterArgs> rest;
-  rest.reserve(n);
+  constexpr int kInline = 32;                  // no host allocation for the usual few jobs
+  OuterArgs rest_inline[kInline];
+  std::vector<OuterArgs> rest_heap;
+  if (n > kInline) rest_heap.resize(n);
+  OuterArgs *rest = n > kInline ? rest_heap.data() : rest_inline;
+  int nrest = 0;
   for (int i = 0; i < n; ++i) {
     if (jobs[i].M > 0 && jobs[i].d_in > 0 && wide_applies(jobs[i])) {
       set_timing_family("outer_product_wide");
       hipError_t e = launch_wide(jobs[i], stream);
       if (e != hipSuccess) return e;
     } else {
-      rest.push_back(jobs[i]);
+      rest[nrest++] = jobs[i];
     }
   }
   set_timing_family("outer_product");
-  jobs = rest.data();
-  n = (int)rest.size();
+  jobs = rest;
+  n = nrest;
   for (int i = 0; i < n; ++i) {
     if (jobs[i].M <= 0) continue;
     if ((int64_t)jobs[i].d_in * jobs[i].d_out > 0x7fffffffLL) return hipErrorInvalidConfiguration;

@@ -193,3 +193,65 @@ def test_cond_grads_skipped_outputs_and_errors():
     with pytest.raises(pfg.PfgError) as ei:
         pfg.pfg_cond_per_example_grads(net, X, lab, invariant_cond=2)
     assert ei.value.code == pfg.PFG_ERR_UNSUPPORTED
+
+
+def test_c13_full_size_in_the_benchmark_configuration():
+    """c13 as `bench.py` times it (1024 rows, 8.15 GB of gradients; the two large layers of the then
+    branch leave through the list-driven wide writer): 40 rows spread over the batch against the oracle,
+    element by element; every row: exact zeros in the slices of the branch it did not take, and
+    agreement with the library's own result on chunks of 16 rows (small launches through the general
+    writer, which the tests above hold against the oracle)."""
+    w = wl.COND_WORKLOADS["c13_cond_grads"]
+    ci = wl.make_cond_inputs(w)
+    n = w.n
+    labels = np.random.Generator(np.random.Philox(wl.BASE_SEED + w.index + 900000)).integers(
+        0, w.then_dims[-1], size=n).astype(np.int32)
+    mk = lambda pair: oracle.Net(pair[0], pair[1], w.act)
+    onet = ocond.Cond(mk(ci.pre), ci.w, ci.c0, mk(ci.then_net), mk(ci.else_net))
+    net = pfg.Cond.from_numpy(ci.pre, ci.w, ci.c0, ci.then_net, ci.else_net, w.act)
+    X, lab = dev(ci.X), dev(labels)
+    say(f"c13 full size: n={n}")
+    out = pfg.pfg_cond_per_example_grads(net, X, lab, out=nan_outputs(net, n))
+    torch.cuda.synchronize()
+    flags = out["cond"].cpu().numpy()
+    scores = np.array([ocond.score(onet, x) for x in ci.X])
+    sure = np.abs(scores) >= MARGIN
+    assert sure.mean() > 0.95
+    assert np.array_equal(flags[sure], (scores > 0)[sure].astype(flags.dtype))
+    assert out["counts"].tolist() == [int(flags.sum()), n - int(flags.sum())]
+    assert 0.3 * n < flags.sum() < 0.7 * n
+    # (1) sampled rows against the oracle
+    rows = np.unique(np.concatenate([np.arange(8), np.arange(n - 8, n), np.linspace(8, n - 9, 24).astype(int)]))
+    rows = rows[sure[rows]]
+    ref = ocond.per_example_grads(onet, ci.X[rows], labels[rows])
+    worst = 0.0
+    for name in ("pre", "then", "else"):
+        for kind in (0, 1):
+            for g, r in zip(out[name][kind], ref[name][kind]):
+                worst = max(worst, slice_rel_err(g[torch.from_numpy(rows).to(g.device)].cpu().numpy(), r))
+    worst = max(worst, slice_rel_err(out["loss"].cpu().numpy()[rows], ref["loss"], lead=0))
+    say(f"  {len(rows)} rows against the oracle: max rel err {worst:.3e}")
+    assert worst <= TOL_F32
+    # (2) every row: written in full, zeros outside its branch
+    ft = torch.from_numpy(flags).to("cuda:0")
+    for name in ("pre", "then", "else"):
+        for kind in (0, 1):
+            for g in out[name][kind]:
+                assert bool(torch.isfinite(g).all()), f"{name}: not written in full"
+                if name != "pre":
+                    outside = ft == (0 if name == "then" else 1)
+                    assert not bool(g[outside].any()), f"{name}: non-zero gradient for an iteration of the other set"
+    # (3) every row against the library's own result on 16 rows at a time
+    worst = 0.0
+    for lo in range(0, n, 16):
+        part = pfg.pfg_cond_per_example_grads(net, X[lo:lo + 16], lab[lo:lo + 16])
+        for name in ("pre", "then", "else"):
+            for kind in (0, 1):
+                for g, q in zip(out[name][kind], part[name][kind]):
+                    a, b = g[lo:lo + 16].reshape(16, -1), q.reshape(16, -1)
+                    scale = b.abs().amax(dim=1).clamp_min(1e-30)
+                    worst = max(worst, float(((a - b).abs().amax(dim=1) / scale).max()))
+        assert torch.equal(part["cond"], out["cond"][lo:lo + 16])
+    torch.cuda.synchronize()
+    say(f"  all rows against calls of 16 rows: max rel err {worst:.3e}")
+    assert worst <= TOL_F32
