@@ -426,3 +426,146 @@ void lstmo_while_forward(const lstmo_net *net, const double *X, const int64_t *o
                              halt_w, halt_c, h_out ? h_out + (size_t)i * net->H : NULL,
                              y_out ? y_out + (size_t)i * net->dy : NULL, steps_out ? steps_out + i : NULL);
 }
+
+/* -------------------------------------------------------------------------------------
+ * Per-example gradients (Section 5.3) of a body that holds the while loop above (Section 3.7):
+ *   body(i): run the loop of lstmo_body_while_forward on the iteration's own tokens (T_i trips),
+ *            y = h W_out + b_out,  ell = -log softmax(y)[label],
+ *            gradient of ell with respect to W, b, W_out, b_out.
+ * The loop condition is a comparison: it has no derivative, and where the score is not exactly on
+ * its threshold the number of trips T_i does not change under a small change of the parameters.
+ * The gradient is therefore that of the T_i cell applications the loop made, taken in reverse:
+ *   dW_out = outer(h, gy), db_out = gy with gy = softmax(y) - onehot;  dh = W_out gy, dc = 0
+ *   for t = T_i - 1 .. 0, with tc = tanh(c_t):
+ *      dc   += dh * o * (1 - tc^2)
+ *      dz_o  = dh * tc * o (1 - o),  dz_i = dc * g * i (1 - i),  dz_g = dc * i (1 - g^2),
+ *      dz_f  = dc * c_{t-1} * f (1 - f)
+ *      dW   += outer([x_t, h_{t-1}], dz),  db += dz;   dh = dz W_h^T,  dc = dc * f
+ * With T_i = 0 the state is zero: dW = 0, db = 0, dW_out = 0, db_out = gy, ell from y = b_out.
+ * Any output may be NULL.
+ * ------------------------------------------------------------------------------------- */
+void lstmo_body_while_grads(const lstmo_net *net, const double *x, int64_t len, int64_t max_steps,
+                            const double *halt_w, double halt_c, int label, double *dW, double *db,
+                            double *dWout, double *dbout, double *loss, int64_t *steps_out) {
+  const int dx = net->dx, H = net->H, dy = net->dy, G = 4 * net->H;
+  int64_t cap = len < max_steps ? len : max_steps;
+  if (cap < 0) cap = 0;
+  /* what the trips leave behind for the reverse sweep; row t belongs to trip t */
+  double *gi = (double *)malloc(sizeof(double) * (size_t)(cap + 1) * H);
+  double *gg = (double *)malloc(sizeof(double) * (size_t)(cap + 1) * H);
+  double *gf = (double *)malloc(sizeof(double) * (size_t)(cap + 1) * H);
+  double *go = (double *)malloc(sizeof(double) * (size_t)(cap + 1) * H);
+  double *cs = (double *)malloc(sizeof(double) * (size_t)(cap + 1) * H);
+  double *hs = (double *)malloc(sizeof(double) * (size_t)(cap + 1) * H);
+  double *h = (double *)calloc((size_t)H, sizeof(double));
+  double *c = (double *)calloc((size_t)H, sizeof(double));
+  double *z = (double *)malloc(sizeof(double) * (size_t)G);
+  int64_t t = 0;
+  for (;;) {
+    double score = halt_c;
+    if (halt_w)
+      for (int k = 0; k < H; ++k) score += h[k] * halt_w[k];
+    if (!(t < len && t < max_steps && score <= 0.0)) break;
+    const double *xt = x + (size_t)t * dx;
+    for (int col = 0; col < G; ++col) {
+      double s = net->b ? net->b[col] : 0.0;
+      for (int r = 0; r < dx; ++r) s += xt[r] * net->W[(size_t)r * G + col];
+      for (int r = 0; r < H; ++r) s += h[r] * net->W[(size_t)(dx + r) * G + col];
+      z[col] = s;
+    }
+    for (int k = 0; k < H; ++k) {
+      const double i = sigmoid(z[k]), g = tanh(z[H + k]), f = sigmoid(z[2 * H + k]),
+                   o = sigmoid(z[3 * H + k]);
+      c[k] = f * c[k] + i * g;
+      gi[(size_t)t * H + k] = i;
+      gg[(size_t)t * H + k] = g;
+      gf[(size_t)t * H + k] = f;
+      go[(size_t)t * H + k] = o;
+      cs[(size_t)t * H + k] = c[k];
+    }
+    for (int k = 0; k < H; ++k) {
+      h[k] = go[(size_t)t * H + k] * tanh(c[k]);
+      hs[(size_t)t * H + k] = h[k];
+    }
+    t = t + 1;
+  }
+  const int64_t T = t;
+  if (steps_out) *steps_out = T;
+
+  double *y = (double *)malloc(sizeof(double) * (size_t)dy);
+  double *gy = (double *)malloc(sizeof(double) * (size_t)dy);
+  for (int j = 0; j < dy; ++j) {
+    double s = net->bout ? net->bout[j] : 0.0;
+    for (int k = 0; k < H; ++k) s += h[k] * net->Wout[(size_t)k * dy + j];
+    y[j] = s;
+  }
+  softmax(y, dy, gy);
+  if (loss) *loss = -log(gy[label]);
+  gy[label] -= 1.0;
+
+  if (dWout)
+    for (int k = 0; k < H; ++k)
+      for (int j = 0; j < dy; ++j) dWout[(size_t)k * dy + j] = h[k] * gy[j];
+  if (dbout)
+    for (int j = 0; j < dy; ++j) dbout[j] = gy[j];
+  if (dW) memset(dW, 0, sizeof(double) * (size_t)(dx + H) * G);
+  if (db) memset(db, 0, sizeof(double) * (size_t)G);
+
+  double *dh = (double *)malloc(sizeof(double) * (size_t)H);
+  double *dc = (double *)calloc((size_t)H, sizeof(double));
+  double *dz = (double *)malloc(sizeof(double) * (size_t)G);
+  for (int k = 0; k < H; ++k) {
+    double s = 0.0;
+    for (int j = 0; j < dy; ++j) s += gy[j] * net->Wout[(size_t)k * dy + j];
+    dh[k] = s;
+  }
+  for (t = T - 1; t >= 0; --t) {
+    const double *xt = x + (size_t)t * dx;
+    const double *hprev = t > 0 ? hs + (size_t)(t - 1) * H : NULL;
+    const double *cprev = t > 0 ? cs + (size_t)(t - 1) * H : NULL;
+    for (int k = 0; k < H; ++k) {
+      const double i = gi[(size_t)t * H + k], g = gg[(size_t)t * H + k], f = gf[(size_t)t * H + k],
+                   o = go[(size_t)t * H + k];
+      const double tc = tanh(cs[(size_t)t * H + k]);
+      const double dct = dc[k] + dh[k] * o * (1.0 - tc * tc);
+      dz[3 * H + k] = dh[k] * tc * o * (1.0 - o);
+      dz[k] = dct * g * i * (1.0 - i);
+      dz[H + k] = dct * i * (1.0 - g * g);
+      dz[2 * H + k] = dct * (cprev ? cprev[k] : 0.0) * f * (1.0 - f);
+      dc[k] = dct * f;
+    }
+    if (dW) {
+      for (int r = 0; r < dx; ++r)
+        for (int col = 0; col < G; ++col) dW[(size_t)r * G + col] += xt[r] * dz[col];
+      if (hprev)
+        for (int r = 0; r < H; ++r)
+          for (int col = 0; col < G; ++col) dW[(size_t)(dx + r) * G + col] += hprev[r] * dz[col];
+    }
+    if (db)
+      for (int col = 0; col < G; ++col) db[col] += dz[col];
+    for (int r = 0; r < H; ++r) {
+      double s = 0.0;
+      for (int col = 0; col < G; ++col) s += dz[col] * net->W[(size_t)(dx + r) * G + col];
+      dh[r] = s;
+    }
+  }
+  free(gi); free(gg); free(gf); free(go); free(cs); free(hs); free(h); free(c); free(z);
+  free(y); free(gy); free(dh); free(dc); free(dz);
+}
+
+/* pfor(body, B): tokens of all sequences back to back in X, sequence i at rows offsets[i] ..
+ * offsets[i + 1]; dW [B, dx+H, 4H], db [B, 4H], dWout [B, H, dy], dbout [B, dy], loss [B], steps [B]. */
+void lstmo_while_per_example_grads(const lstmo_net *net, const double *X, const int64_t *offsets,
+                                   const int32_t *labels, int64_t B, int64_t max_steps,
+                                   const double *halt_w, double halt_c, double *dW, double *db,
+                                   double *dWout, double *dbout, double *loss, int64_t *steps_out) {
+  const size_t G = 4 * (size_t)net->H;
+  const size_t nW = (size_t)(net->dx + net->H) * G, nWo = (size_t)net->H * net->dy;
+#pragma omp parallel for schedule(dynamic)
+  for (int64_t i = 0; i < B; ++i)
+    lstmo_body_while_grads(net, X + (size_t)offsets[i] * net->dx, offsets[i + 1] - offsets[i], max_steps,
+                           halt_w, halt_c, labels[i], dW ? dW + (size_t)i * nW : NULL,
+                           db ? db + (size_t)i * G : NULL, dWout ? dWout + (size_t)i * nWo : NULL,
+                           dbout ? dbout + (size_t)i * net->dy : NULL, loss ? loss + i : NULL,
+                           steps_out ? steps_out + i : NULL);
+}

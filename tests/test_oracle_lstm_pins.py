@@ -430,3 +430,149 @@ def test_while_forward_special_cases():
     h2, y2, s2 = lstm.while_forward(net, Pp, [lengths[b] for b in order], 100, wv, -0.1)
     np.testing.assert_array_equal(h2, h1[order])
     np.testing.assert_array_equal(s2, s1[order])
+
+
+# --------------------------------------------------------------------------------------------
+# Per-example gradients through the while loop (Section 3.7 under Section 5.3).
+# --------------------------------------------------------------------------------------------
+def test_while_grads_against_autograd_through_the_library_cell_under_a_python_while():
+    rng = np.random.default_rng(102)
+    dx, H, dy, cap = 4, 6, 5, 6
+    net = rand_lstm(rng, dx, H, dy, 1)
+    lengths = np.array([3, 0, 9, 2, 9, 5, 1, 7])
+    B = len(lengths)
+    X = rng.standard_normal((B, 9, dx))
+    labels = rng.integers(0, dy, size=B)
+    w = rng.standard_normal(H)
+    c0 = -0.15
+    got = lstm.while_per_example_grads(net, packed(X, lengths), lengths, labels, cap, w, c0)
+    seen = set()
+    for b, n in enumerate(lengths):
+        cell, Wout, bout, cols = torch_cell(net, requires_grad=True)
+        hb = torch.zeros(1, H, dtype=torch.float64)
+        cb = torch.zeros(1, H, dtype=torch.float64)
+        t = 0
+        while True:
+            score = c0 + float(hb[0].detach().numpy() @ w)
+            assert abs(score) > 1e-9
+            if not (t < n and t < cap and score <= 0.0):
+                break
+            hb, cb = cell(torch.from_numpy(X[b, t:t + 1]), (hb, cb))
+            t += 1
+        assert got["steps"][b] == t
+        seen.add("none" if t == 0 else "cap" if t == cap else "len" if t == n else "halt")
+        ell = -torch.log_softmax(hb[0] @ Wout + bout, dim=0)[int(labels[b])]
+        g_ih, g_hh, g_b, g_Wout, g_bout = torch.autograd.grad(
+            ell, [cell.weight_ih, cell.weight_hh, cell.bias_ih, Wout, bout], allow_unused=True)
+        zero = lambda g, like: torch.zeros_like(like) if g is None else g       # no trip: the cell is unused
+        g_ih, g_hh, g_b = zero(g_ih, cell.weight_ih), zero(g_hh, cell.weight_hh), zero(g_b, cell.bias_ih)
+        want_W = np.empty_like(net.W)
+        want_W[:dx][:, cols] = g_ih.numpy().T
+        want_W[dx:][:, cols] = g_hh.numpy().T
+        want_b = np.empty(4 * H)
+        want_b[cols] = g_b.numpy()
+        np.testing.assert_allclose(got["dW"][b], want_W, rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(got["db"][b], want_b, rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(got["dWout"][b], g_Wout.numpy(), rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(got["dbout"][b], g_bout.numpy(), rtol=1e-10, atol=1e-13)
+        assert got["loss"][b] == pytest.approx(float(ell.detach()), rel=1e-12)
+    assert seen == {"none", "cap", "len", "halt"}, seen
+
+
+def test_while_grads_by_central_differences_of_the_pinned_forward_loop():
+    """The loss recomputed from the readout of `while_forward` (pinned above) at parameters moved by
+    +-1e-6: the trip counts do not change (every score is at least 1e-3 from the threshold), so the
+    difference quotient is the derivative of the loop's result."""
+    rng = np.random.default_rng(112)
+    dx, H, dy = 3, 4, 3
+    net = rand_lstm(rng, dx, H, dy, 1)
+    lengths = np.array([5, 2, 7, 4])
+    X = rng.standard_normal((4, 7, dx))
+    P = packed(X, lengths)
+    labels = np.array([0, 2, 1, 1])
+    w = rng.standard_normal(H) * 1.5
+    c0 = -0.12
+    got = lstm.while_per_example_grads(net, P, lengths, labels, 6, w, c0)
+    assert len(set(got["steps"].tolist())) >= 3
+    # margins of every decision taken
+    for b in range(4):
+        full = lstm.Lstm(net.W, net.b, net.Wout, net.bout, 7)
+        hs, _ = lstm.states(full, X[b])
+        hist = np.concatenate([np.zeros((1, H)), hs])
+        for t in range(int(got["steps"][b]) + 1):
+            assert abs(c0 + hist[t] @ w) > 1e-3
+    eps = 1e-6
+
+    def losses():
+        n2 = lstm.Lstm(net.W, net.b, net.Wout, net.bout, 1)
+        _, y, steps = lstm.while_forward(n2, P, lengths, 6, w, c0)
+        assert np.array_equal(steps, got["steps"])
+        return np.array([-(y[b, labels[b]] - scipy.special.logsumexp(y[b])) for b in range(4)])
+
+    def fd(arr, idx):
+        keep = arr[idx]
+        arr[idx] = keep + eps
+        up = losses()
+        arr[idx] = keep - eps
+        dn = losses()
+        arr[idx] = keep
+        return (up - dn) / (2 * eps)
+
+    for idx in [(0, 0), (2, 5), (1, 9), (4, 15), (6, 2), (3, 12), (5, 7)]:     # input rows and recurrent rows
+        np.testing.assert_allclose(got["dW"][(slice(None),) + idx], fd(net.W, idx), rtol=2e-6, atol=1e-9)
+    for k in (0, 5, 10, 15):
+        np.testing.assert_allclose(got["db"][:, k], fd(net.b, k), rtol=2e-6, atol=1e-9)
+    np.testing.assert_allclose(got["dWout"][:, 2, 1], fd(net.Wout, (2, 1)), rtol=2e-6, atol=1e-9)
+    np.testing.assert_allclose(got["dbout"][:, 0], fd(net.bout, 0), rtol=2e-6, atol=1e-9)
+
+
+def test_while_grads_reduce_to_the_fixed_length_gradients_and_special_cases():
+    rng = np.random.default_rng(103)
+    T, dx, H, dy = 5, 3, 4, 3
+    net = rand_lstm(rng, dx, H, dy, T)
+    B = 6
+    X = rng.standard_normal((B, T, dx))
+    labels = rng.integers(0, dy, size=B)
+    # only the lengths stop the loop and every sequence is T long: the unrolled model's gradients
+    dW, db, dWout, dbout, loss = lstm.per_example_grads(net, X, labels)
+    got = lstm.while_per_example_grads(net, X.reshape(B * T, dx), [T] * B, labels, 100, None, 0.0)
+    assert got["steps"].tolist() == [T] * B
+    for a, b in ((got["dW"], dW), (got["db"], db), (got["dWout"], dWout), (got["dbout"], dbout), (got["loss"], loss)):
+        np.testing.assert_allclose(a, b, rtol=1e-13, atol=1e-16)
+    # a cap of n trips: the gradients of the model unrolled to n steps on the first n tokens
+    for n in (1, 3):
+        short = lstm.Lstm(net.W, net.b, net.Wout, net.bout, n)
+        sW, sb, sWo, sbo, sl = lstm.per_example_grads(short, X[:, :n], labels)
+        g = lstm.while_per_example_grads(net, X.reshape(B * T, dx), [T] * B, labels, n, None, -1.0)
+        assert g["steps"].tolist() == [n] * B
+        np.testing.assert_allclose(g["dW"], sW, rtol=1e-13, atol=1e-16)
+        np.testing.assert_allclose(g["db"], sb, rtol=1e-13, atol=1e-16)
+        np.testing.assert_allclose(g["dWout"], sWo, rtol=1e-13, atol=1e-16)
+        np.testing.assert_allclose(g["loss"], sl, rtol=1e-13)
+    # no trip at all (a positive score before the first one, or no tokens): the state is zero, so the
+    # cell's parameters and the readout weights get a zero gradient, the readout bias softmax - onehot
+    for lens, c0 in (([T] * B, 1e-300), ([0] * B, -1.0)):
+        Xp = X.reshape(B * T, dx) if lens[0] else np.zeros((0, dx))
+        g = lstm.while_per_example_grads(net, Xp, lens, labels, 100, np.zeros(H), c0)
+        assert g["steps"].tolist() == [0] * B
+        assert not g["dW"].any() and not g["db"].any() and not g["dWout"].any()
+        p = scipy.special.softmax(net.bout)
+        for b in range(B):
+            want = p.copy()
+            want[labels[b]] -= 1.0
+            np.testing.assert_allclose(g["dbout"][b], want, rtol=1e-13)
+            assert g["loss"][b] == pytest.approx(-math.log(p[labels[b]]), rel=1e-13)
+    # iterations are independent (permutation), and rows of dbout sum to zero
+    lengths = [2, 5, 0, 4, 1, 3]
+    P = packed(X, lengths)
+    wv = rng.standard_normal(H)
+    g1 = lstm.while_per_example_grads(net, P, lengths, labels, 100, wv, -0.1)
+    order = [3, 0, 4, 2, 5, 1]
+    Pp = np.concatenate([X[b, :lengths[b]] for b in order])
+    g2 = lstm.while_per_example_grads(net, Pp, [lengths[b] for b in order], labels[order], 100, wv, -0.1)
+    for k in g1:
+        np.testing.assert_array_equal(g2[k], g1[k][order])
+    np.testing.assert_allclose(g1["dbout"].sum(axis=1), 0.0, atol=1e-15)
+    # the forward results agree with the pinned forward loop
+    _, _, steps = lstm.while_forward(net, P, lengths, 100, wv, -0.1)
+    assert np.array_equal(steps, g1["steps"])

@@ -71,6 +71,8 @@ MUTANTS = [
 
 LSTM_SRC = os.path.join(ROOT, "oracle", "lstm_oracle.c")
 
+WHILE_GRADS = "void lstmo_body_while_grads("
+
 LSTM_MUTANTS = [
     ("norm_cross_term", "for (size_t e = 0; e < nW; ++e) s[0] += dW[e] * dW[e];",
      "for (size_t e = 0; e < nW; ++e) s[0] += dW[e] * dW[(e + 1) % nW];"),
@@ -128,6 +130,35 @@ LSTM_MUTANTS = [
      "halt_w, halt_c, h_out ? h_out + (size_t)(B - 1 - i) * net->H : NULL,"),
     ("varlen_sequence_offset", "X + (size_t)offsets[i] * net->dx, offsets[i + 1] - offsets[i],",
      "X + (size_t)offsets[i] * net->dx + (i > 0 ? net->dx : 0), offsets[i + 1] - offsets[i],"),
+    # gradients through the while loop: mistakes planted in that function only
+    ("while_grads_gate_history_not_indexed_by_trip", "gi[(size_t)t * H + k] = i;", "gi[k] = i;", WHILE_GRADS),
+    ("while_grads_state_history_not_indexed_by_trip", "cs[(size_t)t * H + k] = c[k];", "cs[k] = c[k];", WHILE_GRADS),
+    ("while_grads_sweep_over_the_cap", "for (t = T - 1; t >= 0; --t) {", "for (t = (T > 0 ? cap : 0) - 1; t >= 0; --t) {",
+     WHILE_GRADS),
+    ("while_grads_sweep_skips_the_first_trip", "for (t = T - 1; t >= 0; --t) {", "for (t = T - 1; t >= 1; --t) {",
+     WHILE_GRADS),
+    ("while_grads_cell_carry", "dc[k] = dct * f;", "dc[k] = dct;", WHILE_GRADS),
+    ("while_grads_recurrent_rows_use_current_state", "const double *hprev = t > 0 ? hs + (size_t)(t - 1) * H : NULL;",
+     "const double *hprev = hs + (size_t)t * H;", WHILE_GRADS),
+    ("while_grads_forget_gate_uses_current_cell", "dz[2 * H + k] = dct * (cprev ? cprev[k] : 0.0) * f * (1.0 - f);",
+     "dz[2 * H + k] = dct * cs[(size_t)t * H + k] * f * (1.0 - f);", WHILE_GRADS),
+    ("while_grads_readout_uses_first_state", "dWout[(size_t)k * dy + j] = h[k] * gy[j];",
+     "dWout[(size_t)k * dy + j] = hs[k] * gy[j];", WHILE_GRADS),
+    ("while_grads_head_sign", "gy[label] -= 1.0;", "gy[label] += 1.0;", WHILE_GRADS),
+    ("while_grads_halting_test_strict", "score <= 0.0)) break;", "score < 0.0)) break;", WHILE_GRADS),
+    ("while_grads_cap_ignored", "if (!(t < len && t < max_steps && score <= 0.0)) break;",
+     "if (!(t < len && score <= 0.0)) break;", WHILE_GRADS),
+    ("while_grads_bias_not_summed", "db[col] += dz[col];", "db[col] = dz[col];", WHILE_GRADS),
+    ("while_grads_weights_not_summed", "dW[(size_t)r * G + col] += xt[r] * dz[col];",
+     "dW[(size_t)r * G + col] = xt[r] * dz[col];", WHILE_GRADS),
+    ("while_grads_seed_transposed", "s += gy[j] * net->Wout[(size_t)k * dy + j];",
+     "s += gy[j] * net->Wout[(size_t)((k * dy + j) % H) * dy + (k * dy + j) / H % dy];", WHILE_GRADS),
+    ("while_grads_hidden_cotangent_through_input_rows", "s += dz[col] * net->W[(size_t)(dx + r) * G + col];",
+     "s += dz[col] * net->W[(size_t)(r % dx) * G + col];", WHILE_GRADS),
+    ("while_grads_stacking", "labels[i], dW ? dW + (size_t)i * nW : NULL,",
+     "labels[i], dW ? dW + (size_t)(B - 1 - i) * nW : NULL,", WHILE_GRADS),
+    ("while_grads_sequence_offset", "lstmo_body_while_grads(net, X + (size_t)offsets[i] * net->dx,",
+     "lstmo_body_while_grads(net, X + (size_t)offsets[i] * net->dx + (i > 0 ? net->dx : 0),", WHILE_GRADS),
 ]
 
 
@@ -237,13 +268,23 @@ def run_mutants(oracle, tmp_path, source, mutants, env_var, pins_file):
     """Build every mutant and run the pin file against it, a few at a time; returns the names of
     the mutants that survived (passed every pin)."""
     src = open(source).read()
-    for name, old, _ in mutants:
-        assert src.count(old) >= 1, f"pattern for {name} not found in {os.path.basename(source)}"
+
+    def planted(m):
+        # a fourth entry names the function the mistake belongs to: only the text from there on is changed
+        # (the others stop short of that function, which repeats lines of the reverse sweep above it)
+        name, old, new = m[:3]
+        start = src.index(m[3]) if len(m) > 3 else 0
+        end = src.index(WHILE_GRADS) if len(m) == 3 and WHILE_GRADS in src else len(src)
+        assert src.count(old, start, end) >= 1, f"pattern for {name} not found in {os.path.basename(source)}"
+        return src[:start] + src[start:end].replace(old, new) + src[end:]
+
+    for m in mutants:
+        planted(m)
 
     def one(m):
-        name, old, new = m
+        name = m[0]
         mutated = tmp_path / f"{name}.c"
-        mutated.write_text(src.replace(old, new))
+        mutated.write_text(planted(m))
         lib = tmp_path / f"lib{name}.so"
         oracle.compile_source(str(mutated), str(lib))
         env = dict(os.environ, OMP_NUM_THREADS="2")
