@@ -398,6 +398,57 @@ def main():
             f"roofline frac {roof['frac']:.3f}")
         return rec, inp
 
+    def measure_while_grads(name, steps, warmup):
+        w = pick(wl.LSTM_WORKLOADS, name)
+        log(f"[bench] {name}: uploading inputs")
+        inp, lengths, offsets, halt_w, halt_c = wl.make_while_inputs(w)
+        net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, 1)
+        X, off, hw = torch.from_numpy(inp.X).to(dev), torch.from_numpy(offsets).to(dev), torch.from_numpy(halt_w).to(dev)
+        labels = torch.from_numpy(inp.labels).to(dev)
+        B, H, dx, dy = w.B, w.H, w.dx, w.dy
+        tokens = int(lengths.sum())
+        f32 = dict(dtype=torch.float32, device=dev)
+        out = {"dW": torch.empty((B, dx + H, 4 * H), **f32), "db": torch.empty((B, 4 * H), **f32),
+               "dWout": torch.empty((B, H, dy), **f32), "dbout": torch.empty((B, dy), **f32),
+               "loss": torch.empty((B,), **f32), "steps": torch.empty((B,), dtype=torch.int32, device=dev)}
+        ws = torch.empty(pfg.pfg_lstm_while_grads_workspace_bytes(net, B, tokens, w.T), dtype=torch.uint8, device=dev)
+        step = lambda: pfg.pfg_lstm_while_per_example_grads(net, X, off, labels, w.T, halt_w=hw, halt_c=halt_c,
+                                                            out=out, workspace=ws)
+        step()
+        torch.cuda.synchronize()
+        used = int(out["steps"].sum().item())
+        log(f"[bench] {name}: {used} of {tokens} tokens consumed; timing {steps} steps")
+        sec = timed(step, steps, warmup)
+        sec_graph = None
+        if not args.no_graph:
+            try:
+                sec_graph = timed_graph(step, steps, warmup)
+            except Exception as e:
+                log(f"[bench] {name}: graph replay not measured ({e})")
+        kt = kernel_times(step, steps)
+        # the one large output is the stacked weight gradient: 4 bytes per value of dW and db
+        fam = "outer_sum_ragged"
+        nbytes = 4 * B * (dx + H + 1) * 4 * H
+        gbs = nbytes / kt[fam]["ms_per_step"] / 1e6
+        roof = {"kernel": fam, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                "bytes_per_launch": nbytes / kt[fam]["launches_per_step"],
+                "ms_per_launch": kt[fam]["ms_per_step"] / kt[fam]["launches_per_step"],
+                "launches_per_step": kt[fam]["launches_per_step"],
+                "note": "the writer sums an iteration's trips (2 * tokens_consumed * (dx + H) * 4H flops on the "
+                        "vector units) before it stores; the rest of the step is two chains of dependent "
+                        "launches, one per forward and reverse trip"}
+        rec = {"workload": name, "call": w.call, "input_size": dx, "state_size": H, "output_size": dy,
+               "dtype": "f32", "B": B, "tokens": tokens, "tokens_consumed": used, "max_steps": w.T, "steps": steps,
+               "ms_per_step": sec * 1e3,
+               "ms_per_step_graph_replay": None if sec_graph is None else sec_graph * 1e3,
+               "per_example_grads_per_sec": B / sec, "tokens_per_sec": used / sec, "kernels": kt,
+               "kernel_ms_sum": sum(v["ms_per_step"] for v in kt.values()),
+               "launches_per_step": sum(v["launches_per_step"] for v in kt.values()), "roofline": roof}
+        log(f"[bench] {name}: {rec['ms_per_step']:.4f} ms/step, {rec['per_example_grads_per_sec']:.0f} grads/s, "
+            f"roofline frac {roof['frac']:.3f}")
+        return rec, inp
+
     def measure_conv(name, steps, warmup):
         w = pick(wl.CONV_WORKLOADS, name)
         log(f"[bench] {name}: uploading inputs")
@@ -603,6 +654,8 @@ def main():
             return measure_varlen(name, steps, warmup)
         if w.call == "lstm_while_forward":
             return measure_while(name, steps, warmup)
+        if w.call == "lstm_while_per_example_grads":
+            return measure_while_grads(name, steps, warmup)
         log(f"[bench] {name}: uploading inputs")
         inp = wl.make_lstm_inputs(w)
         net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, w.T)
@@ -821,6 +874,7 @@ def main():
                             ("c8_lstm_jacobian", max(3, args.steps)),
                             ("c9_lstm_varlen", max(3, args.steps)),
                             ("c12_lstm_while", max(3, args.steps)),
+                            ("c14_lstm_while_grads", max(3, args.steps)),
                             ("c10_mnist_convnet_grads", max(3, args.steps)),
                             ("c10_mnist_convnet_grad_norms", max(3, args.steps)),
                             ("c11_cond_two_branches", max(3, args.steps * 2)),

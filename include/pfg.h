@@ -302,6 +302,36 @@ int pfg_lstm_while_forward(const pfg_lstm *net, const void *X, const int32_t *se
                            float *h_out, float *y_out, int32_t *steps_out, int32_t *trips_out,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Per-example gradients (Section 5.3) of a body that holds the while loop above (Section 3.7):
+ * iteration i runs the loop of pfg_lstm_while_forward on its own tokens (T_i trips), then
+ *      ell_i = -log softmax(h W_out + b_out)[labels[i]]
+ * and the call returns the gradient of ell_i with respect to W, b, W_out, b_out for every i.  The
+ * loop condition is a comparison and has no derivative: the gradient is that of the T_i cell
+ * applications the iteration made, taken in reverse.  The vectorised reverse loop runs trip
+ * t = max_steps - 1 .. 0 on the list of iterations the forward loop kept for that trip (an
+ * iteration enters the reverse loop at its own last trip; until then its cotangent keeps the seed
+ * (d ell / d y) W_out^T), and sums every iteration's outer products over its own trips only.
+ * Arguments as for pfg_lstm_while_forward, and
+ *   labels        DEVICE [B] int32 in [0, output_size)
+ *   max_steps     HOST, 0 .. 65536
+ *   dW_out        DEVICE [B, input_size + state_size, 4 * state_size] or NULL
+ *   db_out        DEVICE [B, 4 * state_size] or NULL
+ *   dWout_out     DEVICE [B, state_size, output_size] or NULL
+ *   dbout_out     DEVICE [B, output_size] or NULL
+ *   loss_out      DEVICE [B] or NULL
+ *   steps_out     DEVICE [B] int32 or NULL: T_i
+ * (at least one of the five float outputs is required; B <= 65535).  An iteration with T_i = 0 has
+ * dW = db = dWout = 0 and dbout = softmax(b_out) - onehot.  Every output element is written.  The
+ * workspace keeps one list per trip and the gate values, cell and hidden states by token row; like the
+ * forward call this one copies nothing from or to the host and does not synchronise. */
+int pfg_lstm_while_grads_workspace_bytes(const pfg_lstm *net, int64_t B, int64_t total_tokens, int32_t max_steps,
+                                         size_t *bytes);
+int pfg_lstm_while_per_example_grads(const pfg_lstm *net, const void *X, const int32_t *seq_offsets,
+                                     const int32_t *labels, int64_t B, int64_t total_tokens, int32_t max_steps,
+                                     const float *halt_w, float halt_c, float *dW_out, float *db_out,
+                                     float *dWout_out, float *dbout_out, float *loss_out, int32_t *steps_out,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ------------------------------------------------------------------------------------------
  * Convolutional network of the paper's MNIST benchmarks (Section 6.1: conv-relu-maxpool blocks
  * followed by dense layers; the dropout of that model is a stateful random op and is left out).

@@ -113,6 +113,10 @@ struct GemmArgs {
   float *lstm_hs_w;             // hidden state, same addressing (the product's A operand is read elsewhere)
   int64_t lstm_state_ld, lstm_state_ts;   // [M, T, H] history: T * H and H; state updated in place: H and 0
   int32_t lstm_has_prev;        // 0: c_{step-1} is zero and is not read
+  // history by token row (sequences stored back to back, lstm_zx_rows given): the step's gate values
+  // [tokens, 4H], cell state and hidden state [tokens, H] also go to row lstm_zx_rows[m] + step of these
+  // (any may be nullptr); register-fed kernel only
+  float *lstm_tok_gates, *lstm_tok_c, *lstm_tok_h;
   // a_km == 1: the A operand is stored transposed, [K, M] row-major with row stride lda (row k holds
   // A[0 .. M, k]); a product can then contract over the ROWS of a matrix it also uses row by row
   // elsewhere.  LDS-tiled kernel only; float32, no scale, S == 1, EPI_NONE, M a multiple of 4 and
@@ -371,5 +375,18 @@ hipError_t launch_while_select(const int32_t *I, const int32_t *meta, int32_t t,
                                int32_t *steps, int32_t *trips, hipStream_t stream);
 hipError_t launch_while_state(const int32_t *steps, const float *h_even, const float *h_odd, int64_t B, int32_t H,
                               float *h_out, hipStream_t stream);
+// Reverse trip t on the rows of list I (meta[0] of them): cell backward from dh [B, H] and dc [B, H]
+// (rows by iteration; dc updated in place) with the gate values and cell states kept by token row;
+// dz goes to token row (first token of I[m]) + t of dz_tok [tokens, 4H] and to row m of dz_packed.
+hipError_t launch_while_cell_backward(const int32_t *I, const int32_t *meta, int32_t t, const int32_t *seq_offsets,
+                                      int32_t total_tokens, const float *gates_tok, const float *c_tok,
+                                      const float *dh, float *dc, float *dz_tok, float *dz_packed, int64_t B,
+                                      int32_t H, hipStream_t stream);
+// dW[b] = sum over the steps[b] trips of iteration b of [x_t, h_{t-1}]^T dz_t, db[b] = sum of dz_t (rows by
+// token: iteration b starts at seq_offsets[b]; h before trip 0 is zero); dW [B, dx + H, 4H], db [B, 4H],
+// either may be nullptr.  B <= 65535.
+hipError_t launch_outer_sum_ragged(const float *x, int32_t dx, const float *h_tok, int32_t H, const float *dz_tok,
+                                   const int32_t *seq_offsets, const int32_t *steps, int32_t total_tokens, int64_t B,
+                                   float *dW, float *db, hipStream_t stream);
 
 }  // namespace pfg

@@ -309,8 +309,18 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
           grow[0] = gi; grow[H] = gg; grow[2 * H] = gf; grow[3 * H] = go;
         }
         const int64_t at = lstm_p * g.lstm_state_ld + t * g.lstm_state_ts + lstm_k;
+        const float hnew = go * tanhf(c);
         g.lstm_cs_w[at] = c;
-        g.lstm_hs_w[at] = go * tanhf(c);
+        g.lstm_hs_w[at] = hnew;
+        if (g.lstm_zx_rows && (g.lstm_tok_gates || g.lstm_tok_c || g.lstm_tok_h)) {
+          const int64_t zr = (int64_t)g.lstm_zx_rows[lstm_p] + t;      // the token row of (iteration, step)
+          if (g.lstm_tok_gates) {
+            float *grow = g.lstm_tok_gates + zr * 4 * H + lstm_k;
+            grow[0] = gi; grow[H] = gg; grow[2 * H] = gf; grow[3 * H] = go;
+          }
+          if (g.lstm_tok_c) g.lstm_tok_c[zr * H + lstm_k] = c;
+          if (g.lstm_tok_h) g.lstm_tok_h[zr * H + lstm_k] = hnew;
+        }
       }
       return;
     }

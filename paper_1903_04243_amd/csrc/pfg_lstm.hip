@@ -217,6 +217,8 @@ VarlenPlan make_varlen_plan(const pfg_lstm *net, int64_t B, int64_t tokens) {
 struct WhilePlan {
   size_t total = 0;
   size_t zx = 0, state = 0, hfin = 0, list = 0, meta = 0, flags = 0, cnt = 0, steps = 0;
+  // gradients only: history by token row, cotangents, head
+  size_t gates = 0, cs = 0, hs = 0, dz = 0, dzp = 0, dh = 0, dc = 0, y = 0, gy = 0;
   size_t take(size_t bytes) {
     const size_t at = total;
     total += (bytes + 255) / 256 * 256;
@@ -224,17 +226,31 @@ struct WhilePlan {
   }
 };
 
-WhilePlan make_while_plan(const pfg_lstm *net, int64_t B, int64_t tokens) {
+// lists: how many active lists are kept (2: this trip's and the next one's, used alternately;
+// max_steps + 1 with gradients: the list of every trip stays for the reverse sweep)
+WhilePlan make_while_plan(const pfg_lstm *net, int64_t B, int64_t tokens, int64_t lists = 2, bool grads = false) {
   const size_t H = net->state_size, f = sizeof(float), i = sizeof(int32_t);
+  const size_t tok = tokens > 0 ? tokens : 1;
   WhilePlan p;
-  p.zx = p.take(f * (tokens > 0 ? tokens : 1) * 4 * H);
+  p.zx = p.take(f * tok * 4 * H);
   p.state = p.take(f * 3 * B * H);          // h (two buffers used alternately) and c, zeroed together
   p.hfin = p.take(f * B * H);               // last states, if h_out is not given
-  p.list = p.take(i * 2 * B);               // the active list of this trip and of the next
-  p.meta = p.take(i * 4);                   // their {length, 0} descriptors
+  p.list = p.take(i * lists * B);
+  p.meta = p.take(i * 2 * lists);           // their {length, 0} descriptors
   p.flags = p.take(i * B);
   p.cnt = p.take(i * while_count_entries(B));
   p.steps = p.take(i * B);                  // trip counts, if steps_out is not given
+  if (grads) {
+    p.gates = p.take(f * tok * 4 * H);
+    p.cs = p.take(f * tok * H);
+    p.hs = p.take(f * tok * H);
+    p.dz = p.take(f * tok * 4 * H);
+    p.dzp = p.take(f * B * 4 * H);
+    p.dh = p.take(f * 2 * B * H);           // dh and dc, side by side
+    p.dc = p.dh + f * B * H;
+    p.y = p.take(f * B * net->output_size);
+    p.gy = p.take(f * B * net->output_size);
+  }
   return p;
 }
 
@@ -246,6 +262,77 @@ int check_while_sizes(const pfg_lstm *net, int64_t B, int64_t tokens) {
       B * H > ((int64_t)1 << 38))
     return fail(PFG_ERR_OVERFLOW, "B = %lld sequences with %lld tokens exceed the indexing limits",
                 (long long)B, (long long)tokens);
+  return PFG_OK;
+}
+
+// The part in front of the loop and the loop itself (Section 3.7), shared by the forward call and
+// the gradient call.  With keep == false two lists are used alternately; with keep == true the list
+// of every trip stays (list t + 1 holds the iterations that made trip t, meta t + 1 its length) and
+// every trip also leaves its gate values, cell state and hidden state at the token row it consumed.
+// On return trip t's hidden state of the rows that made it is in buffer t % 2 of p.state.
+int while_forward_loop(const pfg_lstm *net, const void *X, const int32_t *seq_offsets, int64_t B,
+                       int64_t total_tokens, int32_t max_steps, const float *halt_w, float halt_c, int32_t *steps,
+                       int32_t *trips_out, void *ws, const WhilePlan &p, bool keep, hipStream_t stream) {
+  const int32_t dx = net->input_size, H = net->state_size;
+  const float *W = static_cast<const float *>(net->W);
+  auto ints = [&](size_t off) { return reinterpret_cast<int32_t *>(static_cast<char *>(ws) + off); };
+
+  // input projections of all tokens in one product (they do not depend on the recurrence), zero
+  // states, the list of all iterations
+  if (total_tokens > 0 && max_steps > 0) {
+    GemmArgs g{};
+    g.A = X; g.lda = dx; g.a_batch_stride = dx; g.S = 1; g.a_is_f32 = 1;
+    g.W = W; g.ldw = 4 * H; g.w_kn = 1;
+    g.M = (int32_t)total_tokens; g.N = 4 * H; g.K = dx;
+    g.bias = net->b; g.epilogue = EPI_BIAS;
+    g.C = ws_at(ws, p.zx); g.ldc = 4 * H;
+    PFG_LAUNCH("lstm_gemm_input", launch_gemm(g, stream));
+  }
+  float *hbuf[2] = {ws_at(ws, p.state), ws_at(ws, p.state) + B * (int64_t)H};
+  float *c = ws_at(ws, p.state) + 2 * B * (int64_t)H;
+  PFG_LAUNCH("fill_zero", launch_fill_zero(ws_at(ws, p.state), 3 * B * (int64_t)H, stream));
+  auto list = [&](int32_t q) { return ints(p.list) + (keep ? q : (q & 1)) * B; };
+  auto meta = [&](int32_t q) { return ints(p.meta) + 2 * (keep ? q : (q & 1)); };
+  PFG_LAUNCH("while_select", launch_while_init(list(0), meta(0), steps, trips_out, (int32_t)B, max_steps, stream));
+
+  // trip t evaluates the condition on the active rows, keeps those that go on, and runs the cell on
+  // them; h_t goes to buffer t % 2 (a trip reads whole rows of h_{t-1} while other workgroups write
+  // h_t), c is updated in place.  Every kernel takes the live row count from device memory; once the
+  // list is empty the remaining trips find nothing to do.
+  for (int32_t t = 0; t < max_steps; ++t) {
+    PFG_LAUNCH("while_select",
+               launch_while_select(list(t), meta(t), t, seq_offsets, (int32_t)total_tokens, hbuf[(t + 1) & 1], H,
+                                   halt_w, halt_c, (int32_t)B, ints(p.flags), ints(p.cnt), list(t + 1), meta(t + 1),
+                                   steps, trips_out, stream));
+    GemmArgs g{};
+    g.A = hbuf[(t + 1) & 1]; g.lda = H; g.a_batch_stride = H; g.S = 1; g.a_is_f32 = 1;
+    g.W = W + (int64_t)dx * 4 * H; g.ldw = 4 * H; g.w_kn = 1;
+    g.M = (int32_t)B; g.N = 4 * H; g.K = H;
+    g.epilogue = EPI_LSTM_FWD;
+    g.lstm_H = H; g.lstm_T = 1; g.lstm_step = t;
+    g.lstm_zx = ws_at(ws, p.zx); g.lstm_zx_rows = seq_offsets;
+    g.lstm_gates_w = nullptr;
+    g.lstm_cs_w = c; g.lstm_hs_w = hbuf[t & 1];
+    g.lstm_state_ld = H; g.lstm_state_ts = 0; g.lstm_has_prev = 1;
+    if (keep) {
+      g.lstm_tok_gates = ws_at(ws, p.gates); g.lstm_tok_c = ws_at(ws, p.cs); g.lstm_tok_h = ws_at(ws, p.hs);
+    }
+    g.sub = meta(t + 1); g.sub_rows = list(t + 1); g.sub_gather = 1; g.sub_scatter = 0;
+    PFG_LAUNCH("lstm_step", launch_gemm(g, stream));
+  }
+  return PFG_OK;
+}
+
+// The gradient call keeps one list per trip and writes [B, dx + H, 4H] outputs one grid row per iteration.
+int check_while_grads_sizes(const pfg_lstm *net, int64_t B, int64_t tokens, int32_t max_steps) {
+  int rc = check_while_sizes(net, B, tokens);
+  if (rc) return rc;
+  if (max_steps < 0 || max_steps > (1 << 16))
+    return fail(PFG_ERR_SHAPE, "max_steps = %d is outside [0, %d]", max_steps, 1 << 16);
+  if (B > 65535) return fail(PFG_ERR_UNSUPPORTED, "gradients through the while loop take at most 65535 iterations (%lld given)", (long long)B);
+  const int64_t H = net->state_size, dx = net->input_size;
+  if ((dx + H) * 4 * H > kMaxElems / B || ((int64_t)max_steps + 1) * B > ((int64_t)1 << 31))
+    return fail(PFG_ERR_OVERFLOW, "the tensors of this call exceed the indexing limits");
   return PFG_OK;
 }
 
@@ -426,53 +513,14 @@ int pfg_lstm_while_forward(const pfg_lstm *net, const void *X, const int32_t *se
     return fail(PFG_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, p.total);
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const int32_t dx = net->input_size, H = net->state_size, dy = net->output_size;
-  const float *W = static_cast<const float *>(net->W);
+  const int32_t H = net->state_size, dy = net->output_size;
   void *ws = workspace;
   auto ints = [&](size_t off) { return reinterpret_cast<int32_t *>(static_cast<char *>(ws) + off); };
-
-  // ---- the part in front of the loop: input projections of all tokens in one product (they do not
-  // depend on the recurrence), zero states, the list of all iterations ----
-  if (total_tokens > 0 && max_steps > 0) {
-    GemmArgs g{};
-    g.A = X; g.lda = dx; g.a_batch_stride = dx; g.S = 1; g.a_is_f32 = 1;
-    g.W = W; g.ldw = 4 * H; g.w_kn = 1;
-    g.M = (int32_t)total_tokens; g.N = 4 * H; g.K = dx;
-    g.bias = net->b; g.epilogue = EPI_BIAS;
-    g.C = ws_at(ws, p.zx); g.ldc = 4 * H;
-    PFG_LAUNCH("lstm_gemm_input", launch_gemm(g, stream));
-  }
   float *hbuf[2] = {ws_at(ws, p.state), ws_at(ws, p.state) + B * (int64_t)H};
-  float *c = ws_at(ws, p.state) + 2 * B * (int64_t)H;
-  PFG_LAUNCH("fill_zero", launch_fill_zero(ws_at(ws, p.state), 3 * B * (int64_t)H, stream));
-  int32_t *list[2] = {ints(p.list), ints(p.list) + B};
-  int32_t *meta[2] = {ints(p.meta), ints(p.meta) + 2};
   int32_t *steps = steps_out ? steps_out : ints(p.steps);
-  PFG_LAUNCH("while_select", launch_while_init(list[0], meta[0], steps, trips_out, (int32_t)B, max_steps, stream));
-
-  // ---- the loop: trip t evaluates the condition on the active rows, keeps those that go on, and
-  // runs the cell on them; h_t goes to buffer t % 2 (a trip reads whole rows of h_{t-1} while other
-  // workgroups write h_t), c is updated in place.  Every kernel takes the live row count from
-  // device memory; once the list is empty the remaining trips find nothing to do. ----
-  for (int32_t t = 0; t < max_steps; ++t) {
-    const int cur = t & 1, nxt = cur ^ 1;
-    PFG_LAUNCH("while_select",
-               launch_while_select(list[cur], meta[cur], t, seq_offsets, (int32_t)total_tokens, hbuf[(t + 1) & 1], H,
-                                   halt_w, halt_c, (int32_t)B, ints(p.flags), ints(p.cnt), list[nxt], meta[nxt],
-                                   steps, trips_out, stream));
-    GemmArgs g{};
-    g.A = hbuf[(t + 1) & 1]; g.lda = H; g.a_batch_stride = H; g.S = 1; g.a_is_f32 = 1;
-    g.W = W + (int64_t)dx * 4 * H; g.ldw = 4 * H; g.w_kn = 1;
-    g.M = (int32_t)B; g.N = 4 * H; g.K = H;
-    g.epilogue = EPI_LSTM_FWD;
-    g.lstm_H = H; g.lstm_T = 1; g.lstm_step = t;
-    g.lstm_zx = ws_at(ws, p.zx); g.lstm_zx_rows = seq_offsets;
-    g.lstm_gates_w = nullptr;
-    g.lstm_cs_w = c; g.lstm_hs_w = hbuf[t & 1];
-    g.lstm_state_ld = H; g.lstm_state_ts = 0; g.lstm_has_prev = 1;
-    g.sub = meta[nxt]; g.sub_rows = list[nxt]; g.sub_gather = 1; g.sub_scatter = 0;
-    PFG_LAUNCH("lstm_step", launch_gemm(g, stream));
-  }
+  if ((rc = while_forward_loop(net, X, seq_offsets, B, total_tokens, max_steps, halt_w, halt_c, steps, trips_out, ws, p,
+                               false, stream)))
+    return rc;
 
   // ---- behind the loop: every iteration's last state, then the readout on all rows ----
   float *hfin = h_out ? h_out : ws_at(ws, p.hfin);
@@ -487,6 +535,110 @@ int pfg_lstm_while_forward(const pfg_lstm *net, const void *X, const int32_t *se
     g.C = y_out; g.ldc = dy;
     PFG_LAUNCH("lstm_gemm_readout", launch_gemm(g, stream));
   }
+  return PFG_OK;
+}
+
+int pfg_lstm_while_grads_workspace_bytes(const pfg_lstm *net, int64_t B, int64_t total_tokens, int32_t max_steps,
+                                         size_t *bytes) {
+  clear_error();
+  int rc = check_lstm(net);
+  if (rc) return rc;
+  if (!bytes) return fail(PFG_ERR_NULL, "bytes is NULL");
+  if ((rc = check_while_grads_sizes(net, B, total_tokens, max_steps))) return rc;
+  *bytes = make_while_plan(net, B, total_tokens, (int64_t)max_steps + 1, true).total;
+  return PFG_OK;
+}
+
+int pfg_lstm_while_per_example_grads(const pfg_lstm *net, const void *X, const int32_t *seq_offsets,
+                                     const int32_t *labels, int64_t B, int64_t total_tokens, int32_t max_steps,
+                                     const float *halt_w, float halt_c, float *dW_out, float *db_out,
+                                     float *dWout_out, float *dbout_out, float *loss_out, int32_t *steps_out,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream) {
+  clear_error();
+  int rc = check_lstm(net);
+  if (rc) return rc;
+  if (!X && total_tokens > 0) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!seq_offsets) return fail(PFG_ERR_NULL, "seq_offsets is NULL");
+  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
+  if (!dW_out && !db_out && !dWout_out && !dbout_out && !loss_out)
+    return fail(PFG_ERR_NULL, "dW_out, db_out, dWout_out, dbout_out and loss_out are all NULL");
+  if ((rc = check_while_grads_sizes(net, B, total_tokens, max_steps))) return rc;
+  const WhilePlan p = make_while_plan(net, B, total_tokens, (int64_t)max_steps + 1, true);
+  if (!workspace) return fail(PFG_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", p.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(PFG_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  if (workspace_bytes < p.total)
+    return fail(PFG_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, p.total);
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int32_t dx = net->input_size, H = net->state_size, dy = net->output_size;
+  void *ws = workspace;
+  auto ints = [&](size_t off) { return reinterpret_cast<int32_t *>(static_cast<char *>(ws) + off); };
+  float *hbuf[2] = {ws_at(ws, p.state), ws_at(ws, p.state) + B * (int64_t)H};
+  int32_t *steps = steps_out ? steps_out : ints(p.steps);
+  const bool sweep = dW_out || db_out;      // the reverse trips are needed for the cell's parameters only
+  if ((rc = while_forward_loop(net, X, seq_offsets, B, total_tokens, max_steps, halt_w, halt_c, steps, nullptr, ws, p,
+                               sweep, stream)))
+    return rc;
+
+  // ---- behind the loop: last states, readout, loss head (d ell / d y lands in dbout when given) ----
+  float *hfin = ws_at(ws, p.hfin);
+  PFG_LAUNCH("while_state", launch_while_state(steps, hbuf[0], hbuf[1], B, H, hfin, stream));
+  float *gy = dbout_out ? dbout_out : ws_at(ws, p.gy);
+  {
+    GemmArgs g{};
+    g.A = hfin; g.lda = H; g.a_batch_stride = H; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->W_out; g.ldw = dy; g.w_kn = 1;
+    g.M = (int32_t)B; g.N = dy; g.K = H;
+    g.bias = net->b_out; g.ldc = dy;
+    if (dy <= 32) {
+      g.epilogue = EPI_HEAD; g.C = nullptr; g.C2 = gy; g.labels = labels; g.loss = loss_out;
+      PFG_LAUNCH("lstm_gemm_readout", launch_gemm(g, stream));
+    } else {
+      g.epilogue = EPI_BIAS; g.C = ws_at(ws, p.y);
+      PFG_LAUNCH("lstm_gemm_readout", launch_gemm(g, stream));
+      PFG_LAUNCH("head", launch_head_softmax_ce(ws_at(ws, p.y), labels, B, dy, gy, loss_out, stream));
+    }
+  }
+  if (dWout_out) {
+    OuterArgs o{};
+    o.a = hfin; o.lda = H; o.a_bf16 = 0; o.g = gy; o.ldg = dy; o.out = dWout_out;
+    o.M = B; o.S = 1; o.d_in = H; o.d_out = dy;
+    PFG_LAUNCH("outer_product", launch_outer(&o, 1, stream));
+  }
+  if (!sweep) return PFG_OK;
+
+  // ---- the reverse sweep: dh = (d ell / d y) W_out^T on all rows, dc = 0, then trip t on the list the
+  // forward pass kept for it.  An iteration that made fewer than t + 1 trips is in no list yet: its dh
+  // keeps the seed until its own last trip comes up. ----
+  float *dh = ws_at(ws, p.dh), *dc = ws_at(ws, p.dc), *dz = ws_at(ws, p.dz), *dzp = ws_at(ws, p.dzp);
+  {
+    GemmArgs g{};
+    g.A = gy; g.lda = dy; g.a_batch_stride = dy; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->W_out; g.ldw = dy; g.w_kn = 0;
+    g.M = (int32_t)B; g.N = H; g.K = dy;
+    g.epilogue = EPI_NONE; g.C = dh; g.ldc = H;
+    PFG_LAUNCH("lstm_gemm_cotangent", launch_gemm(g, stream));
+  }
+  PFG_LAUNCH("fill_zero", launch_fill_zero(dc, B * (int64_t)H, stream));
+  const float *Wh = static_cast<const float *>(net->W) + (int64_t)dx * 4 * H;
+  for (int32_t t = max_steps - 1; t >= 0; --t) {
+    const int32_t *I = ints(p.list) + (int64_t)(t + 1) * B, *meta = ints(p.meta) + 2 * (t + 1);
+    PFG_LAUNCH("while_cell_backward",
+               launch_while_cell_backward(I, meta, t, seq_offsets, (int32_t)total_tokens, ws_at(ws, p.gates),
+                                          ws_at(ws, p.cs), dh, dc, dz, dzp, B, H, stream));
+    if (t == 0) break;
+    GemmArgs g{};
+    g.A = dzp; g.lda = 4 * H; g.a_batch_stride = 4 * H; g.S = 1; g.a_is_f32 = 1;
+    g.W = Wh; g.ldw = 4 * H; g.w_kn = 0;
+    g.M = (int32_t)B; g.N = H; g.K = 4 * H;
+    g.epilogue = EPI_NONE; g.C = dh; g.ldc = H;
+    g.sub = meta; g.sub_rows = I; g.sub_gather = 0; g.sub_scatter = 1;
+    PFG_LAUNCH("lstm_gemm_reverse", launch_gemm(g, stream));
+  }
+  // ---- per iteration, the sums over its own trips (the same W acts in every trip) ----
+  PFG_LAUNCH("outer_sum_ragged",
+             launch_outer_sum_ragged(static_cast<const float *>(X), dx, ws_at(ws, p.hs), H, dz, seq_offsets, steps,
+                                     (int32_t)total_tokens, B, dW_out, db_out, stream));
   return PFG_OK;
 }
 

@@ -178,6 +178,8 @@ LSTM_WORKLOADS: Dict[str, LstmWorkload] = {
         LstmWorkload("c9_lstm_varlen", 8, "lstm_varlen_forward", 128, 256, 10, 100, 1024),
         # the same sequences under a loop that also stops on a halting score of the hidden state
         LstmWorkload("c12_lstm_while", 8, "lstm_while_forward", 128, 256, 10, 100, 1024),
+        # per-example gradients through that loop (the same sequences, condition and labels drawn for them)
+        LstmWorkload("c14_lstm_while_grads", 8, "lstm_while_per_example_grads", 128, 256, 10, 100, 1024),
     ]
 }
 
@@ -239,6 +241,9 @@ def make_while_inputs(w: LstmWorkload, **kw):
     halt_w = (rng.standard_normal(H) * 2.0 / np.sqrt(H)).astype(np.float32)
     offsets = np.zeros(lengths.size + 1, dtype=np.int32)
     np.cumsum(lengths, out=offsets[1:])
+    # labels for the gradient workload, from a stream of their own (uniform over the classes)
+    lrng = np.random.Generator(np.random.Philox((BASE_SEED + w.index if seed is None else seed) + 800000))
+    inp.labels = lrng.integers(0, inp.Wout.shape[1], size=(lengths.size,)).astype(np.int32)
     return inp, lengths, offsets, halt_w, -0.5
 
 
