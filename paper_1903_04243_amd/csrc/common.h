@@ -117,6 +117,13 @@ struct GemmArgs {
   // [tokens, 4H], cell state and hidden state [tokens, H] also go to row lstm_zx_rows[m] + step of these
   // (any may be nullptr); register-fed kernel only
   float *lstm_tok_gates, *lstm_tok_c, *lstm_tok_h;
+  // halting score of the new hidden state, in pieces (register-fed kernel with a row list only): the
+  // workgroup that finishes hidden units 8 j .. 8 j + 7 of iteration p stores
+  // sum_k h[p, k] * lstm_halt_w[k] over its units at lstm_score_part[p * lstm_score_ld + j]
+  // (lstm_score_ld >= ceil(H / 8)); whoever needs the score adds the pieces in a fixed order
+  const float *lstm_halt_w;
+  float *lstm_score_part;
+  int32_t lstm_score_ld;
   // a_km == 1: the A operand is stored transposed, [K, M] row-major with row stride lda (row k holds
   // A[0 .. M, k]); a product can then contract over the ROWS of a matrix it also uses row by row
   // elsewhere.  LDS-tiled kernel only; float32, no scale, S == 1, EPI_NONE, M a multiple of 4 and
@@ -372,7 +379,11 @@ hipError_t launch_while_init(int32_t *I, int32_t *meta, int32_t *steps, int32_t 
 hipError_t launch_while_select(const int32_t *I, const int32_t *meta, int32_t t, const int32_t *seq_offsets,
                                int32_t total_tokens, const float *h, int32_t H, const float *w, float c0,
                                int32_t B, int32_t *flags, int32_t *cnt, int32_t *I_next, int32_t *meta_next,
-                               int32_t *steps, int32_t *trips, hipStream_t stream);
+                               int32_t *steps, int32_t *trips, hipStream_t stream,
+                               const float *score_part = nullptr, int32_t score_ld = 0);
+// Lists of at most this many rows can take their halting scores in pieces from the step kernel
+// (GemmArgs::lstm_score_part): condition and compaction are then one launch of one workgroup.
+constexpr int kWhileOneLaunchRows = 1024;
 hipError_t launch_while_state(const int32_t *steps, const float *h_even, const float *h_odd, int64_t B, int32_t H,
                               float *h_out, hipStream_t stream);
 // Reverse trip t on the rows of list I (meta[0] of them): cell backward from dh [B, H] and dc [B, H]

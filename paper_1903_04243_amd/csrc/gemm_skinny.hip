@@ -290,6 +290,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   // latency of every dependent global access counts.
   if constexpr (LSTM && WKN) {
     if (lstm_fwd) {
+      float score_piece = 0.f;       // this cell's share of the halting score of its row
       if (lstm_live) {
         const int H = g.lstm_H, T = g.lstm_T, t = g.lstm_step;
         const int r = tid >> 3, u = tid & 7;
@@ -320,6 +321,16 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
           }
           if (g.lstm_tok_c) g.lstm_tok_c[zr * H + lstm_k] = c;
           if (g.lstm_tok_h) g.lstm_tok_h[zr * H + lstm_k] = hnew;
+        }
+        if (SUB && g.lstm_score_part) score_piece = hnew * g.lstm_halt_w[lstm_k];
+      }
+      if constexpr (SUB) {
+        // the eight cells of a row that this workgroup finished sit in eight neighbouring lanes: their
+        // shares are added in a fixed pattern and the first lane stores the piece
+        if (g.lstm_score_part && tid < 256) {
+#pragma unroll
+          for (int off = 4; off > 0; off >>= 1) score_piece += __shfl_xor(score_piece, off, 8);
+          if ((tid & 7) == 0 && lstm_m < M) g.lstm_score_part[lstm_p * g.lstm_score_ld + second] = score_piece;
         }
       }
       return;

@@ -146,6 +146,57 @@ __global__ __launch_bounds__(kPlace) void while_place_kernel(const int32_t *flag
   }
 }
 
+// Condition and compaction of trip t in one workgroup, for lists of at most kPlace rows whose halting
+// scores arrive in pieces (part[i * nparts + j], j < nparts, written by the step kernel of trip t - 1;
+// all zero before the first trip).  Row m of the list: score = c0 + the pieces of iteration I[m] added
+// in increasing j; the rest as in the two kernels above.
+__global__ __launch_bounds__(kPlace) void while_select_one_kernel(const int32_t *I, const int32_t *meta, int t,
+                                                                  const int32_t *seq_offsets, int total_tokens,
+                                                                  const float *part, int nparts, float c0,
+                                                                  int32_t *I_next, int32_t *meta_next,
+                                                                  int32_t *steps, int32_t *trips) {
+  constexpr int kWaves = kPlace / 64;
+  __shared__ int s_wave[kWaves];
+  const int l = min(meta[0], kPlace);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int f = 0, i = 0;
+  if (tid < l) {
+    i = I[tid];
+    float s = 0.f;
+    if (part) {
+      const float *row = part + (int64_t)i * nparts;
+      if ((nparts & 3) == 0 && (reinterpret_cast<uintptr_t>(part) & 15) == 0) {
+        for (int j = 0; j < nparts; j += 4) {
+          const f32x4 v = *reinterpret_cast<const f32x4 *>(row + j);
+          s += v[0]; s += v[1]; s += v[2]; s += v[3];
+        }
+      } else {
+        for (int j = 0; j < nparts; ++j) s += row[j];
+      }
+    }
+    const int lo = seq_offsets[i], hi = min(seq_offsets[i + 1], total_tokens);
+    const int len = (lo >= 0 && hi > lo) ? hi - lo : 0;
+    f = (t < len && s + c0 <= 0.f) ? 1 : 0;
+    if (!f) steps[i] = t;
+  }
+  const unsigned long long set = __ballot(f != 0);
+  const int rank_in_wave = __popcll(set & ((1ull << lane) - 1ull));
+  if (lane == 0) s_wave[wave] = __popcll(set);
+  __syncthreads();
+  int kept_before = 0, kept = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    kept += s_wave[w];
+    if (w < wave) kept_before += s_wave[w];
+  }
+  if (f) I_next[kept_before + rank_in_wave] = i;
+  if (tid == 0) {
+    meta_next[0] = kept;
+    meta_next[1] = 0;
+    if (trips && kept > 0) *trips = t + 1;
+  }
+}
+
 // h_out[i, :] = the state iteration i left the loop with: zero after no trip, else the buffer its
 // last trip wrote (trip t writes buffer t % 2).
 __global__ __launch_bounds__(256) void while_state_kernel(const int32_t *steps, const float *h_even,
@@ -198,102 +249,114 @@ __global__ __launch_bounds__(256) void while_cell_backward_kernel(const int32_t 
 //   dW[b, dx:dx+H, :]   = sum_{1 <= t < T_b} h[r_b + t - 1, :]^T dz[r_b + t, :]      (h before trip 0 is zero)
 //   db[b, :]            = sum_{t < T_b} dz[r_b + t, :]
 // with r_b the iteration's first token row and T_b = steps[b] its trip count (both from device
-// memory, cut to the iteration's token range).  A workgroup takes kRaggedRows rows of one iteration's
-// matrix and up to 1024 columns; a lane keeps its four columns of kRaggedRun cotangent rows in
-// registers at a time and the a-values of the run go through LDS (uniform over the workgroup).  The
-// result is written once, also when T_b = 0 (zeros).
-constexpr int kRaggedRows = 8;
-constexpr int kRaggedRun = 16;
+// memory, cut to the iteration's token range).  Per iteration this is a product
+// [x | h_prev]^T [dx + H, T_b] times dz [T_b, 4H] whose contraction length differs from iteration to
+// iteration: it runs on the matrix cores (v_mfma_f32_32x32x2_f32, two trips per instruction).
+//
+// A workgroup of four waves takes 32 rows of one iteration's matrix and 512 columns, a wave 128 of
+// them as four 32 x 32 tiles whose columns interleave: lane l32 feeds columns base + 4 l32 + e to
+// tile e, so its cotangent values of a trip are one 16-byte load and register r of the four tiles
+// holds four neighbouring columns of one output row, one 16-byte store.  The operands of the next
+// eight trips are requested before the MFMAs of the current eight.  The result is written once, also
+// when T_b = 0 (zeros).  The bias row is a plain sum in workgroups of its own.
+constexpr int kRagGroup = 4;      // MFMA k-steps (of two trips) per register set
 
 struct RaggedSumArgs {
   const float *x; int dx;
   const float *h_tok; int H;
-  const float *dz_tok;           // [tokens, d_out]
+  const float *dz_tok;           // [tokens, d_out], 16-byte aligned rows
   const int32_t *seq_offsets;    // [B + 1]
   const int32_t *steps;          // [B]
   int total_tokens;
   float *dW;                     // [B, dx + H, d_out] or nullptr
   float *db;                     // [B, d_out] or nullptr
-  int d_out;
+  int d_out;                     // 4H
   int vec;                       // 16-byte stores allowed (alignment of dW, db)
+  int mm_blocks;                 // workgroups per iteration that work on dW; the rest sum the bias row
 };
 
 __global__ __launch_bounds__(256) void outer_sum_ragged_kernel(const RaggedSumArgs p) {
-  __shared__ __align__(16) float a_s[kRaggedRows][kRaggedRun];
   const int64_t b = blockIdx.y;
-  const int col_chunks = (p.d_out + 1023) / 1024;
-  const int cchunk = blockIdx.x % col_chunks;
-  int rchunk = blockIdx.x / col_chunks;
-  const int chunks_x = (p.dx + kRaggedRows - 1) / kRaggedRows, chunks_h = (p.H + kRaggedRows - 1) / kRaggedRows;
-  // part 0: input rows, 1: recurrent rows, 2: the bias row
-  int part = 0;
-  if (!p.dW) { part = 2; rchunk = 0; }
-  else if (rchunk >= chunks_x + chunks_h) { part = 2; rchunk = 0; }
-  else if (rchunk >= chunks_x) { part = 1; rchunk -= chunks_x; }
-  const int d_in = part == 0 ? p.dx : part == 1 ? p.H : 1;
-  const int i0 = rchunk * kRaggedRows;
-  const int nrows = min(d_in - i0, kRaggedRows);
   const int lo = p.seq_offsets[b], hi = min(p.seq_offsets[b + 1], p.total_tokens);
   const int len = (lo >= 0 && hi > lo) ? hi - lo : 0;
   const int nt = max(0, min(p.steps[b], len));
-  const int j = (cchunk * 256 + threadIdx.x) * 4;
-  f32x4 acc[kRaggedRows];
-#pragma unroll
-  for (int r = 0; r < kRaggedRows; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int t0 = 0; t0 < nt; t0 += kRaggedRun) {
-    __syncthreads();                       // the previous run's values have been used
-    if (threadIdx.x < kRaggedRows * kRaggedRun) {
-      const int tt = threadIdx.x / kRaggedRows, r = threadIdx.x % kRaggedRows;
-      const int t = t0 + tt;
-      float v = 0.f;
-      if (t < nt && r < nrows) {
-        if (part == 0) v = p.x[(int64_t)(lo + t) * p.dx + i0 + r];
-        else if (part == 1) v = t > 0 ? p.h_tok[(int64_t)(lo + t - 1) * p.H + i0 + r] : 0.f;
-        else v = 1.f;
-      }
-      a_s[r][tt] = v;
-    }
-    __syncthreads();
-    if (j < p.d_out) {
-      f32x4 gv[kRaggedRun];
-#pragma unroll
-      for (int tt = 0; tt < kRaggedRun; ++tt) {
-        gv[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (t0 + tt < nt) {
-          const float *g = p.dz_tok + (int64_t)(lo + t0 + tt) * p.d_out + j;
-          if (j + 4 <= p.d_out && (p.d_out & 3) == 0) {
-            gv[tt] = *reinterpret_cast<const f32x4 *>(g);
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (j + e < p.d_out) gv[tt][e] = g[e];
-          }
-        }
-      }
-#pragma unroll
-      for (int r = 0; r < kRaggedRows; ++r) {
-#pragma unroll
-        for (int t4 = 0; t4 < kRaggedRun; t4 += 4) {
-          const f32x4 av = *reinterpret_cast<const f32x4 *>(&a_s[r][t4]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) acc[r] += av[e] * gv[t4 + e];
-        }
-      }
-    }
-  }
-  if (j >= p.d_out) return;
-  float *out = part == 2 ? p.db + b * (int64_t)p.d_out
-                         : p.dW + (b * (int64_t)(p.dx + p.H) + (part == 1 ? p.dx : 0) + i0) * p.d_out;
-#pragma unroll
-  for (int r = 0; r < kRaggedRows; ++r) {
-    if (r >= nrows) break;
-    float *o = out + (int64_t)r * p.d_out + j;
-    if (p.vec && j + 4 <= p.d_out) {
-      __builtin_nontemporal_store(acc[r], reinterpret_cast<f32x4 *>(o));
+  const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+
+  if ((int)blockIdx.x >= p.mm_blocks) {
+    // ---- bias row: 1024 columns per workgroup, four per lane ----
+    const int j = (((int)blockIdx.x - p.mm_blocks) * 256 + threadIdx.x) * 4;
+    if (j >= p.d_out) return;
+    f32x4 s = zero4;
+    for (int t = 0; t < nt; ++t) s += *reinterpret_cast<const f32x4 *>(p.dz_tok + (int64_t)(lo + t) * p.d_out + j);
+    float *o = p.db + b * (int64_t)p.d_out + j;
+    if (p.vec) {
+      *reinterpret_cast<f32x4 *>(o) = s;
     } else {
 #pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = s[e];
+    }
+    return;
+  }
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, half = lane >> 5;
+  const int col_chunks = (p.d_out + 511) / 512;
+  const int cchunk = blockIdx.x % col_chunks, rtile = blockIdx.x / col_chunks;
+  const int R = p.dx + p.H;
+  const int row = rtile * 32 + l32;                        // the row of [x | h_prev] this lane feeds
+  const int col = cchunk * 512 + wave * 128 + 4 * l32;     // the first of this lane's four columns
+  const bool col_in = col < p.d_out;                       // d_out and col are multiples of 4
+  // the operand values of trip t: this lane's row of [x_t | h_{t-1}] and its four columns of dz_t
+  const float *arow = row < p.dx ? p.x + (int64_t)lo * p.dx + row
+                                 : p.h_tok + (int64_t)lo * p.H + (row - p.dx);
+  const int64_t astride = row < p.dx ? p.dx : p.H;
+  const int t_first = row < p.dx ? 0 : 1;                  // trip t pairs dz_t with h_{t-1}; h before trip 0 is zero
+  const bool row_in = row < R;
+  const float *grow = p.dz_tok + (int64_t)lo * p.d_out + col;
+  auto fetch = [&](int t0, float (&a)[kRagGroup], f32x4 (&g)[kRagGroup]) {
+#pragma unroll
+    for (int s = 0; s < kRagGroup; ++s) {
+      const int t = t0 + 2 * s + half;
+      a[s] = (row_in && t < nt && t >= t_first) ? arow[(t - t_first) * astride] : 0.f;
+      g[s] = (col_in && t < nt) ? *reinterpret_cast<const f32x4 *>(grow + (int64_t)t * p.d_out) : zero4;
+    }
+  };
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[e][r] = 0.f;
+  float a_cur[kRagGroup], a_nxt[kRagGroup];
+  f32x4 g_cur[kRagGroup], g_nxt[kRagGroup];
+  if (nt > 0) fetch(0, a_cur, g_cur);
+  for (int t0 = 0; t0 < nt; t0 += 2 * kRagGroup) {
+    fetch(t0 + 2 * kRagGroup, a_nxt, g_nxt);               // past the last trip: zeros, nothing is read
+#pragma unroll
+    for (int s = 0; s < kRagGroup; ++s)
+#pragma unroll
       for (int e = 0; e < 4; ++e)
-        if (j + e < p.d_out) o[e] = acc[r][e];
+        acc[e] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[s], g_cur[s][e], acc[e], 0, 0, 0);
+#pragma unroll
+    for (int s = 0; s < kRagGroup; ++s) {
+      a_cur[s] = a_nxt[s];
+      g_cur[s] = g_nxt[s];
+    }
+  }
+
+  if (!col_in) return;
+  // register r of a tile is row 8 (r / 4) + 4 half + r % 4 of the tile, column l32
+  float *out = p.dW + (b * (int64_t)R + rtile * 32) * p.d_out + col;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int i = 8 * (r >> 2) + 4 * half + (r & 3);
+    if (rtile * 32 + i >= R) continue;
+    const f32x4 v = {acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+    float *o = out + (int64_t)i * p.d_out;
+    if (p.vec) {
+      __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(o));
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = v[e];
     }
   }
 }
@@ -312,7 +375,14 @@ hipError_t launch_while_init(int32_t *I, int32_t *meta, int32_t *steps, int32_t 
 hipError_t launch_while_select(const int32_t *I, const int32_t *meta, int32_t t, const int32_t *seq_offsets,
                                int32_t total_tokens, const float *h, int32_t H, const float *w, float c0,
                                int32_t B, int32_t *flags, int32_t *cnt, int32_t *I_next, int32_t *meta_next,
-                               int32_t *steps, int32_t *trips, hipStream_t stream) {
+                               int32_t *steps, int32_t *trips, hipStream_t stream, const float *score_part,
+                               int32_t score_ld) {
+  static_assert(kWhileOneLaunchRows == kPlace, "the one-launch selection places its rows in one workgroup");
+  if (B <= kPlace && (score_part || !w)) {
+    PFG_KERNEL(while_select_one_kernel, dim3(1), dim3(kPlace), 0, stream, I, meta, t, seq_offsets, total_tokens,
+               w ? score_part : nullptr, score_ld, c0, I_next, meta_next, steps, trips);
+    return hipGetLastError();
+  }
   const int ngroups = (B + kGroup - 1) / kGroup, nblocks = (B + kPlace - 1) / kPlace;
   PFG_KERNEL(while_flags_kernel, dim3((unsigned)ngroups), dim3(256), 0, stream, I, meta, t, seq_offsets,
              total_tokens, h, H, w, c0, flags, cnt, steps);
@@ -349,16 +419,16 @@ hipError_t launch_outer_sum_ragged(const float *x, int32_t dx, const float *h_to
                                    const int32_t *seq_offsets, const int32_t *steps, int32_t total_tokens, int64_t B,
                                    float *dW, float *db, hipStream_t stream) {
   if (!dW && !db) return hipSuccess;
-  if (B > 65535) return hipErrorInvalidConfiguration;
+  if (B > 65535 || (reinterpret_cast<uintptr_t>(dz_tok) & 15)) return hipErrorInvalidConfiguration;
   RaggedSumArgs p{};
   p.x = x; p.dx = dx; p.h_tok = h_tok; p.H = H; p.dz_tok = dz_tok;
   p.seq_offsets = seq_offsets; p.steps = steps; p.total_tokens = total_tokens;
   p.dW = dW; p.db = db; p.d_out = 4 * H;
   p.vec = (((reinterpret_cast<uintptr_t>(dW) | reinterpret_cast<uintptr_t>(db)) & 15) == 0) ? 1 : 0;
-  const int col_chunks = (p.d_out + 1023) / 1024;
-  const int chunks_x = (dx + kRaggedRows - 1) / kRaggedRows, chunks_h = (H + kRaggedRows - 1) / kRaggedRows;
-  const int row_chunks = dW ? chunks_x + chunks_h + (db ? 1 : 0) : 1;
-  PFG_KERNEL(outer_sum_ragged_kernel, dim3((unsigned)(col_chunks * row_chunks), (unsigned)B), dim3(256), 0, stream, p);
+  const int col_chunks = (p.d_out + 511) / 512, row_tiles = (dx + H + 31) / 32;
+  p.mm_blocks = dW ? col_chunks * row_tiles : 0;
+  const int bias_blocks = db ? (p.d_out + 1023) / 1024 : 0;
+  PFG_KERNEL(outer_sum_ragged_kernel, dim3((unsigned)(p.mm_blocks + bias_blocks), (unsigned)B), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 

@@ -216,7 +216,8 @@ VarlenPlan make_varlen_plan(const pfg_lstm *net, int64_t B, int64_t tokens) {
 
 struct WhilePlan {
   size_t total = 0;
-  size_t zx = 0, state = 0, hfin = 0, list = 0, meta = 0, flags = 0, cnt = 0, steps = 0;
+  size_t zx = 0, state = 0, score = 0, hfin = 0, list = 0, meta = 0, flags = 0, cnt = 0, steps = 0;
+  size_t zeroed = 0;      // floats from `state` on that the call zeroes in front of the loop
   // gradients only: history by token row, cotangents, head
   size_t gates = 0, cs = 0, hs = 0, dz = 0, dzp = 0, dh = 0, dc = 0, y = 0, gy = 0;
   size_t take(size_t bytes) {
@@ -234,6 +235,10 @@ WhilePlan make_while_plan(const pfg_lstm *net, int64_t B, int64_t tokens, int64_
   WhilePlan p;
   p.zx = p.take(f * tok * 4 * H);
   p.state = p.take(f * 3 * B * H);          // h (two buffers used alternately) and c, zeroed together
+  // pieces of the halting score, one per group of 8 hidden units (lists of few rows only; zeroed with the state)
+  const size_t pieces = B <= kWhileOneLaunchRows ? (size_t)B * ((H + 7) / 8) : 0;
+  p.score = p.take(f * pieces);
+  p.zeroed = (p.score + f * pieces - p.state) / f;
   p.hfin = p.take(f * B * H);               // last states, if h_out is not given
   p.list = p.take(i * lists * B);
   p.meta = p.take(i * 2 * lists);           // their {length, 0} descriptors
@@ -290,7 +295,11 @@ int while_forward_loop(const pfg_lstm *net, const void *X, const int32_t *seq_of
   }
   float *hbuf[2] = {ws_at(ws, p.state), ws_at(ws, p.state) + B * (int64_t)H};
   float *c = ws_at(ws, p.state) + 2 * B * (int64_t)H;
-  PFG_LAUNCH("fill_zero", launch_fill_zero(ws_at(ws, p.state), 3 * B * (int64_t)H, stream));
+  PFG_LAUNCH("fill_zero", launch_fill_zero(ws_at(ws, p.state), (int64_t)p.zeroed, stream));
+  // few rows and a condition on the state: the step kernel leaves the halting score of its new state in
+  // pieces, and condition plus compaction of the next trip are one launch
+  const bool pieces = halt_w && B <= kWhileOneLaunchRows;
+  const int32_t nparts = (H + 7) / 8;
   auto list = [&](int32_t q) { return ints(p.list) + (keep ? q : (q & 1)) * B; };
   auto meta = [&](int32_t q) { return ints(p.meta) + 2 * (keep ? q : (q & 1)); };
   PFG_LAUNCH("while_select", launch_while_init(list(0), meta(0), steps, trips_out, (int32_t)B, max_steps, stream));
@@ -303,7 +312,7 @@ int while_forward_loop(const pfg_lstm *net, const void *X, const int32_t *seq_of
     PFG_LAUNCH("while_select",
                launch_while_select(list(t), meta(t), t, seq_offsets, (int32_t)total_tokens, hbuf[(t + 1) & 1], H,
                                    halt_w, halt_c, (int32_t)B, ints(p.flags), ints(p.cnt), list(t + 1), meta(t + 1),
-                                   steps, trips_out, stream));
+                                   steps, trips_out, stream, pieces ? ws_at(ws, p.score) : nullptr, nparts));
     GemmArgs g{};
     g.A = hbuf[(t + 1) & 1]; g.lda = H; g.a_batch_stride = H; g.S = 1; g.a_is_f32 = 1;
     g.W = W + (int64_t)dx * 4 * H; g.ldw = 4 * H; g.w_kn = 1;
@@ -316,6 +325,9 @@ int while_forward_loop(const pfg_lstm *net, const void *X, const int32_t *seq_of
     g.lstm_state_ld = H; g.lstm_state_ts = 0; g.lstm_has_prev = 1;
     if (keep) {
       g.lstm_tok_gates = ws_at(ws, p.gates); g.lstm_tok_c = ws_at(ws, p.cs); g.lstm_tok_h = ws_at(ws, p.hs);
+    }
+    if (pieces) {
+      g.lstm_halt_w = halt_w; g.lstm_score_part = ws_at(ws, p.score); g.lstm_score_ld = nparts;
     }
     g.sub = meta(t + 1); g.sub_rows = list(t + 1); g.sub_gather = 1; g.sub_scatter = 0;
     PFG_LAUNCH("lstm_step", launch_gemm(g, stream));
