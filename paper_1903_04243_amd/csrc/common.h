@@ -105,6 +105,15 @@ struct GemmArgs {
   float *lstm_dc;            // [M, H] running cotangent of the cell state, updated in place
   float *lstm_dz;            // row m at lstm_dz + m * lstm_dz_ld, 4H wide: dz of step lstm_step
   int64_t lstm_dz_ld;
+  // EPI_LSTM_BWD on rows chosen on the device (register-fed kernel, sub_gather set, no scatter): row m
+  // of the product is iteration p = sub_rows[sub[1] + m]; its gate values and cell states are read at
+  // token row lstm_zx_rows[p] + lstm_step of lstm_gates [tokens, 4H] and lstm_cs [tokens, H], lstm_dc
+  // and lstm_dz are indexed by p, the same dz also goes to that token row of lstm_tok_dz (if given),
+  // and lstm_seed[p, :] is added to the product where lstm_steps[p] == lstm_step + 1 (the trip is the
+  // iteration's last: it enters the reverse loop here)
+  float *lstm_tok_dz;
+  const float *lstm_seed;
+  const int32_t *lstm_steps;
   // EPI_LSTM_FWD (M rows, one per active sequence)
   const float *lstm_zx;         // x_t W_x + b, 4H wide rows; row of (m, step): lstm_zx_rows ?
   const int32_t *lstm_zx_rows;  //   lstm_zx_rows[m] + step (sequences stored back to back) : m * T + step
@@ -386,13 +395,6 @@ hipError_t launch_while_select(const int32_t *I, const int32_t *meta, int32_t t,
 constexpr int kWhileOneLaunchRows = 1024;
 hipError_t launch_while_state(const int32_t *steps, const float *h_even, const float *h_odd, int64_t B, int32_t H,
                               float *h_out, hipStream_t stream);
-// Reverse trip t on the rows of list I (meta[0] of them): cell backward from dh [B, H] and dc [B, H]
-// (rows by iteration; dc updated in place) with the gate values and cell states kept by token row;
-// dz goes to token row (first token of I[m]) + t of dz_tok [tokens, 4H] and to row m of dz_packed.
-hipError_t launch_while_cell_backward(const int32_t *I, const int32_t *meta, int32_t t, const int32_t *seq_offsets,
-                                      int32_t total_tokens, const float *gates_tok, const float *c_tok,
-                                      const float *dh, float *dc, float *dz_tok, float *dz_packed, int64_t B,
-                                      int32_t H, hipStream_t stream);
 // dW[b] = sum over the steps[b] trips of iteration b of [x_t, h_{t-1}]^T dz_t, db[b] = sum of dz_t (rows by
 // token: iteration b starts at seq_offsets[b]; h before trip 0 is zero); dW [B, dx + H, 4H], db [B, 4H],
 // either may be nullptr.  B <= 65535.

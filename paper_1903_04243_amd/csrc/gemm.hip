@@ -943,8 +943,9 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
     return hipErrorInvalidValue;
   if (g.sub && (g.bf16 || !g.a_is_f32 || g.S != 1 || g.nbatch > 1 || g.sym_n > 0 || g.a_scale ||
                 (g.epilogue != EPI_NONE && g.epilogue != EPI_BIAS && g.epilogue != EPI_FORWARD &&
-                 g.epilogue != EPI_MASK && g.epilogue != EPI_LSTM_FWD) ||
-                (!g.w_kn && g.epilogue != EPI_NONE && g.epilogue != EPI_MASK) ||
+                 g.epilogue != EPI_MASK && g.epilogue != EPI_LSTM_FWD && g.epilogue != EPI_LSTM_BWD) ||
+                (!g.w_kn && g.epilogue != EPI_NONE && g.epilogue != EPI_MASK && g.epilogue != EPI_LSTM_BWD) ||
+                (g.w_kn && g.epilogue == EPI_LSTM_BWD) ||
                 ((g.sub_gather || g.sub_scatter) && !g.sub_rows)))
     return hipErrorInvalidValue;
   if (!g.sub && (g.sub_gather || g.sub_scatter)) return hipErrorInvalidValue;
@@ -973,7 +974,8 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
   // against 784 x 512 weights: 31 against 45 us; from about 200 tiles on the tiled kernel is level)
   const bool few_tiles = (tiles64 < 128 && g.nbatch < 8) ||
                          (tiles64 < 192 && g.nbatch <= 1 && !g.bf16 && g.a_is_f32 && g.sym_n == 0);
-  if (g.epilogue == EPI_HEAD || g.epilogue == EPI_LSTM_FWD || few_tiles || narrow || small16_batched_applies(g))
+  if (g.epilogue == EPI_HEAD || g.epilogue == EPI_LSTM_FWD || (g.epilogue == EPI_LSTM_BWD && g.sub) || few_tiles ||
+      narrow || small16_batched_applies(g))
     return launch_gemm_skinny(g, stream);
   if (!g.bf16) {
     return g.w_kn ? launch_tiles<A_F32, true>(g, stream) : launch_tiles<A_F32, false>(g, stream);

@@ -47,15 +47,26 @@ __device__ __forceinline__ float act_deriv2(int act, float z) {
 //   dz_i  = dc * g * i (1 - i),  dz_g = dc * i * (1 - g^2),  dz_f = dc * c_{t-1} * f (1 - f)
 //   dc_{t-1} = dc * f
 // The same update on values already in registers.
-struct LstmCellIn { float i, g, f, o, c, cprev, dc; };
+// seed: added to the cotangent of the hidden state before the update (an iteration of a while loop
+// enters the reverse loop at its own last trip with the cotangent of its final state)
+struct LstmCellIn { float i, g, f, o, c, cprev, dc, seed; };
+// dz_row2 (may be nullptr): a second row that receives the same four values
 __device__ __forceinline__ void lstm_reverse_cell_store(const LstmCellIn &v, float dh, float *dz_row,
-                                                        float *dcp, int H, int k) {
+                                                        float *dcp, int H, int k, float *dz_row2 = nullptr) {
   const float tc = tanhf(v.c);
   const float dct = v.dc + dh * v.o * (1.f - tc * tc);
-  dz_row[k] = dct * v.g * v.i * (1.f - v.i);
-  dz_row[H + k] = dct * v.i * (1.f - v.g * v.g);
-  dz_row[2 * H + k] = dct * v.cprev * v.f * (1.f - v.f);
-  dz_row[3 * H + k] = dh * tc * v.o * (1.f - v.o);
+  const float zi = dct * v.g * v.i * (1.f - v.i), zg = dct * v.i * (1.f - v.g * v.g);
+  const float zf = dct * v.cprev * v.f * (1.f - v.f), zo = dh * tc * v.o * (1.f - v.o);
+  dz_row[k] = zi;
+  dz_row[H + k] = zg;
+  dz_row[2 * H + k] = zf;
+  dz_row[3 * H + k] = zo;
+  if (dz_row2) {
+    dz_row2[k] = zi;
+    dz_row2[H + k] = zg;
+    dz_row2[2 * H + k] = zf;
+    dz_row2[3 * H + k] = zo;
+  }
   *dcp = dct * v.f;
 }
 

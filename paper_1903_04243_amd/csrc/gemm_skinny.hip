@@ -216,13 +216,24 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   // EPI_LSTM_BWD: the gate values, cell states and running dc of this thread's Q elements are
   // requested ahead of the contraction too
   LstmCellIn lb0{}, lb1{}, lb2{}, lb3{};
+  // the row that owns dc and dz (SUB: the iteration behind row m of the list) and, with SUB, the
+  // token row of its trip lstm_step, where the gate values and cell states were kept
+  int64_t bwd_p = m, bwd_tok = 0;
   if constexpr (LSTM && !WKN) {
     if (epi == EPI_LSTM_BWD && row_in) {
       const int H = g.lstm_H, T = g.lstm_T, t = g.lstm_step;
-      const int64_t b = m / g.S;
-      const float *grow = g.lstm_gates + (b * T + t) * 4 * (int64_t)H;
-      const float *crow = g.lstm_cs + (b * T + t) * (int64_t)H;
-      const float *dcrow = g.lstm_dc + (int64_t)m * H;
+      int64_t hist = (int64_t)(m / g.S) * T + t;          // row of the gate and cell-state history
+      if constexpr (SUB) {
+        bwd_p = g.sub_rows[sub_off + m];
+        bwd_tok = hist = (int64_t)g.lstm_zx_rows[bwd_p] + t;
+      }
+      const float *grow = g.lstm_gates + hist * 4 * (int64_t)H;
+      const float *crow = g.lstm_cs + hist * (int64_t)H;
+      const float *dcrow = g.lstm_dc + bwd_p * H;
+      const float *seedrow = nullptr;
+      if constexpr (SUB) {
+        if (g.lstm_seed && g.lstm_steps[bwd_p] == t + 1) seedrow = g.lstm_seed + bwd_p * H;
+      }
       auto fetch = [&](int q, LstmCellIn &v) {
         const int k = nn + q - g.n_split;
         if (k < 0 || nn + q >= N) return;
@@ -230,6 +241,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
         v.c = crow[k];
         v.cprev = t > 0 ? crow[k - H] : 0.f;
         v.dc = dcrow[k];
+        if (SUB && seedrow) v.seed = seedrow[k];
       };
       fetch(0, lb0);
       fetch(1, lb1);
@@ -378,8 +390,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
             g.C[off + q] = val;
           } else {
             const int k = nn + q - g.n_split;
-            lstm_reverse_cell_store(in, val, g.lstm_dz + (int64_t)m * g.lstm_dz_ld,
-                                    g.lstm_dc + (int64_t)m * g.lstm_H + k, g.lstm_H, k);
+            float *row2 = (SUB && g.lstm_tok_dz) ? g.lstm_tok_dz + bwd_tok * 4 * g.lstm_H : nullptr;
+            lstm_reverse_cell_store(in, SUB ? val + in.seed : val, g.lstm_dz + bwd_p * g.lstm_dz_ld,
+                                    g.lstm_dc + bwd_p * g.lstm_H + k, g.lstm_H, k, row2);
           }
         };
         finish(0, v[0], lb0);
@@ -492,6 +505,19 @@ hipError_t launch_nw(const GemmArgs &g, hipStream_t stream) {
     if (g.epilogue == EPI_LSTM_FWD && g.sub) {
       // the fused LSTM step on the rows of a device-side list
       if (fast_loads_ok(g, false))
+        PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, true, true, true>), dim3((unsigned)tiles),
+                   dim3(64 * NW), 0, stream, g);
+      else
+        PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, false, true, true>), dim3((unsigned)tiles),
+                   dim3(64 * NW), 0, stream, g);
+      return hipGetLastError();
+    }
+  }
+  if constexpr (AMODE == A_F32 && !WKN) {
+    if (g.epilogue == EPI_LSTM_BWD && g.sub) {
+      // a reverse trip of a while loop on the rows of the list the forward loop kept for it
+      if (!g.sub_gather || g.sub_scatter || !g.lstm_zx_rows) return hipErrorInvalidValue;
+      if (fast_loads_ok(g, true))
         PFG_KERNEL((gemm_skinny_kernel<AMODE, WKN, NW, true, true, true>), dim3((unsigned)tiles),
                    dim3(64 * NW), 0, stream, g);
       else

@@ -250,9 +250,9 @@ WhilePlan make_while_plan(const pfg_lstm *net, int64_t B, int64_t tokens, int64_
     p.cs = p.take(f * tok * H);
     p.hs = p.take(f * tok * H);
     p.dz = p.take(f * tok * 4 * H);
-    p.dzp = p.take(f * B * 4 * H);
-    p.dh = p.take(f * 2 * B * H);           // dh and dc, side by side
-    p.dc = p.dh + f * B * H;
+    p.dh = p.take(f * B * H);               // cotangent of every iteration's final state
+    p.dc = p.take(f * (B * H + 2 * B * 4 * H));   // dc, then dz by iteration (two buffers): zeroed together
+    p.dzp = p.dc + f * B * H;
     p.y = p.take(f * B * net->output_size);
     p.gy = p.take(f * B * net->output_size);
   }
@@ -619,32 +619,35 @@ int pfg_lstm_while_per_example_grads(const pfg_lstm *net, const void *X, const i
   }
   if (!sweep) return PFG_OK;
 
-  // ---- the reverse sweep: dh = (d ell / d y) W_out^T on all rows, dc = 0, then trip t on the list the
-  // forward pass kept for it.  An iteration that made fewer than t + 1 trips is in no list yet: its dh
-  // keeps the seed until its own last trip comes up. ----
-  float *dh = ws_at(ws, p.dh), *dc = ws_at(ws, p.dc), *dz = ws_at(ws, p.dz), *dzp = ws_at(ws, p.dzp);
+  // ---- the reverse sweep.  Every iteration enters it at its own last trip with the cotangent of its
+  // final state, dh = (d ell / d y) W_out^T, and dc = 0.  Reverse trip t runs on the list the forward
+  // loop kept for trip t: one product carries dz_{t+1} W_h^T to the rows of that list (dz by iteration,
+  // two buffers used alternately; the row of an iteration that made no trip t + 1 is still zero), and
+  // its epilogue adds the seed where trip t is the iteration's last, updates dc and writes dz_t. ----
+  float *seed = ws_at(ws, p.dh), *dc = ws_at(ws, p.dc), *dz = ws_at(ws, p.dz);
+  float *dzi[2] = {ws_at(ws, p.dzp), ws_at(ws, p.dzp) + B * (int64_t)4 * H};
   {
     GemmArgs g{};
     g.A = gy; g.lda = dy; g.a_batch_stride = dy; g.S = 1; g.a_is_f32 = 1;
     g.W = net->W_out; g.ldw = dy; g.w_kn = 0;
     g.M = (int32_t)B; g.N = H; g.K = dy;
-    g.epilogue = EPI_NONE; g.C = dh; g.ldc = H;
+    g.epilogue = EPI_NONE; g.C = seed; g.ldc = H;
     PFG_LAUNCH("lstm_gemm_cotangent", launch_gemm(g, stream));
   }
-  PFG_LAUNCH("fill_zero", launch_fill_zero(dc, B * (int64_t)H, stream));
+  PFG_LAUNCH("fill_zero", launch_fill_zero(dc, B * (int64_t)H * 9, stream));
   const float *Wh = static_cast<const float *>(net->W) + (int64_t)dx * 4 * H;
   for (int32_t t = max_steps - 1; t >= 0; --t) {
-    const int32_t *I = ints(p.list) + (int64_t)(t + 1) * B, *meta = ints(p.meta) + 2 * (t + 1);
-    PFG_LAUNCH("while_cell_backward",
-               launch_while_cell_backward(I, meta, t, seq_offsets, (int32_t)total_tokens, ws_at(ws, p.gates),
-                                          ws_at(ws, p.cs), dh, dc, dz, dzp, B, H, stream));
-    if (t == 0) break;
     GemmArgs g{};
-    g.A = dzp; g.lda = 4 * H; g.a_batch_stride = 4 * H; g.S = 1; g.a_is_f32 = 1;
+    g.A = dzi[(t + 1) & 1]; g.lda = 4 * H; g.a_batch_stride = 4 * H; g.S = 1; g.a_is_f32 = 1;
     g.W = Wh; g.ldw = 4 * H; g.w_kn = 0;
     g.M = (int32_t)B; g.N = H; g.K = 4 * H;
-    g.epilogue = EPI_NONE; g.C = dh; g.ldc = H;
-    g.sub = meta; g.sub_rows = I; g.sub_gather = 0; g.sub_scatter = 1;
+    g.epilogue = EPI_LSTM_BWD; g.n_split = 0;
+    g.lstm_H = H; g.lstm_T = 1; g.lstm_step = t;
+    g.lstm_gates = ws_at(ws, p.gates); g.lstm_cs = ws_at(ws, p.cs); g.lstm_zx_rows = seq_offsets;
+    g.lstm_dc = dc; g.lstm_dz = dzi[t & 1]; g.lstm_dz_ld = 4 * H; g.lstm_tok_dz = dz;
+    g.lstm_seed = seed; g.lstm_steps = steps;
+    g.sub = ints(p.meta) + 2 * (t + 1); g.sub_rows = ints(p.list) + (int64_t)(t + 1) * B;
+    g.sub_gather = 1; g.sub_scatter = 0;
     PFG_LAUNCH("lstm_gemm_reverse", launch_gemm(g, stream));
   }
   // ---- per iteration, the sums over its own trips (the same W acts in every trip) ----
