@@ -302,8 +302,13 @@ def test_lstm_while_workspace_and_rejections(lib):
     r = ctypes.byref(net)
     assert lib.pfg_lstm_while_workspace_bytes(r, B, tokens, ctypes.byref(n)) == 0
     groups = (B + 31) // 32 + (B + 1023) // 1024
-    assert n.value == (up(4 * tokens * 4 * H) + up(4 * 3 * B * H) + up(4 * B * H) + up(4 * 2 * B) + up(16) +
+    pieces = up(4 * B * ((H + 7) // 8))          # halting score in pieces: lists of at most 1024 rows only
+    assert n.value == (up(4 * tokens * 4 * H) + up(4 * 3 * B * H) + pieces + up(4 * B * H) + up(4 * 2 * B) + up(16) +
                        up(4 * B) + up(4 * groups) + up(4 * B))
+    assert lib.pfg_lstm_while_workspace_bytes(r, 2 * B, tokens, ctypes.byref(n)) == 0
+    groups2 = (2 * B + 31) // 32 + (2 * B + 1023) // 1024
+    assert n.value == (up(4 * tokens * 4 * H) + up(4 * 3 * 2 * B * H) + up(4 * 2 * B * H) + up(4 * 2 * 2 * B) + up(16) +
+                       up(4 * 2 * B) + up(4 * groups2) + up(4 * 2 * B))
     assert lib.pfg_lstm_while_workspace_bytes(r, 4, 0, ctypes.byref(n)) == 0          # no tokens at all is allowed
     assert lib.pfg_lstm_while_workspace_bytes(r, 0, 5, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
     assert lib.pfg_lstm_while_workspace_bytes(r, 8, -1, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
@@ -322,6 +327,46 @@ def test_lstm_while_workspace_and_rejections(lib):
     assert "max_steps" in lib.pfg_last_error().decode()
     assert fn(r, FAKE, FAKE, 3, 7, 5, None, 0.0, FAKE, FAKE, FAKE, None, None, big, None) == pfg.PFG_ERR_WORKSPACE
     assert fn(r, FAKE, FAKE, 3, 7, 5, None, 0.0, FAKE, FAKE, FAKE, None, FAKE, 64, None) == pfg.PFG_ERR_WORKSPACE
+
+
+def test_lstm_while_grads_workspace_and_rejections(lib):
+    net = make_lstm()
+    B, tokens, H, dy, cap = 1024, 51957, 256, net.output_size, 100
+    n = ctypes.c_size_t(0)
+    r = ctypes.byref(net)
+    wsfn = lib.pfg_lstm_while_grads_workspace_bytes
+    wsfn.argtypes = [ctypes.POINTER(pfg.pfg_lstm), ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                     ctypes.POINTER(ctypes.c_size_t)]
+    assert wsfn(r, B, tokens, cap, ctypes.byref(n)) == 0
+    groups = (B + 31) // 32 + (B + 1023) // 1024
+    forward = (up(4 * tokens * 4 * H) + up(4 * 3 * B * H) + up(4 * B * ((H + 7) // 8)) + up(4 * B * H) +
+               up(4 * (cap + 1) * B) + up(8 * (cap + 1)) + up(4 * B) + up(4 * groups) + up(4 * B))
+    history = up(4 * tokens * 4 * H) + 2 * up(4 * tokens * H) + up(4 * tokens * 4 * H)     # gates, c, h, dz by token
+    sweep = up(4 * B * H) + up(4 * (B * H + 2 * B * 4 * H)) + 2 * up(4 * B * dy)
+    assert n.value == forward + history + sweep
+    assert wsfn(r, B, tokens, -1, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
+    assert wsfn(r, B, tokens, (1 << 16) + 1, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
+    assert wsfn(r, 65536, tokens, cap, ctypes.byref(n)) == pfg.PFG_ERR_UNSUPPORTED
+    assert "65535" in lib.pfg_last_error().decode()
+    assert wsfn(r, 0, tokens, cap, ctypes.byref(n)) == pfg.PFG_ERR_SHAPE
+    assert wsfn(r, B, tokens, cap, None) == pfg.PFG_ERR_NULL
+    fn = lib.pfg_lstm_while_per_example_grads
+    vp = ctypes.c_void_p
+    fn.argtypes = [ctypes.POINTER(pfg.pfg_lstm), vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, vp,
+                   ctypes.c_float, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    big = 1 << 40
+    ok = (FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    assert fn(r, None, FAKE, FAKE, 3, 7, 5, None, 0.0, *ok, FAKE, big, None) == pfg.PFG_ERR_NULL      # X
+    assert fn(r, FAKE, None, FAKE, 3, 7, 5, None, 0.0, *ok, FAKE, big, None) == pfg.PFG_ERR_NULL      # seq_offsets
+    assert fn(r, FAKE, FAKE, None, 3, 7, 5, None, 0.0, *ok, FAKE, big, None) == pfg.PFG_ERR_NULL      # labels
+    assert "labels" in lib.pfg_last_error().decode()
+    none = (None, None, None, None, None, FAKE)                                                       # trip counts alone
+    assert fn(r, FAKE, FAKE, FAKE, 3, 7, 5, None, 0.0, *none, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r, FAKE, FAKE, FAKE, 3, 7, -1, None, 0.0, *ok, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+    assert fn(r, FAKE, FAKE, FAKE, 3, 7, 5, None, 0.0, *ok, None, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(r, FAKE, FAKE, FAKE, 3, 7, 5, None, 0.0, *ok, FAKE + 8, big, None) == pfg.PFG_ERR_WORKSPACE
+    assert "aligned" in lib.pfg_last_error().decode()
+    assert fn(r, FAKE, FAKE, FAKE, 3, 7, 5, None, 0.0, *ok, FAKE, 64, None) == pfg.PFG_ERR_WORKSPACE
 
 
 def make_convnet(h=28, w=28, c=1, kernel=(5, 5), filters=(32, 64), dense=(3136, 1024, 10), Wc_null=None,
