@@ -171,7 +171,9 @@ int pfg_per_example_grad_norms(const pfg_mlp *net, const void *X, const int32_t 
  *      H[b, s] = sum_{l < L} T_l[b]^T diag(h_l[b, s, :] * phi''(z_l[b, :])) T_l[b],
  * one batched matrix product per call (both operands depend on b).  It is identically zero for
  * PFG_ACT_IDENTITY and PFG_ACT_RELU (phi'' = 0, also at the kink) and for L = 1.
- *   net->dtype must be PFG_F32 (PFG_BF16 returns PFG_ERR_UNSUPPORTED)
+ *   net->dtype PFG_BF16: the three sweeps (forward, tangents, cotangents) run their products on bf16
+ *   operands as the other calls do; the tangents, the curvature weights and the batched product that
+ *   forms H stay float32
  *   seeds, S, seed_batch_stride   as for pfg_jacobian_input
  *   H_out   [B, S, d_0, d_0] */
 int pfg_hessian_input(const pfg_mlp *net, const void *X, int64_t B, const float *seeds, int64_t S,

@@ -150,8 +150,6 @@ int check_seeds(const pfg_mlp *net, const float *seeds, int64_t S, int64_t strid
 }
 
 int check_hessian(const pfg_mlp *net, int64_t B, int64_t S) {
-  if (net->dtype != PFG_F32)
-    return fail(PFG_ERR_UNSUPPORTED, "the Hessian is computed in float32 only (dtype %d given)", net->dtype);
   const int64_t n = net->dims[0];
   int64_t ktot = 0;
   for (int l = 1; l < net->num_layers; ++l) ktot += net->dims[l];
@@ -637,6 +635,10 @@ int pfg_hessian_input(const pfg_mlp *net, const void *X, int64_t B, const float 
   const int L = net->num_layers;
   const int32_t *d = net->dims;
   const int64_t n = d[0], rows = B * S, ktot = p.ktot;
+  // a bfloat16 network: its weights (and X) enter the products of the three sweeps as they are, the
+  // float32 intermediates are rounded when staged as matrix-core operands; the tangents, cotangents
+  // and the final batched product (both operands intermediates) stay float32
+  const int32_t bf16 = (net->dtype == PFG_BF16);
 
   if (L == 1 || net->hidden_act == PFG_ACT_IDENTITY || net->hidden_act == PFG_ACT_RELU) {
     // piecewise-linear network: every second derivative vanishes
@@ -649,8 +651,8 @@ int pfg_hessian_input(const pfg_mlp *net, const void *X, int64_t B, const float 
   for (int l = 1; l <= H; ++l) {
     GemmArgs g{};
     g.A = (l == 1) ? X : at(workspace, p.act[l - 1]);
-    g.lda = d[l - 1]; g.a_batch_stride = d[l - 1]; g.S = 1; g.a_is_f32 = 1;
-    g.W = net->W[l - 1]; g.ldw = d[l]; g.w_kn = 1;
+    g.lda = d[l - 1]; g.a_batch_stride = d[l - 1]; g.S = 1; g.a_is_f32 = (l == 1) ? !bf16 : 1;
+    g.W = net->W[l - 1]; g.ldw = d[l]; g.w_kn = 1; g.bf16 = bf16;
     g.M = (int32_t)B; g.N = d[l]; g.K = d[l - 1];
     g.bias = bias_of(net, l);
     g.epilogue = EPI_BIAS;
@@ -667,13 +669,13 @@ int pfg_hessian_input(const pfg_mlp *net, const void *X, int64_t B, const float 
   // U_1 = W_1 for every b; U_{l+1}[b] = (U_l[b] * phi'(z_l[b, :])) W_{l+1}: rows (b, i) folded into
   // one product with the loop-invariant W_{l+1}, the mask broadcast over i.
   float *U = at(workspace, p.U);
-  PFG_LAUNCH("tangent_seed", launch_scale_rows(net->W[0], 0, 0, d[1], nullptr, 0, B, n, d[1], U, ktot,
+  PFG_LAUNCH("tangent_seed", launch_scale_rows(net->W[0], bf16, 0, d[1], nullptr, 0, B, n, d[1], U, ktot,
                                                stream));
   for (int l = 1; l < H; ++l) {
     GemmArgs g{};
     g.A = U + p.koff[l]; g.lda = ktot; g.a_batch_stride = n * ktot; g.S = (int32_t)n; g.a_is_f32 = 1;
     g.a_scale = at(workspace, p.dphi[l]); g.ld_scale = d[l];
-    g.W = net->W[l]; g.ldw = d[l + 1]; g.w_kn = 1;
+    g.W = net->W[l]; g.ldw = d[l + 1]; g.w_kn = 1; g.bf16 = bf16;
     g.M = (int32_t)(B * n); g.N = d[l + 1]; g.K = d[l];
     g.epilogue = EPI_NONE;
     g.C = U + p.koff[l + 1]; g.ldc = ktot;
@@ -690,14 +692,14 @@ int pfg_hessian_input(const pfg_mlp *net, const void *X, int64_t B, const float 
   {
     GemmArgs g{};
     g.A = seeds; g.lda = d[L]; g.S = (int32_t)S; g.a_is_f32 = 1;
-    g.W = net->W[L - 1]; g.ldw = d[L]; g.w_kn = 0;
+    g.W = net->W[L - 1]; g.ldw = d[L]; g.w_kn = 0; g.bf16 = bf16;
     g.N = d[H]; g.K = d[L];
     g.epilogue = EPI_NONE; g.ldc = d[H];
     if (shared) {
       // loop-invariant seeds: the product does not depend on b and is formed once, not stacked
       float *P = at(workspace, p.P);
       if (!seeds) {
-        PFG_LAUNCH("transpose", launch_transpose(net->W[L - 1], 0, d[H], d[L], P, stream));
+        PFG_LAUNCH("transpose", launch_transpose(net->W[L - 1], bf16, d[H], d[L], P, stream));
       } else {
         g.a_batch_stride = 0; g.M = (int32_t)S; g.C = P;
         PFG_LAUNCH("gemm_cotangent", launch_gemm(g, stream));
@@ -718,7 +720,7 @@ int pfg_hessian_input(const pfg_mlp *net, const void *X, int64_t B, const float 
     GemmArgs g{};
     g.A = cur; g.lda = d[l]; g.a_batch_stride = cur_bstride; g.S = (int32_t)S; g.a_is_f32 = 1;
     g.a_scale = at(workspace, p.dphi[l]); g.ld_scale = d[l];
-    g.W = net->W[l - 1]; g.ldw = d[l]; g.w_kn = 0;
+    g.W = net->W[l - 1]; g.ldw = d[l]; g.w_kn = 0; g.bf16 = bf16;
     g.M = (int32_t)rows; g.N = d[l - 1]; g.K = d[l];
     g.epilogue = EPI_NONE;
     g.C = bufs[which]; g.ldc = d[l - 1];

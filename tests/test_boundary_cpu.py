@@ -192,7 +192,7 @@ def test_hessian_workspace_and_rejections(lib):
     assert nbytes == expect
     # a one-layer network has no hidden layer: nothing but the minimum
     assert ws_bytes(lib, make_net([7, 3], act=2), 4, 5, 3) == (0, 256)
-    assert ws_bytes(lib, make_net([4, 3, 2], act=2, dtype=1), 4, 1, 2)[0] == pfg.PFG_ERR_UNSUPPORTED
+    assert ws_bytes(lib, make_net([4, 3, 2], act=2, dtype=1), 4, 1, 2) == ws_bytes(lib, make_net([4, 3, 2], act=2), 4, 1, 2)
     assert ws_bytes(lib, make_net([1 << 16, 3, 2], act=2), 4, 1, 2)[0] == pfg.PFG_ERR_OVERFLOW
     fn = lib.pfg_hessian_input
     big = 1 << 30
@@ -205,9 +205,9 @@ def test_hessian_workspace_and_rejections(lib):
     assert fn(r, FAKE, 0, None, 2, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE
     assert fn(r, FAKE, 2, None, 2, 0, FAKE, None, big, None) == pfg.PFG_ERR_WORKSPACE
     assert fn(r, FAKE, 2, None, 2, 0, FAKE, FAKE, 8, None) == pfg.PFG_ERR_WORKSPACE
-    bf = make_net([4, 3, 2], act=2, dtype=1)
-    assert fn(ctypes.byref(bf), FAKE, 2, None, 2, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_UNSUPPORTED
-    assert "float32" in lib.pfg_last_error().decode()
+    bf = make_net([4, 3, 2], act=2, dtype=1)                      # bfloat16 networks pass the same checks
+    assert fn(ctypes.byref(bf), FAKE, 2, None, 3, 0, FAKE, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+    assert fn(ctypes.byref(bf), FAKE, 2, None, 2, 0, FAKE, FAKE, 8, None) == pfg.PFG_ERR_WORKSPACE
 
 
 def make_lstm(dx=128, H=256, dy=10, T=10, dtype=0, W=FAKE, W_out=FAKE):

@@ -260,14 +260,39 @@ def test_c6_tanh_hessian_full_size_sampled_columns(oracle):
     assert worst <= TOL_F32
 
 
-def test_hessian_rejects_bf16_and_bad_arguments():
-    w = wl.Workload("bfh", 290, "hessian_input", (8, 8, 4), "tanh", "bf16", 2, "normal",
+BF16_HESS_SHAPES = [
+    ((8, 8, 4), 2, "tanh", 0.0),
+    ((24, 40, 36, 8), 5, "tanh", 0.2),
+    ((33, 70, 65, 10), 4, "gelu", 0.1),          # ragged against every tile edge
+    ((128, 256, 192, 16), 6, "gelu", 0.0),       # mirrored tiles (d_0 a multiple of 128), LDS-tiled kernels
+]
+
+
+@pytest.mark.parametrize("dims,B,act,bias_scale", BF16_HESS_SHAPES,
+                         ids=[f"{s[0]}-B{s[1]}-{s[2]}" for s in BF16_HESS_SHAPES])
+def test_hessian_of_bf16_networks(oracle, dims, B, act, bias_scale):
+    # bfloat16 inputs and weights (the oracle gets the rounded values, exact in float64), products on
+    # bf16 operands with float32 accumulation: the tolerance of the bf16 path
+    say(f"Hessian, bf16 network {dims} B={B} act={act}")
+    w = wl.Workload("bfh", 290 + len(dims) + B, "hessian_input", tuple(dims), act, "bf16", B, "normal",
                     "normal_fan_in")
-    inp = draw(w)
-    net = gpu_net(inp, "tanh", "bf16")
-    with pytest.raises(pfg.PfgError) as ei:
-        pfg.pfg_hessian_input(net, gpu_x(inp, "bf16"))
-    assert ei.value.code == pfg.PFG_ERR_UNSUPPORTED
+    inp = draw(w, bias_scale=bias_scale, act=act)
+    onet = oracle.Net(inp.Ws, inp.bs, act)
+    net = gpu_net(inp, act, "bf16")
+    X = gpu_x(inp, "bf16")
+    rng = np.random.default_rng(B)
+    dL, n = dims[-1], dims[0]
+    shared = rng.standard_normal((3, dL)).astype(np.float32)
+    per_ex = rng.standard_normal((B, 2, dL)).astype(np.float32)
+    for name, seeds in (("identity", None), ("shared", shared), ("per-example", per_ex)):
+        ref = oracle.hessian_input(onet, inp.X, seeds=seeds)
+        S = ref.shape[1]
+        H = pfg.pfg_hessian_input(net, X, seeds=None if seeds is None else dev(seeds),
+                                  out=nan_like(B, S, n, n))
+        torch.cuda.synchronize()
+        e = slice_rel_err(H.cpu().numpy(), ref, lead=2)
+        say(f"  H[{name}] rel err {e:.3e}")
+        assert e <= TOL_BF16
 
 
 def test_new_calls_replay_from_a_graph(oracle):
