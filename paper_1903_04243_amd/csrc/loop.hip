@@ -358,6 +358,121 @@ void outer_sum_ragged_kernel(const RaggedSumArgs p) {
   }
 }
 
+// The same sums with the operands staged through LDS, for dx and H that are multiples of 4 (16-byte
+// pieces never straddle the boundary between the x rows and the h rows): a workgroup takes 128 rows
+// and 128 columns of one iteration's matrix and walks the trips in chunks of kLdsTrips.  All 256 threads
+// fetch a chunk's operands -- [32 trips, 128 rows] of [x | h_prev] and [32 trips, 128 columns] of dz,
+// eight 16-byte loads per thread, no value fetched twice -- while the MFMAs of the previous chunk
+// run, and store them to LDS behind a barrier; wave w then feeds its 32 rows and the interleaved
+// column tiles from LDS.  Against the register-fed kernel above: one exposure to memory latency per 32
+// trips instead of one per 8, and 2.5 times fewer bytes requested.  Loads carry no branch (clamped
+// to the iteration's last trip, last rows and last columns); what must be zero is zeroed on its way
+// into LDS.
+constexpr int kLdsTrips = 16;
+constexpr int kLdsPieces = kLdsTrips / 8;    // 16-byte pieces of each operand a thread stages per chunk
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void outer_sum_ragged_lds_kernel(const RaggedSumArgs p) {
+  __shared__ __align__(16) float As[kLdsTrips][128];
+  __shared__ __align__(16) float Gs[kLdsTrips][128];
+  const int64_t b = blockIdx.y;
+  const int lo = p.seq_offsets[b], hi = min(p.seq_offsets[b + 1], p.total_tokens);
+  const int len = (lo >= 0 && hi > lo) ? hi - lo : 0;
+  const int nt = max(0, min(p.steps[b], len));
+  const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+
+  if ((int)blockIdx.x >= p.mm_blocks) {
+    // ---- bias row: 1024 columns per workgroup, four per lane ----
+    const int j = (((int)blockIdx.x - p.mm_blocks) * 256 + threadIdx.x) * 4;
+    if (j >= p.d_out) return;
+    f32x4 s = zero4;
+    for (int t = 0; t < nt; ++t) s += *reinterpret_cast<const f32x4 *>(p.dz_tok + (int64_t)(lo + t) * p.d_out + j);
+    float *o = p.db + b * (int64_t)p.d_out + j;
+    if (p.vec) {
+      *reinterpret_cast<f32x4 *>(o) = s;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = s[e];
+    }
+    return;
+  }
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
+  const int col_chunks = (p.d_out + 127) / 128;
+  const int cchunk = blockIdx.x % col_chunks, rgroup = blockIdx.x / col_chunks;
+  const int R = p.dx + p.H;                                // a multiple of 4, like dx
+  const int row0 = rgroup * 128, col0 = cchunk * 128;
+
+  // staging: this thread's four pieces of a chunk are elements 4 part .. 4 part + 3 of the trips
+  // tl0, tl0 + 8, ... of the chunk, for both operands
+  const int part = tid & 31, tl0 = tid >> 5;
+  const int ar = row0 + 4 * part, gcol = col0 + 4 * part;
+  const bool a_in = ar < R, g_in = gcol < p.d_out;
+  const int arc = min(ar, R - 4), gc = min(gcol, p.d_out - 4);
+  const bool a_is_x = arc < p.dx;
+  const int a_first = a_is_x ? 0 : 1;                      // trip t pairs dz_t with h_{t-1}; h before trip 0 is zero
+  const int64_t astride = a_is_x ? p.dx : p.H;
+  const float *abase = a_is_x ? p.x + (int64_t)lo * p.dx + arc : p.h_tok + (int64_t)lo * p.H + (arc - p.dx);
+  const float *gbase = p.dz_tok + (int64_t)lo * p.d_out + gc;
+  f32x4 ra[kLdsPieces], rg[kLdsPieces];
+  auto fetch = [&](int t0) {                               // nt > 0
+#pragma unroll
+    for (int c = 0; c < kLdsPieces; ++c) {
+      const int t = min(t0 + tl0 + 8 * c, nt - 1);
+      ra[c] = *reinterpret_cast<const f32x4 *>(abase + max(t - a_first, 0) * astride);
+      rg[c] = *reinterpret_cast<const f32x4 *>(gbase + (int64_t)t * p.d_out);
+    }
+  };
+  auto stash = [&](int t0) {
+#pragma unroll
+    for (int c = 0; c < kLdsPieces; ++c) {
+      const int tl = tl0 + 8 * c, t = t0 + tl;
+      const bool live = t < nt;
+      *reinterpret_cast<f32x4 *>(&As[tl][4 * part]) = (live && a_in && t >= a_first) ? ra[c] : zero4;
+      *reinterpret_cast<f32x4 *>(&Gs[tl][4 * part]) = (live && g_in) ? rg[c] : zero4;
+    }
+  };
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[e][r] = 0.f;
+  if (nt > 0) fetch(0);
+#pragma unroll 1
+  for (int t0 = 0; t0 < nt; t0 += kLdsTrips) {
+    __syncthreads();                                       // the previous chunk has been read
+    stash(t0);
+    __syncthreads();
+    if (t0 + kLdsTrips < nt) fetch(t0 + kLdsTrips);        // on its way while this chunk is multiplied
+    const int pairs = min(kLdsTrips / 2, (nt - t0 + 1) / 2);
+#pragma unroll 2
+    for (int s = 0; s < pairs; ++s) {
+      const float a = As[2 * s + half][32 * wave + l32];
+      const f32x4 g = *reinterpret_cast<const f32x4 *>(&Gs[2 * s + half][4 * l32]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[e] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, g[e], acc[e], 0, 0, 0);
+    }
+  }
+
+  const int rtile = rgroup * 4 + wave, col = col0 + 4 * l32;
+  if (rtile * 32 >= R || col >= p.d_out) return;           // (no barrier follows)
+  // register r of a tile is row 8 (r / 4) + 4 half + r % 4 of the tile, column l32
+  float *out = p.dW + (b * (int64_t)R + rtile * 32) * p.d_out + col;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int i = 8 * (r >> 2) + 4 * half + (r & 3);
+    if (rtile * 32 + i >= R) continue;
+    const f32x4 v = {acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+    float *o = out + (int64_t)i * p.d_out;
+    if (p.vec) {
+      __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(o));
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = v[e];
+    }
+  }
+}
+
 }  // namespace
 
 int64_t while_count_entries(int64_t B) { return (B + kGroup - 1) / kGroup + (B + kPlace - 1) / kPlace; }
@@ -416,8 +531,13 @@ hipError_t launch_outer_sum_ragged(const float *x, int32_t dx, const float *h_to
   const int col_chunks = (p.d_out + 32 * NT - 1) / (32 * NT), row_groups = (dx + H + 127) / 128;
   p.mm_blocks = dW ? col_chunks * row_groups : 0;
   const int bias_blocks = db ? (p.d_out + 1023) / 1024 : 0;
-  PFG_KERNEL(outer_sum_ragged_kernel<NT>, dim3((unsigned)(p.mm_blocks + bias_blocks), (unsigned)B), dim3(256), 0, stream,
-             p);
+  const bool aligned = ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(h_tok)) & 15) == 0;
+  if (dW && aligned && dx % 4 == 0 && H % 4 == 0)
+    PFG_KERNEL(outer_sum_ragged_lds_kernel, dim3((unsigned)(p.mm_blocks + bias_blocks), (unsigned)B), dim3(256), 0,
+               stream, p);
+  else
+    PFG_KERNEL(outer_sum_ragged_kernel<NT>, dim3((unsigned)(p.mm_blocks + bias_blocks), (unsigned)B), dim3(256), 0,
+               stream, p);
   return hipGetLastError();
 }
 
