@@ -258,9 +258,9 @@ def test_while_grads_replay_from_a_graph_on_other_inputs():
 
 
 def test_c14_lstm_while_grads_full_size():
-    # all 1024 sequences on the GPU in the launch configuration the benchmark times; the oracle on
-    # 96 of them (iterations are independent, so it can take them one by one): the shortest, the
-    # longest and the ones with the fewest and most trips among them
+    # all 1024 sequences on the GPU in the launch configuration the benchmark times, and every one of
+    # them that is at least 1e-4 from each of its decisions against the oracle, element by element
+    # (iterations are independent, so the oracle takes them 128 at a time to bound the host memory)
     w = wl.LSTM_WORKLOADS["c14_lstm_while_grads"]
     inp, lengths, offsets, halt_w, halt_c = wl.make_while_inputs(w)
     labels = inp.labels.astype(np.int32)
@@ -280,23 +280,21 @@ def test_c14_lstm_while_grads_full_size():
     assert robust.mean() >= 0.95 and (steps[robust] == rsteps[robust]).all() and ((lo <= steps) & (steps <= hi)).all()
     for name in NAMES:
         assert bool(torch.isfinite(res[name]).all()), f"{name} was not written in full"
-    rng = np.random.default_rng(14)
     cand = np.flatnonzero(robust)
-    pick = set(rng.choice(cand, size=88, replace=False).tolist())
-    by_steps = cand[np.argsort(rsteps[cand], kind="stable")]
-    pick.update(by_steps[:4].tolist()); pick.update(by_steps[-4:].tolist())
-    pick = np.array(sorted(pick))
-    Xs = np.concatenate([inp.X[offsets[b]:offsets[b + 1]] for b in pick])
-    ref = olstm.while_per_example_grads(onet, Xs, lengths[pick], labels[pick], w.T, halt_w, halt_c)
-    assert np.array_equal(ref["steps"], rsteps[pick])
-    idx = torch.from_numpy(pick).to("cuda:0")
-    worst = 0.0
+    worst = dict.fromkeys(NAMES, 0.0)
+    for c0 in range(0, len(cand), 128):
+        pick = cand[c0:c0 + 128]
+        Xs = np.concatenate([inp.X[offsets[b]:offsets[b + 1]] for b in pick])
+        ref = olstm.while_per_example_grads(onet, Xs, lengths[pick], labels[pick], w.T, halt_w, halt_c)
+        assert np.array_equal(ref["steps"], rsteps[pick])
+        idx = torch.from_numpy(pick).to("cuda:0")
+        for name in NAMES:
+            g = res[name][idx].cpu().numpy()
+            worst[name] = max(worst[name], slice_rel_err(g.reshape(len(pick), -1), ref[name].reshape(len(pick), -1)))
+        del ref
     for name in NAMES:
-        g = res[name][idx].cpu().numpy()
-        e = slice_rel_err(g.reshape(len(pick), -1), ref[name].reshape(len(pick), -1))
-        say(f"  c14: {name} rel err {e:.3e} over {len(pick)} sampled sequences")
-        worst = max(worst, e)
-    assert worst <= TOL_F32
+        say(f"  c14: {name} rel err {worst[name]:.3e} over {len(cand)} sequences, every element")
+    assert max(worst.values()) <= TOL_F32
     # every sequence that made no trip has exact zeros in the gradients of the cell and of W_out
     none = torch.from_numpy(np.flatnonzero(steps == 0)).to("cuda:0")
     if none.numel():
