@@ -8,8 +8,8 @@ resident in HBM.  The last line of stdout is the headline record: the largest pe
 workload that fits one GPU (4096 -> 4096 -> 4096 -> 10, GELU, bf16 inputs and weights, float32
 accumulation and output, batch 256: 34.4 GB written per step), with its roofline and the CPU
 baseline; the other dense workloads appear in it as short entries.  The full records of every
-workload go to gpurun_out/bench_detail.json and, a workload a line, to stderr.  Per-kernel durations come from HIP events the
-library records on the call's stream in a second, instrumented pass over the same steps.
+workload go to the file named by --detail-file and, a workload a line, to stderr.  Per-kernel
+durations come from HIP events the library records on the call's stream in a second, instrumented pass over the same steps.
 """
 import argparse
 import json
@@ -43,6 +43,8 @@ def main():
                     help="measure plain sequential fills of several sizes (the practical HBM write ceiling)")
     ap.add_argument("--launch-floor", action="store_true",
                     help="measure the cost per launch of a chain of dependent near-empty kernels")
+    ap.add_argument("--detail-file", default=os.path.join("gpurun_out", "bench_detail.json"),
+                    help="where the full per-workload records go (relative to the repository root)")
     ap.add_argument("--workload", default=None,
                     help="measure only this workload and print its record (for profiling runs)")
     ap.add_argument("--batch", type=int, default=None,
@@ -890,10 +892,10 @@ def main():
 
     # The full records (per-kernel tables of every workload) go to a file and, one workload a line,
     # to stderr; the last line of stdout is the compact headline record.
-    out_dir = os.path.join(ROOT, "gpurun_out")
+    detail_file = args.detail_file if os.path.isabs(args.detail_file) else os.path.join(ROOT, args.detail_file)
     try:
-        os.makedirs(out_dir, exist_ok=True)
-        with open(os.path.join(out_dir, "bench_detail.json"), "w") as f:
+        os.makedirs(os.path.dirname(detail_file), exist_ok=True)
+        with open(detail_file, "w") as f:
             json.dump(detail, f, indent=1)
     except OSError as e:
         log(f"[bench] detail file not written: {e}")
@@ -930,7 +932,7 @@ def main():
         "whole_step_hbm_frac": rec["output_GB"] / (rec["ms_per_step"] * 1e-3) / HBM_PEAK_GBS,
         "other_configs": {k: brief(detail[k]) for k in ("c2_mnist_mlp_grads", "c3_tanh_jacobian",
                                                          "c5_nested_weight_jacobian") if k in detail},
-        "detail": "gpurun_out/bench_detail.json and the [bench-detail] lines on stderr",
+        "detail": args.detail_file + " and the [bench-detail] lines on stderr",
     }
     text = json.dumps(line)
     assert len(text) < 2048, len(text)
