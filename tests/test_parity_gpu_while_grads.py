@@ -107,6 +107,11 @@ SHAPES = [
     (16, 32, 40, 30, 100, 40, -0.1),           # a head wider than 32
     (16, 64, 5, 12, 600, 12, -0.08),           # many row tiles
     (10, 300, 4, 5, 20, 5, -0.2),              # more than 1024 gate columns: two column chunks
+    # widths that are multiples of 4 take the LDS-staged summing kernel: two row groups with a ragged
+    # second one and a ragged last column chunk, trip counts around its chunk of 16 (15 .. 18, 31 .. 34)
+    (100, 60, 3, 34, 48, 34, -3.0),
+    (4, 4, 2, 40, 9, 33, -0.5),                # the smallest such widths: one piece per operand row
+    (132, 128, 6, 20, 30, 17, -0.2),           # three row groups, the x rows end inside the second
 ]
 
 
@@ -114,6 +119,10 @@ SHAPES = [
                          ids=[f"dx{s[0]}-H{s[1]}-L{s[3]}-B{s[4]}" for s in SHAPES])
 def test_while_grads_shapes(dx, H, dy, max_len, B, max_steps, halt_c):
     inp, lengths, halt_w, labels = draw(dx, H, dy, max_len, B, 900 + dx + H + B)
+    if max_len >= 34:
+        lengths_fixed = np.array([15, 16, 17, 18, 31, 32, 33, 34], dtype=np.int32)[:min(8, B)]
+        lengths[:len(lengths_fixed)] = lengths_fixed
+        inp.X = np.random.default_rng(B).standard_normal((int(lengths.sum()), dx)).astype(np.float32)
     say(f"while-loop gradients dx={dx} H={H} dy={dy} B={B} lengths 0..{max_len} cap {max_steps}")
     check(inp, lengths, labels, max_steps, halt_w, halt_c, "grads")
 
