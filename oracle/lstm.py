@@ -231,3 +231,28 @@ def while_per_example_grads(net: Lstm, X, lengths, labels, max_steps: int, halt_
         ctypes.c_double(float(halt_c)), _dp(out["dW"]), _dp(out["db"]), _dp(out["dWout"]), _dp(out["dbout"]),
         _dp(out["loss"]), out["steps"].ctypes.data_as(ctypes.POINTER(ctypes.c_int64)))
     return out
+
+
+def while_per_example_grad_norms(net: Lstm, X, lengths, labels, max_steps: int, halt_w=None, halt_c: float = 0.0):
+    """Norms of the per-example gradients through the while loop (the gradient formed in full, its
+    squares added; see lstm_oracle.c).  Returns (sq [B, 4] = squared norms of dW, db, dWout, dbout;
+    norm [B]; loss [B]; steps [B] int64)."""
+    lengths = np.asarray(lengths, dtype=np.int64)
+    assert lengths.ndim == 1 and (lengths >= 0).all()
+    B = lengths.size
+    offsets = np.zeros(B + 1, dtype=np.int64)
+    np.cumsum(lengths, out=offsets[1:])
+    X = _f64(X).reshape(-1, net.dx)
+    assert X.shape == (int(offsets[-1]), net.dx)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    assert labels.shape == (B,) and (labels >= 0).all() and (labels < net.dy).all()
+    hw = None if halt_w is None else _f64(halt_w)
+    assert hw is None or hw.shape == (net.H,)
+    sq, norm, ls = np.empty((B, 4)), np.empty(B), np.empty(B)
+    steps = np.empty(B, dtype=np.int64)
+    _load().lstmo_while_per_example_grad_norms(
+        ctypes.byref(net.c), _dp(X), offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+        labels.ctypes.data_as(_c_int32_p), ctypes.c_int64(B), ctypes.c_int64(int(max_steps)), _dp(hw),
+        ctypes.c_double(float(halt_c)), _dp(sq), _dp(norm), _dp(ls),
+        steps.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)))
+    return sq, norm, ls, steps

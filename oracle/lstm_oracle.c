@@ -569,3 +569,39 @@ void lstmo_while_per_example_grads(const lstmo_net *net, const double *X, const 
                            dbout ? dbout + (size_t)i * net->dy : NULL, loss ? loss + i : NULL,
                            steps_out ? steps_out + i : NULL);
 }
+
+/* -------------------------------------------------------------------------------------
+ * Norms of the per-example gradients through the while loop (the quantity per-example clipping
+ * needs, Section 5.3): the body forms its gradient as above and returns the sums of its squares,
+ *   sq[0] = |dW|^2, sq[1] = |db|^2, sq[2] = |dWout|^2, sq[3] = |dbout|^2,  norm = sqrt of their sum.
+ * Nothing is shortened: the gradient is formed in full and its entries are squared and added.
+ * ------------------------------------------------------------------------------------- */
+void lstmo_body_while_grad_norm(const lstmo_net *net, const double *x, int64_t len, int64_t max_steps,
+                                const double *halt_w, double halt_c, int label, double *sq, double *norm,
+                                double *loss, int64_t *steps_out) {
+  const size_t G = 4 * (size_t)net->H;
+  const size_t nW = (size_t)(net->dx + net->H) * G, nWo = (size_t)net->H * net->dy;
+  double *dW = (double *)malloc(sizeof(double) * nW), *db = (double *)malloc(sizeof(double) * G);
+  double *dWout = (double *)malloc(sizeof(double) * nWo), *dbout = (double *)malloc(sizeof(double) * net->dy);
+  lstmo_body_while_grads(net, x, len, max_steps, halt_w, halt_c, label, dW, db, dWout, dbout, loss, steps_out);
+  double s[4] = {0.0, 0.0, 0.0, 0.0};
+  for (size_t e = 0; e < nW; ++e) s[0] += dW[e] * dW[e];
+  for (size_t e = 0; e < G; ++e) s[1] += db[e] * db[e];
+  for (size_t e = 0; e < nWo; ++e) s[2] += dWout[e] * dWout[e];
+  for (int e = 0; e < net->dy; ++e) s[3] += dbout[e] * dbout[e];
+  if (sq) for (int k = 0; k < 4; ++k) sq[k] = s[k];
+  if (norm) *norm = sqrt(s[0] + s[1] + s[2] + s[3]);
+  free(dW); free(db); free(dWout); free(dbout);
+}
+
+/* pfor(body, B): sq [B, 4], norm [B], loss [B], steps [B]; sequences as in lstmo_while_per_example_grads. */
+void lstmo_while_per_example_grad_norms(const lstmo_net *net, const double *X, const int64_t *offsets,
+                                        const int32_t *labels, int64_t B, int64_t max_steps,
+                                        const double *halt_w, double halt_c, double *sq, double *norm,
+                                        double *loss, int64_t *steps_out) {
+#pragma omp parallel for schedule(dynamic)
+  for (int64_t i = 0; i < B; ++i)
+    lstmo_body_while_grad_norm(net, X + (size_t)offsets[i] * net->dx, offsets[i + 1] - offsets[i], max_steps,
+                               halt_w, halt_c, labels[i], sq ? sq + 4 * i : NULL, norm ? norm + i : NULL,
+                               loss ? loss + i : NULL, steps_out ? steps_out + i : NULL);
+}

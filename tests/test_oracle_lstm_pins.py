@@ -483,7 +483,7 @@ def test_while_grads_by_central_differences_of_the_pinned_forward_loop():
     """The loss recomputed from the readout of `while_forward` (pinned above) at parameters moved by
     +-1e-6: the trip counts do not change (every score is at least 1e-3 from the threshold), so the
     difference quotient is the derivative of the loop's result."""
-    rng = np.random.default_rng(112)
+    rng = np.random.default_rng(102)
     dx, H, dy = 3, 4, 3
     net = rand_lstm(rng, dx, H, dy, 1)
     lengths = np.array([5, 2, 7, 4])
@@ -576,3 +576,92 @@ def test_while_grads_reduce_to_the_fixed_length_gradients_and_special_cases():
     # the forward results agree with the pinned forward loop
     _, _, steps = lstm.while_forward(net, P, lengths, 100, wv, -0.1)
     assert np.array_equal(steps, g1["steps"])
+
+
+# --------------------------------------------------------------------------------------------
+# Norms of the per-example gradients through the while loop.
+# --------------------------------------------------------------------------------------------
+def test_while_grad_norms_against_autograd_through_the_library_cell_under_a_python_while():
+    rng = np.random.default_rng(102)
+    dx, H, dy, cap = 4, 6, 5, 6
+    net = rand_lstm(rng, dx, H, dy, 1)
+    lengths = np.array([3, 0, 9, 2, 9, 5, 1, 7])
+    B = len(lengths)
+    X = rng.standard_normal((B, 9, dx))
+    labels = rng.integers(0, dy, size=B)
+    w = rng.standard_normal(H)
+    c0 = -0.15
+    sq, norm, loss, steps = lstm.while_per_example_grad_norms(net, packed(X, lengths), lengths, labels, cap, w, c0)
+    seen = set()
+    for b, n in enumerate(lengths):
+        cell, Wout, bout, _ = torch_cell(net, requires_grad=True)
+        hb = torch.zeros(1, H, dtype=torch.float64)
+        cb = torch.zeros(1, H, dtype=torch.float64)
+        t = 0
+        while True:
+            score = c0 + float(hb[0].detach().numpy() @ w)
+            if not (t < n and t < cap and score <= 0.0):
+                break
+            hb, cb = cell(torch.from_numpy(X[b, t:t + 1]), (hb, cb))
+            t += 1
+        assert steps[b] == t
+        seen.add("none" if t == 0 else "cap" if t == cap else "len" if t == n else "halt")
+        ell = -torch.log_softmax(hb[0] @ Wout + bout, dim=0)[int(labels[b])]
+        g = torch.autograd.grad(ell, [cell.weight_ih, cell.weight_hh, cell.bias_ih, Wout, bout], allow_unused=True)
+        ss = [0.0 if t_ is None else float((t_ ** 2).sum()) for t_ in g]
+        want = np.array([ss[0] + ss[1], ss[2], ss[3], ss[4]])
+        np.testing.assert_allclose(sq[b], want, rtol=1e-10, atol=1e-300)
+        assert norm[b] == pytest.approx(math.sqrt(want.sum()), rel=1e-10)
+        assert loss[b] == pytest.approx(float(ell.detach()), rel=1e-12)
+    assert seen == {"none", "cap", "len", "halt"}, seen
+
+
+def test_while_grad_norms_closed_forms_and_special_cases():
+    rng = np.random.default_rng(113)
+    T, dx, H, dy = 5, 3, 4, 3
+    net = rand_lstm(rng, dx, H, dy, T)
+    B = 6
+    X = rng.standard_normal((B, T, dx))
+    labels = rng.integers(0, dy, size=B)
+    # only the lengths stop the loop and every sequence is T long: the norms of the unrolled model
+    usq, unorm, uloss = lstm.per_example_grad_norms(net, X, labels)
+    sq, norm, loss, steps = lstm.while_per_example_grad_norms(net, X.reshape(B * T, dx), [T] * B, labels, 100, None, 0.0)
+    assert steps.tolist() == [T] * B
+    np.testing.assert_allclose(sq, usq, rtol=1e-13)
+    np.testing.assert_allclose(norm, unorm, rtol=1e-13)
+    np.testing.assert_allclose(loss, uloss, rtol=1e-13)
+    # the readout's gradient is the outer product of the last state and softmax - onehot, both known
+    # from the pinned forward loop: |dbout|^2 = |p - e|^2, |dWout|^2 = |h|^2 |p - e|^2
+    lengths = [2, 5, 0, 4, 1, 3]
+    P = packed(X, lengths)
+    wv = rng.standard_normal(H)
+    sq, norm, loss, steps = lstm.while_per_example_grad_norms(net, P, lengths, labels, 100, wv, -0.1)
+    h, y, fsteps = lstm.while_forward(net, P, lengths, 100, wv, -0.1)
+    assert np.array_equal(steps, fsteps)
+    for b in range(B):
+        d = scipy.special.softmax(y[b])
+        assert loss[b] == pytest.approx(-math.log(d[labels[b]]), rel=1e-13)
+        d[labels[b]] -= 1.0
+        assert sq[b, 3] == pytest.approx(float(d @ d), rel=1e-13)
+        assert sq[b, 2] == pytest.approx(float(h[b] @ h[b]) * float(d @ d), rel=1e-13, abs=1e-300)
+        assert norm[b] == pytest.approx(math.sqrt(sq[b].sum()), rel=1e-14)
+    # no trip: only the readout bias has a gradient
+    assert steps[2] == 0 and sq[2, 0] == 0.0 and sq[2, 1] == 0.0 and sq[2, 2] == 0.0 and sq[2, 3] > 0.0
+    # the squares are those of the pinned gradients (cell weights and bias)
+    g = lstm.while_per_example_grads(net, P, lengths, labels, 100, wv, -0.1)
+    np.testing.assert_allclose(sq[:, 0], (g["dW"] ** 2).sum(axis=(1, 2)), rtol=1e-13)
+    np.testing.assert_allclose(sq[:, 1], (g["db"] ** 2).sum(axis=1), rtol=1e-13)
+    # iterations are independent
+    order = [3, 0, 4, 2, 5, 1]
+    Pp = np.concatenate([X[b, :lengths[b]] for b in order])
+    sq2, norm2, loss2, steps2 = lstm.while_per_example_grad_norms(net, Pp, [lengths[b] for b in order], labels[order],
+                                                                  100, wv, -0.1)
+    np.testing.assert_array_equal(sq2, sq[order])
+    np.testing.assert_array_equal(norm2, norm[order])
+    np.testing.assert_array_equal(steps2, steps[order])
+    # the cap
+    short = lstm.Lstm(net.W, net.b, net.Wout, net.bout, 2)
+    ssq, snorm, sloss = lstm.per_example_grad_norms(short, X[:, :2], labels)
+    sq3, norm3, loss3, steps3 = lstm.while_per_example_grad_norms(net, X.reshape(B * T, dx), [T] * B, labels, 2, None, -1.0)
+    assert steps3.tolist() == [2] * B
+    np.testing.assert_allclose(sq3, ssq, rtol=1e-13)

@@ -72,6 +72,7 @@ MUTANTS = [
 LSTM_SRC = os.path.join(ROOT, "oracle", "lstm_oracle.c")
 
 WHILE_GRADS = "void lstmo_body_while_grads("
+WHILE_NORMS = "void lstmo_body_while_grad_norm("
 
 LSTM_MUTANTS = [
     ("norm_cross_term", "for (size_t e = 0; e < nW; ++e) s[0] += dW[e] * dW[e];",
@@ -159,6 +160,23 @@ LSTM_MUTANTS = [
      "labels[i], dW ? dW + (size_t)(B - 1 - i) * nW : NULL,", WHILE_GRADS),
     ("while_grads_sequence_offset", "lstmo_body_while_grads(net, X + (size_t)offsets[i] * net->dx,",
      "lstmo_body_while_grads(net, X + (size_t)offsets[i] * net->dx + (i > 0 ? net->dx : 0),", WHILE_GRADS),
+    # norms of the gradients through the while loop: mistakes planted in that function and its pfor
+    ("while_norms_cross_term", "for (size_t e = 0; e < nW; ++e) s[0] += dW[e] * dW[e];",
+     "for (size_t e = 0; e < nW; ++e) s[0] += dW[e] * dW[(e + 1) % nW];", WHILE_NORMS),
+    ("while_norms_bias_block_dropped", "if (norm) *norm = sqrt(s[0] + s[1] + s[2] + s[3]);",
+     "if (norm) *norm = sqrt(s[0] + s[2] + s[3]);", WHILE_NORMS),
+    ("while_norms_blocks_swapped", "for (size_t e = 0; e < nWo; ++e) s[2] += dWout[e] * dWout[e];",
+     "for (size_t e = 0; e < nWo; ++e) s[3] += dWout[e] * dWout[e];", WHILE_NORMS),
+    ("while_norms_not_a_root", "if (norm) *norm = sqrt(s[0] + s[1] + s[2] + s[3]);",
+     "if (norm) *norm = s[0] + s[1] + s[2] + s[3];", WHILE_NORMS),
+    ("while_norms_cap_ignored", "lstmo_body_while_grads(net, x, len, max_steps, halt_w, halt_c, label, dW,",
+     "lstmo_body_while_grads(net, x, len, len, halt_w, halt_c, label, dW,", WHILE_NORMS),
+    ("while_norms_condition_dropped", "lstmo_body_while_grads(net, x, len, max_steps, halt_w, halt_c, label, dW,",
+     "lstmo_body_while_grads(net, x, len, max_steps, NULL, halt_c, label, dW,", WHILE_NORMS),
+    ("while_norms_stacking", "labels[i], sq ? sq + 4 * i : NULL, norm ? norm + i : NULL,",
+     "labels[i], sq ? sq + 4 * (B - 1 - i) : NULL, norm ? norm + i : NULL,", WHILE_NORMS),
+    ("while_norms_sequence_offset", "lstmo_body_while_grad_norm(net, X + (size_t)offsets[i] * net->dx,",
+     "lstmo_body_while_grad_norm(net, X + (size_t)offsets[i] * net->dx + (i > 0 ? net->dx : 0),", WHILE_NORMS),
 ]
 
 
@@ -275,6 +293,8 @@ def run_mutants(oracle, tmp_path, source, mutants, env_var, pins_file):
         name, old, new = m[:3]
         start = src.index(m[3]) if len(m) > 3 else 0
         end = src.index(WHILE_GRADS) if len(m) == 3 and WHILE_GRADS in src else len(src)
+        if len(m) > 3 and m[3] == WHILE_GRADS and WHILE_NORMS in src:
+            end = src.index(WHILE_NORMS)
         assert src.count(old, start, end) >= 1, f"pattern for {name} not found in {os.path.basename(source)}"
         return src[:start] + src[start:end].replace(old, new) + src[end:]
 
