@@ -410,12 +410,19 @@ def main():
         B, H, dx, dy = w.B, w.H, w.dx, w.dy
         tokens = int(lengths.sum())
         f32 = dict(dtype=torch.float32, device=dev)
-        out = {"dW": torch.empty((B, dx + H, 4 * H), **f32), "db": torch.empty((B, 4 * H), **f32),
-               "dWout": torch.empty((B, H, dy), **f32), "dbout": torch.empty((B, dy), **f32),
-               "loss": torch.empty((B,), **f32), "steps": torch.empty((B,), dtype=torch.int32, device=dev)}
+        norms = (w.call == "lstm_while_per_example_grad_norms")
         ws = torch.empty(pfg.pfg_lstm_while_grads_workspace_bytes(net, B, tokens, w.T), dtype=torch.uint8, device=dev)
-        step = lambda: pfg.pfg_lstm_while_per_example_grads(net, X, off, labels, w.T, halt_w=hw, halt_c=halt_c,
-                                                            out=out, workspace=ws)
+        if norms:
+            out = {"sq": torch.empty((B, 4), **f32), "norm": torch.empty((B,), **f32), "loss": torch.empty((B,), **f32),
+                   "steps": torch.empty((B,), dtype=torch.int32, device=dev)}
+            step = lambda: pfg.pfg_lstm_while_per_example_grad_norms(net, X, off, labels, w.T, halt_w=hw,
+                                                                     halt_c=halt_c, out=out, workspace=ws)
+        else:
+            out = {"dW": torch.empty((B, dx + H, 4 * H), **f32), "db": torch.empty((B, 4 * H), **f32),
+                   "dWout": torch.empty((B, H, dy), **f32), "dbout": torch.empty((B, dy), **f32),
+                   "loss": torch.empty((B,), **f32), "steps": torch.empty((B,), dtype=torch.int32, device=dev)}
+            step = lambda: pfg.pfg_lstm_while_per_example_grads(net, X, off, labels, w.T, halt_w=hw, halt_c=halt_c,
+                                                                out=out, workspace=ws)
         step()
         torch.cuda.synchronize()
         used = int(out["steps"].sum().item())
@@ -428,18 +435,32 @@ def main():
             except Exception as e:
                 log(f"[bench] {name}: graph replay not measured ({e})")
         kt = kernel_times(step, steps)
-        # the one large output is the stacked weight gradient: 4 bytes per value of dW and db
-        fam = "outer_sum_ragged"
-        nbytes = 4 * B * (dx + H + 1) * 4 * H
-        gbs = nbytes / kt[fam]["ms_per_step"] / 1e6
-        roof = {"kernel": fam, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": gbs / HBM_PEAK_GBS, "traffic": None,
-                "bytes_per_launch": nbytes / kt[fam]["launches_per_step"],
-                "ms_per_launch": kt[fam]["ms_per_step"] / kt[fam]["launches_per_step"],
-                "launches_per_step": kt[fam]["launches_per_step"],
-                "note": "the writer sums an iteration's trips (2 * tokens_consumed * (dx + H) * 4H flops on the "
-                        "vector units) before it stores; the rest of the step is two chains of dependent "
-                        "launches, one per forward and reverse trip"}
+        if norms:
+            # no large output: the Gram kernel reads x, h and dz of every consumed token once and multiplies the
+            # rows of every iteration with each other on the matrix cores; priced by the flops of the tiles it runs
+            fam = "while_grad_sqnorms"
+            tl = np.minimum(out["steps"].cpu().numpy(), 128)
+            tiles = (((tl + 31) // 32) * ((tl + 31) // 32 + 1) // 2).sum()
+            flops = float(tiles) * 2 * 32 * 32 * (4 * H + dx + H)
+            tf = flops / kt[fam]["ms_per_step"] / 1e9
+            roof = {"kernel": fam, "bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS["f32"],
+                    "unit": "TFLOP/s", "frac": tf / MFMA_PEAK_TFLOPS["f32"], "traffic": None,
+                    "flops_per_launch": flops, "ms_per_launch": kt[fam]["ms_per_step"],
+                    "launches_per_step": kt[fam]["launches_per_step"],
+                    "note": "the step itself is the two chains of dependent launches, one per forward and reverse trip"}
+        else:
+            # the one large output is the stacked weight gradient: 4 bytes per value of dW and db
+            fam = "outer_sum_ragged"
+            nbytes = 4 * B * (dx + H + 1) * 4 * H
+            gbs = nbytes / kt[fam]["ms_per_step"] / 1e6
+            roof = {"kernel": fam, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                    "bytes_per_launch": nbytes / kt[fam]["launches_per_step"],
+                    "ms_per_launch": kt[fam]["ms_per_step"] / kt[fam]["launches_per_step"],
+                    "launches_per_step": kt[fam]["launches_per_step"],
+                    "note": "the writer forms an iteration's product over its trips (2 * tokens_consumed * (dx + H) * 4H "
+                            "flops on the matrix cores) before it stores; the rest of the step is two chains of "
+                            "dependent launches, one per forward and reverse trip"}
         rec = {"workload": name, "call": w.call, "input_size": dx, "state_size": H, "output_size": dy,
                "dtype": "f32", "B": B, "tokens": tokens, "tokens_consumed": used, "max_steps": w.T, "steps": steps,
                "ms_per_step": sec * 1e3,
@@ -656,7 +677,7 @@ def main():
             return measure_varlen(name, steps, warmup)
         if w.call == "lstm_while_forward":
             return measure_while(name, steps, warmup)
-        if w.call == "lstm_while_per_example_grads":
+        if w.call in ("lstm_while_per_example_grads", "lstm_while_per_example_grad_norms"):
             return measure_while_grads(name, steps, warmup)
         log(f"[bench] {name}: uploading inputs")
         inp = wl.make_lstm_inputs(w)
@@ -877,6 +898,7 @@ def main():
                             ("c9_lstm_varlen", max(3, args.steps)),
                             ("c12_lstm_while", max(3, args.steps)),
                             ("c14_lstm_while_grads", max(3, args.steps)),
+                            ("c14_lstm_while_grad_norms", max(3, args.steps)),
                             ("c10_mnist_convnet_grads", max(3, args.steps)),
                             ("c10_mnist_convnet_grad_norms", max(3, args.steps)),
                             ("c11_cond_two_branches", max(3, args.steps * 2)),

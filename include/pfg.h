@@ -334,6 +334,24 @@ int pfg_lstm_while_per_example_grads(const pfg_lstm *net, const void *X, const i
                                      float *dWout_out, float *dbout_out, float *loss_out, int32_t *steps_out,
                                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Norms of those per-example gradients without the gradients (what per-example clipping needs,
+ * Section 5.3): the same forward and reverse loops, then per iteration, with u_t = [x_t | h_{t-1}]
+ * and dz_t the cotangent of the gate pre-activations of its trip t,
+ *      |dW|^2 = |sum_t u_t^T dz_t|^2 = sum_{t, t'} (u_t . u_t') (dz_t . dz_t'),    |db|^2 = sum_{t, t'} dz_t . dz_t',
+ *      |dWout|^2 = |h|^2 |d ell / d y|^2,    |dbout|^2 = |d ell / d y|^2
+ * from two T_i x T_i Gram matrices per iteration; the stacked gradient [B, input_size + state_size,
+ * 4 * state_size] is never written.  Arguments as for pfg_lstm_while_per_example_grads, and
+ *   max_steps     HOST, 0 .. 128
+ *   sq_out        DEVICE [B, 4] or NULL: |dW|^2, |db|^2, |dWout|^2, |dbout|^2
+ *   norm_out      DEVICE [B] or NULL: the root of their sum           (at least one of the two)
+ *   loss_out      DEVICE [B] or NULL;  steps_out  DEVICE [B] int32 or NULL
+ * Workspace: pfg_lstm_while_grads_workspace_bytes. */
+int pfg_lstm_while_per_example_grad_norms(const pfg_lstm *net, const void *X, const int32_t *seq_offsets,
+                                          const int32_t *labels, int64_t B, int64_t total_tokens, int32_t max_steps,
+                                          const float *halt_w, float halt_c, float *sq_out, float *norm_out,
+                                          float *loss_out, int32_t *steps_out, void *workspace,
+                                          size_t workspace_bytes, void *hip_stream);
+
 /* ------------------------------------------------------------------------------------------
  * Convolutional network of the paper's MNIST benchmarks (Section 6.1: conv-relu-maxpool blocks
  * followed by dense layers; the dropout of that model is a stateful random op and is left out).

@@ -32,6 +32,7 @@ EXPORTS = ["pfg_workspace_bytes", "pfg_per_example_grads", "pfg_per_example_grad
            "pfg_lstm_varlen_workspace_bytes", "pfg_lstm_varlen_forward",
            "pfg_lstm_while_workspace_bytes", "pfg_lstm_while_forward",
            "pfg_lstm_while_grads_workspace_bytes", "pfg_lstm_while_per_example_grads",
+           "pfg_lstm_while_per_example_grad_norms",
            "pfg_convnet_workspace_bytes", "pfg_convnet_per_example_grads",
            "pfg_convnet_grad_norms_workspace_bytes", "pfg_convnet_per_example_grad_norms",
            "pfg_cond_workspace_bytes", "pfg_cond_forward",
@@ -141,6 +142,8 @@ def load_library() -> ctypes.CDLL:
         lib.pfg_lstm_while_per_example_grads.argtypes = [lstmp, vp, vp, vp, i64, i64, ctypes.c_int32, vp,
                                                          ctypes.c_float, vp, vp, vp, vp, vp, vp, vp,
                                                          ctypes.c_size_t, vp]
+        lib.pfg_lstm_while_per_example_grad_norms.argtypes = [lstmp, vp, vp, vp, i64, i64, ctypes.c_int32, vp,
+                                                              ctypes.c_float, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         convp = ctypes.POINTER(pfg_convnet)
         lib.pfg_convnet_workspace_bytes.argtypes = [convp, i64, ctypes.POINTER(ctypes.c_size_t)]
         lib.pfg_convnet_per_example_grads.argtypes = [convp, vp, vp, i64, ctypes.POINTER(vp),
@@ -631,6 +634,42 @@ def pfg_lstm_while_per_example_grads(net: Lstm, X, seq_offsets, labels, max_step
         int(max_steps), None if halt_w is None else halt_w.data_ptr(), float(halt_c), ptr("dW"), ptr("db"),
         ptr("dWout"), ptr("dbout"), ptr("loss"), ptr("steps"), workspace.data_ptr(),
         workspace.numel() * workspace.element_size(), _stream_ptr()))
+    return res
+
+
+def pfg_lstm_while_per_example_grad_norms(net: Lstm, X, seq_offsets, labels, max_steps: int, halt_w=None,
+                                          halt_c: float = 0.0, want=("sq", "norm", "loss", "steps"), out=None,
+                                          workspace=None):
+    """Norms of the per-example gradients through the while loop (see include/pfg.h).  Returns a dict
+    with the entries named in ``want``: sq [B, 4], norm [B], loss [B], steps [B] int32."""
+    import torch
+    if (seq_offsets.dtype != torch.int32 or not seq_offsets.is_contiguous() or not seq_offsets.is_cuda or
+            seq_offsets.dim() != 1 or seq_offsets.numel() < 2):
+        raise ValueError("seq_offsets must be a contiguous int32 [B + 1] GPU tensor")
+    if X.dtype != torch.float32 or not X.is_contiguous() or X.dim() != 2 or X.shape[1] != net.dx:
+        raise ValueError("X must be a contiguous float32 [total_tokens, input_size] tensor")
+    B, total = seq_offsets.numel() - 1, int(X.shape[0])
+    if labels.dtype != torch.int32 or not labels.is_contiguous() or tuple(labels.shape) != (B,):
+        raise ValueError("labels must be a contiguous int32 [B] tensor")
+    if halt_w is not None and (halt_w.dtype != torch.float32 or not halt_w.is_contiguous() or
+                               tuple(halt_w.shape) != (net.H,)):
+        raise ValueError("halt_w must be a contiguous float32 [state_size] tensor")
+    shapes = {"sq": (B, 4), "norm": (B,), "loss": (B,), "steps": (B,)}
+    res = {}
+    for name in want:
+        if out is not None and name in out:
+            res[name] = out[name]
+        else:
+            res[name] = torch.empty(shapes[name], dtype=torch.int32 if name == "steps" else torch.float32,
+                                    device=net.device)
+    if workspace is None:
+        workspace = torch.empty(pfg_lstm_while_grads_workspace_bytes(net, B, total, max_steps), dtype=torch.uint8,
+                                device=net.device)
+    ptr = lambda name: res[name].data_ptr() if name in res else None
+    _check(load_library().pfg_lstm_while_per_example_grad_norms(
+        ctypes.byref(net.c), X.data_ptr() if total else None, seq_offsets.data_ptr(), labels.data_ptr(), B, total,
+        int(max_steps), None if halt_w is None else halt_w.data_ptr(), float(halt_c), ptr("sq"), ptr("norm"),
+        ptr("loss"), ptr("steps"), workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr()))
     return res
 
 

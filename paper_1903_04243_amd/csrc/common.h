@@ -402,4 +402,13 @@ hipError_t launch_outer_sum_ragged(const float *x, int32_t dx, const float *h_to
                                    const int32_t *seq_offsets, const int32_t *steps, int32_t total_tokens, int64_t B,
                                    float *dW, float *db, hipStream_t stream);
 
+// Squared norms of the per-example gradients through the while loop from the rows the sweeps left by
+// token (Gram identity, no gradient is formed): sq [B, 4] = |dW|^2, |db|^2, |dWout|^2, |dbout|^2 and / or
+// norm [B]; at most kWhileNormMaxTrips trips per iteration are taken into account.
+constexpr int kWhileNormMaxTrips = 128;
+hipError_t launch_while_grad_sqnorms(const float *x, int32_t dx, const float *h_tok, int32_t H, const float *dz_tok,
+                                     const int32_t *seq_offsets, const int32_t *steps, int32_t total_tokens,
+                                     const float *hfin, const float *gy, int32_t dy, int64_t B, float *sq,
+                                     float *norm, hipStream_t stream);
+
 }  // namespace pfg

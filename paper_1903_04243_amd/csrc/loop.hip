@@ -473,6 +473,179 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   }
 }
 
+// Squared norms of the per-example gradients through the while loop without the gradients.  With
+// u_t = [x_t | h_{t-1}] and dz_t the rows of an iteration's trips,
+//   |dW|^2 = |sum_t u_t^T dz_t|^2 = sum_{t, t'} (u_t . u_t') (dz_t . dz_t'),     |db|^2 = sum_{t, t'} dz_t . dz_t',
+// i.e. the entries of the two T x T Gram matrices multiplied and added; |dWout|^2 = |h|^2 |gy|^2 and
+// |dbout|^2 = |gy|^2 from the last state h and gy = d ell / d y.  One workgroup per iteration, at most
+// kNormTrips trips.  The Gram matrices are products with themselves on the matrix cores: the rows of
+// the operand (first dz, 4H long, then u, dx + H long) go through LDS in chunks of kNormK elements,
+// fetched while the previous chunk is multiplied; only the 32 x 32 tiles on and above the diagonal that
+// hold a trip are computed (each wave takes every fourth, at most three), an off-diagonal tile counts
+// twice.  Rows past the last trip are staged as zeros.  Everything is added in a fixed order.
+constexpr int kNormTrips = 128;
+constexpr int kNormK = 64;
+constexpr int kNormLd = kNormK + 1;      // row stride in floats: 32 consecutive rows of one column hit 32 banks
+constexpr int kNormPieces = kNormTrips * (kNormK / 4) / 256;   // 16-byte pieces a thread stages per chunk
+
+struct WhileNormArgs {
+  const float *x; int dx;
+  const float *h_tok; int H;
+  const float *dz_tok;           // [tokens, 4H]
+  const int32_t *seq_offsets;    // [B + 1]
+  const int32_t *steps;          // [B]
+  int total_tokens;
+  const float *hfin;             // [B, H] last states
+  const float *gy; int dy;       // [B, dy]
+  float *sq;                     // [B, 4] or nullptr
+  float *norm;                   // [B] or nullptr
+  int vec;                       // x, h_tok 16-byte aligned, dx and H multiples of 4
+};
+
+__global__ __launch_bounds__(256) void while_grad_sqnorms_kernel(const WhileNormArgs p) {
+  __shared__ float Zs[kNormTrips][kNormLd];
+  __shared__ float red[2][4];
+  __shared__ float tail[2];
+  const int64_t b = blockIdx.x;
+  const int lo = p.seq_offsets[b], hi = min(p.seq_offsets[b + 1], p.total_tokens);
+  const int len = (lo >= 0 && hi > lo) ? hi - lo : 0;
+  const int nt = max(0, min(min(p.steps[b], len), kNormTrips));
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
+  const int G = 4 * p.H, KU = p.dx + p.H;
+  const int nrt = (nt + 31) / 32;                          // row tiles that hold a trip
+  const int ntiles = nrt * (nrt + 1) / 2;
+  const int chunks_z = (G + kNormK - 1) / kNormK, chunks = chunks_z + (KU + kNormK - 1) / kNormK;
+
+  // this wave's tiles (ti <= tj), numbered row by row over the upper triangle
+  int ti[3], tj[3];
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    int q = wave + 4 * j, r = 0;
+    ti[j] = tj[j] = -1;
+    if (q < ntiles) {
+      while (q >= nrt - r) { q -= nrt - r; ++r; }
+      ti[j] = r;
+      tj[j] = r + q;
+    }
+  }
+
+  // staging: piece c of this thread is elements 4 part .. 4 part + 3 of row tl0 + 16 c of the chunk
+  const int part = tid & 15, tl0 = tid >> 4;
+  f32x4 reg[kNormPieces];
+  const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  // element k of the operand row of trip t (clamped to a valid address; what must be zero is zeroed in stash)
+  auto fetch = [&](int c) {                                // nt > 0
+    const bool is_z = c < chunks_z;
+    const int k = (is_z ? c : c - chunks_z) * kNormK + 4 * part;
+    const int K = is_z ? G : KU;
+#pragma unroll
+    for (int i = 0; i < kNormPieces; ++i) {
+      const int t = min(tl0 + 16 * i, nt - 1);
+      if (p.vec || is_z) {
+        const int kc = min(k, K - 4);                      // G, and with vec dx and H, are multiples of 4
+        const float *src = is_z        ? p.dz_tok + (int64_t)(lo + t) * G + kc
+                           : kc < p.dx ? p.x + (int64_t)(lo + t) * p.dx + kc
+                                       : p.h_tok + (int64_t)(lo + max(t - 1, 0)) * p.H + (kc - p.dx);
+        reg[i] = *reinterpret_cast<const f32x4 *>(src);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int ke = min(k + e, K - 1);
+          reg[i][e] = ke < p.dx ? p.x[(int64_t)(lo + t) * p.dx + ke]
+                                : p.h_tok[(int64_t)(lo + max(t - 1, 0)) * p.H + (ke - p.dx)];
+        }
+      }
+    }
+  };
+  auto stash = [&](int c) {
+    const bool is_z = c < chunks_z;
+    const int k = (is_z ? c : c - chunks_z) * kNormK + 4 * part;
+    const int K = is_z ? G : KU;
+#pragma unroll
+    for (int i = 0; i < kNormPieces; ++i) {
+      const int t = tl0 + 16 * i;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        // u_0 has no recurrent part: h before trip 0 is zero
+        const bool live = t < nt && k + e < K && (is_z || k + e < p.dx || t > 0);
+        Zs[t][4 * part + e] = live ? reg[i][e] : 0.f;
+      }
+    }
+  };
+
+  f32x16 az[3], au[3];
+#pragma unroll
+  for (int j = 0; j < 3; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) az[j][r] = au[j][r] = 0.f;
+
+  if (nt > 0) {
+    fetch(0);
+#pragma unroll 1
+    for (int c = 0; c < chunks; ++c) {
+      __syncthreads();                                     // the previous chunk has been read
+      stash(c);
+      __syncthreads();
+      if (c + 1 < chunks) fetch(c + 1);                    // on its way while this chunk is multiplied
+      const bool is_z = c < chunks_z;
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        if (ti[j] < 0) continue;                           // wave-uniform
+        const float *arow = &Zs[32 * ti[j] + l32][half], *brow = &Zs[32 * tj[j] + l32][half];
+        f32x16 acc = is_z ? az[j] : au[j];
+#pragma unroll 8
+        for (int s2 = 0; s2 < kNormK; s2 += 2) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(arow[s2], brow[s2], acc, 0, 0, 0);
+        if (is_z) az[j] = acc; else au[j] = acc;
+      }
+    }
+  }
+
+  // this wave's share: sum over its tiles of Gu o Gz and of Gz (off-diagonal tiles twice)
+  float sw = 0.f, sb = 0.f;
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    if (ti[j] < 0) continue;
+    float tw = 0.f, tb = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      tw += az[j][r] * au[j][r];
+      tb += az[j][r];
+    }
+    const float twice = ti[j] == tj[j] ? 1.f : 2.f;
+    sw += twice * tw;
+    sb += twice * tb;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    sw += __shfl_xor(sw, off, 64);
+    sb += __shfl_xor(sb, off, 64);
+  }
+  if (lane == 0) {
+    red[0][wave] = sw;
+    red[1][wave] = sb;
+  }
+  // the readout: |h|^2 (wave 2) and |gy|^2 (wave 3)
+  if (wave >= 2) {
+    const float *v = wave == 2 ? p.hfin + b * (int64_t)p.H : p.gy + b * (int64_t)p.dy;
+    const int n = wave == 2 ? p.H : p.dy;
+    float s = 0.f;
+    for (int k = lane; k < n; k += 64) s += v[k] * v[k];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) tail[wave - 2] = s;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const float w2 = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+    const float b2 = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    const float so = tail[0] * tail[1], sbo = tail[1];
+    if (p.sq) {
+      p.sq[4 * b] = w2; p.sq[4 * b + 1] = b2; p.sq[4 * b + 2] = so; p.sq[4 * b + 3] = sbo;
+    }
+    if (p.norm) p.norm[b] = sqrtf(w2 + b2 + so + sbo);
+  }
+}
+
 }  // namespace
 
 int64_t while_count_entries(int64_t B) { return (B + kGroup - 1) / kGroup + (B + kPlace - 1) / kPlace; }
@@ -538,6 +711,22 @@ hipError_t launch_outer_sum_ragged(const float *x, int32_t dx, const float *h_to
   else
     PFG_KERNEL(outer_sum_ragged_kernel<NT>, dim3((unsigned)(p.mm_blocks + bias_blocks), (unsigned)B), dim3(256), 0,
                stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_while_grad_sqnorms(const float *x, int32_t dx, const float *h_tok, int32_t H, const float *dz_tok,
+                                     const int32_t *seq_offsets, const int32_t *steps, int32_t total_tokens,
+                                     const float *hfin, const float *gy, int32_t dy, int64_t B, float *sq,
+                                     float *norm, hipStream_t stream) {
+  if (B <= 0 || (!sq && !norm)) return hipSuccess;
+  if (B > 0x7fffffffLL || (reinterpret_cast<uintptr_t>(dz_tok) & 15)) return hipErrorInvalidValue;
+  WhileNormArgs p{};
+  p.x = x; p.dx = dx; p.h_tok = h_tok; p.H = H; p.dz_tok = dz_tok;
+  p.seq_offsets = seq_offsets; p.steps = steps; p.total_tokens = total_tokens;
+  p.hfin = hfin; p.gy = gy; p.dy = dy; p.sq = sq; p.norm = norm;
+  p.vec = (((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(h_tok)) & 15) == 0 && dx % 4 == 0 &&
+           H % 4 == 0) ? 1 : 0;
+  PFG_KERNEL(while_grad_sqnorms_kernel, dim3((unsigned)B), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 

@@ -348,6 +348,92 @@ int check_while_grads_sizes(const pfg_lstm *net, int64_t B, int64_t tokens, int3
   return PFG_OK;
 }
 
+// Argument checks shared by the two calls that differentiate the while loop.
+int check_while_grads_call(const pfg_lstm *net, const void *X, const int32_t *seq_offsets, const int32_t *labels,
+                           int64_t B, int64_t total_tokens, int32_t max_steps) {
+  int rc = check_lstm(net);
+  if (rc) return rc;
+  if (!X && total_tokens > 0) return fail(PFG_ERR_NULL, "X is NULL");
+  if (!seq_offsets) return fail(PFG_ERR_NULL, "seq_offsets is NULL");
+  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
+  return check_while_grads_sizes(net, B, total_tokens, max_steps);
+}
+
+int check_while_ws(const WhilePlan &p, const void *workspace, size_t workspace_bytes) {
+  if (!workspace) return fail(PFG_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", p.total);
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(PFG_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  if (workspace_bytes < p.total)
+    return fail(PFG_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, p.total);
+  return PFG_OK;
+}
+
+// The loop, the head and -- if sweep -- the reverse loop of the gradient calls.  Leaves the last states
+// in p.hfin, d ell / d y in gy, and with sweep the hidden states (p.hs) and dz (p.dz) of every trip by
+// token row.
+int while_sweeps(const pfg_lstm *net, const void *X, const int32_t *seq_offsets, const int32_t *labels, int64_t B,
+                 int64_t total_tokens, int32_t max_steps, const float *halt_w, float halt_c, float *gy, float *loss_out,
+                 int32_t *steps, bool sweep, void *ws, const WhilePlan &p, hipStream_t stream) {
+  const int32_t dx = net->input_size, H = net->state_size, dy = net->output_size;
+  auto ints = [&](size_t off) { return reinterpret_cast<int32_t *>(static_cast<char *>(ws) + off); };
+  float *hbuf[2] = {ws_at(ws, p.state), ws_at(ws, p.state) + B * (int64_t)H};
+  int rc = while_forward_loop(net, X, seq_offsets, B, total_tokens, max_steps, halt_w, halt_c, steps, nullptr, ws, p,
+                              sweep, stream);
+  if (rc) return rc;
+
+  // ---- behind the loop: last states, readout, loss head ----
+  float *hfin = ws_at(ws, p.hfin);
+  PFG_LAUNCH("while_state", launch_while_state(steps, hbuf[0], hbuf[1], B, H, hfin, stream));
+  {
+    GemmArgs g{};
+    g.A = hfin; g.lda = H; g.a_batch_stride = H; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->W_out; g.ldw = dy; g.w_kn = 1;
+    g.M = (int32_t)B; g.N = dy; g.K = H;
+    g.bias = net->b_out; g.ldc = dy;
+    if (dy <= 32) {
+      g.epilogue = EPI_HEAD; g.C = nullptr; g.C2 = gy; g.labels = labels; g.loss = loss_out;
+      PFG_LAUNCH("lstm_gemm_readout", launch_gemm(g, stream));
+    } else {
+      g.epilogue = EPI_BIAS; g.C = ws_at(ws, p.y);
+      PFG_LAUNCH("lstm_gemm_readout", launch_gemm(g, stream));
+      PFG_LAUNCH("head", launch_head_softmax_ce(ws_at(ws, p.y), labels, B, dy, gy, loss_out, stream));
+    }
+  }
+  if (!sweep) return PFG_OK;
+
+  // ---- the reverse sweep.  Every iteration enters it at its own last trip with the cotangent of its
+  // final state, dh = (d ell / d y) W_out^T, and dc = 0.  Reverse trip t runs on the list the forward
+  // loop kept for trip t: one product carries dz_{t+1} W_h^T to the rows of that list (dz by iteration,
+  // two buffers used alternately; the row of an iteration that made no trip t + 1 is still zero), and
+  // its epilogue adds the seed where trip t is the iteration's last, updates dc and writes dz_t. ----
+  float *seed = ws_at(ws, p.dh), *dc = ws_at(ws, p.dc), *dz = ws_at(ws, p.dz);
+  float *dzi[2] = {ws_at(ws, p.dzp), ws_at(ws, p.dzp) + B * (int64_t)4 * H};
+  {
+    GemmArgs g{};
+    g.A = gy; g.lda = dy; g.a_batch_stride = dy; g.S = 1; g.a_is_f32 = 1;
+    g.W = net->W_out; g.ldw = dy; g.w_kn = 0;
+    g.M = (int32_t)B; g.N = H; g.K = dy;
+    g.epilogue = EPI_NONE; g.C = seed; g.ldc = H;
+    PFG_LAUNCH("lstm_gemm_cotangent", launch_gemm(g, stream));
+  }
+  PFG_LAUNCH("fill_zero", launch_fill_zero(dc, B * (int64_t)H * 9, stream));
+  const float *Wh = static_cast<const float *>(net->W) + (int64_t)dx * 4 * H;
+  for (int32_t t = max_steps - 1; t >= 0; --t) {
+    GemmArgs g{};
+    g.A = dzi[(t + 1) & 1]; g.lda = 4 * H; g.a_batch_stride = 4 * H; g.S = 1; g.a_is_f32 = 1;
+    g.W = Wh; g.ldw = 4 * H; g.w_kn = 0;
+    g.M = (int32_t)B; g.N = H; g.K = 4 * H;
+    g.epilogue = EPI_LSTM_BWD; g.n_split = 0;
+    g.lstm_H = H; g.lstm_T = 1; g.lstm_step = t;
+    g.lstm_gates = ws_at(ws, p.gates); g.lstm_cs = ws_at(ws, p.cs); g.lstm_zx_rows = seq_offsets;
+    g.lstm_dc = dc; g.lstm_dz = dzi[t & 1]; g.lstm_dz_ld = 4 * H; g.lstm_tok_dz = dz;
+    g.lstm_seed = seed; g.lstm_steps = steps;
+    g.sub = ints(p.meta) + 2 * (t + 1); g.sub_rows = ints(p.list) + (int64_t)(t + 1) * B;
+    g.sub_gather = 1; g.sub_scatter = 0;
+    PFG_LAUNCH("lstm_gemm_reverse", launch_gemm(g, stream));
+  }
+  return PFG_OK;
+}
+
 int check_varlen_sizes(const pfg_lstm *net, int64_t B, int64_t tokens) {
   if (B < 1) return fail(PFG_ERR_SHAPE, "B = %lld must be at least 1", (long long)B);
   if (tokens < B) return fail(PFG_ERR_SHAPE, "total_tokens = %lld is less than B = %lld", (long long)tokens, (long long)B);
@@ -567,93 +653,62 @@ int pfg_lstm_while_per_example_grads(const pfg_lstm *net, const void *X, const i
                                      float *dWout_out, float *dbout_out, float *loss_out, int32_t *steps_out,
                                      void *workspace, size_t workspace_bytes, void *hip_stream) {
   clear_error();
-  int rc = check_lstm(net);
+  int rc = check_while_grads_call(net, X, seq_offsets, labels, B, total_tokens, max_steps);
   if (rc) return rc;
-  if (!X && total_tokens > 0) return fail(PFG_ERR_NULL, "X is NULL");
-  if (!seq_offsets) return fail(PFG_ERR_NULL, "seq_offsets is NULL");
-  if (!labels) return fail(PFG_ERR_NULL, "labels is NULL");
   if (!dW_out && !db_out && !dWout_out && !dbout_out && !loss_out)
     return fail(PFG_ERR_NULL, "dW_out, db_out, dWout_out, dbout_out and loss_out are all NULL");
-  if ((rc = check_while_grads_sizes(net, B, total_tokens, max_steps))) return rc;
   const WhilePlan p = make_while_plan(net, B, total_tokens, (int64_t)max_steps + 1, true);
-  if (!workspace) return fail(PFG_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", p.total);
-  if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(PFG_ERR_WORKSPACE, "workspace is not 256-byte aligned");
-  if (workspace_bytes < p.total)
-    return fail(PFG_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, p.total);
+  if ((rc = check_while_ws(p, workspace, workspace_bytes))) return rc;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const int32_t dx = net->input_size, H = net->state_size, dy = net->output_size;
   void *ws = workspace;
-  auto ints = [&](size_t off) { return reinterpret_cast<int32_t *>(static_cast<char *>(ws) + off); };
-  float *hbuf[2] = {ws_at(ws, p.state), ws_at(ws, p.state) + B * (int64_t)H};
-  int32_t *steps = steps_out ? steps_out : ints(p.steps);
+  int32_t *steps = steps_out ? steps_out : reinterpret_cast<int32_t *>(static_cast<char *>(ws) + p.steps);
+  float *gy = dbout_out ? dbout_out : ws_at(ws, p.gy);      // d ell / d y lands in dbout when given
   const bool sweep = dW_out || db_out;      // the reverse trips are needed for the cell's parameters only
-  if ((rc = while_forward_loop(net, X, seq_offsets, B, total_tokens, max_steps, halt_w, halt_c, steps, nullptr, ws, p,
-                               sweep, stream)))
+  if ((rc = while_sweeps(net, X, seq_offsets, labels, B, total_tokens, max_steps, halt_w, halt_c, gy, loss_out, steps,
+                         sweep, ws, p, stream)))
     return rc;
-
-  // ---- behind the loop: last states, readout, loss head (d ell / d y lands in dbout when given) ----
-  float *hfin = ws_at(ws, p.hfin);
-  PFG_LAUNCH("while_state", launch_while_state(steps, hbuf[0], hbuf[1], B, H, hfin, stream));
-  float *gy = dbout_out ? dbout_out : ws_at(ws, p.gy);
-  {
-    GemmArgs g{};
-    g.A = hfin; g.lda = H; g.a_batch_stride = H; g.S = 1; g.a_is_f32 = 1;
-    g.W = net->W_out; g.ldw = dy; g.w_kn = 1;
-    g.M = (int32_t)B; g.N = dy; g.K = H;
-    g.bias = net->b_out; g.ldc = dy;
-    if (dy <= 32) {
-      g.epilogue = EPI_HEAD; g.C = nullptr; g.C2 = gy; g.labels = labels; g.loss = loss_out;
-      PFG_LAUNCH("lstm_gemm_readout", launch_gemm(g, stream));
-    } else {
-      g.epilogue = EPI_BIAS; g.C = ws_at(ws, p.y);
-      PFG_LAUNCH("lstm_gemm_readout", launch_gemm(g, stream));
-      PFG_LAUNCH("head", launch_head_softmax_ce(ws_at(ws, p.y), labels, B, dy, gy, loss_out, stream));
-    }
-  }
   if (dWout_out) {
     OuterArgs o{};
-    o.a = hfin; o.lda = H; o.a_bf16 = 0; o.g = gy; o.ldg = dy; o.out = dWout_out;
+    o.a = ws_at(ws, p.hfin); o.lda = H; o.a_bf16 = 0; o.g = gy; o.ldg = dy; o.out = dWout_out;
     o.M = B; o.S = 1; o.d_in = H; o.d_out = dy;
     PFG_LAUNCH("outer_product", launch_outer(&o, 1, stream));
   }
   if (!sweep) return PFG_OK;
-
-  // ---- the reverse sweep.  Every iteration enters it at its own last trip with the cotangent of its
-  // final state, dh = (d ell / d y) W_out^T, and dc = 0.  Reverse trip t runs on the list the forward
-  // loop kept for trip t: one product carries dz_{t+1} W_h^T to the rows of that list (dz by iteration,
-  // two buffers used alternately; the row of an iteration that made no trip t + 1 is still zero), and
-  // its epilogue adds the seed where trip t is the iteration's last, updates dc and writes dz_t. ----
-  float *seed = ws_at(ws, p.dh), *dc = ws_at(ws, p.dc), *dz = ws_at(ws, p.dz);
-  float *dzi[2] = {ws_at(ws, p.dzp), ws_at(ws, p.dzp) + B * (int64_t)4 * H};
-  {
-    GemmArgs g{};
-    g.A = gy; g.lda = dy; g.a_batch_stride = dy; g.S = 1; g.a_is_f32 = 1;
-    g.W = net->W_out; g.ldw = dy; g.w_kn = 0;
-    g.M = (int32_t)B; g.N = H; g.K = dy;
-    g.epilogue = EPI_NONE; g.C = seed; g.ldc = H;
-    PFG_LAUNCH("lstm_gemm_cotangent", launch_gemm(g, stream));
-  }
-  PFG_LAUNCH("fill_zero", launch_fill_zero(dc, B * (int64_t)H * 9, stream));
-  const float *Wh = static_cast<const float *>(net->W) + (int64_t)dx * 4 * H;
-  for (int32_t t = max_steps - 1; t >= 0; --t) {
-    GemmArgs g{};
-    g.A = dzi[(t + 1) & 1]; g.lda = 4 * H; g.a_batch_stride = 4 * H; g.S = 1; g.a_is_f32 = 1;
-    g.W = Wh; g.ldw = 4 * H; g.w_kn = 0;
-    g.M = (int32_t)B; g.N = H; g.K = 4 * H;
-    g.epilogue = EPI_LSTM_BWD; g.n_split = 0;
-    g.lstm_H = H; g.lstm_T = 1; g.lstm_step = t;
-    g.lstm_gates = ws_at(ws, p.gates); g.lstm_cs = ws_at(ws, p.cs); g.lstm_zx_rows = seq_offsets;
-    g.lstm_dc = dc; g.lstm_dz = dzi[t & 1]; g.lstm_dz_ld = 4 * H; g.lstm_tok_dz = dz;
-    g.lstm_seed = seed; g.lstm_steps = steps;
-    g.sub = ints(p.meta) + 2 * (t + 1); g.sub_rows = ints(p.list) + (int64_t)(t + 1) * B;
-    g.sub_gather = 1; g.sub_scatter = 0;
-    PFG_LAUNCH("lstm_gemm_reverse", launch_gemm(g, stream));
-  }
   // ---- per iteration, the sums over its own trips (the same W acts in every trip) ----
   PFG_LAUNCH("outer_sum_ragged",
-             launch_outer_sum_ragged(static_cast<const float *>(X), dx, ws_at(ws, p.hs), H, dz, seq_offsets, steps,
-                                     (int32_t)total_tokens, B, dW_out, db_out, stream));
+             launch_outer_sum_ragged(static_cast<const float *>(X), dx, ws_at(ws, p.hs), H, ws_at(ws, p.dz), seq_offsets,
+                                     steps, (int32_t)total_tokens, B, dW_out, db_out, stream));
+  return PFG_OK;
+}
+
+int pfg_lstm_while_per_example_grad_norms(const pfg_lstm *net, const void *X, const int32_t *seq_offsets,
+                                          const int32_t *labels, int64_t B, int64_t total_tokens, int32_t max_steps,
+                                          const float *halt_w, float halt_c, float *sq_out, float *norm_out,
+                                          float *loss_out, int32_t *steps_out, void *workspace,
+                                          size_t workspace_bytes, void *hip_stream) {
+  clear_error();
+  int rc = check_while_grads_call(net, X, seq_offsets, labels, B, total_tokens, max_steps);
+  if (rc) return rc;
+  if (!sq_out && !norm_out) return fail(PFG_ERR_NULL, "sq_out and norm_out are both NULL");
+  if (max_steps > kWhileNormMaxTrips)
+    return fail(PFG_ERR_UNSUPPORTED, "gradient norms through the while loop take at most %d trips (max_steps = %d)",
+                kWhileNormMaxTrips, max_steps);
+  const WhilePlan p = make_while_plan(net, B, total_tokens, (int64_t)max_steps + 1, true);
+  if ((rc = check_while_ws(p, workspace, workspace_bytes))) return rc;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  void *ws = workspace;
+  int32_t *steps = steps_out ? steps_out : reinterpret_cast<int32_t *>(static_cast<char *>(ws) + p.steps);
+  float *gy = ws_at(ws, p.gy);
+  if ((rc = while_sweeps(net, X, seq_offsets, labels, B, total_tokens, max_steps, halt_w, halt_c, gy, loss_out, steps,
+                         true, ws, p, stream)))
+    return rc;
+  PFG_LAUNCH("while_grad_sqnorms",
+             launch_while_grad_sqnorms(static_cast<const float *>(X), net->input_size, ws_at(ws, p.hs), net->state_size,
+                                       ws_at(ws, p.dz), seq_offsets, steps, (int32_t)total_tokens, ws_at(ws, p.hfin), gy,
+                                       net->output_size, B, sq_out, norm_out, stream));
   return PFG_OK;
 }
 

@@ -180,6 +180,8 @@ LSTM_WORKLOADS: Dict[str, LstmWorkload] = {
         LstmWorkload("c12_lstm_while", 8, "lstm_while_forward", 128, 256, 10, 100, 1024),
         # per-example gradients through that loop (the same sequences, condition and labels drawn for them)
         LstmWorkload("c14_lstm_while_grads", 8, "lstm_while_per_example_grads", 128, 256, 10, 100, 1024),
+        # the same call with only the norms of the gradients leaving the device
+        LstmWorkload("c14_lstm_while_grad_norms", 8, "lstm_while_per_example_grad_norms", 128, 256, 10, 100, 1024),
     ]
 }
 

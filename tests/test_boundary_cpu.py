@@ -369,6 +369,24 @@ def test_lstm_while_grads_workspace_and_rejections(lib):
     assert fn(r, FAKE, FAKE, FAKE, 3, 7, 5, None, 0.0, *ok, FAKE, 64, None) == pfg.PFG_ERR_WORKSPACE
 
 
+def test_lstm_while_grad_norms_rejections(lib):
+    net = make_lstm()
+    r = ctypes.byref(net)
+    fn = lib.pfg_lstm_while_per_example_grad_norms
+    vp = ctypes.c_void_p
+    fn.argtypes = [ctypes.POINTER(pfg.pfg_lstm), vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, vp,
+                   ctypes.c_float, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    big = 1 << 40
+    assert fn(r, FAKE, FAKE, FAKE, 3, 7, 5, None, 0.0, None, None, FAKE, FAKE, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert "sq_out and norm_out" in lib.pfg_last_error().decode()
+    assert fn(r, FAKE, FAKE, None, 3, 7, 5, None, 0.0, FAKE, FAKE, None, None, FAKE, big, None) == pfg.PFG_ERR_NULL
+    assert fn(r, FAKE, FAKE, FAKE, 3, 7, 129, None, 0.0, FAKE, FAKE, None, None, FAKE, big, None) == pfg.PFG_ERR_UNSUPPORTED
+    assert "128" in lib.pfg_last_error().decode()
+    assert fn(r, FAKE, FAKE, FAKE, 3, 7, -1, None, 0.0, FAKE, FAKE, None, None, FAKE, big, None) == pfg.PFG_ERR_SHAPE
+    assert fn(r, FAKE, FAKE, FAKE, 3, 7, 5, None, 0.0, FAKE, None, None, None, FAKE, 64, None) == pfg.PFG_ERR_WORKSPACE
+    assert fn(r, FAKE, FAKE, FAKE, 3, 7, 5, None, 0.0, None, FAKE, None, None, None, big, None) == pfg.PFG_ERR_WORKSPACE
+
+
 def make_convnet(h=28, w=28, c=1, kernel=(5, 5), filters=(32, 64), dense=(3136, 1024, 10), Wc_null=None,
                  dtype=0):
     nc = len(kernel)

@@ -310,6 +310,109 @@ def test_c14_lstm_while_grads_full_size():
         assert not bool(res["dW"][none].any()) and not bool(res["dWout"][none].any())
 
 
+# --------------------------------------------------------------------------------------------
+# Norms of those gradients without the gradients (two Gram matrices per iteration).
+# --------------------------------------------------------------------------------------------
+def check_norms(inp, lengths, labels, max_steps, halt_w, halt_c, tag, min_robust=0.9):
+    onet = olstm.Lstm(inp.W, inp.b, inp.Wout, inp.bout, 1)
+    net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, 1)
+    B = len(lengths)
+    f32 = dict(dtype=torch.float32, device="cuda:0")
+    out = {"sq": torch.full((B, 4), float("nan"), **f32), "norm": torch.full((B,), float("nan"), **f32),
+           "loss": torch.full((B,), float("nan"), **f32), "steps": torch.full((B,), -7, dtype=torch.int32, device="cuda:0")}
+    got = pfg.pfg_lstm_while_per_example_grad_norms(
+        net, dev(np.ascontiguousarray(inp.X).reshape(-1, net.dx)), dev(offsets_of(lengths)), dev(labels), max_steps,
+        halt_w=None if halt_w is None else dev(halt_w), halt_c=halt_c, out=out)
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in got.items()}
+    rsq, rnorm, rloss, rsteps = olstm.while_per_example_grad_norms(onet, inp.X, lengths, labels, max_steps, halt_w, halt_c)
+    if halt_w is None:
+        lo = hi = rsteps
+    else:
+        _, _, hi = olstm.while_forward(onet, inp.X, lengths, max_steps, halt_w, halt_c - MARGIN)
+        _, _, lo = olstm.while_forward(onet, inp.X, lengths, max_steps, halt_w, halt_c + MARGIN)
+    robust = lo == hi
+    assert robust.mean() >= min_robust
+    assert (got["steps"][robust] == rsteps[robust]).all() and ((lo <= got["steps"]) & (got["steps"] <= hi)).all()
+    for name in ("sq", "norm", "loss"):
+        assert np.isfinite(got[name]).all(), f"{name} was not written in full"
+    # each squared norm against its own value (a sum of squares has no cancellation to excuse)
+    e_sq = float(np.max(np.abs(got["sq"][robust] - rsq[robust]) / np.maximum(rsq[robust], 1e-30), initial=0.0))
+    e_norm = float(np.max(np.abs(got["norm"][robust] - rnorm[robust]) / np.maximum(rnorm[robust], 1e-30), initial=0.0))
+    e_loss = float(np.max(np.abs(got["loss"][robust] - rloss[robust]), initial=0.0) / max(1e-30, np.abs(rloss[robust]).max()))
+    say(f"  {tag}: {int(robust.sum())} of {B} sequences compared, trip counts {rsteps.min()}..{rsteps.max()}; "
+        f"rel err sq {e_sq:.3e}, norm {e_norm:.3e}, loss {e_loss:.3e}")
+    zero = robust & (rsteps == 0)
+    assert not got["sq"][zero][:, :3].any(), "an iteration without a trip has non-zero norms"
+    assert max(e_sq, e_norm, e_loss) <= TOL_F32
+    return net, got
+
+
+NORM_SHAPES = [
+    (3, 4, 2, 6, 7, 10, -0.05),
+    (1, 1, 1, 3, 2, 5, -0.01),
+    (7, 20, 3, 25, 37, 30, -0.1),              # widths that are no multiples of 4: element-wise staging
+    (33, 65, 10, 12, 40, 8, -0.05),
+    (16, 32, 40, 30, 100, 40, -0.1),           # two row tiles of trips: three Gram tiles
+    (100, 60, 3, 34, 48, 34, -3.0),            # trip counts on both sides of 32
+    (8, 12, 4, 128, 12, 128, -3.0),            # up to 128 trips: all ten tiles, three per wave
+    (128, 256, 10, 20, 64, 20, -0.5),          # c14's widths
+]
+
+
+@pytest.mark.parametrize("dx,H,dy,max_len,B,max_steps,halt_c", NORM_SHAPES,
+                         ids=[f"dx{s[0]}-H{s[1]}-L{s[3]}-B{s[4]}" for s in NORM_SHAPES])
+def test_while_grad_norms_shapes(dx, H, dy, max_len, B, max_steps, halt_c):
+    inp, lengths, halt_w, labels = draw(dx, H, dy, max_len, B, 1300 + dx + H + B)
+    if max_len >= 34:
+        fixed = np.array([31, 32, 33, 34, 63, 64, 65, 96, 97, 127, 128, 1], dtype=np.int32)
+        fixed = fixed[fixed <= max_len][:B]
+        lengths[:len(fixed)] = fixed
+        inp.X = np.random.default_rng(B).standard_normal((int(lengths.sum()), dx)).astype(np.float32)
+    say(f"norms of while-loop gradients dx={dx} H={H} dy={dy} B={B} lengths 0..{max_len} cap {max_steps}")
+    check_norms(inp, lengths, labels, max_steps, halt_w, halt_c, "norms")
+
+
+def test_while_grad_norms_agree_with_the_gradient_call_and_special_cases():
+    inp, lengths, halt_w, labels = draw(6, 12, 4, 9, 11, 1360, min_len=1)
+    net, got = check_norms(inp, lengths, labels, 20, halt_w, -0.1, "norms")
+    # the squares of the gradients the other entry point writes
+    g = run_gpu(net, inp.X, lengths, labels, 20, halt_w, -0.1)
+    assert np.array_equal(g["steps"], got["steps"]) and np.array_equal(g["loss"], got["loss"])
+    for k, name in enumerate(("dW", "db", "dWout", "dbout")):
+        want = (g[name].astype(np.float64) ** 2).reshape(11, -1).sum(axis=1)
+        assert np.max(np.abs(got["sq"][:, k] - want) / np.maximum(want, 1e-30)) <= 1e-5, name
+    # no trip at all: only the readout bias has a gradient
+    z = pfg.pfg_lstm_while_per_example_grad_norms(net, dev(inp.X), dev(offsets_of(lengths)), dev(labels), 20,
+                                                  halt_w=dev(np.zeros(12, np.float32)), halt_c=1e-30)
+    torch.cuda.synchronize()
+    sq = z["sq"].cpu().numpy()
+    assert z["steps"].tolist() == [0] * 11 and not sq[:, :3].any() and (sq[:, 3] > 0).all()
+    assert np.allclose(z["norm"].cpu().numpy(), np.sqrt(sq[:, 3]), rtol=1e-6)
+    # one output alone, the cap, lengths only
+    only = pfg.pfg_lstm_while_per_example_grad_norms(net, dev(inp.X), dev(offsets_of(lengths)), dev(labels), 20,
+                                                     halt_w=dev(halt_w), halt_c=-0.1, want=("norm",))
+    torch.cuda.synchronize()
+    assert list(only) == ["norm"] and np.array_equal(only["norm"].cpu().numpy(), got["norm"])
+    check_norms(inp, lengths, labels, 3, None, -1.0, "cap 3")
+    check_norms(inp, lengths, labels, 20, None, 0.0, "lengths only")
+    # rejected: more trips than the Gram tiles of a workgroup cover, no output
+    with pytest.raises(pfg.PfgError) as ei:
+        pfg.pfg_lstm_while_per_example_grad_norms(net, dev(inp.X), dev(offsets_of(lengths)), dev(labels), 129)
+    assert ei.value.code == pfg.PFG_ERR_UNSUPPORTED
+    with pytest.raises(pfg.PfgError) as ei:
+        pfg.pfg_lstm_while_per_example_grad_norms(net, dev(inp.X), dev(offsets_of(lengths)), dev(labels), 20,
+                                                  want=("loss",))
+    assert ei.value.code == pfg.PFG_ERR_NULL
+
+
+def test_c14_lstm_while_grad_norms_full_size():
+    w = wl.LSTM_WORKLOADS["c14_lstm_while_grad_norms"]
+    inp, lengths, offsets, halt_w, halt_c = wl.make_while_inputs(w)
+    say(f"c14_lstm_while_grad_norms: {w.B} sequences, every one against the oracle")
+    check_norms(inp, lengths, inp.labels.astype(np.int32), w.T, halt_w, halt_c, "c14 norms", min_robust=0.95)
+
+
 def test_while_grads_reject_bad_arguments():
     inp, lengths, halt_w, labels = draw(4, 6, 3, 5, 4, 991)
     net = pfg.Lstm.from_numpy(inp.W, inp.b, inp.Wout, inp.bout, 1)
