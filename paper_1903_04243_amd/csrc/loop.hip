@@ -579,24 +579,43 @@ __global__ __launch_bounds__(256) void while_grad_sqnorms_kernel(const WhileNorm
 #pragma unroll
     for (int r = 0; r < 16; ++r) az[j][r] = au[j][r] = 0.f;
 
+  // one chunk of the operand's Gram matrix into acc (the tiles of this wave; a diagonal tile reads its
+  // rows once)
+  auto multiply = [&](f32x16 (&acc)[3]) {
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      if (ti[j] < 0) continue;                             // wave-uniform
+      const float *arow = &Zs[32 * ti[j] + l32][half], *brow = &Zs[32 * tj[j] + l32][half];
+      if (ti[j] == tj[j]) {
+#pragma unroll 8
+        for (int s2 = 0; s2 < kNormK; s2 += 2) {
+          const float v = arow[s2];
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(v, v, acc[j], 0, 0, 0);
+        }
+      } else {
+#pragma unroll 8
+        for (int s2 = 0; s2 < kNormK; s2 += 2)
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(arow[s2], brow[s2], acc[j], 0, 0, 0);
+      }
+    }
+  };
   if (nt > 0) {
     fetch(0);
 #pragma unroll 1
-    for (int c = 0; c < chunks; ++c) {
+    for (int c = 0; c < chunks_z; ++c) {                   // dz dz^T
       __syncthreads();                                     // the previous chunk has been read
       stash(c);
       __syncthreads();
-      if (c + 1 < chunks) fetch(c + 1);                    // on its way while this chunk is multiplied
-      const bool is_z = c < chunks_z;
-#pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        if (ti[j] < 0) continue;                           // wave-uniform
-        const float *arow = &Zs[32 * ti[j] + l32][half], *brow = &Zs[32 * tj[j] + l32][half];
-        f32x16 acc = is_z ? az[j] : au[j];
-#pragma unroll 8
-        for (int s2 = 0; s2 < kNormK; s2 += 2) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(arow[s2], brow[s2], acc, 0, 0, 0);
-        if (is_z) az[j] = acc; else au[j] = acc;
-      }
+      fetch(c + 1);                                        // on its way while this chunk is multiplied (u follows dz)
+      multiply(az);
+    }
+#pragma unroll 1
+    for (int c = chunks_z; c < chunks; ++c) {              // u u^T
+      __syncthreads();
+      stash(c);
+      __syncthreads();
+      if (c + 1 < chunks) fetch(c + 1);
+      multiply(au);
     }
   }
 
