@@ -156,6 +156,9 @@ struct GemmArgs {
   const int32_t *sub;           // {row count, offset into sub_rows}
   const int32_t *sub_rows;
   int32_t sub_gather, sub_scatter;
+  // 1: sub[1] is 0 and sub_rows has M readable entries (the lists of a while loop): the register-fed
+  // kernel then requests its list entries together with the count, not behind it
+  int32_t sub_offset_zero;
 };
 
 // Picks the LDS-tiled kernel or the small-problem kernel.

@@ -42,10 +42,19 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   const int N = g.N, K = g.K;
   const int tiles_m = (g.M + 31) / 32;
   const int m0 = (blockIdx.x % tiles_m) * 32;
-  // rows chosen on the device: the live row count comes from memory, tiles past it have nothing to do
+  // rows chosen on the device: the live row count comes from memory, tiles past it have nothing to do.
+  // When the list is known to start at entry 0 and to have g.M readable entries (sub_offset_zero), the
+  // list entries this lane needs are requested together with the count instead of behind it; an
+  // entry past the count is then replaced by iteration 0, whose rows exist and whose results are dropped.
+  const bool spec = SUB && g.sub_offset_zero;
+  int spec_a = 0, spec_e = 0;
+  if (spec) {
+    spec_a = g.sub_rows[min(m0 + l32, g.M - 1)];
+    spec_e = g.sub_rows[min(m0 + (tid >> 3), g.M - 1)];
+  }
   const int M = SUB ? g.sub[0] : g.M;
   if (SUB && m0 >= M) return;
-  const int sub_off = SUB ? g.sub[1] : 0;
+  const int sub_off = (SUB && !spec) ? g.sub[1] : 0;
   // EPI_HEAD has a single column tile (N <= 32); the second grid index then counts the workgroups
   // that share out the fused cotangent step of one row tile (each recomputes the tile's logits)
   const bool is_head = (g.epilogue == EPI_HEAD);
@@ -76,7 +85,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
     const int m = m0 + l32;
     if (FAST || m < M) {
       int mc = FAST ? min(m, M - 1) : m;           // FAST: rows past the end re-read the last row
-      if (SUB && g.sub_gather) mc = g.sub_rows[sub_off + mc];
+      if (SUB && g.sub_gather) mc = spec ? (m < M ? spec_a : 0) : g.sub_rows[sub_off + mc];
       const int64_t b = mc / g.S, s = mc % g.S;
       const int64_t off = b * g.a_batch_stride + s * g.lda;
       if constexpr (AMODE == A_BF16)
@@ -203,7 +212,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   int64_t lstm_p = lstm_m;
   if constexpr (LSTM && WKN) {
     if (lstm_live) {
-      if (SUB) lstm_p = g.sub_rows[sub_off + lstm_m];
+      if (SUB) lstm_p = spec ? spec_e : g.sub_rows[sub_off + lstm_m];
       const int H = g.lstm_H, T = g.lstm_T, t = g.lstm_step;
       const int64_t zr = g.lstm_zx_rows ? (int64_t)g.lstm_zx_rows[lstm_p] + t : lstm_p * T + t;
       const float *zrow = g.lstm_zx + zr * 4 * H + lstm_k;

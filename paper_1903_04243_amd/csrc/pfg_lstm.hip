@@ -329,7 +329,7 @@ int while_forward_loop(const pfg_lstm *net, const void *X, const int32_t *seq_of
     if (pieces) {
       g.lstm_halt_w = halt_w; g.lstm_score_part = ws_at(ws, p.score); g.lstm_score_ld = nparts;
     }
-    g.sub = meta(t + 1); g.sub_rows = list(t + 1); g.sub_gather = 1; g.sub_scatter = 0;
+    g.sub = meta(t + 1); g.sub_rows = list(t + 1); g.sub_gather = 1; g.sub_scatter = 0; g.sub_offset_zero = 1;
     PFG_LAUNCH("lstm_step", launch_gemm(g, stream));
   }
   return PFG_OK;
