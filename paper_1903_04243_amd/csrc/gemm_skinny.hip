@@ -204,7 +204,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   // EPI_LSTM_FWD: thread (row, unit) = (tid / 8, tid % 8) of the first 256 threads finishes one
   // cell; what it adds to the product is requested here, ahead of the contraction
   f32x4 lstm_z = {0.f, 0.f, 0.f, 0.f};
-  float lstm_cprev = 0.f;
+  float lstm_cprev = 0.f, lstm_hw = 0.f;       // lstm_hw: this cell's entry of the halting vector
   const int lstm_m = m0 + (tid >> 3), lstm_k = 8 * second + (tid & 7);
   const bool lstm_live = lstm_fwd && tid < 256 && lstm_m < M && lstm_k < g.lstm_H;
   // rows chosen on the device (the active list of a while loop): row lstm_m of the product is
@@ -219,6 +219,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
       lstm_z = f32x4{zrow[0], zrow[H], zrow[2 * H], zrow[3 * H]};
       if (g.lstm_has_prev)
         lstm_cprev = g.lstm_cs_w[lstm_p * g.lstm_state_ld + (t - 1) * g.lstm_state_ts + lstm_k];
+      if (SUB && g.lstm_score_part) lstm_hw = g.lstm_halt_w[lstm_k];
     }
   }
 
@@ -343,7 +344,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
           if (g.lstm_tok_c) g.lstm_tok_c[zr * H + lstm_k] = c;
           if (g.lstm_tok_h) g.lstm_tok_h[zr * H + lstm_k] = hnew;
         }
-        if (SUB && g.lstm_score_part) score_piece = hnew * g.lstm_halt_w[lstm_k];
+        score_piece = hnew * lstm_hw;
       }
       if constexpr (SUB) {
         // the eight cells of a row that this workgroup finished sit in eight neighbouring lanes: their
