@@ -44,7 +44,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_small16_kernel(const GemmArgs g)
   const int r16 = lane & 15, kq = lane >> 4;
   const int N = g.N, K = g.K;
   const int tiles_m = (g.M + 15) / 16;
-  const int m0 = (blockIdx.x % tiles_m) * 16, n0 = (blockIdx.x / tiles_m) * 16;
+  // rows chosen on the device: the column tiles of a row tile are numbered next to each other, so that
+  // the live workgroups (the first row tiles) come first in the launch
+  const int tiles_n = SUB ? (int)gridDim.x / tiles_m : 1;
+  const int m0 = (SUB ? (int)blockIdx.x / tiles_n : (int)blockIdx.x % tiles_m) * 16;
+  const int n0 = (SUB ? (int)blockIdx.x % tiles_n : (int)blockIdx.x / tiles_m) * 16;
   const int epi = g.epilogue;
   // rows chosen on the device: the live row count comes from memory, tiles past it have nothing to do
   const int M = SUB ? g.sub[0] : g.M;
