@@ -159,6 +159,11 @@ struct GemmArgs {
   // 1: sub[1] is 0 and sub_rows has M readable entries (the lists of a while loop): the register-fed
   // kernel then requests its list entries together with the count, not behind it
   int32_t sub_offset_zero;
+  // Register-fed kernel with a row list: 0 numbers the column tiles of a row tile next to each other
+  // (the live workgroups, those of the first row tiles, then come first in the launch: best when there
+  // are many column tiles), 1 numbers the row tiles of a column tile next to each other (measured
+  // better for the reverse trip of a while loop, 8 column tiles with a 1024-long contraction)
+  int32_t sub_rows_fastest;
 };
 
 // Picks the LDS-tiled kernel or the small-problem kernel.

@@ -43,9 +43,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   const int tiles_m = (g.M + 31) / 32;
   // rows chosen on the device: only the first row tiles are live, so the column tiles of a row tile
   // are numbered next to each other -- the live workgroups then come first in the launch and the ones
-  // with nothing to do are dealt with while those run
+  // with nothing to do are dealt with while those run (unless the caller asks for the other numbering)
   const int tiles_n_all = SUB ? (int)gridDim.x / tiles_m : 1;
-  const int m0 = (SUB ? (int)blockIdx.x / tiles_n_all : (int)blockIdx.x % tiles_m) * 32;
+  const bool live_first = SUB && !g.sub_rows_fastest;
+  const int m0 = (live_first ? (int)blockIdx.x / tiles_n_all : (int)blockIdx.x % tiles_m) * 32;
   // rows chosen on the device: the live row count comes from memory, tiles past it have nothing to do.
   // When the list is known to start at entry 0 and to have g.M readable entries (sub_offset_zero), the
   // list entries this lane needs are requested together with the count instead of behind it; an
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const GemmArgs g) 
   // EPI_HEAD has a single column tile (N <= 32); the second grid index then counts the workgroups
   // that share out the fused cotangent step of one row tile (each recomputes the tile's logits)
   const bool is_head = (g.epilogue == EPI_HEAD);
-  const int second = SUB ? (int)blockIdx.x % tiles_n_all : (int)blockIdx.x / tiles_m;
+  const int second = live_first ? (int)blockIdx.x % tiles_n_all : (int)blockIdx.x / tiles_m;
   const int n0 = is_head ? 0 : second * 32;
   // EPI_LSTM_FWD: the tile's 32 columns are the four gate columns of the 8 hidden units
   // 8 * second .. 8 * second + 7 (column gate * H + unit of W_h), not 32 consecutive columns

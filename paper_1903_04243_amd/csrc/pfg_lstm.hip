@@ -428,7 +428,7 @@ int while_sweeps(const pfg_lstm *net, const void *X, const int32_t *seq_offsets,
     g.lstm_dc = dc; g.lstm_dz = dzi[t & 1]; g.lstm_dz_ld = 4 * H; g.lstm_tok_dz = dz;
     g.lstm_seed = seed; g.lstm_steps = steps;
     g.sub = ints(p.meta) + 2 * (t + 1); g.sub_rows = ints(p.list) + (int64_t)(t + 1) * B;
-    g.sub_gather = 1; g.sub_scatter = 0;
+    g.sub_gather = 1; g.sub_scatter = 0; g.sub_rows_fastest = 1;
     PFG_LAUNCH("lstm_gemm_reverse", launch_gemm(g, stream));
   }
   return PFG_OK;
