@@ -341,6 +341,31 @@ hipError_t launch_conv_relu_pool(const float *in, const float *Wc, const float *
                                  int32_t w, int32_t ci, int32_t k, int32_t co, float *pooled, uint8_t *which,
                                  hipStream_t stream);
 
+// A conv block with many input channels on a small feature map (the zero-padded image of an example
+// and a chunk of the filter fit in LDS; c_in a multiple of 8, c_out of 32, at most 256 positions):
+// the matrix-core operands are read from the LDS image in place, no patch matrix anywhere.
+//   forward:  product + bias, relu and 2 x 2 pooling in one kernel (pooled / which as launch_relu_pool
+//             writes them);
+//   reverse:  din [B, h, w, ci] = dz [B, h, w, co] convolved with the flipped, transposed filter (in
+//             place of the patch-cotangent product and launch_col2im; c_out a multiple of 8, c_in of 32);
+//   filter:   dWc [B, k k ci, co] = for each example and tap, in_shifted^T dz over the positions
+//             (k = 3 or 5, c_in and c_out multiples of 32).
+bool conv_direct_forward_applies(const float *in, const float *Wc, const float *bias, int64_t B, int32_t h,
+                                 int32_t w, int32_t ci, int32_t k, int32_t co, const float *pooled,
+                                 const uint8_t *which);
+hipError_t launch_conv_direct_forward(const float *in, const float *Wc, const float *bias, int64_t B, int32_t h,
+                                      int32_t w, int32_t ci, int32_t k, int32_t co, float *pooled,
+                                      uint8_t *which, hipStream_t stream);
+bool conv_direct_reverse_applies(const float *dz, const float *Wc, int64_t B, int32_t h, int32_t w, int32_t ci,
+                                 int32_t k, int32_t co, const float *din);
+hipError_t launch_conv_direct_reverse(const float *dz, const float *Wc, int64_t B, int32_t h, int32_t w,
+                                      int32_t ci, int32_t k, int32_t co, float *din, hipStream_t stream);
+bool conv_filter_direct_applies(const float *in, const float *dz, int64_t B, int32_t h, int32_t w, int32_t ci,
+                                int32_t k, int32_t co, const float *dWc);
+hipError_t launch_conv_filter_direct(const float *in, const float *dz, int64_t B, int32_t h, int32_t w,
+                                     int32_t ci, int32_t k, int32_t co, float *dWc, int streaming,
+                                     hipStream_t stream);
+
 // pooled [B, h/2, w/2, c] = max over 2 x 2 windows of relu(z [B, h, w, c]); which = index 0..3 of the
 // window entry that gave it
 hipError_t launch_relu_pool(const float *z, int64_t B, int32_t h, int32_t w, int32_t c, float *pooled,

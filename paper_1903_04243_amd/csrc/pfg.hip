@@ -1032,9 +1032,14 @@ int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, 
     // the filter gradient, in the layout that product reads
     const bool direct = conv_relu_pool_applies(in, filt, bias, B, blk.h, blk.w, blk.ci, blk.k, blk.co,
                                                at(ws, blk.pooled), which);
-    const bool filter_P = want_filter && !gathered && filter_reads_P(i);
-    const bool filter_PT = want_filter && !gathered && !filter_reads_P(i);
-    const bool forward_P = !gathered && !direct;
+    // many channels on a small map: the matrix-core kernels that read the image from LDS in place
+    const bool direct_mfma = !direct && conv_direct_forward_applies(in, filt, bias, B, blk.h, blk.w, blk.ci, blk.k,
+                                                                    blk.co, at(ws, blk.pooled), which);
+    const bool filter_direct = want_filter && conv_filter_direct_applies(in, at(ws, blk.dz), B, blk.h, blk.w, blk.ci,
+                                                                         blk.k, blk.co, dWc_out[i]);
+    const bool filter_P = want_filter && !filter_direct && !gathered && filter_reads_P(i);
+    const bool filter_PT = want_filter && !filter_direct && !gathered && !filter_reads_P(i);
+    const bool forward_P = !gathered && !direct && !direct_mfma;
     if (forward_P || filter_P || filter_PT)
       PFG_LAUNCH("im2col", launch_im2col(in, B, blk.h, blk.w, blk.ci, blk.k,
                                          (forward_P || filter_P) ? at(ws, blk.P) : nullptr,
@@ -1042,6 +1047,9 @@ int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, 
     if (direct) {
       PFG_LAUNCH("conv_relu_pool", launch_conv_relu_pool(in, filt, bias, B, blk.h, blk.w, blk.ci, blk.k,
                                                          blk.co, at(ws, blk.pooled), which, stream));
+    } else if (direct_mfma) {
+      PFG_LAUNCH("conv_gemm_forward", launch_conv_direct_forward(in, filt, bias, B, blk.h, blk.w, blk.ci, blk.k,
+                                                                 blk.co, at(ws, blk.pooled), which, stream));
     } else {
       PFG_LAUNCH("conv_gemm_forward", launch_gemm(forward_product(i, gathered), stream));
       PFG_LAUNCH("relu_pool", launch_relu_pool(at(ws, blk.z), B, blk.h, blk.w, blk.co, at(ws, blk.pooled), which,
@@ -1108,12 +1116,26 @@ int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, 
                                                    dz, stream));
       if (dbc) PFG_LAUNCH("sum_positions", launch_sum_steps(dz, B, hw, blk.co, dbc, at(ws, cp.psum), stream));
     }
-    if (dWc_out && dWc_out[i])
-      PFG_LAUNCH("conv_gemm_filter", launch_gemm(gathers(i) ? gathered_filter_product(i)
-                                                            : filter_product(i, filter_reads_P(i)), stream));
+    if (dWc_out && dWc_out[i]) {
+      if (conv_filter_direct_applies(image[i], dz, B, blk.h, blk.w, blk.ci, blk.k, blk.co, dWc_out[i]))
+        PFG_LAUNCH("conv_gemm_filter", launch_conv_filter_direct(image[i], dz, B, blk.h, blk.w, blk.ci, blk.k,
+                                                                 blk.co, dWc_out[i], norms ? 0 : 1, stream));
+      else
+        PFG_LAUNCH("conv_gemm_filter", launch_gemm(gathers(i) ? gathered_filter_product(i)
+                                                              : filter_product(i, filter_reads_P(i)), stream));
+    }
     bool lower = false;
     for (int j = 0; j < i; ++j) lower = lower || (dWc_out && dWc_out[j]) || (dbc_out && dbc_out[j]);
     if (!lower) break;
+    // the same matrix-core kernel as the forward pass, run on dz with the filter flipped and transposed
+    if (conv_direct_reverse_applies(dz, static_cast<const float *>(net->Wc[i]), B, blk.h, blk.w, blk.ci, blk.k,
+                                    blk.co, at(ws, cp.dout[which_dout ^ 1]))) {
+      which_dout ^= 1;
+      dout = at(ws, cp.dout[which_dout]);
+      PFG_LAUNCH("conv_gemm_cotangent", launch_conv_direct_reverse(dz, static_cast<const float *>(net->Wc[i]), B,
+                                                                   blk.h, blk.w, blk.ci, blk.k, blk.co, dout, stream));
+      continue;
+    }
     // cotangent of the patches, dP = dz Wc^T (into the patch buffer, no longer needed), gathered
     // back to the image that entered this block = the pooled output of the block below
     GemmArgs g{};
