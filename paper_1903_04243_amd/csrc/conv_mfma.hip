@@ -328,8 +328,8 @@ __global__ __launch_bounds__(kThreads) void conv_filter_direct_kernel(const Conv
 
   float *img = smem;                        // [PH][PW][32]
   float *dzs = smem + PH * PW * 32;         // [hw][32]
-  copy_padded_band(a.in + b * hw * a.ci + c0, h, w, a.ci, 8, 0, p, PH, PW, img, 32, tid, kThreads);
   {
+    // the dz columns: the first batch of loads travels while the image is copied
     const float *dsrc = a.dz + b * hw * a.co + n0;
     const int total = hw * 8;
     for (int e0 = 0; e0 < total; e0 += kCopyBatch * kThreads) {
@@ -339,6 +339,7 @@ __global__ __launch_bounds__(kThreads) void conv_filter_direct_kernel(const Conv
         const int e = min(e0 + u * kThreads + tid, total - 1);
         v[u] = *reinterpret_cast<const f32x4 *>(dsrc + (int64_t)(e >> 3) * a.co + 4 * (e & 7));
       }
+      if (e0 == 0) copy_padded_band(a.in + b * hw * a.ci + c0, h, w, a.ci, 8, 0, p, PH, PW, img, 32, tid, kThreads);
 #pragma unroll
       for (int u = 0; u < kCopyBatch; ++u) {
         const int e = e0 + u * kThreads + tid;
@@ -383,7 +384,7 @@ __global__ __launch_bounds__(kThreads) void conv_filter_direct_kernel(const Conv
     };
     auto products = [&](const float (&av)[TT], float bv) {
 #pragma unroll
-      for (int tt = 0; tt < TT; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[tt], bv, acc[tt], 0, 0, 0);
+      for (int tt = 0; tt < TT; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[tt], acc[tt], 0, 0, 0);
     };
     float av0[TT], av1[TT], bv0, bv1;
     request(av0, bv0);
@@ -398,17 +399,22 @@ __global__ __launch_bounds__(kThreads) void conv_filter_direct_kernel(const Conv
   }
   __syncthreads();
 
-  // a tile [32 channels][32 filters] per tap: through this wave's LDS slab, out as 16-byte pieces
+  // A tap's tile comes out of the product as [filter][channel] (D rows = filters), so a lane holds four
+  // consecutive filters of its channel per register quad: written to this wave's LDS slab
+  // [32 channels][36] as 16-byte pieces and read back row by row for 16-byte stores.  The slab is the
+  // wave's own: its LDS operations execute in order, no workgroup barrier is needed between the taps.
   float *slab = smem + wv * (32 * 36);
   float *dst = a.dWc + b * (int64_t)taps * a.ci * a.co;
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) {
     if (tt < my) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) slab[(8 * (r >> 2) + 4 * half + (r & 3)) * 36 + l32] = acc[tt][r];
-    }
-    __syncthreads();
-    if (tt < my) {
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 v = {acc[tt][4 * q4], acc[tt][4 * q4 + 1], acc[tt][4 * q4 + 2], acc[tt][4 * q4 + 3]};
+        *reinterpret_cast<f32x4 *>(slab + l32 * 36 + 8 * q4 + 4 * half) = v;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
       const int tap = tap0 + tt;
 #pragma unroll
       for (int ps = 0; ps < 4; ++ps) {
@@ -418,8 +424,9 @@ __global__ __launch_bounds__(kThreads) void conv_filter_direct_kernel(const Conv
         if (a.streaming) __builtin_nontemporal_store(v, q);
         else *q = v;
       }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
-    __syncthreads();
   }
 }
 
