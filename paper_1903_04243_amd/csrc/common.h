@@ -365,6 +365,13 @@ bool conv_filter_direct_applies(const float *in, const float *dz, int64_t B, int
 hipError_t launch_conv_filter_direct(const float *in, const float *dz, int64_t B, int32_t h, int32_t w,
                                      int32_t ci, int32_t k, int32_t co, float *dWc, int streaming,
                                      hipStream_t stream);
+// The filter gradient of a block with few input channels (k k c_in <= 64, c_out a multiple of 32, the
+// padded image and 32 columns of dz within the LDS of a workgroup): the rows (tap, channel) fill one
+// or two matrix-core tiles, each lane reading its shifted image value through its own offset.
+bool conv_filter_rows_applies(const float *in, const float *dz, int64_t B, int32_t h, int32_t w, int32_t ci,
+                              int32_t k, int32_t co, const float *dWc);
+hipError_t launch_conv_filter_rows(const float *in, const float *dz, int64_t B, int32_t h, int32_t w, int32_t ci,
+                                   int32_t k, int32_t co, float *dWc, int streaming, hipStream_t stream);
 
 // pooled [B, h/2, w/2, c] = max over 2 x 2 windows of relu(z [B, h, w, c]); which = index 0..3 of the
 // window entry that gave it

@@ -430,6 +430,166 @@ __global__ __launch_bounds__(kThreads) void conv_filter_direct_kernel(const Conv
   }
 }
 
+// The same gradient for a block with FEW input channels (a first layer: k k c_in <= 32 MT): the rows
+// (tap, channel) of the gradient fill one or two MFMA tiles, a lane owning one row and reading its
+// shifted image value through its own offset; the four waves split the positions and their partial
+// tiles meet in LDS.  A workgroup = one example and 32 filters; the padded image (all channels) and
+// the dz columns sit in LDS.  Image rows are padded to an odd number of floats, so that the taps of
+// a column of the filter fall into different banks.
+template <int MT>
+__global__ __launch_bounds__(kThreads) void conv_filter_rows_kernel(const ConvFilterArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  float *smem = reinterpret_cast<float *>(smem_raw);
+  const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int k = a.k, p = (k - 1) / 2, h = a.h, w = a.w, hw = h * w, PW = w + k - 1, PH = h + k - 1;
+  const int ci = a.ci, M = k * k * ci;
+  const int RS = (PW * ci) | 1;               // floats per padded image row
+  const int ntiles = a.co / 32;
+  const int n0 = (blockIdx.x % ntiles) * 32;
+  const int64_t b = blockIdx.x / ntiles;
+
+  float *img = smem;                           // [PH][RS]
+  float *dzs = smem + ((PH * RS + 3) & ~3);    // [hw][32]
+  {
+    // the dz columns: the first batch of loads travels while the image is copied
+    const float *dsrc = a.dz + b * hw * a.co + n0;
+    const int total = hw * 8;
+    for (int e0 = 0; e0 < total; e0 += kCopyBatch * kThreads) {
+      f32x4 v[kCopyBatch];
+#pragma unroll
+      for (int u = 0; u < kCopyBatch; ++u) {
+        const int e = min(e0 + u * kThreads + tid, total - 1);
+        v[u] = *reinterpret_cast<const f32x4 *>(dsrc + (int64_t)(e >> 3) * a.co + 4 * (e & 7));
+      }
+      if (e0 == 0) {
+        // the image, value by value (rows of w c_in floats land at odd strides), a batch of loads at a time
+        const float *src = a.in + b * hw * ci;
+        const int wc = w * ci, row_floats = PW * ci, all = PH * row_floats;
+        const float inv_row = 1.f / (float)row_floats;
+        for (int i0 = 0; i0 < all; i0 += 8 * kThreads) {
+          float x[8];
+          int at[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * kThreads + tid, ic = min(i, all - 1);
+            const int r = div_small(ic, row_floats, inv_row), rem = ic - r * row_floats;
+            const int y = r - p, xc = rem - p * ci;
+            const bool inside = y >= 0 && y < h && xc >= 0 && xc < wc;
+            x[u] = src[inside ? y * wc + xc : 0];
+            if (!inside) x[u] = 0.f;
+            at[u] = i < all ? r * RS + rem : -1;
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            if (at[u] >= 0) img[at[u]] = x[u];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kCopyBatch; ++u) {
+        const int e = e0 + u * kThreads + tid;
+        if (e < total) *reinterpret_cast<f32x4 *>(dzs + (e >> 3) * 32 + 4 * (e & 7)) = v[u];
+      }
+    }
+  }
+  // this lane's row (tap, channel) in every tile: where its value sits relative to the window origin
+  int roff[MT];
+  const float inv_ci = 1.f / (float)ci, inv_k = 1.f / (float)k;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = min(mt * 32 + l32, M - 1);
+    const int tap = div_small(m, ci, inv_ci), c = m - tap * ci;
+    const int dy = div_small(tap, k, inv_k), dx = tap - dy * k;
+    roff[mt] = dy * RS + dx * ci + c;
+  }
+  // two accumulators per tile, taken in turn: consecutive products do not wait for each other
+  f32x16 acc[MT], acc2[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mt][r] = acc2[mt][r] = 0.f;
+  __syncthreads();
+
+  // Positions two at a time (one per half-wave; w is even, a pair never straddles a row); this wave's
+  // share of the pairs is a contiguous run.  D rows = filters, D columns = gradient rows.  A product
+  // is short against the latency of its LDS reads, so the operands of four pairs are requested
+  // together, one such group ahead of the products; past the end of the run the last pair is read
+  // again with its dz values replaced by zero.
+  {
+    const int steps = hw / 2, pairs = w / 2;
+    const int s_lo = (wv * steps) / 4, s_hi = ((wv + 1) * steps) / 4;
+    const int y0 = div_small(s_lo, pairs, 1.f / (float)pairs);
+    int xi = s_lo - y0 * pairs, st = s_lo;
+    const float *ap = img + y0 * RS + (2 * xi + half) * ci;
+    const float *bp = dzs + (2 * s_lo + half) * 32 + l32;
+    const int wrap = RS - w * ci;
+    auto request4 = [&](float (&av)[4][MT], float (&bv)[4]) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        bv[u] = *bp;
+        if (st >= s_hi) bv[u] = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) av[u][mt] = ap[roff[mt]];
+        if (st + 1 < s_hi) {
+          ap += 2 * ci;
+          bp += 64;
+          if (++xi == pairs) { xi = 0; ap += wrap; }
+        }
+        ++st;
+      }
+    };
+    auto products4 = [&](const float (&av)[4][MT], const float (&bv)[4]) {
+#pragma unroll
+      for (int u = 0; u < 4; u += 2)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[u], av[u][mt], acc[mt], 0, 0, 0);
+          acc2[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[u + 1], av[u + 1][mt], acc2[mt], 0, 0, 0);
+        }
+    };
+    if (s_lo < s_hi) {
+      float av0[4][MT], av1[4][MT], bv0[4], bv1[4];
+      request4(av0, bv0);
+      for (int done = s_lo; done < s_hi; done += 8) {
+        request4(av1, bv1);
+        products4(av0, bv0);
+        request4(av0, bv0);
+        products4(av1, bv1);
+      }
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mt][r] += acc2[mt][r];
+  }
+  __syncthreads();
+
+  // the four partial tiles meet in LDS as 16-byte pieces part[wave][tile][row][36], added in the
+  // order of the waves; a thread finishes four filters of a gradient row
+  float *part = smem;
+  const int wstride = MT * 32 * 36;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const f32x4 v = {acc[mt][4 * q4], acc[mt][4 * q4 + 1], acc[mt][4 * q4 + 2], acc[mt][4 * q4 + 3]};
+      *reinterpret_cast<f32x4 *>(part + wv * wstride + (mt * 32 + l32) * 36 + 8 * q4 + 4 * half) = v;
+    }
+  __syncthreads();
+  float *dst = a.dWc + b * (int64_t)M * a.co + n0;
+  for (int e = tid; e < M * 8; e += kThreads) {
+    const int n4 = e & 7, m = e >> 3;
+    const float *q = part + m * 36 + 4 * n4;
+    f32x4 sum = *reinterpret_cast<const f32x4 *>(q);
+    sum += *reinterpret_cast<const f32x4 *>(q + wstride);
+    sum += *reinterpret_cast<const f32x4 *>(q + 2 * wstride);
+    sum += *reinterpret_cast<const f32x4 *>(q + 3 * wstride);
+    f32x4 *out = reinterpret_cast<f32x4 *>(dst + (int64_t)m * a.co + 4 * n4);
+    if (a.streaming) __builtin_nontemporal_store(sum, out);
+    else *out = sum;
+  }
+}
+
 int lds_limit() {
   static int limit = -1;
   if (limit < 0) {
@@ -607,6 +767,50 @@ hipError_t launch_conv_filter_direct(const float *in, const float *dz, int64_t B
   const int64_t wgs = B * (ci / 32) * (co / 32);
   const size_t smem = filter_smem(h, w, k);
   return k == 3 ? launch_filter<3>(a, wgs, smem, stream) : launch_filter<7>(a, wgs, smem, stream);
+}
+
+namespace {
+
+size_t filter_rows_smem(int h, int w, int k, int ci) {
+  const int RS = ((w + k - 1) * ci) | 1;
+  const size_t img = ((size_t)(h + k - 1) * RS + 3) & ~(size_t)3;
+  const int mt = (k * k * ci + 31) / 32;
+  return std::max((img + (size_t)h * w * 32) * 4, (size_t)4 * mt * 32 * 36 * 4);
+}
+
+template <int MT>
+hipError_t launch_filter_rows(const ConvFilterArgs &a, int64_t wgs, size_t smem, hipStream_t stream) {
+  auto kern = conv_filter_rows_kernel<MT>;
+  static bool attr_set = false;   // benign race: the attribute is idempotent
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit());
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  PFG_KERNEL(kern, dim3((unsigned)wgs), dim3(kThreads), smem, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool conv_filter_rows_applies(const float *in, const float *dz, int64_t B, int32_t h, int32_t w, int32_t ci,
+                              int32_t k, int32_t co, const float *dWc) {
+  if (!in || !dz || !dWc || B < 1 || h < 2 || w < 2 || h % 2 || w % 2 || k < 1 || k % 2 == 0 || ci < 1) return false;
+  if (!aligned16(dz) || !aligned16(dWc)) return false;
+  if ((int64_t)k * k * ci > 64 || co < 32 || co % 32) return false;
+  if ((int64_t)h * w * 8 >= (1 << 24) || B * (co / 32) > 0x7fffffffLL) return false;
+  return filter_rows_smem(h, w, k, ci) <= (size_t)lds_limit();
+}
+
+hipError_t launch_conv_filter_rows(const float *in, const float *dz, int64_t B, int32_t h, int32_t w, int32_t ci,
+                                   int32_t k, int32_t co, float *dWc, int streaming, hipStream_t stream) {
+  if (!conv_filter_rows_applies(in, dz, B, h, w, ci, k, co, dWc)) return hipErrorInvalidValue;
+  ConvFilterArgs a{};
+  a.in = in; a.dz = dz; a.dWc = dWc; a.h = h; a.w = w; a.k = k; a.ci = ci; a.co = co; a.streaming = streaming;
+  const int64_t wgs = B * (co / 32);
+  const size_t smem = filter_rows_smem(h, w, k, ci);
+  return k * k * ci <= 32 ? launch_filter_rows<1>(a, wgs, smem, stream) : launch_filter_rows<2>(a, wgs, smem, stream);
 }
 
 }  // namespace pfg

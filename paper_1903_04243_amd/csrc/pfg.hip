@@ -1035,8 +1035,9 @@ int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, 
     // many channels on a small map: the matrix-core kernels that read the image from LDS in place
     const bool direct_mfma = !direct && conv_direct_forward_applies(in, filt, bias, B, blk.h, blk.w, blk.ci, blk.k,
                                                                     blk.co, at(ws, blk.pooled), which);
-    const bool filter_direct = want_filter && conv_filter_direct_applies(in, at(ws, blk.dz), B, blk.h, blk.w, blk.ci,
-                                                                         blk.k, blk.co, dWc_out[i]);
+    const bool filter_direct = want_filter &&
+        (conv_filter_direct_applies(in, at(ws, blk.dz), B, blk.h, blk.w, blk.ci, blk.k, blk.co, dWc_out[i]) ||
+         conv_filter_rows_applies(in, at(ws, blk.dz), B, blk.h, blk.w, blk.ci, blk.k, blk.co, dWc_out[i]));
     const bool filter_P = want_filter && !filter_direct && !gathered && filter_reads_P(i);
     const bool filter_PT = want_filter && !filter_direct && !gathered && !filter_reads_P(i);
     const bool forward_P = !gathered && !direct && !direct_mfma;
@@ -1120,6 +1121,9 @@ int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, 
       if (conv_filter_direct_applies(image[i], dz, B, blk.h, blk.w, blk.ci, blk.k, blk.co, dWc_out[i]))
         PFG_LAUNCH("conv_gemm_filter", launch_conv_filter_direct(image[i], dz, B, blk.h, blk.w, blk.ci, blk.k,
                                                                  blk.co, dWc_out[i], norms ? 0 : 1, stream));
+      else if (conv_filter_rows_applies(image[i], dz, B, blk.h, blk.w, blk.ci, blk.k, blk.co, dWc_out[i]))
+        PFG_LAUNCH("conv_gemm_filter", launch_conv_filter_rows(image[i], dz, B, blk.h, blk.w, blk.ci, blk.k, blk.co,
+                                                               dWc_out[i], norms ? 0 : 1, stream));
       else
         PFG_LAUNCH("conv_gemm_filter", launch_gemm(gathers(i) ? gathered_filter_product(i)
                                                               : filter_product(i, filter_reads_P(i)), stream));
