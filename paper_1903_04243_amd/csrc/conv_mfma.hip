@@ -622,11 +622,17 @@ DirectShape direct_shape(int64_t B, int h, int w, int k, int q, int o_total, boo
     if (tiles > 8) return s;
     nt = tiles;
   } else {
-    // the fewest workgroups per example that give every compute unit one (a workgroup stages the
-    // whole filter, so fewer and larger ones re-read it less), tiles dealt evenly
-    int splits = (tiles + 7) / 8;
-    while (splits < tiles && B * per_example * splits < 256) ++splits;
-    nt = (tiles + splits - 1) / splits;
+    // Workgroups per example: a workgroup costs about 20 us whatever it does (launch, image band,
+    // first filter chunk, epilogue) plus 6 us per tile, and one workgroup fits a compute unit, so the
+    // launch runs in rounds of 256; the split with the cheapest estimate wins (measured at 14 x 14 x
+    // 64 -> 32, 5 x 5: one tile 25 us, four 45 us, seven 58 us; 288 workgroups of three tiles 68 us)
+    double best = 1e30;
+    for (int sp = (tiles + 7) / 8; sp <= tiles; ++sp) {
+      const int per = (tiles + sp - 1) / sp;
+      const int64_t wgs = B * per_example * ((tiles + per - 1) / per);
+      const double cost = (double)((wgs + 255) / 256) * (20.0 + 6.0 * per);
+      if (cost < best) { best = cost; nt = per; }
+    }
   }
   s.nt = nt;
   s.splits = (tiles + nt - 1) / nt;
@@ -692,6 +698,9 @@ bool conv_direct_forward_applies(const float *in, const float *Wc, const float *
     return false;
   // below 64 taps per output the plain-ALU kernel of the first layers is the faster one
   if ((int64_t)k * k * ci < 64) return false;
+  // a workgroup takes a whole example however few there are (32 us at 14 x 14 x 32, 5 x 5); below
+  // half a chip of workgroups the tiled product over the gathered patches is faster (B = 32: 20 us)
+  if (B * (co / 32) < 128) return false;
   return direct_shape(B, h, w, k, ci, co, false).ok;
 }
 
@@ -711,7 +720,10 @@ bool conv_direct_reverse_applies(const float *dz, const float *Wc, int64_t B, in
                                  int32_t k, int32_t co, const float *din) {
   if (!dz || !Wc || !din) return false;
   if (!aligned16(dz) || !aligned16(Wc) || !aligned16(din)) return false;
-  if (co % 4) return false;
+  if (co % 4 || ci % 32) return false;
+  // few examples: a workgroup still stages the whole filter, the patch-cotangent product wins
+  // (B = 16 at 14 x 14: 25 against 23 us; from B = 32 on 26 against 27 and better)
+  if (B * (ci / 32) * (((int64_t)h * w + 31) / 32) < 200) return false;
   return direct_shape(B, h, w, k, co, ci, true).ok;
 }
 
@@ -755,6 +767,9 @@ bool conv_filter_direct_applies(const float *in, const float *dz, int64_t B, int
   if (!aligned16(in) || !aligned16(dz) || !aligned16(dWc)) return false;
   if (ci < 32 || ci % 32 || co < 32 || co % 32 || (k != 3 && k != 5)) return false;
   if (B * (ci / 32) * (co / 32) > 0x7fffffffLL) return false;
+  // a workgroup's time does not shrink with the batch (34 us at 14 x 14, 5 x 5): the batched product over
+  // gathered patches is faster until the workgroups nearly fill the chip (B = 64: 38 against 45 us)
+  if (B * (ci / 32) * (co / 32) < 224) return false;
   return filter_smem(h, w, k) <= (size_t)lds_limit();
 }
 
@@ -800,6 +815,8 @@ bool conv_filter_rows_applies(const float *in, const float *dz, int64_t B, int32
   if (!aligned16(dz) || !aligned16(dWc)) return false;
   if ((int64_t)k * k * ci > 64 || co < 32 || co % 32) return false;
   if ((int64_t)h * w * 8 >= (1 << 24) || B * (co / 32) > 0x7fffffffLL) return false;
+  // 12 us whatever the batch (28 x 28, 5 x 5): from 64 workgroups on it beats patch copy + small product
+  if (B * (co / 32) < 64) return false;
   return filter_rows_smem(h, w, k, ci) <= (size_t)lds_limit();
 }
 

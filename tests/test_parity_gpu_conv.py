@@ -113,11 +113,13 @@ CONV_SHAPES = [
     (12, 20, 3, ((3, 4), (1, 8)), (5,), 37),             # few taps per output: both blocks go from image to pooled output in one kernel
     (28, 6, 1, ((7, 8),), (6,), 600),                    # the same with one workgroup per example (14 pooled rows in a band)
     (20, 8, 1, ((5, 12),), (7,), 90),                    # bands of 2 pooled rows and a ragged last one (5 rows)
-    # second blocks with many channels on a small map: the matrix-core kernels that read the image from LDS
-    (16, 16, 4, ((3, 32), (3, 64)), (12,), 5),           # 8 x 8 x 32 -> 64, 3 x 3: two position tiles
-    (28, 28, 1, ((5, 32), (5, 64)), (16, 10), 9),        # the MNIST model's second block (7 tiles, the last ragged)
+    # blocks with many channels on a small map, enough examples for the matrix-core kernels that read the
+    # image from LDS (the library takes them from about half a chip of workgroups on)
+    (16, 16, 4, ((3, 32), (3, 64)), (12,), 120),         # 8 x 8 x 32 -> 64, 3 x 3: two position tiles, one per workgroup in the reverse kernel
+    (28, 28, 1, ((5, 32), (5, 64)), (16, 10), 66),       # the MNIST model's second block: 7 tiles dealt 3 + 3 + 1 in the reverse kernel
     (8, 8, 8, ((3, 64), (3, 32)), (7,), 130),            # 64 -> 32 channels: two channel tiles in the reverse kernels
-    (24, 24, 2, ((3, 32), (5, 32)), (8,), 40),           # 12 x 12 positions: the input cotangent split over three workgroups
+    (24, 24, 2, ((3, 32), (5, 32)), (8,), 230),          # 12 x 12 positions: five tiles in one workgroup
+    (16, 16, 4, ((3, 32), (3, 64)), (12,), 5),           # the same blocks with few examples: the tiled products
 ]
 
 
@@ -222,8 +224,8 @@ NORM_SHAPES = [
     (8, 8, 8, ((3, 64),), (9,), 70, ()),
     (10, 6, 8, ((5, 16),), (12,), 300, (0,)),
     (12, 20, 3, ((3, 4), (1, 8)), (5,), 37, (1,)),       # image-to-pooled-output kernel, one block without a bias
-    (16, 16, 4, ((3, 32), (3, 64)), (12,), 5, (1,)),     # matrix-core kernels on the LDS image, a block without a bias
-    (24, 24, 2, ((3, 32), (5, 32)), (8,), 40, ()),
+    (16, 16, 4, ((3, 32), (3, 64)), (12,), 120, (1,)),   # matrix-core kernels on the LDS image, a block without a bias
+    (24, 24, 2, ((3, 32), (5, 32)), (8,), 230, ()),
 ]
 
 
