@@ -269,7 +269,7 @@ struct NormLayer {
   int32_t d_in, d_out;
   int32_t a_bf16, has_bias;
   int32_t index;      // column of sq
-  int32_t sum_mode;
+  int32_t sum_mode;   // 0: |a|^2 (+1 with a bias) x |g|^2;  1: sum a^2 + sum g^2;  2: sum a + sum g^2 (a holds partial sums of squares)
 };
 hipError_t launch_grad_sqnorms(const NormLayer *layers, int n, int64_t B, float *sq, int64_t ld_sq,
                                float *norm, hipStream_t stream);
@@ -364,14 +364,19 @@ bool conv_filter_direct_applies(const float *in, const float *dz, int64_t B, int
                                 int32_t k, int32_t co, const float *dWc);
 hipError_t launch_conv_filter_direct(const float *in, const float *dz, int64_t B, int32_t h, int32_t w,
                                      int32_t ci, int32_t k, int32_t co, float *dWc, int streaming,
-                                     hipStream_t stream);
+                                     float *sq_part, hipStream_t stream);
 // The filter gradient of a block with few input channels (k k c_in <= 64, c_out a multiple of 32, the
 // padded image and 32 columns of dz within the LDS of a workgroup): the rows (tap, channel) fill one
 // or two matrix-core tiles, each lane reading its shifted image value through its own offset.
 bool conv_filter_rows_applies(const float *in, const float *dz, int64_t B, int32_t h, int32_t w, int32_t ci,
                               int32_t k, int32_t co, const float *dWc);
 hipError_t launch_conv_filter_rows(const float *in, const float *dz, int64_t B, int32_t h, int32_t w, int32_t ci,
-                                   int32_t k, int32_t co, float *dWc, int streaming, hipStream_t stream);
+                                   int32_t k, int32_t co, float *dWc, int streaming, float *sq_part,
+                                   hipStream_t stream);
+// With sq_part set the two filter-gradient kernels store no gradient: each workgroup leaves the sum
+// of the squares of its share at sq_part[b * parts + its index within the example]; parts as below.
+int conv_filter_direct_parts(int32_t ci, int32_t co);
+int conv_filter_rows_parts(int32_t co);
 
 // pooled [B, h/2, w/2, c] = max over 2 x 2 windows of relu(z [B, h, w, c]); which = index 0..3 of the
 // window entry that gave it

@@ -40,6 +40,21 @@ __device__ __forceinline__ int div_small(int n, int d, float inv) {
   return q;
 }
 
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// The sum of `v` over the four waves of a workgroup in the order of the waves, through `slot` (four
+// floats of LDS nobody else touches meanwhile); valid in thread 0.
+__device__ __forceinline__ float workgroup_sum(float v, float *slot, int wv, int lane) {
+  v = wave_sum(v);
+  if (lane == 0) slot[wv] = v;
+  __syncthreads();
+  return ((slot[0] + slot[1]) + slot[2]) + slot[3];
+}
+
 constexpr int kCopyBatch = 16;     // 16-byte loads a thread has in flight while an image is copied to LDS
 
 // Copies the zero-padded band of an image to LDS: rows row0 - p .. of `nrows` padded rows, PW padded
@@ -305,6 +320,7 @@ struct ConvFilterArgs {
   float *dWc;          // [B, k k ci, co]
   int h, w, k, ci, co;
   int streaming;       // non-temporal stores (the gradients are not read back)
+  float *sq_part;      // set: no gradient is stored, only the sum of its squares per workgroup, [B, workgroups per example]
 };
 
 // dWc[b, (dy, dx, c), n] = sum over the positions of in[b, pos + (dy, dx) - p, c] dz[b, pos, n] for 32
@@ -403,6 +419,18 @@ __global__ __launch_bounds__(kThreads) void conv_filter_direct_kernel(const Conv
   // consecutive filters of its channel per register quad: written to this wave's LDS slab
   // [32 channels][36] as 16-byte pieces and read back row by row for 16-byte stores.  The slab is the
   // wave's own: its LDS operations execute in order, no workgroup barrier is needed between the taps.
+  if (a.sq_part) {
+    // only the norm is wanted: this workgroup's share of the sum of squares (dead taps left out)
+    float sq = 0.f;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+      if (tt < my)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sq += acc[tt][r] * acc[tt][r];
+    sq = workgroup_sum(sq, smem, wv, lane);
+    if (tid == 0) a.sq_part[blockIdx.x] = sq;
+    return;
+  }
   float *slab = smem + wv * (32 * 36);
   float *dst = a.dWc + b * (int64_t)taps * a.ci * a.co;
 #pragma unroll
@@ -577,6 +605,7 @@ __global__ __launch_bounds__(kThreads) void conv_filter_rows_kernel(const ConvFi
     }
   __syncthreads();
   float *dst = a.dWc + b * (int64_t)M * a.co + n0;
+  float sq = 0.f;
   for (int e = tid; e < M * 8; e += kThreads) {
     const int n4 = e & 7, m = e >> 3;
     const float *q = part + m * 36 + 4 * n4;
@@ -584,9 +613,19 @@ __global__ __launch_bounds__(kThreads) void conv_filter_rows_kernel(const ConvFi
     sum += *reinterpret_cast<const f32x4 *>(q + wstride);
     sum += *reinterpret_cast<const f32x4 *>(q + 2 * wstride);
     sum += *reinterpret_cast<const f32x4 *>(q + 3 * wstride);
+    if (a.sq_part) {
+      sq += (sum[0] * sum[0] + sum[1] * sum[1]) + (sum[2] * sum[2] + sum[3] * sum[3]);
+      continue;
+    }
     f32x4 *out = reinterpret_cast<f32x4 *>(dst + (int64_t)m * a.co + 4 * n4);
     if (a.streaming) __builtin_nontemporal_store(sum, out);
     else *out = sum;
+  }
+  if (a.sq_part) {
+    // only the norm is wanted: the sum of squares of this workgroup's 32 filters
+    __syncthreads();                         // part[] has been read: its first floats serve as the slot
+    sq = workgroup_sum(sq, smem, wv, lane);
+    if (tid == 0) a.sq_part[blockIdx.x] = sq;
   }
 }
 
@@ -773,12 +812,16 @@ bool conv_filter_direct_applies(const float *in, const float *dz, int64_t B, int
   return filter_smem(h, w, k) <= (size_t)lds_limit();
 }
 
+int conv_filter_direct_parts(int32_t ci, int32_t co) { return (ci / 32) * (co / 32); }
+int conv_filter_rows_parts(int32_t co) { return co / 32; }
+
 hipError_t launch_conv_filter_direct(const float *in, const float *dz, int64_t B, int32_t h, int32_t w,
                                      int32_t ci, int32_t k, int32_t co, float *dWc, int streaming,
-                                     hipStream_t stream) {
+                                     float *sq_part, hipStream_t stream) {
   if (!conv_filter_direct_applies(in, dz, B, h, w, ci, k, co, dWc)) return hipErrorInvalidValue;
   ConvFilterArgs a{};
   a.in = in; a.dz = dz; a.dWc = dWc; a.h = h; a.w = w; a.k = k; a.ci = ci; a.co = co; a.streaming = streaming;
+  a.sq_part = sq_part;
   const int64_t wgs = B * (ci / 32) * (co / 32);
   const size_t smem = filter_smem(h, w, k);
   return k == 3 ? launch_filter<3>(a, wgs, smem, stream) : launch_filter<7>(a, wgs, smem, stream);
@@ -821,10 +864,12 @@ bool conv_filter_rows_applies(const float *in, const float *dz, int64_t B, int32
 }
 
 hipError_t launch_conv_filter_rows(const float *in, const float *dz, int64_t B, int32_t h, int32_t w, int32_t ci,
-                                   int32_t k, int32_t co, float *dWc, int streaming, hipStream_t stream) {
+                                   int32_t k, int32_t co, float *dWc, int streaming, float *sq_part,
+                                   hipStream_t stream) {
   if (!conv_filter_rows_applies(in, dz, B, h, w, ci, k, co, dWc)) return hipErrorInvalidValue;
   ConvFilterArgs a{};
   a.in = in; a.dz = dz; a.dWc = dWc; a.h = h; a.w = w; a.k = k; a.ci = ci; a.co = co; a.streaming = streaming;
+  a.sq_part = sq_part;
   const int64_t wgs = B * (co / 32);
   const size_t smem = filter_rows_smem(h, w, k, ci);
   return k * k * ci <= 32 ? launch_filter_rows<1>(a, wgs, smem, stream) : launch_filter_rows<2>(a, wgs, smem, stream);

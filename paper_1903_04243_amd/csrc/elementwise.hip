@@ -217,7 +217,8 @@ struct NormBatch {
 // its cotangent row (the both-operands-stacked matmul case of Section 3.4 with contraction
 // length 1), so its squared Frobenius norm is the product of the two rows' squared norms; the
 // bias gradient is the cotangent row itself.  A block whose gradient has been formed (sum_mode: a
-// convolution's filter, summed over the positions) contributes the sum of its squares instead.
+// convolution's filter, summed over the positions) contributes the sum of its squares instead
+// (sum_mode 1), or partial sums of those squares that the kernel forming it left behind (sum_mode 2).
 // One workgroup per example, sums in a fixed order.
 __global__ __launch_bounds__(kThreads) void grad_sqnorms_kernel(const NormBatch nb, float *sq,
                                                                 int64_t ld_sq, float *norm) {
@@ -228,7 +229,11 @@ __global__ __launch_bounds__(kThreads) void grad_sqnorms_kernel(const NormBatch 
   for (int li = 0; li < nb.n; ++li) {
     const NormLayer &ly = nb.layer[li];
     float sa = 0.f, sg = 0.f;
-    if (ly.a_bf16) {
+    if (ly.sum_mode == 2) {
+      // the block's squares were summed where its gradient was formed: d_in partial sums per example
+      const float *a = static_cast<const float *>(ly.a) + b * ly.d_in;
+      for (int i = tid; i < ly.d_in; i += kThreads) sa += a[i];
+    } else if (ly.a_bf16) {
       const __bf16 *a = static_cast<const __bf16 *>(ly.a) + b * ly.d_in;
       for (int i = tid; i < ly.d_in; i += kThreads) { const float v = (float)a[i]; sa += v * v; }
     } else {

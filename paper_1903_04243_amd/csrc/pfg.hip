@@ -1102,6 +1102,7 @@ int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, 
   }
 
   // ---- conv blocks, reverse ----
+  std::vector<int> sq_parts(nc, 0);     // > 0: the block's filter gradient left that many partial sums of squares
   for (int i = nc - 1; i >= 0; --i) {
     const ConvBlock &blk = cp.blocks[i];
     const int hw = blk.h * blk.w, kkc = blk.k * blk.k * blk.ci;
@@ -1118,12 +1119,18 @@ int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, 
       if (dbc) PFG_LAUNCH("sum_positions", launch_sum_steps(dz, B, hw, blk.co, dbc, at(ws, cp.psum), stream));
     }
     if (dWc_out && dWc_out[i]) {
-      if (conv_filter_direct_applies(image[i], dz, B, blk.h, blk.w, blk.ci, blk.k, blk.co, dWc_out[i]))
+      // when only norms are wanted, the kernels that form the gradient on the LDS image store the sums
+      // of its squares (a few per example, at the head of the buffer meant for the gradient) and no gradient
+      float *sq_part = norms ? dWc_out[i] : nullptr;
+      if (conv_filter_direct_applies(image[i], dz, B, blk.h, blk.w, blk.ci, blk.k, blk.co, dWc_out[i])) {
         PFG_LAUNCH("conv_gemm_filter", launch_conv_filter_direct(image[i], dz, B, blk.h, blk.w, blk.ci, blk.k,
-                                                                 blk.co, dWc_out[i], norms ? 0 : 1, stream));
-      else if (conv_filter_rows_applies(image[i], dz, B, blk.h, blk.w, blk.ci, blk.k, blk.co, dWc_out[i]))
+                                                                 blk.co, dWc_out[i], 1, sq_part, stream));
+        if (norms) sq_parts[i] = conv_filter_direct_parts(blk.ci, blk.co);
+      } else if (conv_filter_rows_applies(image[i], dz, B, blk.h, blk.w, blk.ci, blk.k, blk.co, dWc_out[i])) {
         PFG_LAUNCH("conv_gemm_filter", launch_conv_filter_rows(image[i], dz, B, blk.h, blk.w, blk.ci, blk.k, blk.co,
-                                                               dWc_out[i], norms ? 0 : 1, stream));
+                                                               dWc_out[i], 1, sq_part, stream));
+        if (norms) sq_parts[i] = conv_filter_rows_parts(blk.co);
+      }
       else
         PFG_LAUNCH("conv_gemm_filter", launch_gemm(gathers(i) ? gathered_filter_product(i)
                                                               : filter_product(i, filter_reads_P(i)), stream));
@@ -1163,9 +1170,9 @@ int convnet_sweep(const pfg_convnet *net, const void *X, const int32_t *labels, 
     NormLayer &ly = layers[i];
     ly.a = dWc_out[i];
     ly.g = dbc_out[i];             // null for a block without a bias
-    ly.d_in = blk.k * blk.k * blk.ci * blk.co;
+    ly.d_in = sq_parts[i] ? sq_parts[i] : blk.k * blk.k * blk.ci * blk.co;
     ly.d_out = blk.co;
-    ly.sum_mode = 1;
+    ly.sum_mode = sq_parts[i] ? 2 : 1;
     ly.index = i;
   }
   for (int l = 1; l <= L; ++l) {
