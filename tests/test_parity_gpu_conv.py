@@ -293,12 +293,22 @@ def test_c10_mnist_convnet_grad_norms_full_size():
     assert (sq[:, -1].double() >= (1.0 - p_label) ** 2 * (1 - 1e-5)).all()
 
 
-def test_convnet_calls_replay_from_a_graph():
+GRAPH_SHAPES = [
+    # the products that gather their patches from the image, the fused unpool + bias kernel and the
+    # split filter products
+    (12, 12, 4, ((3, 8), (3, 16)), (24, 7), 96),
+    # the matrix-core kernels that read the image from LDS (more than 64 KB of it, dynamically sized),
+    # and the norms call that keeps only sums of squares of the filter gradients
+    (16, 16, 4, ((3, 32), (3, 64)), (12,), 120),
+]
+
+
+@pytest.mark.parametrize("h,w,c,blocks,dense,B", GRAPH_SHAPES, ids=["gathered", "lds-image"])
+def test_convnet_calls_replay_from_a_graph(h, w, c, blocks, dense, B):
     # gradients and gradient norms of one network captured into one HIP graph (the library records
     # kernel launches only) and replayed with eager work and synchronisations in between: every
-    # replay reproduces the eager results bit for bit.  The shape takes the products that gather
-    # their patches from the image, the fused unpool + bias kernel and the split filter products.
-    wk = wl.ConvWorkload("graphc", 560, 12, 12, 4, ((3, 8), (3, 16)), (24, 7), 96)
+    # replay reproduces the eager results bit for bit.
+    wk = wl.ConvWorkload("graphc", 560, h, w, c, blocks, dense, B)
     inp = wl.make_conv_inputs(wk, bias_scale=0.2)
     B, h, w, c = inp.X.shape
     net = pfg.ConvNet.from_numpy(h, w, c, inp.Wc, inp.bc, inp.Ws, inp.bs)
