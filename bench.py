@@ -172,6 +172,9 @@ def main():
         return out
 
     def is_wide(M, d_in, d_out):
+        # rows of 1024 floats or more from 128 MiB on; rows of 256 or 512 floats from 512 MiB on
+        if d_out in (256, 512) and M <= 65535 and 4 * M * d_in * d_out >= (512 << 20):
+            return True
         return (d_out % 4 == 0 and d_out >= 1024 and M <= 65535 and d_in <= 65535 and
                 4 * M * d_in * d_out >= (128 << 20))
 

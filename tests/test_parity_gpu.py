@@ -195,6 +195,43 @@ def test_c4_gelu_bf16_full_size_every_element(oracle, c4_full, group):
     assert worst <= TOL_BF16 and worst_elem <= TOL_BF16
 
 
+def test_narrow_rows_of_a_large_output_every_element(oracle):
+    # layers whose rows are 256 and 512 floats wide and whose gradients fill half a GiB or more leave in
+    # launches of their own, one 4 KiB slab (4 or 2 whole rows) per workgroup: 1 GiB + 0.5 GiB here,
+    # every element against the oracle, 64 examples at a time, compared on the device
+    w = wl.WORKLOADS["c2_mnist_mlp_grads"]
+    dims, B = (1024, 256, 512, 10), 1024
+    say(f"narrow rows {dims} B={B}: every element")
+    act = "tanh"             # (with relu, 800 000 pre-activations cannot all be kept off the kink)
+    inp = draw(w, B=B, dims=dims, act=act)
+    net = gpu_net(inp, act, "f32")
+    f32 = dict(dtype=torch.float32, device="cuda:0")
+    out_dW = [torch.full((B, dims[l], dims[l + 1]), float("nan"), **f32) for l in range(3)]
+    dW, db, loss = pfg.pfg_per_example_grads(net, gpu_x(inp, "f32"), dev(inp.labels), out_dW=out_dW)
+    torch.cuda.synchronize()
+    onet = oracle.Net(inp.Ws, inp.bs, act)
+    worst = 0.0
+    for b0 in range(0, B, 64):
+        idx = slice(b0, b0 + 64)
+        rdW, rdb, rloss = oracle.per_example_grads(onet, inp.X[idx], inp.labels[idx])
+        for l in range(3):
+            ref = torch.from_numpy(rdW[l]).to("cuda:0")
+            got = dW[l][idx].double()
+            assert torch.isfinite(got).all().item(), f"dW{l + 1} was not written in full"
+            den = ref.abs().amax(dim=(1, 2))
+            err = (got - ref).abs_().amax(dim=(1, 2))
+            # an example whose reference slice is identically zero (every unit of a layer off) must be zero
+            assert ((den > 0) | (err == 0)).all().item()
+            worst = max(worst, float((err / den.clamp_min(1e-300)).max().item()))
+            del ref, got
+            worst = max(worst, slice_rel_err(db[l][idx].cpu().numpy(), rdb[l]))
+        worst = max(worst, slice_rel_err(loss[idx].cpu().numpy(), rloss, lead=0))
+    say(f"  worst rel err {worst:.3e}")
+    assert worst <= TOL_F32
+    del dW, out_dW
+    torch.cuda.empty_cache()
+
+
 def test_c5_nested_weight_jacobian_full_size(oracle):
     w = wl.WORKLOADS["c5_nested_weight_jacobian"]
     say("c5_nested_weight_jacobian: full size, every element")
