@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpfg.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["gemm.hip", "gemm_skinny.hip", "gemm_small16.hip", "writer.hip", "elementwise.hip", "lstm.hip", "conv.hip", "conv_mfma.hip", "cond.hip", "loop.hip", "head.hip", "pfg.hip",
+SOURCES = ["gemm.hip", "gemm_skinny.hip", "gemm_small16.hip", "gemm_shortk.hip", "writer.hip", "elementwise.hip", "lstm.hip", "conv.hip", "conv_mfma.hip", "cond.hip", "loop.hip", "head.hip", "pfg.hip",
            "pfg_lstm.hip", "pfg_cond.hip"]
 HEADERS = [os.path.join(CSRC, "common.h"), os.path.join(CSRC, "gemm_device.h"),
            os.path.join(CSRC, "host.h"), os.path.join(os.path.dirname(HERE), "include", "pfg.h")]

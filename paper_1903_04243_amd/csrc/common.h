@@ -173,6 +173,10 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream);
 bool akm_supported(const GemmArgs &g);
 hipError_t launch_gemm_skinny(const GemmArgs &g, hipStream_t stream);
 // 16 x 16 tiles for the smallest float32 products (used by launch_gemm_skinny when it applies)
+// A float32 product with a contraction of 32, 64 or 128 and at least 16384 rows (plain or bias epilogue,
+// W in [K, N] layout, N a multiple of 128): the kernel that keeps a W tile in LDS and streams the rows past it.
+bool gemm_shortk_applies(const GemmArgs &g);
+hipError_t launch_gemm_shortk(const GemmArgs &g, hipStream_t stream);
 bool conv_gather_supported(const GemmArgs &g);     // may this product (conv_k > 0) be launched?
 bool lstm_step_tiled_applies(const GemmArgs &g);   // EPI_LSTM_FWD on enough rows for the LDS-tiled kernel
 bool small16_applies(const GemmArgs &g);

@@ -958,6 +958,7 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t stream) {
     if (!akm_supported(g)) return hipErrorInvalidValue;
     return launch_tiles<A_F32, true>(g, stream);
   }
+  if (gemm_shortk_applies(g)) return launch_gemm_shortk(g, stream);
   // Fewer than 128 tiles of 64 x 64 cannot occupy the chip: such products (M = B rows, or a
   // narrow output) go to the kernel that splits the contraction over the waves of a workgroup.
   const int64_t tiles64 = (int64_t)(g.nbatch > 1 ? g.nbatch : 1) * ((g.M + 63) / 64) * ((g.N + 63) / 64);

@@ -288,6 +288,10 @@ VARLEN_SHAPES = [
     (33, 65, 10, 12, 40),        # one past the tile edges; more sequences than one row tile
     (16, 32, 40, 30, 100),
     (16, 64, 5, 12, 900),        # the first steps have more than 768 active rows: the tiled fused step
+    # 16384 token rows or more against inputs of 32 / 64 values and 128 / 256 gate columns: the input
+    # projection on the kernel that keeps its weight tile in LDS (the last row tile is ragged)
+    (32, 32, 3, 60, 600),
+    (64, 64, 4, 90, 400),
 ]
 
 
