@@ -77,7 +77,6 @@ def main():
             return w
         return dataclasses.replace(w, **{"n" if hasattr(w, "n") else "B": args.batch})
     torch.cuda.set_device(0)
-
     def upload(w):
         inp = wl.make_inputs(w)
         net = pfg.Mlp.from_numpy(inp.Ws, inp.bs, w.act, w.dtype, inp.Ws_bits, inp.bs_bits)
@@ -124,15 +123,25 @@ def main():
         return lambda: pfg.pfg_jacobian_weights(net, X, head=w.head, out_JW=JW, out_Jb=Jb,
                                                 workspace=ws)
 
+    # Passes of K steps a workload is timed for; the fastest counts.  The headline workload is timed
+    # once, exactly K steps.  The others get two passes in the default run: on a machine that has just
+    # come up, one launch-bound workload per run (the first after the large buffers were released) has
+    # been seen at a third of its launch rate for about 0.1 s, kernel times unchanged.
+    timing_passes = {"n": 1}
+
     def timed(step, steps, warmup):
-        for _ in range(warmup):
-            step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            step()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
+        best = None
+        for _ in range(timing_passes["n"]):
+            for _ in range(warmup):
+                step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step()
+            torch.cuda.synchronize()
+            sec = (time.perf_counter() - t0) / steps
+            best = sec if best is None else min(best, sec)
+        return best
 
     def timed_graph(step, steps, warmup):
         """The same step captured once into a HIP graph and replayed."""
@@ -908,7 +917,9 @@ def main():
                             ("c13_cond_grads", max(3, args.steps))):
             try:
                 fn = measure if name in wl.WORKLOADS else measure_lstm
+                timing_passes["n"] = 2
                 detail[name], _ = fn(name, steps, max(1, min(max(args.warmup, 10), steps // 2)))
+                detail[name]["timing"] = "fastest of 2 passes of `steps` steps"
             except Exception as e:
                 log(f"[bench] {name}: FAILED: {e}")
                 detail[name] = {"error": str(e)}
