@@ -157,6 +157,9 @@ CONV = [
     (10, 6, 8, ((5, 16),), (12,), 300, 1 / 32),
     (12, 20, 3, ((3, 4), (1, 8)), (5,), 37, 1 / 16),
     (12, 12, 1, ((3, 8), (3, 8)), (32, 10), 7, 1 / 16),            # fewer than 32 examples: the other unpooling route
+    # enough examples and channels for the matrix-core kernels on the LDS image (their own pooling decision)
+    (28, 28, 1, ((5, 32), (5, 64)), (64, 10), 130, 1 / 256),
+    (8, 8, 8, ((3, 32), (3, 32)), (6,), 230, 1 / 16),
 ]
 
 
