@@ -16,6 +16,11 @@
 //       filter flipped and transposed; replaces the patch-cotangent product and its gather.
 //   conv_filter_direct_kernel<TT>: the per-example filter gradient (both operands stacked over the
 //       examples, Section 3.4): for each tap, in_shifted^T dz over the positions.
+//   conv_filter_rows_kernel<MT>:   the same gradient for a block with few input channels (a first
+//       layer): the rows (tap, channel) fill one or two MFMA tiles, each lane reading its own shifted
+//       image value.
+// The host side takes each of them only from the batch size on where it was measured faster than the
+// tiled products (a workgroup here costs the same however few examples there are).
 //
 // v_mfma_f32_32x32x2_f32 computes D[i][j] += A[i][k] B[k][j] with lane (l32, half) supplying
 // A[l32][half] and B[half][l32], and holding D[8 (r / 4) + 4 half + r % 4][l32] in register r.
